@@ -1,0 +1,106 @@
+"""Round-robin driver: plays the scheduler that calls the memory manager at
+every context switch (Sec. 6.1 of the paper) against any implementation that
+offers the calls below.  It builds timelines and retires launches; it never
+looks at pages.
+
+Implementation protocol (duck-typed; the oracle wrapper and the HIP binding
+both satisfy it):
+    kernel_register(rules) -> kernel id
+    task_create() -> task id
+    launch_enqueue(task, kernel_id, args_u64, n_args, latency, ids_off, n_ids)
+    launch_retire(task, n)
+    plan(timeline) -> object with n_fetch, n_evict, n_free_used, g_cut, g_end0,
+                      covered_launches
+    migrate()
+"""
+from dataclasses import dataclass
+from typing import Iterator, List, Optional, Tuple
+
+import numpy as np
+
+from .trace import Trace
+
+
+@dataclass
+class SwitchRecord:
+    index: int                       # running count of plan calls
+    task: int                        # incoming task
+    timeline: List[Tuple[int, int]]  # (task, timeslice ticks) entries passed to plan
+    plan: object                     # what impl.plan returned
+    first_launch: int                # index (in the task's program order) of the first covered launch
+    n_launches: int                  # launches that run before the next plan call
+    replan: bool                     # True when the previous plan was truncated
+
+
+def load_trace(impl, trace: Trace) -> None:
+    """Register templates and enqueue every launch up front (launches are
+    asynchronous and run far ahead of execution)."""
+    kid = [impl.kernel_register(rules) for rules in trace.kernels]
+    for t, cmds in enumerate(trace.tasks):
+        tid = impl.task_create()
+        assert tid == t
+        for i in range(len(cmds)):
+            impl.launch_enqueue(t, kid[int(cmds.kernel_id[i])], cmds.args[i], int(cmds.n_args[i]),
+                                int(cmds.latency[i]), int(cmds.ids_off[i]), int(cmds.n_ids[i]))
+
+
+def _slice_count(latency: np.ndarray, start: int, ticks: int) -> int:
+    """Launches of one task, from `start`, that begin inside a timeslice of `ticks`."""
+    acc, n = 0, 0
+    while start + n < latency.shape[0] and acc < ticks:
+        acc += int(latency[start + n])
+        n += 1
+    return n
+
+
+def _timeline(trace: Trace, cursor: List[int], cur: int, first_ticks: int, horizon: str):
+    n = trace.n_tasks
+    remaining = [len(trace.tasks[t]) - cursor[t] for t in range(n)]
+    entries = []
+    if horizon == "round":
+        for k in range(n):
+            t = (cur + k) % n
+            if remaining[t] > 0:
+                entries.append((t, first_ticks if k == 0 else trace.timeslice))
+        return entries
+    # full horizon: the whole remaining round-robin schedule
+    pos = list(cursor)
+    t, ticks = cur, first_ticks
+    while any(pos[i] < len(trace.tasks[i]) for i in range(n)):
+        if pos[t] < len(trace.tasks[t]):
+            entries.append((t, ticks))
+            pos[t] += _slice_count(trace.tasks[t].latency, pos[t], ticks)
+        t, ticks = (t + 1) % n, trace.timeslice
+    return entries
+
+
+def run_schedule(trace: Trace, impl, horizon: str = "round",
+                 max_plans: Optional[int] = None) -> Iterator[SwitchRecord]:
+    """Drive `impl` through the trace.  Yields after each plan + migrate and
+    before the covered launches are retired, so the caller can inspect state
+    at the moment those launches would start."""
+    n = trace.n_tasks
+    cursor = [0] * n
+    cur, index = 0, 0
+    while any(cursor[t] < len(trace.tasks[t]) for t in range(n)):
+        if cursor[cur] >= len(trace.tasks[cur]):
+            cur = (cur + 1) % n
+            continue
+        budget, replan = trace.timeslice, False
+        while budget > 0 and cursor[cur] < len(trace.tasks[cur]):
+            tl = _timeline(trace, cursor, cur, budget, horizon)
+            plan = impl.plan(tl)
+            impl.migrate()
+            covered = int(plan.covered_launches)
+            yield SwitchRecord(index, cur, tl, plan, cursor[cur], covered, replan)
+            index += 1
+            lat = trace.tasks[cur].latency
+            budget -= int(lat[cursor[cur]:cursor[cur] + covered].sum())
+            impl.launch_retire(cur, covered)
+            cursor[cur] += covered
+            if max_plans is not None and index >= max_plans:
+                return
+            if covered == int(plan.g_end0):
+                break
+            replan = True
+        cur = (cur + 1) % n
