@@ -1,0 +1,185 @@
+/*
+ * msched.h -- C ABI of the MI355X-native MSched hot path (arXiv 2512.24637,
+ * "Towards Fully-fledged GPU Multitasking via Proactive Memory Scheduling").
+ *
+ * One context = one GPU's HBM frame pool, its page table and the command
+ * queues of the tasks that share it.  At every context switch the scheduler
+ * calls msched_plan() with its task timeline and then msched_migrate(); both
+ * run as HIP kernels on gfx950.  No torch types cross this boundary: callers
+ * pass plain pointers (each marked HOST or DEVICE below) and sizes.
+ *
+ * Threading: a context is used by one thread at a time (the paper's
+ * coordinator is a single daemon, Sec. 6.2).  All device work is issued on the
+ * stream given at creation.
+ *
+ * Errors: every call returns MSCHED_OK (0) or a negative code and leaves the
+ * context unchanged on error.
+ */
+#ifndef MSCHED_H
+#define MSCHED_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MSCHED_NOT_RESIDENT 0xFFFFFFFFu       /* page-table value of a page that is not in HBM */
+#define MSCHED_NO_SLOT 0xFFFFFFFFu            /* host_slot value of a page without backing store */
+#define MSCHED_MAX_ARGS 12                    /* 64-bit launch arguments per command */
+#define MSCHED_MAX_RULES 8                    /* access rules per kernel template */
+#define MSCHED_MAX_PRODUCT_ARGS 4             /* arguments multiplied in one formula */
+#define MSCHED_MAX_TIMELINE_COMMANDS 4095     /* commands one plan may look ahead over */
+#define MSCHED_MAX_TIMELINE_ENTRIES 1024
+
+enum {
+    MSCHED_OK = 0,
+    MSCHED_E_INVAL = -1,           /* bad argument, unknown task or kernel, too long a timeline */
+    MSCHED_E_RANGE = -2,           /* page >= n_virtual_pages, page without backing slot, rule names a missing argument */
+    MSCHED_E_OVERFLOW = -3,        /* template arithmetic exceeds 64 bits */
+    MSCHED_E_WSET_TOO_LARGE = -4,  /* the first command of the incoming task alone needs more than n_frames pages */
+    MSCHED_E_STALE_PLAN = -5,      /* migrate with a plan that is not the latest, or already carried out */
+    MSCHED_E_NOMEM = -6,
+    MSCHED_E_HIP = -7              /* a HIP call failed; see msched_last_hip_error() */
+};
+
+typedef struct msched_ctx msched_ctx;          /* opaque, library-owned */
+
+typedef struct {
+    uint32_t page_shift;          /* log2(page bytes), 6..30 */
+    uint32_t n_frames;            /* F: frames in the HBM pool */
+    uint64_t n_virtual_pages;     /* V: page-table length, < 2^32 - 1 */
+    void *hbm_pool;               /* DEVICE, n_frames << page_shift bytes, 16-byte aligned, caller-owned */
+    void *host_store;             /* HOST pinned and device-accessible, n_host_slots << page_shift bytes, caller-owned */
+    uint64_t n_host_slots;        /* pages in host_store */
+    const uint32_t *host_slot;    /* HOST, V entries (page -> slot, MSCHED_NO_SLOT = none) or NULL = identity; copied */
+    void *stream;                 /* hipStream_t all device work is issued on (NULL = default stream) */
+} msched_config;
+
+/*
+ * One access rule of a kernel template (Sec. 5.2, "Access pattern templates").
+ * The region starts at the byte address held in launch argument base_arg.  Each
+ * of size, stride and count is coeff * product(args[idx[0..n-1]]), empty product = 1,
+ * evaluated in unsigned 64-bit arithmetic.
+ *   FIXED   (T1) one range of size_coeff bytes (n_size_args must be 0)
+ *   LINEAR  (T2) one range of `size` bytes
+ *   STRIDED (T3) `count` ranges of `size` bytes, the j-th starting at base + j*stride
+ *   LIST         the explicit page ids attached to the launch (sparse gathers, which the
+ *                paper's templates do not cover); base/size/stride/count are ignored
+ * A range of b bytes at address a touches pages floor(a/P) .. floor((a+b-1)/P); zero bytes touch nothing.
+ */
+enum { MSCHED_RULE_FIXED = 1, MSCHED_RULE_LINEAR = 2, MSCHED_RULE_STRIDED = 3, MSCHED_RULE_LIST = 4 };
+
+typedef struct {
+    uint8_t kind;
+    uint8_t base_arg;
+    uint8_t n_size_args, n_stride_args, n_count_args;
+    uint8_t size_args[MSCHED_MAX_PRODUCT_ARGS];
+    uint8_t stride_args[MSCHED_MAX_PRODUCT_ARGS];
+    uint8_t count_args[MSCHED_MAX_PRODUCT_ARGS];
+    uint8_t reserved[7];
+    uint64_t size_coeff, stride_coeff, count_coeff;
+} msched_rule;                                  /* 48 bytes */
+
+/* One entry of the task scheduling timeline (Sec. 6.1): which task runs next and for how
+ * many ticks.  Commands are taken from the task's queue while the latency accumulated in
+ * the entry is below timeslice; a task listed again continues where it stopped. */
+typedef struct { uint32_t task; uint32_t timeslice; } msched_timeline_entry;
+
+typedef struct {
+    uint32_t n_evict;             /* pages to copy out, in eviction order */
+    uint32_t n_fetch;             /* pages to copy in, in order of first use */
+    uint32_t n_free_used;         /* fetches that go to free frames (the first n_free_used of the list) */
+    uint32_t covered_launches;    /* commands of entry 0 whose pages will all be resident (= g_cut) */
+    uint32_t g_cut;
+    uint32_t g_end0;              /* commands entry 0 holds; covered_launches < g_end0 means the slice was cut */
+    uint32_t n_commands;          /* G: commands in the flattened timeline */
+    uint32_t reserved;
+    const uint32_t *evict_pages;  /* DEVICE, context-owned, valid until the next msched_plan */
+    const uint32_t *evict_frames; /* DEVICE */
+    const uint32_t *fetch_pages;  /* DEVICE */
+    const uint32_t *fetch_frames; /* DEVICE */
+    uint64_t plan_id;
+} msched_plan_t;
+
+/* Create a context.  Nothing is resident, every frame is free.  *out is set on success. */
+int msched_create(const msched_config *cfg, msched_ctx **out);
+int msched_destroy(msched_ctx *ctx);
+
+/* Register a kernel template of n_rules <= MSCHED_MAX_RULES rules (HOST array); *kernel_id receives its id.
+ * Stands for one record of the offline description file (Sec. 4.1). */
+int msched_kernel_register(msched_ctx *ctx, const msched_rule *rules, uint32_t n_rules, uint32_t *kernel_id);
+
+/* Create a task (one process's command queue, Sec. 6.2 "Distributed metadata management"). */
+int msched_task_create(msched_ctx *ctx, uint32_t *task_id);
+
+/*
+ * Append a launch to a task's queue (Sec. 5.2 "Memory access prediction": launch arguments are
+ * captured when the command is issued; Sec. 6.2: the queue holds the command and its profiled
+ * latency).  args: HOST, n_args <= MSCHED_MAX_ARGS values (32-bit arguments zero-extended).
+ * id_list: DEVICE array of n_ids page ids for the kernel's LIST rule, or NULL; it is NOT copied
+ * and must stay valid and unchanged until the launch has been retired.
+ * The template is evaluated here once for validation: E_RANGE / E_OVERFLOW launches are refused.
+ * (Ids inside id_list are checked by msched_plan, which then returns E_RANGE.)
+ */
+int msched_launch_enqueue(msched_ctx *ctx, uint32_t task, uint32_t kernel_id,
+                          const uint64_t *args, uint32_t n_args, uint32_t latency_ticks,
+                          const uint32_t *id_list, uint32_t n_ids);
+
+/* The first n_launches queued commands of the task have executed ("currently executing command"
+ * of Sec. 6.2 moves forward). */
+int msched_launch_retire(msched_ctx *ctx, uint32_t task, uint32_t n_launches);
+
+/*
+ * Plan the migration for a context switch (Sec. 6.2 "Enforcing the OPT memory scheduling").
+ * tl: HOST, n_entries <= MSCHED_MAX_TIMELINE_ENTRIES, entry 0 is the incoming task.
+ * Flattens the timeline into the order of future commands, expands every command's template
+ * into pages, gives each page the position of its first future use, cuts entry 0 to the longest
+ * command prefix whose pages fit the pool, and selects
+ *   fetch  = wanted and not resident, ordered by (first use, page id)
+ *   evict  = first max(0, n_fetch - free frames) resident pages that are not wanted, ordered by
+ *            (first use descending with never-used first, page id)
+ * Fetched page i takes the i-th lowest free frame, or the frame of evict[i - n_free_used].
+ * Does not change the page table.  Blocks until the counts in *out are known.
+ */
+int msched_plan(msched_ctx *ctx, const msched_timeline_entry *tl, uint32_t n_entries, msched_plan_t *out);
+
+/*
+ * Carry out the latest plan (Sec. 6.2 "Driver support": evict, then populate; Sec. 6.3: victim
+ * copy-out and target copy-in proceed in parallel, target i reusing the space of victim i):
+ * host_store[slot(evict[i])] <- pool[evict_frames[i]], pool[fetch_frames[i]] <- host_store[slot(fetch[i])],
+ * then the page table and frame owners are updated.  Asynchronous on the context's stream; a plan
+ * can be carried out once.
+ */
+int msched_migrate(msched_ctx *ctx, const msched_plan_t *plan);
+
+/* Frame of each page, or MSCHED_NOT_RESIDENT.  page_ids: HOST, out: HOST.  Waits for the stream. */
+int msched_pagetable_query(msched_ctx *ctx, const uint64_t *page_ids, uint32_t n, uint32_t *out);
+
+/* Copy the lists of the latest plan to HOST arrays (any may be NULL) of n_evict / n_fetch entries. */
+int msched_plan_copy_lists(msched_ctx *ctx, const msched_plan_t *plan, uint32_t *evict_pages,
+                           uint32_t *evict_frames, uint32_t *fetch_pages, uint32_t *fetch_frames);
+
+/* Copy the whole page table (V entries) and frame-owner table (F entries) to HOST arrays (either may be NULL). */
+int msched_state_copy(msched_ctx *ctx, uint32_t *page_table, uint32_t *frame_owner);
+
+/*
+ * Per-phase device times of the last plan and the last migrate, measured with HIP events on the
+ * context's stream when profiling is on.  ms: HOST array of MSCHED_N_PHASES floats.
+ */
+enum { MSCHED_PHASE_EXPAND = 0,   /* next-use reset + template expansion + scatter-min */
+       MSCHED_PHASE_COUNT = 1,    /* per-chunk class histograms over the page table */
+       MSCHED_PHASE_CUT = 2,      /* totals, budget cut, victim threshold, output offsets */
+       MSCHED_PHASE_EMIT = 3,     /* ordered compaction of both lists + frame assignment */
+       MSCHED_PHASE_MIGRATE = 4,  /* copy kernel + page-table update */
+       MSCHED_N_PHASES = 5 };
+int msched_set_profiling(msched_ctx *ctx, int on);
+int msched_get_phase_ms(msched_ctx *ctx, float *ms);
+
+const char *msched_strerror(int code);
+int msched_last_hip_error(msched_ctx *ctx);     /* hipError_t of the last MSCHED_E_HIP, as int */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MSCHED_H */

@@ -1,0 +1,259 @@
+"""ctypes binding of libmsched.so: argument marshalling only.  Every step of the
+path runs in the library's HIP kernels; there is no CPU fallback, and a missing
+library is an error."""
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+NOT_RESIDENT = 0xFFFFFFFF
+PHASES = ("expand", "count", "cut", "emit", "migrate")
+EXPORTED_SYMBOLS = (
+    "msched_create", "msched_destroy", "msched_kernel_register", "msched_task_create",
+    "msched_launch_enqueue", "msched_launch_retire", "msched_plan", "msched_migrate",
+    "msched_pagetable_query", "msched_plan_copy_lists", "msched_state_copy",
+    "msched_set_profiling", "msched_get_phase_ms", "msched_strerror", "msched_last_hip_error",
+)
+
+
+class _Config(C.Structure):
+    _fields_ = [("page_shift", C.c_uint32), ("n_frames", C.c_uint32), ("n_virtual_pages", C.c_uint64),
+                ("hbm_pool", C.c_void_p), ("host_store", C.c_void_p), ("n_host_slots", C.c_uint64),
+                ("host_slot", C.c_void_p), ("stream", C.c_void_p)]
+
+
+class _Rule(C.Structure):
+    _fields_ = [("kind", C.c_uint8), ("base_arg", C.c_uint8), ("n_size_args", C.c_uint8),
+                ("n_stride_args", C.c_uint8), ("n_count_args", C.c_uint8),
+                ("size_args", C.c_uint8 * 4), ("stride_args", C.c_uint8 * 4), ("count_args", C.c_uint8 * 4),
+                ("reserved", C.c_uint8 * 7),
+                ("size_coeff", C.c_uint64), ("stride_coeff", C.c_uint64), ("count_coeff", C.c_uint64)]
+
+
+class _TimelineEntry(C.Structure):
+    _fields_ = [("task", C.c_uint32), ("timeslice", C.c_uint32)]
+
+
+class _Plan(C.Structure):
+    _fields_ = [("n_evict", C.c_uint32), ("n_fetch", C.c_uint32), ("n_free_used", C.c_uint32),
+                ("covered_launches", C.c_uint32), ("g_cut", C.c_uint32), ("g_end0", C.c_uint32),
+                ("n_commands", C.c_uint32), ("reserved", C.c_uint32),
+                ("evict_pages", C.c_void_p), ("evict_frames", C.c_void_p),
+                ("fetch_pages", C.c_void_p), ("fetch_frames", C.c_void_p), ("plan_id", C.c_uint64)]
+
+
+assert C.sizeof(_Rule) == 48
+
+
+class MSchedError(RuntimeError):
+    NAMES = {-1: "E_INVAL", -2: "E_RANGE", -3: "E_OVERFLOW", -4: "E_WSET_TOO_LARGE",
+             -5: "E_STALE_PLAN", -6: "E_NOMEM", -7: "E_HIP"}
+
+    def __init__(self, code, text="", hip=0):
+        self.code, self.name, self.hip = code, self.NAMES.get(code, "?"), hip
+        super().__init__(f"msched error {code} ({self.name}): {text}" + (f" [hipError {hip}]" if hip else ""))
+
+
+def library_path() -> str:
+    return os.path.join(_PKG, "libmsched.so")
+
+
+_lib = None
+
+
+def load_library():
+    """Load libmsched.so.  Raises if it has not been built: there is no other path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with paper_2512_24637_amd.build.build() "
+                          "(hipcc --offload-arch=gfx950); there is no CPU fallback")
+    lib = C.CDLL(path)
+    vp, u32, u64 = C.c_void_p, C.c_uint32, C.c_uint64
+    sig = {
+        "msched_create": [C.POINTER(_Config), C.POINTER(vp)],
+        "msched_destroy": [vp],
+        "msched_kernel_register": [vp, C.POINTER(_Rule), u32, C.POINTER(u32)],
+        "msched_task_create": [vp, C.POINTER(u32)],
+        "msched_launch_enqueue": [vp, u32, u32, vp, u32, u32, vp, u32],
+        "msched_launch_retire": [vp, u32, u32],
+        "msched_plan": [vp, C.POINTER(_TimelineEntry), u32, C.POINTER(_Plan)],
+        "msched_migrate": [vp, C.POINTER(_Plan)],
+        "msched_pagetable_query": [vp, vp, u32, vp],
+        "msched_plan_copy_lists": [vp, C.POINTER(_Plan), vp, vp, vp, vp],
+        "msched_state_copy": [vp, vp, vp],
+        "msched_set_profiling": [vp, C.c_int],
+        "msched_get_phase_ms": [vp, vp],
+        "msched_last_hip_error": [vp],
+    }
+    for name, argtypes in sig.items():
+        fn = getattr(lib, name)
+        fn.argtypes, fn.restype = argtypes, C.c_int
+    lib.msched_strerror.argtypes, lib.msched_strerror.restype = [C.c_int], C.c_char_p
+    _lib = lib
+    return lib
+
+
+def _np_ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+@dataclass
+class Plan:
+    n_evict: int
+    n_fetch: int
+    n_free_used: int
+    covered_launches: int
+    g_cut: int
+    g_end0: int
+    n_commands: int
+    plan_id: int
+    _raw: object = None
+    _owner: object = None
+
+    def _lists(self):
+        if getattr(self, "_cache", None) is None:
+            self._cache = self._owner.plan_lists(self)
+        return self._cache
+
+    @property
+    def evict_pages(self): return self._lists()[0]
+    @property
+    def evict_frames(self): return self._lists()[1]
+    @property
+    def fetch_pages(self): return self._lists()[2]
+    @property
+    def fetch_frames(self): return self._lists()[3]
+
+
+class MSched:
+    """One memory-scheduling context on the current GPU.
+
+    hbm_pool / host_store are addresses of caller-owned buffers (a device tensor and a
+    pinned host tensor); `stream` is a hipStream_t handle (e.g. torch's cuda_stream).
+    ids_pool_ptr is the device address of the page-id pool that LIST launches index into.
+    """
+
+    def __init__(self, page_shift, n_virtual_pages, n_frames, hbm_pool_ptr, host_store_ptr,
+                 n_host_slots, host_slot: Optional[np.ndarray] = None, stream: int = 0,
+                 ids_pool_ptr: int = 0):
+        self.lib = load_library()
+        self.page_shift, self.V, self.F = int(page_shift), int(n_virtual_pages), int(n_frames)
+        self._slot = None if host_slot is None else np.ascontiguousarray(host_slot, np.uint32)
+        self.ids_pool_ptr = int(ids_pool_ptr)
+        cfg = _Config(self.page_shift, self.F, self.V, hbm_pool_ptr, host_store_ptr, int(n_host_slots),
+                      None if self._slot is None else self._slot.ctypes.data, stream or None)
+        h = C.c_void_p()
+        self.h = None
+        self._check(self.lib.msched_create(C.byref(cfg), C.byref(h)))
+        self.h = h
+        self._last = None
+
+    def _check(self, rc):
+        if rc != 0:
+            hip = self.lib.msched_last_hip_error(self.h) if self.h else 0
+            raise MSchedError(rc, self.lib.msched_strerror(rc).decode(), hip)
+
+    def close(self):
+        if self.h:
+            self.lib.msched_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def kernel_register(self, rules: Sequence) -> int:
+        arr = (_Rule * max(len(rules), 1))()
+        for r, q in enumerate(rules):
+            if max(len(q.size_args), len(q.stride_args), len(q.count_args)) > 4:
+                raise MSchedError(-1, "more than 4 arguments in a product")
+            arr[r].kind, arr[r].base_arg = q.kind, q.base_arg
+            arr[r].n_size_args, arr[r].n_stride_args, arr[r].n_count_args = (
+                len(q.size_args), len(q.stride_args), len(q.count_args))
+            for j, a in enumerate(q.size_args): arr[r].size_args[j] = a
+            for j, a in enumerate(q.stride_args): arr[r].stride_args[j] = a
+            for j, a in enumerate(q.count_args): arr[r].count_args[j] = a
+            arr[r].size_coeff, arr[r].stride_coeff, arr[r].count_coeff = (
+                q.size_coeff, q.stride_coeff, q.count_coeff)
+        kid = C.c_uint32()
+        self._check(self.lib.msched_kernel_register(self.h, arr, len(rules), C.byref(kid)))
+        return kid.value
+
+    def task_create(self) -> int:
+        tid = C.c_uint32()
+        self._check(self.lib.msched_task_create(self.h, C.byref(tid)))
+        return tid.value
+
+    def launch_enqueue(self, task, kernel_id, args, n_args, latency=1, ids_off=0, n_ids=0, ids_ptr=None):
+        a = np.zeros(12, np.uint64)
+        m = min(int(n_args), 12)
+        a[:m] = np.asarray(args, np.uint64)[:m]
+        if ids_ptr is None:
+            ids_ptr = (self.ids_pool_ptr + 4 * int(ids_off)) if n_ids else None
+        self._check(self.lib.msched_launch_enqueue(self.h, task, kernel_id, _np_ptr(a), n_args, latency,
+                                                   ids_ptr, n_ids))
+
+    def launch_retire(self, task, n):
+        self._check(self.lib.msched_launch_retire(self.h, task, n))
+
+    def plan(self, timeline) -> Plan:
+        n = len(timeline)
+        tl = (_TimelineEntry * max(n, 1))()
+        for i, (t, s) in enumerate(timeline):
+            tl[i].task, tl[i].timeslice = int(t), int(s)
+        raw = _Plan()
+        self._check(self.lib.msched_plan(self.h, tl, n, C.byref(raw)))
+        self._last = Plan(raw.n_evict, raw.n_fetch, raw.n_free_used, raw.covered_launches, raw.g_cut,
+                          raw.g_end0, raw.n_commands, raw.plan_id, raw, self)
+        return self._last
+
+    def migrate(self, plan: Optional[Plan] = None):
+        plan = plan or self._last
+        if plan is None:
+            raise MSchedError(-5, "no plan")
+        plan._lists()                      # read the lists back before they can be overwritten
+        self._check(self.lib.msched_migrate(self.h, C.byref(plan._raw)))
+
+    def migrate_only(self, plan: Optional[Plan] = None):
+        """migrate without first copying the lists to the host (timed runs)."""
+        plan = plan or self._last
+        self._check(self.lib.msched_migrate(self.h, C.byref(plan._raw)))
+
+    def plan_lists(self, plan: Plan):
+        ne, nf = plan.n_evict, plan.n_fetch
+        ep, ef = np.zeros(max(ne, 1), np.uint32), np.zeros(max(ne, 1), np.uint32)
+        fp, ff = np.zeros(max(nf, 1), np.uint32), np.zeros(max(nf, 1), np.uint32)
+        self._check(self.lib.msched_plan_copy_lists(self.h, C.byref(plan._raw), _np_ptr(ep), _np_ptr(ef),
+                                                    _np_ptr(fp), _np_ptr(ff)))
+        return ep[:ne], ef[:ne], fp[:nf], ff[:nf]
+
+    def pagetable_query(self, pages) -> np.ndarray:
+        pages = np.ascontiguousarray(pages, np.uint64)
+        out = np.zeros(max(pages.shape[0], 1), np.uint32)
+        self._check(self.lib.msched_pagetable_query(self.h, _np_ptr(pages), pages.shape[0], _np_ptr(out)))
+        return out[:pages.shape[0]]
+
+    def state(self):
+        pt, fo = np.zeros(self.V, np.uint32), np.zeros(self.F, np.uint32)
+        self._check(self.lib.msched_state_copy(self.h, _np_ptr(pt), _np_ptr(fo)))
+        return pt, fo
+
+    def set_profiling(self, on: bool):
+        self._check(self.lib.msched_set_profiling(self.h, int(on)))
+
+    def phase_ms(self) -> dict:
+        ms = np.zeros(len(PHASES), np.float32)
+        self._check(self.lib.msched_get_phase_ms(self.h, _np_ptr(ms)))
+        return dict(zip(PHASES, ms.tolist()))
+
+    def slot_of(self, pages):
+        pages = np.asarray(pages, np.int64)
+        return pages if self._slot is None else self._slot[pages].astype(np.int64)

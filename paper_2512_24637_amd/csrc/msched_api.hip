@@ -1,0 +1,379 @@
+// C-ABI entry points of libmsched: context, template registry, per-task command queues,
+// timeline flattening, and the calls that drive the planning and migration kernels.
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "msched_internal.h"
+
+using namespace msched;
+
+namespace {
+
+#define HIP_TRY(c, x)                                                \
+    do {                                                             \
+        hipError_t e_ = (x);                                         \
+        if (e_ != hipSuccess) { (c)->last_hip = (int)e_; return MSCHED_E_HIP; } \
+    } while (0)
+
+// value = coeff * product(args[idx]), refusing arithmetic that leaves 64 bits (Sec. 5.2: extents
+// are a linear coefficient times a product of launch arguments).
+int checked_formula(uint64_t coeff, const uint8_t *idx, int n, const uint64_t *args, uint32_t n_args, uint64_t *out) {
+    uint64_t v = coeff;
+    for (int j = 0; j < n; ++j) {
+        if (idx[j] >= n_args) return MSCHED_E_RANGE;
+        if (__builtin_mul_overflow(v, args[idx[j]], &v)) return MSCHED_E_OVERFLOW;
+    }
+    *out = v;
+    return MSCHED_OK;
+}
+
+int check_range(const msched_ctx *c, uint64_t addr, uint64_t len) {
+    if (len == 0) return MSCHED_OK;
+    uint64_t last;
+    if (__builtin_add_overflow(addr, len - 1, &last)) return MSCHED_E_OVERFLOW;
+    if ((last >> c->page_shift) >= c->V) return MSCHED_E_RANGE;
+    return MSCHED_OK;
+}
+
+// Evaluate every rule once on the host so that nothing the kernels will touch can be out of bounds.
+int validate_launch(const msched_ctx *c, const DevKernel &k, const uint64_t *args, uint32_t n_args) {
+    for (uint32_t r = 0; r < k.n_rules; ++r) {
+        const msched_rule &q = k.rules[r];
+        if (q.kind == MSCHED_RULE_LIST) continue;
+        if (q.base_arg >= n_args) return MSCHED_E_RANGE;
+        const uint64_t base = args[q.base_arg];
+        uint64_t size, stride, count;
+        int rc;
+        if ((rc = checked_formula(q.size_coeff, q.size_args, q.n_size_args, args, n_args, &size))) return rc;
+        if (q.kind != MSCHED_RULE_STRIDED) {
+            if ((rc = check_range(c, base, size))) return rc;
+            continue;
+        }
+        if ((rc = checked_formula(q.stride_coeff, q.stride_args, q.n_stride_args, args, n_args, &stride))) return rc;
+        if ((rc = checked_formula(q.count_coeff, q.count_args, q.n_count_args, args, n_args, &count))) return rc;
+        if (size == 0 || count == 0) continue;
+        uint64_t span, last_start;                       // the last chunk reaches farthest
+        if (__builtin_mul_overflow(count - 1, stride, &span)) return MSCHED_E_OVERFLOW;
+        if (__builtin_add_overflow(base, span, &last_start)) return MSCHED_E_OVERFLOW;
+        if ((rc = check_range(c, last_start, size))) return rc;
+    }
+    return MSCHED_OK;
+}
+
+void free_ctx(msched_ctx *c) {
+    if (!c) return;
+    (void)hipStreamSynchronize(c->stream);
+    for (auto &t : c->tasks) if (t.recs) (void)hipHostFree(t.recs);
+    void *dev[] = {c->page_table, c->frame_owner, c->nu, c->slot, c->evict_pages, c->evict_frames, c->fetch_pages,
+                   c->fetch_frames, c->flags, c->matrix, c->partial, c->offsets, c->hdr_dev, c->kernels_dev,
+                   c->query_buf};
+    for (void *p : dev) if (p) (void)hipFree(p);
+    if (c->hdr_host) (void)hipHostFree(c->hdr_host);
+    if (c->cmd_ptrs_host) (void)hipHostFree((void *)c->cmd_ptrs_host);
+    for (auto &e : c->ev) if (e) (void)hipEventDestroy(e);
+    delete c;
+}
+
+int env_u32(const char *name, uint32_t lo, uint32_t hi, uint32_t dflt) {
+    const char *s = getenv(name);
+    if (!s || !*s) return (int)dflt;
+    long v = strtol(s, nullptr, 10);
+    if (v < (long)lo || v > (long)hi) return (int)dflt;
+    return (int)v;
+}
+
+}  // namespace
+
+extern "C" {
+
+int msched_create(const msched_config *cfg, msched_ctx **out) {
+    if (!cfg || !out) return MSCHED_E_INVAL;
+    if (cfg->page_shift < 6 || cfg->page_shift > 30 || cfg->n_frames == 0 || cfg->n_virtual_pages == 0 ||
+        cfg->n_virtual_pages >= 0xFFFFFFFFull || !cfg->hbm_pool || !cfg->host_store ||
+        ((uintptr_t)cfg->hbm_pool & 15) || ((uintptr_t)cfg->host_store & 15))
+        return MSCHED_E_INVAL;
+    if (!cfg->host_slot && cfg->n_host_slots < cfg->n_virtual_pages) return MSCHED_E_INVAL;
+    if (cfg->host_slot)
+        for (uint64_t p = 0; p < cfg->n_virtual_pages; ++p)
+            if (cfg->host_slot[p] != MSCHED_NO_SLOT && cfg->host_slot[p] >= cfg->n_host_slots) return MSCHED_E_RANGE;
+    msched_ctx *c = new (std::nothrow) msched_ctx();
+    if (!c) return MSCHED_E_NOMEM;
+    c->cfg = *cfg;
+    c->cfg.host_slot = nullptr;
+    c->stream = (hipStream_t)cfg->stream;
+    c->V = cfg->n_virtual_pages; c->F = cfg->n_frames; c->page_shift = cfg->page_shift;
+    c->migrate_chunk_shift = (uint32_t)env_u32("MSCHED_MIGRATE_CHUNK_SHIFT", 6, 24, 14);
+    c->migrate_max_blocks = (uint32_t)env_u32("MSCHED_MIGRATE_BLOCKS", 1, 1 << 20, 4096);
+    int rc = MSCHED_OK;
+    auto fail = [&](hipError_t e) { c->last_hip = (int)e; rc = MSCHED_E_HIP; };
+    hipError_t e;
+#define ALLOC(ptr, bytes) if (rc == MSCHED_OK && (e = hipMalloc((void **)&(ptr), (bytes))) != hipSuccess) fail(e)
+    ALLOC(c->page_table, c->V * 4);
+    ALLOC(c->frame_owner, (size_t)c->F * 4);
+    ALLOC(c->nu, c->V * 4);
+    ALLOC(c->evict_pages, (size_t)c->F * 4);
+    ALLOC(c->evict_frames, (size_t)c->F * 4);
+    ALLOC(c->fetch_pages, (size_t)c->F * 4);
+    ALLOC(c->fetch_frames, (size_t)c->F * 4);
+    ALLOC(c->flags, 256);
+    ALLOC(c->offsets, (size_t)2 * (MSCHED_MAX_TIMELINE_COMMANDS + 1) * 4);
+    ALLOC(c->hdr_dev, sizeof(PlanHeader));
+    if (cfg->host_slot) {
+        ALLOC(c->slot, c->V * 4);
+        if (rc == MSCHED_OK && (e = hipMemcpy(c->slot, cfg->host_slot, c->V * 4, hipMemcpyHostToDevice)) != hipSuccess) fail(e);
+    }
+#undef ALLOC
+    if (rc == MSCHED_OK && (e = hipHostMalloc((void **)&c->hdr_host, sizeof(PlanHeader), hipHostMallocDefault)) != hipSuccess) fail(e);
+    if (rc == MSCHED_OK && (e = hipHostMalloc((void **)&c->cmd_ptrs_host,
+                                              sizeof(void *) * (MSCHED_MAX_TIMELINE_COMMANDS + 1), hipHostMallocDefault)) != hipSuccess) fail(e);
+    if (rc == MSCHED_OK && (e = hipHostGetDevicePointer((void **)&c->cmd_ptrs_dev, (void *)c->cmd_ptrs_host, 0)) != hipSuccess) fail(e);
+    if (rc == MSCHED_OK && (e = hipHostGetDevicePointer(&c->host_dev, cfg->host_store, 0)) != hipSuccess) fail(e);
+    for (int i = 0; i < 8 && rc == MSCHED_OK; ++i)
+        if ((e = hipEventCreate(&c->ev[i])) != hipSuccess) fail(e);
+    if (rc == MSCHED_OK && (e = launch_init_tables(c)) != hipSuccess) fail(e);
+    if (rc == MSCHED_OK && (e = hipStreamSynchronize(c->stream)) != hipSuccess) fail(e);
+    if (rc != MSCHED_OK) { free_ctx(c); return rc; }
+    *out = c;
+    return MSCHED_OK;
+}
+
+int msched_destroy(msched_ctx *ctx) {
+    if (!ctx) return MSCHED_E_INVAL;
+    free_ctx(ctx);
+    return MSCHED_OK;
+}
+
+int msched_kernel_register(msched_ctx *c, const msched_rule *rules, uint32_t n_rules, uint32_t *kernel_id) {
+    if (!c || !kernel_id || n_rules > MSCHED_MAX_RULES || (n_rules && !rules)) return MSCHED_E_INVAL;
+    DevKernel k;
+    memset(&k, 0, sizeof k);
+    k.n_rules = n_rules;
+    for (uint32_t r = 0; r < n_rules; ++r) {
+        const msched_rule &q = rules[r];
+        if (q.kind < MSCHED_RULE_FIXED || q.kind > MSCHED_RULE_LIST) return MSCHED_E_INVAL;
+        if (q.n_size_args > MSCHED_MAX_PRODUCT_ARGS || q.n_stride_args > MSCHED_MAX_PRODUCT_ARGS ||
+            q.n_count_args > MSCHED_MAX_PRODUCT_ARGS)
+            return MSCHED_E_INVAL;
+        if (q.kind == MSCHED_RULE_FIXED && q.n_size_args != 0) return MSCHED_E_INVAL;
+        k.rules[r] = q;
+    }
+    // the table is small and changes rarely: keep a device copy in step with the host one
+    if (c->kernels.size() + 1 > c->kernels_cap) {
+        const size_t ncap = std::max<size_t>(64, c->kernels_cap * 2);
+        DevKernel *nd = nullptr;
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        HIP_TRY(c, hipMalloc((void **)&nd, ncap * sizeof(DevKernel)));
+        if (!c->kernels.empty())
+            HIP_TRY(c, hipMemcpy(nd, c->kernels.data(), c->kernels.size() * sizeof(DevKernel), hipMemcpyHostToDevice));
+        if (c->kernels_dev) HIP_TRY(c, hipFree(c->kernels_dev));
+        c->kernels_dev = nd;
+        c->kernels_cap = ncap;
+    }
+    HIP_TRY(c, hipMemcpy(c->kernels_dev + c->kernels.size(), &k, sizeof k, hipMemcpyHostToDevice));
+    c->kernels.push_back(k);
+    c->max_rules = std::max(c->max_rules, n_rules);
+    *kernel_id = (uint32_t)(c->kernels.size() - 1);
+    return MSCHED_OK;
+}
+
+int msched_task_create(msched_ctx *c, uint32_t *task_id) {
+    if (!c || !task_id) return MSCHED_E_INVAL;
+    c->tasks.emplace_back();
+    *task_id = (uint32_t)(c->tasks.size() - 1);
+    return MSCHED_OK;
+}
+
+int msched_launch_enqueue(msched_ctx *c, uint32_t task, uint32_t kernel_id, const uint64_t *args, uint32_t n_args,
+                          uint32_t latency_ticks, const uint32_t *id_list, uint32_t n_ids) {
+    if (!c || task >= c->tasks.size() || kernel_id >= c->kernels.size() || n_args > MSCHED_MAX_ARGS ||
+        (n_args && !args) || (n_ids && !id_list))
+        return MSCHED_E_INVAL;
+    const int rc = validate_launch(c, c->kernels[kernel_id], args, n_args);
+    if (rc) return rc;
+    TaskQueue &t = c->tasks[task];
+    if (t.n - t.base == t.cap) {
+        // Grow the pinned record array, dropping retired records.  No kernel can be reading it:
+        // msched_plan returns only after its kernels have finished.
+        const size_t live = t.n - t.cursor;
+        const size_t ncap = std::max<size_t>(256, live * 2);
+        CmdRec *nr = nullptr, *nd = nullptr;
+        HIP_TRY(c, hipHostMalloc((void **)&nr, ncap * sizeof(CmdRec), hipHostMallocDefault));
+        HIP_TRY(c, hipHostGetDevicePointer((void **)&nd, nr, 0));
+        if (live) memcpy(nr, t.recs + (t.cursor - t.base), live * sizeof(CmdRec));
+        if (t.recs) HIP_TRY(c, hipHostFree(t.recs));
+        t.recs = nr; t.recs_dev = nd; t.cap = ncap; t.base = t.cursor;
+    }
+    CmdRec &r = t.recs[t.n - t.base];
+    memset(&r, 0, sizeof r);
+    r.kernel = kernel_id; r.n_args = n_args; r.latency = latency_ticks; r.n_ids = n_ids; r.ids = id_list;
+    for (uint32_t i = 0; i < n_args; ++i) r.args[i] = args[i];
+    t.n++;
+    return MSCHED_OK;
+}
+
+int msched_launch_retire(msched_ctx *c, uint32_t task, uint32_t n_launches) {
+    if (!c || task >= c->tasks.size()) return MSCHED_E_INVAL;
+    TaskQueue &t = c->tasks[task];
+    if (t.cursor + n_launches > t.n) return MSCHED_E_RANGE;
+    t.cursor += n_launches;
+    return MSCHED_OK;
+}
+
+int msched_plan(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entries, msched_plan_t *out) {
+    if (!c || !out || (n_entries && !tl) || n_entries > MSCHED_MAX_TIMELINE_ENTRIES) return MSCHED_E_INVAL;
+    for (uint32_t e = 0; e < n_entries; ++e) if (tl[e].task >= c->tasks.size()) return MSCHED_E_INVAL;
+    c->pending_plan = 0;
+
+    // Flatten the timeline into the order of future commands (Sec. 6.1: the timeline says which
+    // task runs, for how long and in what order; Sec. 6.2: each queue holds command latencies).
+    // A command belongs to the entry in which it starts.  G sizes every launch below, so this
+    // short walk is done here and its result handed to the kernels as a table of record addresses.
+    std::vector<size_t> pos(c->tasks.size());
+    for (size_t t = 0; t < c->tasks.size(); ++t) pos[t] = c->tasks[t].cursor;
+    uint32_t G = 0, g_end0 = 0;
+    for (uint32_t e = 0; e < n_entries; ++e) {
+        TaskQueue &t = c->tasks[tl[e].task];
+        size_t &p = pos[tl[e].task];
+        uint64_t elapsed = 0;
+        while (p < t.n && elapsed < tl[e].timeslice) {
+            if (G == MSCHED_MAX_TIMELINE_COMMANDS) return MSCHED_E_INVAL;
+            c->cmd_ptrs_host[G++] = t.recs_dev + (p - t.base);
+            elapsed += t.recs[p - t.base].latency;
+            ++p;
+        }
+        if (e == 0) g_end0 = G;
+    }
+    memset(out, 0, sizeof *out);
+    out->g_end0 = g_end0;
+    out->n_commands = G;
+    out->evict_pages = c->evict_pages; out->evict_frames = c->evict_frames;
+    out->fetch_pages = c->fetch_pages; out->fetch_frames = c->fetch_frames;
+    PlanHeader h;
+    memset(&h, 0, sizeof h);
+    h.n_resident = c->n_resident; h.first_free = c->n_resident;
+    if (G > 0) {
+        PlanGeom g;
+        g.G = G; g.g_end0 = g_end0; g.n_keys = 2 * (G + 1);
+        const uint64_t per = (c->V + kMaxChunks - 1) / kMaxChunks;
+        g.chunk_pages = (uint32_t)std::max<uint64_t>(kMinChunkPages, (per + 255) / 256 * 256);
+        g.n_chunks = (uint32_t)((c->V + g.chunk_pages - 1) / g.chunk_pages);
+        const size_t need = (size_t)g.n_chunks * g.n_keys;
+        if (need > c->matrix_cap) {
+            HIP_TRY(c, hipStreamSynchronize(c->stream));
+            if (c->matrix) HIP_TRY(c, hipFree(c->matrix));
+            c->matrix = nullptr; c->matrix_cap = 0;
+            HIP_TRY(c, hipMalloc((void **)&c->matrix, need * 4));
+            c->matrix_cap = need;
+        }
+        const size_t pneed = (size_t)kRowGroups * g.n_keys;
+        if (pneed > c->partial_cap) {
+            HIP_TRY(c, hipStreamSynchronize(c->stream));
+            if (c->partial) HIP_TRY(c, hipFree(c->partial));
+            c->partial = nullptr; c->partial_cap = 0;
+            HIP_TRY(c, hipMalloc((void **)&c->partial, pneed * 4));
+            c->partial_cap = pneed;
+        }
+        HIP_TRY(c, launch_plan(c, g));
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        h = *c->hdr_host;
+        if (c->profiling)
+            for (int i = 0; i < 4; ++i) HIP_TRY(c, hipEventElapsedTime(&c->phase_ms[i], c->ev[i], c->ev[i + 1]));
+        if (h.status & kStatRange) return MSCHED_E_RANGE;
+        if (h.status & kStatWset) return MSCHED_E_WSET_TOO_LARGE;
+    }
+    out->n_fetch = h.n_fetch; out->n_evict = h.n_evict; out->n_free_used = h.n_free_used;
+    out->g_cut = h.g_cut; out->covered_launches = h.g_cut;
+    out->plan_id = ++c->plan_seq;
+    c->pending_plan = out->plan_id;
+    c->pending = h;
+    return MSCHED_OK;
+}
+
+int msched_migrate(msched_ctx *c, const msched_plan_t *plan) {
+    if (!c || !plan) return MSCHED_E_INVAL;
+    if (c->pending_plan == 0 || plan->plan_id != c->pending_plan) return MSCHED_E_STALE_PLAN;
+    if (c->profiling) HIP_TRY(c, hipEventRecord(c->ev[5], c->stream));
+    HIP_TRY(c, launch_migrate(c, c->pending));
+    if (c->profiling) HIP_TRY(c, hipEventRecord(c->ev[6], c->stream));
+    c->n_resident += c->pending.n_free_used;
+    c->pending_plan = 0;
+    return MSCHED_OK;
+}
+
+int msched_pagetable_query(msched_ctx *c, const uint64_t *page_ids, uint32_t n, uint32_t *out) {
+    if (!c || (n && (!page_ids || !out))) return MSCHED_E_INVAL;
+    for (uint32_t i = 0; i < n; ++i) if (page_ids[i] >= c->V) return MSCHED_E_RANGE;
+    if (n == 0) return MSCHED_OK;
+    if ((size_t)n * 2 > c->query_cap) {
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        if (c->query_buf) HIP_TRY(c, hipFree(c->query_buf));
+        c->query_buf = nullptr; c->query_cap = 0;
+        HIP_TRY(c, hipMalloc((void **)&c->query_buf, (size_t)n * 2 * 4));
+        c->query_cap = (size_t)n * 2;
+    }
+    std::vector<uint32_t> ids(n);
+    for (uint32_t i = 0; i < n; ++i) ids[i] = (uint32_t)page_ids[i];
+    HIP_TRY(c, hipMemcpyAsync(c->query_buf, ids.data(), (size_t)n * 4, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, launch_query(c, c->query_buf, n, c->query_buf + n));
+    HIP_TRY(c, hipMemcpyAsync(out, c->query_buf + n, (size_t)n * 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return MSCHED_OK;
+}
+
+int msched_plan_copy_lists(msched_ctx *c, const msched_plan_t *plan, uint32_t *evict_pages, uint32_t *evict_frames,
+                           uint32_t *fetch_pages, uint32_t *fetch_frames) {
+    if (!c || !plan) return MSCHED_E_INVAL;
+    if (plan->plan_id != c->plan_seq) return MSCHED_E_STALE_PLAN;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    const size_t ne = (size_t)plan->n_evict * 4, nf = (size_t)plan->n_fetch * 4;
+    if (evict_pages && ne) HIP_TRY(c, hipMemcpy(evict_pages, c->evict_pages, ne, hipMemcpyDeviceToHost));
+    if (evict_frames && ne) HIP_TRY(c, hipMemcpy(evict_frames, c->evict_frames, ne, hipMemcpyDeviceToHost));
+    if (fetch_pages && nf) HIP_TRY(c, hipMemcpy(fetch_pages, c->fetch_pages, nf, hipMemcpyDeviceToHost));
+    if (fetch_frames && nf) HIP_TRY(c, hipMemcpy(fetch_frames, c->fetch_frames, nf, hipMemcpyDeviceToHost));
+    return MSCHED_OK;
+}
+
+int msched_state_copy(msched_ctx *c, uint32_t *page_table, uint32_t *frame_owner) {
+    if (!c) return MSCHED_E_INVAL;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (page_table) HIP_TRY(c, hipMemcpy(page_table, c->page_table, c->V * 4, hipMemcpyDeviceToHost));
+    if (frame_owner) HIP_TRY(c, hipMemcpy(frame_owner, c->frame_owner, (size_t)c->F * 4, hipMemcpyDeviceToHost));
+    return MSCHED_OK;
+}
+
+int msched_set_profiling(msched_ctx *c, int on) {
+    if (!c) return MSCHED_E_INVAL;
+    c->profiling = on ? 1 : 0;
+    return MSCHED_OK;
+}
+
+int msched_get_phase_ms(msched_ctx *c, float *ms) {
+    if (!c || !ms) return MSCHED_E_INVAL;
+    if (c->profiling) {
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        float m = 0.f;
+        if (hipEventElapsedTime(&m, c->ev[5], c->ev[6]) == hipSuccess) c->phase_ms[MSCHED_PHASE_MIGRATE] = m;
+    }
+    for (int i = 0; i < MSCHED_N_PHASES; ++i) ms[i] = c->phase_ms[i];
+    return MSCHED_OK;
+}
+
+const char *msched_strerror(int code) {
+    switch (code) {
+        case MSCHED_OK: return "ok";
+        case MSCHED_E_INVAL: return "invalid argument";
+        case MSCHED_E_RANGE: return "page, slot or argument index out of range";
+        case MSCHED_E_OVERFLOW: return "template arithmetic overflows 64 bits";
+        case MSCHED_E_WSET_TOO_LARGE: return "first command's working set exceeds the frame pool";
+        case MSCHED_E_STALE_PLAN: return "plan is not the latest or was already carried out";
+        case MSCHED_E_NOMEM: return "out of memory";
+        case MSCHED_E_HIP: return "HIP call failed";
+        default: return "unknown error";
+    }
+}
+
+int msched_last_hip_error(msched_ctx *c) { return c ? c->last_hip : 0; }
+
+}  // extern "C"

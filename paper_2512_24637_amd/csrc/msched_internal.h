@@ -1,0 +1,99 @@
+// Internal declarations shared by the HIP translation units of libmsched.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <vector>
+
+#include "msched.h"
+
+namespace msched {
+
+constexpr uint32_t kNone = 0xFFFFFFFFu;         // not resident / free frame / no next use
+constexpr uint32_t kSkip = 0x80000000u;         // output offset of a class that is not emitted
+constexpr int kWave = 64;                       // CDNA wavefront
+constexpr uint32_t kMaxChunks = 2048;           // page-table chunks (one wavefront each)
+constexpr uint32_t kMinChunkPages = 1024;
+constexpr uint32_t kRowGroups = 32;             // row groups of the chunk x class count matrix
+
+// status bits raised by device code while planning
+constexpr uint32_t kStatRange = 1u;             // a LIST id >= V, or a touched page without backing slot
+constexpr uint32_t kStatWset = 2u;              // first command alone exceeds the pool
+
+// A queued launch as the expansion kernel reads it (lives in pinned, device-visible host memory).
+struct alignas(16) CmdRec {
+    uint32_t kernel, n_args, latency, n_ids;
+    const uint32_t *ids;                        // device pointer (caller-owned) or null
+    uint64_t reserved;
+    uint64_t args[MSCHED_MAX_ARGS];
+};
+static_assert(sizeof(CmdRec) == 128, "CmdRec layout");
+
+struct DevKernel {
+    uint32_t n_rules, pad;
+    msched_rule rules[MSCHED_MAX_RULES];
+};
+
+// Written by the cut kernel; read by later kernels (device copy) and by the host (pinned copy).
+struct PlanHeader {
+    uint32_t n_fetch, n_evict, n_free_used, g_cut;
+    uint32_t n_resident, status, first_free, pad;
+};
+
+struct TaskQueue {
+    CmdRec *recs = nullptr;                     // pinned host memory
+    CmdRec *recs_dev = nullptr;                 // same memory, device address
+    size_t cap = 0;                             // records allocated
+    size_t base = 0;                            // program-order index of recs[0]
+    size_t n = 0;                               // commands ever enqueued
+    size_t cursor = 0;                          // first command not yet retired
+};
+
+struct PlanGeom {
+    uint32_t G, g_end0, n_chunks, chunk_pages, n_keys;   // n_keys = 2 * (G + 1)
+};
+
+}  // namespace msched
+
+struct msched_ctx {
+    msched_config cfg;
+    hipStream_t stream;
+    uint64_t V;
+    uint32_t F, page_shift;
+    void *host_dev = nullptr;                   // device address of cfg.host_store
+    uint32_t migrate_chunk_shift = 14;          // bytes a workgroup moves per work unit (log2)
+    uint32_t migrate_max_blocks = 4096;         // grid cap of the copy kernel
+    uint32_t *page_table = nullptr, *frame_owner = nullptr, *nu = nullptr, *slot = nullptr;  // device
+    uint32_t *evict_pages = nullptr, *evict_frames = nullptr, *fetch_pages = nullptr, *fetch_frames = nullptr;
+    uint32_t *flags = nullptr;                  // device status word
+    uint32_t *matrix = nullptr; size_t matrix_cap = 0;       // [n_chunks][n_keys] counts, then offsets
+    uint32_t *partial = nullptr; size_t partial_cap = 0;     // [kRowGroups][n_keys]
+    uint32_t *offsets = nullptr;                // [2 * (MAX_G + 1)] per-class output offsets
+    msched::PlanHeader *hdr_dev = nullptr;      // device
+    msched::PlanHeader *hdr_host = nullptr;     // pinned
+    const msched::CmdRec **cmd_ptrs_host = nullptr;          // pinned: record of the g-th future command
+    const msched::CmdRec *const *cmd_ptrs_dev = nullptr;     // same memory, device address
+    msched::DevKernel *kernels_dev = nullptr; size_t kernels_cap = 0;
+    std::vector<msched::DevKernel> kernels;
+    std::vector<msched::TaskQueue> tasks;
+    uint32_t max_rules = 0;
+    uint32_t n_resident = 0;
+    uint64_t plan_seq = 0, pending_plan = 0;    // pending_plan == 0: nothing to migrate
+    msched::PlanHeader pending{};
+    uint32_t *query_buf = nullptr; size_t query_cap = 0;     // device scratch for pagetable_query
+    int profiling = 0;
+    hipEvent_t ev[8] = {};
+    float phase_ms[MSCHED_N_PHASES] = {};
+    int last_hip = 0;
+};
+
+namespace msched {
+
+// plan kernels (msched_plan.hip)
+hipError_t launch_plan(msched_ctx *c, const PlanGeom &g);
+// migrate + query kernels (msched_migrate.hip)
+hipError_t launch_migrate(msched_ctx *c, const PlanHeader &h);
+hipError_t launch_query(msched_ctx *c, const uint32_t *ids_dev, uint32_t n, uint32_t *out_dev);
+hipError_t launch_init_tables(msched_ctx *c);
+
+}  // namespace msched

@@ -1,0 +1,127 @@
+"""Shared plumbing of the GPU parity tests: device/pinned buffers for a trace, and the
+lock-step comparison of the HIP path against the CPU oracle."""
+import numpy as np
+
+from workloads import run_schedule, page_words, stamp_of
+from workloads.content import page_words_torch
+from workloads.harness import load_trace
+
+NONE = 0xFFFFFFFF
+POISON = 0x5A5A5A5A5A5A5A5A
+
+
+class GpuSide:
+    """Owns the torch buffers and the MSched context for one trace."""
+
+    def __init__(self, trace, fill="host"):
+        import torch
+        from paper_2512_24637_amd import MSched
+        self.torch, self.trace = torch, trace
+        dev = torch.device("cuda:0")
+        self.wpp = trace.page_bytes // 8
+        self.pool = torch.full((trace.n_frames, self.wpp), POISON, dtype=torch.int64, device=dev)
+        self.host = torch.empty((trace.n_slots, self.wpp), dtype=torch.int64, pin_memory=True)
+        self.ids = None
+        ids_ptr = 0
+        if trace.ids_pool.size:
+            self.ids = torch.from_numpy(trace.ids_pool.view(np.int32)).to(dev)
+            ids_ptr = self.ids.data_ptr()
+        self.pages_with_slot = (np.arange(trace.n_virtual_pages) if trace.host_slot is None
+                                else np.nonzero(trace.host_slot != NONE)[0])
+        self.fill_host_store()
+        torch.cuda.synchronize()
+        self.stream = torch.cuda.current_stream()
+        self.ms = MSched(trace.page_shift, trace.n_virtual_pages, trace.n_frames, self.pool.data_ptr(),
+                         self.host.data_ptr(), trace.n_slots, trace.host_slot,
+                         stream=self.stream.cuda_stream, ids_pool_ptr=ids_ptr)
+        load_trace(self.ms, trace)
+
+    def fill_host_store(self, chunk_pages=1 << 14):
+        """host[slot(p)] = initial contents of page p, generated on the device in chunks."""
+        torch = self.torch
+        pages = self.pages_with_slot
+        slot = pages if self.trace.host_slot is None else self.trace.host_slot[pages].astype(np.int64)
+        step = max(1, min(chunk_pages, (256 << 20) // self.trace.page_bytes))
+        for i in range(0, pages.size, step):
+            pg = torch.from_numpy(pages[i:i + step].astype(np.int64)).cuda()
+            words = page_words_torch(pg, self.wpp).cpu()
+            self.host[torch.from_numpy(np.asarray(slot[i:i + step], np.int64))] = words
+
+    def stamp(self, frames, idx, val):
+        torch = self.torch
+        if len(frames) == 0:
+            return
+        f = torch.from_numpy(np.asarray(frames, np.int64)).cuda()
+        i = torch.from_numpy(np.asarray(idx, np.int64)).cuda()
+        v = torch.from_numpy(np.asarray(val, np.uint64).view(np.int64)).cuda()
+        self.pool[f, i] = v
+
+    def pool_words(self):
+        self.torch.cuda.synchronize()
+        return self.pool.cpu().numpy().view(np.uint64)
+
+    def host_words(self):
+        self.torch.cuda.synchronize()
+        return self.host.numpy().view(np.uint64)
+
+    def close(self):
+        self.torch.cuda.synchronize()
+        self.ms.close()
+
+
+def make_oracle(oracle_mod, trace, with_bytes):
+    o = oracle_mod.Oracle.for_trace(trace, with_bytes=with_bytes)
+    load_trace(o, trace)
+    if with_bytes:
+        wpp = trace.page_bytes // 8
+        pages = (np.arange(trace.n_virtual_pages) if trace.host_slot is None
+                 else np.nonzero(trace.host_slot != NONE)[0])
+        o.host_words[o.slot_of(pages)] = page_words(pages, wpp)
+        o.pool_words[:] = np.uint64(POISON)
+    return o
+
+
+def assert_same_plan(po, pg, where):
+    for f in ("n_fetch", "n_evict", "n_free_used", "g_cut", "g_end0", "n_commands", "covered_launches"):
+        assert getattr(po, f) == getattr(pg, f), (where, f, getattr(po, f), getattr(pg, f))
+    for f in ("fetch_pages", "fetch_frames", "evict_pages", "evict_frames"):
+        a, b = getattr(po, f), getattr(pg, f)
+        if not np.array_equal(a, b):
+            bad = np.nonzero(a != b)[0]
+            raise AssertionError((where, f, "first mismatch at", int(bad[0]), a[bad[:5]], b[bad[:5]]))
+
+
+def lockstep(oracle_mod, trace, with_bytes=True, horizon="round", max_plans=None, bytes_every=1, log=None):
+    """Run the oracle and the HIP path side by side and require identical plans, page
+    tables, frame owners and (with_bytes) pool and host-store bytes after every switch."""
+    g = GpuSide(trace)
+    o = make_oracle(oracle_mod, trace, with_bytes)
+    wpp = trace.page_bytes // 8
+    n = 0
+    try:
+        for ro, rg in zip(run_schedule(trace, o, horizon=horizon, max_plans=max_plans),
+                          run_schedule(trace, g.ms, horizon=horizon, max_plans=max_plans)):
+            where = (trace.name, "plan", ro.index, "task", ro.task)
+            assert (ro.task, ro.first_launch, ro.timeline) == (rg.task, rg.first_launch, rg.timeline)
+            assert_same_plan(ro.plan, rg.plan, where)
+            idx, val = stamp_of(ro.plan.fetch_pages, ro.index, wpp)
+            if with_bytes:
+                o.pool_words[ro.plan.fetch_frames, idx] = val
+            g.stamp(rg.plan.fetch_frames, idx, val)
+            pto, foo = o.state()
+            ptg, fog = g.ms.state()
+            assert np.array_equal(pto, ptg), (where, "page table")
+            assert np.array_equal(foo, fog), (where, "frame owner")
+            if with_bytes and (n % bytes_every == 0):
+                assert np.array_equal(o.pool_words, g.pool_words()), (where, "pool bytes")
+                assert np.array_equal(o.host_words, g.host_words()), (where, "host bytes")
+            n += 1
+            if log:
+                log(f"{trace.name} plan {ro.index}: fetch {ro.plan.n_fetch} evict {ro.plan.n_evict} ok")
+        if with_bytes:
+            assert np.array_equal(o.pool_words, g.pool_words())
+            assert np.array_equal(o.host_words, g.host_words())
+    finally:
+        g.close()
+        o.close()
+    return n
