@@ -1,0 +1,320 @@
+#!/usr/bin/env python3
+"""Benchmark of the MSched hot path on one MI355X.
+
+A step is one context switch: msched_plan (timeline -> fetch / eviction lists) followed by
+msched_migrate (full-duplex batched copy + page-table update), on a synthetic schedule with
+the page structure of the configured workload.  Prints ONE JSON line on stdout.
+
+  value         migrated GB/s over the K timed steps (bytes evicted + fetched, divided by
+                the wall time of plan + migrate)
+  roofline      the copy kernel against the host link: the same byte mix at the
+                hipMemcpy rates measured in this run with both directions busy
+  roofline_plan the planning kernels against HBM bandwidth on the planning-stress
+                page structure (10 M pages, 4 M frames, 8 M page ids per plan)
+  cpu_baseline  the plain CPU oracle timed on a bounded sample of the same schedule
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class TimedImpl:
+    """Adapter between the round-robin driver and the MSched binding that keeps host work
+    out of the timed region (no list read-back) and collects per-phase device times."""
+
+    def __init__(self, ms, sync, profile=True):
+        self.ms, self.sync, self.profile = ms, sync, profile
+        self.plan_wall, self.phases, self.migrate_ms, self.plans = [], [], [], []
+        if profile:
+            ms.set_profiling(True)
+        self._pending_migrate = False
+
+    def plan(self, timeline):
+        self.sync()                          # the previous migrate is asynchronous: keep its tail out of the plan's time
+        t0 = time.perf_counter()
+        p = self.ms.plan(timeline)
+        self.plan_wall.append(time.perf_counter() - t0)
+        if self.profile:
+            ph = self.ms.phase_ms()          # stream is idle here: plan has just synchronised
+            if self._pending_migrate:
+                self.migrate_ms.append(ph["migrate"])
+            self.phases.append(ph)
+        self.plans.append(p)
+        return p
+
+    def migrate(self):
+        self.ms.migrate_only()
+        self._pending_migrate = True
+
+    def launch_retire(self, task, n):
+        self.ms.launch_retire(task, n)
+
+    def finish(self):
+        if self.profile and self._pending_migrate:
+            self.migrate_ms.append(self.ms.phase_ms()["migrate"])
+            self._pending_migrate = False
+
+
+def measure_link_peak(torch, nbytes=1 << 30, reps=3):
+    """Pinned hipMemcpyAsync rates: each direction alone, then both at once on two streams."""
+    dev = torch.device("cuda:0")
+    n = nbytes // 8
+    h_src = torch.empty(n, dtype=torch.int64, pin_memory=True).fill_(3)
+    h_dst = torch.empty(n, dtype=torch.int64, pin_memory=True).fill_(4)
+    d_dst = torch.empty(n, dtype=torch.int64, device=dev)
+    d_src = torch.full((n,), 5, dtype=torch.int64, device=dev)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def timed(fn_a, fn_b=None):
+        best = None
+        for _ in range(reps):
+            torch.cuda.synchronize()
+            ea0, ea1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            eb0, eb1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            with torch.cuda.stream(s1):
+                ea0.record(); fn_a(); ea1.record()
+            if fn_b:
+                with torch.cuda.stream(s2):
+                    eb0.record(); fn_b(); eb1.record()
+            torch.cuda.synchronize()
+            ta = ea0.elapsed_time(ea1) / 1e3
+            tb = eb0.elapsed_time(eb1) / 1e3 if fn_b else None
+            cur = (ta, tb)
+            if best is None or (ta + (tb or 0)) < (best[0] + (best[1] or 0)):
+                best = cur
+        return best
+
+    h2d = lambda: d_dst.copy_(h_src, non_blocking=True)
+    d2h = lambda: h_dst.copy_(d_src, non_blocking=True)
+    t_h2d, _ = timed(h2d)
+    t_d2h, _ = timed(d2h)
+    tb_h2d, tb_d2h = timed(h2d, d2h)
+    gb = nbytes / 1e9
+    # device copy as a cross-check of the HBM peak
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    d_dst.copy_(d_src)
+    e0.record()
+    for _ in range(5):
+        d_dst.copy_(d_src)
+    e1.record()
+    torch.cuda.synchronize()
+    hbm = 5 * 2 * gb / (e0.elapsed_time(e1) / 1e3)
+    del h_src, h_dst, d_dst, d_src
+    return {"h2d_alone_GBs": gb / t_h2d, "d2h_alone_GBs": gb / t_d2h,
+            "h2d_bidir_GBs": gb / tb_h2d, "d2h_bidir_GBs": gb / tb_d2h,
+            "hbm_copy_GBs": hbm, "bytes_each": nbytes}
+
+
+def make_context(torch, trace, fill_contents):
+    from paper_2512_24637_amd import MSched
+    from workloads.device import DeviceBuffers
+    from workloads.harness import load_trace
+    buf = DeviceBuffers(trace, fill_contents=fill_contents)
+    ms = MSched(trace.page_shift, trace.n_virtual_pages, trace.n_frames, buf.pool.data_ptr(),
+                buf.host.data_ptr(), trace.n_slots, trace.host_slot,
+                stream=torch.cuda.current_stream().cuda_stream, ids_pool_ptr=buf.ids_ptr)
+    load_trace(ms, trace)
+    return buf, ms
+
+
+def run_steps(torch, trace, ms, warmup, steps):
+    from workloads import run_schedule
+    impl = TimedImpl(ms, torch.cuda.current_stream().synchronize)
+    gen = run_schedule(trace, impl)
+    for _ in range(warmup):
+        next(gen)
+    impl.finish()
+    torch.cuda.synchronize()
+    n_warm_plans, n_warm_mig = len(impl.plans), len(impl.migrate_ms)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        next(gen)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    impl.finish()
+    plans = impl.plans[n_warm_plans:]
+    return {
+        "wall_s": wall,
+        "plans": plans,
+        "plan_wall_s": impl.plan_wall[n_warm_plans:],
+        "phases": impl.phases[n_warm_plans:],
+        "migrate_ms": impl.migrate_ms[n_warm_mig:],
+    }
+
+
+def planning_bytes(trace, plan, n_ids, n_touch_est):
+    """Algorithmic HBM bytes of one plan: next-use reset (4V), one scattered 4-byte update per
+    page-touch occurrence, the page-id lists (4 per id), two sweeps over page table + next use
+    (2 * 8V), and the list writes."""
+    V = trace.n_virtual_pages
+    return 4 * V + 4 * n_touch_est + 4 * n_ids + 16 * V + 4 * plan.n_fetch * 2 + 8 * plan.n_evict
+
+
+def cpu_baseline(trace_args, sample_steps):
+    """Oracle (plain C, one thread) on the first `sample_steps` switches of the same schedule,
+    with real byte copies between two host buffers standing for HBM and host DRAM."""
+    from oracle import oracle as oracle_mod
+    from workloads import make_trace, run_schedule
+    from workloads.harness import load_trace
+    trace = make_trace(**trace_args)
+    o = oracle_mod.Oracle.for_trace(trace, with_bytes=True)
+    o.pool_words.fill(1)
+    o.host_words.fill(2)                                   # touch every page before timing
+    load_trace(o, trace)
+    moved, n = 0, 0
+    t0 = time.perf_counter()
+    for rec in run_schedule(trace, o, max_plans=sample_steps):
+        moved += (rec.plan.n_fetch + rec.plan.n_evict) * trace.page_bytes
+        n += 1
+    dt = time.perf_counter() - t0
+    o.close()
+    return {"value": moved / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {n} context switches of the same schedule (plan + memcpy migrate), "
+                      f"{moved / 2**30:.1f} GiB moved in {dt:.1f} s",
+            "ms_per_step": dt / max(n, 1) * 1e3, "host_cores_available": os.cpu_count()}
+
+
+def miss_volume(trace_args):
+    """Pages fetched over the whole schedule: the plan path (= oracle, one round of look-ahead),
+    LRU demand paging, and Belady with the full trace as horizon (the paper's "Ideal")."""
+    from oracle import oracle as oracle_mod
+    from workloads import make_trace, run_schedule
+    from workloads.harness import load_trace
+    trace = make_trace(**trace_args)
+    out = {}
+    for horizon in ("round", "full"):
+        o = oracle_mod.Oracle.for_trace(trace)
+        load_trace(o, trace)
+        fetched, tasks, idx = 0, [], []
+        for rec in run_schedule(trace, o, horizon=horizon):
+            fetched += rec.plan.n_fetch
+            tasks += [rec.task] * rec.n_launches
+            idx += list(range(rec.first_launch, rec.first_launch + rec.n_launches))
+        out["belady_one_round_pages" if horizon == "round" else "belady_full_horizon_pages"] = fetched
+        if horizon == "round":
+            out["lru_demand_paging_pages"] = o.lru_faults(tasks, idx, trace.n_frames)
+        o.close()
+    out["lru_over_plan"] = out["lru_demand_paging_pages"] / max(1, out["belady_one_round_pages"])
+    return out
+
+
+def bench_planning_stress(torch, warmup=8, steps=16):
+    """c5 page structure (10 M pages, 4 M frames, 8 tasks, 2 dense ranges + 20 k Zipf ids per launch).
+    Planning never reads page bytes, so pages are shrunk to 64 B to keep the backing store small."""
+    from workloads import make_trace
+    slices = -(-(warmup + steps) // 8)
+    t0 = time.perf_counter()
+    trace = make_trace(5, page_shift=6, n_launches=50 * slices)
+    log(f"[bench] planning-stress trace: V={trace.n_virtual_pages} F={trace.n_frames} "
+        f"ids={trace.ids_pool.size} ({time.perf_counter() - t0:.1f} s to generate)")
+    buf, ms = make_context(torch, trace, fill_contents=False)
+    r = run_steps(torch, trace, ms, warmup, steps)
+    ids_per_plan = int(trace.tasks[0].n_ids[0]) * 50 * 8
+    touch_est = ids_per_plan + 2 * 50 * 8 * (1024 + 16384) // 2
+    dev_ms = [sum(ph[k] for k in ("expand", "count", "cut", "emit")) for ph in r["phases"]]
+    bytes_ = [planning_bytes(trace, p, ids_per_plan, touch_est) for p in r["plans"]]
+    ach = sum(bytes_) / (sum(dev_ms) / 1e3) / 1e9
+    phase_mean = {k: float(np.mean([ph[k] for ph in r["phases"]])) * 1e3 for k in ("expand", "count", "cut", "emit")}
+    out = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+           "traffic": None, "workload": "c5-planning-stress page structure (V=10485760, F=4194304, G=400)",
+           "plan_device_us_mean": float(np.mean(dev_ms)) * 1e3,
+           "plan_host_wall_us_mean": float(np.mean(r["plan_wall_s"])) * 1e6,
+           "phase_us_mean": phase_mean,
+           "algorithmic_bytes_per_plan": float(np.mean(bytes_)),
+           "n_fetch_mean": float(np.mean([p.n_fetch for p in r["plans"]])),
+           "n_evict_mean": float(np.mean([p.n_evict for p in r["plans"]]))}
+    ms.close()
+    del buf
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--no-plan-stress", action="store_true", help="skip the planning-stress leg")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-steps", type=int, default=80)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (a context is per GPU: N GPUs would be "
+              "N independent contexts)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    from workloads import make_trace
+
+    link = measure_link_peak(torch)
+    log(f"[bench] link peak: {json.dumps(link)}")
+
+    per_task = 25 * (-(-(args.steps + args.warmup) // 4))
+    trace_args = dict(config=2, n_launches=max(500, per_task))
+    trace = make_trace(**trace_args)
+    P = trace.page_bytes
+    buf, ms = make_context(torch, trace, fill_contents=True)
+    log(f"[bench] {trace.name}: V={trace.n_virtual_pages} F={trace.n_frames} page={P >> 10} KiB")
+    r = run_steps(torch, trace, ms, args.warmup, args.steps)
+    plans = r["plans"]
+    h2d = sum(p.n_fetch for p in plans) * P
+    d2h = sum(p.n_evict for p in plans) * P
+    moved = h2d + d2h
+    value = moved / r["wall_s"] / 1e9
+    mig_s = sum(r["migrate_ms"]) / 1e3
+    roof_s = sum(max(p.n_fetch * P / (link["h2d_bidir_GBs"] * 1e9), p.n_evict * P / (link["d2h_bidir_GBs"] * 1e9))
+                 for p in plans)
+    n_copy = sum(1 for p in plans if p.n_fetch)
+    achieved = moved / mig_s / 1e9 if mig_s > 0 else 0.0
+    peak = moved / roof_s / 1e9 if roof_s > 0 else 0.0
+    plan_dev = [sum(ph[k] for k in ("expand", "count", "cut", "emit")) for ph in r["phases"]]
+    ms.close()
+    del buf
+
+    result = {
+        "metric": "migrated GB/s vs host-link peak; plan latency (us) per context switch",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": r["wall_s"] / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "c2-stencil-sweep: 4 tasks x 3 arrays of 256 MiB, 2 MiB pages, pool 1024 frames "
+                               "(2 GiB), footprint 3 GiB (150 %), round-robin timeslice 25 launches",
+                   "page_bytes": P, "n_virtual_pages": trace.n_virtual_pages, "n_frames": trace.n_frames},
+        "bytes_migrated": {"h2d": h2d, "d2h": d2h},
+        "plan_latency_us": {"host_wall_mean": float(np.mean(r["plan_wall_s"])) * 1e6,
+                            "host_wall_p50": float(np.median(r["plan_wall_s"])) * 1e6,
+                            "host_wall_max": float(np.max(r["plan_wall_s"])) * 1e6,
+                            "device_mean": float(np.mean(plan_dev)) * 1e3},
+        "roofline": {"bound": "host-link", "achieved": achieved, "peak": peak, "unit": "GB/s",
+                     "frac": (achieved / peak) if peak else None, "traffic": None,
+                     "kernel": "k_migrate", "launches": n_copy,
+                     "avg_launch_ms": (mig_s / n_copy * 1e3) if n_copy else None,
+                     "note": "peak = the same per-step byte mix at the pinned hipMemcpyAsync rates measured "
+                             "in this run with both directions busy"},
+        "link_peak": link,
+    }
+    if not args.no_plan_stress:
+        result["roofline_plan"] = bench_planning_stress(torch)
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(trace_args, args.cpu_sample_steps)
+        result["miss_volume"] = miss_volume(dict(config=2))
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -177,7 +177,8 @@ int msched_set_profiling(msched_ctx *ctx, int on);
 int msched_get_phase_ms(msched_ctx *ctx, float *ms);
 
 const char *msched_strerror(int code);
-int msched_last_hip_error(msched_ctx *ctx);     /* hipError_t of the last MSCHED_E_HIP, as int */
+int msched_last_hip_error(msched_ctx *ctx);     /* hipError_t of the last MSCHED_E_HIP, as int; ctx may be NULL
+                                                    (then: the last one of any context, e.g. a failed create) */
 
 #ifdef __cplusplus
 }

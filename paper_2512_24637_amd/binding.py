@@ -69,6 +69,9 @@ def load_library():
     global _lib
     if _lib is not None:
         return _lib
+    # torch ships its own HIP runtime; it has to be the one this process loads first, or the
+    # pool / stream handles torch hands over would belong to a different runtime instance
+    import torch  # noqa: F401
     path = library_path()
     if not os.path.exists(path):
         raise ImportError(f"{path} is missing: build it with paper_2512_24637_amd.build.build() "
@@ -156,7 +159,7 @@ class MSched:
 
     def _check(self, rc):
         if rc != 0:
-            hip = self.lib.msched_last_hip_error(self.h) if self.h else 0
+            hip = self.lib.msched_last_hip_error(self.h)
             raise MSchedError(rc, self.lib.msched_strerror(rc).decode(), hip)
 
     def close(self):

@@ -11,10 +11,12 @@ using namespace msched;
 
 namespace {
 
+int g_last_hip = 0;   // last HIP error of any context (readable when no context exists, e.g. after a failed create)
+
 #define HIP_TRY(c, x)                                                \
     do {                                                             \
         hipError_t e_ = (x);                                         \
-        if (e_ != hipSuccess) { (c)->last_hip = (int)e_; return MSCHED_E_HIP; } \
+        if (e_ != hipSuccess) { (c)->last_hip = g_last_hip = (int)e_; return MSCHED_E_HIP; } \
     } while (0)
 
 // value = coeff * product(args[idx]), refusing arithmetic that leaves 64 bits (Sec. 5.2: extents
@@ -107,7 +109,7 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     c->migrate_chunk_shift = (uint32_t)env_u32("MSCHED_MIGRATE_CHUNK_SHIFT", 6, 24, 14);
     c->migrate_max_blocks = (uint32_t)env_u32("MSCHED_MIGRATE_BLOCKS", 1, 1 << 20, 4096);
     int rc = MSCHED_OK;
-    auto fail = [&](hipError_t e) { c->last_hip = (int)e; rc = MSCHED_E_HIP; };
+    auto fail = [&](hipError_t e) { c->last_hip = g_last_hip = (int)e; rc = MSCHED_E_HIP; };
     hipError_t e;
 #define ALLOC(ptr, bytes) if (rc == MSCHED_OK && (e = hipMalloc((void **)&(ptr), (bytes))) != hipSuccess) fail(e)
     ALLOC(c->page_table, c->V * 4);
@@ -296,7 +298,7 @@ int msched_migrate(msched_ctx *c, const msched_plan_t *plan) {
     if (c->pending_plan == 0 || plan->plan_id != c->pending_plan) return MSCHED_E_STALE_PLAN;
     if (c->profiling) HIP_TRY(c, hipEventRecord(c->ev[5], c->stream));
     HIP_TRY(c, launch_migrate(c, c->pending));
-    if (c->profiling) HIP_TRY(c, hipEventRecord(c->ev[6], c->stream));
+    if (c->profiling) { HIP_TRY(c, hipEventRecord(c->ev[6], c->stream)); c->migrate_timed = 1; }
     c->n_resident += c->pending.n_free_used;
     c->pending_plan = 0;
     return MSCHED_OK;
@@ -351,10 +353,9 @@ int msched_set_profiling(msched_ctx *c, int on) {
 
 int msched_get_phase_ms(msched_ctx *c, float *ms) {
     if (!c || !ms) return MSCHED_E_INVAL;
-    if (c->profiling) {
+    if (c->profiling && c->migrate_timed) {
         HIP_TRY(c, hipStreamSynchronize(c->stream));
-        float m = 0.f;
-        if (hipEventElapsedTime(&m, c->ev[5], c->ev[6]) == hipSuccess) c->phase_ms[MSCHED_PHASE_MIGRATE] = m;
+        HIP_TRY(c, hipEventElapsedTime(&c->phase_ms[MSCHED_PHASE_MIGRATE], c->ev[5], c->ev[6]));
     }
     for (int i = 0; i < MSCHED_N_PHASES; ++i) ms[i] = c->phase_ms[i];
     return MSCHED_OK;
@@ -374,6 +375,6 @@ const char *msched_strerror(int code) {
     }
 }
 
-int msched_last_hip_error(msched_ctx *c) { return c ? c->last_hip : 0; }
+int msched_last_hip_error(msched_ctx *c) { return c ? c->last_hip : g_last_hip; }
 
 }  // extern "C"

@@ -82,6 +82,7 @@ struct msched_ctx {
     msched::PlanHeader pending{};
     uint32_t *query_buf = nullptr; size_t query_cap = 0;     // device scratch for pagetable_query
     int profiling = 0;
+    int migrate_timed = 0;                      // ev[5], ev[6] have been recorded
     hipEvent_t ev[8] = {};
     float phase_ms[MSCHED_N_PHASES] = {};
     int last_hip = 0;

@@ -91,6 +91,7 @@ __global__ __launch_bounds__(256) void k_query(const uint32_t *__restrict__ page
 }
 
 hipError_t launch_init_tables(msched_ctx *c) {
+    (void)hipGetLastError();
     const uint32_t bv = (uint32_t)std::min<uint64_t>(4096, (c->V + 255) / 256);
     const uint32_t bf = (uint32_t)std::min<uint64_t>(4096, ((uint64_t)c->F + 255) / 256);
     k_fill_u32<<<bv, 256, 0, c->stream>>>(c->page_table, c->V, kNone);
@@ -100,12 +101,14 @@ hipError_t launch_init_tables(msched_ctx *c) {
 
 hipError_t launch_query(msched_ctx *c, const uint32_t *ids_dev, uint32_t n, uint32_t *out_dev) {
     if (n == 0) return hipSuccess;
+    (void)hipGetLastError();
     k_query<<<(n + 255) / 256, 256, 0, c->stream>>>(c->page_table, ids_dev, n, out_dev);
     return hipGetLastError();
 }
 
 hipError_t launch_migrate(msched_ctx *c, const PlanHeader &h) {
     if (h.n_fetch == 0) return hipSuccess;
+    (void)hipGetLastError();
     MigrateArgs a;
     a.pool = static_cast<uint8_t *>(c->cfg.hbm_pool);
     a.host = static_cast<uint8_t *>(c->host_dev);

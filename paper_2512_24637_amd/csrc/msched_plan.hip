@@ -367,6 +367,7 @@ __global__ __launch_bounds__(256) void k_frames(const PlanHeader *__restrict__ h
 #define CK(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) return e_; } while (0)
 
 hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
+    (void)hipGetLastError();   // launches below are checked through the sticky error: start clean
     hipStream_t st = c->stream;
     const bool prof = c->profiling != 0;
     if (prof) CK(hipEventRecord(c->ev[0], st));

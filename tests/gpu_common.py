@@ -3,66 +3,24 @@ lock-step comparison of the HIP path against the CPU oracle."""
 import numpy as np
 
 from workloads import run_schedule, page_words, stamp_of
-from workloads.content import page_words_torch
+from workloads.device import DeviceBuffers, POISON
 from workloads.harness import load_trace
 
 NONE = 0xFFFFFFFF
-POISON = 0x5A5A5A5A5A5A5A5A
 
 
-class GpuSide:
-    """Owns the torch buffers and the MSched context for one trace."""
+class GpuSide(DeviceBuffers):
+    """Device buffers of a trace plus the MSched context that manages them."""
 
-    def __init__(self, trace, fill="host"):
+    def __init__(self, trace):
         import torch
         from paper_2512_24637_amd import MSched
-        self.torch, self.trace = torch, trace
-        dev = torch.device("cuda:0")
-        self.wpp = trace.page_bytes // 8
-        self.pool = torch.full((trace.n_frames, self.wpp), POISON, dtype=torch.int64, device=dev)
-        self.host = torch.empty((trace.n_slots, self.wpp), dtype=torch.int64, pin_memory=True)
-        self.ids = None
-        ids_ptr = 0
-        if trace.ids_pool.size:
-            self.ids = torch.from_numpy(trace.ids_pool.view(np.int32)).to(dev)
-            ids_ptr = self.ids.data_ptr()
-        self.pages_with_slot = (np.arange(trace.n_virtual_pages) if trace.host_slot is None
-                                else np.nonzero(trace.host_slot != NONE)[0])
-        self.fill_host_store()
-        torch.cuda.synchronize()
+        super().__init__(trace)
         self.stream = torch.cuda.current_stream()
         self.ms = MSched(trace.page_shift, trace.n_virtual_pages, trace.n_frames, self.pool.data_ptr(),
                          self.host.data_ptr(), trace.n_slots, trace.host_slot,
-                         stream=self.stream.cuda_stream, ids_pool_ptr=ids_ptr)
+                         stream=self.stream.cuda_stream, ids_pool_ptr=self.ids_ptr)
         load_trace(self.ms, trace)
-
-    def fill_host_store(self, chunk_pages=1 << 14):
-        """host[slot(p)] = initial contents of page p, generated on the device in chunks."""
-        torch = self.torch
-        pages = self.pages_with_slot
-        slot = pages if self.trace.host_slot is None else self.trace.host_slot[pages].astype(np.int64)
-        step = max(1, min(chunk_pages, (256 << 20) // self.trace.page_bytes))
-        for i in range(0, pages.size, step):
-            pg = torch.from_numpy(pages[i:i + step].astype(np.int64)).cuda()
-            words = page_words_torch(pg, self.wpp).cpu()
-            self.host[torch.from_numpy(np.asarray(slot[i:i + step], np.int64))] = words
-
-    def stamp(self, frames, idx, val):
-        torch = self.torch
-        if len(frames) == 0:
-            return
-        f = torch.from_numpy(np.asarray(frames, np.int64)).cuda()
-        i = torch.from_numpy(np.asarray(idx, np.int64)).cuda()
-        v = torch.from_numpy(np.asarray(val, np.uint64).view(np.int64)).cuda()
-        self.pool[f, i] = v
-
-    def pool_words(self):
-        self.torch.cuda.synchronize()
-        return self.pool.cpu().numpy().view(np.uint64)
-
-    def host_words(self):
-        self.torch.cuda.synchronize()
-        return self.host.numpy().view(np.uint64)
 
     def close(self):
         self.torch.cuda.synchronize()
