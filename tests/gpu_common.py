@@ -25,6 +25,7 @@ class GpuSide(DeviceBuffers):
     def close(self):
         self.torch.cuda.synchronize()
         self.ms.close()
+        self.release()
 
 
 def make_oracle(oracle_mod, trace, with_bytes):
@@ -79,6 +80,61 @@ def lockstep(oracle_mod, trace, with_bytes=True, horizon="round", max_plans=None
         if with_bytes:
             assert np.array_equal(o.pool_words, g.pool_words())
             assert np.array_equal(o.host_words, g.host_words())
+    finally:
+        g.close()
+        o.close()
+    return n
+
+
+def lockstep_sampled(oracle_mod, trace, n_sample=4096, max_plans=None, check_every=4, seed=1, log=None):
+    """Full-size variant: plans, page table and frame owners are compared in full after every
+    switch against the metadata-only oracle; bytes are compared on a seeded sample of pages whose
+    expected contents (initial function of (page, word) plus every word the running task wrote)
+    are tracked one by one on the CPU."""
+    import torch
+    g = GpuSide(trace)
+    o = make_oracle(oracle_mod, trace, with_bytes=False)
+    wpp = trace.page_bytes // 8
+    rng = np.random.default_rng(seed)
+    cand = g.pages_with_slot
+    sample = np.sort(rng.choice(cand, size=min(n_sample, cand.size), replace=False))
+    truth = page_words(sample, wpp)                       # [n_sample, wpp]
+    slot_s = torch.from_numpy(np.asarray(o.slot_of(sample), np.int64))
+    n = 0
+
+    def check_bytes(where):
+        pt = o.pagetable_query(sample)
+        res = pt != NONE
+        if res.any():
+            rows = g.pool[torch.from_numpy(pt[res].astype(np.int64)).cuda()].cpu().numpy().view(np.uint64)
+            assert np.array_equal(rows, truth[res]), (where, "sampled frames")
+        if (~res).any():
+            torch.cuda.synchronize()
+            rows = g.host[slot_s[torch.from_numpy(~res)]].numpy().view(np.uint64)
+            assert np.array_equal(rows, truth[~res]), (where, "sampled host slots")
+
+    try:
+        for ro, rg in zip(run_schedule(trace, o, max_plans=max_plans),
+                          run_schedule(trace, g.ms, max_plans=max_plans)):
+            where = (trace.name, "plan", ro.index, "task", ro.task)
+            assert_same_plan(ro.plan, rg.plan, where)
+            idx, val = stamp_of(rg.plan.fetch_pages, ro.index, wpp)
+            g.stamp(rg.plan.fetch_frames, idx, val)
+            pos = np.searchsorted(sample, ro.plan.fetch_pages)
+            pos[pos == sample.size] = 0
+            hit = sample[pos] == ro.plan.fetch_pages
+            truth[pos[hit], idx[hit]] = val[hit]
+            pto, foo = o.state()
+            ptg, fog = g.ms.state()
+            assert np.array_equal(pto, ptg), (where, "page table")
+            assert np.array_equal(foo, fog), (where, "frame owner")
+            if n % check_every == 0:
+                check_bytes(where)
+            n += 1
+            if log:
+                log(f"{trace.name} plan {ro.index}: fetch {ro.plan.n_fetch} evict {ro.plan.n_evict} "
+                    f"covered {ro.plan.covered_launches}/{ro.plan.g_end0} ok")
+        check_bytes((trace.name, "end"))
     finally:
         g.close()
         o.close()

@@ -61,3 +61,13 @@ class DeviceBuffers:
     def host_words(self):
         self.torch.cuda.synchronize()
         return self.host.numpy().view(np.uint64)
+
+    def release(self):
+        """Drop the buffers and hand cached device and pinned memory back to the system."""
+        torch = self.torch
+        torch.cuda.synchronize()
+        self.pool = self.host = self.ids = None
+        torch.cuda.empty_cache()
+        empty_host = getattr(torch._C, "_host_emptyCache", None)
+        if empty_host is not None:
+            empty_host()

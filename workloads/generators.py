@@ -207,11 +207,14 @@ def _c4(seed, page_shift, scale, n_launches, layers=32, steps=256):
                  notes=f"2 decoders, {layers} layers, KV grows one token per step")
 
 
-def _zipf_ranks(rng, n_items, alpha, size):
+def _zipf_cdf(n_items, alpha):
     w = np.arange(1, n_items + 1, dtype=np.float64) ** (-alpha)
     cdf = np.cumsum(w)
-    cdf /= cdf[-1]
-    return np.minimum(np.searchsorted(cdf, rng.random(size)), n_items - 1)
+    return cdf / cdf[-1]
+
+
+def _zipf_ranks(rng, cdf, size):
+    return np.minimum(np.searchsorted(cdf, rng.random(size)), cdf.size - 1)
 
 
 def _c5(seed, page_shift, scale, n_launches):
@@ -226,6 +229,7 @@ def _c5(seed, page_shift, scale, n_launches):
     per_task = (625 if n_launches is None else n_launches)
     rng = np.random.default_rng([seed, 5])
     perm = rng.permutation(table).astype(np.uint32)
+    cdf = _zipf_cdf(table, 1.1)
     table_base = n_tasks * private
     kernels = [[Rule(RULE_LINEAR, 0, (2,), 4), Rule(RULE_LINEAR, 1, (3,), 4),
                 Rule(RULE_LIST)]]
@@ -241,7 +245,7 @@ def _c5(seed, page_shift, scale, n_launches):
                 base, size = _ragged_extent(rng, start, length, P, 4)
                 args.append(base)
                 counts.append(size // 4)
-            ranks = _zipf_ranks(rng, table, 1.1, n_ids)
+            ranks = _zipf_ranks(rng, cdf, n_ids)
             pools.append(perm[ranks] + np.uint32(table_base))
             builders[t].add(0, args + counts, latency=1, ids_off=off, n_ids=n_ids)
             off += n_ids
