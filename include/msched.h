@@ -29,7 +29,7 @@ extern "C" {
 #define MSCHED_MAX_ARGS 12                    /* 64-bit launch arguments per command */
 #define MSCHED_MAX_RULES 8                    /* access rules per kernel template */
 #define MSCHED_MAX_PRODUCT_ARGS 4             /* arguments multiplied in one formula */
-#define MSCHED_MAX_TIMELINE_COMMANDS 4095     /* commands one plan may look ahead over */
+#define MSCHED_MAX_TIMELINE_COMMANDS 3071     /* commands one plan may look ahead over */
 #define MSCHED_MAX_TIMELINE_ENTRIES 1024
 
 enum {

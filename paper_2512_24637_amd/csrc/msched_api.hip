@@ -70,7 +70,7 @@ void free_ctx(msched_ctx *c) {
     for (auto &t : c->tasks) if (t.recs) (void)hipHostFree(t.recs);
     void *dev[] = {c->page_table, c->frame_owner, c->nu, c->slot, c->evict_pages, c->evict_frames, c->fetch_pages,
                    c->fetch_frames, c->flags, c->matrix, c->partial, c->offsets, c->hdr_dev, c->kernels_dev,
-                   c->query_buf};
+                   c->query_buf, c->cmd_dev};
     for (void *p : dev) if (p) (void)hipFree(p);
     if (c->hdr_host) (void)hipHostFree(c->hdr_host);
     if (c->cmd_ptrs_host) (void)hipHostFree((void *)c->cmd_ptrs_host);
@@ -108,6 +108,7 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     c->V = cfg->n_virtual_pages; c->F = cfg->n_frames; c->page_shift = cfg->page_shift;
     c->migrate_chunk_shift = (uint32_t)env_u32("MSCHED_MIGRATE_CHUNK_SHIFT", 6, 24, 14);
     c->migrate_max_blocks = (uint32_t)env_u32("MSCHED_MIGRATE_BLOCKS", 1, 1 << 20, 4096);
+    c->epoch = (uint32_t)env_u32("MSCHED_INITIAL_EPOCH", 0, kMaxEpoch, 0);   // test hook: start near the wrap
     int rc = MSCHED_OK;
     auto fail = [&](hipError_t e) { c->last_hip = g_last_hip = (int)e; rc = MSCHED_E_HIP; };
     hipError_t e;
@@ -122,6 +123,7 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     ALLOC(c->flags, 256);
     ALLOC(c->offsets, (size_t)2 * (MSCHED_MAX_TIMELINE_COMMANDS + 1) * 4);
     ALLOC(c->hdr_dev, sizeof(PlanHeader));
+    ALLOC(c->cmd_dev, sizeof(CmdRec) * (MSCHED_MAX_TIMELINE_COMMANDS + 1));
     if (cfg->host_slot) {
         ALLOC(c->slot, c->V * 4);
         if (rc == MSCHED_OK && (e = hipMemcpy(c->slot, cfg->host_slot, c->V * 4, hipMemcpyHostToDevice)) != hipSuccess) fail(e);
@@ -135,6 +137,7 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     for (int i = 0; i < 8 && rc == MSCHED_OK; ++i)
         if ((e = hipEventCreate(&c->ev[i])) != hipSuccess) fail(e);
     if (rc == MSCHED_OK && (e = launch_init_tables(c)) != hipSuccess) fail(e);
+    if (rc == MSCHED_OK && (e = launch_nu_reset(c)) != hipSuccess) fail(e);
     if (rc == MSCHED_OK && (e = hipStreamSynchronize(c->stream)) != hipSuccess) fail(e);
     if (rc != MSCHED_OK) { free_ctx(c); return rc; }
     *out = c;
@@ -257,10 +260,13 @@ int msched_plan(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entri
     h.n_resident = c->n_resident; h.first_free = c->n_resident;
     if (G > 0) {
         PlanGeom g;
-        g.G = G; g.g_end0 = g_end0; g.n_keys = 2 * (G + 1);
-        const uint64_t per = (c->V + kMaxChunks - 1) / kMaxChunks;
-        g.chunk_pages = (uint32_t)std::max<uint64_t>(kMinChunkPages, (per + 255) / 256 * 256);
-        g.n_chunks = (uint32_t)((c->V + g.chunk_pages - 1) / g.chunk_pages);
+        plan_geometry(c, G, g);
+        g.g_end0 = g_end0;
+        if (c->epoch == kMaxEpoch) {                 // the epoch field is about to wrap: start over
+            HIP_TRY(c, launch_nu_reset(c));
+            c->epoch = 0;
+        }
+        ++c->epoch;
         const size_t need = (size_t)g.n_chunks * g.n_keys;
         if (need > c->matrix_cap) {
             HIP_TRY(c, hipStreamSynchronize(c->stream));

@@ -12,8 +12,13 @@ namespace msched {
 constexpr uint32_t kNone = 0xFFFFFFFFu;         // not resident / free frame / no next use
 constexpr uint32_t kSkip = 0x80000000u;         // output offset of a class that is not emitted
 constexpr int kWave = 64;                       // CDNA wavefront
-constexpr uint32_t kMaxChunks = 2048;           // page-table chunks (one wavefront each)
-constexpr uint32_t kMinChunkPages = 1024;
+constexpr uint32_t kMaxChunks = 2048;           // page-table chunks (one workgroup each)
+constexpr int kMaxWaves = 8;                    // wavefronts per sweep workgroup
+constexpr int kMaxSteps = 16;                   // 64-page steps a wavefront keeps in registers per tile
+constexpr uint32_t kNuShift = 12;               // nu entry = (epoch << kNuShift) | (kNuMask - g)
+constexpr uint32_t kNuMask = (1u << kNuShift) - 1;
+constexpr uint32_t kMaxEpoch = (1u << (32 - kNuShift)) - 1;
+static_assert(MSCHED_MAX_TIMELINE_COMMANDS < kNuMask, "g must fit the next-use encoding");
 constexpr uint32_t kRowGroups = 32;             // row groups of the chunk x class count matrix
 
 // status bits raised by device code while planning
@@ -51,6 +56,7 @@ struct TaskQueue {
 
 struct PlanGeom {
     uint32_t G, g_end0, n_chunks, chunk_pages, n_keys;   // n_keys = 2 * (G + 1)
+    uint32_t waves, steps, rounds;                       // sweep workgroup shape
 };
 
 }  // namespace msched
@@ -73,6 +79,8 @@ struct msched_ctx {
     msched::PlanHeader *hdr_host = nullptr;     // pinned
     const msched::CmdRec **cmd_ptrs_host = nullptr;          // pinned: record of the g-th future command
     const msched::CmdRec *const *cmd_ptrs_dev = nullptr;     // same memory, device address
+    msched::CmdRec *cmd_dev = nullptr;                       // device: this plan's records, in g order
+    uint32_t epoch = 0;                                      // next-use epoch of the latest plan
     msched::DevKernel *kernels_dev = nullptr; size_t kernels_cap = 0;
     std::vector<msched::DevKernel> kernels;
     std::vector<msched::TaskQueue> tasks;
@@ -92,6 +100,8 @@ namespace msched {
 
 // plan kernels (msched_plan.hip)
 hipError_t launch_plan(msched_ctx *c, const PlanGeom &g);
+hipError_t launch_nu_reset(msched_ctx *c);
+void plan_geometry(const msched_ctx *c, uint32_t G, PlanGeom &g);
 // migrate + query kernels (msched_migrate.hip)
 hipError_t launch_migrate(msched_ctx *c, const PlanHeader &h);
 hipError_t launch_query(msched_ctx *c, const uint32_t *ids_dev, uint32_t n, uint32_t *out_dev);

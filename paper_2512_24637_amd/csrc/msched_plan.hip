@@ -3,14 +3,18 @@
 // of the fetch and eviction lists.
 //
 // Method (paper: arXiv 2512.24637, Sec. 5.2 and Sec. 6.1-6.2): every page gets nu[p] = position
-// of the first future command that touches it (kNone if the timeline never does).  The fetch
+// of the first future command that touches it ("never" if the timeline does not).  The fetch
 // list is the non-resident pages with nu < g_cut ordered by (nu, page id); the eviction list is
-// the resident pages with nu >= g_cut ordered by (nu descending with kNone first, page id),
+// the resident pages with nu >= g_cut ordered by (nu descending with "never" first, page id),
 // truncated to what the fetches need.  Both orders are "class (a small integer) then page id",
 // so the lists come out of one stable counting sort whose classes are the G+1 possible values of
-// nu: a wavefront owns a contiguous chunk of the page table, counts its pages per class, a small
-// kernel turns the chunk x class counts into absolute output offsets, and a second sweep writes
-// each page straight to its final position.  No comparison sort, no per-command bitmaps.
+// nu: a workgroup owns a contiguous chunk of the page table, counts its pages per class, a small
+// kernel turns the chunk x class counts into output offsets, and a second sweep writes each page
+// straight to its final position.  No comparison sort, no per-command bitmaps.
+//
+// nu[] is never reset: an entry holds (epoch << 12) | (4095 - g), the epoch grows by one per plan
+// and the scatter is an atomic max, so entries of earlier plans read as "never" and the smallest
+// g of the current plan wins.
 #include <algorithm>
 
 #include "msched_internal.h"
@@ -21,35 +25,34 @@ __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 __device__ __forceinline__ uint64_t lanes_below() { return (1ull << lane_id()) - 1ull; }
 
 // ------------------------------------------------------------------------------------------
-// nu[] reset
+// Stage the G command records of this plan from pinned host memory into device memory (one
+// pass over the link instead of one round trip per expansion workgroup) and clear the status word.
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_fill(uint32_t *__restrict__ dst, uint64_t n, uint32_t v,
-                                               uint32_t *__restrict__ flags) {
-    const uint64_t tid = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
-    const uint64_t nthreads = gridDim.x * (uint64_t)blockDim.x;
-    if (tid == 0) *flags = 0;
-    const uint64_t n4 = n >> 2;
-    uint4 *d4 = reinterpret_cast<uint4 *>(dst);
-    const uint4 vv = make_uint4(v, v, v, v);
-    for (uint64_t i = tid; i < n4; i += nthreads) d4[i] = vv;
-    for (uint64_t i = (n4 << 2) + tid; i < n; i += nthreads) dst[i] = v;
+__global__ __launch_bounds__(256) void k_stage(const CmdRec *const *__restrict__ cmd_ptrs, uint32_t G,
+                                                CmdRec *__restrict__ cmd_dev, uint32_t *__restrict__ flags) {
+    const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t == 0) *flags = 0;
+    const uint32_t g = t >> 3, part = t & 7;
+    if (g >= G) return;
+    const uint4 *src = reinterpret_cast<const uint4 *>(cmd_ptrs[g]);
+    reinterpret_cast<uint4 *>(cmd_dev + g)[part] = src[part];
 }
 
 // ------------------------------------------------------------------------------------------
 // Template expansion + next-use scatter (Sec. 5.2 templates; Sec. 6.2 access order).
-// One workgroup per (command g, rule r, split s).  A page's next use only ever decreases while
-// this kernel runs, so a plain load that still shows a value <= g lets the atomic be skipped.
+// One workgroup per (command g, rule r, split s).  An entry only ever grows while this kernel
+// runs, so a plain load that already shows a value >= ours lets the atomic be skipped.
 // ------------------------------------------------------------------------------------------
 struct ExpandArgs {
-    const CmdRec *const *cmd_ptrs; uint32_t G;
+    const CmdRec *cmds; uint32_t G;
     const DevKernel *kernels;
     uint32_t *nu; const uint32_t *slot; uint32_t *flags;
-    uint64_t V; uint32_t page_shift, n_split;
+    uint64_t V; uint32_t page_shift, n_split, epoch_base;   // epoch_base = epoch << kNuShift
 };
 
-__device__ __forceinline__ void touch(const ExpandArgs &a, uint32_t p, uint32_t g) {
+__device__ __forceinline__ void touch(const ExpandArgs &a, uint32_t p, uint32_t enc) {
     if (a.slot != nullptr && a.slot[p] == kNone) { atomicOr(a.flags, kStatRange); return; }
-    if (a.nu[p] > g) atomicMin(&a.nu[p], g);
+    if (a.nu[p] < enc) atomicMax(&a.nu[p], enc);
 }
 
 __device__ __forceinline__ uint64_t formula(const uint64_t *args, uint64_t coeff, const uint8_t *idx, int n) {
@@ -61,15 +64,15 @@ __device__ __forceinline__ uint64_t formula(const uint64_t *args, uint64_t coeff
 __global__ __launch_bounds__(256) void k_expand(ExpandArgs a) {
     const uint32_t g = blockIdx.x, r = blockIdx.y;
     __shared__ uint64_t s_rec[sizeof(CmdRec) / 8];
-    // The record sits in pinned host memory: fetch it once per workgroup (two dependent reads).
     if (threadIdx.x < sizeof(CmdRec) / 8)
-        s_rec[threadIdx.x] = reinterpret_cast<const uint64_t *>(a.cmd_ptrs[g])[threadIdx.x];
+        s_rec[threadIdx.x] = reinterpret_cast<const uint64_t *>(a.cmds + g)[threadIdx.x];
     __syncthreads();
     const CmdRec *rec = reinterpret_cast<const CmdRec *>(s_rec);
     const DevKernel &k = a.kernels[rec->kernel];
     if (r >= k.n_rules) return;
     const msched_rule q = k.rules[r];
     const uint32_t sh = a.page_shift;
+    const uint32_t enc = a.epoch_base | (kNuMask - g);
     const uint64_t t0 = blockIdx.z * (uint64_t)blockDim.x + threadIdx.x;
     const uint64_t step = a.n_split * (uint64_t)blockDim.x;
 
@@ -79,7 +82,7 @@ __global__ __launch_bounds__(256) void k_expand(ExpandArgs a) {
         for (uint64_t i = t0; i < n; i += step) {
             const uint32_t p = ids[i];
             if (p >= a.V) { atomicOr(a.flags, kStatRange); continue; }
-            touch(a, p, g);
+            touch(a, p, enc);
         }
         return;
     }
@@ -99,70 +102,106 @@ __global__ __launch_bounds__(256) void k_expand(ExpandArgs a) {
                 for (uint64_t j = t0; j < count; j += step) {
                     const uint64_t c0 = base + j * stride;
                     const uint64_t p0 = c0 >> sh, p1 = (c0 + size - 1) >> sh;
-                    for (uint64_t p = p0; p <= p1; ++p) touch(a, (uint32_t)p, g);
+                    for (uint64_t p = p0; p <= p1; ++p) touch(a, (uint32_t)p, enc);
                 }
             } else {                                        // few large chunks: threads across pages
                 for (uint64_t j = 0; j < count; ++j) {
                     const uint64_t c0 = base + j * stride;
                     const uint64_t p0 = c0 >> sh, n = ((c0 + size - 1) >> sh) - p0 + 1;
-                    for (uint64_t i = t0; i < n; i += step) touch(a, (uint32_t)(p0 + i), g);
+                    for (uint64_t i = t0; i < n; i += step) touch(a, (uint32_t)(p0 + i), enc);
                 }
             }
             return;
         }
     }
     const uint64_t p0 = base >> sh, n = ((base + size - 1) >> sh) - p0 + 1;
-    for (uint64_t i = t0; i < n; i += step) touch(a, (uint32_t)(p0 + i), g);
+    for (uint64_t i = t0; i < n; i += step) touch(a, (uint32_t)(p0 + i), enc);
 }
 
 // ------------------------------------------------------------------------------------------
 // Class of a page: key in [0, K) = not resident with nu = key; key in [K, 2K) = resident with
 // nu = key - K; K = G + 1 and class G stands for "never used in the timeline".  Pages that are
-// neither resident nor used take part in nothing.
+// neither resident nor used take part in nothing (key kNone).
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ bool classify(uint32_t frame, uint32_t nu, uint32_t G, uint32_t &key) {
+__device__ __forceinline__ uint32_t classify(uint32_t frame, uint32_t enc, uint32_t epoch, uint32_t G) {
     const bool resident = frame != kNone;
-    const uint32_t c = (nu == kNone) ? G : nu;
-    key = resident ? (G + 1 + c) : c;
-    return resident || c != G;
+    const uint32_t c = ((enc >> kNuShift) == epoch) ? (kNuMask - (enc & kNuMask)) : G;
+    if (!resident && c == G) return kNone;
+    return resident ? (G + 1 + c) : c;
 }
 
-// Count pages per class in this wavefront's chunk; one matrix row per chunk.
-__global__ __launch_bounds__(kWave) void k_count(const uint32_t *__restrict__ page_table,
-                                                 const uint32_t *__restrict__ nu, uint64_t V,
-                                                 uint32_t chunk_pages, uint32_t G,
-                                                 uint32_t *__restrict__ matrix) {
-    extern __shared__ uint32_t hist[];
-    const uint32_t n_keys = 2 * (G + 1);
+struct SweepGeom {
+    uint64_t V;
+    uint32_t chunk_pages;     // pages per workgroup
+    uint32_t steps;           // 64-page steps per wavefront per tile (<= kMaxSteps)
+    uint32_t rounds;          // tiles per chunk; a tile is waves * steps * 64 consecutive pages
+    uint32_t G, epoch;
+};
+
+// One tile: every wavefront loads its `steps` x 64 consecutive pages, classifies them and ranks
+// each page among the earlier pages of the same key inside this wavefront's slice (page order),
+// counting into its own LDS histogram.  Lanes with equal keys are grouped by ballot, so a step
+// costs one pass per distinct key present, not one per page.
+__device__ __forceinline__ void rank_tile(const uint32_t *__restrict__ page_table, const uint32_t *__restrict__ nu,
+                                          const SweepGeom &sg, uint64_t wave_begin, uint64_t p_end,
+                                          uint32_t *hist, uint32_t (&key)[kMaxSteps], uint32_t (&fr)[kMaxSteps],
+                                          uint32_t (&rk)[kMaxSteps]) {
     const int lane = lane_id();
-    for (uint32_t k = lane; k < n_keys; k += kWave) hist[k] = 0;
-    const uint64_t p_begin = (uint64_t)blockIdx.x * chunk_pages;
-    const uint64_t p_end = min(V, p_begin + chunk_pages);
-    for (uint64_t p0 = p_begin; p0 < p_end; p0 += 4 * kWave) {
-        uint32_t fr[4], nx[4];
+    const uint64_t below = lanes_below();
+    uint32_t enc[kMaxSteps];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const uint64_t p = p0 + u * kWave + lane;
-            const bool in = p < p_end;
-            fr[u] = in ? page_table[p] : kNone;
-            nx[u] = in ? nu[p] : kNone;
-        }
+    for (int s = 0; s < kMaxSteps; ++s) {
+        const uint64_t p = wave_begin + (uint64_t)s * kWave + lane;
+        const bool in = (uint32_t)s < sg.steps && p < p_end;
+        fr[s] = in ? page_table[p] : kNone;
+        enc[s] = in ? nu[p] : 0u;
+    }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            uint32_t key;
-            const bool valid = classify(fr[u], nx[u], G, key);
+    for (int s = 0; s < kMaxSteps; ++s) {
+        key[s] = classify(fr[s], enc[s], sg.epoch, sg.G);
+        rk[s] = 0;
+        if ((uint32_t)s < sg.steps) {
+            const bool valid = key[s] != kNone;
             uint64_t todo = __ballot(valid);
             while (todo) {
                 const int leader = __ffsll((long long)todo) - 1;
-                const uint32_t k = __builtin_amdgcn_readlane(key, leader);
-                const uint64_t same = __ballot(valid && key == k);
-                if (lane == leader) hist[k] += __popcll(same);
+                const uint32_t k = __builtin_amdgcn_readlane(key[s], leader);
+                const uint64_t same = __ballot(valid && key[s] == k);
+                uint32_t before = 0;
+                if (lane == leader) { before = hist[k]; hist[k] = before + __popcll(same); }
+                before = __builtin_amdgcn_readlane(before, leader);
+                if (valid && key[s] == k) rk[s] = before + __popcll(same & below);
                 todo &= ~same;
             }
         }
     }
+}
+
+// First sweep: pages per key in each chunk; one matrix row per chunk.
+__global__ __launch_bounds__(kWave * kMaxWaves) void k_count(const uint32_t *__restrict__ page_table,
+                                                              const uint32_t *__restrict__ nu, SweepGeom sg,
+                                                              uint32_t *__restrict__ matrix) {
+    extern __shared__ uint32_t lds[];
+    const uint32_t n_keys = 2 * (sg.G + 1);
+    const uint32_t waves = blockDim.x / kWave, wave = threadIdx.x / kWave;
+    uint32_t *hist = lds + wave * n_keys;
+    for (uint32_t i = threadIdx.x; i < waves * n_keys; i += blockDim.x) lds[i] = 0;
+    __syncthreads();
+    const uint64_t p_begin = (uint64_t)blockIdx.x * sg.chunk_pages;
+    const uint64_t p_end = min(sg.V, p_begin + sg.chunk_pages);
+    const uint64_t tile_pages = (uint64_t)waves * sg.steps * kWave;
+    for (uint32_t round = 0; round < sg.rounds; ++round) {
+        uint32_t key[kMaxSteps], fr[kMaxSteps], rk[kMaxSteps];
+        rank_tile(page_table, nu, sg, p_begin + round * tile_pages + (uint64_t)wave * sg.steps * kWave, p_end,
+                  hist, key, fr, rk);
+    }
+    __syncthreads();
     uint32_t *row = matrix + (size_t)blockIdx.x * n_keys;
-    for (uint32_t k = lane; k < n_keys; k += kWave) row[k] = hist[k];
+    for (uint32_t k = threadIdx.x; k < n_keys; k += blockDim.x) {
+        uint32_t s = 0;
+        for (uint32_t w = 0; w < waves; ++w) s += lds[w * n_keys + k];
+        row[k] = s;
+    }
 }
 
 // Column sums of the count matrix, by row group.
@@ -212,8 +251,10 @@ __device__ uint32_t block_exclusive_scan(uint32_t *a, uint32_t n, uint32_t *wave
 //   D(k) = pages with nu < k; g_cut = largest k <= g_end0 with D(k) <= F            (cut)
 //   fetch offsets: classes 0..g_cut-1 of non-resident pages, ascending
 //   victim offsets: resident classes G (never used), G-1, ..., g_cut, in that order
-__global__ __launch_bounds__(1024) void k_cut(uint32_t *__restrict__ partial, uint32_t G, uint32_t g_end0,
-                                               uint32_t F, const uint32_t *__restrict__ flags,
+// `groups` holds n_groups rows of per-key counts (row-group sums, or the matrix itself when it has
+// few rows); they are replaced by their exclusive prefix over the rows.
+__global__ __launch_bounds__(1024) void k_cut(uint32_t *__restrict__ groups, uint32_t n_groups, uint32_t G,
+                                               uint32_t g_end0, uint32_t F, const uint32_t *__restrict__ flags,
                                                uint32_t *__restrict__ offsets, PlanHeader *__restrict__ hdr_dev,
                                                PlanHeader *__restrict__ hdr_host) {
     extern __shared__ uint32_t lds[];
@@ -225,11 +266,14 @@ __global__ __launch_bounds__(1024) void k_cut(uint32_t *__restrict__ partial, ui
     const uint32_t tid = threadIdx.x;
     if (tid == 0) { s_cut = 0; s_res = 0; }
     for (uint32_t key = tid; key < n_keys; key += 1024) {
+        uint32_t v[kRowGroups];
+#pragma unroll
+        for (uint32_t rg = 0; rg < kRowGroups; ++rg) v[rg] = (rg < n_groups) ? groups[rg * n_keys + key] : 0;
         uint32_t run = 0;
+#pragma unroll
         for (uint32_t rg = 0; rg < kRowGroups; ++rg) {
-            const uint32_t v = partial[rg * n_keys + key];
-            partial[rg * n_keys + key] = run;               // exclusive prefix over row groups
-            run += v;
+            if (rg < n_groups) groups[rg * n_keys + key] = run;
+            run += v[rg];
         }
         tot[key] = run;
     }
@@ -237,12 +281,9 @@ __global__ __launch_bounds__(1024) void k_cut(uint32_t *__restrict__ partial, ui
     // cut
     for (uint32_t c = tid; c < K; c += 1024) sc[c] = (c < g_end0) ? tot[c] + tot[K + c] : 0;
     __syncthreads();
-    const uint32_t d_all = block_exclusive_scan(sc, K, wave_sums);   // sc[k] = D(k) for k < K
+    block_exclusive_scan(sc, K, wave_sums);                          // sc[k] = D(k) for k < K
     uint32_t fit = 0, res = 0;
-    for (uint32_t k = 1 + tid; k <= g_end0; k += 1024) {
-        const uint32_t d = (k < K) ? sc[k] : d_all;
-        fit += (d <= F) ? 1u : 0u;
-    }
+    for (uint32_t k = 1 + tid; k <= g_end0; k += 1024) fit += (sc[k] <= F) ? 1u : 0u;   // g_end0 <= G < K
     for (uint32_t c = tid; c < K; c += 1024) res += tot[K + c];
     if (fit) atomicAdd(&s_cut, fit);
     if (res) atomicAdd(&s_res, res);
@@ -274,11 +315,9 @@ __global__ __launch_bounds__(1024) void k_cut(uint32_t *__restrict__ partial, ui
     }
 }
 
-// Turn counts into absolute output positions: matrix[w][key] = offset[key] + pages of that class in
-// chunks before w.
+// matrix[w][key] = pages of that key in chunks before w (exclusive prefix down each column).
 __global__ __launch_bounds__(256) void k_offsets(uint32_t *__restrict__ matrix, uint32_t n_chunks, uint32_t n_keys,
                                                  const uint32_t *__restrict__ partial,
-                                                 const uint32_t *__restrict__ offsets,
                                                  const PlanHeader *__restrict__ hdr) {
     if (hdr->n_fetch == 0) return;
     const uint32_t key = blockIdx.x * 64 + threadIdx.x;
@@ -286,7 +325,7 @@ __global__ __launch_bounds__(256) void k_offsets(uint32_t *__restrict__ matrix, 
     if (key >= n_keys) return;
     const uint32_t rows = (n_chunks + kRowGroups - 1) / kRowGroups;
     const uint32_t w0 = rg * rows, w1 = min(n_chunks, w0 + rows);
-    uint32_t run = offsets[key] + partial[rg * n_keys + key];
+    uint32_t run = partial[rg * n_keys + key];
 #pragma unroll 8
     for (uint32_t w = w0; w < w1; ++w) {
         const size_t i = (size_t)w * n_keys + key;
@@ -296,60 +335,65 @@ __global__ __launch_bounds__(256) void k_offsets(uint32_t *__restrict__ matrix, 
     }
 }
 
-// Second sweep: every listed page goes to its final position.
-__global__ __launch_bounds__(kWave) void k_emit(const uint32_t *__restrict__ page_table,
-                                                const uint32_t *__restrict__ nu, uint64_t V,
-                                                uint32_t chunk_pages, uint32_t G,
-                                                const uint32_t *__restrict__ matrix,
-                                                const PlanHeader *__restrict__ hdr,
-                                                uint32_t *__restrict__ fetch_pages,
-                                                uint32_t *__restrict__ evict_pages,
-                                                uint32_t *__restrict__ evict_frames) {
-    extern __shared__ uint32_t pos[];
+// Second sweep: every listed page goes to its final position =
+//   class offset + pages of the key in earlier chunks + in earlier tiles and wavefronts of this
+//   chunk + rank inside the wavefront's slice.
+__global__ __launch_bounds__(kWave * kMaxWaves) void k_emit(const uint32_t *__restrict__ page_table,
+                                                             const uint32_t *__restrict__ nu, SweepGeom sg,
+                                                             const uint32_t *__restrict__ matrix,
+                                                             const uint32_t *__restrict__ offsets,
+                                                             const PlanHeader *__restrict__ hdr,
+                                                             uint32_t *__restrict__ fetch_pages,
+                                                             uint32_t *__restrict__ evict_pages,
+                                                             uint32_t *__restrict__ evict_frames) {
+    extern __shared__ uint32_t lds[];
     const uint32_t n_fetch = hdr->n_fetch, n_evict = hdr->n_evict;
     if (n_fetch == 0) return;
-    const uint32_t K = G + 1, n_keys = 2 * K;
+    const uint32_t K = sg.G + 1, n_keys = 2 * K;
+    const uint32_t waves = blockDim.x / kWave, wave = threadIdx.x / kWave;
     const int lane = lane_id();
+    uint32_t *base = lds + waves * n_keys;               // [n_keys] running output position per key
+    uint32_t *hist = lds + wave * n_keys;
     const uint32_t *row = matrix + (size_t)blockIdx.x * n_keys;
-    for (uint32_t k = lane; k < n_keys; k += kWave) pos[k] = row[k];
-    const uint64_t below = lanes_below();
-    const uint64_t p_begin = (uint64_t)blockIdx.x * chunk_pages;
-    const uint64_t p_end = min(V, p_begin + chunk_pages);
-    for (uint64_t p0 = p_begin; p0 < p_end; p0 += 4 * kWave) {
-        uint32_t fr[4], nx[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const uint64_t p = p0 + u * kWave + lane;
-            const bool in = p < p_end;
-            fr[u] = in ? page_table[p] : kNone;
-            nx[u] = in ? nu[p] : kNone;
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            uint32_t key;
-            const bool valid = classify(fr[u], nx[u], G, key);
-            uint32_t where = kSkip;
-            uint64_t todo = __ballot(valid);
-            while (todo) {
-                const int leader = __ffsll((long long)todo) - 1;
-                const uint32_t k = __builtin_amdgcn_readlane(key, leader);
-                const uint64_t same = __ballot(valid && key == k);
-                uint32_t base = 0;
-                if (lane == leader) { base = pos[k]; pos[k] = base + __popcll(same); }
-                base = __builtin_amdgcn_readlane(base, leader);
-                if (valid && key == k) where = base + __popcll(same & below);
-                todo &= ~same;
+    for (uint32_t k = threadIdx.x; k < n_keys; k += blockDim.x) {
+        const uint32_t off = offsets[k];
+        base[k] = (off == kSkip) ? kSkip : off + row[k];
+    }
+    const uint64_t p_begin = (uint64_t)blockIdx.x * sg.chunk_pages;
+    const uint64_t p_end = min(sg.V, p_begin + sg.chunk_pages);
+    const uint64_t tile_pages = (uint64_t)waves * sg.steps * kWave;
+    for (uint32_t round = 0; round < sg.rounds; ++round) {
+        for (uint32_t i = threadIdx.x; i < waves * n_keys; i += blockDim.x) lds[i] = 0;
+        __syncthreads();
+        const uint64_t wave_begin = p_begin + round * tile_pages + (uint64_t)wave * sg.steps * kWave;
+        uint32_t key[kMaxSteps], fr[kMaxSteps], rk[kMaxSteps];
+        rank_tile(page_table, nu, sg, wave_begin, p_end, hist, key, fr, rk);
+        __syncthreads();
+        // per key: each wavefront's start position in this tile; carry the running position on
+        for (uint32_t k = threadIdx.x; k < n_keys; k += blockDim.x) {
+            uint32_t run = base[k];
+            for (uint32_t w = 0; w < waves; ++w) {
+                const uint32_t t = lds[w * n_keys + k];
+                lds[w * n_keys + k] = run;
+                run += t;
             }
-            const uint32_t p = (uint32_t)(p0 + u * kWave + lane);
-            if (valid) {
-                if (key < K) {
+            base[k] = run;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < kMaxSteps; ++s) {
+            if ((uint32_t)s < sg.steps && key[s] != kNone) {
+                const uint32_t where = hist[key[s]] + rk[s];
+                const uint32_t p = (uint32_t)(wave_begin + (uint64_t)s * kWave + lane);
+                if (key[s] < K) {
                     if (where < n_fetch) fetch_pages[where] = p;
                 } else if (where < n_evict) {
                     evict_pages[where] = p;
-                    evict_frames[where] = fr[u];
+                    evict_frames[where] = fr[s];
                 }
             }
         }
+        __syncthreads();
     }
 }
 
@@ -364,7 +408,38 @@ __global__ __launch_bounds__(256) void k_frames(const PlanHeader *__restrict__ h
         fetch_frames[i] = (i < nfu) ? first + i : evict_frames[i - nfu];
 }
 
+__global__ __launch_bounds__(256) void k_zero(uint32_t *dst, uint64_t n) {
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < n; i += gridDim.x * (uint64_t)blockDim.x)
+        dst[i] = 0;
+}
+
 #define CK(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) return e_; } while (0)
+
+hipError_t launch_nu_reset(msched_ctx *c) {
+    (void)hipGetLastError();
+    const uint32_t blocks = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(4096, (c->V + 255) / 256));
+    k_zero<<<blocks, 256, 0, c->stream>>>(c->nu, c->V);
+    return hipGetLastError();
+}
+
+void plan_geometry(const msched_ctx *c, uint32_t G, PlanGeom &g) {
+    g.G = G;
+    g.n_keys = 2 * (G + 1);
+    // (waves + 1) arrays of n_keys counters must fit in 48 KiB of LDS
+    const uint32_t fit = (48u * 1024u) / (g.n_keys * 4u);
+    g.waves = std::max<uint32_t>(1, std::min<uint32_t>(kMaxWaves, fit > 1 ? fit - 1 : 1));
+    const uint64_t per_chunk = (c->V + kMaxChunks - 1) / kMaxChunks;
+    const uint64_t sub_steps = (per_chunk + (uint64_t)g.waves * kWave - 1) / ((uint64_t)g.waves * kWave);
+    if (sub_steps <= kMaxSteps) {
+        g.steps = (uint32_t)std::max<uint64_t>(4, sub_steps);
+        g.rounds = 1;
+    } else {
+        g.steps = kMaxSteps;
+        g.rounds = (uint32_t)((sub_steps + kMaxSteps - 1) / kMaxSteps);
+    }
+    g.chunk_pages = g.rounds * g.waves * g.steps * kWave;
+    g.n_chunks = (uint32_t)((c->V + g.chunk_pages - 1) / g.chunk_pages);
+}
 
 hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     (void)hipGetLastError();   // launches below are checked through the sticky error: start clean
@@ -372,27 +447,31 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     const bool prof = c->profiling != 0;
     if (prof) CK(hipEventRecord(c->ev[0], st));
     {
-        const uint64_t n4 = (c->V + 3) / 4;
-        const uint32_t blocks = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(4096, (n4 + 255) / 256));
-        k_fill<<<blocks, 256, 0, st>>>(c->nu, c->V, kNone, c->flags);
+        k_stage<<<(g.G * 8 + 255) / 256, 256, 0, st>>>(c->cmd_ptrs_dev, g.G, c->cmd_dev, c->flags);
         ExpandArgs a;
-        a.cmd_ptrs = c->cmd_ptrs_dev; a.G = g.G; a.kernels = c->kernels_dev;
+        a.cmds = c->cmd_dev; a.G = g.G; a.kernels = c->kernels_dev;
         a.nu = c->nu; a.slot = c->slot; a.flags = c->flags; a.V = c->V; a.page_shift = c->page_shift;
         a.n_split = (c->V > (1u << 20)) ? 8 : 1;
+        a.epoch_base = c->epoch << kNuShift;
         k_expand<<<dim3(g.G, c->max_rules, a.n_split), 256, 0, st>>>(a);
     }
     if (prof) CK(hipEventRecord(c->ev[1], st));
-    const size_t row_bytes = (size_t)g.n_keys * sizeof(uint32_t);
-    k_count<<<g.n_chunks, kWave, row_bytes, st>>>(c->page_table, c->nu, c->V, g.chunk_pages, g.G, c->matrix);
+    SweepGeom sg;
+    sg.V = c->V; sg.chunk_pages = g.chunk_pages; sg.steps = g.steps; sg.rounds = g.rounds; sg.G = g.G;
+    sg.epoch = c->epoch;
+    const uint32_t threads = g.waves * kWave;
+    k_count<<<g.n_chunks, threads, (size_t)g.waves * g.n_keys * 4, st>>>(c->page_table, c->nu, sg, c->matrix);
     if (prof) CK(hipEventRecord(c->ev[2], st));
     const dim3 cgrid((g.n_keys + 63) / 64, kRowGroups / 4), cblock(64, 4);
-    k_colsum<<<cgrid, cblock, 0, st>>>(c->matrix, g.n_chunks, g.n_keys, c->partial);
-    k_cut<<<1, 1024, (size_t)(g.n_keys + g.G + 1) * sizeof(uint32_t), st>>>(
-        c->partial, g.G, g.g_end0, c->F, c->flags, c->offsets, c->hdr_dev, c->hdr_host);
-    k_offsets<<<cgrid, cblock, 0, st>>>(c->matrix, g.n_chunks, g.n_keys, c->partial, c->offsets, c->hdr_dev);
+    const bool few_rows = g.n_chunks <= kRowGroups;          // the matrix rows are the row groups
+    if (!few_rows) k_colsum<<<cgrid, cblock, 0, st>>>(c->matrix, g.n_chunks, g.n_keys, c->partial);
+    k_cut<<<1, 1024, (size_t)(g.n_keys + g.G + 1) * 4, st>>>(few_rows ? c->matrix : c->partial,
+                                                              few_rows ? g.n_chunks : kRowGroups, g.G, g.g_end0, c->F,
+                                                              c->flags, c->offsets, c->hdr_dev, c->hdr_host);
+    if (!few_rows) k_offsets<<<cgrid, cblock, 0, st>>>(c->matrix, g.n_chunks, g.n_keys, c->partial, c->hdr_dev);
     if (prof) CK(hipEventRecord(c->ev[3], st));
-    k_emit<<<g.n_chunks, kWave, row_bytes, st>>>(c->page_table, c->nu, c->V, g.chunk_pages, g.G, c->matrix,
-                                                 c->hdr_dev, c->fetch_pages, c->evict_pages, c->evict_frames);
+    k_emit<<<g.n_chunks, threads, (size_t)(g.waves + 1) * g.n_keys * 4, st>>>(
+        c->page_table, c->nu, sg, c->matrix, c->offsets, c->hdr_dev, c->fetch_pages, c->evict_pages, c->evict_frames);
     const uint32_t fblocks = (uint32_t)std::min<uint64_t>(2048, ((uint64_t)c->F + 255) / 256);
     k_frames<<<fblocks, 256, 0, st>>>(c->hdr_dev, c->evict_frames, c->fetch_frames);
     if (prof) CK(hipEventRecord(c->ev[4], st));

@@ -61,6 +61,13 @@ def test_many_commands_in_one_timeline(oracle_mod):
     assert lockstep(oracle_mod, trace, with_bytes=True, horizon="full", max_plans=4) == 4
 
 
+def test_next_use_epoch_wraps_cleanly(oracle_mod, monkeypatch):
+    # the next-use array is never cleared between plans: entries carry a plan epoch that wraps
+    # after 2^20 - 1 plans; start 5 plans before the wrap and run across it
+    monkeypatch.setenv("MSCHED_INITIAL_EPOCH", str((1 << 20) - 6))
+    assert lockstep(oracle_mod, make_trace(1, seed=4), with_bytes=True) >= 20
+
+
 def test_errors_and_edge_cases(oracle_mod):
     from paper_2512_24637_amd import MSchedError
     trace = explicit_trace([[[0, 1, 2, 3], [4]], [[5]]], 8, 3, timeslice=1, page_shift=6)
