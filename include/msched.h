@@ -172,8 +172,11 @@ enum { MSCHED_PHASE_EXPAND = 0,   /* next-use reset + template expansion + scatt
        MSCHED_PHASE_CUT = 2,      /* totals, budget cut, victim threshold, output offsets */
        MSCHED_PHASE_EMIT = 3,     /* ordered compaction of both lists + frame assignment */
        MSCHED_PHASE_MIGRATE = 4,  /* copy kernel + page-table update */
-       MSCHED_N_PHASES = 5 };
-int msched_set_profiling(msched_ctx *ctx, int on);
+       MSCHED_PHASE_PLAN = 5,     /* all planning kernels of one msched_plan, first launch to last */
+       MSCHED_N_PHASES = 6 };
+/* level 0: off; 1: time each plan as a whole and each migrate (two events per call); 2: also time the
+ * four planning phases separately (the extra events between kernels add a few microseconds each). */
+int msched_set_profiling(msched_ctx *ctx, int level);
 int msched_get_phase_ms(msched_ctx *ctx, float *ms);
 
 const char *msched_strerror(int code);

@@ -10,7 +10,7 @@ import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 NOT_RESIDENT = 0xFFFFFFFF
-PHASES = ("expand", "count", "cut", "emit", "migrate")
+PHASES = ("expand", "count", "cut", "emit", "migrate", "plan")
 EXPORTED_SYMBOLS = (
     "msched_create", "msched_destroy", "msched_kernel_register", "msched_task_create",
     "msched_launch_enqueue", "msched_launch_retire", "msched_plan", "msched_migrate",
@@ -249,8 +249,9 @@ class MSched:
         self._check(self.lib.msched_state_copy(self.h, _np_ptr(pt), _np_ptr(fo)))
         return pt, fo
 
-    def set_profiling(self, on: bool):
-        self._check(self.lib.msched_set_profiling(self.h, int(on)))
+    def set_profiling(self, level: int):
+        """0 off, 1 whole-plan and migrate device times, 2 also the four planning phases."""
+        self._check(self.lib.msched_set_profiling(self.h, int(level)))
 
     def phase_ms(self) -> dict:
         ms = np.zeros(len(PHASES), np.float32)

@@ -75,6 +75,9 @@ void free_ctx(msched_ctx *c) {
     if (c->hdr_host) (void)hipHostFree(c->hdr_host);
     if (c->cmd_ptrs_host) (void)hipHostFree((void *)c->cmd_ptrs_host);
     for (auto &e : c->ev) if (e) (void)hipEventDestroy(e);
+    if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+    if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+    if (c->side) { (void)hipStreamSynchronize(c->side); (void)hipStreamDestroy(c->side); }
     delete c;
 }
 
@@ -108,6 +111,11 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     c->V = cfg->n_virtual_pages; c->F = cfg->n_frames; c->page_shift = cfg->page_shift;
     c->migrate_chunk_shift = (uint32_t)env_u32("MSCHED_MIGRATE_CHUNK_SHIFT", 6, 24, 14);
     c->migrate_max_blocks = (uint32_t)env_u32("MSCHED_MIGRATE_BLOCKS", 1, 1 << 20, 4096);
+    c->expand_split = (uint32_t)env_u32("MSCHED_EXPAND_SPLIT", 1, 64, 0);
+    c->max_chunks = (uint32_t)env_u32("MSCHED_MAX_CHUNKS", 1, kMaxChunks, kMaxChunks);
+    c->list_b0 = (uint32_t)env_u32("MSCHED_LIST_B0", 0, 4096, 4);
+    c->list_b1 = std::max(c->list_b0, (uint32_t)env_u32("MSCHED_LIST_B1", 0, 4096, 32));
+    c->list_overlap = env_u32("MSCHED_LIST_OVERLAP", 0, 1, 0);
     c->epoch = (uint32_t)env_u32("MSCHED_INITIAL_EPOCH", 0, kMaxEpoch, 0);   // test hook: start near the wrap
     int rc = MSCHED_OK;
     auto fail = [&](hipError_t e) { c->last_hip = g_last_hip = (int)e; rc = MSCHED_E_HIP; };
@@ -136,6 +144,9 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     if (rc == MSCHED_OK && (e = hipHostGetDevicePointer(&c->host_dev, cfg->host_store, 0)) != hipSuccess) fail(e);
     for (int i = 0; i < 8 && rc == MSCHED_OK; ++i)
         if ((e = hipEventCreate(&c->ev[i])) != hipSuccess) fail(e);
+    if (rc == MSCHED_OK && (e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming)) != hipSuccess) fail(e);
+    if (rc == MSCHED_OK && (e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming)) != hipSuccess) fail(e);
+    if (rc == MSCHED_OK && (e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking)) != hipSuccess) fail(e);
     if (rc == MSCHED_OK && (e = launch_init_tables(c)) != hipSuccess) fail(e);
     if (rc == MSCHED_OK && (e = launch_nu_reset(c)) != hipSuccess) fail(e);
     if (rc == MSCHED_OK && (e = hipStreamSynchronize(c->stream)) != hipSuccess) fail(e);
@@ -155,6 +166,7 @@ int msched_kernel_register(msched_ctx *c, const msched_rule *rules, uint32_t n_r
     DevKernel k;
     memset(&k, 0, sizeof k);
     k.n_rules = n_rules;
+    bool has_list = false;
     for (uint32_t r = 0; r < n_rules; ++r) {
         const msched_rule &q = rules[r];
         if (q.kind < MSCHED_RULE_FIXED || q.kind > MSCHED_RULE_LIST) return MSCHED_E_INVAL;
@@ -163,6 +175,7 @@ int msched_kernel_register(msched_ctx *c, const msched_rule *rules, uint32_t n_r
             return MSCHED_E_INVAL;
         if (q.kind == MSCHED_RULE_FIXED && q.n_size_args != 0) return MSCHED_E_INVAL;
         k.rules[r] = q;
+        if (q.kind == MSCHED_RULE_LIST) has_list = true;
     }
     // the table is small and changes rarely: keep a device copy in step with the host one
     if (c->kernels.size() + 1 > c->kernels_cap) {
@@ -178,6 +191,7 @@ int msched_kernel_register(msched_ctx *c, const msched_rule *rules, uint32_t n_r
     }
     HIP_TRY(c, hipMemcpy(c->kernels_dev + c->kernels.size(), &k, sizeof k, hipMemcpyHostToDevice));
     c->kernels.push_back(k);
+    c->has_list_rule = c->has_list_rule || has_list;
     c->max_rules = std::max(c->max_rules, n_rules);
     *kernel_id = (uint32_t)(c->kernels.size() - 1);
     return MSCHED_OK;
@@ -286,7 +300,8 @@ int msched_plan(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entri
         HIP_TRY(c, launch_plan(c, g));
         HIP_TRY(c, hipStreamSynchronize(c->stream));
         h = *c->hdr_host;
-        if (c->profiling)
+        if (c->profiling) HIP_TRY(c, hipEventElapsedTime(&c->phase_ms[MSCHED_PHASE_PLAN], c->ev[0], c->ev[4]));
+        if (c->profiling >= 2)
             for (int i = 0; i < 4; ++i) HIP_TRY(c, hipEventElapsedTime(&c->phase_ms[i], c->ev[i], c->ev[i + 1]));
         if (h.status & kStatRange) return MSCHED_E_RANGE;
         if (h.status & kStatWset) return MSCHED_E_WSET_TOO_LARGE;
@@ -351,9 +366,10 @@ int msched_state_copy(msched_ctx *c, uint32_t *page_table, uint32_t *frame_owner
     return MSCHED_OK;
 }
 
-int msched_set_profiling(msched_ctx *c, int on) {
-    if (!c) return MSCHED_E_INVAL;
-    c->profiling = on ? 1 : 0;
+int msched_set_profiling(msched_ctx *c, int level) {
+    if (!c || level < 0 || level > 2) return MSCHED_E_INVAL;
+    c->profiling = level;
+    for (float &m : c->phase_ms) m = 0.f;
     return MSCHED_OK;
 }
 

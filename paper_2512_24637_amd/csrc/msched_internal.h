@@ -69,6 +69,13 @@ struct msched_ctx {
     void *host_dev = nullptr;                   // device address of cfg.host_store
     uint32_t migrate_chunk_shift = 14;          // bytes a workgroup moves per work unit (log2)
     uint32_t migrate_max_blocks = 4096;         // grid cap of the copy kernel
+    uint32_t expand_split = 0;                  // workgroups per (command, rule); 0 = by page-table size
+    uint32_t max_chunks = msched::kMaxChunks;   // page-table chunks (sweep workgroups) at most
+    bool has_list_rule = false;                 // some registered kernel has a LIST rule
+    uint32_t list_b0 = 4, list_b1 = 32;         // id lists: commands [0,b0), [b0,b1), [b1,G) run as ordered batches
+    int list_overlap = 0;                       // last batch on the side stream, beside the range expansion (measured slower)
+    hipStream_t side = nullptr;                 // library-owned, default priority
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     uint32_t *page_table = nullptr, *frame_owner = nullptr, *nu = nullptr, *slot = nullptr;  // device
     uint32_t *evict_pages = nullptr, *evict_frames = nullptr, *fetch_pages = nullptr, *fetch_frames = nullptr;
     uint32_t *flags = nullptr;                  // device status word

@@ -55,6 +55,50 @@ __device__ __forceinline__ void touch(const ExpandArgs &a, uint32_t p, uint32_t 
     if (a.nu[p] < enc) atomicMax(&a.nu[p], enc);
 }
 
+// Items t0, t0 + step, ... < n of a page sequence, kBatch at a time: all page ids first, then all
+// current entries, then the atomics (which return nothing and are not waited for), so a lane keeps
+// kBatch independent memory round trips in flight instead of one dependent chain per page.
+// With kDedupe (explicit id lists, where popular pages repeat many times inside one command) a small
+// direct-mapped table in LDS remembers pages this workgroup has already handled: every workgroup
+// writes one value only, so a repeat can be dropped before it reaches memory.  The table is a filter,
+// not a set: a lost race or an evicted entry only costs a redundant atomic.
+constexpr int kBatch = 8;
+constexpr uint32_t kListSeenBits = 15;     // entries (log2) of the duplicate filter of k_expand_list
+constexpr int kListThreads = 1024;
+template <bool kDedupe, typename PageOf>
+__device__ __forceinline__ void touch_many(const ExpandArgs &a, uint64_t t0, uint64_t step, uint64_t n, uint32_t enc,
+                                           uint32_t *seen, uint32_t seen_bits, PageOf page_of) {
+    for (uint64_t i0 = t0; i0 < n; i0 += step * kBatch) {
+        uint32_t p[kBatch], cur[kBatch];
+        bool ok[kBatch];
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const uint64_t i = i0 + (uint64_t)j * step;
+            ok[j] = i < n;
+            p[j] = ok[j] ? page_of(i) : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            if (ok[j] && p[j] >= a.V) { atomicOr(a.flags, kStatRange); ok[j] = false; }
+            if (kDedupe && ok[j]) {
+                // an LDS exchange also settles duplicates among the lanes of one instruction
+                const uint32_t h = (p[j] * 2654435761u) >> (32 - seen_bits);
+                if (atomicExch(&seen[h], p[j]) == p[j]) ok[j] = false;
+            }
+        }
+        if (a.slot != nullptr) {
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j)
+                if (ok[j] && a.slot[p[j]] == kNone) { atomicOr(a.flags, kStatRange); ok[j] = false; }
+        }
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) cur[j] = ok[j] ? a.nu[p[j]] : 0xFFFFFFFFu;
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j)
+            if (cur[j] < enc) atomicMax(&a.nu[p[j]], enc);
+    }
+}
+
 __device__ __forceinline__ uint64_t formula(const uint64_t *args, uint64_t coeff, const uint8_t *idx, int n) {
     uint64_t v = coeff;
     for (int j = 0; j < n; ++j) v *= args[idx[j]];
@@ -76,16 +120,7 @@ __global__ __launch_bounds__(256) void k_expand(ExpandArgs a) {
     const uint64_t t0 = blockIdx.z * (uint64_t)blockDim.x + threadIdx.x;
     const uint64_t step = a.n_split * (uint64_t)blockDim.x;
 
-    if (q.kind == MSCHED_RULE_LIST) {
-        const uint32_t *ids = rec->ids;
-        const uint32_t n = rec->n_ids;
-        for (uint64_t i = t0; i < n; i += step) {
-            const uint32_t p = ids[i];
-            if (p >= a.V) { atomicOr(a.flags, kStatRange); continue; }
-            touch(a, p, enc);
-        }
-        return;
-    }
+    if (q.kind == MSCHED_RULE_LIST) return;                 // id lists are expanded by k_expand_list
     uint64_t base = rec->args[q.base_arg];
     uint64_t size = (q.kind == MSCHED_RULE_FIXED) ? q.size_coeff
                                                   : formula(rec->args, q.size_coeff, q.size_args, q.n_size_args);
@@ -108,14 +143,41 @@ __global__ __launch_bounds__(256) void k_expand(ExpandArgs a) {
                 for (uint64_t j = 0; j < count; ++j) {
                     const uint64_t c0 = base + j * stride;
                     const uint64_t p0 = c0 >> sh, n = ((c0 + size - 1) >> sh) - p0 + 1;
-                    for (uint64_t i = t0; i < n; i += step) touch(a, (uint32_t)(p0 + i), enc);
+                    touch_many<false>(a, t0, step, n, enc, nullptr, 0, [p0](uint64_t i) { return (uint32_t)(p0 + i); });
                 }
             }
             return;
         }
     }
     const uint64_t p0 = base >> sh, n = ((base + size - 1) >> sh) - p0 + 1;
-    for (uint64_t i = t0; i < n; i += step) touch(a, (uint32_t)(p0 + i), enc);
+    touch_many<false>(a, t0, step, n, enc, nullptr, 0, [p0](uint64_t i) { return (uint32_t)(p0 + i); });
+}
+
+// Explicit page-id lists (sparse gathers).  One 1024-thread workgroup per command: popular pages repeat
+// many times inside one list, and every repeat that reaches memory costs a random cache-line access, so
+// the workgroup first drops repeats in a 32 Ki-entry direct-mapped table in LDS (gfx950 has 160 KiB per
+// workgroup); what is left goes through the same check-then-atomic as the ranges.
+__global__ __launch_bounds__(kListThreads) void k_expand_list(ExpandArgs a, uint32_t g0, uint32_t n_split,
+                                                              uint32_t seen_bits) {
+    const uint32_t g = g0 + blockIdx.x / n_split, split = blockIdx.x % n_split;
+    __shared__ uint64_t s_rec[sizeof(CmdRec) / 8];
+    __shared__ uint32_t seen[1u << kListSeenBits];
+    if (threadIdx.x < sizeof(CmdRec) / 8)
+        s_rec[threadIdx.x] = reinterpret_cast<const uint64_t *>(a.cmds + g)[threadIdx.x];
+    __syncthreads();
+    const CmdRec *rec = reinterpret_cast<const CmdRec *>(s_rec);
+    const uint32_t n = rec->n_ids;
+    if (n == 0) return;
+    const DevKernel &k = a.kernels[rec->kernel];
+    bool has_list = false;
+    for (uint32_t r = 0; r < k.n_rules; ++r) has_list |= k.rules[r].kind == MSCHED_RULE_LIST;
+    if (!has_list) return;
+    for (uint32_t i = threadIdx.x; i < (1u << seen_bits); i += blockDim.x) seen[i] = kNone;
+    __syncthreads();
+    const uint32_t *ids = rec->ids;
+    const uint32_t enc = a.epoch_base | (kNuMask - g);
+    touch_many<true>(a, (uint64_t)split * blockDim.x + threadIdx.x, (uint64_t)n_split * blockDim.x, n, enc, seen, seen_bits,
+                     [ids](uint64_t i) { return ids[i]; });
 }
 
 // ------------------------------------------------------------------------------------------
@@ -130,6 +192,15 @@ __device__ __forceinline__ uint32_t classify(uint32_t frame, uint32_t enc, uint3
     return resident ? (G + 1 + c) : c;
 }
 
+// Workgroups are dispatched in blockIdx order; chunks whose pages carry many different classes
+// (sparse gathers) cost more than uniform ones and tend to be neighbours in the page table.  Striding
+// the block -> chunk map spreads them over the whole launch instead of leaving them for its tail.
+__device__ __forceinline__ uint32_t chunk_of_block(uint32_t block, uint32_t n_chunks) {
+    constexpr uint32_t kStride = 61;                       // prime; the map is a bijection when it does not divide n
+    if (n_chunks % kStride == 0) return block;
+    return (uint32_t)(((uint64_t)block * kStride) % n_chunks);
+}
+
 struct SweepGeom {
     uint64_t V;
     uint32_t chunk_pages;     // pages per workgroup
@@ -138,16 +209,12 @@ struct SweepGeom {
     uint32_t G, epoch;
 };
 
-// One tile: every wavefront loads its `steps` x 64 consecutive pages, classifies them and ranks
-// each page among the earlier pages of the same key inside this wavefront's slice (page order),
-// counting into its own LDS histogram.  Lanes with equal keys are grouped by ballot, so a step
-// costs one pass per distinct key present, not one per page.
-__device__ __forceinline__ void rank_tile(const uint32_t *__restrict__ page_table, const uint32_t *__restrict__ nu,
+// One tile: every wavefront loads its `steps` x 64 consecutive pages (all loads issued before any
+// use) and classifies them.
+__device__ __forceinline__ void load_tile(const uint32_t *__restrict__ page_table, const uint32_t *__restrict__ nu,
                                           const SweepGeom &sg, uint64_t wave_begin, uint64_t p_end,
-                                          uint32_t *hist, uint32_t (&key)[kMaxSteps], uint32_t (&fr)[kMaxSteps],
-                                          uint32_t (&rk)[kMaxSteps]) {
+                                          uint32_t (&key)[kMaxSteps], uint32_t (&fr)[kMaxSteps]) {
     const int lane = lane_id();
-    const uint64_t below = lanes_below();
     uint32_t enc[kMaxSteps];
 #pragma unroll
     for (int s = 0; s < kMaxSteps; ++s) {
@@ -157,51 +224,87 @@ __device__ __forceinline__ void rank_tile(const uint32_t *__restrict__ page_tabl
         enc[s] = in ? nu[p] : 0u;
     }
 #pragma unroll
+    for (int s = 0; s < kMaxSteps; ++s) key[s] = classify(fr[s], enc[s], sg.epoch, sg.G);
+}
+
+// Count the tile's pages per key into one LDS histogram.  Runs of pages usually share a key (dense
+// ranges, long stretches of resident pages nobody will use), so the first lane's key is settled for
+// all its lanes with one add; whatever other keys the step holds go through per-lane LDS atomics.
+__device__ __forceinline__ void count_tile(const SweepGeom &sg, uint32_t *hist, const uint32_t (&key)[kMaxSteps]) {
+    const int lane = lane_id();
+#pragma unroll
     for (int s = 0; s < kMaxSteps; ++s) {
-        key[s] = classify(fr[s], enc[s], sg.epoch, sg.G);
-        rk[s] = 0;
         if ((uint32_t)s < sg.steps) {
             const bool valid = key[s] != kNone;
-            uint64_t todo = __ballot(valid);
-            while (todo) {
-                const int leader = __ffsll((long long)todo) - 1;
+            const uint64_t any = __ballot(valid);
+            if (any) {
+                const int leader = __ffsll((long long)any) - 1;
                 const uint32_t k = __builtin_amdgcn_readlane(key[s], leader);
                 const uint64_t same = __ballot(valid && key[s] == k);
-                uint32_t before = 0;
-                if (lane == leader) { before = hist[k]; hist[k] = before + __popcll(same); }
-                before = __builtin_amdgcn_readlane(before, leader);
-                if (valid && key[s] == k) rk[s] = before + __popcll(same & below);
-                todo &= ~same;
+                if (lane == leader) atomicAdd(&hist[k], (uint32_t)__popcll(same));
+                if (valid && key[s] != k) atomicAdd(&hist[key[s]], 1u);
             }
         }
     }
 }
 
-// First sweep: pages per key in each chunk; one matrix row per chunk.
+// Rank each page among the earlier pages of the same key inside this wavefront's slice (page
+// order), counting into the wavefront's own LDS histogram.  Lanes with equal keys are grouped by
+// ballot, so a step costs one pass per distinct key present, not one per page, and the loop itself
+// touches no memory; one LDS atomic per distinct key then reserves the group's slots.
+__device__ __forceinline__ void rank_tile(const SweepGeom &sg, uint32_t *hist, const uint32_t (&key)[kMaxSteps],
+                                          uint32_t (&rk)[kMaxSteps]) {
+    const int lane = lane_id();
+    const uint64_t below = lanes_below();
+#pragma unroll
+    for (int s = 0; s < kMaxSteps; ++s) {
+        rk[s] = 0;
+        if ((uint32_t)s < sg.steps) {
+            const bool valid = key[s] != kNone;
+            int my_leader = lane;
+            uint32_t my_rank = 0, group = 0;
+            uint64_t todo = __ballot(valid);
+            while (todo) {
+                const int leader = __ffsll((long long)todo) - 1;
+                const uint32_t k = __builtin_amdgcn_readlane(key[s], leader);
+                const uint64_t same = __ballot(valid && key[s] == k);
+                if (valid && key[s] == k) {
+                    my_leader = leader;
+                    my_rank = __popcll(same & below);
+                    group = __popcll(same);
+                }
+                todo &= ~same;
+            }
+            uint32_t before = 0;
+            if (valid && lane == my_leader) before = atomicAdd(&hist[key[s]], group);
+            before = __shfl(before, my_leader, kWave);
+            rk[s] = before + my_rank;
+        }
+    }
+}
+
+// First sweep: pages per key in each chunk; one matrix row per chunk.  Counting needs no order, so
+// all wavefronts of the workgroup add into one LDS histogram.
 __global__ __launch_bounds__(kWave * kMaxWaves) void k_count(const uint32_t *__restrict__ page_table,
                                                               const uint32_t *__restrict__ nu, SweepGeom sg,
                                                               uint32_t *__restrict__ matrix) {
     extern __shared__ uint32_t lds[];
     const uint32_t n_keys = 2 * (sg.G + 1);
     const uint32_t waves = blockDim.x / kWave, wave = threadIdx.x / kWave;
-    uint32_t *hist = lds + wave * n_keys;
-    for (uint32_t i = threadIdx.x; i < waves * n_keys; i += blockDim.x) lds[i] = 0;
+    for (uint32_t i = threadIdx.x; i < n_keys; i += blockDim.x) lds[i] = 0;
     __syncthreads();
-    const uint64_t p_begin = (uint64_t)blockIdx.x * sg.chunk_pages;
+    const uint32_t chunk = chunk_of_block(blockIdx.x, gridDim.x);
+    const uint64_t p_begin = (uint64_t)chunk * sg.chunk_pages;
     const uint64_t p_end = min(sg.V, p_begin + sg.chunk_pages);
     const uint64_t tile_pages = (uint64_t)waves * sg.steps * kWave;
     for (uint32_t round = 0; round < sg.rounds; ++round) {
-        uint32_t key[kMaxSteps], fr[kMaxSteps], rk[kMaxSteps];
-        rank_tile(page_table, nu, sg, p_begin + round * tile_pages + (uint64_t)wave * sg.steps * kWave, p_end,
-                  hist, key, fr, rk);
+        uint32_t key[kMaxSteps], fr[kMaxSteps];
+        load_tile(page_table, nu, sg, p_begin + round * tile_pages + (uint64_t)wave * sg.steps * kWave, p_end, key, fr);
+        count_tile(sg, lds, key);
     }
     __syncthreads();
-    uint32_t *row = matrix + (size_t)blockIdx.x * n_keys;
-    for (uint32_t k = threadIdx.x; k < n_keys; k += blockDim.x) {
-        uint32_t s = 0;
-        for (uint32_t w = 0; w < waves; ++w) s += lds[w * n_keys + k];
-        row[k] = s;
-    }
+    uint32_t *row = matrix + (size_t)chunk * n_keys;
+    for (uint32_t k = threadIdx.x; k < n_keys; k += blockDim.x) row[k] = lds[k];
 }
 
 // Column sums of the count matrix, by row group.
@@ -354,12 +457,13 @@ __global__ __launch_bounds__(kWave * kMaxWaves) void k_emit(const uint32_t *__re
     const int lane = lane_id();
     uint32_t *base = lds + waves * n_keys;               // [n_keys] running output position per key
     uint32_t *hist = lds + wave * n_keys;
-    const uint32_t *row = matrix + (size_t)blockIdx.x * n_keys;
+    const uint32_t chunk = chunk_of_block(blockIdx.x, gridDim.x);
+    const uint32_t *row = matrix + (size_t)chunk * n_keys;
     for (uint32_t k = threadIdx.x; k < n_keys; k += blockDim.x) {
         const uint32_t off = offsets[k];
         base[k] = (off == kSkip) ? kSkip : off + row[k];
     }
-    const uint64_t p_begin = (uint64_t)blockIdx.x * sg.chunk_pages;
+    const uint64_t p_begin = (uint64_t)chunk * sg.chunk_pages;
     const uint64_t p_end = min(sg.V, p_begin + sg.chunk_pages);
     const uint64_t tile_pages = (uint64_t)waves * sg.steps * kWave;
     for (uint32_t round = 0; round < sg.rounds; ++round) {
@@ -367,7 +471,12 @@ __global__ __launch_bounds__(kWave * kMaxWaves) void k_emit(const uint32_t *__re
         __syncthreads();
         const uint64_t wave_begin = p_begin + round * tile_pages + (uint64_t)wave * sg.steps * kWave;
         uint32_t key[kMaxSteps], fr[kMaxSteps], rk[kMaxSteps];
-        rank_tile(page_table, nu, sg, wave_begin, p_end, hist, key, fr, rk);
+        load_tile(page_table, nu, sg, wave_begin, p_end, key, fr);
+        // a key none of whose pages in this chunk can land inside its list is dropped here
+#pragma unroll
+        for (int s = 0; s < kMaxSteps; ++s)
+            if (key[s] != kNone && base[key[s]] >= (key[s] < K ? n_fetch : n_evict)) key[s] = kNone;
+        rank_tile(sg, hist, key, rk);
         __syncthreads();
         // per key: each wavefront's start position in this tile; carry the running position on
         for (uint32_t k = threadIdx.x; k < n_keys; k += blockDim.x) {
@@ -428,7 +537,7 @@ void plan_geometry(const msched_ctx *c, uint32_t G, PlanGeom &g) {
     // (waves + 1) arrays of n_keys counters must fit in 48 KiB of LDS
     const uint32_t fit = (48u * 1024u) / (g.n_keys * 4u);
     g.waves = std::max<uint32_t>(1, std::min<uint32_t>(kMaxWaves, fit > 1 ? fit - 1 : 1));
-    const uint64_t per_chunk = (c->V + kMaxChunks - 1) / kMaxChunks;
+    const uint64_t per_chunk = (c->V + c->max_chunks - 1) / c->max_chunks;
     const uint64_t sub_steps = (per_chunk + (uint64_t)g.waves * kWave - 1) / ((uint64_t)g.waves * kWave);
     if (sub_steps <= kMaxSteps) {
         g.steps = (uint32_t)std::max<uint64_t>(4, sub_steps);
@@ -444,23 +553,43 @@ void plan_geometry(const msched_ctx *c, uint32_t G, PlanGeom &g) {
 hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     (void)hipGetLastError();   // launches below are checked through the sticky error: start clean
     hipStream_t st = c->stream;
-    const bool prof = c->profiling != 0;
-    if (prof) CK(hipEventRecord(c->ev[0], st));
+    const bool prof = c->profiling >= 2;
+    if (c->profiling) CK(hipEventRecord(c->ev[0], st));
     {
         k_stage<<<(g.G * 8 + 255) / 256, 256, 0, st>>>(c->cmd_ptrs_dev, g.G, c->cmd_dev, c->flags);
         ExpandArgs a;
         a.cmds = c->cmd_dev; a.G = g.G; a.kernels = c->kernels_dev;
         a.nu = c->nu; a.slot = c->slot; a.flags = c->flags; a.V = c->V; a.page_shift = c->page_shift;
-        a.n_split = (c->V > (1u << 20)) ? 8 : 1;
+        a.n_split = c->expand_split ? c->expand_split : ((c->V > (1u << 20)) ? 8 : 1);
         a.epoch_base = c->epoch << kNuShift;
+        // Id lists go first in three stream-ordered batches of growing size: the smallest g wins a page,
+        // so once the first few commands have written the popular pages, the check in front of the
+        // atomic turns every later touch of them into a plain (cached) load.  The big last batch runs on
+        // a side stream, next to the range expansion.
+        hipStream_t ls = st;
+        if (c->has_list_rule) {
+            const uint32_t b0 = std::min<uint32_t>(g.G, c->list_b0), b1 = std::min<uint32_t>(g.G, c->list_b1);
+            if (b0) k_expand_list<<<b0 * 16, kListThreads, 0, st>>>(a, 0, 16, kListSeenBits - 3);
+            if (b1 > b0) k_expand_list<<<(b1 - b0) * 4, kListThreads, 0, st>>>(a, b0, 4, kListSeenBits - 2);
+            if (g.G > b1) {
+                if (c->list_overlap) {
+                    CK(hipEventRecord(c->ev_fork, st));
+                    CK(hipStreamWaitEvent(c->side, c->ev_fork, 0));
+                    ls = c->side;
+                }
+                k_expand_list<<<g.G - b1, kListThreads, 0, ls>>>(a, b1, 1, kListSeenBits);
+                if (ls != st) CK(hipEventRecord(c->ev_join, ls));
+            }
+        }
         k_expand<<<dim3(g.G, c->max_rules, a.n_split), 256, 0, st>>>(a);
+        if (ls != st) CK(hipStreamWaitEvent(st, c->ev_join, 0));
     }
     if (prof) CK(hipEventRecord(c->ev[1], st));
     SweepGeom sg;
     sg.V = c->V; sg.chunk_pages = g.chunk_pages; sg.steps = g.steps; sg.rounds = g.rounds; sg.G = g.G;
     sg.epoch = c->epoch;
     const uint32_t threads = g.waves * kWave;
-    k_count<<<g.n_chunks, threads, (size_t)g.waves * g.n_keys * 4, st>>>(c->page_table, c->nu, sg, c->matrix);
+    k_count<<<g.n_chunks, threads, (size_t)g.n_keys * 4, st>>>(c->page_table, c->nu, sg, c->matrix);
     if (prof) CK(hipEventRecord(c->ev[2], st));
     const dim3 cgrid((g.n_keys + 63) / 64, kRowGroups / 4), cblock(64, 4);
     const bool few_rows = g.n_chunks <= kRowGroups;          // the matrix rows are the row groups
@@ -474,7 +603,7 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         c->page_table, c->nu, sg, c->matrix, c->offsets, c->hdr_dev, c->fetch_pages, c->evict_pages, c->evict_frames);
     const uint32_t fblocks = (uint32_t)std::min<uint64_t>(2048, ((uint64_t)c->F + 255) / 256);
     k_frames<<<fblocks, 256, 0, st>>>(c->hdr_dev, c->evict_frames, c->fetch_frames);
-    if (prof) CK(hipEventRecord(c->ev[4], st));
+    if (c->profiling) CK(hipEventRecord(c->ev[4], st));
     return hipGetLastError();
 }
 
