@@ -26,6 +26,21 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# Measured traffic of k_migrate at the L2's external port (HBM + host fabric) relative to the bytes it has to
+# move, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script calibrated against a 1 GiB device copy
+# (profiles/k_migrate_c2_stencil_pmc_traffic.md).
+MIGRATE_TRAFFIC_RATIO = {"read": 1.0001, "write": 1.0018}
+WORKLOADS = {
+    1: "c1-tiny-round-robin: 3 tasks, 64 KiB pages, pool 256 frames (16 MiB), footprint 24 MiB, timeslice 10 launches",
+    2: "c2-stencil-sweep: 4 tasks x 3 arrays of 256 MiB, 2 MiB pages, pool 1024 frames (2 GiB), footprint 3 GiB "
+       "(150 %), round-robin timeslice 25 launches",
+    3: "c3-dl-training: 2 tasks x 48 layers (weights 64-192 MiB, activations 32 MiB), 64 KiB pages, pool = half "
+       "the footprint, timeslice one iteration (96 launches)",
+    4: "c4-llm-decode: 2 tasks x 32 layers x 400 MiB weights + growing KV cache, 2 MiB pages, pool 8192 frames "
+       "(16 GiB), timeslice 4 decode steps",
+    5: "c5-planning-stress: 8 tasks, 4 KiB pages, 10 Mi pages, pool 4 Mi frames, 2 dense ranges + 20 000 Zipf page "
+       "ids per launch, timeslice 50 launches",
+}
 
 
 def log(*a):
@@ -114,6 +129,10 @@ def measure_link_peak(torch, nbytes=1 << 30, reps=3):
     torch.cuda.synchronize()
     hbm = 5 * 2 * gb / (e0.elapsed_time(e1) / 1e3)
     del h_src, h_dst, d_dst, d_src
+    torch.cuda.empty_cache()
+    empty_host = getattr(torch._C, "_host_emptyCache", None)
+    if empty_host is not None:
+        empty_host()                          # hand the pinned probe buffers back before the big stores are pinned
     return {"h2d_alone_GBs": gb / t_h2d, "d2h_alone_GBs": gb / t_d2h,
             "h2d_bidir_GBs": gb / tb_h2d, "d2h_bidir_GBs": gb / tb_d2h,
             "hbm_copy_GBs": hbm, "bytes_each": nbytes}
@@ -252,6 +271,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5],
+                    help="workload (default 2 = the configuration the metric is quoted on)")
     ap.add_argument("--no-plan-stress", action="store_true", help="skip the planning-stress leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-steps", type=int, default=80)
@@ -269,8 +290,17 @@ def main():
     link = measure_link_peak(torch)
     log(f"[bench] link peak: {json.dumps(link)}")
 
-    per_task = 25 * (-(-(args.steps + args.warmup) // 4))
-    trace_args = dict(config=2, n_launches=max(500, per_task))
+    need = args.steps + args.warmup
+    if args.config == 1:
+        trace_args = dict(config=1, n_launches=max(200, 10 * (need + 3)))
+    elif args.config == 2:
+        trace_args = dict(config=2, n_launches=max(500, 25 * (-(-need // 4))))
+    elif args.config == 3:
+        trace_args = dict(config=3, iterations=max(2, -(-need // 2)))        # >= 1 plan per iteration and task
+    elif args.config == 4:
+        trace_args = dict(config=4, steps=4 * (-(-need // 2)))
+    else:
+        trace_args = dict(config=5, n_launches=50 * (-(-need // 8)))
     trace = make_trace(**trace_args)
     P = trace.page_bytes
     buf, ms = make_context(torch, trace, fill_contents=True)
@@ -289,15 +319,14 @@ def main():
     peak = moved / roof_s / 1e9 if roof_s > 0 else 0.0
     plan_dev = [ph["plan"] for ph in r["phases"]]
     ms.close()
-    del buf
+    buf.release()
 
     result = {
         "metric": "migrated GB/s vs host-link peak; plan latency (us) per context switch",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": r["wall_s"] / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u8", "data": "synthetic",
-        "config": {"workload": "c2-stencil-sweep: 4 tasks x 3 arrays of 256 MiB, 2 MiB pages, pool 1024 frames "
-                               "(2 GiB), footprint 3 GiB (150 %), round-robin timeslice 25 launches",
+        "config": {"workload": WORKLOADS[args.config],
                    "page_bytes": P, "n_virtual_pages": trace.n_virtual_pages, "n_frames": trace.n_frames},
         "bytes_migrated": {"h2d": h2d, "d2h": d2h},
         "plan_latency_us": {"host_wall_mean": float(np.mean(r["plan_wall_s"])) * 1e6,
@@ -305,7 +334,12 @@ def main():
                             "host_wall_max": float(np.max(r["plan_wall_s"])) * 1e6,
                             "device_mean": float(np.mean(plan_dev)) * 1e3},
         "roofline": {"bound": "host-link", "achieved": achieved, "peak": peak, "unit": "GB/s",
-                     "frac": (achieved / peak) if peak else None, "traffic": None,
+                     "frac": (achieved / peak) if peak else None,
+                     "traffic": (MIGRATE_TRAFFIC_RATIO["read"] * moved / n_copy) if n_copy else None,
+                     "traffic_write": (MIGRATE_TRAFFIC_RATIO["write"] * moved / n_copy) if n_copy else None,
+                     "algorithmic_bytes_per_launch": (moved / n_copy) if n_copy else None,
+                     "traffic_source": "profiles/k_migrate_c2_stencil_pmc_traffic.md (FETCH_SIZE x2.000 and "
+                                       "WRITE_SIZE x1.000 after calibration; bytes per launch at the L2 external port)",
                      "kernel": "k_migrate", "launches": n_copy,
                      "avg_launch_ms": (mig_s / n_copy * 1e3) if n_copy else None,
                      "note": "peak = the same per-step byte mix at the pinned hipMemcpyAsync rates measured "
@@ -315,8 +349,11 @@ def main():
     if not args.no_plan_stress:
         result["roofline_plan"] = bench_planning_stress(torch)
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(trace_args, args.cpu_sample_steps)
-        result["miss_volume"] = miss_volume(dict(config=2))
+        if args.config == 2:
+            result["cpu_baseline"] = cpu_baseline(trace_args, args.cpu_sample_steps)
+            result["miss_volume"] = miss_volume(dict(config=2))
+        else:
+            result["cpu_baseline"] = None      # the oracle leg is sized for the default workload only
     print(json.dumps(result), flush=True)
 
 

@@ -124,3 +124,82 @@ def test_errors_and_edge_cases(oracle_mod):
         assert np.array_equal(before[0], after[0]) and np.array_equal(before[1], after[1])
     finally:
         g.close()
+
+
+def _random_rule_trace(rng, page_shift, V, n_frames, n_tasks, n_cmds, with_lists):
+    """Random templates of every kind (fixed, linear in 1-3 arguments, strided with small, large,
+    abutting and overlapping chunks, id lists with repeats) and random launches that stay in range."""
+    from workloads import Trace, RULE_FIXED, RULE_STRIDED
+    from workloads.trace import CommandBuilder
+    P = 1 << page_shift
+    n_bytes = V * P
+    kernels, makers = [], []
+    for k in range(12):
+        n_rules = int(rng.integers(1, 5))
+        rules, parts = [], []
+        n_args = 0
+        for r in range(n_rules):
+            kind = int(rng.choice([RULE_FIXED, RULE_LINEAR, RULE_STRIDED] + ([RULE_LIST] if with_lists and r == 0 else [])))
+            if kind == RULE_LIST:
+                rules.append(Rule(RULE_LIST)); parts.append(("list",)); continue
+            if n_args > 8:
+                break
+            base_idx = n_args; n_args += 1
+            if kind == RULE_FIXED:
+                size = int(rng.integers(0, 40 * P))
+                rules.append(Rule(RULE_FIXED, base_idx, (), size)); parts.append(("fixed", size))
+            elif kind == RULE_LINEAR:
+                m = int(rng.integers(1, 3))
+                idx = tuple(range(n_args, n_args + m)); n_args += m
+                coeff = int(rng.choice([1, 2, 4, 8]))
+                rules.append(Rule(RULE_LINEAR, base_idx, idx, coeff)); parts.append(("linear", m, coeff))
+            else:
+                idx = (n_args, n_args + 1, n_args + 2); n_args += 3
+                cs, cst = int(rng.choice([1, 16, 64])), int(rng.choice([1, 16, 64]))
+                rules.append(Rule(RULE_STRIDED, base_idx, (idx[0],), cs, (idx[1],), cst, (idx[2],), 1))
+                parts.append(("strided", cs, cst))
+        kernels.append(rules); makers.append((parts, n_args))
+    tasks, pools, off = [], [], 0
+    for t in range(n_tasks):
+        b = CommandBuilder()
+        for _ in range(n_cmds):
+            k = int(rng.integers(0, len(kernels)))
+            parts, n_args = makers[k]
+            args, n_ids, ids_off = [], 0, 0
+            for part in parts:
+                if part[0] == "list":
+                    n_ids = int(rng.integers(0, 200))
+                    pools.append(rng.integers(0, V, size=n_ids).astype(np.uint32)); ids_off = off; off += n_ids
+                    continue
+                span_cap = min(n_bytes // 2, 60 * P)
+                if part[0] == "fixed":
+                    args.append(int(rng.integers(0, n_bytes - part[1] + 1)))
+                elif part[0] == "linear":
+                    vals = [int(rng.integers(0, 40)) for _ in range(part[1])]
+                    size = part[2] * int(np.prod(vals))
+                    while size > span_cap:
+                        vals[0] = max(0, vals[0] // 2); size = part[2] * int(np.prod(vals))
+                    args.append(int(rng.integers(0, n_bytes - size + 1))); args.extend(vals)
+                else:
+                    chunk_n = int(rng.integers(0, 30 * P // part[1] + 1))       # up to ~30 pages per chunk
+                    stride_n = int(rng.integers(0, 40 * P // part[2] + 1))
+                    count = int(rng.integers(0, 6))
+                    span = (max(count, 1) - 1) * stride_n * part[2] + chunk_n * part[1]
+                    while span > n_bytes // 2:
+                        stride_n //= 2; chunk_n //= 2
+                        span = (max(count, 1) - 1) * stride_n * part[2] + chunk_n * part[1]
+                    args.append(int(rng.integers(0, n_bytes - span + 1))); args.extend([chunk_n, stride_n, count])
+            b.add(k, args, latency=int(rng.integers(1, 4)), ids_off=ids_off, n_ids=n_ids)
+        tasks.append(b.build())
+    ids_pool = np.concatenate(pools).astype(np.uint32) if pools else np.zeros(0, np.uint32)
+    return Trace(name="random-rules", page_shift=page_shift, n_virtual_pages=V, n_frames=n_frames,
+                 timeslice=4, kernels=kernels, tasks=tasks, ids_pool=ids_pool, n_slots=V)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_random_templates_of_every_kind(oracle_mod, seed):
+    rng = np.random.default_rng(100 + seed)
+    V = int(rng.choice([700, 3000, 9000]))
+    trace = _random_rule_trace(rng, page_shift=8, V=V, n_frames=V // 3 + 200, n_tasks=3, n_cmds=30,
+                               with_lists=bool(seed % 2))
+    assert lockstep(oracle_mod, trace, with_bytes=True, bytes_every=5) >= 10
