@@ -113,6 +113,7 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     c->migrate_max_blocks = (uint32_t)env_u32("MSCHED_MIGRATE_BLOCKS", 1, 1 << 20, 4096);
     c->expand_split = (uint32_t)env_u32("MSCHED_EXPAND_SPLIT", 1, 64, 0);
     c->max_chunks = (uint32_t)env_u32("MSCHED_MAX_CHUNKS", 1, kMaxChunks, kMaxChunks);
+    c->force_multi_kernel = env_u32("MSCHED_FORCE_MULTI_KERNEL", 0, 1, 0) != 0;
     c->list_b0 = (uint32_t)env_u32("MSCHED_LIST_B0", 0, 4096, 4);
     c->list_b1 = std::max(c->list_b0, (uint32_t)env_u32("MSCHED_LIST_B1", 0, 4096, 32));
     c->list_overlap = env_u32("MSCHED_LIST_OVERLAP", 0, 1, 0);
@@ -149,6 +150,7 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     if (rc == MSCHED_OK && (e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking)) != hipSuccess) fail(e);
     if (rc == MSCHED_OK && (e = launch_init_tables(c)) != hipSuccess) fail(e);
     if (rc == MSCHED_OK && (e = launch_nu_reset(c)) != hipSuccess) fail(e);
+    if (rc == MSCHED_OK && (e = hipMemsetAsync(c->flags, 0, 256, c->stream)) != hipSuccess) fail(e);
     if (rc == MSCHED_OK && (e = hipStreamSynchronize(c->stream)) != hipSuccess) fail(e);
     if (rc != MSCHED_OK) { free_ctx(c); return rc; }
     *out = c;

@@ -13,6 +13,7 @@ constexpr uint32_t kNone = 0xFFFFFFFFu;         // not resident / free frame / n
 constexpr uint32_t kSkip = 0x80000000u;         // output offset of a class that is not emitted
 constexpr int kWave = 64;                       // CDNA wavefront
 constexpr uint32_t kMaxChunks = 2048;           // page-table chunks (one workgroup each)
+constexpr uint32_t kSingleChunkPages = 32768;   // page tables up to this size are swept by one workgroup
 constexpr int kMaxWaves = 8;                    // wavefronts per sweep workgroup
 constexpr int kMaxSteps = 16;                   // 64-page steps a wavefront keeps in registers per tile
 constexpr uint32_t kNuShift = 12;               // nu entry = (epoch << kNuShift) | (kNuMask - g)
@@ -57,6 +58,7 @@ struct TaskQueue {
 struct PlanGeom {
     uint32_t G, g_end0, n_chunks, chunk_pages, n_keys;   // n_keys = 2 * (G + 1)
     uint32_t waves, steps, rounds;                       // sweep workgroup shape
+    bool single;                                         // one workgroup sweeps the whole table (fused tail kernel)
 };
 
 }  // namespace msched
@@ -71,6 +73,7 @@ struct msched_ctx {
     uint32_t migrate_max_blocks = 4096;         // grid cap of the copy kernel
     uint32_t expand_split = 0;                  // workgroups per (command, rule); 0 = by page-table size
     uint32_t max_chunks = msched::kMaxChunks;   // page-table chunks (sweep workgroups) at most
+    bool force_multi_kernel = false;            // test hook: never use the fused single-workgroup tail
     bool has_list_rule = false;                 // some registered kernel has a LIST rule
     uint32_t list_b0 = 4, list_b1 = 32;         // id lists: commands [0,b0), [b0,b1), [b1,G) run as ordered batches
     int list_overlap = 0;                       // last batch on the side stream, beside the range expansion (measured slower)

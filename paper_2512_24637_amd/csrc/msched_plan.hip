@@ -26,12 +26,12 @@ __device__ __forceinline__ uint64_t lanes_below() { return (1ull << lane_id()) -
 
 // ------------------------------------------------------------------------------------------
 // Stage the G command records of this plan from pinned host memory into device memory (one
-// pass over the link instead of one round trip per expansion workgroup) and clear the status word.
+// pass over the link instead of one round trip per expansion workgroup).  Short timelines skip this
+// and let the few expansion workgroups read their record through the pinned table themselves.
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_stage(const CmdRec *const *__restrict__ cmd_ptrs, uint32_t G,
-                                                CmdRec *__restrict__ cmd_dev, uint32_t *__restrict__ flags) {
+                                                CmdRec *__restrict__ cmd_dev) {
     const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t == 0) *flags = 0;
     const uint32_t g = t >> 3, part = t & 7;
     if (g >= G) return;
     const uint4 *src = reinterpret_cast<const uint4 *>(cmd_ptrs[g]);
@@ -44,7 +44,8 @@ __global__ __launch_bounds__(256) void k_stage(const CmdRec *const *__restrict__
 // runs, so a plain load that already shows a value >= ours lets the atomic be skipped.
 // ------------------------------------------------------------------------------------------
 struct ExpandArgs {
-    const CmdRec *cmds; uint32_t G;
+    const CmdRec *cmds;                 // staged records, or null: read through cmd_ptrs
+    const CmdRec *const *cmd_ptrs; uint32_t G;
     const DevKernel *kernels;
     uint32_t *nu; const uint32_t *slot; uint32_t *flags;
     uint64_t V; uint32_t page_shift, n_split, epoch_base;   // epoch_base = epoch << kNuShift
@@ -108,8 +109,10 @@ __device__ __forceinline__ uint64_t formula(const uint64_t *args, uint64_t coeff
 __global__ __launch_bounds__(256) void k_expand(ExpandArgs a) {
     const uint32_t g = blockIdx.x, r = blockIdx.y;
     __shared__ uint64_t s_rec[sizeof(CmdRec) / 8];
-    if (threadIdx.x < sizeof(CmdRec) / 8)
-        s_rec[threadIdx.x] = reinterpret_cast<const uint64_t *>(a.cmds + g)[threadIdx.x];
+    if (threadIdx.x < sizeof(CmdRec) / 8) {
+        const CmdRec *src = a.cmds ? a.cmds + g : a.cmd_ptrs[g];
+        s_rec[threadIdx.x] = reinterpret_cast<const uint64_t *>(src)[threadIdx.x];
+    }
     __syncthreads();
     const CmdRec *rec = reinterpret_cast<const CmdRec *>(s_rec);
     const DevKernel &k = a.kernels[rec->kernel];
@@ -162,8 +165,10 @@ __global__ __launch_bounds__(kListThreads) void k_expand_list(ExpandArgs a, uint
     const uint32_t g = g0 + blockIdx.x / n_split, split = blockIdx.x % n_split;
     __shared__ uint64_t s_rec[sizeof(CmdRec) / 8];
     __shared__ uint32_t seen[1u << kListSeenBits];
-    if (threadIdx.x < sizeof(CmdRec) / 8)
-        s_rec[threadIdx.x] = reinterpret_cast<const uint64_t *>(a.cmds + g)[threadIdx.x];
+    if (threadIdx.x < sizeof(CmdRec) / 8) {
+        const CmdRec *src = a.cmds ? a.cmds + g : a.cmd_ptrs[g];
+        s_rec[threadIdx.x] = reinterpret_cast<const uint64_t *>(src)[threadIdx.x];
+    }
     __syncthreads();
     const CmdRec *rec = reinterpret_cast<const CmdRec *>(s_rec);
     const uint32_t n = rec->n_ids;
@@ -283,17 +288,14 @@ __device__ __forceinline__ void rank_tile(const SweepGeom &sg, uint32_t *hist, c
     }
 }
 
-// First sweep: pages per key in each chunk; one matrix row per chunk.  Counting needs no order, so
-// all wavefronts of the workgroup add into one LDS histogram.
-__global__ __launch_bounds__(kWave * kMaxWaves) void k_count(const uint32_t *__restrict__ page_table,
-                                                              const uint32_t *__restrict__ nu, SweepGeom sg,
-                                                              uint32_t *__restrict__ matrix) {
-    extern __shared__ uint32_t lds[];
+// First sweep: pages per key in one chunk -> one matrix row.  Counting needs no order, so all
+// wavefronts of the workgroup add into one LDS histogram.
+__device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_table, const uint32_t *__restrict__ nu,
+                                           const SweepGeom &sg, uint32_t chunk, uint32_t *lds, uint32_t *row) {
     const uint32_t n_keys = 2 * (sg.G + 1);
     const uint32_t waves = blockDim.x / kWave, wave = threadIdx.x / kWave;
     for (uint32_t i = threadIdx.x; i < n_keys; i += blockDim.x) lds[i] = 0;
     __syncthreads();
-    const uint32_t chunk = chunk_of_block(blockIdx.x, gridDim.x);
     const uint64_t p_begin = (uint64_t)chunk * sg.chunk_pages;
     const uint64_t p_end = min(sg.V, p_begin + sg.chunk_pages);
     const uint64_t tile_pages = (uint64_t)waves * sg.steps * kWave;
@@ -303,8 +305,15 @@ __global__ __launch_bounds__(kWave * kMaxWaves) void k_count(const uint32_t *__r
         count_tile(sg, lds, key);
     }
     __syncthreads();
-    uint32_t *row = matrix + (size_t)chunk * n_keys;
     for (uint32_t k = threadIdx.x; k < n_keys; k += blockDim.x) row[k] = lds[k];
+}
+
+__global__ __launch_bounds__(kWave * kMaxWaves) void k_count(const uint32_t *__restrict__ page_table,
+                                                              const uint32_t *__restrict__ nu, SweepGeom sg,
+                                                              uint32_t *__restrict__ matrix) {
+    extern __shared__ uint32_t lds[];
+    const uint32_t chunk = chunk_of_block(blockIdx.x, gridDim.x);
+    count_body(page_table, nu, sg, chunk, lds, matrix + (size_t)chunk * 2 * (sg.G + 1));
 }
 
 // Column sums of the count matrix, by row group.
@@ -321,10 +330,11 @@ __global__ __launch_bounds__(256) void k_colsum(const uint32_t *__restrict__ mat
     partial[rg * n_keys + key] = s;
 }
 
-// In-place exclusive scan of a[0..n) in LDS by a 1024-thread block; returns the total to all threads.
+// In-place exclusive scan of a[0..n) in LDS by the whole block (a multiple of 64 threads, at most
+// 1024); returns the total to all threads.
 __device__ uint32_t block_exclusive_scan(uint32_t *a, uint32_t n, uint32_t *wave_sums) {
-    const uint32_t tid = threadIdx.x;
-    const uint32_t per = (n + 1023) / 1024;
+    const uint32_t tid = threadIdx.x, nthreads = blockDim.x;
+    const uint32_t per = (n + nthreads - 1) / nthreads;
     const uint32_t i0 = min(n, tid * per), i1 = min(n, i0 + per);
     uint32_t local = 0;
     for (uint32_t i = i0; i < i1; ++i) local += a[i];
@@ -339,7 +349,7 @@ __device__ uint32_t block_exclusive_scan(uint32_t *a, uint32_t n, uint32_t *wave
     if (lane == kWave - 1) wave_sums[wave] = incl;
     __syncthreads();
     uint32_t wave_base = 0, total = 0;
-    for (uint32_t w = 0; w < 1024 / kWave; ++w) {
+    for (uint32_t w = 0; w < nthreads / kWave; ++w) {
         const uint32_t s = wave_sums[w];
         if (w < wave) wave_base += s;
         total += s;
@@ -355,67 +365,75 @@ __device__ uint32_t block_exclusive_scan(uint32_t *a, uint32_t n, uint32_t *wave
 //   fetch offsets: classes 0..g_cut-1 of non-resident pages, ascending
 //   victim offsets: resident classes G (never used), G-1, ..., g_cut, in that order
 // `groups` holds n_groups rows of per-key counts (row-group sums, or the matrix itself when it has
-// few rows); they are replaced by their exclusive prefix over the rows.
-__global__ __launch_bounds__(1024) void k_cut(uint32_t *__restrict__ groups, uint32_t n_groups, uint32_t G,
-                                               uint32_t g_end0, uint32_t F, const uint32_t *__restrict__ flags,
-                                               uint32_t *__restrict__ offsets, PlanHeader *__restrict__ hdr_dev,
-                                               PlanHeader *__restrict__ hdr_host) {
-    extern __shared__ uint32_t lds[];
-    const uint32_t K = G + 1, n_keys = 2 * K;
+// few rows); they are replaced by their exclusive prefix over the rows.  One workgroup.
+struct CutArgs {
+    uint32_t *groups; uint32_t n_groups, G, g_end0, F;
+    uint32_t *flags, *offsets;
+    PlanHeader *hdr_dev, *hdr_host;
+};
+
+__device__ void cut_body(const CutArgs &a, uint32_t *lds) {
+    const uint32_t G = a.G, K = G + 1, n_keys = 2 * K, g_end0 = a.g_end0, nthreads = blockDim.x;
     uint32_t *tot = lds;                 // [n_keys]
     uint32_t *sc = lds + n_keys;         // [K]
     __shared__ uint32_t wave_sums[1024 / kWave];
     __shared__ uint32_t s_cut, s_res;
     const uint32_t tid = threadIdx.x;
     if (tid == 0) { s_cut = 0; s_res = 0; }
-    for (uint32_t key = tid; key < n_keys; key += 1024) {
+    for (uint32_t key = tid; key < n_keys; key += nthreads) {
         uint32_t v[kRowGroups];
 #pragma unroll
-        for (uint32_t rg = 0; rg < kRowGroups; ++rg) v[rg] = (rg < n_groups) ? groups[rg * n_keys + key] : 0;
+        for (uint32_t rg = 0; rg < kRowGroups; ++rg) v[rg] = (rg < a.n_groups) ? a.groups[rg * n_keys + key] : 0;
         uint32_t run = 0;
 #pragma unroll
         for (uint32_t rg = 0; rg < kRowGroups; ++rg) {
-            if (rg < n_groups) groups[rg * n_keys + key] = run;
+            if (rg < a.n_groups) a.groups[rg * n_keys + key] = run;
             run += v[rg];
         }
         tot[key] = run;
     }
     __syncthreads();
     // cut
-    for (uint32_t c = tid; c < K; c += 1024) sc[c] = (c < g_end0) ? tot[c] + tot[K + c] : 0;
+    for (uint32_t c = tid; c < K; c += nthreads) sc[c] = (c < g_end0) ? tot[c] + tot[K + c] : 0;
     __syncthreads();
     block_exclusive_scan(sc, K, wave_sums);                          // sc[k] = D(k) for k < K
     uint32_t fit = 0, res = 0;
-    for (uint32_t k = 1 + tid; k <= g_end0; k += 1024) fit += (sc[k] <= F) ? 1u : 0u;   // g_end0 <= G < K
-    for (uint32_t c = tid; c < K; c += 1024) res += tot[K + c];
+    for (uint32_t k = 1 + tid; k <= g_end0; k += nthreads) fit += (sc[k] <= a.F) ? 1u : 0u;   // g_end0 <= G < K
+    for (uint32_t c = tid; c < K; c += nthreads) res += tot[K + c];
     if (fit) atomicAdd(&s_cut, fit);
     if (res) atomicAdd(&s_res, res);
     __syncthreads();
     const uint32_t g_cut = s_cut, n_res = s_res;
     // fetch offsets
-    for (uint32_t c = tid; c < K; c += 1024) sc[c] = (c < g_cut) ? tot[c] : 0;
+    for (uint32_t c = tid; c < K; c += nthreads) sc[c] = (c < g_cut) ? tot[c] : 0;
     __syncthreads();
     uint32_t n_fetch = block_exclusive_scan(sc, K, wave_sums);
-    for (uint32_t c = tid; c < K; c += 1024) offsets[c] = (c < g_cut) ? sc[c] : kSkip;
+    for (uint32_t c = tid; c < K; c += nthreads) a.offsets[c] = (c < g_cut) ? sc[c] : kSkip;
     __syncthreads();
     // victim offsets, farthest next use first
-    for (uint32_t j = tid; j < K; j += 1024) sc[j] = (G - j >= g_cut) ? tot[K + (G - j)] : 0;
+    for (uint32_t j = tid; j < K; j += nthreads) sc[j] = (G - j >= g_cut) ? tot[K + (G - j)] : 0;
     __syncthreads();
     block_exclusive_scan(sc, K, wave_sums);
-    for (uint32_t c = tid; c < K; c += 1024) offsets[K + c] = (c >= g_cut) ? sc[G - c] : kSkip;
+    for (uint32_t c = tid; c < K; c += nthreads) a.offsets[K + c] = (c >= g_cut) ? sc[G - c] : kSkip;
     if (tid == 0) {
-        uint32_t status = *flags;
+        uint32_t status = *a.flags;
+        *a.flags = 0;                                       // clean for the next plan's expansion
         if (g_end0 > 0 && g_cut == 0) status |= kStatWset;
         if (status) n_fetch = 0;
-        const uint32_t n_free = F - n_res;
+        const uint32_t n_free = a.F - n_res;
         PlanHeader h;
         h.n_fetch = n_fetch;
         h.n_free_used = min(n_free, n_fetch);
         h.n_evict = n_fetch - h.n_free_used;
         h.g_cut = g_cut; h.n_resident = n_res; h.status = status; h.first_free = n_res; h.pad = 0;
-        *hdr_dev = h;
-        *hdr_host = h;
+        *a.hdr_dev = h;
+        *a.hdr_host = h;
     }
+}
+
+__global__ __launch_bounds__(1024) void k_cut(CutArgs a) {
+    extern __shared__ uint32_t lds[];
+    cut_body(a, lds);
 }
 
 // matrix[w][key] = pages of that key in chunks before w (exclusive prefix down each column).
@@ -438,29 +456,26 @@ __global__ __launch_bounds__(256) void k_offsets(uint32_t *__restrict__ matrix, 
     }
 }
 
-// Second sweep: every listed page goes to its final position =
+// Second sweep over one chunk: every listed page goes to its final position =
 //   class offset + pages of the key in earlier chunks + in earlier tiles and wavefronts of this
 //   chunk + rank inside the wavefront's slice.
-__global__ __launch_bounds__(kWave * kMaxWaves) void k_emit(const uint32_t *__restrict__ page_table,
-                                                             const uint32_t *__restrict__ nu, SweepGeom sg,
-                                                             const uint32_t *__restrict__ matrix,
-                                                             const uint32_t *__restrict__ offsets,
-                                                             const PlanHeader *__restrict__ hdr,
-                                                             uint32_t *__restrict__ fetch_pages,
-                                                             uint32_t *__restrict__ evict_pages,
-                                                             uint32_t *__restrict__ evict_frames) {
-    extern __shared__ uint32_t lds[];
-    const uint32_t n_fetch = hdr->n_fetch, n_evict = hdr->n_evict;
-    if (n_fetch == 0) return;
+struct EmitArgs {
+    const uint32_t *page_table, *nu, *matrix, *offsets;
+    const PlanHeader *hdr;
+    uint32_t *fetch_pages, *evict_pages, *evict_frames;
+};
+
+__device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg, uint32_t chunk, uint32_t *lds) {
+    const uint32_t n_fetch = a.hdr->n_fetch, n_evict = a.hdr->n_evict;
+    if (n_fetch == 0) return;                             // same for every thread of the block
     const uint32_t K = sg.G + 1, n_keys = 2 * K;
     const uint32_t waves = blockDim.x / kWave, wave = threadIdx.x / kWave;
     const int lane = lane_id();
     uint32_t *base = lds + waves * n_keys;               // [n_keys] running output position per key
     uint32_t *hist = lds + wave * n_keys;
-    const uint32_t chunk = chunk_of_block(blockIdx.x, gridDim.x);
-    const uint32_t *row = matrix + (size_t)chunk * n_keys;
+    const uint32_t *row = a.matrix + (size_t)chunk * n_keys;
     for (uint32_t k = threadIdx.x; k < n_keys; k += blockDim.x) {
-        const uint32_t off = offsets[k];
+        const uint32_t off = a.offsets[k];
         base[k] = (off == kSkip) ? kSkip : off + row[k];
     }
     const uint64_t p_begin = (uint64_t)chunk * sg.chunk_pages;
@@ -471,7 +486,7 @@ __global__ __launch_bounds__(kWave * kMaxWaves) void k_emit(const uint32_t *__re
         __syncthreads();
         const uint64_t wave_begin = p_begin + round * tile_pages + (uint64_t)wave * sg.steps * kWave;
         uint32_t key[kMaxSteps], fr[kMaxSteps], rk[kMaxSteps];
-        load_tile(page_table, nu, sg, wave_begin, p_end, key, fr);
+        load_tile(a.page_table, a.nu, sg, wave_begin, p_end, key, fr);
         // a key none of whose pages in this chunk can land inside its list is dropped here
 #pragma unroll
         for (int s = 0; s < kMaxSteps; ++s)
@@ -495,10 +510,10 @@ __global__ __launch_bounds__(kWave * kMaxWaves) void k_emit(const uint32_t *__re
                 const uint32_t where = hist[key[s]] + rk[s];
                 const uint32_t p = (uint32_t)(wave_begin + (uint64_t)s * kWave + lane);
                 if (key[s] < K) {
-                    if (where < n_fetch) fetch_pages[where] = p;
+                    if (where < n_fetch) a.fetch_pages[where] = p;
                 } else if (where < n_evict) {
-                    evict_pages[where] = p;
-                    evict_frames[where] = fr[s];
+                    a.evict_pages[where] = p;
+                    a.evict_frames[where] = fr[s];
                 }
             }
         }
@@ -506,15 +521,38 @@ __global__ __launch_bounds__(kWave * kMaxWaves) void k_emit(const uint32_t *__re
     }
 }
 
+__global__ __launch_bounds__(kWave * kMaxWaves) void k_emit(EmitArgs a, SweepGeom sg) {
+    extern __shared__ uint32_t lds[];
+    emit_body(a, sg, chunk_of_block(blockIdx.x, gridDim.x), lds);
+}
+
 // Frame of every fetched page: free frames lowest first, then the victims' frames in eviction order
 // (Sec. 6.3: target i is populated into the space reclaimed from victim i).  Frames are handed out
 // in ascending order and only ever reused through an eviction, so the free ones are [first_free, F).
+__device__ __forceinline__ void frames_body(const PlanHeader *hdr, const uint32_t *evict_frames,
+                                            uint32_t *fetch_frames, uint32_t t0, uint32_t nthreads) {
+    const uint32_t n = hdr->n_fetch, nfu = hdr->n_free_used, first = hdr->first_free;
+    for (uint32_t i = t0; i < n; i += nthreads) fetch_frames[i] = (i < nfu) ? first + i : evict_frames[i - nfu];
+}
+
 __global__ __launch_bounds__(256) void k_frames(const PlanHeader *__restrict__ hdr,
                                                 const uint32_t *__restrict__ evict_frames,
                                                 uint32_t *__restrict__ fetch_frames) {
-    const uint32_t n = hdr->n_fetch, nfu = hdr->n_free_used, first = hdr->first_free;
-    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x)
-        fetch_frames[i] = (i < nfu) ? first + i : evict_frames[i - nfu];
+    frames_body(hdr, evict_frames, fetch_frames, blockIdx.x * blockDim.x + threadIdx.x, gridDim.x * blockDim.x);
+}
+
+// Page tables small enough for one workgroup: count, cut, emit and frame assignment in one launch
+// (planning such a table is bound by launch latency, not by bandwidth).
+__global__ __launch_bounds__(kWave * kMaxWaves) void k_tail(SweepGeom sg, CutArgs ca, EmitArgs ea,
+                                                             uint32_t *__restrict__ fetch_frames) {
+    extern __shared__ uint32_t lds[];
+    count_body(ea.page_table, ea.nu, sg, 0, lds, ca.groups);
+    __syncthreads();
+    cut_body(ca, lds);
+    __syncthreads();
+    emit_body(ea, sg, 0, lds);
+    __syncthreads();
+    frames_body(ea.hdr, ea.evict_frames, fetch_frames, threadIdx.x, blockDim.x);
 }
 
 __global__ __launch_bounds__(256) void k_zero(uint32_t *dst, uint64_t n) {
@@ -537,8 +575,20 @@ void plan_geometry(const msched_ctx *c, uint32_t G, PlanGeom &g) {
     // (waves + 1) arrays of n_keys counters must fit in 48 KiB of LDS
     const uint32_t fit = (48u * 1024u) / (g.n_keys * 4u);
     g.waves = std::max<uint32_t>(1, std::min<uint32_t>(kMaxWaves, fit > 1 ? fit - 1 : 1));
+    const uint64_t wave_pages = (uint64_t)g.waves * kWave;
+    if (c->V <= kSingleChunkPages && !c->force_multi_kernel) {
+        // one workgroup sweeps the whole table: count, cut, emit and frames fuse into one launch
+        const uint64_t sub_steps = (c->V + wave_pages - 1) / wave_pages;
+        g.steps = (uint32_t)std::min<uint64_t>(kMaxSteps, std::max<uint64_t>(1, sub_steps));
+        g.rounds = (uint32_t)((sub_steps + g.steps - 1) / g.steps);
+        g.chunk_pages = g.rounds * g.waves * g.steps * kWave;
+        g.n_chunks = 1;
+        g.single = true;
+        return;
+    }
+    g.single = false;
     const uint64_t per_chunk = (c->V + c->max_chunks - 1) / c->max_chunks;
-    const uint64_t sub_steps = (per_chunk + (uint64_t)g.waves * kWave - 1) / ((uint64_t)g.waves * kWave);
+    const uint64_t sub_steps = (per_chunk + wave_pages - 1) / wave_pages;
     if (sub_steps <= kMaxSteps) {
         g.steps = (uint32_t)std::max<uint64_t>(4, sub_steps);
         g.rounds = 1;
@@ -556,16 +606,18 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     const bool prof = c->profiling >= 2;
     if (c->profiling) CK(hipEventRecord(c->ev[0], st));
     {
-        k_stage<<<(g.G * 8 + 255) / 256, 256, 0, st>>>(c->cmd_ptrs_dev, g.G, c->cmd_dev, c->flags);
         ExpandArgs a;
-        a.cmds = c->cmd_dev; a.G = g.G; a.kernels = c->kernels_dev;
+        a.cmd_ptrs = c->cmd_ptrs_dev; a.G = g.G; a.kernels = c->kernels_dev;
         a.nu = c->nu; a.slot = c->slot; a.flags = c->flags; a.V = c->V; a.page_shift = c->page_shift;
         a.n_split = c->expand_split ? c->expand_split : ((c->V > (1u << 20)) ? 8 : 1);
         a.epoch_base = c->epoch << kNuShift;
+        // few expansion workgroups: each reads its record over the link itself; many: stage once
+        const bool stage = (uint64_t)g.G * c->max_rules * a.n_split > 2048 || c->has_list_rule;
+        a.cmds = stage ? c->cmd_dev : nullptr;
+        if (stage) k_stage<<<(g.G * 8 + 255) / 256, 256, 0, st>>>(c->cmd_ptrs_dev, g.G, c->cmd_dev);
         // Id lists go first in three stream-ordered batches of growing size: the smallest g wins a page,
         // so once the first few commands have written the popular pages, the check in front of the
-        // atomic turns every later touch of them into a plain (cached) load.  The big last batch runs on
-        // a side stream, next to the range expansion.
+        // atomic turns every later touch of them into a plain (cached) load.
         hipStream_t ls = st;
         if (c->has_list_rule) {
             const uint32_t b0 = std::min<uint32_t>(g.G, c->list_b0), b1 = std::min<uint32_t>(g.G, c->list_b1);
@@ -589,18 +641,28 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     sg.V = c->V; sg.chunk_pages = g.chunk_pages; sg.steps = g.steps; sg.rounds = g.rounds; sg.G = g.G;
     sg.epoch = c->epoch;
     const uint32_t threads = g.waves * kWave;
+    const bool few_rows = g.n_chunks <= kRowGroups;          // the matrix rows are the row groups
+    CutArgs ca;
+    ca.groups = few_rows ? c->matrix : c->partial; ca.n_groups = few_rows ? g.n_chunks : kRowGroups;
+    ca.G = g.G; ca.g_end0 = g.g_end0; ca.F = c->F; ca.flags = c->flags; ca.offsets = c->offsets;
+    ca.hdr_dev = c->hdr_dev; ca.hdr_host = c->hdr_host;
+    EmitArgs ea;
+    ea.page_table = c->page_table; ea.nu = c->nu; ea.matrix = c->matrix; ea.offsets = c->offsets; ea.hdr = c->hdr_dev;
+    ea.fetch_pages = c->fetch_pages; ea.evict_pages = c->evict_pages; ea.evict_frames = c->evict_frames;
+    const size_t cut_lds = (size_t)(g.n_keys + g.G + 1) * 4, emit_lds = (size_t)(g.waves + 1) * g.n_keys * 4;
+    if (g.single) {
+        k_tail<<<1, threads, std::max(cut_lds, emit_lds), st>>>(sg, ca, ea, c->fetch_frames);
+        if (c->profiling) CK(hipEventRecord(c->ev[4], st));
+        return hipGetLastError();
+    }
     k_count<<<g.n_chunks, threads, (size_t)g.n_keys * 4, st>>>(c->page_table, c->nu, sg, c->matrix);
     if (prof) CK(hipEventRecord(c->ev[2], st));
     const dim3 cgrid((g.n_keys + 63) / 64, kRowGroups / 4), cblock(64, 4);
-    const bool few_rows = g.n_chunks <= kRowGroups;          // the matrix rows are the row groups
     if (!few_rows) k_colsum<<<cgrid, cblock, 0, st>>>(c->matrix, g.n_chunks, g.n_keys, c->partial);
-    k_cut<<<1, 1024, (size_t)(g.n_keys + g.G + 1) * 4, st>>>(few_rows ? c->matrix : c->partial,
-                                                              few_rows ? g.n_chunks : kRowGroups, g.G, g.g_end0, c->F,
-                                                              c->flags, c->offsets, c->hdr_dev, c->hdr_host);
+    k_cut<<<1, 1024, cut_lds, st>>>(ca);
     if (!few_rows) k_offsets<<<cgrid, cblock, 0, st>>>(c->matrix, g.n_chunks, g.n_keys, c->partial, c->hdr_dev);
     if (prof) CK(hipEventRecord(c->ev[3], st));
-    k_emit<<<g.n_chunks, threads, (size_t)(g.waves + 1) * g.n_keys * 4, st>>>(
-        c->page_table, c->nu, sg, c->matrix, c->offsets, c->hdr_dev, c->fetch_pages, c->evict_pages, c->evict_frames);
+    k_emit<<<g.n_chunks, threads, emit_lds, st>>>(ea, sg);
     const uint32_t fblocks = (uint32_t)std::min<uint64_t>(2048, ((uint64_t)c->F + 255) / 256);
     k_frames<<<fblocks, 256, 0, st>>>(c->hdr_dev, c->evict_frames, c->fetch_frames);
     if (c->profiling) CK(hipEventRecord(c->ev[4], st));

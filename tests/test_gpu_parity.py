@@ -68,6 +68,13 @@ def test_next_use_epoch_wraps_cleanly(oracle_mod, monkeypatch):
     assert lockstep(oracle_mod, make_trace(1, seed=4), with_bytes=True) >= 20
 
 
+def test_small_tables_also_pass_through_the_multi_kernel_path(oracle_mod, monkeypatch):
+    # page tables of up to 32 Ki pages normally take the fused single-workgroup kernel
+    monkeypatch.setenv("MSCHED_FORCE_MULTI_KERNEL", "1")
+    assert lockstep(oracle_mod, make_trace(1, seed=2), with_bytes=True) >= 20
+    assert lockstep(oracle_mod, make_trace(4, page_shift=12, layers=8, steps=16), with_bytes=True, bytes_every=3) >= 8
+
+
 def test_errors_and_edge_cases(oracle_mod):
     from paper_2512_24637_amd import MSchedError
     trace = explicit_trace([[[0, 1, 2, 3], [4]], [[5]]], 8, 3, timeslice=1, page_shift=6)
