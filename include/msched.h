@@ -165,7 +165,8 @@ int msched_state_copy(msched_ctx *ctx, uint32_t *page_table, uint32_t *frame_own
 
 /*
  * Per-phase device times of the last plan and the last migrate, measured with HIP events on the
- * context's stream when profiling is on.  ms: HOST array of MSCHED_N_PHASES floats.
+ * context's stream when profiling is on, and the host-clock split of the last msched_plan call (always
+ * measured).  ms: HOST array of MSCHED_N_PHASES floats, all in milliseconds.
  */
 enum { MSCHED_PHASE_EXPAND = 0,   /* next-use reset + template expansion + scatter-min */
        MSCHED_PHASE_COUNT = 1,    /* per-chunk class histograms over the page table */
@@ -173,7 +174,10 @@ enum { MSCHED_PHASE_EXPAND = 0,   /* next-use reset + template expansion + scatt
        MSCHED_PHASE_EMIT = 3,     /* ordered compaction of both lists + frame assignment */
        MSCHED_PHASE_MIGRATE = 4,  /* copy kernel + page-table update */
        MSCHED_PHASE_PLAN = 5,     /* all planning kernels of one msched_plan, first launch to last */
-       MSCHED_N_PHASES = 6 };
+       MSCHED_HOST_PREP = 6,      /* host clock: timeline flatten + repeat detection of the last plan */
+       MSCHED_HOST_LAUNCH = 7,    /* host clock: issuing the plan's kernel launches */
+       MSCHED_HOST_WAIT = 8,      /* host clock: waiting for the plan's kernels and reading the counts */
+       MSCHED_N_PHASES = 9 };
 /* level 0: off; 1: time each plan as a whole and each migrate (two events per call); 2: also time the
  * four planning phases separately (the extra events between kernels add a few microseconds each). */
 int msched_set_profiling(msched_ctx *ctx, int level);

@@ -10,7 +10,7 @@ import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 NOT_RESIDENT = 0xFFFFFFFF
-PHASES = ("expand", "count", "cut", "emit", "migrate", "plan")
+PHASES = ("expand", "count", "cut", "emit", "migrate", "plan", "host_prep", "host_launch", "host_wait")
 EXPORTED_SYMBOLS = (
     "msched_create", "msched_destroy", "msched_kernel_register", "msched_task_create",
     "msched_launch_enqueue", "msched_launch_retire", "msched_plan", "msched_migrate",

@@ -1,6 +1,7 @@
 // C-ABI entry points of libmsched: context, template registry, per-task command queues,
 // timeline flattening, and the calls that drive the planning and migration kernels.
 #include <algorithm>
+#include <chrono>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -64,6 +65,52 @@ int validate_launch(const msched_ctx *c, const DevKernel &k, const uint64_t *arg
     return MSCHED_OK;
 }
 
+// A later command whose rule describes exactly the region an earlier command of this plan already
+// described cannot lower any page's first use, so its expansion is skipped.  Iterative workloads
+// launch the same kernels over the same buffers again and again (the paper finds 77 % of accesses
+// fixed-size, Sec. 5.2), which makes most rules of a timeline repeats.  The test is exact: regions are
+// compared as full tuples (page range for fixed/linear rules, the four strided parameters, or the
+// id-list address and length), never by hash alone.
+struct RegionSig { uint64_t a, b, c, d; };
+
+inline bool region_signature(const msched_ctx *c, const msched_rule &q, const CmdRec &r, RegionSig &sig, bool &empty) {
+    empty = false;
+    if (q.kind == MSCHED_RULE_LIST) {
+        sig = {4, (uint64_t)(uintptr_t)r.ids, r.n_ids, 0};
+        empty = r.n_ids == 0;
+        return true;
+    }
+    auto eval = [&](uint64_t coeff, const uint8_t *idx, int n) {
+        uint64_t v = coeff;
+        for (int j = 0; j < n; ++j) v *= r.args[idx[j]];      // validated at enqueue: cannot overflow
+        return v;
+    };
+    const uint64_t base = r.args[q.base_arg];
+    const uint64_t size = q.kind == MSCHED_RULE_FIXED ? q.size_coeff : eval(q.size_coeff, q.size_args, q.n_size_args);
+    if (q.kind != MSCHED_RULE_STRIDED) {
+        if (size == 0) { empty = true; return true; }
+        sig = {1, base >> c->page_shift, (base + size - 1) >> c->page_shift, 0};
+        return true;
+    }
+    const uint64_t stride = eval(q.stride_coeff, q.stride_args, q.n_stride_args);
+    const uint64_t count = eval(q.count_coeff, q.count_args, q.n_count_args);
+    if (size == 0 || count == 0) { empty = true; return true; }
+    sig = {base, size, stride, count ^ (3ull << 62)};
+    return true;
+}
+
+// Insert sig into the per-plan table; returns true when it was already there.
+inline bool seen_before(msched_ctx *c, const RegionSig &sig, size_t mask) {
+    uint64_t h = sig.a * 0x9E3779B97F4A7C15ull ^ (sig.b + 0x7F4A7C15ull) * 0xC2B2AE3D27D4EB4Full ^
+                 (sig.c * 0x165667B19E3779F9ull) ^ (sig.d * 0x27D4EB2F165667C5ull);
+    h ^= h >> 29;
+    for (size_t i = h & mask;; i = (i + 1) & mask) {
+        msched_ctx::SeenEntry &e = c->seen[i];
+        if (e.stamp != c->plan_seq + 1) { e = {sig.a, sig.b, sig.c, sig.d, c->plan_seq + 1}; return false; }
+        if (e.a == sig.a && e.b == sig.b && e.c == sig.c && e.d == sig.d) return true;
+    }
+}
+
 void free_ctx(msched_ctx *c) {
     if (!c) return;
     (void)hipStreamSynchronize(c->stream);
@@ -113,6 +160,10 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     c->migrate_max_blocks = (uint32_t)env_u32("MSCHED_MIGRATE_BLOCKS", 1, 1 << 20, 4096);
     c->expand_split = (uint32_t)env_u32("MSCHED_EXPAND_SPLIT", 1, 64, 0);
     c->max_chunks = (uint32_t)env_u32("MSCHED_MAX_CHUNKS", 1, kMaxChunks, kMaxChunks);
+    c->stage_threshold = (uint32_t)env_u32("MSCHED_STAGE_THRESHOLD", 0, 1 << 30, 2048);
+    c->dedupe_regions = env_u32("MSCHED_DEDUPE_REGIONS", 0, 1, 1) != 0;
+    c->seen.assign(131072, msched_ctx::SeenEntry{0, 0, 0, 0, 0});     // >= 4 x MAX_TIMELINE_COMMANDS x MAX_RULES
+    c->plan_recs.resize(MSCHED_MAX_TIMELINE_COMMANDS + 1);
     c->force_multi_kernel = env_u32("MSCHED_FORCE_MULTI_KERNEL", 0, 1, 0) != 0;
     c->list_b0 = (uint32_t)env_u32("MSCHED_LIST_B0", 0, 4096, 4);
     c->list_b1 = std::max(c->list_b0, (uint32_t)env_u32("MSCHED_LIST_B1", 0, 4096, 32));
@@ -246,6 +297,8 @@ int msched_plan(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entri
     if (!c || !out || (n_entries && !tl) || n_entries > MSCHED_MAX_TIMELINE_ENTRIES) return MSCHED_E_INVAL;
     for (uint32_t e = 0; e < n_entries; ++e) if (tl[e].task >= c->tasks.size()) return MSCHED_E_INVAL;
     c->pending_plan = 0;
+    using clk = std::chrono::steady_clock;
+    const clk::time_point t_start = clk::now();
 
     // Flatten the timeline into the order of future commands (Sec. 6.1: the timeline says which
     // task runs, for how long and in what order; Sec. 6.2: each queue holds command latencies).
@@ -260,11 +313,33 @@ int msched_plan(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entri
         uint64_t elapsed = 0;
         while (p < t.n && elapsed < tl[e].timeslice) {
             if (G == MSCHED_MAX_TIMELINE_COMMANDS) return MSCHED_E_INVAL;
+            c->plan_recs[G] = &t.recs[p - t.base];
             c->cmd_ptrs_host[G++] = t.recs_dev + (p - t.base);
             elapsed += t.recs[p - t.base].latency;
             ++p;
         }
         if (e == 0) g_end0 = G;
+    }
+    if (c->dedupe_regions && G > 1) {
+        // bit r of a command's skip mask: rule r repeats a region an earlier command already brought
+        // in.  The mask rides in the top byte of the record's address (addresses use 48 bits).  The
+        // table is sized to this plan so that it stays in the host's cache.
+        size_t cap = 64;
+        while (cap < (size_t)4 * G * std::max<uint32_t>(1, c->max_rules)) cap <<= 1;
+        cap = std::min(cap, c->seen.size());
+        for (uint32_t g = 0; g < G; ++g) {
+            const CmdRec &rec = *c->plan_recs[g];
+            const DevKernel &k = c->kernels[rec.kernel];
+            uint64_t skip = 0;
+            for (uint32_t r = 0; r < k.n_rules; ++r) {
+                RegionSig sig;
+                bool empty;
+                region_signature(c, k.rules[r], rec, sig, empty);
+                if (empty || seen_before(c, sig, cap - 1)) skip |= 1ull << r;
+            }
+            c->cmd_ptrs_host[g] = reinterpret_cast<const CmdRec *>(
+                reinterpret_cast<uintptr_t>(c->cmd_ptrs_host[g]) | (skip << 56));
+        }
     }
     memset(out, 0, sizeof *out);
     out->g_end0 = g_end0;
@@ -299,9 +374,15 @@ int msched_plan(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entri
             HIP_TRY(c, hipMalloc((void **)&c->partial, pneed * 4));
             c->partial_cap = pneed;
         }
+        const clk::time_point t_prep = clk::now();
         HIP_TRY(c, launch_plan(c, g));
+        const clk::time_point t_launch = clk::now();
         HIP_TRY(c, hipStreamSynchronize(c->stream));
         h = *c->hdr_host;
+        const clk::time_point t_done = clk::now();
+        c->phase_ms[MSCHED_HOST_PREP] = std::chrono::duration<float, std::milli>(t_prep - t_start).count();
+        c->phase_ms[MSCHED_HOST_LAUNCH] = std::chrono::duration<float, std::milli>(t_launch - t_prep).count();
+        c->phase_ms[MSCHED_HOST_WAIT] = std::chrono::duration<float, std::milli>(t_done - t_launch).count();
         if (c->profiling) HIP_TRY(c, hipEventElapsedTime(&c->phase_ms[MSCHED_PHASE_PLAN], c->ev[0], c->ev[4]));
         if (c->profiling >= 2)
             for (int i = 0; i < 4; ++i) HIP_TRY(c, hipEventElapsedTime(&c->phase_ms[i], c->ev[i], c->ev[i + 1]));

@@ -13,11 +13,12 @@ constexpr uint32_t kNone = 0xFFFFFFFFu;         // not resident / free frame / n
 constexpr uint32_t kSkip = 0x80000000u;         // output offset of a class that is not emitted
 constexpr int kWave = 64;                       // CDNA wavefront
 constexpr uint32_t kMaxChunks = 2048;           // page-table chunks (one workgroup each)
-constexpr uint32_t kSingleChunkPages = 32768;   // page tables up to this size are swept by one workgroup
+constexpr uint32_t kSingleChunkPages = 8192;    // page tables up to this size are swept by one workgroup (one tile)
 constexpr int kMaxWaves = 8;                    // wavefronts per sweep workgroup
 constexpr int kMaxSteps = 16;                   // 64-page steps a wavefront keeps in registers per tile
 constexpr uint32_t kNuShift = 12;               // nu entry = (epoch << kNuShift) | (kNuMask - g)
 constexpr uint32_t kNuMask = (1u << kNuShift) - 1;
+constexpr uint64_t kPtrMask = (1ull << 56) - 1; // record address without the skip mask in its top byte
 constexpr uint32_t kMaxEpoch = (1u << (32 - kNuShift)) - 1;
 static_assert(MSCHED_MAX_TIMELINE_COMMANDS < kNuMask, "g must fit the next-use encoding");
 constexpr uint32_t kRowGroups = 32;             // row groups of the chunk x class count matrix
@@ -73,6 +74,11 @@ struct msched_ctx {
     uint32_t migrate_max_blocks = 4096;         // grid cap of the copy kernel
     uint32_t expand_split = 0;                  // workgroups per (command, rule); 0 = by page-table size
     uint32_t max_chunks = msched::kMaxChunks;   // page-table chunks (sweep workgroups) at most
+    uint32_t stage_threshold = 2048;            // expansion workgroups above which records are staged first
+    bool dedupe_regions = true;                 // skip rules that repeat a region seen earlier in the plan
+    struct SeenEntry { uint64_t a, b, c, d, stamp; };
+    std::vector<const msched::CmdRec *> plan_recs;   // host addresses of this plan's records, in g order
+    std::vector<SeenEntry> seen;                // open-addressing table of region signatures, stamped per plan
     bool force_multi_kernel = false;            // test hook: never use the fused single-workgroup tail
     bool has_list_rule = false;                 // some registered kernel has a LIST rule
     uint32_t list_b0 = 4, list_b1 = 32;         // id lists: commands [0,b0), [b0,b1), [b1,G) run as ordered batches

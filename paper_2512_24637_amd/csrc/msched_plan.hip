@@ -34,8 +34,11 @@ __global__ __launch_bounds__(256) void k_stage(const CmdRec *const *__restrict__
     const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
     const uint32_t g = t >> 3, part = t & 7;
     if (g >= G) return;
-    const uint4 *src = reinterpret_cast<const uint4 *>(cmd_ptrs[g]);
-    reinterpret_cast<uint4 *>(cmd_dev + g)[part] = src[part];
+    const uint64_t tagged = reinterpret_cast<uint64_t>(cmd_ptrs[g]);
+    const uint4 *src = reinterpret_cast<const uint4 *>(tagged & kPtrMask);
+    uint4 v = src[part];
+    if (part == 1) { v.z = (uint32_t)(tagged >> 56); v.w = 0; }       // CmdRec::reserved <- skip mask
+    reinterpret_cast<uint4 *>(cmd_dev + g)[part] = v;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -106,17 +109,28 @@ __device__ __forceinline__ uint64_t formula(const uint64_t *args, uint64_t coeff
     return v;
 }
 
+// The command record of position g into LDS: from the staged copy, or through the pinned table
+// (whose entries carry the skip mask in their top byte).
+__device__ __forceinline__ void load_record(const ExpandArgs &a, uint32_t g, uint64_t *s_rec) {
+    if (threadIdx.x < sizeof(CmdRec) / 8) {
+        if (a.cmds) {
+            s_rec[threadIdx.x] = reinterpret_cast<const uint64_t *>(a.cmds + g)[threadIdx.x];
+        } else {
+            const uint64_t tagged = reinterpret_cast<uint64_t>(a.cmd_ptrs[g]);
+            const uint64_t v = reinterpret_cast<const uint64_t *>(tagged & kPtrMask)[threadIdx.x];
+            s_rec[threadIdx.x] = (threadIdx.x == 3) ? (tagged >> 56) : v;     // word 3 = CmdRec::reserved
+        }
+    }
+    __syncthreads();
+}
+
 __global__ __launch_bounds__(256) void k_expand(ExpandArgs a) {
     const uint32_t g = blockIdx.x, r = blockIdx.y;
     __shared__ uint64_t s_rec[sizeof(CmdRec) / 8];
-    if (threadIdx.x < sizeof(CmdRec) / 8) {
-        const CmdRec *src = a.cmds ? a.cmds + g : a.cmd_ptrs[g];
-        s_rec[threadIdx.x] = reinterpret_cast<const uint64_t *>(src)[threadIdx.x];
-    }
-    __syncthreads();
+    load_record(a, g, s_rec);
     const CmdRec *rec = reinterpret_cast<const CmdRec *>(s_rec);
     const DevKernel &k = a.kernels[rec->kernel];
-    if (r >= k.n_rules) return;
+    if (r >= k.n_rules || ((rec->reserved >> r) & 1)) return;
     const msched_rule q = k.rules[r];
     const uint32_t sh = a.page_shift;
     const uint32_t enc = a.epoch_base | (kNuMask - g);
@@ -165,17 +179,14 @@ __global__ __launch_bounds__(kListThreads) void k_expand_list(ExpandArgs a, uint
     const uint32_t g = g0 + blockIdx.x / n_split, split = blockIdx.x % n_split;
     __shared__ uint64_t s_rec[sizeof(CmdRec) / 8];
     __shared__ uint32_t seen[1u << kListSeenBits];
-    if (threadIdx.x < sizeof(CmdRec) / 8) {
-        const CmdRec *src = a.cmds ? a.cmds + g : a.cmd_ptrs[g];
-        s_rec[threadIdx.x] = reinterpret_cast<const uint64_t *>(src)[threadIdx.x];
-    }
-    __syncthreads();
+    load_record(a, g, s_rec);
     const CmdRec *rec = reinterpret_cast<const CmdRec *>(s_rec);
     const uint32_t n = rec->n_ids;
     if (n == 0) return;
     const DevKernel &k = a.kernels[rec->kernel];
     bool has_list = false;
-    for (uint32_t r = 0; r < k.n_rules; ++r) has_list |= k.rules[r].kind == MSCHED_RULE_LIST;
+    for (uint32_t r = 0; r < k.n_rules; ++r)
+        has_list |= k.rules[r].kind == MSCHED_RULE_LIST && !((rec->reserved >> r) & 1);
     if (!has_list) return;
     for (uint32_t i = threadIdx.x; i < (1u << seen_bits); i += blockDim.x) seen[i] = kNone;
     __syncthreads();
@@ -612,7 +623,7 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         a.n_split = c->expand_split ? c->expand_split : ((c->V > (1u << 20)) ? 8 : 1);
         a.epoch_base = c->epoch << kNuShift;
         // few expansion workgroups: each reads its record over the link itself; many: stage once
-        const bool stage = (uint64_t)g.G * c->max_rules * a.n_split > 2048 || c->has_list_rule;
+        const bool stage = (uint64_t)g.G * c->max_rules * a.n_split > c->stage_threshold || c->has_list_rule;
         a.cmds = stage ? c->cmd_dev : nullptr;
         if (stage) k_stage<<<(g.G * 8 + 255) / 256, 256, 0, st>>>(c->cmd_ptrs_dev, g.G, c->cmd_dev);
         // Id lists go first in three stream-ordered batches of growing size: the smallest g wins a page,

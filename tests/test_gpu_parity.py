@@ -69,7 +69,7 @@ def test_next_use_epoch_wraps_cleanly(oracle_mod, monkeypatch):
 
 
 def test_small_tables_also_pass_through_the_multi_kernel_path(oracle_mod, monkeypatch):
-    # page tables of up to 32 Ki pages normally take the fused single-workgroup kernel
+    # page tables of up to 8 Ki pages normally take the fused single-workgroup kernel
     monkeypatch.setenv("MSCHED_FORCE_MULTI_KERNEL", "1")
     assert lockstep(oracle_mod, make_trace(1, seed=2), with_bytes=True) >= 20
     assert lockstep(oracle_mod, make_trace(4, page_shift=12, layers=8, steps=16), with_bytes=True, bytes_every=3) >= 8
