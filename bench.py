@@ -275,7 +275,7 @@ def main():
                     help="workload (default 2 = the configuration the metric is quoted on)")
     ap.add_argument("--no-plan-stress", action="store_true", help="skip the planning-stress leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-steps", type=int, default=80)
+    ap.add_argument("--cpu-sample-steps", type=int, default=480)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (a context is per GPU: N GPUs would be "
@@ -332,7 +332,10 @@ def main():
         "plan_latency_us": {"host_wall_mean": float(np.mean(r["plan_wall_s"])) * 1e6,
                             "host_wall_p50": float(np.median(r["plan_wall_s"])) * 1e6,
                             "host_wall_max": float(np.max(r["plan_wall_s"])) * 1e6,
-                            "device_mean": float(np.mean(plan_dev)) * 1e3},
+                            "device_mean": float(np.mean(plan_dev)) * 1e3,
+                            "host_flatten_mean": float(np.mean([ph["host_prep"] for ph in r["phases"]])) * 1e3,
+                            "host_launch_mean": float(np.mean([ph["host_launch"] for ph in r["phases"]])) * 1e3,
+                            "host_wait_mean": float(np.mean([ph["host_wait"] for ph in r["phases"]])) * 1e3},
         "roofline": {"bound": "host-link", "achieved": achieved, "peak": peak, "unit": "GB/s",
                      "frac": (achieved / peak) if peak else None,
                      "traffic": (MIGRATE_TRAFFIC_RATIO["read"] * moved / n_copy) if n_copy else None,
@@ -350,7 +353,8 @@ def main():
         result["roofline_plan"] = bench_planning_stress(torch)
     if not args.no_cpu_baseline:
         if args.config == 2:
-            result["cpu_baseline"] = cpu_baseline(trace_args, args.cpu_sample_steps)
+            cpu_args = dict(config=2, n_launches=max(500, 25 * (-(-args.cpu_sample_steps // 4))))
+            result["cpu_baseline"] = cpu_baseline(cpu_args, args.cpu_sample_steps)
             result["miss_volume"] = miss_volume(dict(config=2))
         else:
             result["cpu_baseline"] = None      # the oracle leg is sized for the default workload only
