@@ -117,7 +117,7 @@ void free_ctx(msched_ctx *c) {
     for (auto &t : c->tasks) if (t.recs) (void)hipHostFree(t.recs);
     void *dev[] = {c->page_table, c->frame_owner, c->nu, c->slot, c->evict_pages, c->evict_frames, c->fetch_pages,
                    c->fetch_frames, c->flags, c->matrix, c->partial, c->offsets, c->hdr_dev, c->kernels_dev,
-                   c->query_buf, c->cmd_dev};
+                   c->query_buf, c->cmd_dev, c->list_bucket_fill, c->list_pairs};
     for (void *p : dev) if (p) (void)hipFree(p);
     if (c->hdr_host) (void)hipHostFree(c->hdr_host);
     if (c->cmd_ptrs_host) (void)hipHostFree((void *)c->cmd_ptrs_host);
@@ -165,6 +165,7 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     c->seen.assign(131072, msched_ctx::SeenEntry{0, 0, 0, 0, 0});     // >= 4 x MAX_TIMELINE_COMMANDS x MAX_RULES
     c->plan_recs.resize(MSCHED_MAX_TIMELINE_COMMANDS + 1);
     c->force_multi_kernel = env_u32("MSCHED_FORCE_MULTI_KERNEL", 0, 1, 0) != 0;
+    c->list_binned_min_ids = (uint64_t)env_u32("MSCHED_LIST_BINNED_MIN_IDS", 0, 1 << 30, 262144);
     c->list_b0 = (uint32_t)env_u32("MSCHED_LIST_B0", 0, 4096, 4);
     c->list_b1 = std::max(c->list_b0, (uint32_t)env_u32("MSCHED_LIST_B1", 0, 4096, 32));
     c->list_overlap = env_u32("MSCHED_LIST_OVERLAP", 0, 1, 0);
@@ -353,6 +354,35 @@ int msched_plan(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entri
         PlanGeom g;
         plan_geometry(c, G, g);
         g.g_end0 = g_end0;
+        // Id lists: how many ids does this plan carry (repeated lists excluded)?  Many -> bucket path.
+        g.list_binned = false;
+        g.n_buckets = (uint32_t)((c->V + (1u << 13) - 1) >> 13);           // buckets of 8 Ki pages
+        if (c->has_list_rule && g.n_buckets <= kMaxBuckets) {
+            uint64_t total = 0;
+            for (uint32_t gi = 0; gi < G; ++gi) {
+                const CmdRec &rec = *c->plan_recs[gi];
+                const DevKernel &k = c->kernels[rec.kernel];
+                const uint64_t skip = reinterpret_cast<uintptr_t>(c->cmd_ptrs_host[gi]) >> 56;
+                bool live = false;
+                for (uint32_t r = 0; r < k.n_rules; ++r)
+                    live |= k.rules[r].kind == MSCHED_RULE_LIST && !((skip >> r) & 1);
+                if (live) total += rec.n_ids;
+            }
+            if (total >= c->list_binned_min_ids && total < (1ull << 31)) {
+                g.list_binned = true;
+                // room per sub-segment (8 per bucket): four times the average, at least 256 pairs
+                g.bucket_cap = (uint32_t)std::max<uint64_t>(256, 4 * total / ((uint64_t)g.n_buckets * 8) + 1);
+                const size_t need = (size_t)g.n_buckets * 8 * g.bucket_cap;
+                if (!c->list_bucket_fill) HIP_TRY(c, hipMalloc((void **)&c->list_bucket_fill, 4 * kMaxBuckets * 8));
+                if (need > c->list_cap) {
+                    HIP_TRY(c, hipStreamSynchronize(c->stream));
+                    if (c->list_pairs) HIP_TRY(c, hipFree(c->list_pairs));
+                    c->list_pairs = nullptr; c->list_cap = 0;
+                    HIP_TRY(c, hipMalloc((void **)&c->list_pairs, (need + need / 4) * 4));
+                    c->list_cap = need + need / 4;
+                }
+            }
+        }
         if (c->epoch == kMaxEpoch) {                 // the epoch field is about to wrap: start over
             HIP_TRY(c, launch_nu_reset(c));
             c->epoch = 0;

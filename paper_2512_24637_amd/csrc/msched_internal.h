@@ -14,6 +14,7 @@ constexpr uint32_t kSkip = 0x80000000u;         // output offset of a class that
 constexpr int kWave = 64;                       // CDNA wavefront
 constexpr uint32_t kMaxChunks = 2048;           // page-table chunks (one workgroup each)
 constexpr uint32_t kSingleChunkPages = 8192;    // page tables up to this size are swept by one workgroup (one tile)
+constexpr uint32_t kMaxBuckets = 4096;          // binned id lists: buckets of 32 Ki pages, counters in LDS
 constexpr int kMaxWaves = 8;                    // wavefronts per sweep workgroup
 constexpr int kMaxSteps = 16;                   // 64-page steps a wavefront keeps in registers per tile
 constexpr uint32_t kNuShift = 12;               // nu entry = (epoch << kNuShift) | (kNuMask - g)
@@ -60,6 +61,8 @@ struct PlanGeom {
     uint32_t G, g_end0, n_chunks, chunk_pages, n_keys;   // n_keys = 2 * (G + 1)
     uint32_t waves, steps, rounds;                       // sweep workgroup shape
     bool single;                                         // one workgroup sweeps the whole table (fused tail kernel)
+    bool list_binned;                                    // id lists go through the bucket path
+    uint32_t n_buckets, bucket_cap;                      // bucket_cap: pairs per sub-segment
 };
 
 }  // namespace msched
@@ -81,6 +84,10 @@ struct msched_ctx {
     std::vector<SeenEntry> seen;                // open-addressing table of region signatures, stamped per plan
     bool force_multi_kernel = false;            // test hook: never use the fused single-workgroup tail
     bool has_list_rule = false;                 // some registered kernel has a LIST rule
+    // binned id lists (allocated on first use)
+    uint32_t *list_bucket_fill = nullptr;       // [kMaxBuckets][8]
+    uint32_t *list_pairs = nullptr; size_t list_cap = 0;   // n_buckets x 8 x bucket_cap
+    uint64_t list_binned_min_ids = 262144;      // plans with at least this many ids take the bucket path
     uint32_t list_b0 = 4, list_b1 = 32;         // id lists: commands [0,b0), [b0,b1), [b1,G) run as ordered batches
     int list_overlap = 0;                       // last batch on the side stream, beside the range expansion (measured slower)
     hipStream_t side = nullptr;                 // library-owned, default priority

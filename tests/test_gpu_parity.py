@@ -75,6 +75,16 @@ def test_small_tables_also_pass_through_the_multi_kernel_path(oracle_mod, monkey
     assert lockstep(oracle_mod, make_trace(4, page_shift=12, layers=8, steps=16), with_bytes=True, bytes_every=3) >= 8
 
 
+def test_id_lists_through_the_bucket_path(oracle_mod, monkeypatch):
+    # plans with many ids bin them by page bucket instead of scattering atomics; force it for small lists
+    monkeypatch.setenv("MSCHED_LIST_BINNED_MIN_IDS", "0")
+    trace = make_trace(5, scale=64, n_launches=100)
+    assert lockstep(oracle_mod, trace, with_bytes=True, bytes_every=4) >= 16
+    rng = np.random.default_rng(77)
+    trace = _random_rule_trace(rng, page_shift=8, V=70000, n_frames=9000, n_tasks=3, n_cmds=24, with_lists=True)
+    assert lockstep(oracle_mod, trace, with_bytes=True, bytes_every=6) >= 8
+
+
 def test_errors_and_edge_cases(oracle_mod):
     from paper_2512_24637_amd import MSchedError
     trace = explicit_trace([[[0, 1, 2, 3], [4]], [[5]]], 8, 3, timeslice=1, page_shift=6)
