@@ -184,6 +184,9 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     ALLOC(c->flags, 256);
     ALLOC(c->offsets, (size_t)2 * (MSCHED_MAX_TIMELINE_COMMANDS + 1) * 4);
     ALLOC(c->hdr_dev, sizeof(PlanHeader));
+    // row-group sums of the count matrix: the counting sweep adds into them, k_offsets clears what it read
+    ALLOC(c->partial, (size_t)kRowGroups * 2 * (MSCHED_MAX_TIMELINE_COMMANDS + 1) * 4);
+    if (rc == MSCHED_OK && (e = hipMemset(c->partial, 0, (size_t)kRowGroups * 2 * (MSCHED_MAX_TIMELINE_COMMANDS + 1) * 4)) != hipSuccess) fail(e);
     ALLOC(c->cmd_dev, sizeof(CmdRec) * (MSCHED_MAX_TIMELINE_COMMANDS + 1));
     if (cfg->host_slot) {
         ALLOC(c->slot, c->V * 4);
@@ -395,14 +398,6 @@ int msched_plan(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entri
             c->matrix = nullptr; c->matrix_cap = 0;
             HIP_TRY(c, hipMalloc((void **)&c->matrix, need * 4));
             c->matrix_cap = need;
-        }
-        const size_t pneed = (size_t)kRowGroups * g.n_keys;
-        if (pneed > c->partial_cap) {
-            HIP_TRY(c, hipStreamSynchronize(c->stream));
-            if (c->partial) HIP_TRY(c, hipFree(c->partial));
-            c->partial = nullptr; c->partial_cap = 0;
-            HIP_TRY(c, hipMalloc((void **)&c->partial, pneed * 4));
-            c->partial_cap = pneed;
         }
         const clk::time_point t_prep = clk::now();
         HIP_TRY(c, launch_plan(c, g));

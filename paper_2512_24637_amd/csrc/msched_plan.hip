@@ -452,7 +452,8 @@ __device__ __forceinline__ void rank_tile(const SweepGeom &sg, uint32_t *hist, c
 // First sweep: pages per key in one chunk -> one matrix row.  Counting needs no order, so all
 // wavefronts of the workgroup add into one LDS histogram.
 __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_table, const uint32_t *__restrict__ nu,
-                                           const SweepGeom &sg, uint32_t chunk, uint32_t *lds, uint32_t *row) {
+                                           const SweepGeom &sg, uint32_t chunk, uint32_t *lds, uint32_t *row,
+                                           uint32_t *group_row) {
     const uint32_t n_keys = 2 * (sg.G + 1);
     const uint32_t waves = blockDim.x / kWave, wave = threadIdx.x / kWave;
     for (uint32_t i = threadIdx.x; i < n_keys; i += blockDim.x) lds[i] = 0;
@@ -466,29 +467,22 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
         count_tile(sg, lds, key);
     }
     __syncthreads();
-    for (uint32_t k = threadIdx.x; k < n_keys; k += blockDim.x) row[k] = lds[k];
+    for (uint32_t k = threadIdx.x; k < n_keys; k += blockDim.x) {
+        const uint32_t v = lds[k];
+        row[k] = v;
+        if (group_row != nullptr && v) atomicAdd(&group_row[k], v);     // column sums by row group, few keys are non-zero
+    }
 }
 
 __global__ __launch_bounds__(kWave * kMaxWaves) void k_count(const uint32_t *__restrict__ page_table,
                                                               const uint32_t *__restrict__ nu, SweepGeom sg,
-                                                              uint32_t *__restrict__ matrix) {
+                                                              uint32_t *__restrict__ matrix,
+                                                              uint32_t *__restrict__ partial) {
     extern __shared__ uint32_t lds[];
-    const uint32_t chunk = chunk_of_block(blockIdx.x, gridDim.x);
-    count_body(page_table, nu, sg, chunk, lds, matrix + (size_t)chunk * 2 * (sg.G + 1));
-}
-
-// Column sums of the count matrix, by row group.
-__global__ __launch_bounds__(256) void k_colsum(const uint32_t *__restrict__ matrix, uint32_t n_chunks,
-                                                uint32_t n_keys, uint32_t *__restrict__ partial) {
-    const uint32_t key = blockIdx.x * 64 + threadIdx.x;
-    const uint32_t rg = blockIdx.y * 4 + threadIdx.y;
-    if (key >= n_keys) return;
-    const uint32_t rows = (n_chunks + kRowGroups - 1) / kRowGroups;
-    const uint32_t w0 = rg * rows, w1 = min(n_chunks, w0 + rows);
-    uint32_t s = 0;
-#pragma unroll 8
-    for (uint32_t w = w0; w < w1; ++w) s += matrix[(size_t)w * n_keys + key];
-    partial[rg * n_keys + key] = s;
+    const uint32_t chunk = chunk_of_block(blockIdx.x, gridDim.x), n_keys = 2 * (sg.G + 1);
+    const uint32_t rows = (gridDim.x + kRowGroups - 1) / kRowGroups;      // chunks per row group
+    count_body(page_table, nu, sg, chunk, lds, matrix + (size_t)chunk * n_keys,
+               partial ? partial + (size_t)(chunk / rows) * n_keys : nullptr);
 }
 
 // In-place exclusive scan of a[0..n) in LDS by the whole block (a multiple of 64 threads, at most
@@ -597,17 +591,19 @@ __global__ __launch_bounds__(1024) void k_cut(CutArgs a) {
     cut_body(a, lds);
 }
 
-// matrix[w][key] = pages of that key in chunks before w (exclusive prefix down each column).
+// matrix[w][key] = pages of that key in chunks before w (exclusive prefix down each column).  The
+// row-group sums are consumed here and cleared for the next plan's counting sweep to add into.
 __global__ __launch_bounds__(256) void k_offsets(uint32_t *__restrict__ matrix, uint32_t n_chunks, uint32_t n_keys,
-                                                 const uint32_t *__restrict__ partial,
+                                                 uint32_t *__restrict__ partial,
                                                  const PlanHeader *__restrict__ hdr) {
-    if (hdr->n_fetch == 0) return;
     const uint32_t key = blockIdx.x * 64 + threadIdx.x;
     const uint32_t rg = blockIdx.y * 4 + threadIdx.y;
     if (key >= n_keys) return;
+    uint32_t run = partial[rg * n_keys + key];
+    partial[rg * n_keys + key] = 0;
+    if (hdr->n_fetch == 0) return;
     const uint32_t rows = (n_chunks + kRowGroups - 1) / kRowGroups;
     const uint32_t w0 = rg * rows, w1 = min(n_chunks, w0 + rows);
-    uint32_t run = partial[rg * n_keys + key];
 #pragma unroll 8
     for (uint32_t w = w0; w < w1; ++w) {
         const size_t i = (size_t)w * n_keys + key;
@@ -707,7 +703,7 @@ __global__ __launch_bounds__(256) void k_frames(const PlanHeader *__restrict__ h
 __global__ __launch_bounds__(kWave * kMaxWaves) void k_tail(SweepGeom sg, CutArgs ca, EmitArgs ea,
                                                              uint32_t *__restrict__ fetch_frames) {
     extern __shared__ uint32_t lds[];
-    count_body(ea.page_table, ea.nu, sg, 0, lds, ca.groups);
+    count_body(ea.page_table, ea.nu, sg, 0, lds, ca.groups, nullptr);
     __syncthreads();
     cut_body(ca, lds);
     __syncthreads();
@@ -825,11 +821,12 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         if (c->profiling) CK(hipEventRecord(c->ev[4], st));
         return hipGetLastError();
     }
-    k_count<<<g.n_chunks, threads, (size_t)g.n_keys * 4, st>>>(c->page_table, c->nu, sg, c->matrix);
+    k_count<<<g.n_chunks, threads, (size_t)g.n_keys * 4, st>>>(c->page_table, c->nu, sg, c->matrix,
+                                                                few_rows ? nullptr : c->partial);
     if (prof) CK(hipEventRecord(c->ev[2], st));
     const dim3 cgrid((g.n_keys + 63) / 64, kRowGroups / 4), cblock(64, 4);
-    if (!few_rows) k_colsum<<<cgrid, cblock, 0, st>>>(c->matrix, g.n_chunks, g.n_keys, c->partial);
-    k_cut<<<1, 1024, cut_lds, st>>>(ca);
+    const uint32_t cut_threads = std::min<uint32_t>(1024, std::max<uint32_t>(256, (g.n_keys / 2 + 63) / 64 * 64));
+    k_cut<<<1, cut_threads, cut_lds, st>>>(ca);
     if (!few_rows) k_offsets<<<cgrid, cblock, 0, st>>>(c->matrix, g.n_chunks, g.n_keys, c->partial, c->hdr_dev);
     if (prof) CK(hipEventRecord(c->ev[3], st));
     k_emit<<<g.n_chunks, threads, emit_lds, st>>>(ea, sg);
