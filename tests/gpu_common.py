@@ -12,7 +12,7 @@ NONE = 0xFFFFFFFF
 class GpuSide(DeviceBuffers):
     """Device buffers of a trace plus the MSched context that manages them."""
 
-    def __init__(self, trace):
+    def __init__(self, trace, preload=True):
         import torch
         from paper_2512_24637_amd import MSched
         super().__init__(trace)
@@ -20,7 +20,8 @@ class GpuSide(DeviceBuffers):
         self.ms = MSched(trace.page_shift, trace.n_virtual_pages, trace.n_frames, self.pool.data_ptr(),
                          self.host.data_ptr(), trace.n_slots, trace.host_slot,
                          stream=self.stream.cuda_stream, ids_pool_ptr=self.ids_ptr)
-        load_trace(self.ms, trace)
+        if preload:
+            load_trace(self.ms, trace)
 
     def close(self):
         self.torch.cuda.synchronize()
@@ -28,9 +29,10 @@ class GpuSide(DeviceBuffers):
         self.release()
 
 
-def make_oracle(oracle_mod, trace, with_bytes):
+def make_oracle(oracle_mod, trace, with_bytes, preload=True):
     o = oracle_mod.Oracle.for_trace(trace, with_bytes=with_bytes)
-    load_trace(o, trace)
+    if preload:
+        load_trace(o, trace)
     if with_bytes:
         wpp = trace.page_bytes // 8
         pages = (np.arange(trace.n_virtual_pages) if trace.host_slot is None
@@ -50,16 +52,22 @@ def assert_same_plan(po, pg, where):
             raise AssertionError((where, f, "first mismatch at", int(bad[0]), a[bad[:5]], b[bad[:5]]))
 
 
-def lockstep(oracle_mod, trace, with_bytes=True, horizon="round", max_plans=None, bytes_every=1, log=None):
+def lockstep(oracle_mod, trace, with_bytes=True, horizon="round", max_plans=None, bytes_every=1, log=None,
+             lazy_slices=None):
     """Run the oracle and the HIP path side by side and require identical plans, page
-    tables, frame owners and (with_bytes) pool and host-store bytes after every switch."""
-    g = GpuSide(trace)
-    o = make_oracle(oracle_mod, trace, with_bytes)
+    tables, frame owners and (with_bytes) pool and host-store bytes after every switch.
+    lazy_slices: enqueue launches only that many timeslices ahead of execution."""
+    from workloads.harness import LazyLoader
+    g = GpuSide(trace, preload=lazy_slices is None)
+    o = make_oracle(oracle_mod, trace, with_bytes, preload=lazy_slices is None)
+    lo = lg = None
+    if lazy_slices is not None:
+        lo, lg = LazyLoader(o, trace, lazy_slices), LazyLoader(g.ms, trace, lazy_slices)
     wpp = trace.page_bytes // 8
     n = 0
     try:
-        for ro, rg in zip(run_schedule(trace, o, horizon=horizon, max_plans=max_plans),
-                          run_schedule(trace, g.ms, horizon=horizon, max_plans=max_plans)):
+        for ro, rg in zip(run_schedule(trace, o, horizon=horizon, max_plans=max_plans, loader=lo),
+                          run_schedule(trace, g.ms, horizon=horizon, max_plans=max_plans, loader=lg)):
             where = (trace.name, "plan", ro.index, "task", ro.task)
             assert (ro.task, ro.first_launch, ro.timeline) == (rg.task, rg.first_launch, rg.timeline)
             assert_same_plan(ro.plan, rg.plan, where)

@@ -85,6 +85,14 @@ def test_id_lists_through_the_bucket_path(oracle_mod, monkeypatch):
     assert lockstep(oracle_mod, trace, with_bytes=True, bytes_every=6) >= 8
 
 
+def test_launches_arriving_between_switches(oracle_mod):
+    # launches are enqueued only two or three timeslices ahead, so queues grow while their heads retire
+    assert lockstep(oracle_mod, make_trace(1, seed=6, n_launches=900), with_bytes=True, bytes_every=7,
+                    lazy_slices=2) >= 90
+    assert lockstep(oracle_mod, make_trace(4, page_shift=12, layers=8, steps=40), with_bytes=True, bytes_every=5,
+                    lazy_slices=3) >= 20
+
+
 def test_errors_and_edge_cases(oracle_mod):
     from paper_2512_24637_amd import MSchedError
     trace = explicit_trace([[[0, 1, 2, 3], [4]], [[5]]], 8, 3, timeslice=1, page_shift=6)

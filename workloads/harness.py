@@ -74,20 +74,51 @@ def _timeline(trace: Trace, cursor: List[int], cur: int, first_ticks: int, horiz
     return entries
 
 
-def run_schedule(trace: Trace, impl, horizon: str = "round",
-                 max_plans: Optional[int] = None) -> Iterator[SwitchRecord]:
+class LazyLoader:
+    """Enqueues launches a bounded distance ahead of execution instead of all up front: new
+    commands keep arriving between context switches (training loops, decoding; Sec. 6.2 of the
+    paper on dynamically launched commands), and queues shrink and grow as launches retire."""
+
+    def __init__(self, impl, trace: Trace, ahead_slices: int = 3):
+        self.impl, self.trace = impl, trace
+        self.kid = [impl.kernel_register(rules) for rules in trace.kernels]
+        self.sent = [0] * trace.n_tasks
+        self.ahead = ahead_slices
+        for t in range(trace.n_tasks):
+            assert impl.task_create() == t
+
+    def top_up(self, cursor):
+        """Make sure every task has its next `ahead` timeslices queued."""
+        for t, cmds in enumerate(self.trace.tasks):
+            want = cursor[t]
+            for _ in range(self.ahead):
+                want += _slice_count(cmds.latency, want, self.trace.timeslice)
+            while self.sent[t] < want:
+                i = self.sent[t]
+                self.impl.launch_enqueue(t, self.kid[int(cmds.kernel_id[i])], cmds.args[i], int(cmds.n_args[i]),
+                                         int(cmds.latency[i]), int(cmds.ids_off[i]), int(cmds.n_ids[i]))
+                self.sent[t] += 1
+
+
+def run_schedule(trace: Trace, impl, horizon: str = "round", max_plans: Optional[int] = None,
+                 loader: Optional[LazyLoader] = None) -> Iterator[SwitchRecord]:
     """Drive `impl` through the trace.  Yields after each plan + migrate and
     before the covered launches are retired, so the caller can inspect state
-    at the moment those launches would start."""
+    at the moment those launches would start.  With a `loader`, launches are
+    enqueued only a few timeslices ahead (one round of look-ahead must fit)."""
     n = trace.n_tasks
     cursor = [0] * n
     cur, index = 0, 0
     while any(cursor[t] < len(trace.tasks[t]) for t in range(n)):
+        if loader is not None:
+            loader.top_up(cursor)
         if cursor[cur] >= len(trace.tasks[cur]):
             cur = (cur + 1) % n
             continue
         budget, replan = trace.timeslice, False
         while budget > 0 and cursor[cur] < len(trace.tasks[cur]):
+            if loader is not None:
+                loader.top_up(cursor)
             tl = _timeline(trace, cursor, cur, budget, horizon)
             plan = impl.plan(tl)
             impl.migrate()
