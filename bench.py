@@ -30,6 +30,9 @@ HBM_PEAK_GBS = 8000.0
 # move, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script calibrated against a 1 GiB device copy
 # (profiles/k_migrate_c2_stencil_pmc_traffic.md).
 MIGRATE_TRAFFIC_RATIO = {"read": 1.0001, "write": 1.0018}
+# Same for all planning kernels of one plan on the planning-stress structure: 307.1 MiB measured against
+# 251.8 MiB algorithmic (profiles/planning_c5_structure_kernels_and_traffic.md).
+PLAN_TRAFFIC_RATIO = 1.22
 WORKLOADS = {
     1: "c1-tiny-round-robin: 3 tasks, 64 KiB pages, pool 256 frames (16 MiB), footprint 24 MiB, timeslice 10 launches",
     2: "c2-stencil-sweep: 4 tasks x 3 arrays of 256 MiB, 2 MiB pages, pool 1024 frames (2 GiB), footprint 3 GiB "
@@ -231,7 +234,7 @@ def miss_volume(trace_args):
     return out
 
 
-def bench_planning_stress(torch, warmup=8, steps=16):
+def bench_planning_stress(torch, warmup=8, steps=16, phases=True):
     """c5 page structure (10 M pages, 4 M frames, 8 tasks, 2 dense ranges + 20 k Zipf ids per launch).
     Planning never reads page bytes, so pages are shrunk to 64 B to keep the backing store small."""
     from workloads import make_trace
@@ -248,7 +251,10 @@ def bench_planning_stress(torch, warmup=8, steps=16):
     bytes_ = [planning_bytes(trace, p, ids_per_plan, touch_est) for p in r["plans"]]
     ach = sum(bytes_) / (sum(dev_ms) / 1e3) / 1e9
     out = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-           "traffic": None, "workload": "c5-planning-stress page structure (V=10485760, F=4194304, G=400)",
+           "traffic": PLAN_TRAFFIC_RATIO * float(np.mean(bytes_)),
+           "traffic_source": "profiles/planning_c5_structure_kernels_and_traffic.md (FETCH_SIZE + WRITE_SIZE of all "
+                             "planning kernels, calibrated, per plan)",
+           "workload": "c5-planning-stress page structure (V=10485760, F=4194304, G=400)",
            "plan_device_us_mean": float(np.mean(dev_ms)) * 1e3,
            "plan_host_wall_us_mean": float(np.mean(r["plan_wall_s"])) * 1e6,
            "algorithmic_bytes_per_plan": float(np.mean(bytes_)),
@@ -256,6 +262,8 @@ def bench_planning_stress(torch, warmup=8, steps=16):
            "n_evict_mean": float(np.mean([p.n_evict for p in r["plans"]]))}
     ms.close()
     buf.release()
+    if not phases:
+        return out
     # the per-phase split comes from a second pass: its extra events lengthen each plan by a few microseconds
     buf, ms = make_context(torch, trace, fill_contents=False)
     r2 = run_steps(torch, trace, ms, warmup, steps, profile=2)
@@ -274,6 +282,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5],
                     help="workload (default 2 = the configuration the metric is quoted on)")
     ap.add_argument("--no-plan-stress", action="store_true", help="skip the planning-stress leg")
+    ap.add_argument("--plan-stress-only", action="store_true",
+                    help="run only the planning-stress leg (for profiling the planning kernels)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-steps", type=int, default=480)
     args = ap.parse_args()
@@ -286,6 +296,14 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     from workloads import make_trace
+
+    if args.plan_stress_only:
+        r = bench_planning_stress(torch, warmup=args.warmup, steps=min(args.steps, 24), phases=False)
+        print(json.dumps({"metric": "plan latency (us) per context switch, planning-stress page structure",
+                          "value": r["plan_device_us_mean"], "unit": "us", "n_gpus": 1, "higher_is_better": False,
+                          "data": "synthetic", "dtype": "u32", "config": {"workload": r["workload"]},
+                          "roofline": r}), flush=True)
+        return
 
     link = measure_link_peak(torch)
     log(f"[bench] link peak: {json.dumps(link)}")
