@@ -122,9 +122,6 @@ void free_ctx(msched_ctx *c) {
     if (c->hdr_host) (void)hipHostFree(c->hdr_host);
     if (c->cmd_ptrs_host) (void)hipHostFree((void *)c->cmd_ptrs_host);
     for (auto &e : c->ev) if (e) (void)hipEventDestroy(e);
-    if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
-    if (c->ev_join) (void)hipEventDestroy(c->ev_join);
-    if (c->side) { (void)hipStreamSynchronize(c->side); (void)hipStreamDestroy(c->side); }
     delete c;
 }
 
@@ -168,7 +165,7 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     c->list_binned_min_ids = (uint64_t)env_u32("MSCHED_LIST_BINNED_MIN_IDS", 0, 1 << 30, 262144);
     c->list_b0 = (uint32_t)env_u32("MSCHED_LIST_B0", 0, 4096, 4);
     c->list_b1 = std::max(c->list_b0, (uint32_t)env_u32("MSCHED_LIST_B1", 0, 4096, 32));
-    c->list_overlap = env_u32("MSCHED_LIST_OVERLAP", 0, 1, 0);
+
     c->epoch = (uint32_t)env_u32("MSCHED_INITIAL_EPOCH", 0, kMaxEpoch, 0);   // test hook: start near the wrap
     int rc = MSCHED_OK;
     auto fail = [&](hipError_t e) { c->last_hip = g_last_hip = (int)e; rc = MSCHED_E_HIP; };
@@ -200,9 +197,7 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     if (rc == MSCHED_OK && (e = hipHostGetDevicePointer(&c->host_dev, cfg->host_store, 0)) != hipSuccess) fail(e);
     for (int i = 0; i < 8 && rc == MSCHED_OK; ++i)
         if ((e = hipEventCreate(&c->ev[i])) != hipSuccess) fail(e);
-    if (rc == MSCHED_OK && (e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming)) != hipSuccess) fail(e);
-    if (rc == MSCHED_OK && (e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming)) != hipSuccess) fail(e);
-    if (rc == MSCHED_OK && (e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking)) != hipSuccess) fail(e);
+
     if (rc == MSCHED_OK && (e = launch_init_tables(c)) != hipSuccess) fail(e);
     if (rc == MSCHED_OK && (e = launch_nu_reset(c)) != hipSuccess) fail(e);
     if (rc == MSCHED_OK && (e = hipMemsetAsync(c->flags, 0, 256, c->stream)) != hipSuccess) fail(e);

@@ -89,9 +89,6 @@ struct msched_ctx {
     uint32_t *list_pairs = nullptr; size_t list_cap = 0;   // n_buckets x 8 x bucket_cap
     uint64_t list_binned_min_ids = 262144;      // plans with at least this many ids take the bucket path
     uint32_t list_b0 = 4, list_b1 = 32;         // id lists: commands [0,b0), [b0,b1), [b1,G) run as ordered batches
-    int list_overlap = 0;                       // last batch on the side stream, beside the range expansion (measured slower)
-    hipStream_t side = nullptr;                 // library-owned, default priority
-    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     uint32_t *page_table = nullptr, *frame_owner = nullptr, *nu = nullptr, *slot = nullptr;  // device
     uint32_t *evict_pages = nullptr, *evict_frames = nullptr, *fetch_pages = nullptr, *fetch_frames = nullptr;
     uint32_t *flags = nullptr;                  // device status word

@@ -777,7 +777,6 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         // Id lists go first in three stream-ordered batches of growing size: the smallest g wins a page,
         // so once the first few commands have written the popular pages, the check in front of the
         // atomic turns every later touch of them into a plain (cached) load.
-        hipStream_t ls = st;
         if (c->has_list_rule && g.list_binned) {
             ListArgs la;
             la.e = a; la.bucket_fill = c->list_bucket_fill; la.pairs = c->list_pairs;
@@ -789,18 +788,10 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
             const uint32_t b0 = std::min<uint32_t>(g.G, c->list_b0), b1 = std::min<uint32_t>(g.G, c->list_b1);
             if (b0) k_expand_list<<<b0 * 16, kListThreads, 0, st>>>(a, 0, 16, kListSeenBits - 3);
             if (b1 > b0) k_expand_list<<<(b1 - b0) * 4, kListThreads, 0, st>>>(a, b0, 4, kListSeenBits - 2);
-            if (g.G > b1) {
-                if (c->list_overlap) {
-                    CK(hipEventRecord(c->ev_fork, st));
-                    CK(hipStreamWaitEvent(c->side, c->ev_fork, 0));
-                    ls = c->side;
-                }
-                k_expand_list<<<g.G - b1, kListThreads, 0, ls>>>(a, b1, 1, kListSeenBits);
-                if (ls != st) CK(hipEventRecord(c->ev_join, ls));
-            }
+            if (g.G > b1) k_expand_list<<<g.G - b1, kListThreads, 0, st>>>(a, b1, 1, kListSeenBits);
         }
+        // the ranges go after the lists: k_list_reduce merges into nu[] without atomics
         k_expand<<<dim3(g.G, c->max_rules, a.n_split), 256, 0, st>>>(a);
-        if (ls != st) CK(hipStreamWaitEvent(st, c->ev_join, 0));
     }
     if (prof) CK(hipEventRecord(c->ev[1], st));
     SweepGeom sg;

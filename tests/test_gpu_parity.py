@@ -93,6 +93,37 @@ def test_launches_arriving_between_switches(oracle_mod):
                     lazy_slices=3) >= 20
 
 
+@pytest.mark.parametrize("binned", [False, True])
+def test_list_id_without_backing_slot_is_refused_at_plan_time(oracle_mod, monkeypatch, binned):
+    import torch
+    from paper_2512_24637_amd import MSchedError
+    if binned:
+        monkeypatch.setenv("MSCHED_LIST_BINNED_MIN_IDS", "0")
+    trace = explicit_trace([[[0, 1]]], 64, 8, timeslice=1, page_shift=6)
+    slot = np.full(64, 0xFFFFFFFF, np.uint32)
+    slot[:32] = np.arange(32)                            # pages 32..63 have no backing store
+    trace.host_slot, trace.n_slots = slot, 32
+    g = GpuSide(trace)
+    try:
+        ms = g.ms
+        kl = ms.kernel_register([Rule(RULE_LIST)])
+        ok = torch.tensor([3, 5, 3, 31], dtype=torch.int32, device="cuda")
+        bad = torch.tensor([3, 40, 5], dtype=torch.int32, device="cuda")
+        ms.launch_retire(0, 1)
+        ms.launch_enqueue(0, kl, [], 0, ids_ptr=ok.data_ptr(), n_ids=4)
+        p = ms.plan([(0, 1)])
+        assert p.fetch_pages.tolist() == [3, 5, 31]
+        ms.migrate(p)
+        ms.launch_retire(0, 1)
+        ms.launch_enqueue(0, kl, [], 0, ids_ptr=bad.data_ptr(), n_ids=3)
+        with pytest.raises(MSchedError) as e:
+            ms.plan([(0, 1)])
+        assert e.value.name == "E_RANGE"
+        assert ms.pagetable_query([3, 5, 31, 40]).tolist() == [0, 1, 2, 0xFFFFFFFF]
+    finally:
+        g.close()
+
+
 def test_errors_and_edge_cases(oracle_mod):
     from paper_2512_24637_amd import MSchedError
     trace = explicit_trace([[[0, 1, 2, 3], [4]], [[5]]], 8, 3, timeslice=1, page_shift=6)

@@ -110,33 +110,50 @@ def test_one_page_commands_reduce_to_textbook_min(oracle_mod):
         assert sum(r.plan.n_fetch for r in recs) == _textbook_min_misses(refs, n_frames)
 
 
+def _read_golden(name):
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", name)
+    out = {}
+    for line in open(path):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            key, val = line.split(":", 1)
+            out[key.strip()] = val.strip()
+    return out
+
+
 def test_three_task_example_eviction_order(oracle_mod):
-    """Sec. 6.2, memory-manager figure: with the timeline Task1 (20 ms) -> Task2 (10 ms) ->
-    Task3 (30 ms), the eviction order is: pages unreferenced across the timeline, then
-    Task3's working set, then Task2's, then Task1's; migrate populates Task1's set."""
-    ms = 10                                      # each command runs for 10 ms
-    grey = [[40, 41, 42, 43], [44, 45]]          # an idle task's pages, resident, not on the timeline
-    t1 = [[0, 1, 2, 3], [4, 5, 6, 7]]            # 2 commands fit in 20 ms
-    t2 = [[10, 11, 12, 13], [14, 15]]            # only the first starts within 10 ms
-    t3 = [[20, 21], [22, 23], [24, 25], [26]]    # 3 commands start within 30 ms
-    cmds = [t1, t2, t3, grey]
+    """Sec. 6.2, memory-manager figure (tests/golden/sec6_2_three_task_timeline.txt): with the
+    timeline Task1 (20 ms) -> Task2 (10 ms) -> Task3 (30 ms), the eviction order is: pages
+    unreferenced across the timeline, then Task3's working set, then Task2's, then Task1's; migrate
+    populates Task1's set."""
+    gold = _read_golden("sec6_2_three_task_timeline.txt")
+    ms = int(gold["command_ms"])
+    cmds_of = lambda key: [[int(x) for x in part.split()] for part in gold[key].split("|")]
+    t1, t2, t3, idle = cmds_of("task1"), cmds_of("task2"), cmds_of("task3"), cmds_of("idle")
+    tl = [int(x) for x in gold["timeline"].split()]
+    timeline = [(tl[i] - 1, tl[i + 1]) for i in range(0, len(tl), 2)]     # tasks are numbered from 1 in the paper
+    assert gold["eviction_class_order"].split() == ["idle", "task3", "task2", "task1"]
+    cmds = [t1, t2, t3, idle]
     lat = [[ms] * len(c) for c in cmds]
     trace = explicit_trace(cmds, 48, 16, timeslice=20, latencies=lat)
     o = oracle_mod.Oracle.for_trace(trace)
     load_trace(o, trace)
-    # bring grey, Task3's and Task2's slices into HBM (16 frames: 6 + 6 + 4)
-    for tl in ([(3, 20)], [(2, 30)], [(1, 10)]):
-        p = o.plan(tl)
+    # bring the idle task's, Task3's and Task2's slices into HBM (16 frames: 6 + 6 + 4)
+    for warm in ([(3, 20)], [timeline[2]], [timeline[1]]):
+        p = o.plan(warm)
         assert p.n_evict == 0
         o.migrate()
     o.launch_retire(3, 2)                        # the idle task has nothing queued any more
-    p = o.plan([(0, 20), (1, 10), (2, 30)])
+    p = o.plan(timeline)
     assert (p.g_end0, p.g_cut, p.n_commands) == (2, 2, 6)
-    assert p.fetch_pages.tolist() == [0, 1, 2, 3, 4, 5, 6, 7]        # Task1's set, in access order
+    assert p.fetch_pages.tolist() == [q for c in t1 for q in c]     # Task1's set, in access order
     assert p.n_free_used == 0 and p.n_evict == 8
     ev = p.evict_pages.tolist()
-    assert ev[:6] == [40, 41, 42, 43, 44, 45]                       # unreferenced first
-    assert ev[6:] == [24, 25]                                       # then the far end of Task3's slice
+    idle_pages = sorted(q for c in idle for q in c)
+    assert ev[:6] == idle_pages                                     # unreferenced first
+    assert ev[6:] == t3[2]                                          # then the far end of Task3's slice
+    assert not set(ev) & set(q for c in t2 for q in c)              # Task2's and Task1's classes are not reached
 
 
 def test_victims_come_class_by_class_unreferenced_then_farthest_slice(oracle_mod):
