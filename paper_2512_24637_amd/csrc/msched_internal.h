@@ -73,8 +73,9 @@ struct msched_ctx {
     uint64_t V;
     uint32_t F, page_shift;
     void *host_dev = nullptr;                   // device address of cfg.host_store
-    uint32_t migrate_chunk_shift = 14;          // bytes a workgroup moves per work unit (log2)
-    uint32_t migrate_max_blocks = 4096;         // grid cap of the copy kernel
+    uint32_t migrate_chunk_shift = 21;          // bytes a workgroup moves per work unit (log2), at most a page
+    uint32_t migrate_max_blocks = 512;          // grid cap of the copy kernel (two workgroups per CU measured best)
+    uint32_t migrate_hints = 0;                 // bit 0: plain host stores, bit 1: plain host loads (default: non-temporal)
     uint32_t expand_split = 0;                  // workgroups per (command, rule); 0 = by page-table size
     uint32_t max_chunks = msched::kMaxChunks;   // page-table chunks (sweep workgroups) at most
     uint32_t stage_threshold = 2048;            // expansion workgroups above which records are staged first

@@ -23,6 +23,7 @@ struct MigrateArgs {
     uint32_t *page_table, *frame_owner;
     uint32_t n_fetch, n_free_used, page_shift;
     uint32_t chunk_shift;          // log2(bytes one workgroup moves per unit)
+    uint32_t hints;                // bit 0: plain (not non-temporal) host stores, bit 1: plain host loads
     uint64_t n_units;              // n_fetch << (page_shift - chunk_shift)
 };
 
@@ -51,7 +52,9 @@ __global__ __launch_bounds__(256) void k_migrate(MigrateArgs a) {
 #pragma unroll
             for (int u = 0; u < kBatch; ++u) {
                 const uint32_t off = off0 + u * sweep;
-                if (off < chunk_bytes) in[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + off));
+                if (off < chunk_bytes)
+                    in[u] = (a.hints & 2) ? *reinterpret_cast<const u32x4 *>(src + off)
+                                          : __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + off));
             }
             if (swap) {
 #pragma unroll
@@ -62,7 +65,10 @@ __global__ __launch_bounds__(256) void k_migrate(MigrateArgs a) {
 #pragma unroll
                 for (int u = 0; u < kBatch; ++u) {
                     const uint32_t off = off0 + u * sweep;
-                    if (off < chunk_bytes) __builtin_nontemporal_store(out[u], reinterpret_cast<u32x4 *>(dst + off));
+                    if (off < chunk_bytes) {
+                        if (a.hints & 1) *reinterpret_cast<u32x4 *>(dst + off) = out[u];
+                        else __builtin_nontemporal_store(out[u], reinterpret_cast<u32x4 *>(dst + off));
+                    }
                 }
             }
 #pragma unroll
@@ -117,6 +123,7 @@ hipError_t launch_migrate(msched_ctx *c, const PlanHeader &h) {
     a.page_table = c->page_table; a.frame_owner = c->frame_owner;
     a.n_fetch = h.n_fetch; a.n_free_used = h.n_free_used; a.page_shift = c->page_shift;
     a.chunk_shift = std::min<uint32_t>(c->page_shift, c->migrate_chunk_shift);
+    a.hints = c->migrate_hints;
     a.n_units = (uint64_t)h.n_fetch << (a.page_shift - a.chunk_shift);
     const uint64_t blocks = std::min<uint64_t>(a.n_units, c->migrate_max_blocks);
     k_migrate<<<(uint32_t)blocks, 256, 0, c->stream>>>(a);
