@@ -183,6 +183,41 @@ enum { MSCHED_PHASE_EXPAND = 0,   /* next-use reset + template expansion + scatt
 int msched_set_profiling(msched_ctx *ctx, int level);
 int msched_get_phase_ms(msched_ctx *ctx, float *ms);
 
+/*
+ * Offline memory analyzer (Sec. 5.2, "Memory analyzer"): derive access rules from profiled invocations.
+ * A batch holds n_kernels kernels, each with n_invocations profiled invocations.  Per invocation: the
+ * launch arguments as 64-bit values (32-bit ones zero-extended), and the byte intervals (start, length)
+ * the kernel touched, sorted by start, disjoint and non-adjacent.  All arrays are DEVICE memory, owned by
+ * the caller, read only:
+ *   n_args      [K]                         arguments per kernel, <= MSCHED_MAX_ARGS
+ *   int64_mask  [K]                         bit a set: argument a is a 64-bit integer (a possible pointer)
+ *   args        [K][n_inv][MSCHED_MAX_ARGS] argument values (entries >= n_args ignored)
+ *   intervals   [K][n_inv][max_intervals][2]
+ *   n_intervals [K][n_inv]                  intervals in use, <= max_intervals
+ * For each kernel: a 64-bit argument whose value starts a touched interval in every invocation is a base
+ * pointer; the region at a base (one interval, or a run of equal intervals at a regular stride that ends
+ * at a different length, an irregular gap or another base's address) is matched against T1, T2, T3 in this
+ * order, each of size / stride / count as coeff * product of at most three non-pointer arguments with a
+ * positive integer coeff; candidates are tried as: no argument, single arguments, pairs, triples, indices
+ * ascending, first match wins.  An argument that equals a lower base in every invocation yields no rule.
+ * Output (DEVICE, caller-owned): rules [K][MSCHED_MAX_RULES] in ascending base_arg (unused tail untouched),
+ * n_rules [K], unexplained [K] = (invocation, interval) pairs that no rule accounts for.  The rules are
+ * what msched_kernel_register takes.
+ * Limits: 1 <= n_invocations <= 512; n_invocations * max_intervals <= 262144.  Asynchronous on `stream`
+ * (a hipStream_t, NULL = the default stream).  Errors: MSCHED_E_INVAL (null pointer, limits), MSCHED_E_HIP.
+ * Input that breaks the interval ordering gives unspecified rules but no out-of-bounds access.
+ */
+typedef struct {
+    uint32_t n_kernels, n_invocations, max_intervals, reserved;
+    const int32_t *n_args;
+    const uint32_t *int64_mask;
+    const uint64_t *args;
+    const uint64_t *intervals;
+    const uint32_t *n_intervals;
+} msched_profile_batch;                         /* 56 bytes */
+int msched_analyze(const msched_profile_batch *batch, msched_rule *rules, uint32_t *n_rules,
+                   uint32_t *unexplained, void *stream);
+
 const char *msched_strerror(int code);
 int msched_last_hip_error(msched_ctx *ctx);     /* hipError_t of the last MSCHED_E_HIP, as int; ctx may be NULL
                                                     (then: the last one of any context, e.g. a failed create) */

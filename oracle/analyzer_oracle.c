@@ -92,7 +92,7 @@ static int fit_search(const ktrace_t *k, const uint8_t *is_base, const uint64_t 
                       int *S_out, int *nS_out, uint64_t *c_out) {
     int cand[MAX_ARGS], nc = 0;
     for (int a = 0; a < k->n_args; a++) if (!is_base[a]) cand[nc++] = a;
-    int S[MAX_PROD];
+    int S[MAX_PROD] = {0};
     if (fits(k, val, use, S, 0, c_out)) { *nS_out = 0; return 1; }
     for (int x = 0; x < nc; x++) {
         S[0] = cand[x];

@@ -2,7 +2,7 @@
 plan a migration at each context switch and carry it out, as HIP kernels behind the
 C ABI declared in include/msched.h.  This package is the thin Python binding."""
 from .binding import (MSched, MSchedError, Plan, load_library, library_path, NOT_RESIDENT,
-                      EXPORTED_SYMBOLS, PHASES)
+                      EXPORTED_SYMBOLS, PHASES, analyze, rules_from_bytes)
 
 __all__ = ["MSched", "MSchedError", "Plan", "load_library", "library_path", "NOT_RESIDENT",
-           "EXPORTED_SYMBOLS", "PHASES"]
+           "EXPORTED_SYMBOLS", "PHASES", "analyze", "rules_from_bytes"]

@@ -16,6 +16,7 @@ EXPORTED_SYMBOLS = (
     "msched_launch_enqueue", "msched_launch_retire", "msched_plan", "msched_migrate",
     "msched_pagetable_query", "msched_plan_copy_lists", "msched_state_copy",
     "msched_set_profiling", "msched_get_phase_ms", "msched_strerror", "msched_last_hip_error",
+    "msched_analyze",
 )
 
 
@@ -31,6 +32,12 @@ class _Rule(C.Structure):
                 ("size_args", C.c_uint8 * 4), ("stride_args", C.c_uint8 * 4), ("count_args", C.c_uint8 * 4),
                 ("reserved", C.c_uint8 * 7),
                 ("size_coeff", C.c_uint64), ("stride_coeff", C.c_uint64), ("count_coeff", C.c_uint64)]
+
+
+class _ProfileBatch(C.Structure):
+    _fields_ = [("n_kernels", C.c_uint32), ("n_invocations", C.c_uint32), ("max_intervals", C.c_uint32),
+                ("reserved", C.c_uint32), ("n_args", C.c_void_p), ("int64_mask", C.c_void_p),
+                ("args", C.c_void_p), ("intervals", C.c_void_p), ("n_intervals", C.c_void_p)]
 
 
 class _TimelineEntry(C.Structure):
@@ -93,6 +100,7 @@ def load_library():
         "msched_set_profiling": [vp, C.c_int],
         "msched_get_phase_ms": [vp, vp],
         "msched_last_hip_error": [vp],
+        "msched_analyze": [C.POINTER(_ProfileBatch), vp, vp, vp, vp],
     }
     for name, argtypes in sig.items():
         fn = getattr(lib, name)
@@ -261,3 +269,29 @@ class MSched:
     def slot_of(self, pages):
         pages = np.asarray(pages, np.int64)
         return pages if self._slot is None else self._slot[pages].astype(np.int64)
+
+
+def rules_from_bytes(raw: np.ndarray, n_rules: np.ndarray):
+    """Decode msched_analyze's rule array (uint8 [K, 8, 48]) into per-kernel lists of tuples
+    (kind, base_arg, size_args, size_coeff, stride_args, stride_coeff, count_args, count_coeff)."""
+    out = []
+    for k in range(raw.shape[0]):
+        rs = []
+        for r in range(int(n_rules[k])):
+            q = _Rule.from_buffer_copy(raw[k, r].tobytes())
+            rs.append((q.kind, q.base_arg, tuple(q.size_args[:q.n_size_args]), q.size_coeff,
+                       tuple(q.stride_args[:q.n_stride_args]), q.stride_coeff,
+                       tuple(q.count_args[:q.n_count_args]), q.count_coeff))
+        out.append(rs)
+    return out
+
+
+def analyze(n_kernels, n_invocations, max_intervals, n_args_ptr, int64_mask_ptr, args_ptr, intervals_ptr,
+            n_intervals_ptr, rules_ptr, n_rules_ptr, unexplained_ptr, stream_ptr=0):
+    """msched_analyze on device pointers (ints).  Asynchronous on the stream."""
+    lib = load_library()
+    b = _ProfileBatch(n_kernels, n_invocations, max_intervals, 0, n_args_ptr, int64_mask_ptr, args_ptr,
+                      intervals_ptr, n_intervals_ptr)
+    rc = lib.msched_analyze(C.byref(b), rules_ptr, n_rules_ptr, unexplained_ptr, stream_ptr or None)
+    if rc != 0:
+        raise MSchedError(rc, lib.msched_strerror(rc).decode(), lib.msched_last_hip_error(None))

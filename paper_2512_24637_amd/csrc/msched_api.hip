@@ -10,9 +10,11 @@
 
 using namespace msched;
 
-namespace {
-
+namespace msched {
 int g_last_hip = 0;   // last HIP error of any context (readable when no context exists, e.g. after a failed create)
+}
+
+namespace {
 
 #define HIP_TRY(c, x)                                                \
     do {                                                             \

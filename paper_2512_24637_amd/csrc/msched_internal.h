@@ -128,4 +128,6 @@ hipError_t launch_migrate(msched_ctx *c, const PlanHeader &h);
 hipError_t launch_query(msched_ctx *c, const uint32_t *ids_dev, uint32_t n, uint32_t *out_dev);
 hipError_t launch_init_tables(msched_ctx *c);
 
+extern int g_last_hip;                        // hipError_t of the last failed HIP call of any context
+
 }  // namespace msched

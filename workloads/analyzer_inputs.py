@@ -119,3 +119,77 @@ def make_batch(seed=0, n_kernels=64, n_inv=16, max_iv=48, vary=True) -> Analyzer
             for m, (st, ln) in enumerate(rows):
                 iv[k, i, m] = (st, ln)
     return AnalyzerBatch(n_kernels, n_inv, max_iv, n_args, ptr_mask, args, iv, n_iv, hidden, n_other)
+
+
+def make_adversarial_batch(seed=0, n_kernels=64, n_inv=8, max_iv=32) -> AnalyzerBatch:
+    """Profiler output full of coincidences: tiny integer arguments, some duplicated or constant (many
+    argument subsets explain the same extent; the order of the search decides), zero-valued arguments,
+    pointers into the middle of a strided run, pointers that coincide in some or all invocations,
+    neighbouring groups of chunks that line up into one longer run, and 64-bit integers large enough
+    to overflow a product."""
+    rng = np.random.default_rng([seed, 13])
+    n_args = np.zeros(n_kernels, np.int32)
+    ptr_mask = np.zeros(n_kernels, np.uint32)
+    args = np.zeros((n_kernels, n_inv, MAX_ARGS), np.uint64)
+    iv = np.zeros((n_kernels, n_inv, max_iv, 2), np.uint64)
+    n_iv = np.zeros((n_kernels, n_inv), np.uint32)
+    step = 4096
+    for k in range(n_kernels):
+        n_groups = int(rng.integers(1, 4))
+        n_ptr = int(rng.integers(1, 5))
+        n_int = int(rng.integers(1, MAX_ARGS - n_ptr + 1))
+        na = n_ptr + n_int
+        n_args[k] = na
+        order = rng.permutation(na)                               # pointers and integers interleaved
+        ptr_args, int_args = sorted(order[:n_ptr].tolist()), sorted(order[n_ptr:].tolist())
+        mask = sum(1 << a for a in ptr_args)
+        for a in int_args:
+            if rng.random() < 0.4:
+                mask |= 1 << a
+        ptr_mask[k] = mask
+        int_role = {a: int(rng.choice([0, 0, 0, 1, 2, 3])) for a in int_args}   # 0 tiny, 1 constant, 2 copy, 3 huge
+        sub = lambda hi: tuple(sorted(rng.choice(int_args, size=min(len(int_args), int(rng.integers(0, hi))),
+                                                  replace=False).tolist()))
+        groups = [dict(len_c=int(rng.choice([4, 8, 16])), len_s=sub(4), cnt_s=sub(3), str_s=sub(2),
+                       glue=rng.random() < 0.3) for _ in range(n_groups)]
+        ptr_role = {a: (int(rng.integers(0, n_groups)), int(rng.choice([0, 0, 0, 1])), rng.random() < 0.15)
+                    for a in ptr_args}                            # (group, chunk pointed at, sometimes elsewhere)
+        const_val = {a: int(rng.integers(1, 4)) for a in int_args}
+        for i in range(n_inv):
+            for a in int_args:
+                r = int_role[a]
+                if r == 1:
+                    v = const_val[a]
+                elif r == 2 and a != int_args[0]:
+                    v = int(args[k, i, int_args[0]])
+                elif r == 3:
+                    v = int(rng.integers(1 << 40, 1 << 62))
+                else:
+                    v = int(rng.integers(0, 4)) if rng.random() < 0.1 else int(rng.integers(1, 4))
+                args[k, i, a] = v
+            val = lambda S: _prod(min(int(args[k, i, a]), 3) for a in S)
+            rows, starts, cursor = [], [], (1 << 40) + int(rng.integers(0, 1 << 20)) * step
+            for g in groups:
+                ln = max(1, g["len_c"] * val(g["len_s"]))
+                cnt = max(1, val(g["cnt_s"]))
+                stride = step * max(1, val(g["str_s"]))
+                if not (g["glue"] and rows):                      # glued: continues the previous group's grid
+                    cursor += step * int(rng.integers(2, 6))
+                first = len(rows)
+                for j in range(cnt):
+                    if len(rows) < max_iv:
+                        rows.append((cursor + j * stride, ln))
+                starts.append((first, len(rows)))
+                cursor = rows[-1][0] + stride
+            for a in ptr_args:
+                g, chunk, stray = ptr_role[a]
+                lo, hi = starts[g]
+                m = min(lo + chunk, max(hi - 1, lo)) if hi > lo else 0
+                if stray and rng.random() < 0.5:
+                    m = int(rng.integers(0, len(rows)))
+                args[k, i, a] = rows[min(m, len(rows) - 1)][0]
+            n_iv[k, i] = len(rows)
+            for m, (st, ln) in enumerate(rows):
+                iv[k, i, m] = (st, ln)
+    return AnalyzerBatch(n_kernels, n_inv, max_iv, n_args, ptr_mask, args, iv, n_iv, [[] for _ in range(n_kernels)],
+                         np.zeros(n_kernels, np.uint32))
