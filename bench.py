@@ -12,6 +12,8 @@ the page structure of the configured workload.  Prints ONE JSON line on stdout.
   roofline_plan the planning kernels against HBM bandwidth on the planning-stress
                 page structure (10 M pages, 4 M frames, 8 M page ids per plan)
   cpu_baseline  the plain CPU oracle timed on a bounded sample of the same schedule
+  analyzer      the offline memory analyzer (msched_analyze) on a batch of profiled kernels: kernels per
+                second, its roofline against HBM bandwidth and the CPU oracle on a sample of the batch
 """
 import argparse
 import json
@@ -274,6 +276,65 @@ def bench_planning_stress(torch, warmup=8, steps=16, phases=True):
     return out
 
 
+ANALYZER_TRAFFIC_RATIO = None     # set from profiles/k_analyze_pmc_traffic.md once measured
+
+
+def bench_analyzer(torch, base_kernels=256, tile=64, n_inv=64, max_iv=48, reps=20, cpu=True):
+    """Offline memory analyzer on profiler output of `base_kernels` synthetic kernels (hidden T1/T2/T3 models,
+    some arguments constant across invocations, some regions no argument explains), tiled `tile` times to a
+    batch that fills the chip.  Algorithmic bytes: every argument row, interval count and used interval read
+    once, every rule slot and counter written once."""
+    import paper_2512_24637_amd as M
+    from workloads.analyzer_inputs import make_batch, MAX_ARGS
+    b = make_batch(0, base_kernels, n_inv, max_iv, vary=False)
+    dev = torch.device("cuda:0")
+    up = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a).view(dt)).to(dev)
+    rep = lambda x: x.repeat((tile,) + (1,) * (x.dim() - 1)).contiguous()
+    n_args, mask = rep(up(b.n_args, np.int32)), rep(up(b.ptr_mask, np.int32))
+    args, iv, n_iv = rep(up(b.args, np.int64)), rep(up(b.iv, np.int64)), rep(up(b.n_iv, np.int32))
+    K = base_kernels * tile
+    rules = torch.zeros((K, 8, 48), dtype=torch.uint8, device=dev)
+    n_rules = torch.zeros(K, dtype=torch.int32, device=dev)
+    unexplained = torch.zeros(K, dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    call = lambda: M.analyze(K, n_inv, max_iv, n_args.data_ptr(), mask.data_ptr(), args.data_ptr(), iv.data_ptr(),
+                             n_iv.data_ptr(), rules.data_ptr(), n_rules.data_ptr(), unexplained.data_ptr(), stream)
+    for _ in range(3):
+        call()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        call()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    found = int(n_rules.sum().item())
+    alg = K * n_inv * (MAX_ARGS * 8 + 4) + int(b.n_iv.sum()) * tile * 16 + K * 8 + found * 48 + K * 8
+    ach = alg / (ms / 1e3) / 1e9
+    out = {"workload": f"{K} profiled kernels ({base_kernels} distinct, tiled x{tile}), {n_inv} invocations each, "
+                       f"up to {max_iv} touched intervals per invocation, {int(b.n_args.mean() * 10) / 10} arguments on average",
+           "kernels_per_s": K / (ms / 1e3), "ms_per_batch": ms, "rules_found": found,
+           "roofline": {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                        "traffic": ANALYZER_TRAFFIC_RATIO * alg if ANALYZER_TRAFFIC_RATIO else None,
+                        "kernel": "k_analyze", "avg_launch_ms": ms, "algorithmic_bytes_per_launch": alg,
+                        "note": "one wavefront per kernel; run time is a chain of dependent loads and LDS passes, "
+                                "hidden only by the other resident wavefronts"}}
+    if cpu:
+        from oracle import analyzer as oracle_analyzer
+        oracle_analyzer.build()
+        oracle_analyzer.analyze(b)
+        t0 = time.perf_counter()
+        n = 0
+        while time.perf_counter() - t0 < 3.0:
+            oracle_analyzer.analyze(b)
+            n += 1
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": n * base_kernels / dt, "unit": "kernels/s", "cores": 1, "kind": "oracle",
+                               "sample": f"the {base_kernels} distinct kernels of the batch, {n} passes"}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -285,6 +346,9 @@ def main():
     ap.add_argument("--plan-stress-only", action="store_true",
                     help="run only the planning-stress leg (for profiling the planning kernels)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-analyzer", action="store_true", help="skip the memory-analyzer leg")
+    ap.add_argument("--analyzer-only", action="store_true",
+                    help="run only the memory-analyzer leg (for profiling k_analyze)")
     ap.add_argument("--cpu-sample-steps", type=int, default=480)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -303,6 +367,14 @@ def main():
                           "value": r["plan_device_us_mean"], "unit": "us", "n_gpus": 1, "higher_is_better": False,
                           "data": "synthetic", "dtype": "u32", "config": {"workload": r["workload"]},
                           "roofline": r}), flush=True)
+        return
+
+    if args.analyzer_only:
+        r = bench_analyzer(torch, reps=max(1, min(args.steps, 20)), cpu=not args.no_cpu_baseline)
+        print(json.dumps({"metric": "profiled kernels analyzed per second", "value": r["kernels_per_s"],
+                          "unit": "kernels/s", "n_gpus": 1, "higher_is_better": True, "data": "synthetic",
+                          "dtype": "u64", "config": {"workload": r["workload"]}, "roofline": r["roofline"],
+                          "cpu_baseline": r.get("cpu_baseline")}), flush=True)
         return
 
     link = measure_link_peak(torch)
@@ -369,6 +441,8 @@ def main():
     }
     if not args.no_plan_stress:
         result["roofline_plan"] = bench_planning_stress(torch)
+    if not args.no_analyzer:
+        result["analyzer"] = bench_analyzer(torch, cpu=not args.no_cpu_baseline)
     if not args.no_cpu_baseline:
         if args.config == 2:
             cpu_args = dict(config=2, n_launches=max(500, 25 * (-(-args.cpu_sample_steps // 4))))

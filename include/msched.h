@@ -203,7 +203,9 @@ int msched_get_phase_ms(msched_ctx *ctx, float *ms);
  * Output (DEVICE, caller-owned): rules [K][MSCHED_MAX_RULES] in ascending base_arg (unused tail untouched),
  * n_rules [K], unexplained [K] = (invocation, interval) pairs that no rule accounts for.  The rules are
  * what msched_kernel_register takes.
- * Limits: 1 <= n_invocations <= 512; n_invocations * max_intervals <= 262144.  Asynchronous on `stream`
+ * Limits: 1 <= n_invocations <= 512; 1 <= max_intervals <= 65535; args and intervals 16-byte aligned,
+ * rules 8-byte aligned.  The first call on a device also writes a small constant table and waits for it.
+ * Asynchronous on `stream`
  * (a hipStream_t, NULL = the default stream).  Errors: MSCHED_E_INVAL (null pointer, limits), MSCHED_E_HIP.
  * Input that breaks the interval ordering gives unspecified rules but no out-of-bounds access.
  */

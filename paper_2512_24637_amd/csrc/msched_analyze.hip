@@ -2,24 +2,29 @@
 // launch arguments and touched byte intervals of a kernel's profiled invocations, derive the access
 // rules (T1 fixed / T2 linear / T3 strided) that msched_kernel_register consumes.
 //
-// One workgroup per profiled kernel; kernels of a batch are independent.  Inside a workgroup:
-//   * threads run over invocations to decide which 64-bit arguments are base pointers (their value
-//     starts a touched interval in every invocation) and to measure the region at each base
-//     (chunk length, stride and chunk count of the run of equal intervals that starts there);
-//   * threads run over candidate argument subsets ({}, singles, pairs, triples of the non-pointer
-//     arguments, in that order: at most 232) to test "value = c * product(args[S])" on every invocation;
-//     the lowest-ranked subset that fits wins, which makes the constant beat any product and a single
-//     argument beat a pair.
+// One wavefront per profiled kernel; kernels of a batch are independent, and a batch of thousands fills
+// the chip with many resident wavefronts per compute unit, which is what hides the latency of the
+// dependent loads (binary searches, run scans).  Inside a wavefront:
+//   * lanes run over (invocation, pointer argument) pairs to decide which 64-bit arguments are base
+//     pointers (their value starts a touched interval in every invocation), then over invocations to
+//     measure the region at each base (chunk length, stride and count of the run that starts there);
+//   * to fit "value = c * product(args[S])", lanes run over the candidate subsets S ({}, singles, pairs,
+//     triples of the non-pointer arguments, in that order: at most 232) and screen each on the first few
+//     invocations; survivors are then tested in rank order on every invocation with lanes over
+//     invocations.  The first that passes is the lowest-ranked fit: the constant beats any product and a
+//     single argument beats a pair.
 #include <algorithm>
+#include <cstddef>
+#include <mutex>
 
 #include "msched_internal.h"
 
 namespace msched {
 
-constexpr int kAnaThreads = 256;
 constexpr int kAnaMaxInv = 512;
-constexpr uint32_t kAnaMaxBits = 262144;          // n_invocations * max_intervals at most (coverage bitmap in LDS)
 constexpr int kAnaMaxProd = 3;
+constexpr int kAnaProbe = 3;                      // invocations a subset is screened on before the full test
+constexpr int kAnaMaxSubsets = 1 + 12 + 66 + 220; // {} + singles + pairs + triples of 12 candidates
 
 struct AnaArgs {
     uint32_t n_inv, max_iv;
@@ -28,34 +33,40 @@ struct AnaArgs {
     msched_rule *rules; uint32_t *n_rules, *unexplained;
 };
 
-// index of the interval of invocation row `iv` (sorted by start) that starts at addr, or -1
-__device__ __forceinline__ int find_start(const uint64_t *iv, uint32_t n, uint64_t addr) {
+// index of the interval of one invocation (sorted by start) that starts at addr, or -1
+__device__ __forceinline__ int find_start(const uint64_t *row, uint32_t n, uint64_t addr) {
     uint32_t lo = 0, hi = n;
     while (lo < hi) {
         const uint32_t mid = (lo + hi) >> 1;
-        if (iv[2 * mid] < addr) lo = mid + 1; else hi = mid;
+        if (row[2 * mid] < addr) lo = mid + 1; else hi = mid;
     }
-    return (lo < n && iv[2 * lo] == addr) ? (int)lo : -1;
+    return (lo < n && row[2 * lo] == addr) ? (int)lo : -1;
 }
 
-// the rank-th subset in the order {} ; {a} ; {a,b} ; {a,b,c} over nc candidates; returns its size
-__device__ __forceinline__ int unrank_subset(uint32_t rank, uint32_t nc, uint32_t *pos) {
+// the rank-th subset in the order {} ; {a} ; {a,b} ; {a,b,c} over nc candidates, as positions in the
+// candidate list packed one per byte, the size in the top byte
+__device__ uint32_t unrank_subset(uint32_t rank, uint32_t nc) {
     if (rank == 0) return 0;
     rank -= 1;
-    if (rank < nc) { pos[0] = rank; return 1; }
+    if (rank < nc) return (1u << 24) | rank;
     rank -= nc;
-    for (uint32_t x = 0; x < nc; ++x) {
+    for (uint32_t x = 0; x + 1 < nc; ++x) {
         const uint32_t row = nc - 1 - x;
-        if (rank < row) { pos[0] = x; pos[1] = x + 1 + rank; return 2; }
+        if (rank < row) return (2u << 24) | x | ((x + 1 + rank) << 8);
         rank -= row;
     }
-    for (uint32_t x = 0; x < nc; ++x)
-        for (uint32_t y = x + 1; y < nc; ++y) {
+    for (uint32_t x = 0; x + 2 < nc; ++x)
+        for (uint32_t y = x + 1; y + 1 < nc; ++y) {
             const uint32_t row = nc - 1 - y;
-            if (rank < row) { pos[0] = x; pos[1] = y; pos[2] = y + 1 + rank; return 3; }
+            if (rank < row) return (3u << 24) | x | (y << 8) | ((y + 1 + rank) << 16);
             rank -= row;
         }
-    return -1;
+    return 0;
+}
+
+// v / p, p != 0; extents and argument values rarely need more than 32 bits, where the division is far cheaper
+__device__ __forceinline__ uint64_t div_u64(uint64_t v, uint64_t p) {
+    return ((v | p) >> 32) == 0 ? (uint64_t)((uint32_t)v / (uint32_t)p) : v / p;
 }
 
 __device__ __forceinline__ bool mul_ok(uint64_t a, uint64_t b, uint64_t &out) {
@@ -63,183 +74,323 @@ __device__ __forceinline__ bool mul_ok(uint64_t a, uint64_t b, uint64_t &out) {
     return __umul64hi(a, b) == 0;
 }
 
-// Does value_i = c * product(args_i[S]) hold for every invocation with use_i != 0?  (c: from the first
-// such invocation whose product is not zero; c >= 1.)
-__device__ bool subset_fits(const uint64_t *s_args, uint32_t n_inv, const uint64_t *val, const uint8_t *use,
-                            const uint32_t *S, int nS, uint64_t &c_out) {
-    uint64_t c = 0;
-    bool have_c = false;
-    for (uint32_t i = 0; i < n_inv && !have_c; ++i) {
-        if (!use[i]) continue;
-        uint64_t prod = 1;
-        for (int j = 0; j < nS; ++j)
-            if (!mul_ok(prod, s_args[i * MSCHED_MAX_ARGS + S[j]], prod)) return false;
-        if (prod != 0) {
-            if (val[i] % prod) return false;
-            c = val[i] / prod;
-            have_c = true;
-        }
-    }
-    if (!have_c || c == 0) return false;
-    for (uint32_t i = 0; i < n_inv; ++i) {
-        if (!use[i]) continue;
-        uint64_t prod = 1, want;
-        for (int j = 0; j < nS; ++j)
-            if (!mul_ok(prod, s_args[i * MSCHED_MAX_ARGS + S[j]], prod)) return false;
-        if (!mul_ok(c, prod, want) || want != val[i]) return false;
-    }
-    c_out = c;
-    return true;
+struct Subset { int n; uint32_t idx[kAnaMaxProd]; };
+
+__device__ __forceinline__ bool product_of(const uint64_t *row, const Subset &S, uint64_t &prod) {
+    prod = 1;
+    bool ok = true;
+    for (int j = 0; j < kAnaMaxProd; ++j)
+        if (j < S.n) ok &= mul_ok(prod, row[S.idx[j]], prod);
+    return ok;
 }
 
-struct Fit { int n; uint32_t idx[kAnaMaxProd]; uint64_t coeff; };
+// One wavefront analyzes one kernel.  Lanes run over invocations (finding intervals, measuring regions,
+// testing one formula on all invocations) or over candidate subsets (screening each on a few invocations).
+struct Analyzer {
+    uint32_t n_inv, lane;
+    const uint64_t *s_args;         // LDS [n_inv][12]
+    const uint64_t *val;            // LDS [n_inv]: the quantity being fitted
+    const uint64_t *count;          // LDS [n_inv]: chunks in the region
+    bool multi_only;                // fit over invocations with more than one chunk only
+    const uint32_t *subsets;        // LDS [n_subsets] packed positions
+    const uint32_t *cand;           // LDS [nc] argument index of each candidate
+    uint32_t n_subsets, n_singles;
 
-// Block-wide: first fitting subset (lowest rank) for the values val[] over the invocations use[].
-__device__ bool fit_search(const uint64_t *s_args, uint32_t n_inv, const uint32_t *cand, uint32_t nc,
-                           const uint64_t *val, const uint8_t *use, uint32_t *s_best, uint64_t *s_coeff, Fit &out) {
-    const uint32_t n_subsets = 1 + nc + nc * (nc - 1) / 2 + nc * (nc - 1) * (nc - 2) / 6;
-    if (threadIdx.x == 0) *s_best = kNone;
-    __syncthreads();
-    for (uint32_t rank = threadIdx.x; rank < n_subsets; rank += blockDim.x) {
-        uint32_t pos[kAnaMaxProd], S[kAnaMaxProd];
-        const int nS = unrank_subset(rank, nc, pos);
-        for (int j = 0; j < nS; ++j) S[j] = cand[pos[j]];
-        uint64_t c;
-        if (*s_best > rank && subset_fits(s_args, n_inv, val, use, S, nS, c)) atomicMin(s_best, rank);
+    __device__ bool used(uint32_t i) const { return !multi_only || count[i] > 1; }
+
+    __device__ Subset subset(uint32_t rank) const {
+        const uint32_t packed = subsets[rank];
+        Subset S;
+        S.n = (int)(packed >> 24);
+        for (int j = 0; j < kAnaMaxProd; ++j) S.idx[j] = j < S.n ? cand[(packed >> (8 * j)) & 0xff] : 0;
+        return S;
     }
-    __syncthreads();
-    const uint32_t best = *s_best;
-    if (best == kNone) return false;
-    uint32_t pos[kAnaMaxProd];
-    out.n = unrank_subset(best, nc, pos);
-    for (int j = 0; j < out.n; ++j) out.idx[j] = cand[pos[j]];
-    if (threadIdx.x == best % blockDim.x) {                 // the thread that tested it recomputes the coefficient
+
+    // per lane: could value = c * product(args[S]) hold, judging by the probe invocations alone?
+    __device__ bool screen(const Subset &S, const uint32_t *probe, int n_probe) const {
         uint64_t c = 0;
-        subset_fits(s_args, n_inv, val, use, out.idx, out.n, c);
-        *s_coeff = c;
+        bool have_c = false;
+        for (int t = 0; t < n_probe; ++t) {
+            const uint32_t i = probe[t];
+            uint64_t prod, want;
+            if (!product_of(s_args + i * MSCHED_MAX_ARGS, S, prod)) return false;
+            const uint64_t v = val[i];
+            if (!have_c) {
+                if (prod == 0) { if (v != 0) return false; continue; }
+                c = div_u64(v, prod);
+                if (c == 0 || c * prod != v) return false;
+                have_c = true;
+            } else if (!mul_ok(c, prod, want) || want != v) return false;
+        }
+        return true;
     }
-    __syncthreads();
-    out.coeff = *s_coeff;
-    __syncthreads();
-    return true;
+
+    // whole wave, S uniform: the test on every used invocation; the coefficient comes from the first used
+    // invocation whose product is not zero
+    __device__ bool verify(const Subset &S, uint64_t &c_out) const {
+        uint64_t c = 0;
+        bool have_c = false;
+        for (uint32_t i0 = 0; i0 < n_inv && !have_c; i0 += kWave) {
+            const uint32_t i = i0 + lane;
+            const bool act = i < n_inv && used(i);
+            uint64_t prod = 0;
+            bool ovf = false;
+            if (act) ovf = !product_of(s_args + i * MSCHED_MAX_ARGS, S, prod);
+            const uint64_t m = __ballot(act && (ovf || prod != 0));
+            if (m) {
+                const int l = __ffsll((unsigned long long)m) - 1;
+                if (__shfl((int)ovf, l)) return false;
+                const uint64_t p = __shfl((unsigned long long)prod, l), v = __shfl((unsigned long long)(act ? val[i] : 0), l);
+                c = div_u64(v, p);
+                if (c == 0 || c * p != v) return false;
+                have_c = true;
+            }
+        }
+        if (!have_c) return false;
+        for (uint32_t i0 = 0; i0 < n_inv; i0 += kWave) {
+            const uint32_t i = i0 + lane;
+            bool bad = false;
+            if (i < n_inv && used(i)) {
+                uint64_t prod, want;
+                bad = !product_of(s_args + i * MSCHED_MAX_ARGS, S, prod) || !mul_ok(c, prod, want) || want != val[i];
+            }
+            if (__ballot(bad)) return false;
+        }
+        c_out = c;
+        return true;
+    }
+
+    // whole wave: the lowest-ranked subset that fits
+    __device__ bool search(Subset &S_out, uint64_t &c_out) const {
+        uint32_t probe[kAnaProbe];
+        int n_probe = 0;
+        for (uint32_t i0 = 0; i0 < n_inv && n_probe < kAnaProbe; i0 += kWave) {
+            const uint32_t i = i0 + lane;
+            uint64_t m = __ballot(i < n_inv && used(i));
+            while (m && n_probe < kAnaProbe) {
+                probe[n_probe++] = i0 + __ffsll((unsigned long long)m) - 1;
+                m &= m - 1;
+            }
+        }
+        if (n_probe == 0) return false;
+        // {} first and on its own: most regions have an invariant extent (template T1) and need nothing else;
+        // then the single arguments, then pairs and triples a wavefront at a time
+        Subset none;
+        none.n = 0; none.idx[0] = none.idx[1] = none.idx[2] = 0;
+        if (verify(none, c_out)) { S_out = none; return true; }
+        const uint32_t n_cand = n_singles;
+        for (uint32_t r0 = 1; r0 < n_subsets;) {
+            const uint32_t r1 = min(r0 <= n_cand ? 1 + n_cand : r0 + kWave, n_subsets);
+            const uint32_t rank = r0 + lane;
+            bool pass = false;
+            if (rank < r1) pass = screen(subset(rank), probe, n_probe);
+            uint64_t m = __ballot(pass);
+            while (m) {
+                const uint32_t best = r0 + __ffsll((unsigned long long)m) - 1;
+                m &= m - 1;
+                const Subset S = subset(best);
+                if (verify(S, c_out)) { S_out = S; return true; }
+            }
+            r0 = r1;
+        }
+        return false;
+    }
+};
+
+// subsets in search order for every possible number of candidates; filled once per device
+__device__ uint32_t g_subset_table[MSCHED_MAX_ARGS + 1][kAnaMaxSubsets];
+
+__device__ __host__ constexpr uint32_t subsets_of(uint32_t nc) {
+    return 1 + nc + nc * (nc - 1) / 2 + (nc >= 3 ? nc * (nc - 1) * (nc - 2) / 6 : 0);
 }
 
-__global__ __launch_bounds__(kAnaThreads) void k_analyze(AnaArgs a) {
-    extern __shared__ uint64_t ana_lds[];
-    const uint32_t k = blockIdx.x, n_inv = a.n_inv, max_iv = a.max_iv, tid = threadIdx.x;
+__global__ void k_subset_table() {
+    const uint32_t nc = blockIdx.x;
+    for (uint32_t r = threadIdx.x; r < subsets_of(nc); r += blockDim.x) g_subset_table[nc][r] = unrank_subset(r, nc);
+}
+
+static_assert(sizeof(msched_rule) == 48 && offsetof(msched_rule, size_args) == 5 && offsetof(msched_rule, stride_args) == 9 &&
+              offsetof(msched_rule, count_args) == 13 && offsetof(msched_rule, size_coeff) == 24,
+              "rule_words packs this layout");
+
+// the first 24 bytes of a msched_rule as three little-endian words
+__device__ __forceinline__ void rule_words(uint32_t kind, uint32_t base_arg, const Subset &size, const Subset &stride,
+                                           const Subset &count, uint64_t w[3]) {
+    auto at = [](const Subset &S, int j) { return (uint64_t)(j < S.n ? S.idx[j] : 0); };
+    w[0] = kind | (uint64_t)base_arg << 8 | (uint64_t)size.n << 16 | (uint64_t)stride.n << 24 | (uint64_t)count.n << 32 |
+           at(size, 0) << 40 | at(size, 1) << 48 | at(size, 2) << 56;
+    w[1] = at(stride, 0) << 8 | at(stride, 1) << 16 | at(stride, 2) << 24 | at(count, 0) << 40 | at(count, 1) << 48 |
+           at(count, 2) << 56;
+    w[2] = 0;
+}
+
+constexpr uint32_t kRowLanes = 8;                 // lanes that share one invocation's interval row when matching pointers
+constexpr uint32_t kRowsPerLane = kWave / kRowLanes;           // rows each lane visits per block of 64 invocations
+constexpr uint32_t kArgBatch = 6;                 // 16-byte loads a lane keeps in flight while staging arguments
+constexpr uint32_t kNoInterval = 0xffff;
+static_assert(kArgBatch * 2 == MSCHED_MAX_ARGS, "one trip of the staging loop moves 64 whole argument rows");
+
+// Every phase that reads global memory issues all its loads before it looks at any of them: one wavefront
+// has little else to hide a memory round trip behind, and the number of dependent round trips is what its
+// run time is made of.
+__global__ __launch_bounds__(kWave) void k_analyze(AnaArgs a) {
+    extern __shared__ __align__(16) uint64_t ana_lds[];
+    const uint32_t k = blockIdx.x, n_inv = a.n_inv, max_iv = a.max_iv, lane = threadIdx.x;
     uint64_t *s_args = ana_lds;                                   // [n_inv][12]
     uint64_t *chunk = s_args + (size_t)n_inv * MSCHED_MAX_ARGS;   // [n_inv]
     uint64_t *stride = chunk + n_inv, *count = stride + n_inv;    // [n_inv] each
-    uint32_t *covered = reinterpret_cast<uint32_t *>(count + n_inv);               // [(n_inv * max_iv + 31) / 32]
-    const uint32_t cov_words = (n_inv * max_iv + 31) / 32;
-    uint8_t *all_inv = reinterpret_cast<uint8_t *>(covered + cov_words);           // [n_inv]
-    uint8_t *multi = all_inv + n_inv;                                              // [n_inv]
-    __shared__ uint32_t s_flag[MSCHED_MAX_ARGS], s_alias, s_any_multi, s_best, s_covered, s_total, cand[MSCHED_MAX_ARGS];
-    __shared__ uint64_t s_coeff;
-    __shared__ uint32_t s_n_rules;
-    const int n_args = min(max(a.n_args[k], 0), MSCHED_MAX_ARGS);
-    const uint32_t mask = a.int64_mask[k];
-    const uint64_t *g_args = a.args + (size_t)k * n_inv * MSCHED_MAX_ARGS;
-    const uint64_t *g_iv = a.iv + (size_t)k * n_inv * max_iv * 2;
+    uint32_t *s_niv = reinterpret_cast<uint32_t *>(count + n_inv);                 // [n_inv]
+    uint16_t *s_m0 = reinterpret_cast<uint16_t *>(s_niv + n_inv); // [12][n_inv]: interval index at each pointer
+    __shared__ uint32_t s_cand[MSCHED_MAX_ARGS], s_subsets[kAnaMaxSubsets];
+    const ulonglong2 *g_args = reinterpret_cast<const ulonglong2 *>(a.args + (size_t)k * n_inv * MSCHED_MAX_ARGS);
+    const ulonglong2 *g_iv = reinterpret_cast<const ulonglong2 *>(a.iv + (size_t)k * n_inv * max_iv * 2);   // (start, length)
     const uint32_t *g_niv = a.n_iv + (size_t)k * n_inv;
-    for (uint32_t i = tid; i < n_inv * MSCHED_MAX_ARGS; i += blockDim.x) s_args[i] = g_args[i];
-    for (uint32_t i = tid; i < cov_words; i += blockDim.x) covered[i] = 0;
-    for (uint32_t i = tid; i < n_inv; i += blockDim.x) all_inv[i] = 1;
-    if (tid < MSCHED_MAX_ARGS) s_flag[tid] = (tid < (uint32_t)n_args && ((mask >> tid) & 1) && n_inv > 0) ? 1u : 0u;
-    if (tid == 0) { s_n_rules = 0; s_covered = 0; s_total = 0; }
-    __syncthreads();
-    // 1. base pointers
-    for (int arg = 0; arg < n_args; ++arg) {
-        if (!((mask >> arg) & 1)) continue;
-        bool ok = true;
-        for (uint32_t i = tid; i < n_inv && ok; i += blockDim.x)
-            ok = find_start(g_iv + (size_t)i * max_iv * 2, min(g_niv[i], max_iv), s_args[i * MSCHED_MAX_ARGS + arg]) >= 0;
-        if (!ok) atomicAnd(&s_flag[arg], 0u);
-    }
+    // 0. arguments and interval counts into LDS
     uint32_t total = 0;
-    for (uint32_t i = tid; i < n_inv; i += blockDim.x) total += min(g_niv[i], max_iv);
-    if (total) atomicAdd(&s_total, total);
-    __syncthreads();
-    uint32_t nc = 0;                                              // candidates for products: the non-pointer arguments
-    for (int arg = 0; arg < n_args; ++arg) if (!s_flag[arg]) { if (tid == 0) cand[nc] = arg; ++nc; }
-    __syncthreads();
-    for (int arg = 0; arg < n_args; ++arg) {
-        if (!s_flag[arg]) continue;                               // uniform across the block
-        // an argument that equals a lower base in every invocation is an alias
-        bool alias = false;
-        for (int b = 0; b < arg && !alias; ++b) {
-            if (!s_flag[b]) continue;
-            if (tid == 0) s_alias = 1;
-            __syncthreads();
-            bool same = true;
-            for (uint32_t i = tid; i < n_inv && same; i += blockDim.x)
-                same = s_args[i * MSCHED_MAX_ARGS + arg] == s_args[i * MSCHED_MAX_ARGS + b];
-            if (!same) atomicAnd(&s_alias, 0u);
-            __syncthreads();
-            alias = s_alias != 0;
-            __syncthreads();
+    {
+        ulonglong2 *s2 = reinterpret_cast<ulonglong2 *>(s_args);
+        const uint32_t n2 = n_inv * (MSCHED_MAX_ARGS / 2);
+        for (uint32_t f = lane; f < n2; f += kArgBatch * kWave) {
+            ulonglong2 v[kArgBatch];
+            uint32_t niv = 0;
+            for (uint32_t u = 0; u < kArgBatch; ++u) if (f + u * kWave < n2) v[u] = g_args[f + u * kWave];
+            const uint32_t i = f / (kArgBatch * kWave) * kWave + lane;   // one invocation per lane and trip: 64 rows are 6 * 64 loads
+            if (i < n_inv) niv = g_niv[i];
+            for (uint32_t u = 0; u < kArgBatch; ++u) if (f + u * kWave < n2) s2[f + u * kWave] = v[u];
+            if (i < n_inv) { niv = min(niv, max_iv); s_niv[i] = niv; total += niv; }
         }
-        if (alias) continue;
-        // 2. the region that starts at this base, per invocation
-        if (tid == 0) s_any_multi = 0;
-        __syncthreads();
-        for (uint32_t i = tid; i < n_inv; i += blockDim.x) {
-            const uint64_t *row = g_iv + (size_t)i * max_iv * 2;
-            const uint32_t n = min(g_niv[i], max_iv);
-            const int m0 = find_start(row, n, s_args[i * MSCHED_MAX_ARGS + arg]);
-            const uint64_t len = row[2 * m0 + 1];
-            uint64_t st = 0, cnt = 1;
-            for (uint32_t m = (uint32_t)m0 + 1; m < n; ++m) {
-                if (row[2 * m + 1] != len) break;
-                bool other = false;
-                for (int b = 0; b < n_args; ++b)
-                    other |= s_flag[b] && b != arg && s_args[i * MSCHED_MAX_ARGS + b] == row[2 * m];
-                if (other) break;
-                const uint64_t gap = row[2 * m] - row[2 * (m - 1)];
-                if (cnt == 1) st = gap; else if (gap != st) break;
-                ++cnt;
+    }
+    for (uint32_t f = lane; f < n_inv * MSCHED_MAX_ARGS; f += kWave) s_m0[f] = kNoInterval;
+    const int n_args = min(max(a.n_args[k], 0), MSCHED_MAX_ARGS);
+    const uint32_t mask = a.int64_mask[k] & ((1u << n_args) - 1);
+    __syncthreads();
+    // 1. base pointers: 64-bit arguments whose value starts an interval in every invocation.  Every interval
+    //    start is read once, eight lanes to a row, and compared with the invocation's 64-bit arguments.
+    auto match = [&](uint32_t i, uint32_t m, uint64_t start) {
+        for (uint32_t rest = mask; rest; rest &= rest - 1) {
+            const uint32_t arg = __builtin_ctz(rest);
+            if (s_args[i * MSCHED_MAX_ARGS + arg] == start) s_m0[arg * n_inv + i] = (uint16_t)m;
+        }
+    };
+    if (mask)
+        for (uint32_t ib = 0; ib < n_inv; ib += kWave) {
+            const uint32_t sub = lane % kRowLanes;
+            uint64_t start[kRowsPerLane];
+            uint32_t nn[kRowsPerLane];
+            for (uint32_t p = 0; p < kRowsPerLane; ++p) {
+                const uint32_t i = ib + p * kRowsPerLane + lane / kRowLanes;
+                nn[p] = i < n_inv ? s_niv[i] : 0;
+                start[p] = sub < nn[p] ? g_iv[(size_t)i * max_iv + sub].x : 0;
+            }
+            for (uint32_t p = 0; p < kRowsPerLane; ++p) {
+                const uint32_t i = ib + p * kRowsPerLane + lane / kRowLanes;
+                if (sub < nn[p]) match(i, sub, start[p]);
+                for (uint32_t m = sub + kRowLanes; m < nn[p]; m += kRowLanes) match(i, m, g_iv[(size_t)i * max_iv + m].x);
+            }
+        }
+    __syncthreads();
+    uint32_t nc = 0, base_mask = 0;
+    for (int arg = 0; arg < n_args; ++arg) {
+        bool missing = !((mask >> arg) & 1);
+        for (uint32_t i = lane; i < n_inv && !missing; i += kWave) missing = s_m0[arg * n_inv + i] == kNoInterval;
+        if (__ballot(missing) == 0) base_mask |= 1u << arg;
+        else { if (lane == 0) s_cand[nc] = arg; ++nc; }
+    }
+    // an argument that equals a lower base in every invocation is an alias and gets no rule
+    uint32_t live_mask = 0;
+    for (uint32_t rest = base_mask; rest; rest &= rest - 1) {
+        const uint32_t arg = __builtin_ctz(rest);
+        bool alias = false;
+        for (uint32_t lower = base_mask & ((1u << arg) - 1); lower && !alias; lower &= lower - 1) {
+            const uint32_t b = __builtin_ctz(lower);
+            bool differs = false;
+            for (uint32_t i = lane; i < n_inv; i += kWave)
+                differs |= s_args[i * MSCHED_MAX_ARGS + arg] != s_args[i * MSCHED_MAX_ARGS + b];
+            alias = __ballot(differs) == 0;
+        }
+        if (!alias) live_mask |= 1u << arg;
+    }
+    const uint32_t n_subsets = subsets_of(nc);
+    // the first two intervals at a base, for the first 64 invocations: loaded one base ahead of their use
+    ulonglong2 w0 = {0, 0}, w1 = {0, 0};
+    auto window = [&](uint32_t arg) {
+        if (lane < n_inv) {
+            const uint32_t n = s_niv[lane], m0 = s_m0[arg * n_inv + lane];
+            w0 = g_iv[(size_t)lane * max_iv + m0];
+            if (m0 + 1 < n) w1 = g_iv[(size_t)lane * max_iv + m0 + 1];
+        }
+    };
+    if (live_mask) {
+        window(__builtin_ctz(live_mask));
+        for (uint32_t r = lane; r < n_subsets; r += kWave) s_subsets[r] = g_subset_table[nc][r];
+    }
+    Analyzer an;
+    an.n_inv = n_inv; an.lane = lane; an.s_args = s_args; an.count = count;
+    an.subsets = s_subsets; an.cand = s_cand; an.n_subsets = n_subsets; an.n_singles = nc;
+    uint32_t n_rules = 0, covered = 0, accepted_mask = 0;
+    for (uint32_t rest = live_mask; rest; rest &= rest - 1) {
+        const uint32_t arg = __builtin_ctz(rest);
+        // 2. the region that starts at this base, per invocation: a run of equal intervals at a regular stride
+        bool any_multi = false;
+        for (uint32_t i = lane; i < n_inv; i += kWave) {
+            const ulonglong2 *row = g_iv + (size_t)i * max_iv;
+            const uint64_t *arow = s_args + i * MSCHED_MAX_ARGS;
+            const uint32_t n = s_niv[i], m0 = s_m0[arg * n_inv + i];
+            ulonglong2 first = w0, next = w1;
+            if (i >= kWave) {
+                first = row[m0];
+                if (m0 + 1 < n) next = row[m0 + 1];
+            }
+            const uint64_t len = first.y;
+            uint64_t st = 0, cnt = 1, prev = first.x;
+            for (uint32_t m = m0 + 1; m < n; ++m) {
+                if (m > m0 + 1) next = row[m];
+                bool other = next.y != len;
+                for (uint32_t bases = base_mask & ~(1u << arg); bases; bases &= bases - 1)
+                    other |= arow[__builtin_ctz(bases)] == next.x;
+                const uint64_t gap = next.x - prev;
+                if (other || (cnt > 1 && gap != st)) break;
+                st = gap; prev = next.x; ++cnt;
             }
             chunk[i] = len; stride[i] = st; count[i] = cnt;
-            multi[i] = cnt > 1;
-            if (cnt > 1) atomicOr(&s_any_multi, 1u);
+            any_multi |= cnt > 1;
         }
         __syncthreads();
-        // 3. templates in order
-        const bool strided = s_any_multi != 0;
-        Fit f_size, f_stride, f_count;
-        f_stride.n = f_count.n = 0; f_stride.coeff = f_count.coeff = 0;
-        bool ok = fit_search(s_args, n_inv, cand, nc, chunk, all_inv, &s_best, &s_coeff, f_size);
-        if (ok && strided) ok = fit_search(s_args, n_inv, cand, nc, stride, multi, &s_best, &s_coeff, f_stride);
-        if (ok && strided) ok = fit_search(s_args, n_inv, cand, nc, count, all_inv, &s_best, &s_coeff, f_count);
-        if (!ok || s_n_rules == MSCHED_MAX_RULES) { __syncthreads(); continue; }
-        if (tid == 0) {
-            msched_rule q;
-            memset(&q, 0, sizeof q);
-            q.kind = strided ? MSCHED_RULE_STRIDED : (f_size.n == 0 ? MSCHED_RULE_FIXED : MSCHED_RULE_LINEAR);
-            q.base_arg = (uint8_t)arg;
-            q.n_size_args = (uint8_t)f_size.n; q.n_stride_args = (uint8_t)f_stride.n; q.n_count_args = (uint8_t)f_count.n;
-            for (int j = 0; j < f_size.n; ++j) q.size_args[j] = (uint8_t)f_size.idx[j];
-            for (int j = 0; j < f_stride.n; ++j) q.stride_args[j] = (uint8_t)f_stride.idx[j];
-            for (int j = 0; j < f_count.n; ++j) q.count_args[j] = (uint8_t)f_count.idx[j];
-            q.size_coeff = f_size.coeff; q.stride_coeff = f_stride.coeff; q.count_coeff = f_count.coeff;
-            a.rules[(size_t)k * MSCHED_MAX_RULES + s_n_rules] = q;
-        }
-        // mark what the rule accounts for
-        for (uint32_t i = tid; i < n_inv; i += blockDim.x) {
-            const int m0 = find_start(g_iv + (size_t)i * max_iv * 2, min(g_niv[i], max_iv), s_args[i * MSCHED_MAX_ARGS + arg]);
-            for (uint64_t j = 0; j < count[i]; ++j) {
-                const uint32_t bit = i * max_iv + (uint32_t)m0 + (uint32_t)j;
-                const uint32_t old = atomicOr(&covered[bit >> 5], 1u << (bit & 31));
-                if (!(old & (1u << (bit & 31)))) atomicAdd(&s_covered, 1u);
+        if (rest & (rest - 1)) window(__builtin_ctz(rest & (rest - 1)));
+        const bool strided = __ballot(any_multi) != 0;
+        // 3. templates in order: invariant size, size proportional to arguments, strided
+        Subset S_size, S_stride, S_count;
+        S_size.n = S_stride.n = S_count.n = 0;
+        uint64_t c_size = 0, c_stride = 0, c_count = 0;
+        an.val = chunk; an.multi_only = false;
+        bool ok = an.search(S_size, c_size);
+        if (ok && strided) { an.val = stride; an.multi_only = true; ok = an.search(S_stride, c_stride); }
+        if (ok && strided) { an.val = count; an.multi_only = false; ok = an.search(S_count, c_count); }
+        if (ok && n_rules < MSCHED_MAX_RULES) {
+            uint64_t w[3];
+            rule_words(strided ? MSCHED_RULE_STRIDED : (S_size.n == 0 ? MSCHED_RULE_FIXED : MSCHED_RULE_LINEAR), arg,
+                       S_size, S_stride, S_count, w);
+            const uint64_t word = lane == 0 ? w[0] : lane == 1 ? w[1] : lane == 2 ? w[2] : lane == 3 ? c_size :
+                                  lane == 4 ? c_stride : c_count;
+            if (lane < 6) reinterpret_cast<uint64_t *>(a.rules + (size_t)k * MSCHED_MAX_RULES + n_rules)[lane] = word;
+            // What the rule accounts for.  Two bases that hold the same address in an invocation start the
+            // same run there (a run never reaches past another base), so it is counted for the first only.
+            for (uint32_t i = lane; i < n_inv; i += kWave) {
+                bool seen = false;
+                for (uint32_t lower = accepted_mask; lower; lower &= lower - 1)
+                    seen |= s_args[i * MSCHED_MAX_ARGS + __builtin_ctz(lower)] == s_args[i * MSCHED_MAX_ARGS + arg];
+                if (!seen) covered += (uint32_t)count[i];
             }
+            accepted_mask |= 1u << arg;
+            ++n_rules;
         }
-        __syncthreads();
-        if (tid == 0) s_n_rules += 1;
-        __syncthreads();
+        __syncthreads();                                          // chunk / stride / count are reused by the next base
     }
-    if (tid == 0) {
-        a.n_rules[k] = s_n_rules;
-        a.unexplained[k] = s_total - s_covered;
+    int unexplained = (int)total - (int)covered;
+    for (int off = kWave / 2; off > 0; off >>= 1) unexplained += __shfl_down(unexplained, off);
+    if (lane == 0) {
+        a.n_rules[k] = n_rules;
+        a.unexplained[k] = (uint32_t)unexplained;
     }
 }
 
@@ -247,26 +398,50 @@ __global__ __launch_bounds__(kAnaThreads) void k_analyze(AnaArgs a) {
 
 using namespace msched;
 
+namespace {
+
+// The subset table is written by a kernel the first time a device is used, and waited for, so that later
+// calls on any stream find it complete.
+hipError_t ensure_subset_table(hipStream_t stream) {
+    static std::mutex mu;
+    static bool ready[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (ready[dev]) return hipSuccess;
+    (void)hipGetLastError();
+    k_subset_table<<<MSCHED_MAX_ARGS + 1, kWave, 0, stream>>>();
+    e = hipGetLastError();
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e == hipSuccess) ready[dev] = true;
+    return e;
+}
+
+}  // namespace
+
 extern "C" int msched_analyze(const msched_profile_batch *b, msched_rule *rules, uint32_t *n_rules,
                               uint32_t *unexplained, void *stream) {
     if (!b || !rules || !n_rules || !unexplained) return MSCHED_E_INVAL;
     if (b->n_kernels == 0) return MSCHED_OK;
     if (!b->n_args || !b->int64_mask || !b->args || !b->intervals || !b->n_intervals) return MSCHED_E_INVAL;
     if (b->n_invocations == 0 || b->n_invocations > (uint32_t)kAnaMaxInv || b->max_intervals == 0 ||
-        (uint64_t)b->n_invocations * b->max_intervals > kAnaMaxBits)
+        b->max_intervals > 65535u)
         return MSCHED_E_INVAL;
+    if (((uintptr_t)b->args | (uintptr_t)b->intervals) & 15 || ((uintptr_t)rules & 7)) return MSCHED_E_INVAL;
+    hipError_t e = ensure_subset_table((hipStream_t)stream);
+    if (e != hipSuccess) { g_last_hip = (int)e; return MSCHED_E_HIP; }
     AnaArgs a;
     a.n_inv = b->n_invocations; a.max_iv = b->max_intervals;
     a.n_args = b->n_args; a.int64_mask = b->int64_mask; a.args = b->args; a.iv = b->intervals; a.n_iv = b->n_intervals;
     a.rules = rules; a.n_rules = n_rules; a.unexplained = unexplained;
-    const size_t lds = (size_t)a.n_inv * (MSCHED_MAX_ARGS + 3) * 8 + ((size_t)a.n_inv * a.max_iv + 31) / 32 * 4 +
-                       2 * (size_t)a.n_inv + 16;
+    const size_t lds = (size_t)a.n_inv * ((MSCHED_MAX_ARGS + 3) * 8 + 4 + MSCHED_MAX_ARGS * 2);
     (void)hipGetLastError();
-    hipError_t e = hipSuccess;
     if (lds > 48 * 1024)
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_analyze), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e == hipSuccess) {
-        k_analyze<<<b->n_kernels, kAnaThreads, lds, (hipStream_t)stream>>>(a);
+        k_analyze<<<b->n_kernels, kWave, lds, (hipStream_t)stream>>>(a);
         e = hipGetLastError();
     }
     if (e != hipSuccess) { g_last_hip = (int)e; return MSCHED_E_HIP; }

@@ -82,7 +82,7 @@ def test_argument_errors():
     import paper_2512_24637_amd as M
     d = torch.zeros(1024, dtype=torch.int64, device="cuda:0").data_ptr()
     M.analyze(0, 4, 4, d, d, d, d, d, d, d, d)                       # empty batch: nothing to do
-    for n_inv, max_iv in [(0, 4), (513, 4), (4, 0), (512, 513)]:
+    for n_inv, max_iv in [(0, 4), (513, 4), (4, 0), (4, 65536)]:
         with pytest.raises(M.MSchedError) as e:
             M.analyze(1, n_inv, max_iv, d, d, d, d, d, d, d, d)
         assert e.value.code == -1
