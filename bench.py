@@ -276,7 +276,9 @@ def bench_planning_stress(torch, warmup=8, steps=16, phases=True):
     return out
 
 
-ANALYZER_TRAFFIC_RATIO = None     # set from profiles/k_analyze_pmc_traffic.md once measured
+# k_analyze: 309.7 MB measured (FETCH_SIZE + WRITE_SIZE, calibrated) against 164.3 MB algorithmic per launch
+# (profiles/k_analyze_batch16384_kernel_trace_and_traffic.md).
+ANALYZER_TRAFFIC_RATIO = 1.88
 
 
 def bench_analyzer(torch, base_kernels=256, tile=64, n_inv=64, max_iv=48, reps=20, cpu=True):
@@ -317,6 +319,7 @@ def bench_analyzer(torch, base_kernels=256, tile=64, n_inv=64, max_iv=48, reps=2
            "kernels_per_s": K / (ms / 1e3), "ms_per_batch": ms, "rules_found": found,
            "roofline": {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
                         "traffic": ANALYZER_TRAFFIC_RATIO * alg if ANALYZER_TRAFFIC_RATIO else None,
+                        "traffic_source": "profiles/k_analyze_batch16384_kernel_trace_and_traffic.md",
                         "kernel": "k_analyze", "avg_launch_ms": ms, "algorithmic_bytes_per_launch": alg,
                         "note": "one wavefront per kernel; run time is a chain of dependent loads and LDS passes, "
                                 "hidden only by the other resident wavefronts"}}

@@ -74,13 +74,28 @@ __device__ __forceinline__ bool mul_ok(uint64_t a, uint64_t b, uint64_t &out) {
     return __umul64hi(a, b) == 0;
 }
 
-struct Subset { int n; uint32_t idx[kAnaMaxProd]; };
+// argument indices of a product; plain members so that they stay in registers
+struct Subset {
+    int n = 0;
+    uint32_t a0 = 0, a1 = 0, a2 = 0;
+    __device__ __forceinline__ uint32_t at(int j) const { return j == 0 ? a0 : j == 1 ? a1 : a2; }
+};
+static_assert(kAnaMaxProd == 3, "Subset holds three indices");
+
+// the invocations a subset is screened on; plain members, selected by comparison, so that they stay in registers
+struct Probes {
+    int n = 0;
+    uint32_t i0 = 0, i1 = 0, i2 = 0;
+    __device__ uint32_t at(int t) const { return t == 0 ? i0 : t == 1 ? i1 : i2; }
+};
+static_assert(kAnaProbe == 3, "Probes holds three invocations");
 
 __device__ __forceinline__ bool product_of(const uint64_t *row, const Subset &S, uint64_t &prod) {
     prod = 1;
     bool ok = true;
-    for (int j = 0; j < kAnaMaxProd; ++j)
-        if (j < S.n) ok &= mul_ok(prod, row[S.idx[j]], prod);
+    if (S.n > 0) ok &= mul_ok(prod, row[S.a0], prod);
+    if (S.n > 1) ok &= mul_ok(prod, row[S.a1], prod);
+    if (S.n > 2) ok &= mul_ok(prod, row[S.a2], prod);
     return ok;
 }
 
@@ -96,22 +111,25 @@ struct Analyzer {
     const uint32_t *cand;           // LDS [nc] argument index of each candidate
     uint32_t n_subsets, n_singles;
 
-    __device__ bool used(uint32_t i) const { return !multi_only || count[i] > 1; }
+    __device__ __forceinline__ bool used(uint32_t i) const { return !multi_only || count[i] > 1; }
 
-    __device__ Subset subset(uint32_t rank) const {
+    __device__ __forceinline__ Subset subset(uint32_t rank) const {
         const uint32_t packed = subsets[rank];
         Subset S;
         S.n = (int)(packed >> 24);
-        for (int j = 0; j < kAnaMaxProd; ++j) S.idx[j] = j < S.n ? cand[(packed >> (8 * j)) & 0xff] : 0;
+        S.a0 = S.n > 0 ? cand[packed & 0xff] : 0;
+        S.a1 = S.n > 1 ? cand[(packed >> 8) & 0xff] : 0;
+        S.a2 = S.n > 2 ? cand[(packed >> 16) & 0xff] : 0;
         return S;
     }
 
     // per lane: could value = c * product(args[S]) hold, judging by the probe invocations alone?
-    __device__ bool screen(const Subset &S, const uint32_t *probe, int n_probe) const {
+    __device__ __forceinline__ bool screen(const Subset &S, const Probes &probe) const {
         uint64_t c = 0;
         bool have_c = false;
-        for (int t = 0; t < n_probe; ++t) {
-            const uint32_t i = probe[t];
+        for (int t = 0; t < kAnaProbe; ++t) {
+            if (t >= probe.n) break;
+            const uint32_t i = probe.at(t);
             uint64_t prod, want;
             if (!product_of(s_args + i * MSCHED_MAX_ARGS, S, prod)) return false;
             const uint64_t v = val[i];
@@ -127,7 +145,7 @@ struct Analyzer {
 
     // whole wave, S uniform: the test on every used invocation; the coefficient comes from the first used
     // invocation whose product is not zero
-    __device__ bool verify(const Subset &S, uint64_t &c_out) const {
+    __device__ __forceinline__ bool verify(const Subset &S, uint64_t &c_out) const {
         uint64_t c = 0;
         bool have_c = false;
         for (uint32_t i0 = 0; i0 < n_inv && !have_c; i0 += kWave) {
@@ -161,29 +179,27 @@ struct Analyzer {
     }
 
     // whole wave: the lowest-ranked subset that fits
-    __device__ bool search(Subset &S_out, uint64_t &c_out) const {
-        uint32_t probe[kAnaProbe];
-        int n_probe = 0;
-        for (uint32_t i0 = 0; i0 < n_inv && n_probe < kAnaProbe; i0 += kWave) {
+    __device__ __forceinline__ bool search(Subset &S_out, uint64_t &c_out) const {
+        // screen on the first (up to three) used invocations of the first 64-invocation block that has any
+        Probes probe;
+        for (uint32_t i0 = 0; i0 < n_inv && probe.n == 0; i0 += kWave) {
             const uint32_t i = i0 + lane;
             uint64_t m = __ballot(i < n_inv && used(i));
-            while (m && n_probe < kAnaProbe) {
-                probe[n_probe++] = i0 + __ffsll((unsigned long long)m) - 1;
-                m &= m - 1;
-            }
+            if (m) { probe.i0 = i0 + __ffsll((unsigned long long)m) - 1; probe.n = 1; m &= m - 1; }
+            if (m) { probe.i1 = i0 + __ffsll((unsigned long long)m) - 1; probe.n = 2; m &= m - 1; }
+            if (m) { probe.i2 = i0 + __ffsll((unsigned long long)m) - 1; probe.n = 3; }
         }
-        if (n_probe == 0) return false;
+        if (probe.n == 0) return false;
         // {} first and on its own: most regions have an invariant extent (template T1) and need nothing else;
         // then the single arguments, then pairs and triples a wavefront at a time
         Subset none;
-        none.n = 0; none.idx[0] = none.idx[1] = none.idx[2] = 0;
         if (verify(none, c_out)) { S_out = none; return true; }
         const uint32_t n_cand = n_singles;
         for (uint32_t r0 = 1; r0 < n_subsets;) {
             const uint32_t r1 = min(r0 <= n_cand ? 1 + n_cand : r0 + kWave, n_subsets);
             const uint32_t rank = r0 + lane;
             bool pass = false;
-            if (rank < r1) pass = screen(subset(rank), probe, n_probe);
+            if (rank < r1) pass = screen(subset(rank), probe);
             uint64_t m = __ballot(pass);
             while (m) {
                 const uint32_t best = r0 + __ffsll((unsigned long long)m) - 1;
@@ -216,7 +232,7 @@ static_assert(sizeof(msched_rule) == 48 && offsetof(msched_rule, size_args) == 5
 // the first 24 bytes of a msched_rule as three little-endian words
 __device__ __forceinline__ void rule_words(uint32_t kind, uint32_t base_arg, const Subset &size, const Subset &stride,
                                            const Subset &count, uint64_t w[3]) {
-    auto at = [](const Subset &S, int j) { return (uint64_t)(j < S.n ? S.idx[j] : 0); };
+    auto at = [](const Subset &S, int j) { return (uint64_t)(j < S.n ? S.at(j) : 0); };
     w[0] = kind | (uint64_t)base_arg << 8 | (uint64_t)size.n << 16 | (uint64_t)stride.n << 24 | (uint64_t)count.n << 32 |
            at(size, 0) << 40 | at(size, 1) << 48 | at(size, 2) << 56;
     w[1] = at(stride, 0) << 8 | at(stride, 1) << 16 | at(stride, 2) << 24 | at(count, 0) << 40 | at(count, 1) << 48 |
@@ -251,12 +267,18 @@ __global__ __launch_bounds__(kWave) void k_analyze(AnaArgs a) {
         ulonglong2 *s2 = reinterpret_cast<ulonglong2 *>(s_args);
         const uint32_t n2 = n_inv * (MSCHED_MAX_ARGS / 2);
         for (uint32_t f = lane; f < n2; f += kArgBatch * kWave) {
-            ulonglong2 v[kArgBatch];
-            uint32_t niv = 0;
-            for (uint32_t u = 0; u < kArgBatch; ++u) if (f + u * kWave < n2) v[u] = g_args[f + u * kWave];
+            // every load is issued (at a clamped index) before any is stored: all six are in flight together
+            const ulonglong2 v0 = g_args[min(f, n2 - 1)], v1 = g_args[min(f + kWave, n2 - 1)],
+                             v2 = g_args[min(f + 2 * kWave, n2 - 1)], v3 = g_args[min(f + 3 * kWave, n2 - 1)],
+                             v4 = g_args[min(f + 4 * kWave, n2 - 1)], v5 = g_args[min(f + 5 * kWave, n2 - 1)];
             const uint32_t i = f / (kArgBatch * kWave) * kWave + lane;   // one invocation per lane and trip: 64 rows are 6 * 64 loads
-            if (i < n_inv) niv = g_niv[i];
-            for (uint32_t u = 0; u < kArgBatch; ++u) if (f + u * kWave < n2) s2[f + u * kWave] = v[u];
+            uint32_t niv = g_niv[min(i, n_inv - 1)];
+            s2[f] = v0;
+            if (f + kWave < n2) s2[f + kWave] = v1;
+            if (f + 2 * kWave < n2) s2[f + 2 * kWave] = v2;
+            if (f + 3 * kWave < n2) s2[f + 3 * kWave] = v3;
+            if (f + 4 * kWave < n2) s2[f + 4 * kWave] = v4;
+            if (f + 5 * kWave < n2) s2[f + 5 * kWave] = v5;
             if (i < n_inv) { niv = min(niv, max_iv); s_niv[i] = niv; total += niv; }
         }
     }
@@ -277,11 +299,13 @@ __global__ __launch_bounds__(kWave) void k_analyze(AnaArgs a) {
             const uint32_t sub = lane % kRowLanes;
             uint64_t start[kRowsPerLane];
             uint32_t nn[kRowsPerLane];
+            #pragma unroll
             for (uint32_t p = 0; p < kRowsPerLane; ++p) {
                 const uint32_t i = ib + p * kRowsPerLane + lane / kRowLanes;
                 nn[p] = i < n_inv ? s_niv[i] : 0;
                 start[p] = sub < nn[p] ? g_iv[(size_t)i * max_iv + sub].x : 0;
             }
+            #pragma unroll
             for (uint32_t p = 0; p < kRowsPerLane; ++p) {
                 const uint32_t i = ib + p * kRowsPerLane + lane / kRowLanes;
                 if (sub < nn[p]) match(i, sub, start[p]);
@@ -360,12 +384,16 @@ __global__ __launch_bounds__(kWave) void k_analyze(AnaArgs a) {
         const bool strided = __ballot(any_multi) != 0;
         // 3. templates in order: invariant size, size proportional to arguments, strided
         Subset S_size, S_stride, S_count;
-        S_size.n = S_stride.n = S_count.n = 0;
         uint64_t c_size = 0, c_stride = 0, c_count = 0;
-        an.val = chunk; an.multi_only = false;
-        bool ok = an.search(S_size, c_size);
-        if (ok && strided) { an.val = stride; an.multi_only = true; ok = an.search(S_stride, c_stride); }
-        if (ok && strided) { an.val = count; an.multi_only = false; ok = an.search(S_count, c_count); }
+        bool ok = true;
+        for (int q = 0; q < (strided ? 3 : 1) && ok; ++q) {       // size; then stride and count of a strided region
+            an.val = q == 0 ? chunk : q == 1 ? stride : count;
+            an.multi_only = q == 1;
+            Subset S;
+            uint64_t c = 0;
+            ok = an.search(S, c);
+            if (q == 0) { S_size = S; c_size = c; } else if (q == 1) { S_stride = S; c_stride = c; } else { S_count = S; c_count = c; }
+        }
         if (ok && n_rules < MSCHED_MAX_RULES) {
             uint64_t w[3];
             rule_words(strided ? MSCHED_RULE_STRIDED : (S_size.n == 0 ? MSCHED_RULE_FIXED : MSCHED_RULE_LINEAR), arg,
