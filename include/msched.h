@@ -187,7 +187,8 @@ int msched_get_phase_ms(msched_ctx *ctx, float *ms);
  * Offline memory analyzer (Sec. 5.2, "Memory analyzer"): derive access rules from profiled invocations.
  * A batch holds n_kernels kernels, each with n_invocations profiled invocations.  Per invocation: the
  * launch arguments as 64-bit values (32-bit ones zero-extended), and the byte intervals (start, length)
- * the kernel touched, sorted by start, disjoint and non-adjacent.  All arrays are DEVICE memory, owned by
+ * the kernel touched: one per region a memory instruction covers, regions that begin at the same address merged;
+ * sorted by start, starts distinct; intervals of different buffers may touch or overlap.  All arrays are DEVICE memory, owned by
  * the caller, read only:
  *   n_args      [K]                         arguments per kernel, <= MSCHED_MAX_ARGS
  *   int64_mask  [K]                         bit a set: argument a is a 64-bit integer (a possible pointer)
@@ -207,7 +208,7 @@ int msched_get_phase_ms(msched_ctx *ctx, float *ms);
  * rules 8-byte aligned.  The first call on a device also writes a small constant table and waits for it.
  * Asynchronous on `stream`
  * (a hipStream_t, NULL = the default stream).  Errors: MSCHED_E_INVAL (null pointer, limits), MSCHED_E_HIP.
- * Input that breaks the interval ordering gives unspecified rules but no out-of-bounds access.
+ * Input whose intervals are not sorted by distinct starts gives unspecified rules but no out-of-bounds access.
  */
 typedef struct {
     uint32_t n_kernels, n_invocations, max_intervals, reserved;

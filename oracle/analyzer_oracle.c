@@ -24,8 +24,10 @@
  * at an irregular gap, or where another base pointer points.
  *
  * Input per kernel: n_inv invocations, each with n_args 64-bit argument values and up to max_iv
- * touched byte intervals (start, length), sorted by start, disjoint and non-adjacent (what a profiler
- * that records every accessed address yields after merging neighbouring bytes).
+ * touched byte intervals (start, length), sorted by start, starts distinct: one per region that a memory
+ * instruction of the kernel covers (the profiler instruments every memory instruction and records the
+ * addresses it accesses), regions that begin at the same address merged; intervals of different buffers
+ * may touch or overlap.
  *
  * Pins: tests/test_oracle_analyzer.py (the paper's vector_add / matrix_mul examples, round trips
  * through an independent rule evaluator, exhaustive first-match search, unexplained regions).

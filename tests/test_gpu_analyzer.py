@@ -88,3 +88,94 @@ def test_argument_errors():
         assert e.value.code == -1
     with pytest.raises(M.MSchedError):
         M.analyze(1, 4, 4, d, d, 0, d, d, d, d, d)
+
+
+# ---- closing the loop: templates derived by the analyzer drive the planner like the hand-written ones ----
+
+def _ranges_of(rules, args):
+    """Byte ranges a launch touches under a kernel template (forward evaluation of the rule definition)."""
+    out = []
+    prod = lambda idx: int(np.prod([int(args[j]) for j in idx], dtype=object)) if len(idx) else 1
+    for r in rules:
+        kind, base_arg, s_idx, s_c, t_idx, t_c, c_idx, c_c = r
+        base, size = int(args[base_arg]), s_c * prod(s_idx)
+        if kind in (1, 2):
+            out.append((base, size))
+        else:
+            out += [(base + j * t_c * prod(t_idx), size) for j in range(c_c * prod(c_idx))]
+    return [(a, b) for a, b in out if b > 0]
+
+
+def _merged(ranges):
+    """What the profiler reports: one interval per region a memory instruction covers; regions that begin at
+    the same address become one.  Regions of different buffers stay apart even where they touch or overlap."""
+    out = []
+    for a, b in sorted(ranges):
+        if out and a == out[-1][0]:
+            out[-1] = (a, max(out[-1][1], b))
+        else:
+            out.append((a, b))
+    return out
+
+
+def _pages(ranges, shift):
+    s = set()
+    for a, b in ranges:
+        s.update(range(a >> shift, ((a + b - 1) >> shift) + 1))
+    return s
+
+
+def _as_tuple(r):
+    return (r.kind, r.base_arg, tuple(r.size_args), r.size_coeff, tuple(r.stride_args), r.stride_coeff,
+            tuple(r.count_args), r.count_coeff)
+
+
+@pytest.mark.parametrize("config,kw", [(1, {}), (3, dict(scale=16, n_launches=480)), (4, dict(scale=16, n_launches=512))])
+def test_derived_templates_drive_the_same_plans(oracle_mod, oracle_analyzer, config, kw):
+    import dataclasses
+    from workloads import make_trace, run_schedule
+    from workloads.trace import Rule
+    from gpu_common import GpuSide, make_oracle, assert_same_plan
+    trace = make_trace(config, **kw)
+    hand = [[_as_tuple(r) for r in rules] for rules in trace.kernels]
+    # "profile" every kernel: its launches' arguments and the intervals its template touches
+    launches = {k: [] for k in range(len(hand))}
+    for cmds in trace.tasks:
+        for i in range(len(cmds)):
+            launches[int(cmds.kernel_id[i])].append((int(cmds.n_args[i]), cmds.args[i]))
+    n_inv = min(512, max(len(v) for v in launches.values()))
+    prof = {k: [v[j * len(v) // n_inv] for j in range(n_inv)] for k, v in launches.items() if v}
+    rows = {k: [_merged(_ranges_of(hand[k], a)) for _, a in v] for k, v in prof.items()}
+    K, max_iv = len(hand), max(len(r) for v in rows.values() for r in v)
+    b = AnalyzerBatch(K, n_inv, max_iv, np.zeros(K, np.int32), np.zeros(K, np.uint32),
+                      np.zeros((K, n_inv, MAX_ARGS), np.uint64), np.zeros((K, n_inv, max_iv, 2), np.uint64),
+                      np.zeros((K, n_inv), np.uint32), [[]] * K, np.zeros(K, np.uint32))
+    for k, v in prof.items():
+        b.n_args[k] = v[0][0]
+        b.ptr_mask[k] = (1 << v[0][0]) - 1                  # nothing says which arguments are pointers
+        for i, (_, a) in enumerate(v):
+            b.args[k, i] = a
+            b.n_iv[k, i] = len(rows[k][i])
+            for m, iv in enumerate(rows[k][i]):
+                b.iv[k, i, m] = iv
+    derived = assert_same(b, oracle_analyzer)
+    # the derived templates must predict the pages of every launch, profiled or not
+    for k, v in launches.items():
+        for na, a in v:
+            assert _pages(_ranges_of(derived[k], a), trace.page_shift) == _pages(_ranges_of(hand[k], a), trace.page_shift), (k, a[:na])
+    # and the planner, fed with them, must decide exactly what the oracle decides from the hand-written ones
+    t2 = dataclasses.replace(trace, kernels=[[Rule(*r) for r in rs] for rs in derived])
+    g = GpuSide(t2)
+    o = make_oracle(oracle_mod, trace, with_bytes=False)
+    try:
+        n = 0
+        for ro, rg in zip(run_schedule(trace, o, max_plans=24), run_schedule(t2, g.ms, max_plans=24)):
+            assert_same_plan(ro.plan, rg.plan, (trace.name, "plan", ro.index))
+            pto, foo = o.state()
+            ptg, fog = g.ms.state()
+            assert np.array_equal(pto, ptg) and np.array_equal(foo, fog)
+            n += 1
+        assert n > 3
+    finally:
+        g.close()
+        o.close()

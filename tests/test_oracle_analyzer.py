@@ -173,3 +173,17 @@ def test_derived_rules_reproduce_every_profiled_invocation(ana, vary):
                 if h.kind == STRIDED:
                     continue                              # a count that is always 1 in the sample legitimately degenerates
                 assert r[0] == h.kind and r[1] == h.base_arg and r[2] == h.size_args and r[3] == h.size_coeff, (k, r, h)
+
+
+def test_buffers_that_touch_or_overlap_are_still_told_apart(ana):
+    # A and B are neighbours in memory (B begins where A ends); C overlaps the tail of B.  One interval per
+    # memory instruction, so each pointer still begins an interval and gets its own rule.
+    A = 9 << 40
+    inv = []
+    for n in (3, 8, 5, 13):
+        B = A + 4 * n
+        C = B + 8
+        inv.append(([A, B, C, n], [(A, 4 * n), (B, 64), (C, 16 * n)]))
+    rules, un = ana.analyze(_single_kernel(4, 0b0111, inv))
+    assert rules[0] == [(LINEAR, 0, (3,), 4, (), 0, (), 0), (FIXED, 1, (), 64, (), 0, (), 0), (LINEAR, 2, (3,), 16, (), 0, (), 0)]
+    assert un[0] == 0
