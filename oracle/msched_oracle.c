@@ -82,6 +82,7 @@ typedef struct {
     task_t *tasks; size_t n_tasks, cap_tasks;
     /* last plan */
     int plan_pending;
+    uint32_t mig_done;                 /* fetch entries already carried out by orc_migrate_prefix */
     uint32_t n_fetch, n_evict, n_free_used, g_cut, g_end0, G;
     vec32 fetch_pages, fetch_frames, evict_pages, evict_frames;
     uint32_t *nu;             /* [V] scratch */
@@ -305,6 +306,7 @@ static int cmp_victim(const void *a, const void *b) {     /* next use descending
 /* One context switch: decide what to evict and what to fetch.  State is not changed. */
 int orc_plan(orc_t *o, const uint32_t *tl_task, const uint32_t *tl_slice, uint32_t n_entries) {
     o->plan_pending = 0;
+    o->mig_done = 0;
     for (uint32_t e = 0; e < n_entries; e++) if (tl_task[e] >= o->n_tasks) return E_INVAL;
 
     /* 1. Flatten the timeline into the global order of future commands. */
@@ -409,6 +411,7 @@ static uint64_t slot_of(const orc_t *o, uint32_t page) {
 /* Carry out the pending plan: victims out (unmap, copy to host), then targets in (copy, map). */
 int orc_migrate(orc_t *o) {
     if (!o->plan_pending) return E_STALE;
+    if (o->mig_done) return E_INVAL;                       /* a prefix has been carried out: finish it the same way */
     size_t P = (size_t)1 << o->page_shift;
     for (uint32_t i = 0; i < o->n_evict; i++) {
         uint32_t p = o->evict_pages.v[i], f = o->evict_frames.v[i];
@@ -423,6 +426,43 @@ int orc_migrate(orc_t *o) {
         o->frame_owner[f] = p;
     }
     o->plan_pending = 0;
+    return E_OK;
+}
+
+/* Early execution (Sec. 6.3: pages migrate in predicted access order and a kernel starts as soon as the
+ * pages it depends on are resident).  need[g], g < g_cut: how many leading entries of the fetch list must
+ * have landed before the g-th covered command may start = fetches first used by a command <= g. */
+int orc_ready_need(const orc_t *o, uint32_t *need) {
+    if (!o->plan_pending) return E_STALE;
+    for (uint32_t g = 0; g < o->g_cut; g++) {
+        uint32_t n = 0;
+        for (uint32_t i = 0; i < o->n_fetch; i++) if (o->nu[o->fetch_pages.v[i]] <= g) n++;
+        need[g] = n;
+    }
+    return E_OK;
+}
+
+/* Carry out the pending plan up to and including fetch entry n - 1, entry by entry in list order: the
+ * victim whose frame the entry reuses goes out first, then the target comes in.  Calls continue where the
+ * last one stopped; the plan is done when n reaches n_fetch. */
+int orc_migrate_prefix(orc_t *o, uint32_t n) {
+    if (!o->plan_pending) return E_STALE;
+    if (n > o->n_fetch || n < o->mig_done) return E_INVAL;
+    size_t P = (size_t)1 << o->page_shift;
+    for (uint32_t i = o->mig_done; i < n; i++) {
+        uint32_t p = o->fetch_pages.v[i], f = o->fetch_frames.v[i];
+        if (i >= o->n_free_used) {
+            uint32_t v = o->evict_pages.v[i - o->n_free_used];
+            o->page_table[v] = NONE32;
+            o->frame_owner[f] = NONE32;
+            if (o->pool) memcpy(o->host + slot_of(o, v) * P, o->pool + (size_t)f * P, P);
+        }
+        if (o->pool) memcpy(o->pool + (size_t)f * P, o->host + slot_of(o, p) * P, P);
+        o->page_table[p] = f;
+        o->frame_owner[f] = p;
+    }
+    o->mig_done = n;
+    if (n == o->n_fetch) { o->plan_pending = 0; o->mig_done = 0; }
     return E_OK;
 }
 

@@ -60,6 +60,8 @@ def _load():
     lib.orc_plan_counts.argtypes = [C.c_void_p, C.c_void_p]
     lib.orc_plan_lists.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.orc_migrate.argtypes = [C.c_void_p]
+    lib.orc_ready_need.argtypes = [C.c_void_p, C.c_void_p]
+    lib.orc_migrate_prefix.argtypes = [C.c_void_p, C.c_uint32]
     lib.orc_pagetable_query.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p]
     lib.orc_state.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
     lib.orc_state.restype = None
@@ -194,6 +196,16 @@ class Oracle:
 
     def migrate(self):
         self._check(self.lib.orc_migrate(self.h))
+
+    def ready_need(self, g_cut) -> np.ndarray:
+        """need[g]: leading fetch entries that must have landed before covered command g may start."""
+        out = np.zeros(max(int(g_cut), 1), np.uint32)
+        self._check(self.lib.orc_ready_need(self.h, _ptr(out)))
+        return out[:int(g_cut)]
+
+    def migrate_prefix(self, n):
+        """Carry out the pending plan up to fetch entry n - 1 (in list order)."""
+        self._check(self.lib.orc_migrate_prefix(self.h, int(n)))
 
     def pagetable_query(self, pages) -> np.ndarray:
         pages = np.ascontiguousarray(pages, np.uint64)
