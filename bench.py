@@ -12,6 +12,8 @@ the page structure of the configured workload.  Prints ONE JSON line on stdout.
   roofline_plan the planning kernels against HBM bandwidth on the planning-stress
                 page structure (10 M pages, 4 M frames, 8 M page ids per plan)
   cpu_baseline  the plain CPU oracle timed on a bounded sample of the same schedule
+  early_start   early execution on the LLM-decode schedule: copy rate with the in-order landing switched on,
+                and when each covered launch could start, against the end of the whole migration
   analyzer      the offline memory analyzer (msched_analyze) on a batch of profiled kernels: kernels per
                 second, its roofline against HBM bandwidth and the CPU oracle on a sample of the batch
 """
@@ -338,6 +340,71 @@ def bench_analyzer(torch, base_kernels=256, tile=64, n_inv=64, max_iv=48, reps=2
     return out
 
 
+def bench_early_start(torch, switches=8, warm=2):
+    """LLM-decode schedule (config 4) with 512 KiB pages, i.e. the same page structure at a quarter of the bytes:
+    every launch of a decode step needs one more layer's weights, so readiness grows along the fetch list."""
+    from workloads import make_trace
+    from workloads.device import DeviceBuffers
+    from paper_2512_24637_amd import MSched
+    trace = make_trace(4, page_shift=19, steps=4 * (switches + 2))
+    out = {"workload": "c4-llm-decode page structure with 512 KiB pages (pool 4 GiB, 6656 pages in, 6656 out per switch)"}
+    for early in (False, True):
+        buf, ms = make_context(torch, trace, fill_contents=False)
+        ms.set_early_start(early)
+        main = torch.cuda.current_stream()
+        rates, first_ms, mean_frac, total_ms, ramp_frac, ramp_len = [], [], [], [], [], []
+        cursor = [0] * trace.n_tasks
+        for sw in range(switches):
+            t = sw % trace.n_tasks
+            p = ms.plan([((t + k) % trace.n_tasks, trace.timeslice) for k in range(trace.n_tasks)])
+            need = ms.ready_need(p) if early else None
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            t0 = time.perf_counter()
+            ms.migrate_only(p)
+            e1.record()
+            seen = []
+            if early:
+                while True:
+                    v = ms.progress()
+                    now = time.perf_counter() - t0
+                    seen.append((now, v))
+                    if main.query():
+                        break
+            torch.cuda.synchronize()
+            dur = e0.elapsed_time(e1)
+            if sw >= warm and p.n_fetch:
+                rates.append((p.n_fetch + p.n_evict) * trace.page_bytes / dur / 1e6)
+                total_ms.append(dur)
+                if early:
+                    ts = np.array([a for a, _ in seen]) * 1e3
+                    vs = np.array([v for _, v in seen])
+                    ready = ts[np.minimum(np.searchsorted(vs, need, side="left"), len(ts) - 1)]   # first poll that saw need[g]
+                    ready = np.minimum(ready, dur)
+                    first_ms.append(float(ready[0]))
+                    mean_frac.append(float(np.mean(ready) / dur))
+                    ramp = int(np.searchsorted(need, p.n_fetch, side="left")) + 1     # launches before everything is needed
+                    ramp_frac.append(float(np.mean(ready[:ramp]) / dur))
+                    ramp_len.append(ramp)
+            ms.launch_retire(t, p.covered_launches)
+        key = "early" if early else "plain"
+        out[f"migrate_gbps_{key}"] = float(np.mean(rates))
+        out[f"migrate_ms_{key}"] = float(np.mean(total_ms))
+        if early:
+            out["first_launch_ready_ms"] = float(np.mean(first_ms))
+            out["mean_launch_ready_fraction"] = float(np.mean(mean_frac))
+            out["first_pass_launches"] = float(np.mean(ramp_len))
+            out["first_pass_mean_ready_fraction"] = float(np.mean(ramp_frac))
+            out["note"] = ("ready = first progress poll (about 2 ms apart) that saw need[g] entries landed; fraction = mean over "
+                           "the covered launches of ready time / whole migration; first pass = the launches up to the first "
+                           "that needs the whole fetch list (one decode step; later steps reuse its pages); without early "
+                           "execution every launch waits for the whole migration (fraction 1)")
+        ms.close()
+        buf.release()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -350,6 +417,8 @@ def main():
                     help="run only the planning-stress leg (for profiling the planning kernels)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-analyzer", action="store_true", help="skip the memory-analyzer leg")
+    ap.add_argument("--no-early-start", action="store_true", help="skip the early-execution leg")
+    ap.add_argument("--early-start-only", action="store_true", help="run only the early-execution leg")
     ap.add_argument("--analyzer-only", action="store_true",
                     help="run only the memory-analyzer leg (for profiling k_analyze)")
     ap.add_argument("--cpu-sample-steps", type=int, default=480)
@@ -372,6 +441,13 @@ def main():
                           "roofline": r}), flush=True)
         return
 
+    if args.early_start_only:
+        r = bench_early_start(torch)
+        print(json.dumps({"metric": "migrated GB/s with early execution; mean launch-ready time / migration time",
+                          "value": r["migrate_gbps_early"], "unit": "GB/s", "n_gpus": 1, "higher_is_better": True,
+                          "data": "synthetic", "dtype": "u8", "config": {"workload": r["workload"]}, "early_start": r}),
+              flush=True)
+        return
     if args.analyzer_only:
         r = bench_analyzer(torch, reps=max(1, min(args.steps, 20)), cpu=not args.no_cpu_baseline)
         print(json.dumps({"metric": "profiled kernels analyzed per second", "value": r["kernels_per_s"],
@@ -444,6 +520,8 @@ def main():
     }
     if not args.no_plan_stress:
         result["roofline_plan"] = bench_planning_stress(torch)
+    if not args.no_early_start:
+        result["early_start"] = bench_early_start(torch)
     if not args.no_analyzer:
         result["analyzer"] = bench_analyzer(torch, cpu=not args.no_cpu_baseline)
     if not args.no_cpu_baseline:

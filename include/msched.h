@@ -184,6 +184,26 @@ int msched_set_profiling(msched_ctx *ctx, int level);
 int msched_get_phase_ms(msched_ctx *ctx, float *ms);
 
 /*
+ * Early execution (Sec. 6.3: pages migrate in predicted access order, and a kernel starts as soon as the pages
+ * it depends on are resident instead of waiting for the whole working set).
+ * With early start enabled, msched_plan also computes need[g] for every covered command g: the number of
+ * leading fetch-list entries that hold the pages commands 0..g use; and the kernel of msched_migrate
+ * publishes `landed`, the number of leading fetch entries that are complete (bytes in the frame, victim's
+ * bytes in the host store, page table updated), advancing strictly in list order.  Command g may be
+ * submitted once landed >= need[g]; after the migration, landed == n_fetch.
+ *   msched_set_early_start   enable != 0 switches it on for later plans and migrations (off by default: the
+ *                            in-order bookkeeping costs a fence and a few atomics per copied chunk).
+ *   msched_plan_ready_need   need: HOST, covered_launches entries; E_STALE_PLAN unless `plan` is the latest
+ *                            plan and was made with early start enabled.
+ *   msched_progress          *landed of the latest early migration (0 before the first).  Does not wait for
+ *                            the migration: it runs a one-thread kernel on a stream of its own and waits
+ *                            for that.  Data of landed entries is visible to kernels launched afterwards.
+ */
+int msched_set_early_start(msched_ctx *ctx, int enable);
+int msched_plan_ready_need(msched_ctx *ctx, const msched_plan_t *plan, uint32_t *need);
+int msched_progress(msched_ctx *ctx, uint32_t *landed);
+
+/*
  * Offline memory analyzer (Sec. 5.2, "Memory analyzer"): derive access rules from profiled invocations.
  * A batch holds n_kernels kernels, each with n_invocations profiled invocations.  Per invocation: the
  * launch arguments as 64-bit values (32-bit ones zero-extended), and the byte intervals (start, length)

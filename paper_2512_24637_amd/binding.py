@@ -16,7 +16,7 @@ EXPORTED_SYMBOLS = (
     "msched_launch_enqueue", "msched_launch_retire", "msched_plan", "msched_migrate",
     "msched_pagetable_query", "msched_plan_copy_lists", "msched_state_copy",
     "msched_set_profiling", "msched_get_phase_ms", "msched_strerror", "msched_last_hip_error",
-    "msched_analyze",
+    "msched_analyze", "msched_set_early_start", "msched_plan_ready_need", "msched_progress",
 )
 
 
@@ -101,6 +101,9 @@ def load_library():
         "msched_get_phase_ms": [vp, vp],
         "msched_last_hip_error": [vp],
         "msched_analyze": [C.POINTER(_ProfileBatch), vp, vp, vp, vp],
+        "msched_set_early_start": [vp, C.c_int],
+        "msched_plan_ready_need": [vp, C.POINTER(_Plan), vp],
+        "msched_progress": [vp, C.POINTER(u32)],
     }
     for name, argtypes in sig.items():
         fn = getattr(lib, name)
@@ -245,6 +248,21 @@ class MSched:
         self._check(self.lib.msched_plan_copy_lists(self.h, C.byref(plan._raw), _np_ptr(ep), _np_ptr(ef),
                                                     _np_ptr(fp), _np_ptr(ff)))
         return ep[:ne], ef[:ne], fp[:nf], ff[:nf]
+
+    def set_early_start(self, enable: bool):
+        self._check(self.lib.msched_set_early_start(self.h, int(bool(enable))))
+
+    def ready_need(self, plan: Plan) -> np.ndarray:
+        """need[g] for the covered commands of the latest plan (early start must be on)."""
+        out = np.zeros(max(plan.covered_launches, 1), np.uint32)
+        self._check(self.lib.msched_plan_ready_need(self.h, C.byref(plan._raw), _np_ptr(out)))
+        return out[:plan.covered_launches]
+
+    def progress(self) -> int:
+        """Leading fetch entries of the latest early migration that have landed; does not wait for it."""
+        v = C.c_uint32(0)
+        self._check(self.lib.msched_progress(self.h, C.byref(v)))
+        return int(v.value)
 
     def pagetable_query(self, pages) -> np.ndarray:
         pages = np.ascontiguousarray(pages, np.uint64)

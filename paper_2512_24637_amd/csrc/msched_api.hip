@@ -122,6 +122,10 @@ void free_ctx(msched_ctx *c) {
                    c->query_buf, c->cmd_dev, c->list_bucket_fill, c->list_pairs};
     for (void *p : dev) if (p) (void)hipFree(p);
     if (c->hdr_host) (void)hipHostFree(c->hdr_host);
+    if (c->poll_stream) { (void)hipStreamSynchronize(c->poll_stream); (void)hipStreamDestroy(c->poll_stream); }
+    for (void *p : {(void *)c->page_done, (void *)c->chunks_done, (void *)c->landed}) if (p) (void)hipFree(p);
+    if (c->need_host) (void)hipHostFree(c->need_host);
+    if (c->progress_host) (void)hipHostFree(c->progress_host);
     if (c->cmd_ptrs_host) (void)hipHostFree((void *)c->cmd_ptrs_host);
     for (auto &e : c->ev) if (e) (void)hipEventDestroy(e);
     delete c;
@@ -156,6 +160,7 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     c->stream = (hipStream_t)cfg->stream;
     c->V = cfg->n_virtual_pages; c->F = cfg->n_frames; c->page_shift = cfg->page_shift;
     c->migrate_chunk_shift = (uint32_t)env_u32("MSCHED_MIGRATE_CHUNK_SHIFT", 6, 24, 21);
+    c->early_chunk_shift = (uint32_t)env_u32("MSCHED_EARLY_CHUNK_SHIFT", 12, 24, 16);
     c->migrate_max_blocks = (uint32_t)env_u32("MSCHED_MIGRATE_BLOCKS", 1, 1 << 20, 512);
     c->migrate_hints = (uint32_t)env_u32("MSCHED_MIGRATE_HINTS", 0, 3, 0);
     c->expand_split = (uint32_t)env_u32("MSCHED_EXPAND_SPLIT", 1, 64, 0);
@@ -415,6 +420,8 @@ int msched_plan(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entri
     out->n_fetch = h.n_fetch; out->n_evict = h.n_evict; out->n_free_used = h.n_free_used;
     out->g_cut = h.g_cut; out->covered_launches = h.g_cut;
     out->plan_id = ++c->plan_seq;
+    c->plan_early = c->early;
+    c->early_tag = (uint32_t)out->plan_id ? (uint32_t)out->plan_id : 1u;
     c->pending_plan = out->plan_id;
     c->pending = h;
     return MSCHED_OK;
@@ -428,6 +435,42 @@ int msched_migrate(msched_ctx *c, const msched_plan_t *plan) {
     if (c->profiling) { HIP_TRY(c, hipEventRecord(c->ev[6], c->stream)); c->migrate_timed = 1; }
     c->n_resident += c->pending.n_free_used;
     c->pending_plan = 0;
+    return MSCHED_OK;
+}
+
+int msched_set_early_start(msched_ctx *c, int enable) {
+    if (!c) return MSCHED_E_INVAL;
+    if (enable && !c->landed) {                              // first use: bookkeeping of the in-order landing
+        HIP_TRY(c, hipMalloc((void **)&c->page_done, (size_t)c->F * 4));
+        HIP_TRY(c, hipMalloc((void **)&c->chunks_done, (size_t)c->F * 4));
+        HIP_TRY(c, hipMalloc((void **)&c->landed, 256));
+        HIP_TRY(c, hipMemset(c->page_done, 0, (size_t)c->F * 4));
+        HIP_TRY(c, hipMemset(c->chunks_done, 0, (size_t)c->F * 4));
+        HIP_TRY(c, hipMemset(c->landed, 0, 256));
+        HIP_TRY(c, hipHostMalloc((void **)&c->need_host, (MSCHED_MAX_TIMELINE_COMMANDS + 1) * 4, hipHostMallocDefault));
+        HIP_TRY(c, hipHostMalloc((void **)&c->progress_host, 64, hipHostMallocDefault));
+        *c->progress_host = 0;
+        HIP_TRY(c, hipStreamCreateWithFlags(&c->poll_stream, hipStreamNonBlocking));
+        HIP_TRY(c, launch_peek(c));                          // the first launch on a stream sets up its queue: not during a migration
+        HIP_TRY(c, hipDeviceSynchronize());
+    }
+    c->early = enable ? 1 : 0;
+    return MSCHED_OK;
+}
+
+int msched_plan_ready_need(msched_ctx *c, const msched_plan_t *plan, uint32_t *need) {
+    if (!c || !plan || (plan->covered_launches && !need)) return MSCHED_E_INVAL;
+    if (plan->plan_id != c->plan_seq || !c->plan_early) return MSCHED_E_STALE_PLAN;
+    memcpy(need, c->need_host, (size_t)plan->covered_launches * 4);   // written by the plan's kernels, which have finished
+    return MSCHED_OK;
+}
+
+int msched_progress(msched_ctx *c, uint32_t *landed) {
+    if (!c || !landed) return MSCHED_E_INVAL;
+    if (!c->landed) { *landed = 0; return MSCHED_OK; }
+    HIP_TRY(c, launch_peek(c));
+    HIP_TRY(c, hipStreamSynchronize(c->poll_stream));
+    *landed = *c->progress_host;
     return MSCHED_OK;
 }
 

@@ -74,6 +74,7 @@ struct msched_ctx {
     uint32_t F, page_shift;
     void *host_dev = nullptr;                   // device address of cfg.host_store
     uint32_t migrate_chunk_shift = 21;          // bytes a workgroup moves per work unit (log2), at most a page
+    uint32_t early_chunk_shift = 16;            // the same under early execution: small, so that entries complete in list order
     uint32_t migrate_max_blocks = 512;          // grid cap of the copy kernel (two workgroups per CU measured best)
     uint32_t migrate_hints = 0;                 // bit 0: plain host stores, bit 1: plain host loads (default: non-temporal)
     uint32_t expand_split = 0;                  // workgroups per (command, rule); 0 = by page-table size
@@ -110,6 +111,16 @@ struct msched_ctx {
     uint64_t plan_seq = 0, pending_plan = 0;    // pending_plan == 0: nothing to migrate
     msched::PlanHeader pending{};
     uint32_t *query_buf = nullptr; size_t query_cap = 0;     // device scratch for pagetable_query
+    // early execution: in-order landing of the fetch list
+    int early = 0;                              // msched_set_early_start
+    uint32_t *need_host = nullptr;              // pinned [MAX_G + 1]: need[g] of the latest plan (written by the cut kernel)
+    uint32_t *page_done = nullptr;              // device [F]: tag of the migration that completed fetch entry i
+    uint32_t *chunks_done = nullptr;            // device [F]: chunks of entry i copied so far (zero between migrations)
+    uint32_t *landed = nullptr;                 // device: [0] leading fetch entries complete, [1] work units handed out
+    uint32_t *progress_host = nullptr;          // pinned: where msched_progress reads `landed` into
+    hipStream_t poll_stream = nullptr;          // msched_progress works here, beside the migration
+    uint32_t early_tag = 0;                     // nonzero tag of the latest early migration
+    int plan_early = 0;                         // the latest plan computed need[] and reset landed
     int profiling = 0;
     int migrate_timed = 0;                      // ev[5], ev[6] have been recorded
     hipEvent_t ev[8] = {};
@@ -127,6 +138,7 @@ void plan_geometry(const msched_ctx *c, uint32_t G, PlanGeom &g);
 hipError_t launch_migrate(msched_ctx *c, const PlanHeader &h);
 hipError_t launch_query(msched_ctx *c, const uint32_t *ids_dev, uint32_t n, uint32_t *out_dev);
 hipError_t launch_init_tables(msched_ctx *c);
+hipError_t launch_peek(msched_ctx *c);      // landed -> progress_host on the poll stream
 
 extern int g_last_hip;                        // hipError_t of the last failed HIP call of any context
 

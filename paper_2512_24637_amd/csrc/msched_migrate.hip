@@ -25,17 +25,37 @@ struct MigrateArgs {
     uint32_t chunk_shift;          // log2(bytes one workgroup moves per unit)
     uint32_t hints;                // bit 0: plain (not non-temporal) host stores, bit 1: plain host loads
     uint64_t n_units;              // n_fetch << (page_shift - chunk_shift)
+    // early execution (all null / 0 when it is off)
+    uint32_t *page_done, *chunks_done, *landed;
+    uint32_t early_tag;
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kLanesBytes = 16;    // one dwordx4 per lane
 constexpr int kBatch = 4;          // independent 16-byte transfers in flight per lane and direction
 
+// kEarly: early execution.  Entries are declared complete one by one while the kernel runs, so a frame's bytes
+// must be in memory, not dirty in this XCD's L2, when that happens.  A release fence at device scope would
+// write the whole L2 back each time (measured: a third of the copy rate lost); instead the frame is written
+// with write-through stores (system-scope relaxed atomic stores of 8 bytes), and waiting for the stores'
+// acknowledgements is then all the release that is needed.
+template <bool kEarly>
 __global__ __launch_bounds__(256) void k_migrate(MigrateArgs a) {
     const uint32_t cpp_shift = a.page_shift - a.chunk_shift;
     const uint32_t chunk_bytes = 1u << a.chunk_shift;
     const uint32_t sweep = 256 * kLanesBytes;                  // bytes one pass of the workgroup covers
-    for (uint64_t unit = blockIdx.x; unit < a.n_units; unit += gridDim.x) {
+    __shared__ uint32_t s_unit;
+    for (uint64_t unit = blockIdx.x;; unit += gridDim.x) {
+        if (kEarly) {
+            // Units are handed out in list order from a counter (landed[1]), not dealt round-robin: workgroups
+            // get uneven shares of the host link, and a fixed deal would let the slowest one hold `landed` back
+            // while the others run far ahead.
+            __syncthreads();
+            if (threadIdx.x == 0) s_unit = __hip_atomic_fetch_add(a.landed + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            unit = s_unit;
+        }
+        if (unit >= a.n_units) break;
         const uint32_t i = (uint32_t)(unit >> cpp_shift);
         const uint64_t chunk_off = (unit & ((1ull << cpp_shift) - 1)) << a.chunk_shift;
         const uint32_t frame = a.fetch_frames[i];
@@ -74,15 +94,61 @@ __global__ __launch_bounds__(256) void k_migrate(MigrateArgs a) {
 #pragma unroll
             for (int u = 0; u < kBatch; ++u) {
                 const uint32_t off = off0 + u * sweep;
-                if (off < chunk_bytes) *reinterpret_cast<u32x4 *>(fr + off) = in[u];
+                if (off < chunk_bytes) {
+                    if (kEarly) {
+                        uint64_t *q = reinterpret_cast<uint64_t *>(fr + off);
+                        __hip_atomic_store(q, (uint64_t)in[u].x | (uint64_t)in[u].y << 32, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                        __hip_atomic_store(q + 1, (uint64_t)in[u].z | (uint64_t)in[u].w << 32, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                    } else {
+                        *reinterpret_cast<u32x4 *>(fr + off) = in[u];
+                    }
+                }
             }
         }
-        if (chunk_off == 0 && threadIdx.x == 0) {              // unmap the victim, map the target
-            if (swap) a.page_table[vpage] = kNone;
-            a.page_table[fpage] = frame;
-            a.frame_owner[frame] = fpage;
+        if (!kEarly) {
+            if (chunk_off == 0 && threadIdx.x == 0) {          // unmap the victim, map the target
+                if (swap) a.page_table[vpage] = kNone;
+                a.page_table[fpage] = frame;
+                a.frame_owner[frame] = fpage;
+            }
+            continue;
+        }
+        // Early execution: declare the entry complete and move `landed` over every leading complete entry.
+        // All atomics below are relaxed and write through to the device's coherence point; program order between
+        // them is kept by waiting for each to be acknowledged (the workgroup-scope fences are those waits).
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this lane's stores have been acknowledged
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            bool complete = true;
+            if (cpp_shift) {                                   // the workgroup that copies the last chunk completes the entry
+                complete = __hip_atomic_fetch_add(&a.chunks_done[i], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1 == (1u << cpp_shift);
+                if (complete) __hip_atomic_store(&a.chunks_done[i], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next migration
+            }
+            if (complete) {
+                if (swap) __hip_atomic_store(&a.page_table[vpage], kNone, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                __hip_atomic_store(&a.page_table[fpage], frame, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                __hip_atomic_store(&a.frame_owner[frame], fpage, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                // "mine is done" then "how far are we", against "we are this far" then "is the next one done":
+                // with each step acknowledged before the next is issued, one of two workgroups sees the other's write
+                __hip_atomic_store(&a.page_done[i], a.early_tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                uint32_t p = __hip_atomic_load(a.landed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                while (p < a.n_fetch &&
+                       __hip_atomic_load(&a.page_done[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.early_tag) {
+                    uint32_t expected = p;                     // landed only grows: a failed exchange returns a larger value
+                    if (__hip_atomic_compare_exchange_strong(a.landed, &expected, p + 1, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                             __HIP_MEMORY_SCOPE_AGENT))
+                        p = p + 1;
+                    else
+                        p = expected;
+                }
+            }
         }
     }
+}
+
+__global__ void k_peek(const uint32_t *landed, uint32_t *out) {
+    *out = __hip_atomic_load(landed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __global__ __launch_bounds__(256) void k_fill_u32(uint32_t *dst, uint64_t n, uint32_t v) {
@@ -124,9 +190,25 @@ hipError_t launch_migrate(msched_ctx *c, const PlanHeader &h) {
     a.n_fetch = h.n_fetch; a.n_free_used = h.n_free_used; a.page_shift = c->page_shift;
     a.chunk_shift = std::min<uint32_t>(c->page_shift, c->migrate_chunk_shift);
     a.hints = c->migrate_hints;
+    a.page_done = a.chunks_done = a.landed = nullptr; a.early_tag = 0;
+    if (c->early && c->plan_early) {
+        // Workgroups take consecutive chunks, so with chunks much smaller than the whole transfer the
+        // entries are worked on, and complete, in list order.
+        a.chunk_shift = std::min<uint32_t>(c->page_shift, c->early_chunk_shift);
+        while (((uint64_t)h.n_fetch << (a.page_shift - a.chunk_shift)) >> 31) ++a.chunk_shift;   // the unit counter has 32 bits
+        a.page_done = c->page_done; a.chunks_done = c->chunks_done; a.landed = c->landed;
+        a.early_tag = c->early_tag;
+    }
     a.n_units = (uint64_t)h.n_fetch << (a.page_shift - a.chunk_shift);
     const uint64_t blocks = std::min<uint64_t>(a.n_units, c->migrate_max_blocks);
-    k_migrate<<<(uint32_t)blocks, 256, 0, c->stream>>>(a);
+    if (a.landed) k_migrate<true><<<(uint32_t)blocks, 256, 0, c->stream>>>(a);
+    else k_migrate<false><<<(uint32_t)blocks, 256, 0, c->stream>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_peek(msched_ctx *c) {
+    (void)hipGetLastError();
+    k_peek<<<1, 1, 0, c->poll_stream>>>(c->landed, c->progress_host);
     return hipGetLastError();
 }
 

@@ -525,6 +525,7 @@ struct CutArgs {
     uint32_t *groups; uint32_t n_groups, G, g_end0, F;
     uint32_t *flags, *offsets;
     PlanHeader *hdr_dev, *hdr_host;
+    uint32_t *need_host, *landed;      // early execution (both null when it is off)
 };
 
 __device__ void cut_body(const CutArgs &a, uint32_t *lds) {
@@ -564,6 +565,10 @@ __device__ void cut_body(const CutArgs &a, uint32_t *lds) {
     __syncthreads();
     uint32_t n_fetch = block_exclusive_scan(sc, K, wave_sums);
     for (uint32_t c = tid; c < K; c += nthreads) a.offsets[c] = (c < g_cut) ? sc[c] : kSkip;
+    // early execution: command c may start once the fetches of classes 0..c have landed
+    if (a.need_host)
+        for (uint32_t c = tid; c < g_cut; c += nthreads) a.need_host[c] = sc[c] + tot[c];
+    if (a.landed && tid == 0) { a.landed[0] = 0; a.landed[1] = 0; }   // entries landed, work units handed out
     __syncthreads();
     // victim offsets, farthest next use first
     for (uint32_t j = tid; j < K; j += nthreads) sc[j] = (G - j >= g_cut) ? tot[K + (G - j)] : 0;
@@ -803,6 +808,7 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     ca.groups = few_rows ? c->matrix : c->partial; ca.n_groups = few_rows ? g.n_chunks : kRowGroups;
     ca.G = g.G; ca.g_end0 = g.g_end0; ca.F = c->F; ca.flags = c->flags; ca.offsets = c->offsets;
     ca.hdr_dev = c->hdr_dev; ca.hdr_host = c->hdr_host;
+    ca.need_host = c->early ? c->need_host : nullptr; ca.landed = c->early ? c->landed : nullptr;
     EmitArgs ea;
     ea.page_table = c->page_table; ea.nu = c->nu; ea.matrix = c->matrix; ea.offsets = c->offsets; ea.hdr = c->hdr_dev;
     ea.fetch_pages = c->fetch_pages; ea.evict_pages = c->evict_pages; ea.evict_frames = c->evict_frames;

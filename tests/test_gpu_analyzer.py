@@ -130,7 +130,7 @@ def _as_tuple(r):
             tuple(r.count_args), r.count_coeff)
 
 
-@pytest.mark.parametrize("config,kw", [(1, {}), (3, dict(scale=16, n_launches=480)), (4, dict(scale=16, n_launches=512))])
+@pytest.mark.parametrize("config,kw", [(1, {}), (3, dict(scale=16, n_launches=480)), (4, dict(page_shift=16, n_launches=512))])
 def test_derived_templates_drive_the_same_plans(oracle_mod, oracle_analyzer, config, kw):
     import dataclasses
     from workloads import make_trace, run_schedule

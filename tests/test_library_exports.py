@@ -35,6 +35,7 @@ def test_struct_layouts_match_the_header():
     assert C.sizeof(b._TimelineEntry) == 8
     assert C.sizeof(b._Plan) == 72
     assert C.sizeof(b._Config) == 56
+    assert C.sizeof(b._ProfileBatch) == 56
 
 
 def test_create_refuses_bad_configurations_before_touching_the_gpu():

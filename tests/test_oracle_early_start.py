@@ -26,7 +26,7 @@ def _need_by_definition(o, rec, pt_before):
     return np.array(need, np.uint32), missing
 
 
-@pytest.mark.parametrize("config,kw", [(1, {}), (3, dict(scale=32, n_launches=192)), (4, dict(scale=32, n_launches=256))])
+@pytest.mark.parametrize("config,kw", [(1, {}), (3, dict(scale=32, n_launches=192)), (4, dict(page_shift=15, n_launches=256))])
 def test_need_counts_the_missing_pages_of_the_commands_so_far(oracle_mod, config, kw):
     trace = make_trace(config, **kw)
     o = _schedule(oracle_mod, trace)
