@@ -161,6 +161,7 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     c->V = cfg->n_virtual_pages; c->F = cfg->n_frames; c->page_shift = cfg->page_shift;
     c->migrate_chunk_shift = (uint32_t)env_u32("MSCHED_MIGRATE_CHUNK_SHIFT", 6, 24, 21);
     c->early_chunk_shift = (uint32_t)env_u32("MSCHED_EARLY_CHUNK_SHIFT", 12, 24, 16);
+    c->migrate_ticket = (uint32_t)env_u32("MSCHED_MIGRATE_TICKET", 0, 1, 0);
     c->migrate_max_blocks = (uint32_t)env_u32("MSCHED_MIGRATE_BLOCKS", 1, 1 << 20, 512);
     c->migrate_hints = (uint32_t)env_u32("MSCHED_MIGRATE_HINTS", 0, 3, 0);
     c->expand_split = (uint32_t)env_u32("MSCHED_EXPAND_SPLIT", 1, 64, 0);

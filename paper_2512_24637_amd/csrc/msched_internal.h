@@ -74,6 +74,7 @@ struct msched_ctx {
     uint32_t F, page_shift;
     void *host_dev = nullptr;                   // device address of cfg.host_store
     uint32_t migrate_chunk_shift = 21;          // bytes a workgroup moves per work unit (log2), at most a page
+    uint32_t migrate_ticket = 0;                // hand work units out from a counter instead of dealing them round-robin
     uint32_t early_chunk_shift = 16;            // the same under early execution: small, so that entries complete in list order
     uint32_t migrate_max_blocks = 512;          // grid cap of the copy kernel (two workgroups per CU measured best)
     uint32_t migrate_hints = 0;                 // bit 0: plain host stores, bit 1: plain host loads (default: non-temporal)

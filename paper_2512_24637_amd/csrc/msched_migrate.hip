@@ -28,6 +28,7 @@ struct MigrateArgs {
     // early execution (all null / 0 when it is off)
     uint32_t *page_done, *chunks_done, *landed;
     uint32_t early_tag;
+    uint32_t *ticket;              // work-unit counter (zero at launch) when units are handed out in order
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -39,19 +40,19 @@ constexpr int kBatch = 4;          // independent 16-byte transfers in flight pe
 // write the whole L2 back each time (measured: a third of the copy rate lost); instead the frame is written
 // with write-through stores (system-scope relaxed atomic stores of 8 bytes), and waiting for the stores'
 // acknowledgements is then all the release that is needed.
-template <bool kEarly>
+template <bool kEarly, bool kTicket>
 __global__ __launch_bounds__(256) void k_migrate(MigrateArgs a) {
     const uint32_t cpp_shift = a.page_shift - a.chunk_shift;
     const uint32_t chunk_bytes = 1u << a.chunk_shift;
     const uint32_t sweep = 256 * kLanesBytes;                  // bytes one pass of the workgroup covers
     __shared__ uint32_t s_unit;
     for (uint64_t unit = blockIdx.x;; unit += gridDim.x) {
-        if (kEarly) {
-            // Units are handed out in list order from a counter (landed[1]), not dealt round-robin: workgroups
+        if (kTicket) {
+            // Units are handed out in list order from a counter, not dealt round-robin: workgroups
             // get uneven shares of the host link, and a fixed deal would let the slowest one hold `landed` back
             // while the others run far ahead.
             __syncthreads();
-            if (threadIdx.x == 0) s_unit = __hip_atomic_fetch_add(a.landed + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (threadIdx.x == 0) s_unit = __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __syncthreads();
             unit = s_unit;
         }
@@ -201,8 +202,10 @@ hipError_t launch_migrate(msched_ctx *c, const PlanHeader &h) {
     }
     a.n_units = (uint64_t)h.n_fetch << (a.page_shift - a.chunk_shift);
     const uint64_t blocks = std::min<uint64_t>(a.n_units, c->migrate_max_blocks);
-    if (a.landed) k_migrate<true><<<(uint32_t)blocks, 256, 0, c->stream>>>(a);
-    else k_migrate<false><<<(uint32_t)blocks, 256, 0, c->stream>>>(a);
+    a.ticket = a.landed ? a.landed + 1 : c->flags + 1;
+    if (a.landed) k_migrate<true, true><<<(uint32_t)blocks, 256, 0, c->stream>>>(a);
+    else if (c->migrate_ticket) k_migrate<false, true><<<(uint32_t)blocks, 256, 0, c->stream>>>(a);
+    else k_migrate<false, false><<<(uint32_t)blocks, 256, 0, c->stream>>>(a);
     return hipGetLastError();
 }
 

@@ -577,7 +577,8 @@ __device__ void cut_body(const CutArgs &a, uint32_t *lds) {
     for (uint32_t c = tid; c < K; c += nthreads) a.offsets[K + c] = (c >= g_cut) ? sc[G - c] : kSkip;
     if (tid == 0) {
         uint32_t status = *a.flags;
-        *a.flags = 0;                                       // clean for the next plan's expansion
+        a.flags[0] = 0;                                     // clean for the next plan's expansion
+        a.flags[1] = 0;                                     // work-unit counter of the migration that follows
         if (g_end0 > 0 && g_cut == 0) status |= kStatWset;
         if (status) n_fetch = 0;
         const uint32_t n_free = a.F - n_res;
