@@ -14,6 +14,8 @@ the page structure of the configured workload.  Prints ONE JSON line on stdout.
   cpu_baseline  the plain CPU oracle timed on a bounded sample of the same schedule
   early_start   early execution on the LLM-decode schedule: copy rate with the in-order landing switched on,
                 and when each covered launch could start, against the end of the whole migration
+  priority      real-time inference preempting best-effort training under the priority policy (latency-weighted
+                timelines): what a request's context switch costs (plan + restore of its working set)
   analyzer      the offline memory analyzer (msched_analyze) on a batch of profiled kernels: kernels per
                 second, its roofline against HBM bandwidth and the CPU oracle on a sample of the batch
 """
@@ -83,6 +85,9 @@ class TimedImpl:
 
     def launch_retire(self, task, n):
         self.ms.launch_retire(task, n)
+
+    def __getattr__(self, name):             # registration calls of drivers that load the schedule themselves
+        return getattr(self.ms, name)
 
     def finish(self):
         if self.profile and self._pending_migrate:
@@ -340,6 +345,50 @@ def bench_analyzer(torch, base_kernels=256, tile=64, n_inv=64, max_iv=48, reps=2
     return out
 
 
+def bench_priority(torch, requests=6, be_iterations=3, lru=True):
+    """Config 6 at full size: per real-time request, the context switch into it (plan + migration of the part of
+    its working set the best-effort task pushed out), and the same launch order under LRU demand paging (oracle)."""
+    from workloads import make_trace, run_priority_schedule
+    from workloads.device import DeviceBuffers
+    from paper_2512_24637_amd import MSched
+    trace = make_trace(6, requests=requests, be_iterations=be_iterations)
+    buf = DeviceBuffers(trace, fill_contents=False)
+    ms = MSched(trace.page_shift, trace.n_virtual_pages, trace.n_frames, buf.pool.data_ptr(), buf.host.data_ptr(),
+                trace.n_slots, trace.host_slot, stream=torch.cuda.current_stream().cuda_stream, ids_pool_ptr=buf.ids_ptr)
+    impl = TimedImpl(ms, torch.cuda.current_stream().synchronize, profile=1)
+    rows, order = [], []
+    for rec in run_priority_schedule(trace, impl):
+        rows.append((rec.task, rec.replan, rec.plan.n_fetch, rec.plan.n_evict, rec.plan.n_commands))
+        order += [(rec.task, rec.first_launch + g) for g in range(rec.n_launches)]
+    impl.finish()
+    torch.cuda.synchronize()
+    rt = trace.policy["rt_task"]
+    P = trace.page_bytes
+    # the first request finds an empty pool; the later ones show the steady state of the colocation
+    sel = [i for i, r in enumerate(rows) if r[0] == rt and not r[1]][1:]
+    sel = [i for i in sel if rows[i][2] > 0]
+    mig = [impl.migrate_ms[i] for i in sel]
+    out = {"workload": f"c6-priority-colocation: {trace.notes}, 64 KiB pages, pool {trace.n_frames} frames "
+                       f"({trace.n_frames * P / 2**30:.1f} GiB), request = {trace.policy['request_launches']} launches "
+                       f"({trace.timeslice} us of profiled latency), period {trace.policy['period']} us",
+           "plans": len(rows), "requests_measured": len(sel),
+           "rt_switch_plan_us_mean": float(np.mean([impl.plan_wall[i] for i in sel]) * 1e6) if sel else None,
+           "rt_switch_migrate_ms_mean": float(np.mean(mig)) if sel else None,
+           "rt_switch_pages_in_mean": float(np.mean([rows[i][2] for i in sel])) if sel else None,
+           "rt_switch_gbps": float(np.sum([(rows[i][2] + rows[i][3]) * P for i in sel]) / (np.sum(mig) / 1e3) / 1e9) if sel else None,
+           "pages_fetched_total": int(sum(r[2] for r in rows))}
+    ms.close()
+    buf.release()
+    if lru:
+        from oracle import oracle as oracle_mod
+        from workloads.harness import load_trace
+        o = oracle_mod.Oracle.for_trace(trace)
+        load_trace(o, trace)
+        out["lru_demand_paging_faults"] = int(o.lru_faults([t for t, _ in order], [i for _, i in order], trace.n_frames))
+        o.close()
+    return out
+
+
 def bench_early_start(torch, switches=8, warm=2):
     """LLM-decode schedule (config 4) with 512 KiB pages, i.e. the same page structure at a quarter of the bytes:
     every launch of a decode step needs one more layer's weights, so readiness grows along the fetch list."""
@@ -418,6 +467,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-analyzer", action="store_true", help="skip the memory-analyzer leg")
     ap.add_argument("--no-early-start", action="store_true", help="skip the early-execution leg")
+    ap.add_argument("--no-priority", action="store_true", help="skip the priority-policy leg")
+    ap.add_argument("--priority-only", action="store_true", help="run only the priority-policy leg")
     ap.add_argument("--early-start-only", action="store_true", help="run only the early-execution leg")
     ap.add_argument("--analyzer-only", action="store_true",
                     help="run only the memory-analyzer leg (for profiling k_analyze)")
@@ -441,6 +492,13 @@ def main():
                           "roofline": r}), flush=True)
         return
 
+    if args.priority_only:
+        r = bench_priority(torch, lru=not args.no_cpu_baseline)
+        print(json.dumps({"metric": "context switch into a real-time request: migrated GB/s; plan latency (us)",
+                          "value": r["rt_switch_gbps"], "unit": "GB/s", "n_gpus": 1, "higher_is_better": True,
+                          "data": "synthetic", "dtype": "u8", "config": {"workload": r["workload"]}, "priority": r}),
+              flush=True)
+        return
     if args.early_start_only:
         r = bench_early_start(torch)
         print(json.dumps({"metric": "migrated GB/s with early execution; mean launch-ready time / migration time",
@@ -522,6 +580,8 @@ def main():
         result["roofline_plan"] = bench_planning_stress(torch)
     if not args.no_early_start:
         result["early_start"] = bench_early_start(torch)
+    if not args.no_priority:
+        result["priority"] = bench_priority(torch, lru=not args.no_cpu_baseline)
     if not args.no_analyzer:
         result["analyzer"] = bench_analyzer(torch, cpu=not args.no_cpu_baseline)
     if not args.no_cpu_baseline:

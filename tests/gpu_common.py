@@ -53,21 +53,28 @@ def assert_same_plan(po, pg, where):
 
 
 def lockstep(oracle_mod, trace, with_bytes=True, horizon="round", max_plans=None, bytes_every=1, log=None,
-             lazy_slices=None):
+             lazy_slices=None, driver=None):
     """Run the oracle and the HIP path side by side and require identical plans, page
     tables, frame owners and (with_bytes) pool and host-store bytes after every switch.
-    lazy_slices: enqueue launches only that many timeslices ahead of execution."""
+    lazy_slices: enqueue launches only that many timeslices ahead of execution.
+    driver: a scheduling policy other than round-robin, called as driver(trace, impl, max_plans) on an empty
+    implementation (it registers kernels, tasks and launches itself)."""
     from workloads.harness import LazyLoader
-    g = GpuSide(trace, preload=lazy_slices is None)
-    o = make_oracle(oracle_mod, trace, with_bytes, preload=lazy_slices is None)
+    preload = lazy_slices is None and driver is None
+    g = GpuSide(trace, preload=preload)
+    o = make_oracle(oracle_mod, trace, with_bytes, preload=preload)
     lo = lg = None
     if lazy_slices is not None:
         lo, lg = LazyLoader(o, trace, lazy_slices), LazyLoader(g.ms, trace, lazy_slices)
     wpp = trace.page_bytes // 8
     n = 0
     try:
-        for ro, rg in zip(run_schedule(trace, o, horizon=horizon, max_plans=max_plans, loader=lo),
-                          run_schedule(trace, g.ms, horizon=horizon, max_plans=max_plans, loader=lg)):
+        if driver is not None:
+            runs = zip(driver(trace, o, max_plans), driver(trace, g.ms, max_plans))
+        else:
+            runs = zip(run_schedule(trace, o, horizon=horizon, max_plans=max_plans, loader=lo),
+                       run_schedule(trace, g.ms, horizon=horizon, max_plans=max_plans, loader=lg))
+        for ro, rg in runs:
             where = (trace.name, "plan", ro.index, "task", ro.task)
             assert (ro.task, ro.first_launch, ro.timeline) == (rg.task, rg.first_launch, rg.timeline)
             assert_same_plan(ro.plan, rg.plan, where)

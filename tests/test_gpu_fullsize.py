@@ -30,3 +30,12 @@ def test_c4_decode_full_size_first_switches(oracle_mod):
 def test_c5_planning_stress_full_size_first_switches(oracle_mod):
     trace = make_trace(5, n_launches=100)          # full page counts; 100 of the 625 launches per task
     assert lockstep_sampled(oracle_mod, trace, n_sample=16384, check_every=4, log=_log) >= 16
+
+
+def test_c6_priority_colocation_full_size_first_requests(oracle_mod):
+    from workloads import run_priority_schedule
+    from gpu_common import lockstep
+    trace = make_trace(6, requests=3, be_iterations=2)           # full layer sizes and pool (13.5 GiB); 3 requests
+    n = lockstep(oracle_mod, trace, with_bytes=False, log=_log,
+                 driver=lambda tr, impl, max_plans: run_priority_schedule(tr, impl, max_plans))
+    assert n >= 5

@@ -259,3 +259,13 @@ def test_random_templates_of_every_kind(oracle_mod, seed):
     trace = _random_rule_trace(rng, page_shift=8, V=V, n_frames=V // 3 + 200, n_tasks=3, n_cmds=30,
                                with_lists=bool(seed % 2))
     assert lockstep(oracle_mod, trace, with_bytes=True, bytes_every=5) >= 10
+
+
+@pytest.mark.parametrize("announce", [False, True])
+def test_priority_policy_with_profiled_latencies(oracle_mod, announce):
+    """Real-time inference preempting best-effort training: latency-weighted slices, a timeline that changes
+    shape between switches, requests enqueued while the schedule runs."""
+    from workloads import run_priority_schedule
+    trace = make_trace(6, scale=16)
+    driver = lambda tr, impl, max_plans: run_priority_schedule(tr, impl, max_plans, announce_next_request=announce)
+    assert lockstep(oracle_mod, trace, with_bytes=True, bytes_every=3, driver=driver) >= 15

@@ -9,10 +9,10 @@ from .trace import (RULE_FIXED, RULE_LINEAR, RULE_STRIDED, RULE_LIST, MAX_ARGS,
                     Rule, Trace, TaskCommands)
 from .generators import make_trace, CONFIG_NAMES
 from .content import mix64, page_words, stamp_of
-from .harness import run_schedule, SwitchRecord
+from .harness import run_schedule, run_priority_schedule, SwitchRecord
 
 __all__ = [
     "RULE_FIXED", "RULE_LINEAR", "RULE_STRIDED", "RULE_LIST", "MAX_ARGS",
     "Rule", "Trace", "TaskCommands", "make_trace", "CONFIG_NAMES",
-    "mix64", "page_words", "stamp_of", "run_schedule", "SwitchRecord",
+    "mix64", "page_words", "stamp_of", "run_schedule", "run_priority_schedule", "SwitchRecord",
 ]

@@ -1,4 +1,4 @@
-"""Seeded generators for the five synthetic schedules.
+"""Seeded generators for the synthetic schedules.
 
 Each stands in for one of the paper's workload classes (Sec. 7: micro-benchmark,
 scientific computing, DNN training, LLM decoding; the fifth stresses planning
@@ -23,6 +23,7 @@ CONFIG_NAMES = {
     3: "c3-dl-training",
     4: "c4-llm-decode",
     5: "c5-planning-stress",
+    6: "c6-priority-colocation",
 }
 
 KiB = 1 << 10
@@ -258,14 +259,78 @@ def _c5(seed, page_shift, scale, n_launches):
                  notes="8 tasks, 2 dense ranges + Zipf(1.1) page-id gather over a shared table")
 
 
+def _c6(seed, page_shift, scale, n_launches, rt_layers=50, be_layers=40, requests=12, be_iterations=6):
+    """Real-time inference beside best-effort training under a priority policy (the paper's colocation
+    test T): task 0 serves requests of `rt_layers` launches, one layer each, and preempts task 1, which
+    trains (forward + backward over `be_layers` layers).  The real-time model takes a third of the footprint
+    and the pool holds 8/9 of it, the paper's 6 GB + 12 GB on a 16 GB card.  Launch latencies (ticks of a
+    microsecond) follow the bytes a launch touches, with seeded jitter, as profiled latencies would."""
+    page_shift = 16 if page_shift is None else page_shift
+    P = 1 << page_shift
+    rng = np.random.default_rng([seed, 6])
+    s = max(1, int(scale))
+    cols = 4096
+    batch, feat = 2048 // s, 4096
+    act_bytes = 2 * batch * feat                     # 16 MiB / s
+    infer = [Rule(RULE_LINEAR, 0, (3, 4), 2), Rule(RULE_LINEAR, 1, (5, 6), 2), Rule(RULE_LINEAR, 2, (5, 6), 2)]
+    fwd = infer
+    bwd = [Rule(RULE_LINEAR, 0, (6, 7), 2), Rule(RULE_LINEAR, 1, (6, 7), 2),
+           Rule(RULE_LINEAR, 2, (8, 9), 2), Rule(RULE_LINEAR, 3, (8, 9), 2),
+           Rule(RULE_FIXED, 4, (), act_bytes), Rule(RULE_FIXED, 5, (), act_bytes)]
+    kernels = [infer, fwd, bwd]
+    cursor = 0
+
+    def alloc(nbytes):
+        nonlocal cursor
+        addr = cursor
+        cursor += -(-nbytes // P) * P
+        return addr
+
+    def ticks(nbytes):                               # about 1 us per 2 MiB touched at full size, +-25 %
+        return max(1, int(nbytes * s / (2 * MiB) * rng.uniform(0.75, 1.25)))
+
+    # real-time task: weights 32..160 MiB / s per layer, two activation buffers reused by every layer
+    rows = rng.integers(4096 // s, 20480 // s + 1, size=rt_layers)
+    W = [alloc(int(r) * cols * 2) for r in rows]
+    A = [alloc(act_bytes), alloc(act_bytes)]
+    rt = CommandBuilder()
+    for _ in range(requests):
+        for l in range(rt_layers):
+            rt.add(0, [W[l], A[l % 2], A[(l + 1) % 2], int(rows[l]), cols, batch, feat],
+                   latency=ticks(int(rows[l]) * cols * 2 + 2 * act_bytes))
+    rt_pages = cursor // P
+    # best-effort task: training, twice the real-time footprint
+    rows = rng.integers(8192 // s, 24576 // s + 1, size=be_layers)
+    W = [alloc(int(r) * cols * 2) for r in rows]
+    dW = [alloc(int(r) * cols * 2) for r in rows]
+    A = [alloc(act_bytes) for _ in range(be_layers + 1)]
+    G = [alloc(act_bytes), alloc(act_bytes)]
+    be = CommandBuilder()
+    for _ in range(be_iterations):
+        for l in range(be_layers):
+            be.add(1, [W[l], A[l], A[l + 1], int(rows[l]), cols, batch, feat],
+                   latency=ticks(int(rows[l]) * cols * 2 + 2 * act_bytes))
+        for l in reversed(range(be_layers)):
+            be.add(2, [W[l], dW[l], A[l + 1], A[l], G[l % 2], G[(l + 1) % 2], int(rows[l]), cols, batch, feat],
+                   latency=ticks(2 * int(rows[l]) * cols * 2 + 4 * act_bytes))
+    V = cursor // P
+    tasks = [rt.build(), be.build()]
+    request_ticks = int(tasks[0].latency[:rt_layers].sum())
+    return Trace(name=CONFIG_NAMES[6], page_shift=page_shift, n_virtual_pages=V, n_frames=V * 8 // 9,
+                 timeslice=request_ticks, kernels=kernels, tasks=tasks, n_slots=V,
+                 notes=f"real-time inference ({rt_pages} pages) preempting best-effort training ({V - rt_pages} pages)",
+                 policy={"kind": "priority", "rt_task": 0, "be_task": 1, "request_launches": rt_layers,
+                         "period": 4 * request_ticks, "be_quantum": 4 * request_ticks})
+
+
 def make_trace(config: int, seed: int = 0, page_shift: Optional[int] = None, scale: int = 1,
                n_launches: Optional[int] = None, **kw) -> Trace:
-    """Build schedule `config` (1..5).
+    """Build schedule `config` (1..6).
 
     page_shift  override the page size (byte sizes of c2/c4 scale with it, so
                 the page structure is unchanged)
     scale       integer divisor for the size-like parameters of c3/c5
     n_launches  launches per task (total for c1) instead of the full count
     """
-    gen = {1: _c1, 2: _c2, 3: _c3, 4: _c4, 5: _c5}[config]
+    gen = {1: _c1, 2: _c2, 3: _c3, 4: _c4, 5: _c5, 6: _c6}[config]
     return gen(seed, page_shift, scale, n_launches, **kw)

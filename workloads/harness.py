@@ -135,3 +135,90 @@ def run_schedule(trace: Trace, impl, horizon: str = "round", max_plans: Optional
                 break
             replan = True
         cur = (cur + 1) % n
+
+
+def run_priority_schedule(trace: Trace, impl, max_plans: Optional[int] = None,
+                          announce_next_request: bool = False) -> Iterator[SwitchRecord]:
+    """Priority policy (Sec. 7 of the paper, real-time beside best-effort): the real-time task's requests
+    arrive every `period` ticks, preempt the best-effort task at its next launch boundary and run to
+    completion; the best-effort task runs in the gaps.  A request's launches are enqueued when it arrives
+    (dynamically launched commands), or, with announce_next_request, as soon as the previous request has
+    finished, so that plans made for the best-effort task already see the next request in the timeline.
+    `impl` must be empty: kernels, tasks and launches are registered here.  Time is counted in ticks of
+    profiled latency; a launch belongs to the slice it starts in, so the one that straddles an arrival
+    delays the request by its remainder."""
+    pol = trace.policy
+    rt, be, L, period = pol["rt_task"], pol["be_task"], pol["request_launches"], pol["period"]
+    kid = [impl.kernel_register(rules) for rules in trace.kernels]
+    for t in range(trace.n_tasks):
+        assert impl.task_create() == t
+
+    def enqueue(t, lo, hi):
+        cmds = trace.tasks[t]
+        for i in range(lo, hi):
+            impl.launch_enqueue(t, kid[int(cmds.kernel_id[i])], cmds.args[i], int(cmds.n_args[i]),
+                                int(cmds.latency[i]), int(cmds.ids_off[i]), int(cmds.n_ids[i]))
+
+    n_be, n_req = len(trace.tasks[be]), len(trace.tasks[rt]) // L
+    enqueue(be, 0, n_be)
+    lat = {t: trace.tasks[t].latency.astype(np.int64) for t in (rt, be)}
+    cursor = {rt: 0, be: 0}
+    sent, now, req, index = 0, 0, 0, 0
+
+    def step(task, tl, replan):
+        nonlocal index, now
+        plan = impl.plan(tl)
+        impl.migrate()
+        covered = int(plan.covered_launches)
+        rec = SwitchRecord(index, task, tl, plan, cursor[task], covered, replan)
+        index += 1
+        now += int(lat[task][cursor[task]:cursor[task] + covered].sum())
+        return rec, covered
+
+    if announce_next_request and n_req:
+        enqueue(rt, 0, L)
+        sent = L
+    while req < n_req or cursor[be] < n_be:
+        arrival = req * period
+        if req < n_req and now >= arrival:                     # a request runs to completion
+            if sent < (req + 1) * L:
+                enqueue(rt, sent, (req + 1) * L)
+                sent = (req + 1) * L
+            replan = False
+            while cursor[rt] < (req + 1) * L:
+                ticks = int(lat[rt][cursor[rt]:(req + 1) * L].sum())
+                tl = [(rt, ticks)]
+                if cursor[be] < n_be:
+                    tl.append((be, max(1, (req + 1) * period - now - ticks)))
+                rec, covered = step(rt, tl, replan)
+                yield rec
+                impl.launch_retire(rt, covered)
+                cursor[rt] += covered
+                replan = True
+                if max_plans is not None and index >= max_plans:
+                    return
+            req += 1
+            if announce_next_request and req < n_req:
+                enqueue(rt, sent, (req + 1) * L)
+                sent = (req + 1) * L
+        elif cursor[be] < n_be:                                # the best-effort task fills the gap
+            budget = (arrival - now) if req < n_req else pol["be_quantum"]
+            replan = False
+            while budget > 0 and cursor[be] < n_be:
+                tl = [(be, budget)]
+                if req < n_req:
+                    tl.append((rt, trace.timeslice))           # holds commands only once the request is known
+                    tl.append((be, period))
+                before = now
+                rec, covered = step(be, tl, replan)
+                yield rec
+                impl.launch_retire(be, covered)
+                cursor[be] += covered
+                budget -= now - before
+                if max_plans is not None and index >= max_plans:
+                    return
+                if covered == int(rec.plan.g_end0):
+                    break
+                replan = True
+        else:
+            now = arrival                                      # idle until the next request

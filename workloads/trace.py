@@ -66,6 +66,7 @@ class Trace:
     host_slot: Optional[np.ndarray] = None  # uint32 [V] page -> backing slot, or None = identity
     n_slots: int = 0                        # pages in the host backing store
     notes: str = ""
+    policy: dict = field(default_factory=dict)  # parameters of a non-round-robin scheduling policy, if any
 
     @property
     def page_bytes(self) -> int:
