@@ -16,6 +16,8 @@ the page structure of the configured workload.  Prints ONE JSON line on stdout.
                 and when each covered launch could start, against the end of the whole migration
   priority      real-time inference preempting best-effort training under the priority policy (latency-weighted
                 timelines): what a request's context switch costs (plan + restore of its working set)
+  ablation      allocation-granularity prediction against the templates on the LLM-decode schedule (migration volume
+                and memory-scheduling time), and demand-paging faults under injected false negatives (oracle simulation)
   analyzer      the offline memory analyzer (msched_analyze) on a batch of profiled kernels: kernels per
                 second, its roofline against HBM bandwidth and the CPU oracle on a sample of the batch
 """
@@ -389,6 +391,56 @@ def bench_priority(torch, requests=6, be_iterations=3, lru=True):
     return out
 
 
+def bench_ablation(torch, steps=16, cpu=True):
+    """Fig. "eval-naive" of the paper in shape: the LLM-decode schedule (512 KiB pages, every page of every buffer
+    backed) planned from the templates and from whole allocations, through the same HIP path."""
+    from workloads import make_trace, run_schedule
+    from workloads.ablation import allocation_granularity, drop_rules
+    base = make_trace(4, page_shift=19, steps=steps, full_backing=True)
+    out = {"workload": f"c4-llm-decode with 512 KiB pages, {steps} decode steps per task, pool {base.n_frames} frames"}
+    for name, trace in (("template", base), ("allocation", allocation_granularity(base))):
+        buf, ms = make_context(torch, trace, fill_contents=False)
+        impl = TimedImpl(ms, torch.cuda.current_stream().synchronize, profile=1)
+        t0 = time.perf_counter()
+        pages = plans = 0
+        for rec in run_schedule(trace, impl):
+            pages += rec.plan.n_fetch + rec.plan.n_evict
+            plans += 1
+        torch.cuda.synchronize()
+        impl.finish()
+        out[name] = {"plans": plans, "pages_moved": pages, "gb_moved": pages * trace.page_bytes / 1e9,
+                     "migrate_ms_total": float(np.sum(impl.migrate_ms)), "plan_ms_total": float(np.sum(impl.plan_wall) * 1e3),
+                     "wall_ms": (time.perf_counter() - t0) * 1e3}
+        ms.close()
+        buf.release()
+    out["migration_volume_inflation"] = out["allocation"]["pages_moved"] / out["template"]["pages_moved"]
+    out["memory_scheduling_time_inflation"] = ((out["allocation"]["migrate_ms_total"] + out["allocation"]["plan_ms_total"]) /
+                                               (out["template"]["migrate_ms_total"] + out["template"]["plan_ms_total"]))
+    if cpu:
+        # false negatives: plans from templates that lost a share of their rules, true launches, faults resolved by the
+        # oracle's demand-paging fallback (simulation on the scaled training schedule)
+        from oracle import oracle as oracle_mod
+        from workloads.harness import load_trace
+        t3 = make_trace(3, scale=32, iterations=3)
+        truth = oracle_mod.Oracle.for_trace(t3)
+        load_trace(truth, t3)
+        fn = {}
+        for rate in (0.0, 0.0025, 0.02, 0.2):
+            pred = drop_rules(t3, rate, seed=1) if rate else t3
+            o = oracle_mod.Oracle.for_trace(pred)
+            load_trace(o, pred)
+            fetched = faults = 0
+            for rec in run_schedule(pred, o):
+                fetched += rec.plan.n_fetch
+                for g in range(rec.n_launches):
+                    faults += o.demand_touch(truth.command_pages(rec.task, rec.first_launch + g))
+            o.close()
+            fn[str(rate)] = {"pages_fetched_by_plans": fetched, "demand_faults": faults}
+        truth.close()
+        out["false_negative_simulation"] = {"workload": "c3-dl-training scaled 1/32, 3 iterations (oracle, CPU)", "by_rate": fn}
+    return out
+
+
 def bench_early_start(torch, switches=8, warm=2):
     """LLM-decode schedule (config 4) with 512 KiB pages, i.e. the same page structure at a quarter of the bytes:
     every launch of a decode step needs one more layer's weights, so readiness grows along the fetch list."""
@@ -468,6 +520,8 @@ def main():
     ap.add_argument("--no-analyzer", action="store_true", help="skip the memory-analyzer leg")
     ap.add_argument("--no-early-start", action="store_true", help="skip the early-execution leg")
     ap.add_argument("--no-priority", action="store_true", help="skip the priority-policy leg")
+    ap.add_argument("--no-ablation", action="store_true", help="skip the predictor-ablation leg")
+    ap.add_argument("--ablation-only", action="store_true", help="run only the predictor-ablation leg")
     ap.add_argument("--priority-only", action="store_true", help="run only the priority-policy leg")
     ap.add_argument("--early-start-only", action="store_true", help="run only the early-execution leg")
     ap.add_argument("--analyzer-only", action="store_true",
@@ -492,6 +546,13 @@ def main():
                           "roofline": r}), flush=True)
         return
 
+    if args.ablation_only:
+        r = bench_ablation(torch, cpu=not args.no_cpu_baseline)
+        print(json.dumps({"metric": "migration volume of allocation-granularity prediction / template prediction",
+                          "value": r["migration_volume_inflation"], "unit": "x", "n_gpus": 1, "higher_is_better": False,
+                          "data": "synthetic", "dtype": "u8", "config": {"workload": r["workload"]}, "ablation": r}),
+              flush=True)
+        return
     if args.priority_only:
         r = bench_priority(torch, lru=not args.no_cpu_baseline)
         print(json.dumps({"metric": "context switch into a real-time request: migrated GB/s; plan latency (us)",
@@ -580,6 +641,8 @@ def main():
         result["roofline_plan"] = bench_planning_stress(torch)
     if not args.no_early_start:
         result["early_start"] = bench_early_start(torch)
+    if not args.no_ablation:
+        result["ablation"] = bench_ablation(torch, cpu=not args.no_cpu_baseline)
     if not args.no_priority:
         result["priority"] = bench_priority(torch, lru=not args.no_cpu_baseline)
     if not args.no_analyzer:

@@ -466,6 +466,45 @@ int orc_migrate_prefix(orc_t *o, uint32_t n) {
     return E_OK;
 }
 
+/* Demand-paging fallback (Sec. 5.2: a page the prediction missed is brought in by an ordinary page fault).
+ * The running command touches `pages`; every one that is not resident faults: it takes the lowest free
+ * frame, or else the frame of the resident page outside `pages` whose next use (as of the latest plan) is
+ * farthest - never-used pages first, ties to the lowest page id - which is the head of the eviction order
+ * the plan established (Sec. 6.2).  Bytes move as in a migration.  Returns the number of faults. */
+int64_t orc_demand_touch(orc_t *o, const uint32_t *pages, uint32_t n) {
+    if (o->plan_pending) return E_INVAL;                      /* between a plan and its migration nothing runs */
+    size_t P = (size_t)1 << o->page_shift;
+    int64_t faults = 0;
+    uint8_t *in_use = (uint8_t *)calloc(o->V + 1, 1);
+    if (!in_use) return E_NOMEM;
+    for (uint32_t i = 0; i < n; i++) { if (pages[i] >= o->V) { free(in_use); return E_RANGE; } in_use[pages[i]] = 1; }
+    for (uint32_t i = 0; i < n; i++) {
+        uint32_t p = pages[i];
+        if (o->page_table[p] != NONE32) continue;
+        if (o->host_slot && o->host_slot[p] == NONE32) { free(in_use); return E_RANGE; }
+        faults++;
+        uint32_t f = NONE32;
+        for (uint32_t k = 0; k < o->F && f == NONE32; k++) if (o->frame_owner[k] == NONE32) f = k;
+        if (f == NONE32) {
+            uint32_t victim = NONE32;
+            for (uint64_t q = 0; q < o->V; q++) {
+                if (o->page_table[q] == NONE32 || in_use[q]) continue;
+                if (victim == NONE32 || o->nu[q] > o->nu[victim]) victim = (uint32_t)q;
+            }
+            if (victim == NONE32) { free(in_use); return E_WSET; }   /* the command alone does not fit */
+            f = o->page_table[victim];
+            o->page_table[victim] = NONE32;
+            if (o->pool) memcpy(o->host + slot_of(o, victim) * P, o->pool + (size_t)f * P, P);
+        }
+        if (o->pool) memcpy(o->pool + (size_t)f * P, o->host + slot_of(o, p) * P, P);
+        o->page_table[p] = f;
+        o->frame_owner[f] = p;
+        o->nu[p] = 0;                                         /* in use now */
+    }
+    free(in_use);
+    return faults;
+}
+
 int orc_pagetable_query(const orc_t *o, const uint64_t *pages, uint32_t n, uint32_t *out) {
     for (uint32_t i = 0; i < n; i++) if (pages[i] >= o->V) return E_RANGE;
     for (uint32_t i = 0; i < n; i++) out[i] = o->page_table[pages[i]];

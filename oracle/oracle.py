@@ -62,6 +62,8 @@ def _load():
     lib.orc_migrate.argtypes = [C.c_void_p]
     lib.orc_ready_need.argtypes = [C.c_void_p, C.c_void_p]
     lib.orc_migrate_prefix.argtypes = [C.c_void_p, C.c_uint32]
+    lib.orc_demand_touch.restype = C.c_int64
+    lib.orc_demand_touch.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32]
     lib.orc_pagetable_query.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p]
     lib.orc_state.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
     lib.orc_state.restype = None
@@ -206,6 +208,11 @@ class Oracle:
     def migrate_prefix(self, n):
         """Carry out the pending plan up to fetch entry n - 1 (in list order)."""
         self._check(self.lib.orc_migrate_prefix(self.h, int(n)))
+
+    def demand_touch(self, pages) -> int:
+        """The running command touches these pages; the ones that are not resident fault in.  Returns the faults."""
+        pages = np.ascontiguousarray(pages, np.uint32)
+        return self._check(self.lib.orc_demand_touch(self.h, _ptr(pages), pages.shape[0]))
 
     def pagetable_query(self, pages) -> np.ndarray:
         pages = np.ascontiguousarray(pages, np.uint64)

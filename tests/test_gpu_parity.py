@@ -269,3 +269,11 @@ def test_priority_policy_with_profiled_latencies(oracle_mod, announce):
     trace = make_trace(6, scale=16)
     driver = lambda tr, impl, max_plans: run_priority_schedule(tr, impl, max_plans, announce_next_request=announce)
     assert lockstep(oracle_mod, trace, with_bytes=True, bytes_every=3, driver=driver) >= 15
+
+
+def test_allocation_granularity_ablation_runs_bit_exact(oracle_mod):
+    """The naive predictor's schedule (whole buffers per pointer) through the same path: larger working sets,
+    slices cut to what fits, replans inside a timeslice."""
+    from workloads.ablation import allocation_granularity
+    trace = allocation_granularity(make_trace(4, page_shift=15, steps=12, full_backing=True))
+    assert lockstep(oracle_mod, trace, with_bytes=True, bytes_every=4) >= 20

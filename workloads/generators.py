@@ -126,10 +126,13 @@ def _c3(seed, page_shift, scale, n_launches, layers=48, iterations=20):
     kernels = [fwd, bwd]
     tasks, cursor = [], 0                            # cursor: next free byte (page aligned)
 
+    allocations = []
+
     def alloc(nbytes):
         nonlocal cursor
         addr = cursor
         cursor += -(-nbytes // P) * P
+        allocations.append((addr, nbytes))
         return addr
 
     for t in range(2):
@@ -149,10 +152,11 @@ def _c3(seed, page_shift, scale, n_launches, layers=48, iterations=20):
     V = cursor // P
     return Trace(name=CONFIG_NAMES[3], page_shift=page_shift, n_virtual_pages=V,
                  n_frames=V // 2, timeslice=2 * layers, kernels=kernels, tasks=tasks, n_slots=V,
-                 notes=f"2 tasks, {layers} layers, fwd+bwd per iteration, pool = half the footprint")
+                 notes=f"2 tasks, {layers} layers, fwd+bwd per iteration, pool = half the footprint",
+                 allocations=np.asarray(allocations, np.uint64))
 
 
-def _c4(seed, page_shift, scale, n_launches, layers=32, steps=256):
+def _c4(seed, page_shift, scale, n_launches, layers=32, steps=256, full_backing=False):
     page_shift = 21 if page_shift is None else page_shift
     P = 1 << page_shift
     unit = P / (2 * MiB)                             # byte sizes scale with the page size
@@ -170,10 +174,13 @@ def _c4(seed, page_shift, scale, n_launches, layers=32, steps=256):
     tasks, cursor = [], 0
     slot_pages = []                                   # page ids that own a backing slot
 
+    allocations = []
+
     def alloc(nbytes):
         nonlocal cursor
         addr = cursor
         cursor += -(-nbytes // P) * P
+        allocations.append((addr, nbytes))
         return addr
 
     for t in range(2):
@@ -201,11 +208,14 @@ def _c4(seed, page_shift, scale, n_launches, layers=32, steps=256):
     pages = np.unique(np.concatenate(slot_pages))
     host_slot = np.full(V, 0xFFFFFFFF, np.uint32)
     host_slot[pages] = np.arange(pages.size, dtype=np.uint32)
+    if full_backing:                                 # every page of every buffer can be paged (allocation-granularity ablation)
+        host_slot, pages = None, np.arange(V)
     n_frames = int(8192 * layers / 32)
     return Trace(name=CONFIG_NAMES[4], page_shift=page_shift, n_virtual_pages=V,
                  n_frames=n_frames, timeslice=steps_per_slice * 2 * layers, kernels=kernels,
                  tasks=tasks, host_slot=host_slot, n_slots=int(pages.size),
-                 notes=f"2 decoders, {layers} layers, KV grows one token per step")
+                 notes=f"2 decoders, {layers} layers, KV grows one token per step",
+                 allocations=np.asarray(allocations, np.uint64))
 
 
 def _zipf_cdf(n_items, alpha):
@@ -280,10 +290,13 @@ def _c6(seed, page_shift, scale, n_launches, rt_layers=50, be_layers=40, request
     kernels = [infer, fwd, bwd]
     cursor = 0
 
+    allocations = []
+
     def alloc(nbytes):
         nonlocal cursor
         addr = cursor
         cursor += -(-nbytes // P) * P
+        allocations.append((addr, nbytes))
         return addr
 
     def ticks(nbytes):                               # about 1 us per 2 MiB touched at full size, +-25 %
@@ -320,7 +333,8 @@ def _c6(seed, page_shift, scale, n_launches, rt_layers=50, be_layers=40, request
                  timeslice=request_ticks, kernels=kernels, tasks=tasks, n_slots=V,
                  notes=f"real-time inference ({rt_pages} pages) preempting best-effort training ({V - rt_pages} pages)",
                  policy={"kind": "priority", "rt_task": 0, "be_task": 1, "request_launches": rt_layers,
-                         "period": 4 * request_ticks, "be_quantum": 4 * request_ticks})
+                         "period": 4 * request_ticks, "be_quantum": 4 * request_ticks},
+                 allocations=np.asarray(allocations, np.uint64))
 
 
 def make_trace(config: int, seed: int = 0, page_shift: Optional[int] = None, scale: int = 1,

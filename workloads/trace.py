@@ -67,6 +67,7 @@ class Trace:
     n_slots: int = 0                        # pages in the host backing store
     notes: str = ""
     policy: dict = field(default_factory=dict)  # parameters of a non-round-robin scheduling policy, if any
+    allocations: Optional[np.ndarray] = None    # uint64 [n, 2] (start, bytes) of the buffers the tasks allocated, by start
 
     @property
     def page_bytes(self) -> int:
