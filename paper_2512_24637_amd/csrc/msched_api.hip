@@ -101,6 +101,34 @@ inline bool region_signature(const msched_ctx *c, const msched_rule &q, const Cm
     return true;
 }
 
+// The page ranges a fixed / linear / strided rule describes for one command, appended to out[n..cap).
+// Returns false when they do not fit (the plan then scatters next uses per page instead).
+inline bool append_ranges(const msched_ctx *c, const msched_rule &q, const CmdRec &r, uint32_t g, PageRange *out,
+                          uint32_t &n, uint32_t cap) {
+    auto eval = [&](uint64_t coeff, const uint8_t *idx, int cnt) {
+        uint64_t v = coeff;
+        for (int j = 0; j < cnt; ++j) v *= r.args[idx[j]];    // validated at enqueue: cannot overflow
+        return v;
+    };
+    const uint32_t sh = c->page_shift;
+    const uint64_t base = r.args[q.base_arg];
+    uint64_t size = q.kind == MSCHED_RULE_FIXED ? q.size_coeff : eval(q.size_coeff, q.size_args, q.n_size_args);
+    if (size == 0) return true;
+    uint64_t stride = 0, count = 1;
+    if (q.kind == MSCHED_RULE_STRIDED) {
+        stride = eval(q.stride_coeff, q.stride_args, q.n_stride_args);
+        count = eval(q.count_coeff, q.count_args, q.n_count_args);
+        if (count == 0) return true;
+        if (size >= stride || count == 1) { size = (count - 1) * stride + size; count = 1; }   // the chunks abut or overlap
+    }
+    if (count > cap - n) return false;
+    for (uint64_t j = 0; j < count; ++j) {
+        const uint64_t c0 = base + j * stride;
+        out[n++] = {(uint32_t)(c0 >> sh), (uint32_t)(((c0 + size - 1) >> sh) + 1), g, 0};
+    }
+    return true;
+}
+
 // Insert sig into the per-plan table; returns true when it was already there.
 inline bool seen_before(msched_ctx *c, const RegionSig &sig, size_t mask) {
     uint64_t h = sig.a * 0x9E3779B97F4A7C15ull ^ (sig.b + 0x7F4A7C15ull) * 0xC2B2AE3D27D4EB4Full ^
@@ -122,6 +150,9 @@ void free_ctx(msched_ctx *c) {
                    c->query_buf, c->cmd_dev, c->list_bucket_fill, c->list_pairs};
     for (void *p : dev) if (p) (void)hipFree(p);
     if (c->hdr_host) (void)hipHostFree(c->hdr_host);
+    if (c->ranges_host) (void)hipHostFree(c->ranges_host);
+    if (c->ranges_dev) (void)hipFree(c->ranges_dev);
+    if (c->key16) (void)hipFree(c->key16);
     if (c->poll_stream) { (void)hipStreamSynchronize(c->poll_stream); (void)hipStreamDestroy(c->poll_stream); }
     for (void *p : {(void *)c->page_done, (void *)c->chunks_done, (void *)c->landed}) if (p) (void)hipFree(p);
     if (c->need_host) (void)hipHostFree(c->need_host);
@@ -162,6 +193,7 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     c->migrate_chunk_shift = (uint32_t)env_u32("MSCHED_MIGRATE_CHUNK_SHIFT", 6, 24, 21);
     c->early_chunk_shift = (uint32_t)env_u32("MSCHED_EARLY_CHUNK_SHIFT", 12, 24, 16);
     c->migrate_ticket = (uint32_t)env_u32("MSCHED_MIGRATE_TICKET", 0, 1, 0);
+    c->paint = (uint32_t)env_u32("MSCHED_PAINT", 0, 1, 1);
     c->migrate_max_blocks = (uint32_t)env_u32("MSCHED_MIGRATE_BLOCKS", 1, 1 << 20, 512);
     c->migrate_hints = (uint32_t)env_u32("MSCHED_MIGRATE_HINTS", 0, 3, 0);
     c->expand_split = (uint32_t)env_u32("MSCHED_EXPAND_SPLIT", 1, 64, 0);
@@ -204,6 +236,10 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
                                               sizeof(void *) * (MSCHED_MAX_TIMELINE_COMMANDS + 1), hipHostMallocDefault)) != hipSuccess) fail(e);
     if (rc == MSCHED_OK && (e = hipHostGetDevicePointer((void **)&c->cmd_ptrs_dev, (void *)c->cmd_ptrs_host, 0)) != hipSuccess) fail(e);
     if (rc == MSCHED_OK && (e = hipHostGetDevicePointer(&c->host_dev, cfg->host_store, 0)) != hipSuccess) fail(e);
+    if (rc == MSCHED_OK && (e = hipHostMalloc((void **)&c->ranges_host, sizeof(PageRange) * kMaxRanges, hipHostMallocDefault)) != hipSuccess) fail(e);
+    if (rc == MSCHED_OK && (e = hipHostGetDevicePointer((void **)&c->ranges_host_dev, c->ranges_host, 0)) != hipSuccess) fail(e);
+    if (rc == MSCHED_OK && (e = hipMalloc((void **)&c->ranges_dev, sizeof(PageRange) * kMaxRanges)) != hipSuccess) fail(e);
+    if (rc == MSCHED_OK && (e = hipMalloc((void **)&c->key16, c->V * 2 + 64)) != hipSuccess) fail(e);
     for (int i = 0; i < 8 && rc == MSCHED_OK; ++i)
         if ((e = hipEventCreate(&c->ev[i])) != hipSuccess) fail(e);
 
@@ -349,6 +385,20 @@ int msched_plan(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entri
                 reinterpret_cast<uintptr_t>(c->cmd_ptrs_host[g]) | (skip << 56));
         }
     }
+    // Range rules as a list of page ranges: the sweeps paint them into LDS tile by tile, and no per-page next
+    // use goes through memory.  Id lists, and plans with more ranges than the list holds, scatter into nu[].
+    uint32_t n_ranges = 0;
+    bool painted = c->paint != 0, live_list = false;
+    for (uint32_t g = 0; g < G; ++g) {
+        const CmdRec &rec = *c->plan_recs[g];
+        const DevKernel &k = c->kernels[rec.kernel];
+        const uint64_t skip = reinterpret_cast<uintptr_t>(c->cmd_ptrs_host[g]) >> 56;
+        for (uint32_t r = 0; r < k.n_rules; ++r) {
+            if ((skip >> r) & 1) continue;
+            if (k.rules[r].kind == MSCHED_RULE_LIST) { live_list |= rec.n_ids != 0; continue; }
+            if (painted && !append_ranges(c, k.rules[r], rec, g, c->ranges_host, n_ranges, kMaxRanges)) painted = false;
+        }
+    }
     memset(out, 0, sizeof *out);
     out->g_end0 = g_end0;
     out->n_commands = G;
@@ -361,6 +411,9 @@ int msched_plan(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entri
         PlanGeom g;
         plan_geometry(c, G, g);
         g.g_end0 = g_end0;
+        g.painted = painted;
+        g.n_ranges = painted ? n_ranges : 0;
+        g.use_nu = !painted || live_list;
         // Id lists: how many ids does this plan carry (repeated lists excluded)?  Many -> bucket path.
         g.list_binned = false;
         g.n_buckets = (uint32_t)((c->V + (1u << 13) - 1) >> 13);           // buckets of 8 Ki pages

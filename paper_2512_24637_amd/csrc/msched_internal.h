@@ -57,12 +57,20 @@ struct TaskQueue {
     size_t cursor = 0;                          // first command not yet retired
 };
 
+// A page range [lo, hi) first used by command g: what a fixed / linear rule, or one chunk of a strided
+// rule, describes once its formulas are evaluated.
+struct PageRange { uint32_t lo, hi, g, pad; };
+constexpr uint32_t kMaxRanges = 4096;           // more ranges than this in one plan: next use is scattered per page instead
+
 struct PlanGeom {
     uint32_t G, g_end0, n_chunks, chunk_pages, n_keys;   // n_keys = 2 * (G + 1)
     uint32_t waves, steps, rounds;                       // sweep workgroup shape
     bool single;                                         // one workgroup sweeps the whole table (fused tail kernel)
     bool list_binned;                                    // id lists go through the bucket path
     uint32_t n_buckets, bucket_cap;                      // bucket_cap: pairs per sub-segment
+    bool painted;                                        // range rules arrive as a range list the sweeps paint into LDS
+    bool use_nu;                                         // some next uses are in nu[] (id lists, or the scatter path)
+    uint32_t n_ranges;
 };
 
 }  // namespace msched
@@ -113,6 +121,12 @@ struct msched_ctx {
     msched::PlanHeader pending{};
     uint32_t *query_buf = nullptr; size_t query_cap = 0;     // device scratch for pagetable_query
     // early execution: in-order landing of the fetch list
+    // range list of the latest plan (painted path)
+    msched::PageRange *ranges_host = nullptr;   // pinned [kMaxRanges], written by the timeline flatten
+    msched::PageRange *ranges_host_dev = nullptr;   // the same memory, device address
+    msched::PageRange *ranges_dev = nullptr;    // device copy for sweeps of many workgroups
+    uint16_t *key16 = nullptr;                  // device [V]: class key of every page (first sweep -> second sweep)
+    uint32_t paint = 1;                         // 0: always scatter next uses per page (MSCHED_PAINT)
     int early = 0;                              // msched_set_early_start
     uint32_t *need_host = nullptr;              // pinned [MAX_G + 1]: need[g] of the latest plan (written by the cut kernel)
     uint32_t *page_done = nullptr;              // device [F]: tag of the migration that completed fetch entry i

@@ -17,6 +17,8 @@
 // g of the current plan wins.
 #include <algorithm>
 
+#include <cstdlib>
+
 #include "msched_internal.h"
 
 namespace msched {
@@ -351,9 +353,9 @@ __global__ __launch_bounds__(kListThreads) void k_list_reduce(ListArgs a) {
 // nu = key - K; K = G + 1 and class G stands for "never used in the timeline".  Pages that are
 // neither resident nor used take part in nothing (key kNone).
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t classify(uint32_t frame, uint32_t enc, uint32_t epoch, uint32_t G) {
+__device__ __forceinline__ uint32_t classify(uint32_t frame, uint32_t enc, uint32_t epoch, uint32_t G, uint32_t painted) {
     const bool resident = frame != kNone;
-    const uint32_t c = ((enc >> kNuShift) == epoch) ? (kNuMask - (enc & kNuMask)) : G;
+    const uint32_t c = min(painted, ((enc >> kNuShift) == epoch) ? (kNuMask - (enc & kNuMask)) : G);
     if (!resident && c == G) return kNone;
     return resident ? (G + 1 + c) : c;
 }
@@ -373,13 +375,75 @@ struct SweepGeom {
     uint32_t steps;           // 64-page steps per wavefront per tile (<= kMaxSteps)
     uint32_t rounds;          // tiles per chunk; a tile is waves * steps * 64 consecutive pages
     uint32_t G, epoch;
+    // next uses that come from range rules: a list of page ranges painted into LDS tile by tile
+    const PageRange *ranges;
+    uint32_t n_ranges;        // 0: nothing to paint
+    uint32_t use_nu;          // 0: nu[] holds nothing for this plan and is not read
+    const uint32_t *slot;     // page -> backing slot (or null): a wanted page without one is an error
+    uint32_t *flags;
+    uint16_t *key16;          // [V] class key of every page, written by the first sweep for the second
 };
+constexpr uint16_t kNoKey16 = 0xffff;                  // keys are below 2 * (MSCHED_MAX_TIMELINE_COMMANDS + 1) = 6144
+
+// ------------------------------------------------------------------------------------------
+// Painting.  A tile's next uses from range rules = for every page the smallest g among the ranges that
+// cover it.  Each workgroup scans the plan's range list (a few KB, L2-resident), and
+//   * a range that covers the whole tile only lowers one word, the tile's floor;
+//   * a range that covers part of it is queued and painted with LDS atomic minima, by all threads
+//     together when it is long, by one thread when it is a few pages.
+// Nothing per page goes through memory: that is what the scatter path (k_expand) spends its time on.
+// ------------------------------------------------------------------------------------------
+constexpr uint32_t kPaintQueue = kWave * kMaxWaves;       // one slot per thread and batch
+constexpr uint32_t kPaintSerial = 32;                     // ranges up to this many pages are painted by one thread
+
+struct PaintLds {
+    uint32_t n_queued, floor;
+    uint32_t lo[kPaintQueue], hi[kPaintQueue], g[kPaintQueue];
+};
+
+__device__ void paint_tile(const SweepGeom &sg, uint64_t t0, uint64_t t1, uint32_t *paint, PaintLds &q) {
+    const uint32_t n = (t1 > t0) ? (uint32_t)(t1 - t0) : 0;
+    for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) paint[i] = sg.G;
+    if (threadIdx.x == 0) { q.n_queued = 0; q.floor = sg.G; }
+    __syncthreads();
+    for (uint32_t r0 = 0; r0 < sg.n_ranges; r0 += blockDim.x) {
+        const uint32_t r = r0 + threadIdx.x;
+        if (r < sg.n_ranges) {
+            const PageRange R = sg.ranges[r];
+            const uint64_t lo = max((uint64_t)R.lo, t0), hi = min((uint64_t)R.hi, t1);
+            if (lo < hi) {
+                if (lo == t0 && hi == t1) {
+                    atomicMin(&q.floor, R.g);
+                } else {
+                    const uint32_t at = atomicAdd(&q.n_queued, 1u);
+                    q.lo[at] = (uint32_t)(lo - t0); q.hi[at] = (uint32_t)(hi - t0); q.g[at] = R.g;
+                }
+            }
+        }
+        __syncthreads();
+        const uint32_t nq = q.n_queued;
+        for (uint32_t w = 0; w < nq; ++w) {
+            const uint32_t lo = q.lo[w], hi = q.hi[w];
+            if (hi - lo > kPaintSerial)
+                for (uint32_t i = lo + threadIdx.x; i < hi; i += blockDim.x) atomicMin(&paint[i], q.g[w]);
+        }
+        if (threadIdx.x < nq) {
+            const uint32_t lo = q.lo[threadIdx.x], hi = q.hi[threadIdx.x];
+            if (hi - lo <= kPaintSerial)
+                for (uint32_t i = lo; i < hi; ++i) atomicMin(&paint[i], q.g[threadIdx.x]);
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) q.n_queued = 0;
+        __syncthreads();
+    }
+}
 
 // One tile: every wavefront loads its `steps` x 64 consecutive pages (all loads issued before any
 // use) and classifies them.
 __device__ __forceinline__ void load_tile(const uint32_t *__restrict__ page_table, const uint32_t *__restrict__ nu,
                                           const SweepGeom &sg, uint64_t wave_begin, uint64_t p_end,
-                                          uint32_t (&key)[kMaxSteps], uint32_t (&fr)[kMaxSteps]) {
+                                          uint32_t (&key)[kMaxSteps], uint32_t (&fr)[kMaxSteps],
+                                          const uint32_t *paint, uint64_t tile_begin, uint32_t floor) {
     const int lane = lane_id();
     uint32_t enc[kMaxSteps];
 #pragma unroll
@@ -387,10 +451,15 @@ __device__ __forceinline__ void load_tile(const uint32_t *__restrict__ page_tabl
         const uint64_t p = wave_begin + (uint64_t)s * kWave + lane;
         const bool in = (uint32_t)s < sg.steps && p < p_end;
         fr[s] = in ? page_table[p] : kNone;
-        enc[s] = in ? nu[p] : 0u;
+        enc[s] = (in && sg.use_nu) ? nu[p] : 0u;
     }
 #pragma unroll
-    for (int s = 0; s < kMaxSteps; ++s) key[s] = classify(fr[s], enc[s], sg.epoch, sg.G);
+    for (int s = 0; s < kMaxSteps; ++s) {
+        const uint64_t p = wave_begin + (uint64_t)s * kWave + lane;
+        const bool in = (uint32_t)s < sg.steps && p < p_end;
+        const uint32_t painted = (in && sg.n_ranges) ? min(floor, paint[p - tile_begin]) : sg.G;
+        key[s] = classify(fr[s], enc[s], sg.epoch, sg.G, painted);
+    }
 }
 
 // Count the tile's pages per key into one LDS histogram.  Runs of pages usually share a key (dense
@@ -461,10 +530,30 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
     const uint64_t p_begin = (uint64_t)chunk * sg.chunk_pages;
     const uint64_t p_end = min(sg.V, p_begin + sg.chunk_pages);
     const uint64_t tile_pages = (uint64_t)waves * sg.steps * kWave;
+    uint32_t *paint = lds + n_keys;                       // [tile_pages] when there are ranges to paint
+    __shared__ PaintLds s_paint;
     for (uint32_t round = 0; round < sg.rounds; ++round) {
         uint32_t key[kMaxSteps], fr[kMaxSteps];
-        load_tile(page_table, nu, sg, p_begin + round * tile_pages + (uint64_t)wave * sg.steps * kWave, p_end, key, fr);
+        const uint64_t tile_begin = p_begin + round * tile_pages;
+        if (sg.n_ranges) paint_tile(sg, tile_begin, min(p_end, tile_begin + tile_pages), paint, s_paint);
+        const uint64_t wave_begin = tile_begin + (uint64_t)wave * sg.steps * kWave;
+        load_tile(page_table, nu, sg, wave_begin, p_end, key, fr, paint, tile_begin, s_paint.floor);
+        if (sg.slot != nullptr && sg.n_ranges) {          // a page a range wants must have a backing slot
+            const int lane = lane_id();
+#pragma unroll
+            for (int s = 0; s < kMaxSteps; ++s)
+                if (key[s] < sg.G && sg.slot[wave_begin + (uint64_t)s * kWave + lane] == kNone) atomicOr(sg.flags, kStatRange);
+        }
+        {                                                 // the second sweep reads the classes from here, 2 bytes a page
+            const int lane = lane_id();
+#pragma unroll
+            for (int s = 0; s < kMaxSteps; ++s) {
+                const uint64_t p = wave_begin + (uint64_t)s * kWave + lane;
+                if ((uint32_t)s < sg.steps && p < p_end) sg.key16[p] = key[s] == kNone ? kNoKey16 : (uint16_t)key[s];
+            }
+        }
         count_tile(sg, lds, key);
+        if (sg.n_ranges) __syncthreads();                 // the next tile repaints
     }
     __syncthreads();
     for (uint32_t k = threadIdx.x; k < n_keys; k += blockDim.x) {
@@ -647,9 +736,15 @@ __device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg
     for (uint32_t round = 0; round < sg.rounds; ++round) {
         for (uint32_t i = threadIdx.x; i < waves * n_keys; i += blockDim.x) lds[i] = 0;
         __syncthreads();
-        const uint64_t wave_begin = p_begin + round * tile_pages + (uint64_t)wave * sg.steps * kWave;
-        uint32_t key[kMaxSteps], fr[kMaxSteps], rk[kMaxSteps];
-        load_tile(a.page_table, a.nu, sg, wave_begin, p_end, key, fr);
+        const uint64_t tile_begin = p_begin + round * tile_pages;
+        const uint64_t wave_begin = tile_begin + (uint64_t)wave * sg.steps * kWave;
+        uint32_t key[kMaxSteps], rk[kMaxSteps];
+#pragma unroll
+        for (int s = 0; s < kMaxSteps; ++s) {
+            const uint64_t p = wave_begin + (uint64_t)s * kWave + lane;
+            const uint16_t k16 = ((uint32_t)s < sg.steps && p < p_end) ? sg.key16[p] : kNoKey16;
+            key[s] = k16 == kNoKey16 ? kNone : (uint32_t)k16;
+        }
         // a key none of whose pages in this chunk can land inside its list is dropped here
 #pragma unroll
         for (int s = 0; s < kMaxSteps; ++s)
@@ -676,7 +771,7 @@ __device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg
                     if (where < n_fetch) a.fetch_pages[where] = p;
                 } else if (where < n_evict) {
                     a.evict_pages[where] = p;
-                    a.evict_frames[where] = fr[s];
+                    a.evict_frames[where] = a.page_table[p];
                 }
             }
         }
@@ -763,6 +858,26 @@ void plan_geometry(const msched_ctx *c, uint32_t G, PlanGeom &g) {
     g.n_chunks = (uint32_t)((c->V + g.chunk_pages - 1) / g.chunk_pages);
 }
 
+__global__ __launch_bounds__(256) void k_copy_ranges(const PageRange *__restrict__ src, PageRange *__restrict__ dst, uint32_t n) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) reinterpret_cast<uint4 *>(dst)[i] = reinterpret_cast<const uint4 *>(src)[i];
+}
+
+// The sweeps may ask for more dynamic LDS than the 64 KiB a kernel gets by default (counters + a painted tile).
+hipError_t allow_large_lds() {
+    static bool done[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= 64) return e == hipSuccess ? hipErrorInvalidDevice : e;
+    if (done[dev]) return hipSuccess;
+    const int bytes = 128 * 1024;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_count), hipFuncAttributeMaxDynamicSharedMemorySize, bytes)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_emit), hipFuncAttributeMaxDynamicSharedMemorySize, bytes)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_tail), hipFuncAttributeMaxDynamicSharedMemorySize, bytes)) != hipSuccess) return e;
+    done[dev] = true;
+    return hipSuccess;
+}
+
 hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     (void)hipGetLastError();   // launches below are checked through the sticky error: start clean
     hipStream_t st = c->stream;
@@ -775,7 +890,9 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         a.n_split = c->expand_split ? c->expand_split : ((c->V > (1u << 20)) ? 8 : 1);
         a.epoch_base = c->epoch << kNuShift;
         // few expansion workgroups: each reads its record over the link itself; many: stage once
-        const bool stage = (uint64_t)g.G * c->max_rules * a.n_split > c->stage_threshold || c->has_list_rule;
+        // painted plans without id lists need no command records on the device at all
+        const bool records = !g.painted || c->has_list_rule;
+        const bool stage = records && ((uint64_t)g.G * c->max_rules * a.n_split > c->stage_threshold || c->has_list_rule);
         a.cmds = stage ? c->cmd_dev : nullptr;
         if (stage)
             k_stage<<<(g.G * 8 + 255) / 256, 256, 0, st>>>(c->cmd_ptrs_dev, g.G, c->cmd_dev, c->list_bucket_fill,
@@ -797,13 +914,20 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
             if (g.G > b1) k_expand_list<<<g.G - b1, kListThreads, 0, st>>>(a, b1, 1, kListSeenBits);
         }
         // the ranges go after the lists: k_list_reduce merges into nu[] without atomics
-        k_expand<<<dim3(g.G, c->max_rules, a.n_split), 256, 0, st>>>(a);
+        if (!g.painted) k_expand<<<dim3(g.G, c->max_rules, a.n_split), 256, 0, st>>>(a);
     }
-    if (prof) CK(hipEventRecord(c->ev[1], st));
     SweepGeom sg;
     sg.V = c->V; sg.chunk_pages = g.chunk_pages; sg.steps = g.steps; sg.rounds = g.rounds; sg.G = g.G;
     sg.epoch = c->epoch;
+    sg.n_ranges = g.n_ranges; sg.use_nu = g.use_nu ? 1u : 0u; sg.slot = c->slot; sg.flags = c->flags; sg.key16 = c->key16;
+    // one workgroup reads the range list where the host wrote it; many read a device copy
+    sg.ranges = g.single ? c->ranges_host_dev : c->ranges_dev;
+    if (g.n_ranges && !g.single)
+        k_copy_ranges<<<(g.n_ranges + 255) / 256, 256, 0, st>>>(c->ranges_host_dev, c->ranges_dev, g.n_ranges);
+    if (prof) CK(hipEventRecord(c->ev[1], st));
     const uint32_t threads = g.waves * kWave;
+    const size_t paint_lds = g.n_ranges ? (size_t)g.waves * g.steps * kWave * 4 : 0;
+    if (!getenv("MSCHED_NO_LARGE_LDS")) CK(allow_large_lds());
     const bool few_rows = g.n_chunks <= kRowGroups;          // the matrix rows are the row groups
     CutArgs ca;
     ca.groups = few_rows ? c->matrix : c->partial; ca.n_groups = few_rows ? g.n_chunks : kRowGroups;
@@ -815,11 +939,11 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     ea.fetch_pages = c->fetch_pages; ea.evict_pages = c->evict_pages; ea.evict_frames = c->evict_frames;
     const size_t cut_lds = (size_t)(g.n_keys + g.G + 1) * 4, emit_lds = (size_t)(g.waves + 1) * g.n_keys * 4;
     if (g.single) {
-        k_tail<<<1, threads, std::max(cut_lds, emit_lds), st>>>(sg, ca, ea, c->fetch_frames);
+        k_tail<<<1, threads, std::max(cut_lds, emit_lds + paint_lds), st>>>(sg, ca, ea, c->fetch_frames);
         if (c->profiling) CK(hipEventRecord(c->ev[4], st));
         return hipGetLastError();
     }
-    k_count<<<g.n_chunks, threads, (size_t)g.n_keys * 4, st>>>(c->page_table, c->nu, sg, c->matrix,
+    k_count<<<g.n_chunks, threads, (size_t)g.n_keys * 4 + paint_lds, st>>>(c->page_table, c->nu, sg, c->matrix,
                                                                 few_rows ? nullptr : c->partial);
     if (prof) CK(hipEventRecord(c->ev[2], st));
     const dim3 cgrid((g.n_keys + 63) / 64, kRowGroups / 4), cblock(64, 4);
