@@ -33,9 +33,12 @@ __device__ __forceinline__ uint64_t lanes_below() { return (1ull << lane_id()) -
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_stage(const CmdRec *const *__restrict__ cmd_ptrs, uint32_t G,
                                                 CmdRec *__restrict__ cmd_dev, uint32_t *__restrict__ bucket_fill,
-                                                uint32_t n_buckets) {
+                                                uint32_t n_buckets, const PageRange *__restrict__ ranges_src,
+                                                PageRange *__restrict__ ranges_dst, uint32_t n_ranges) {
     const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
     for (uint32_t b = t; b < n_buckets; b += gridDim.x * blockDim.x) bucket_fill[b] = 0;   // binned id lists start empty
+    for (uint32_t r = t; r < n_ranges; r += gridDim.x * blockDim.x)                        // the range list rides along
+        reinterpret_cast<uint4 *>(ranges_dst)[r] = reinterpret_cast<const uint4 *>(ranges_src)[r];
     const uint32_t g = t >> 3, part = t & 7;
     if (g >= G) return;
     const uint64_t tagged = reinterpret_cast<uint64_t>(cmd_ptrs[g]);
@@ -615,6 +618,7 @@ struct CutArgs {
     uint32_t *flags, *offsets;
     PlanHeader *hdr_dev, *hdr_host;
     uint32_t *need_host, *landed;      // early execution (both null when it is off)
+    uint32_t in_place;                 // replace `groups` by their exclusive prefix over the rows (they are the matrix itself)
 };
 
 __device__ void cut_body(const CutArgs &a, uint32_t *lds) {
@@ -632,7 +636,7 @@ __device__ void cut_body(const CutArgs &a, uint32_t *lds) {
         uint32_t run = 0;
 #pragma unroll
         for (uint32_t rg = 0; rg < kRowGroups; ++rg) {
-            if (rg < a.n_groups) a.groups[rg * n_keys + key] = run;
+            if (rg < a.n_groups && a.in_place) a.groups[rg * n_keys + key] = run;
             run += v[rg];
         }
         tot[key] = run;
@@ -686,17 +690,14 @@ __global__ __launch_bounds__(1024) void k_cut(CutArgs a) {
     cut_body(a, lds);
 }
 
-// matrix[w][key] = pages of that key in chunks before w (exclusive prefix down each column).  The
-// row-group sums are consumed here and cleared for the next plan's counting sweep to add into.
-__global__ __launch_bounds__(256) void k_offsets(uint32_t *__restrict__ matrix, uint32_t n_chunks, uint32_t n_keys,
-                                                 uint32_t *__restrict__ partial,
-                                                 const PlanHeader *__restrict__ hdr) {
-    const uint32_t key = blockIdx.x * 64 + threadIdx.x;
-    const uint32_t rg = blockIdx.y * 4 + threadIdx.y;
-    if (key >= n_keys) return;
-    uint32_t run = partial[rg * n_keys + key];
-    partial[rg * n_keys + key] = 0;
-    if (hdr->n_fetch == 0) return;
+// matrix[w][key] = pages of that key in chunks before w (exclusive prefix down each column), one thread per
+// (key, row group): it starts from the sums of the row groups before its own and walks its rows.
+__device__ __forceinline__ void offsets_body(uint32_t *__restrict__ matrix, uint32_t n_chunks, uint32_t n_keys,
+                                             const uint32_t *__restrict__ partial, uint32_t item) {
+    const uint32_t key = item % n_keys, rg = item / n_keys;
+    if (rg >= kRowGroups) return;
+    uint32_t run = 0;
+    for (uint32_t before = 0; before < rg; ++before) run += partial[before * n_keys + key];
     const uint32_t rows = (n_chunks + kRowGroups - 1) / kRowGroups;
     const uint32_t w0 = rg * rows, w1 = min(n_chunks, w0 + rows);
 #pragma unroll 8
@@ -706,6 +707,15 @@ __global__ __launch_bounds__(256) void k_offsets(uint32_t *__restrict__ matrix, 
         matrix[i] = run;
         run += v;
     }
+}
+
+// The cut (one workgroup, a chain of block-wide scans) and the column prefixes (wide) need the same input,
+// the per-key sums of the row groups, and nothing from each other: one launch, block 0 cuts.
+__global__ __launch_bounds__(1024) void k_cut_offsets(CutArgs a, uint32_t *__restrict__ matrix, uint32_t n_chunks,
+                                                        uint32_t n_keys) {
+    extern __shared__ uint32_t lds[];
+    if (blockIdx.x == 0) { cut_body(a, lds); return; }
+    offsets_body(matrix, n_chunks, n_keys, a.groups, (blockIdx.x - 1) * blockDim.x + threadIdx.x);
 }
 
 // Second sweep over one chunk: every listed page goes to its final position =
@@ -795,8 +805,11 @@ __device__ __forceinline__ void frames_body(const PlanHeader *hdr, const uint32_
 
 __global__ __launch_bounds__(256) void k_frames(const PlanHeader *__restrict__ hdr,
                                                 const uint32_t *__restrict__ evict_frames,
-                                                uint32_t *__restrict__ fetch_frames) {
-    frames_body(hdr, evict_frames, fetch_frames, blockIdx.x * blockDim.x + threadIdx.x, gridDim.x * blockDim.x);
+                                                uint32_t *__restrict__ fetch_frames, uint32_t *__restrict__ partial,
+                                                uint32_t n_partial) {
+    const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x, nt = gridDim.x * blockDim.x;
+    for (uint32_t i = t; i < n_partial; i += nt) partial[i] = 0;    // the next plan's first sweep adds into these
+    frames_body(hdr, evict_frames, fetch_frames, t, nt);
 }
 
 // Page tables small enough for one workgroup: count, cut, emit and frame assignment in one launch
@@ -894,9 +907,13 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         const bool records = !g.painted || c->has_list_rule;
         const bool stage = records && ((uint64_t)g.G * c->max_rules * a.n_split > c->stage_threshold || c->has_list_rule);
         a.cmds = stage ? c->cmd_dev : nullptr;
+        const bool copy_ranges = g.n_ranges && !g.single;
         if (stage)
             k_stage<<<(g.G * 8 + 255) / 256, 256, 0, st>>>(c->cmd_ptrs_dev, g.G, c->cmd_dev, c->list_bucket_fill,
-                                                           g.list_binned ? g.n_buckets * 8 : 0);
+                                                           g.list_binned ? g.n_buckets * 8 : 0, c->ranges_host_dev,
+                                                           c->ranges_dev, copy_ranges ? g.n_ranges : 0);
+        else if (copy_ranges)
+            k_copy_ranges<<<(g.n_ranges + 255) / 256, 256, 0, st>>>(c->ranges_host_dev, c->ranges_dev, g.n_ranges);
         // Id lists go first in three stream-ordered batches of growing size: the smallest g wins a page,
         // so once the first few commands have written the popular pages, the check in front of the
         // atomic turns every later touch of them into a plain (cached) load.
@@ -922,8 +939,6 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     sg.n_ranges = g.n_ranges; sg.use_nu = g.use_nu ? 1u : 0u; sg.slot = c->slot; sg.flags = c->flags; sg.key16 = c->key16;
     // one workgroup reads the range list where the host wrote it; many read a device copy
     sg.ranges = g.single ? c->ranges_host_dev : c->ranges_dev;
-    if (g.n_ranges && !g.single)
-        k_copy_ranges<<<(g.n_ranges + 255) / 256, 256, 0, st>>>(c->ranges_host_dev, c->ranges_dev, g.n_ranges);
     if (prof) CK(hipEventRecord(c->ev[1], st));
     const uint32_t threads = g.waves * kWave;
     const size_t paint_lds = g.n_ranges ? (size_t)g.waves * g.steps * kWave * 4 : 0;
@@ -934,6 +949,7 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     ca.G = g.G; ca.g_end0 = g.g_end0; ca.F = c->F; ca.flags = c->flags; ca.offsets = c->offsets;
     ca.hdr_dev = c->hdr_dev; ca.hdr_host = c->hdr_host;
     ca.need_host = c->early ? c->need_host : nullptr; ca.landed = c->early ? c->landed : nullptr;
+    ca.in_place = few_rows ? 1u : 0u;
     EmitArgs ea;
     ea.page_table = c->page_table; ea.nu = c->nu; ea.matrix = c->matrix; ea.offsets = c->offsets; ea.hdr = c->hdr_dev;
     ea.fetch_pages = c->fetch_pages; ea.evict_pages = c->evict_pages; ea.evict_frames = c->evict_frames;
@@ -946,14 +962,18 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     k_count<<<g.n_chunks, threads, (size_t)g.n_keys * 4 + paint_lds, st>>>(c->page_table, c->nu, sg, c->matrix,
                                                                 few_rows ? nullptr : c->partial);
     if (prof) CK(hipEventRecord(c->ev[2], st));
-    const dim3 cgrid((g.n_keys + 63) / 64, kRowGroups / 4), cblock(64, 4);
     const uint32_t cut_threads = std::min<uint32_t>(1024, std::max<uint32_t>(256, (g.n_keys / 2 + 63) / 64 * 64));
-    k_cut<<<1, cut_threads, cut_lds, st>>>(ca);
-    if (!few_rows) k_offsets<<<cgrid, cblock, 0, st>>>(c->matrix, g.n_chunks, g.n_keys, c->partial, c->hdr_dev);
+    if (few_rows) {
+        k_cut<<<1, cut_threads, cut_lds, st>>>(ca);
+    } else {
+        const uint32_t items = g.n_keys * kRowGroups;
+        k_cut_offsets<<<1 + (items + cut_threads - 1) / cut_threads, cut_threads, cut_lds, st>>>(ca, c->matrix, g.n_chunks, g.n_keys);
+    }
     if (prof) CK(hipEventRecord(c->ev[3], st));
     k_emit<<<g.n_chunks, threads, emit_lds, st>>>(ea, sg);
     const uint32_t fblocks = (uint32_t)std::min<uint64_t>(2048, ((uint64_t)c->F + 255) / 256);
-    k_frames<<<fblocks, 256, 0, st>>>(c->hdr_dev, c->evict_frames, c->fetch_frames);
+    k_frames<<<fblocks, 256, 0, st>>>(c->hdr_dev, c->evict_frames, c->fetch_frames, c->partial,
+                                      few_rows ? 0 : kRowGroups * g.n_keys);
     if (c->profiling) CK(hipEventRecord(c->ev[4], st));
     return hipGetLastError();
 }
