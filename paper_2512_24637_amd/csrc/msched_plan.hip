@@ -441,38 +441,40 @@ __device__ void paint_tile(const SweepGeom &sg, uint64_t t0, uint64_t t1, uint32
     }
 }
 
-// One tile: every wavefront loads its `steps` x 64 consecutive pages (all loads issued before any
-// use) and classifies them.
-__device__ __forceinline__ void load_tile(const uint32_t *__restrict__ page_table, const uint32_t *__restrict__ nu,
-                                          const SweepGeom &sg, uint64_t wave_begin, uint64_t p_end,
-                                          uint32_t (&key)[kMaxSteps], uint32_t (&fr)[kMaxSteps],
-                                          const uint32_t *paint, uint64_t tile_begin, uint32_t floor) {
+// A batch of a tile: the wavefront loads kCountBatch x 64 consecutive pages of its slice (all loads issued
+// before any use) and classifies them.  Eight steps at a time keep the first sweep at half the registers of
+// a whole 16-step slice, which doubles the workgroups a compute unit holds.
+constexpr int kCountBatch = 8;
+__device__ __forceinline__ void load_batch(const uint32_t *__restrict__ page_table, const uint32_t *__restrict__ nu,
+                                           const SweepGeom &sg, uint64_t batch_begin, uint32_t n_steps, uint64_t p_end,
+                                           uint32_t (&key)[kCountBatch], const uint32_t *paint, uint64_t tile_begin,
+                                           uint32_t floor) {
     const int lane = lane_id();
-    uint32_t enc[kMaxSteps];
+    uint32_t enc[kCountBatch], fr[kCountBatch];
 #pragma unroll
-    for (int s = 0; s < kMaxSteps; ++s) {
-        const uint64_t p = wave_begin + (uint64_t)s * kWave + lane;
-        const bool in = (uint32_t)s < sg.steps && p < p_end;
+    for (int s = 0; s < kCountBatch; ++s) {
+        const uint64_t p = batch_begin + (uint64_t)s * kWave + lane;
+        const bool in = (uint32_t)s < n_steps && p < p_end;
         fr[s] = in ? page_table[p] : kNone;
         enc[s] = (in && sg.use_nu) ? nu[p] : 0u;
     }
 #pragma unroll
-    for (int s = 0; s < kMaxSteps; ++s) {
-        const uint64_t p = wave_begin + (uint64_t)s * kWave + lane;
-        const bool in = (uint32_t)s < sg.steps && p < p_end;
+    for (int s = 0; s < kCountBatch; ++s) {
+        const uint64_t p = batch_begin + (uint64_t)s * kWave + lane;
+        const bool in = (uint32_t)s < n_steps && p < p_end;
         const uint32_t painted = (in && sg.n_ranges) ? min(floor, paint[p - tile_begin]) : sg.G;
         key[s] = classify(fr[s], enc[s], sg.epoch, sg.G, painted);
     }
 }
 
-// Count the tile's pages per key into one LDS histogram.  Runs of pages usually share a key (dense
+// Count the batch's pages per key into one LDS histogram.  Runs of pages usually share a key (dense
 // ranges, long stretches of resident pages nobody will use), so the first lane's key is settled for
 // all its lanes with one add; whatever other keys the step holds go through per-lane LDS atomics.
-__device__ __forceinline__ void count_tile(const SweepGeom &sg, uint32_t *hist, const uint32_t (&key)[kMaxSteps]) {
+__device__ __forceinline__ void count_batch(uint32_t n_steps, uint32_t *hist, const uint32_t (&key)[kCountBatch]) {
     const int lane = lane_id();
 #pragma unroll
-    for (int s = 0; s < kMaxSteps; ++s) {
-        if ((uint32_t)s < sg.steps) {
+    for (int s = 0; s < kCountBatch; ++s) {
+        if ((uint32_t)s < n_steps) {
             const bool valid = key[s] != kNone;
             const uint64_t any = __ballot(valid);
             if (any) {
@@ -535,27 +537,28 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
     const uint64_t tile_pages = (uint64_t)waves * sg.steps * kWave;
     uint32_t *paint = lds + n_keys;                       // [tile_pages] when there are ranges to paint
     __shared__ PaintLds s_paint;
+    const int lane = lane_id();
     for (uint32_t round = 0; round < sg.rounds; ++round) {
-        uint32_t key[kMaxSteps], fr[kMaxSteps];
         const uint64_t tile_begin = p_begin + round * tile_pages;
         if (sg.n_ranges) paint_tile(sg, tile_begin, min(p_end, tile_begin + tile_pages), paint, s_paint);
         const uint64_t wave_begin = tile_begin + (uint64_t)wave * sg.steps * kWave;
-        load_tile(page_table, nu, sg, wave_begin, p_end, key, fr, paint, tile_begin, s_paint.floor);
-        if (sg.slot != nullptr && sg.n_ranges) {          // a page a range wants must have a backing slot
-            const int lane = lane_id();
+        for (uint32_t s0 = 0; s0 < sg.steps; s0 += kCountBatch) {
+            uint32_t key[kCountBatch];
+            const uint32_t n_steps = min((uint32_t)kCountBatch, sg.steps - s0);
+            const uint64_t batch_begin = wave_begin + (uint64_t)s0 * kWave;
+            load_batch(page_table, nu, sg, batch_begin, n_steps, p_end, key, paint, tile_begin, s_paint.floor);
+            if (sg.slot != nullptr && sg.n_ranges) {      // a page a range wants must have a backing slot
 #pragma unroll
-            for (int s = 0; s < kMaxSteps; ++s)
-                if (key[s] < sg.G && sg.slot[wave_begin + (uint64_t)s * kWave + lane] == kNone) atomicOr(sg.flags, kStatRange);
-        }
-        {                                                 // the second sweep reads the classes from here, 2 bytes a page
-            const int lane = lane_id();
-#pragma unroll
-            for (int s = 0; s < kMaxSteps; ++s) {
-                const uint64_t p = wave_begin + (uint64_t)s * kWave + lane;
-                if ((uint32_t)s < sg.steps && p < p_end) sg.key16[p] = key[s] == kNone ? kNoKey16 : (uint16_t)key[s];
+                for (int s = 0; s < kCountBatch; ++s)
+                    if (key[s] < sg.G && sg.slot[batch_begin + (uint64_t)s * kWave + lane] == kNone) atomicOr(sg.flags, kStatRange);
             }
+#pragma unroll
+            for (int s = 0; s < kCountBatch; ++s) {       // the second sweep reads the classes from here, 2 bytes a page
+                const uint64_t p = batch_begin + (uint64_t)s * kWave + lane;
+                if ((uint32_t)s < n_steps && p < p_end) sg.key16[p] = key[s] == kNone ? kNoKey16 : (uint16_t)key[s];
+            }
+            count_batch(n_steps, lds, key);
         }
-        count_tile(sg, lds, key);
         if (sg.n_ranges) __syncthreads();                 // the next tile repaints
     }
     __syncthreads();
@@ -789,7 +792,7 @@ __device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg
     }
 }
 
-__global__ __launch_bounds__(kWave * kMaxWaves) void k_emit(EmitArgs a, SweepGeom sg) {
+__global__ __launch_bounds__(kWave * kMaxWaves, 6) void k_emit(EmitArgs a, SweepGeom sg) {
     extern __shared__ uint32_t lds[];
     emit_body(a, sg, chunk_of_block(blockIdx.x, gridDim.x), lds);
 }
