@@ -145,6 +145,10 @@ void free_ctx(msched_ctx *c) {
     if (!c) return;
     (void)hipStreamSynchronize(c->stream);
     for (auto &t : c->tasks) if (t.recs) (void)hipHostFree(t.recs);
+    for (auto &t : c->tasks) if (t.prep_buf) (void)hipFree(t.prep_buf);
+    if (c->list_src_host) (void)hipHostFree(c->list_src_host);
+    if (c->list_prep_host) (void)hipHostFree(c->list_prep_host);
+    if (c->list_src_stage) (void)hipFree(c->list_src_stage);
     void *dev[] = {c->page_table, c->frame_owner, c->nu, c->slot, c->evict_pages, c->evict_frames, c->fetch_pages,
                    c->fetch_frames, c->flags, c->matrix, c->partial, c->offsets, c->hdr_dev, c->kernels_dev,
                    c->query_buf, c->cmd_dev, c->list_bucket_fill, c->list_pairs};
@@ -202,6 +206,9 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     c->dedupe_regions = env_u32("MSCHED_DEDUPE_REGIONS", 0, 1, 1) != 0;
     c->seen.assign(131072, msched_ctx::SeenEntry{0, 0, 0, 0, 0});     // >= 4 x MAX_TIMELINE_COMMANDS x MAX_RULES
     c->plan_recs.resize(MSCHED_MAX_TIMELINE_COMMANDS + 1);
+    c->plan_task.resize(MSCHED_MAX_TIMELINE_COMMANDS + 1);
+    c->list_prepared = (uint32_t)env_u32("MSCHED_LIST_PREPARED", 0, 1, 1);
+    c->list_cache_bytes = (uint64_t)env_u32("MSCHED_LIST_CACHE_MB", 1, 65536, 128) << 20;
     c->force_multi_kernel = env_u32("MSCHED_FORCE_MULTI_KERNEL", 0, 1, 0) != 0;
     c->list_binned_min_ids = (uint64_t)env_u32("MSCHED_LIST_BINNED_MIN_IDS", 0, 1 << 30, 262144);
     c->list_b0 = (uint32_t)env_u32("MSCHED_LIST_B0", 0, 4096, 4);
@@ -337,6 +344,90 @@ int msched_launch_retire(msched_ctx *c, uint32_t task, uint32_t n_launches) {
     return MSCHED_OK;
 }
 
+namespace {
+
+// Room for `bytes` in a task's ring of prepared id lists.  Blocks are handed out in program order and die in
+// program order (with their command's retirement), so the ring's tail is the oldest live command's block.
+bool ring_alloc(msched_ctx *c, TaskQueue &t, uint64_t bytes, uint64_t &off, hipError_t &err) {
+    err = hipSuccess;
+    if (!t.prep_buf) {
+        if ((err = hipMalloc((void **)&t.prep_buf, c->list_cache_bytes)) != hipSuccess) return false;
+        t.prep_size = c->list_cache_bytes;
+    }
+    if (bytes > t.prep_size) return false;
+    uint64_t head = t.prep_head;
+    const uint64_t pos = head % t.prep_size;
+    if (pos + bytes > t.prep_size) head += t.prep_size - pos;        // a block never wraps: skip the ring's end
+    if (head + bytes - t.prep_tail > t.prep_size) {
+        t.prep_tail = t.prep_head;                                     // nothing live, unless a queued command says otherwise
+        for (size_t i = t.cursor; i < t.n; ++i)
+            if (t.recs[i - t.base].reserved) { t.prep_tail = t.recs[i - t.base].reserved - 1; break; }
+        if (head + bytes - t.prep_tail > t.prep_size) return false;
+    }
+    off = head;
+    t.prep_head = head + bytes;
+    return true;
+}
+
+// The pieces of every live id list of the plan: prepared on first sight, reused by every later plan that still
+// has the command in its timeline (a command is typically planned once per task of the round).
+// Returns 0 and fills the two pinned tables, 1 when the pieces do not fit (the caller bins from scratch), or < 0.
+int gather_list_sources(msched_ctx *c, uint32_t G, PlanGeom &g) {
+    if (!c->list_src_host) {
+        HIP_TRY(c, hipHostMalloc((void **)&c->list_src_host, sizeof(ListSource) * kMaxListSources, hipHostMallocDefault));
+        HIP_TRY(c, hipHostGetDevicePointer((void **)&c->list_src_dev, c->list_src_host, 0));
+        HIP_TRY(c, hipHostMalloc((void **)&c->list_prep_host, sizeof(ListPrep) * kMaxListSources, hipHostMallocDefault));
+        HIP_TRY(c, hipHostGetDevicePointer((void **)&c->list_prep_dev, c->list_prep_host, 0));
+        HIP_TRY(c, hipMalloc((void **)&c->list_src_stage, sizeof(ListSource) * kMaxListSources));
+    }
+    uint32_t n_src = 0, n_new = 0;
+    std::vector<CmdRec *> fresh;
+    std::vector<std::pair<TaskQueue *, uint64_t>> heads;
+    auto undo = [&]() {
+        for (CmdRec *r : fresh) r->reserved = 0;
+        for (auto it = heads.rbegin(); it != heads.rend(); ++it) it->first->prep_head = it->second;
+    };
+    const uint64_t hdr_words = (uint64_t)g.n_buckets + 2;
+    for (uint32_t gi = 0; gi < G; ++gi) {
+        CmdRec &rec = const_cast<CmdRec &>(*c->plan_recs[gi]);
+        const DevKernel &k = c->kernels[rec.kernel];
+        const uint64_t skip = reinterpret_cast<uintptr_t>(c->cmd_ptrs_host[gi]) >> 56;
+        bool live = false;
+        for (uint32_t r = 0; r < k.n_rules; ++r) live |= k.rules[r].kind == MSCHED_RULE_LIST && !((skip >> r) & 1);
+        if (!live || rec.n_ids == 0) continue;
+        const uint32_t pieces = (rec.n_ids + kPrepBlock - 1) / kPrepBlock;
+        if (n_src + pieces > kMaxListSources) { undo(); return 1; }
+        TaskQueue &t = c->tasks[c->plan_task[gi]];
+        const bool is_new = rec.reserved == 0;
+        if (is_new) {
+            const uint64_t bytes = (((uint64_t)pieces * hdr_words + rec.n_ids) * 4 + 15) & ~15ull;
+            uint64_t off;
+            hipError_t err;
+            heads.emplace_back(&t, t.prep_head);
+            if (!ring_alloc(c, t, bytes, off, err)) {
+                heads.pop_back();
+                undo();
+                if (err != hipSuccess) { c->last_hip = g_last_hip = (int)err; return MSCHED_E_HIP; }
+                return 1;
+            }
+            rec.reserved = off + 1;
+            fresh.push_back(&rec);
+        }
+        uint32_t *block = reinterpret_cast<uint32_t *>(t.prep_buf + (rec.reserved - 1) % t.prep_size);
+        for (uint32_t p = 0; p < pieces; ++p) {
+            const uint32_t n = std::min<uint32_t>(kPrepBlock, rec.n_ids - p * kPrepBlock);
+            if (is_new) c->list_prep_host[n_new++] = {rec.ids + (size_t)p * kPrepBlock, block, n, {0, 0, 0}};
+            c->list_src_host[n_src++] = {block, gi, 0};
+            block += hdr_words + n;
+        }
+    }
+    g.n_list_sources = n_src;
+    g.n_list_new = n_new;
+    return 0;
+}
+
+}  // namespace
+
 int msched_plan(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entries, msched_plan_t *out) {
     if (!c || !out || (n_entries && !tl) || n_entries > MSCHED_MAX_TIMELINE_ENTRIES) return MSCHED_E_INVAL;
     for (uint32_t e = 0; e < n_entries; ++e) if (tl[e].task >= c->tasks.size()) return MSCHED_E_INVAL;
@@ -358,6 +449,7 @@ int msched_plan(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entri
         while (p < t.n && elapsed < tl[e].timeslice) {
             if (G == MSCHED_MAX_TIMELINE_COMMANDS) return MSCHED_E_INVAL;
             c->plan_recs[G] = &t.recs[p - t.base];
+            c->plan_task[G] = tl[e].task;
             c->cmd_ptrs_host[G++] = t.recs_dev + (p - t.base);
             elapsed += t.recs[p - t.base].latency;
             ++p;
@@ -416,6 +508,8 @@ int msched_plan(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entri
         g.use_nu = !painted || live_list;
         // Id lists: how many ids does this plan carry (repeated lists excluded)?  Many -> bucket path.
         g.list_binned = false;
+        g.list_prepared = false;
+        g.n_list_sources = g.n_list_new = 0;
         g.n_buckets = (uint32_t)((c->V + (1u << 13) - 1) >> 13);           // buckets of 8 Ki pages
         if (c->has_list_rule && g.n_buckets <= kMaxBuckets) {
             uint64_t total = 0;
@@ -428,7 +522,12 @@ int msched_plan(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entri
                     live |= k.rules[r].kind == MSCHED_RULE_LIST && !((skip >> r) & 1);
                 if (live) total += rec.n_ids;
             }
-            if (total >= c->list_binned_min_ids && total < (1ull << 31)) {
+            if (total >= c->list_binned_min_ids && total < (1ull << 31) && c->list_prepared) {
+                const int rc_src = gather_list_sources(c, G, g);
+                if (rc_src < 0) return rc_src;
+                g.list_prepared = rc_src == 0;
+            }
+            if (total >= c->list_binned_min_ids && total < (1ull << 31) && !g.list_prepared) {
                 g.list_binned = true;
                 // room per sub-segment (8 per bucket): four times the average, at least 256 pairs
                 g.bucket_cap = (uint32_t)std::max<uint64_t>(256, 4 * total / ((uint64_t)g.n_buckets * 8) + 1);

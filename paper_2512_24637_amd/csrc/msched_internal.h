@@ -32,7 +32,8 @@ constexpr uint32_t kStatWset = 2u;              // first command alone exceeds t
 struct alignas(16) CmdRec {
     uint32_t kernel, n_args, latency, n_ids;
     const uint32_t *ids;                        // device pointer (caller-owned) or null
-    uint64_t reserved;
+    uint64_t reserved;                          // host copy: 1 + ring offset of the command's prepared id list (0 = none);
+                                                // device copy: mask of rules to skip in this plan
     uint64_t args[MSCHED_MAX_ARGS];
 };
 static_assert(sizeof(CmdRec) == 128, "CmdRec layout");
@@ -55,7 +56,20 @@ struct TaskQueue {
     size_t base = 0;                            // program-order index of recs[0]
     size_t n = 0;                               // commands ever enqueued
     size_t cursor = 0;                          // first command not yet retired
+    // prepared id lists of this task's queued commands: a ring in device memory, filled in program order
+    uint8_t *prep_buf = nullptr;
+    uint64_t prep_size = 0, prep_head = 0, prep_tail = 0;   // head / tail are running byte offsets (never wrap)
 };
+
+// One source of the id-list merge: a prepared (de-duplicated, grouped by bucket) piece of a command's list.
+//   block[0] = 1 if the piece held an id that is out of range or has no backing slot
+//   block[1 .. n_buckets + 1] = start of every bucket's ids (exclusive prefix, last = total)
+//   block[n_buckets + 2 ..] = the ids
+struct ListSource { const uint32_t *block; uint32_t g, pad; };
+// A piece still to be prepared: n ids of a command's list, and where its block goes.
+struct ListPrep { const uint32_t *ids; uint32_t *block; uint32_t n, pad[3]; };
+constexpr uint32_t kMaxListSources = 4096;
+constexpr uint32_t kPrepBlock = 24576;          // ids per prepared piece (what one workgroup keeps in LDS)
 
 // A page range [lo, hi) first used by command g: what a fixed / linear rule, or one chunk of a strided
 // rule, describes once its formulas are evaluated.
@@ -67,6 +81,8 @@ struct PlanGeom {
     uint32_t waves, steps, rounds;                       // sweep workgroup shape
     bool single;                                         // one workgroup sweeps the whole table (fused tail kernel)
     bool list_binned;                                    // id lists go through the bucket path
+    bool list_prepared;                                  // ... from per-command prepared pieces (cached across plans)
+    uint32_t n_list_sources, n_list_new;                 // pieces merged by this plan; of those, prepared by it
     uint32_t n_buckets, bucket_cap;                      // bucket_cap: pairs per sub-segment
     bool painted;                                        // range rules arrive as a range list the sweeps paint into LDS
     bool use_nu;                                         // some next uses are in nu[] (id lists, or the scatter path)
@@ -99,6 +115,14 @@ struct msched_ctx {
     uint32_t *list_bucket_fill = nullptr;       // [kMaxBuckets][8]
     uint32_t *list_pairs = nullptr; size_t list_cap = 0;   // n_buckets x 8 x bucket_cap
     uint64_t list_binned_min_ids = 262144;      // plans with at least this many ids take the bucket path
+    uint32_t list_prepared = 1;                 // 0: bin every plan's ids from scratch (MSCHED_LIST_PREPARED)
+    uint64_t list_cache_bytes = 128ull << 20;   // ring of prepared pieces per task (MSCHED_LIST_CACHE_MB)
+    msched::ListSource *list_src_host = nullptr;   // pinned [kMaxListSources]: the pieces this plan merges
+    msched::ListSource *list_src_dev = nullptr;    // the same memory, device address
+    msched::ListPrep *list_prep_host = nullptr;    // pinned [kMaxListSources]: the pieces this plan has to prepare first
+    msched::ListPrep *list_prep_dev = nullptr;
+    msched::ListSource *list_src_stage = nullptr;  // device copy of the source table (every merge workgroup reads it)
+    std::vector<uint32_t> plan_task;               // task of the g-th future command
     uint32_t list_b0 = 4, list_b1 = 32;         // id lists: commands [0,b0), [b0,b1), [b1,G) run as ordered batches
     uint32_t *page_table = nullptr, *frame_owner = nullptr, *nu = nullptr, *slot = nullptr;  // device
     uint32_t *evict_pages = nullptr, *evict_frames = nullptr, *fetch_pages = nullptr, *fetch_frames = nullptr;

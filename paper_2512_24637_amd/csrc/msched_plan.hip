@@ -34,8 +34,12 @@ __device__ __forceinline__ uint64_t lanes_below() { return (1ull << lane_id()) -
 __global__ __launch_bounds__(256) void k_stage(const CmdRec *const *__restrict__ cmd_ptrs, uint32_t G,
                                                 CmdRec *__restrict__ cmd_dev, uint32_t *__restrict__ bucket_fill,
                                                 uint32_t n_buckets, const PageRange *__restrict__ ranges_src,
-                                                PageRange *__restrict__ ranges_dst, uint32_t n_ranges) {
+                                                PageRange *__restrict__ ranges_dst, uint32_t n_ranges,
+                                                const ListSource *__restrict__ list_src, ListSource *__restrict__ list_dst,
+                                                uint32_t n_list_src) {
     const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+    for (uint32_t i = t; i < n_list_src; i += gridDim.x * blockDim.x)                      // and so does the table of list pieces
+        reinterpret_cast<uint4 *>(list_dst)[i] = reinterpret_cast<const uint4 *>(list_src)[i];
     for (uint32_t b = t; b < n_buckets; b += gridDim.x * blockDim.x) bucket_fill[b] = 0;   // binned id lists start empty
     for (uint32_t r = t; r < n_ranges; r += gridDim.x * blockDim.x)                        // the range list rides along
         reinterpret_cast<uint4 *>(ranges_dst)[r] = reinterpret_cast<const uint4 *>(ranges_src)[r];
@@ -348,6 +352,124 @@ __global__ __launch_bounds__(kListThreads) void k_list_reduce(ListArgs a) {
         const uint32_t cur = a.e.nu[p];
         const uint32_t enc = a.e.epoch_base | v;
         if (v && cur < enc) a.e.nu[p] = enc;                 // this workgroup is the only writer of its slice
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Prepared id lists.  Binning a command's ids by bucket does not depend on the plan, only merging them under
+// the command's position g does, and a queued command is planned again at every context switch until it has
+// run.  So the first plan that sees a command bins its list once, into a block of its own (no shared
+// cursors, no global atomics), and every plan merges the blocks of the commands in its timeline:
+//   k_list_prepare  per new piece (up to 24 Ki ids): drop repeats in LDS, count per bucket, exclusive scan,
+//                   write the bucket starts and the ids grouped by bucket
+//   k_list_merge    per bucket: gather that bucket's ids from every piece of the plan, max-reduce them under
+//                   their commands' g in a 32 KiB LDS table, merge the table into the bucket's slice of nu[]
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kListThreads) void k_list_prepare(const ListPrep *__restrict__ prep, uint32_t n_buckets,
+                                                               uint64_t V, const uint32_t *__restrict__ slot) {
+    extern __shared__ uint32_t bin_lds[];
+    uint32_t *seen = bin_lds;                               // [1 << kBinSeenBits]
+    uint32_t *kept = seen + (1u << kBinSeenBits);           // [kPrepBlock]
+    uint32_t *cnt = kept + kPrepBlock;                      // [n_buckets + 1] counts, then starts, then write cursors
+    __shared__ uint32_t n_kept, bad;
+    __shared__ uint32_t wave_sums[kListThreads / kWave];
+    const ListPrep pr = prep[blockIdx.x];
+    const uint32_t n = min(pr.n, kPrepBlock);
+    for (uint32_t i = threadIdx.x; i < (1u << kBinSeenBits); i += blockDim.x) seen[i] = kNone;
+    for (uint32_t b = threadIdx.x; b <= n_buckets; b += blockDim.x) cnt[b] = 0;
+    if (threadIdx.x == 0) { n_kept = 0; bad = 0; }
+    __syncthreads();
+    const int lane = lane_id();
+    const uint64_t below = lanes_below();
+    for (uint32_t base = 0; base < n; base += blockDim.x * kBatch) {
+        uint32_t p[kBatch];
+        bool ok[kBatch];
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const uint32_t i = base + j * blockDim.x + threadIdx.x;
+            ok[j] = i < n;
+            p[j] = ok[j] ? pr.ids[i] : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            if (ok[j] && p[j] >= V) { bad = 1; ok[j] = false; }
+            if (ok[j] && slot != nullptr && slot[p[j]] == kNone) { bad = 1; ok[j] = false; }
+            if (ok[j]) {
+                const uint32_t h = (p[j] * 2654435761u) >> (32 - kBinSeenBits);
+                if (atomicExch(&seen[h], p[j]) == p[j]) ok[j] = false;
+            }
+            const uint64_t keep = __ballot(ok[j]);
+            if (keep) {
+                uint32_t start = 0;
+                const int leader = __ffsll((long long)keep) - 1;
+                if (lane == leader) start = atomicAdd(&n_kept, (uint32_t)__popcll(keep));
+                start = __builtin_amdgcn_readlane(start, leader);
+                if (ok[j]) {
+                    kept[start + __popcll(keep & below)] = p[j];
+                    atomicAdd(&cnt[p[j] >> kBucketShift], 1u);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    block_exclusive_scan(cnt, n_buckets + 1, wave_sums);   // cnt[b] = start of bucket b, cnt[n_buckets] = total
+    uint32_t *block = pr.block;
+    if (threadIdx.x == 0) block[0] = bad;
+    for (uint32_t b = threadIdx.x; b <= n_buckets; b += blockDim.x) block[1 + b] = cnt[b];
+    __syncthreads();
+    uint32_t *out = block + n_buckets + 2;
+    const uint32_t m = n_kept;
+    for (uint32_t i = threadIdx.x; i < m; i += blockDim.x) {
+        const uint32_t p = kept[i];
+        out[atomicAdd(&cnt[p >> kBucketShift], 1u)] = p;   // the starts double as write cursors
+    }
+}
+
+struct MergeArgs {
+    const ListSource *src; uint32_t n_src, n_buckets;
+    uint32_t *nu; uint32_t *flags; uint64_t V; uint32_t epoch_base;
+};
+
+__global__ __launch_bounds__(kListThreads) void k_list_merge(MergeArgs a) {
+    const uint32_t b = blockIdx.x;
+    __shared__ uint32_t tab[kBucketPages];
+    __shared__ uint32_t pre[kMaxListSources + 1];           // ids of this bucket in the pieces before s
+    __shared__ uint32_t wave_sums[kListThreads / kWave];
+    for (uint32_t s = threadIdx.x; s < a.n_src; s += blockDim.x) {
+        const uint32_t *blk = a.src[s].block;
+        pre[s] = blk[2 + b] - blk[1 + b];
+        if (b == 0 && blk[0]) atomicOr(a.flags, kStatRange);   // the piece held an id that cannot be planned
+    }
+    if (threadIdx.x == 0) pre[a.n_src] = 0;
+    __syncthreads();
+    const uint32_t total = block_exclusive_scan(pre, a.n_src + 1, wave_sums);
+    if (total == 0) return;
+    for (uint32_t i = threadIdx.x; i < kBucketPages; i += blockDim.x) tab[i] = 0;
+    __syncthreads();
+    for (uint32_t i0 = threadIdx.x; i0 < total; i0 += blockDim.x * 4) {     // four ids in flight per lane
+        uint32_t id[4], enc[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t i = i0 + j * blockDim.x;
+            id[j] = kNone;
+            if (i < total) {
+                uint32_t lo = 0, hi = a.n_src;                              // last s with pre[s] <= i
+                while (hi - lo > 1) { const uint32_t mid = (lo + hi) >> 1; if (pre[mid] <= i) lo = mid; else hi = mid; }
+                const ListSource S = a.src[lo];
+                id[j] = S.block[a.n_buckets + 2 + S.block[1 + b] + (i - pre[lo])];
+                enc[j] = kNuMask - S.g;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (id[j] != kNone) atomicMax(&tab[id[j] & (kBucketPages - 1)], enc[j]);   // never 0
+    }
+    __syncthreads();
+    const uint64_t p0 = (uint64_t)b << kBucketShift;
+    const uint64_t p1 = min(a.V, p0 + kBucketPages);
+    for (uint64_t p = p0 + threadIdx.x; p < p1; p += blockDim.x) {
+        const uint32_t v = tab[p - p0];
+        if (v) a.nu[p] = a.epoch_base | v;                   // this workgroup is the only writer of its slice
     }
 }
 
@@ -914,13 +1036,23 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         if (stage)
             k_stage<<<(g.G * 8 + 255) / 256, 256, 0, st>>>(c->cmd_ptrs_dev, g.G, c->cmd_dev, c->list_bucket_fill,
                                                            g.list_binned ? g.n_buckets * 8 : 0, c->ranges_host_dev,
-                                                           c->ranges_dev, copy_ranges ? g.n_ranges : 0);
+                                                           c->ranges_dev, copy_ranges ? g.n_ranges : 0,
+                                                           c->list_src_dev, c->list_src_stage,
+                                                           g.list_prepared ? g.n_list_sources : 0);
         else if (copy_ranges)
             k_copy_ranges<<<(g.n_ranges + 255) / 256, 256, 0, st>>>(c->ranges_host_dev, c->ranges_dev, g.n_ranges);
         // Id lists go first in three stream-ordered batches of growing size: the smallest g wins a page,
         // so once the first few commands have written the popular pages, the check in front of the
         // atomic turns every later touch of them into a plain (cached) load.
-        if (c->has_list_rule && g.list_binned) {
+        if (c->has_list_rule && g.list_prepared) {
+            const size_t prep_lds = 4 * ((size_t)(1u << kBinSeenBits) + kPrepBlock + g.n_buckets + 1);
+            if (g.n_list_new)
+                k_list_prepare<<<g.n_list_new, kListThreads, prep_lds, st>>>(c->list_prep_dev, g.n_buckets, c->V, c->slot);
+            MergeArgs ma;
+            ma.src = c->list_src_stage; ma.n_src = g.n_list_sources; ma.n_buckets = g.n_buckets;
+            ma.nu = c->nu; ma.flags = c->flags; ma.V = c->V; ma.epoch_base = a.epoch_base;
+            if (g.n_list_sources) k_list_merge<<<g.n_buckets, kListThreads, 0, st>>>(ma);
+        } else if (c->has_list_rule && g.list_binned) {
             ListArgs la;
             la.e = a; la.bucket_fill = c->list_bucket_fill; la.pairs = c->list_pairs;
             la.n_buckets = g.n_buckets; la.sub_cap = g.bucket_cap;
