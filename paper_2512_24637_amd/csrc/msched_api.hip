@@ -510,7 +510,7 @@ int msched_plan(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entri
         g.list_binned = false;
         g.list_prepared = false;
         g.n_list_sources = g.n_list_new = 0;
-        g.n_buckets = (uint32_t)((c->V + (1u << 13) - 1) >> 13);           // buckets of 8 Ki pages
+        g.n_buckets = (uint32_t)((c->V + (1u << kBucketShift) - 1) >> kBucketShift);
         if (c->has_list_rule && g.n_buckets <= kMaxBuckets) {
             uint64_t total = 0;
             for (uint32_t gi = 0; gi < G; ++gi) {

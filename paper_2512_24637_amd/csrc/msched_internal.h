@@ -69,6 +69,7 @@ struct ListSource { const uint32_t *block; uint32_t g, pad; };
 // A piece still to be prepared: n ids of a command's list, and where its block goes.
 struct ListPrep { const uint32_t *ids; uint32_t *block; uint32_t n, pad[3]; };
 constexpr uint32_t kMaxListSources = 4096;
+constexpr uint32_t kBucketShift = 13;           // id lists are grouped by bucket of this many (log2) consecutive pages
 constexpr uint32_t kPrepBlock = 24576;          // ids per prepared piece (what one workgroup keeps in LDS)
 
 // A page range [lo, hi) first used by command g: what a fixed / linear rule, or one chunk of a strided

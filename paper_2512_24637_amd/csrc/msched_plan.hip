@@ -222,7 +222,6 @@ __global__ __launch_bounds__(kListThreads) void k_expand_list(ExpandArgs a, uint
 // ------------------------------------------------------------------------------------------
 __device__ uint32_t block_exclusive_scan(uint32_t *a, uint32_t n, uint32_t *wave_sums);
 
-constexpr uint32_t kBucketShift = 13;                       // 8 Ki pages per bucket: a 32 KiB table in LDS
 constexpr uint32_t kBucketPages = 1u << kBucketShift;
 constexpr uint32_t kBinSeenBits = 13;                       // duplicate filter: 8 Ki entries, 32 KiB
 constexpr uint32_t kBinBlock = 24576;                       // ids handled per pass of k_list_bin (survivors: 96 KiB of LDS)
@@ -433,12 +432,18 @@ struct MergeArgs {
 __global__ __launch_bounds__(kListThreads) void k_list_merge(MergeArgs a) {
     const uint32_t b = blockIdx.x;
     __shared__ uint32_t tab[kBucketPages];
-    __shared__ uint32_t pre[kMaxListSources + 1];           // ids of this bucket in the pieces before s
     __shared__ uint32_t wave_sums[kListThreads / kWave];
+    extern __shared__ uint64_t merge_lds[];
+    const uint32_t **first = reinterpret_cast<const uint32_t **>(merge_lds);   // [n_src] this bucket's first id in piece s
+    uint32_t *pre = reinterpret_cast<uint32_t *>(first + a.n_src);             // [n_src + 1] ids of this bucket in the pieces before s
+    uint32_t *enc = pre + a.n_src + 1;                                          // [n_src] next-use code of the piece's command
     for (uint32_t s = threadIdx.x; s < a.n_src; s += blockDim.x) {
-        const uint32_t *blk = a.src[s].block;
-        pre[s] = blk[2 + b] - blk[1 + b];
-        if (b == 0 && blk[0]) atomicOr(a.flags, kStatRange);   // the piece held an id that cannot be planned
+        const ListSource S = a.src[s];
+        const uint32_t lo = S.block[1 + b], hi = S.block[2 + b];
+        first[s] = S.block + a.n_buckets + 2 + lo;
+        pre[s] = hi - lo;
+        enc[s] = kNuMask - S.g;
+        if (b == 0 && S.block[0]) atomicOr(a.flags, kStatRange);   // the piece held an id that cannot be planned
     }
     if (threadIdx.x == 0) pre[a.n_src] = 0;
     __syncthreads();
@@ -446,23 +451,23 @@ __global__ __launch_bounds__(kListThreads) void k_list_merge(MergeArgs a) {
     if (total == 0) return;
     for (uint32_t i = threadIdx.x; i < kBucketPages; i += blockDim.x) tab[i] = 0;
     __syncthreads();
-    for (uint32_t i0 = threadIdx.x; i0 < total; i0 += blockDim.x * 4) {     // four ids in flight per lane
-        uint32_t id[4], enc[4];
+    constexpr int kInFlight = 8;                                            // ids in flight per lane
+    for (uint32_t i0 = threadIdx.x; i0 < total; i0 += blockDim.x * kInFlight) {
+        uint32_t id[kInFlight], e[kInFlight];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < kInFlight; ++j) {
             const uint32_t i = i0 + j * blockDim.x;
             id[j] = kNone;
             if (i < total) {
                 uint32_t lo = 0, hi = a.n_src;                              // last s with pre[s] <= i
                 while (hi - lo > 1) { const uint32_t mid = (lo + hi) >> 1; if (pre[mid] <= i) lo = mid; else hi = mid; }
-                const ListSource S = a.src[lo];
-                id[j] = S.block[a.n_buckets + 2 + S.block[1 + b] + (i - pre[lo])];
-                enc[j] = kNuMask - S.g;
+                id[j] = first[lo][i - pre[lo]];
+                e[j] = enc[lo];
             }
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (id[j] != kNone) atomicMax(&tab[id[j] & (kBucketPages - 1)], enc[j]);   // never 0
+        for (int j = 0; j < kInFlight; ++j)
+            if (id[j] != kNone) atomicMax(&tab[id[j] & (kBucketPages - 1)], e[j]);   // never 0
     }
     __syncthreads();
     const uint64_t p0 = (uint64_t)b << kBucketShift;
@@ -1051,7 +1056,8 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
             MergeArgs ma;
             ma.src = c->list_src_stage; ma.n_src = g.n_list_sources; ma.n_buckets = g.n_buckets;
             ma.nu = c->nu; ma.flags = c->flags; ma.V = c->V; ma.epoch_base = a.epoch_base;
-            if (g.n_list_sources) k_list_merge<<<g.n_buckets, kListThreads, 0, st>>>(ma);
+            if (g.n_list_sources)
+                k_list_merge<<<g.n_buckets, kListThreads, (size_t)g.n_list_sources * 16 + 16, st>>>(ma);
         } else if (c->has_list_rule && g.list_binned) {
             ListArgs la;
             la.e = a; la.bucket_fill = c->list_bucket_fill; la.pairs = c->list_pairs;
