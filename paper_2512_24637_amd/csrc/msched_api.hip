@@ -136,7 +136,7 @@ inline bool seen_before(msched_ctx *c, const RegionSig &sig, size_t mask) {
     h ^= h >> 29;
     for (size_t i = h & mask;; i = (i + 1) & mask) {
         msched_ctx::SeenEntry &e = c->seen[i];
-        if (e.stamp != c->plan_seq + 1) { e = {sig.a, sig.b, sig.c, sig.d, c->plan_seq + 1}; return false; }
+        if (e.stamp != c->dedupe_stamp) { e = {sig.a, sig.b, sig.c, sig.d, c->dedupe_stamp}; return false; }
         if (e.a == sig.a && e.b == sig.b && e.c == sig.c && e.d == sig.d) return true;
     }
 }
@@ -456,6 +456,7 @@ int msched_plan(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entri
         }
         if (e == 0) g_end0 = G;
     }
+    ++c->dedupe_stamp;                   // per attempt, not per successful plan: a refused plan leaves its entries behind
     if (c->dedupe_regions && G > 1) {
         // bit r of a command's skip mask: rule r repeats a region an earlier command already brought
         // in.  The mask rides in the top byte of the record's address (addresses use 48 bits).  The

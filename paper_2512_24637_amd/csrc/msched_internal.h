@@ -143,6 +143,7 @@ struct msched_ctx {
     uint32_t max_rules = 0;
     uint32_t n_resident = 0;
     uint64_t plan_seq = 0, pending_plan = 0;    // pending_plan == 0: nothing to migrate
+    uint64_t dedupe_stamp = 0;                  // tags the entries of the repeat-region table with the plan attempt that wrote them
     msched::PlanHeader pending{};
     uint32_t *query_buf = nullptr; size_t query_cap = 0;     // device scratch for pagetable_query
     // early execution: in-order landing of the fetch list

@@ -277,3 +277,95 @@ def test_allocation_granularity_ablation_runs_bit_exact(oracle_mod):
     from workloads.ablation import allocation_granularity
     trace = allocation_granularity(make_trace(4, page_shift=15, steps=12, full_backing=True))
     assert lockstep(oracle_mod, trace, with_bytes=True, bytes_every=4) >= 20
+
+
+@pytest.mark.parametrize("env", [{"MSCHED_PAINT": "0"}, {"MSCHED_LIST_PREPARED": "0"},
+                                 {"MSCHED_PAINT": "0", "MSCHED_LIST_PREPARED": "0"},
+                                 {"MSCHED_LIST_CACHE_MB": "1"}],
+                         ids=["scatter-ranges", "bin-per-plan", "both-earlier-paths", "one-megabyte-ring"])
+def test_earlier_planning_paths_stay_bit_exact(oracle_mod, monkeypatch, env):
+    """Range pages scattered into the next-use array instead of painted, id lists binned from scratch in every
+    plan instead of prepared once per command, and a ring too small for the prepared lists (which makes plans fall
+    back to binning from scratch part of the time)."""
+    monkeypatch.setenv("MSCHED_LIST_BINNED_MIN_IDS", "0")
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    assert lockstep(oracle_mod, make_trace(5, scale=64, n_launches=100), with_bytes=True, bytes_every=4) >= 16
+    assert lockstep(oracle_mod, make_trace(3, scale=16, iterations=2), with_bytes=True, bytes_every=3) >= 4
+    assert lockstep(oracle_mod, make_trace(4, page_shift=12, layers=8, steps=16), with_bytes=True, bytes_every=3) >= 8
+
+
+def test_id_lists_longer_than_one_prepared_piece(oracle_mod, monkeypatch):
+    """A list of 60 000 ids is prepared as three pieces of up to 24 576; the same list object repeated by a later
+    command is skipped, a different list over the same pages is merged."""
+    import torch
+    monkeypatch.setenv("MSCHED_LIST_BINNED_MIN_IDS", "0")
+    V, F = 40000, 38000
+    trace = explicit_trace([[[0]], [[1]]], V, F, timeslice=4, page_shift=6)
+    g = GpuSide(trace)
+    o = make_oracle(oracle_mod, trace, with_bytes=False)
+    rng = np.random.default_rng(3)
+    try:
+        lists = [rng.integers(0, V, 60000).astype(np.uint32), rng.integers(0, V // 2, 30000).astype(np.uint32),
+                 rng.integers(V // 3, V, 5).astype(np.uint32)]
+        dev = [torch.from_numpy(a.view(np.int32)).cuda() for a in lists]
+        kg = g.ms.kernel_register([Rule(RULE_LIST)])
+        ko = o.kernel_register([Rule(RULE_LIST)])
+        for impl, k in ((g.ms, kg), (o, ko)):
+            impl.launch_retire(0, 1)
+            impl.launch_retire(1, 1)
+        for task, which in ((0, 1), (0, 0), (1, 2), (0, 0), (1, 1)):
+            g.ms.launch_enqueue(task, kg, [], 0, ids_ptr=dev[which].data_ptr(), n_ids=len(lists[which]))
+            o.launch_enqueue(task, ko, [], 0, ids=lists[which])
+        for tl, retire in (([(0, 1), (1, 4)], (0, 1)), ([(1, 1), (0, 4)], (1, 1)), ([(0, 2), (1, 4)], (0, 2)), ([(1, 4)], (1, 1))):
+            po, pg = o.plan(tl), g.ms.plan(tl)
+            assert_same_plan(po, pg, tl)
+            o.migrate()
+            g.ms.migrate()
+            pto, foo = o.state()
+            ptg, fog = g.ms.state()
+            assert np.array_equal(pto, ptg) and np.array_equal(foo, fog)
+            o.launch_retire(*retire)
+            g.ms.launch_retire(*retire)
+    finally:
+        g.close()
+        o.close()
+
+
+def test_a_prepared_list_with_a_bad_id_is_refused_by_every_plan(oracle_mod, monkeypatch):
+    import torch
+    from paper_2512_24637_amd import MSchedError
+    monkeypatch.setenv("MSCHED_LIST_BINNED_MIN_IDS", "0")
+    trace = explicit_trace([[[0]], [[1]]], 64, 16, timeslice=2, page_shift=6)
+    g = GpuSide(trace)
+    try:
+        ms = g.ms
+        kl = ms.kernel_register([Rule(RULE_LIST)])
+        bad = torch.tensor([3, 400, 5], dtype=torch.int32, device="cuda")      # 400 >= V
+        ms.launch_enqueue(1, kl, [], 0, ids_ptr=bad.data_ptr(), n_ids=3)
+        for _ in range(3):                               # the list is prepared by the first plan, refused by all
+            with pytest.raises(MSchedError) as e:
+                ms.plan([(0, 1), (1, 2)])
+            assert e.value.name == "E_RANGE"
+        p = ms.plan([(0, 1)])                            # a timeline without that command is fine
+        assert p.n_fetch == 1
+    finally:
+        g.close()
+
+
+def test_a_refused_plan_leaves_nothing_behind_for_the_next_one(oracle_mod):
+    """After E_WSET_TOO_LARGE the same queues planned with a timeline that fits give the oracle's plan (the
+    repeat-region table of the refused attempt must not count as this plan's)."""
+    from paper_2512_24637_amd import MSchedError
+    trace = explicit_trace([[[0, 1, 2, 3], [4]], [[5, 6], [0, 1]]], 8, 3, timeslice=2, page_shift=6)
+    g = GpuSide(trace)
+    o = make_oracle(oracle_mod, trace, with_bytes=False)
+    try:
+        with pytest.raises(MSchedError) as e:
+            g.ms.plan([(0, 2), (1, 2)])
+        assert e.value.name == "E_WSET_TOO_LARGE"
+        for tl in ([(1, 2), (0, 2)], [(1, 1)]):
+            assert_same_plan(o.plan(tl), g.ms.plan(tl), tl)
+    finally:
+        g.close()
+        o.close()
