@@ -221,6 +221,7 @@ __global__ __launch_bounds__(kListThreads) void k_expand_list(ExpandArgs a, uint
 // check-then-atomic of the direct path, so any distribution is handled, a uniform one is handled fast.
 // ------------------------------------------------------------------------------------------
 __device__ uint32_t block_exclusive_scan(uint32_t *a, uint32_t n, uint32_t *wave_sums);
+__device__ __forceinline__ uint32_t chunk_of_block(uint32_t block, uint32_t n_chunks);
 
 constexpr uint32_t kBucketPages = 1u << kBucketShift;
 constexpr uint32_t kBinSeenBits = 13;                       // duplicate filter: 8 Ki entries, 32 KiB
@@ -424,19 +425,22 @@ __global__ __launch_bounds__(kListThreads) void k_list_prepare(const ListPrep *_
     }
 }
 
+constexpr uint32_t kMergeHints = 4096;
 struct MergeArgs {
     const ListSource *src; uint32_t n_src, n_buckets;
     uint32_t *nu; uint32_t *flags; uint64_t V; uint32_t epoch_base;
 };
 
 __global__ __launch_bounds__(kListThreads) void k_list_merge(MergeArgs a) {
-    const uint32_t b = blockIdx.x;
+    // buckets with ids tend to be neighbours (one table): the strided map spreads them over the dispatch order
+    const uint32_t b = chunk_of_block(blockIdx.x, gridDim.x);
     __shared__ uint32_t tab[kBucketPages];
     __shared__ uint32_t wave_sums[kListThreads / kWave];
     extern __shared__ uint64_t merge_lds[];
     const uint32_t **first = reinterpret_cast<const uint32_t **>(merge_lds);   // [n_src] this bucket's first id in piece s
     uint32_t *pre = reinterpret_cast<uint32_t *>(first + a.n_src);             // [n_src + 1] ids of this bucket in the pieces before s
     uint32_t *enc = pre + a.n_src + 1;                                          // [n_src] next-use code of the piece's command
+    uint32_t *hint = enc + a.n_src;                                             // [kMergeHints] piece of every 64th (or 128th, ...) id
     for (uint32_t s = threadIdx.x; s < a.n_src; s += blockDim.x) {
         const ListSource S = a.src[s];
         const uint32_t lo = S.block[1 + b], hi = S.block[2 + b];
@@ -451,6 +455,18 @@ __global__ __launch_bounds__(kListThreads) void k_list_merge(MergeArgs a) {
     if (total == 0) return;
     for (uint32_t i = threadIdx.x; i < kBucketPages; i += blockDim.x) tab[i] = 0;
     __syncthreads();
+    // Which piece holds the i-th id of the bucket?  One binary search per 64 ids (or more) fills a table of starting
+    // points; from there a lane walks forward over at most a few pieces (a piece holds tens of ids per bucket).
+    uint32_t hint_shift = 6;                                               // the table has kMergeHints entries: coarser for huge buckets
+    while ((total >> hint_shift) >= kMergeHints) ++hint_shift;
+    const uint32_t n_hint = (total >> hint_shift) + 1;
+    for (uint32_t h = threadIdx.x; h < n_hint; h += blockDim.x) {
+        const uint32_t i = h << hint_shift;
+        uint32_t lo = 0, hi = a.n_src;                                      // last s with pre[s] <= i
+        while (hi - lo > 1) { const uint32_t mid = (lo + hi) >> 1; if (pre[mid] <= i) lo = mid; else hi = mid; }
+        hint[h] = lo;
+    }
+    __syncthreads();
     constexpr int kInFlight = 8;                                            // ids in flight per lane
     for (uint32_t i0 = threadIdx.x; i0 < total; i0 += blockDim.x * kInFlight) {
         uint32_t id[kInFlight], e[kInFlight];
@@ -459,10 +475,10 @@ __global__ __launch_bounds__(kListThreads) void k_list_merge(MergeArgs a) {
             const uint32_t i = i0 + j * blockDim.x;
             id[j] = kNone;
             if (i < total) {
-                uint32_t lo = 0, hi = a.n_src;                              // last s with pre[s] <= i
-                while (hi - lo > 1) { const uint32_t mid = (lo + hi) >> 1; if (pre[mid] <= i) lo = mid; else hi = mid; }
-                id[j] = first[lo][i - pre[lo]];
-                e[j] = enc[lo];
+                uint32_t s = hint[i >> hint_shift];
+                while (pre[s + 1] <= i) ++s;                                // pre[n_src] = total > i ends the walk
+                id[j] = first[s][i - pre[s]];
+                e[j] = enc[s];
             }
         }
 #pragma unroll
@@ -1057,7 +1073,7 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
             ma.src = c->list_src_stage; ma.n_src = g.n_list_sources; ma.n_buckets = g.n_buckets;
             ma.nu = c->nu; ma.flags = c->flags; ma.V = c->V; ma.epoch_base = a.epoch_base;
             if (g.n_list_sources)
-                k_list_merge<<<g.n_buckets, kListThreads, (size_t)g.n_list_sources * 16 + 16, st>>>(ma);
+                k_list_merge<<<g.n_buckets, kListThreads, (size_t)g.n_list_sources * 16 + 16 + kMergeHints * 4, st>>>(ma);
         } else if (c->has_list_rule && g.list_binned) {
             ListArgs la;
             la.e = a; la.bucket_fill = c->list_bucket_fill; la.pairs = c->list_pairs;
