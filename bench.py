@@ -250,7 +250,7 @@ def bench_planning_stress(torch, warmup=8, steps=16, phases=True):
     """c5 page structure (10 M pages, 4 M frames, 8 tasks, 2 dense ranges + 20 k Zipf ids per launch).
     Planning never reads page bytes, so pages are shrunk to 64 B to keep the backing store small."""
     from workloads import make_trace
-    slices = -(-(warmup + steps) // 8)
+    slices = -(-(warmup + steps) // 8) + 1        # one slice more than is run: every timed plan sees full queues (400 commands)
     t0 = time.perf_counter()
     trace = make_trace(5, page_shift=6, n_launches=50 * slices)
     log(f"[bench] planning-stress trace: V={trace.n_virtual_pages} F={trace.n_frames} "
@@ -260,6 +260,7 @@ def bench_planning_stress(torch, warmup=8, steps=16, phases=True):
     buf, ms = make_context(torch, trace, fill_contents=False)
     r = run_steps(torch, trace, ms, warmup, steps, profile=1)
     dev_ms = [ph["plan"] for ph in r["phases"]]
+    assert all(p.n_commands == 400 for p in r["plans"]), "the byte count assumes 8 tasks x 50 commands in every plan"
     bytes_ = [planning_bytes(trace, p, ids_per_plan, touch_est) for p in r["plans"]]
     ach = sum(bytes_) / (sum(dev_ms) / 1e3) / 1e9
     out = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
