@@ -149,6 +149,8 @@ void free_ctx(msched_ctx *c) {
     if (c->list_src_host) (void)hipHostFree(c->list_src_host);
     if (c->list_prep_host) (void)hipHostFree(c->list_prep_host);
     if (c->list_src_stage) (void)hipFree(c->list_src_stage);
+    if (c->list_ahead_host) (void)hipHostFree(c->list_ahead_host);
+    if (c->ahead_ev) (void)hipEventDestroy(c->ahead_ev);
     void *dev[] = {c->page_table, c->frame_owner, c->nu, c->slot, c->evict_pages, c->evict_frames, c->fetch_pages,
                    c->fetch_frames, c->flags, c->matrix, c->partial, c->offsets, c->hdr_dev, c->kernels_dev,
                    c->query_buf, c->cmd_dev, c->list_bucket_fill, c->list_pairs};
@@ -209,6 +211,7 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     c->plan_task.resize(MSCHED_MAX_TIMELINE_COMMANDS + 1);
     c->list_prepared = (uint32_t)env_u32("MSCHED_LIST_PREPARED", 0, 1, 1);
     c->list_cache_bytes = (uint64_t)env_u32("MSCHED_LIST_CACHE_MB", 1, 65536, 128) << 20;
+    c->list_ahead = (uint32_t)env_u32("MSCHED_LIST_AHEAD", 0, 65536, 128);
     c->force_multi_kernel = env_u32("MSCHED_FORCE_MULTI_KERNEL", 0, 1, 0) != 0;
     c->list_binned_min_ids = (uint64_t)env_u32("MSCHED_LIST_BINNED_MIN_IDS", 0, 1 << 30, 262144);
     c->list_b0 = (uint32_t)env_u32("MSCHED_LIST_B0", 0, 4096, 4);
@@ -296,6 +299,7 @@ int msched_kernel_register(msched_ctx *c, const msched_rule *rules, uint32_t n_r
     HIP_TRY(c, hipMemcpy(c->kernels_dev + c->kernels.size(), &k, sizeof k, hipMemcpyHostToDevice));
     c->kernels.push_back(k);
     c->has_list_rule = c->has_list_rule || has_list;
+    c->kernel_has_list.push_back(has_list ? 1 : 0);
     c->max_rules = std::max(c->max_rules, n_rules);
     *kernel_id = (uint32_t)(c->kernels.size() - 1);
     return MSCHED_OK;
@@ -346,8 +350,8 @@ int msched_launch_retire(msched_ctx *c, uint32_t task, uint32_t n_launches) {
 
 namespace {
 
-// Room for `bytes` in a task's ring of prepared id lists.  Blocks are handed out in program order and die in
-// program order (with their command's retirement), so the ring's tail is the oldest live command's block.
+// Room for `bytes` in a task's ring of prepared id lists.  Blocks are handed out roughly in program order and
+// die with their command's retirement, so the ring's tail is the oldest block a queued command still owns.
 bool ring_alloc(msched_ctx *c, TaskQueue &t, uint64_t bytes, uint64_t &off, hipError_t &err) {
     err = hipSuccess;
     if (!t.prep_buf) {
@@ -360,8 +364,8 @@ bool ring_alloc(msched_ctx *c, TaskQueue &t, uint64_t bytes, uint64_t &off, hipE
     if (pos + bytes > t.prep_size) head += t.prep_size - pos;        // a block never wraps: skip the ring's end
     if (head + bytes - t.prep_tail > t.prep_size) {
         t.prep_tail = t.prep_head;                                     // nothing live, unless a queued command says otherwise
-        for (size_t i = t.cursor; i < t.n; ++i)
-            if (t.recs[i - t.base].reserved) { t.prep_tail = t.recs[i - t.base].reserved - 1; break; }
+        for (size_t i = t.cursor; i < t.n; ++i)                        // (mostly, not strictly, in program order: take the oldest)
+            if (t.recs[i - t.base].reserved) t.prep_tail = std::min(t.prep_tail, t.recs[i - t.base].reserved - 1);
         if (head + bytes - t.prep_tail > t.prep_size) return false;
     }
     off = head;
@@ -528,6 +532,7 @@ int msched_plan(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entri
                 if (rc_src < 0) return rc_src;
                 g.list_prepared = rc_src == 0;
             }
+            c->last_plan_prepared = g.list_prepared;
             if (total >= c->list_binned_min_ids && total < (1ull << 31) && !g.list_prepared) {
                 g.list_binned = true;
                 // room per sub-segment (8 per bucket): four times the average, at least 256 pairs
@@ -581,6 +586,58 @@ int msched_plan(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entri
     return MSCHED_OK;
 }
 
+namespace {
+
+// Bin the id lists of commands queued behind the ones just planned, while the migration keeps the host link
+// busy and most compute units idle: the next plan then finds them prepared.  Blocks are handed out in program
+// order, so a task stops at the first command that does not fit its ring.
+int prepare_ahead(msched_ctx *c) {
+    if (!c->list_ahead || !c->list_prepared || !c->last_plan_prepared) return MSCHED_OK;
+    const uint32_t n_buckets = (uint32_t)((c->V + (1u << kBucketShift) - 1) >> kBucketShift);
+    if (!c->list_ahead_host) {
+        HIP_TRY(c, hipHostMalloc((void **)&c->list_ahead_host, sizeof(ListPrep) * kMaxListSources, hipHostMallocDefault));
+        HIP_TRY(c, hipHostGetDevicePointer((void **)&c->list_ahead_dev, c->list_ahead_host, 0));
+        HIP_TRY(c, hipEventCreateWithFlags(&c->ahead_ev, hipEventDisableTiming));
+    }
+    if (c->ahead_pending) { HIP_TRY(c, hipEventSynchronize(c->ahead_ev)); c->ahead_pending = false; }   // the table is free again
+    const uint64_t hdr_words = (uint64_t)n_buckets + 2;
+    uint32_t n_new = 0;
+    bool full = false;
+    for (TaskQueue &t : c->tasks) {
+        size_t i = std::max(t.prep_scan, t.cursor);
+        const size_t end = std::min(t.n, t.cursor + (size_t)c->list_ahead);
+        for (; i < end && !full; ++i) {
+            CmdRec &rec = t.recs[i - t.base];
+            if (!c->kernel_has_list[rec.kernel] || rec.n_ids == 0 || rec.reserved) continue;
+            const uint32_t pieces = (rec.n_ids + kPrepBlock - 1) / kPrepBlock;
+            if (n_new + pieces > kMaxListSources) { full = true; break; }
+            const uint64_t bytes = (((uint64_t)pieces * hdr_words + rec.n_ids) * 4 + 15) & ~15ull;
+            uint64_t off;
+            hipError_t err;
+            if (!ring_alloc(c, t, bytes, off, err)) {
+                if (err != hipSuccess) { c->last_hip = g_last_hip = (int)err; return MSCHED_E_HIP; }
+                break;                                   // no room now: the plan that needs it will see to it
+            }
+            rec.reserved = off + 1;
+            uint32_t *block = reinterpret_cast<uint32_t *>(t.prep_buf + off % t.prep_size);
+            for (uint32_t p = 0; p < pieces; ++p) {
+                const uint32_t n = std::min<uint32_t>(kPrepBlock, rec.n_ids - p * kPrepBlock);
+                c->list_ahead_host[n_new++] = {rec.ids + (size_t)p * kPrepBlock, block, n, {0, 0, 0}};
+                block += hdr_words + n;
+            }
+        }
+        t.prep_scan = i;
+        if (full) break;
+    }
+    if (n_new == 0) return MSCHED_OK;
+    HIP_TRY(c, launch_list_prepare(c, c->list_ahead_dev, n_new, n_buckets));
+    HIP_TRY(c, hipEventRecord(c->ahead_ev, c->stream));
+    c->ahead_pending = true;
+    return MSCHED_OK;
+}
+
+}  // namespace
+
 int msched_migrate(msched_ctx *c, const msched_plan_t *plan) {
     if (!c || !plan) return MSCHED_E_INVAL;
     if (c->pending_plan == 0 || plan->plan_id != c->pending_plan) return MSCHED_E_STALE_PLAN;
@@ -589,7 +646,7 @@ int msched_migrate(msched_ctx *c, const msched_plan_t *plan) {
     if (c->profiling) { HIP_TRY(c, hipEventRecord(c->ev[6], c->stream)); c->migrate_timed = 1; }
     c->n_resident += c->pending.n_free_used;
     c->pending_plan = 0;
-    return MSCHED_OK;
+    return prepare_ahead(c);
 }
 
 int msched_set_early_start(msched_ctx *c, int enable) {

@@ -59,6 +59,7 @@ struct TaskQueue {
     // prepared id lists of this task's queued commands: a ring in device memory, filled in program order
     uint8_t *prep_buf = nullptr;
     uint64_t prep_size = 0, prep_head = 0, prep_tail = 0;   // head / tail are running byte offsets (never wrap)
+    size_t prep_scan = 0;                       // commands before this index have been looked at by the look-ahead preparation
 };
 
 // One source of the id-list merge: a prepared (de-duplicated, grouped by bucket) piece of a command's list.
@@ -124,6 +125,13 @@ struct msched_ctx {
     msched::ListPrep *list_prep_dev = nullptr;
     msched::ListSource *list_src_stage = nullptr;  // device copy of the source table (every merge workgroup reads it)
     std::vector<uint32_t> plan_task;               // task of the g-th future command
+    // look-ahead preparation: id lists of queued commands are binned behind a migration, off the plan's path
+    uint32_t list_ahead = 128;                     // commands per task looked ahead at each migration (MSCHED_LIST_AHEAD, 0 = off)
+    msched::ListPrep *list_ahead_host = nullptr;   // pinned [kMaxListSources]
+    msched::ListPrep *list_ahead_dev = nullptr;
+    hipEvent_t ahead_ev = nullptr; bool ahead_pending = false;   // the last look-ahead kernel still reads the table
+    bool last_plan_prepared = false;               // the latest plan merged prepared pieces
+    std::vector<uint8_t> kernel_has_list;          // per registered kernel
     uint32_t list_b0 = 4, list_b1 = 32;         // id lists: commands [0,b0), [b0,b1), [b1,G) run as ordered batches
     uint32_t *page_table = nullptr, *frame_owner = nullptr, *nu = nullptr, *slot = nullptr;  // device
     uint32_t *evict_pages = nullptr, *evict_frames = nullptr, *fetch_pages = nullptr, *fetch_frames = nullptr;
@@ -179,7 +187,8 @@ void plan_geometry(const msched_ctx *c, uint32_t G, PlanGeom &g);
 hipError_t launch_migrate(msched_ctx *c, const PlanHeader &h);
 hipError_t launch_query(msched_ctx *c, const uint32_t *ids_dev, uint32_t n, uint32_t *out_dev);
 hipError_t launch_init_tables(msched_ctx *c);
-hipError_t launch_peek(msched_ctx *c);      // landed -> progress_host on the poll stream
+hipError_t launch_peek(msched_ctx *c);
+hipError_t launch_list_prepare(msched_ctx *c, const ListPrep *table_dev, uint32_t n, uint32_t n_buckets);      // landed -> progress_host on the poll stream
 
 extern int g_last_hip;                        // hipError_t of the last failed HIP call of any context
 

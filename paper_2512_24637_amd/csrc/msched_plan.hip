@@ -1004,7 +1004,12 @@ void plan_geometry(const msched_ctx *c, uint32_t G, PlanGeom &g) {
         return;
     }
     g.single = false;
-    const uint64_t per_chunk = (c->V + c->max_chunks - 1) / c->max_chunks;
+    uint64_t per_chunk = (c->V + c->max_chunks - 1) / c->max_chunks;
+    // Tables that still give every compute unit three workgroups of full-size tiles take those: fewer, longer
+    // workgroups spend less of the sweep in its fixed per-workgroup parts (measured on 10 Mi pages: 1280
+    // chunks of 8 Ki pages against 2048 of 5 Ki, 128 us against 139 us per plan).
+    const uint64_t full_tile = wave_pages * kMaxSteps;
+    if (per_chunk < full_tile && c->V / full_tile >= 768) per_chunk = full_tile;
     const uint64_t sub_steps = (per_chunk + wave_pages - 1) / wave_pages;
     if (sub_steps <= kMaxSteps) {
         g.steps = (uint32_t)std::max<uint64_t>(4, sub_steps);
@@ -1037,6 +1042,14 @@ hipError_t allow_large_lds() {
     return hipSuccess;
 }
 
+hipError_t launch_list_prepare(msched_ctx *c, const ListPrep *table_dev, uint32_t n, uint32_t n_buckets) {
+    if (n == 0) return hipSuccess;
+    (void)hipGetLastError();
+    const size_t prep_lds = 4 * ((size_t)(1u << kBinSeenBits) + kPrepBlock + n_buckets + 1);
+    k_list_prepare<<<n, kListThreads, prep_lds, c->stream>>>(table_dev, n_buckets, c->V, c->slot);
+    return hipGetLastError();
+}
+
 hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     (void)hipGetLastError();   // launches below are checked through the sticky error: start clean
     hipStream_t st = c->stream;
@@ -1066,9 +1079,7 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         // so once the first few commands have written the popular pages, the check in front of the
         // atomic turns every later touch of them into a plain (cached) load.
         if (c->has_list_rule && g.list_prepared) {
-            const size_t prep_lds = 4 * ((size_t)(1u << kBinSeenBits) + kPrepBlock + g.n_buckets + 1);
-            if (g.n_list_new)
-                k_list_prepare<<<g.n_list_new, kListThreads, prep_lds, st>>>(c->list_prep_dev, g.n_buckets, c->V, c->slot);
+            if (g.n_list_new) CK(launch_list_prepare(c, c->list_prep_dev, g.n_list_new, g.n_buckets));
             MergeArgs ma;
             ma.src = c->list_src_stage; ma.n_src = g.n_list_sources; ma.n_buckets = g.n_buckets;
             ma.nu = c->nu; ma.flags = c->flags; ma.V = c->V; ma.epoch_base = a.epoch_base;
