@@ -149,6 +149,7 @@ void free_ctx(msched_ctx *c) {
     if (c->list_src_host) (void)hipHostFree(c->list_src_host);
     if (c->list_prep_host) (void)hipHostFree(c->list_prep_host);
     if (c->list_src_stage) (void)hipFree(c->list_src_stage);
+    if (c->bucket_mark) (void)hipFree(c->bucket_mark);
     if (c->list_ahead_host) (void)hipHostFree(c->list_ahead_host);
     if (c->ahead_ev) (void)hipEventDestroy(c->ahead_ev);
     void *dev[] = {c->page_table, c->frame_owner, c->nu, c->slot, c->evict_pages, c->evict_frames, c->fetch_pages,
@@ -383,6 +384,8 @@ int gather_list_sources(msched_ctx *c, uint32_t G, PlanGeom &g) {
         HIP_TRY(c, hipHostMalloc((void **)&c->list_prep_host, sizeof(ListPrep) * kMaxListSources, hipHostMallocDefault));
         HIP_TRY(c, hipHostGetDevicePointer((void **)&c->list_prep_dev, c->list_prep_host, 0));
         HIP_TRY(c, hipMalloc((void **)&c->list_src_stage, sizeof(ListSource) * kMaxListSources));
+        HIP_TRY(c, hipMalloc((void **)&c->bucket_mark, 4 * kMaxBuckets));
+        HIP_TRY(c, hipMemset(c->bucket_mark, 0, 4 * kMaxBuckets));
     }
     uint32_t n_src = 0, n_new = 0;
     std::vector<CmdRec *> fresh;

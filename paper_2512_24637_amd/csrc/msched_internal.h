@@ -123,6 +123,7 @@ struct msched_ctx {
     msched::ListSource *list_src_dev = nullptr;    // the same memory, device address
     msched::ListPrep *list_prep_host = nullptr;    // pinned [kMaxListSources]: the pieces this plan has to prepare first
     msched::ListPrep *list_prep_dev = nullptr;
+    uint32_t *bucket_mark = nullptr;               // device [kMaxBuckets]: buckets some prepared piece has put an id in
     msched::ListSource *list_src_stage = nullptr;  // device copy of the source table (every merge workgroup reads it)
     std::vector<uint32_t> plan_task;               // task of the g-th future command
     // look-ahead preparation: id lists of queued commands are binned behind a migration, off the plan's path

@@ -366,7 +366,8 @@ __global__ __launch_bounds__(kListThreads) void k_list_reduce(ListArgs a) {
 //                   their commands' g in a 32 KiB LDS table, merge the table into the bucket's slice of nu[]
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kListThreads) void k_list_prepare(const ListPrep *__restrict__ prep, uint32_t n_buckets,
-                                                               uint64_t V, const uint32_t *__restrict__ slot) {
+                                                               uint64_t V, const uint32_t *__restrict__ slot,
+                                                               uint32_t *__restrict__ bucket_mark) {
     extern __shared__ uint32_t bin_lds[];
     uint32_t *seen = bin_lds;                               // [1 << kBinSeenBits]
     uint32_t *kept = seen + (1u << kBinSeenBits);           // [kPrepBlock]
@@ -412,6 +413,10 @@ __global__ __launch_bounds__(kListThreads) void k_list_prepare(const ListPrep *_
         }
     }
     __syncthreads();
+    // Buckets that ever received an id stay marked for the life of the context: the merge looks at no other.
+    // (Marks are never taken back, so a bucket whose commands have all retired costs a look, not a wrong result.)
+    for (uint32_t b = threadIdx.x; b < n_buckets; b += blockDim.x)
+        if (cnt[b] && !bucket_mark[b]) bucket_mark[b] = 1;
     block_exclusive_scan(cnt, n_buckets + 1, wave_sums);   // cnt[b] = start of bucket b, cnt[n_buckets] = total
     uint32_t *block = pr.block;
     if (threadIdx.x == 0) block[0] = bad;
@@ -429,11 +434,13 @@ constexpr uint32_t kMergeHints = 4096;
 struct MergeArgs {
     const ListSource *src; uint32_t n_src, n_buckets;
     uint32_t *nu; uint32_t *flags; uint64_t V; uint32_t epoch_base;
+    const uint32_t *bucket_mark;        // [n_buckets] has any prepared piece of this context ever put an id here?
 };
 
 __global__ __launch_bounds__(kListThreads) void k_list_merge(MergeArgs a) {
     // buckets with ids tend to be neighbours (one table): the strided map spreads them over the dispatch order
     const uint32_t b = chunk_of_block(blockIdx.x, gridDim.x);
+    if (b != 0 && !a.bucket_mark[b]) return;                // bucket 0 always runs: it also reports unplannable ids
     __shared__ uint32_t tab[kBucketPages];
     __shared__ uint32_t wave_sums[kListThreads / kWave];
     extern __shared__ uint64_t merge_lds[];
@@ -467,23 +474,37 @@ __global__ __launch_bounds__(kListThreads) void k_list_merge(MergeArgs a) {
         hint[h] = lo;
     }
     __syncthreads();
+    // Every step is taken for all of a lane's ids before the next one starts, so that their LDS and memory round
+    // trips overlap instead of queueing behind each other (the piece lookup is a chain of dependent LDS reads).
     constexpr int kInFlight = 8;                                            // ids in flight per lane
     for (uint32_t i0 = threadIdx.x; i0 < total; i0 += blockDim.x * kInFlight) {
-        uint32_t id[kInFlight], e[kInFlight];
+        uint32_t s[kInFlight], nxt[kInFlight], id[kInFlight];
 #pragma unroll
         for (int j = 0; j < kInFlight; ++j) {
             const uint32_t i = i0 + j * blockDim.x;
-            id[j] = kNone;
-            if (i < total) {
-                uint32_t s = hint[i >> hint_shift];
-                while (pre[s + 1] <= i) ++s;                                // pre[n_src] = total > i ends the walk
-                id[j] = first[s][i - pre[s]];
-                e[j] = enc[s];
+            s[j] = i < total ? hint[i >> hint_shift] : 0u;
+        }
+        for (bool moved = true; moved;) {                                   // walk forward to the piece that holds id i
+            moved = false;
+#pragma unroll
+            for (int j = 0; j < kInFlight; ++j) nxt[j] = pre[s[j] + 1];
+#pragma unroll
+            for (int j = 0; j < kInFlight; ++j) {
+                const uint32_t i = i0 + j * blockDim.x;
+                if (i < total && nxt[j] <= i) { ++s[j]; moved = true; }     // pre[n_src] = total > i ends the walk
             }
         }
+        const uint32_t *src_ptr[kInFlight];
+#pragma unroll
+        for (int j = 0; j < kInFlight; ++j) {
+            const uint32_t i = i0 + j * blockDim.x;
+            src_ptr[j] = i < total ? first[s[j]] + (i - pre[s[j]]) : nullptr;
+        }
+#pragma unroll
+        for (int j = 0; j < kInFlight; ++j) id[j] = src_ptr[j] ? *src_ptr[j] : kNone;
 #pragma unroll
         for (int j = 0; j < kInFlight; ++j)
-            if (id[j] != kNone) atomicMax(&tab[id[j] & (kBucketPages - 1)], e[j]);   // never 0
+            if (id[j] != kNone) atomicMax(&tab[id[j] & (kBucketPages - 1)], enc[s[j]]);   // never 0
     }
     __syncthreads();
     const uint64_t p0 = (uint64_t)b << kBucketShift;
@@ -1046,7 +1067,7 @@ hipError_t launch_list_prepare(msched_ctx *c, const ListPrep *table_dev, uint32_
     if (n == 0) return hipSuccess;
     (void)hipGetLastError();
     const size_t prep_lds = 4 * ((size_t)(1u << kBinSeenBits) + kPrepBlock + n_buckets + 1);
-    k_list_prepare<<<n, kListThreads, prep_lds, c->stream>>>(table_dev, n_buckets, c->V, c->slot);
+    k_list_prepare<<<n, kListThreads, prep_lds, c->stream>>>(table_dev, n_buckets, c->V, c->slot, c->bucket_mark);
     return hipGetLastError();
 }
 
@@ -1082,7 +1103,7 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
             if (g.n_list_new) CK(launch_list_prepare(c, c->list_prep_dev, g.n_list_new, g.n_buckets));
             MergeArgs ma;
             ma.src = c->list_src_stage; ma.n_src = g.n_list_sources; ma.n_buckets = g.n_buckets;
-            ma.nu = c->nu; ma.flags = c->flags; ma.V = c->V; ma.epoch_base = a.epoch_base;
+            ma.nu = c->nu; ma.flags = c->flags; ma.V = c->V; ma.epoch_base = a.epoch_base; ma.bucket_mark = c->bucket_mark;
             if (g.n_list_sources)
                 k_list_merge<<<g.n_buckets, kListThreads, (size_t)g.n_list_sources * 16 + 16 + kMergeHints * 4, st>>>(ma);
         } else if (c->has_list_rule && g.list_binned) {
