@@ -17,6 +17,8 @@ class _ARule(C.Structure):
 
 
 def build(force: bool = False) -> str:
+    if os.environ.get("MSCHED_ANALYZER_ORACLE_LIB"):     # a deliberately broken build, see tests/test_oracle_mutations.py
+        return os.environ["MSCHED_ANALYZER_ORACLE_LIB"]
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC", "-o", _LIB, _SRC])
     return _LIB

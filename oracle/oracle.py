@@ -28,7 +28,11 @@ class OracleError(RuntimeError):
 
 
 def build(force: bool = False) -> str:
-    """Compile the oracle with gcc if the shared object is missing or stale."""
+    """Compile the oracle with gcc if the shared object is missing or stale.  MSCHED_ORACLE_LIB names a
+    library to load instead (tests/test_oracle_mutations.py points it at deliberately broken builds to
+    show that the pins notice)."""
+    if os.environ.get("MSCHED_ORACLE_LIB"):
+        return os.environ["MSCHED_ORACLE_LIB"]
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC",
                                "-o", _LIB, _SRC])

@@ -187,3 +187,20 @@ def test_buffers_that_touch_or_overlap_are_still_told_apart(ana):
     rules, un = ana.analyze(_single_kernel(4, 0b0111, inv))
     assert rules[0] == [(LINEAR, 0, (3,), 4, (), 0, (), 0), (FIXED, 1, (), 64, (), 0, (), 0), (LINEAR, 2, (3,), 16, (), 0, (), 0)]
     assert un[0] == 0
+
+
+def test_a_base_pointer_starts_a_region_in_every_invocation(ana):
+    """Sec. 5.2: a base pointer is a 64-bit argument that appears as the beginning address of a region.  A 64-bit
+    integer that happens to equal some region's start in one invocation only is not one: it yields no rule of its
+    own and stays available as a factor of the size."""
+    A, B = 9 << 40, 11 << 40
+    inv = []
+    for i, n in enumerate([B // 8, 1000, 4096, 77]):            # invocation 0: 8 * n == B, and n == the start of a region
+        a = [A + 32 * i, n]
+        rows = [(a[0], 8 * n)]
+        if i == 0:
+            rows.append((n, 64))                                 # some other buffer happens to begin at address n
+        inv.append((a, rows))
+    rules, un = ana.analyze(_single_kernel(2, 0b11, inv))
+    assert rules[0] == [(LINEAR, 0, (1,), 8, (), 0, (), 0)]
+    assert un[0] == 1

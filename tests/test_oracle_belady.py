@@ -277,3 +277,45 @@ def test_latency_decides_which_commands_fall_in_a_slice(oracle_mod):
     # a task listed twice continues where its first entry stopped
     p = o.plan([(0, 3), (0, 6)])
     assert (p.g_end0, p.n_commands) == (1, 3)
+
+
+def _list_lru_faults(refs, capacity):
+    """LRU as the textbooks state it: a recency list, most recent last."""
+    order, faults = [], 0
+    for p in refs:
+        if p in order:
+            order.remove(p)
+        else:
+            faults += 1
+            if len(order) == capacity:
+                order.pop(0)
+        order.append(p)
+    return faults
+
+
+def test_lru_simulator_is_textbook_lru(oracle_mod):
+    """The demand-paging baseline (Sec. 6.2 "Driver support": a fault with full HBM evicts from the head of the
+    driver's LRU list).  A capacity of exactly n frames: n distinct pages cycled forever miss n times, n + 1
+    distinct pages cycled miss every time; random reference strings agree with a recency-list LRU."""
+    for n in (1, 2, 3, 7):
+        cyc = [[[p] for _ in range(5) for p in range(n)]]
+        trace = explicit_trace(cyc, n + 1, n, timeslice=1)
+        o = oracle_mod.Oracle.for_trace(trace)
+        load_trace(o, trace)
+        assert o.lru_faults([0] * (5 * n), list(range(5 * n)), n) == n
+        o.close()
+        cyc = [[[p] for _ in range(5) for p in range(n + 1)]]
+        trace = explicit_trace(cyc, n + 1, n, timeslice=1)
+        o = oracle_mod.Oracle.for_trace(trace)
+        load_trace(o, trace)
+        assert o.lru_faults([0] * (5 * (n + 1)), list(range(5 * (n + 1))), n) == 5 * (n + 1)
+        o.close()
+    rng = np.random.default_rng(11)
+    for trial in range(40):
+        n_pages, cap = int(rng.integers(3, 14)), int(rng.integers(1, 6))
+        refs = [int(x) for x in rng.integers(0, n_pages, int(rng.integers(5, 60)))]
+        trace = explicit_trace([[[p] for p in refs]], n_pages, max(cap, 1), timeslice=1)
+        o = oracle_mod.Oracle.for_trace(trace)
+        load_trace(o, trace)
+        assert o.lru_faults([0] * len(refs), list(range(len(refs))), cap) == _list_lru_faults(refs, cap)
+        o.close()
