@@ -169,6 +169,13 @@ void free_ctx(msched_ctx *c) {
     delete c;
 }
 
+// Nothing may be thrown across the C boundary: the few container operations inside can only fail for memory.
+template <class F> int guarded(F &&body) noexcept {
+    try { return body(); }
+    catch (const std::bad_alloc &) { return MSCHED_E_NOMEM; }
+    catch (...) { return MSCHED_E_INVAL; }
+}
+
 int env_u32(const char *name, uint32_t lo, uint32_t hi, uint32_t dflt) {
     const char *s = getenv(name);
     if (!s || !*s) return (int)dflt;
@@ -193,6 +200,13 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
             if (cfg->host_slot[p] != MSCHED_NO_SLOT && cfg->host_slot[p] >= cfg->n_host_slots) return MSCHED_E_RANGE;
     msched_ctx *c = new (std::nothrow) msched_ctx();
     if (!c) return MSCHED_E_NOMEM;
+    const int rc_tables = guarded([&]() -> int {
+        c->seen.assign(131072, msched_ctx::SeenEntry{0, 0, 0, 0, 0});     // >= 4 x MAX_TIMELINE_COMMANDS x MAX_RULES
+        c->plan_recs.resize(MSCHED_MAX_TIMELINE_COMMANDS + 1);
+        c->plan_task.resize(MSCHED_MAX_TIMELINE_COMMANDS + 1);
+        return MSCHED_OK;
+    });
+    if (rc_tables) { delete c; return rc_tables; }
     c->cfg = *cfg;
     c->cfg.host_slot = nullptr;
     c->stream = (hipStream_t)cfg->stream;
@@ -207,9 +221,6 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     c->max_chunks = (uint32_t)env_u32("MSCHED_MAX_CHUNKS", 1, kMaxChunks, kMaxChunks);
     c->stage_threshold = (uint32_t)env_u32("MSCHED_STAGE_THRESHOLD", 0, 1 << 30, 2048);
     c->dedupe_regions = env_u32("MSCHED_DEDUPE_REGIONS", 0, 1, 1) != 0;
-    c->seen.assign(131072, msched_ctx::SeenEntry{0, 0, 0, 0, 0});     // >= 4 x MAX_TIMELINE_COMMANDS x MAX_RULES
-    c->plan_recs.resize(MSCHED_MAX_TIMELINE_COMMANDS + 1);
-    c->plan_task.resize(MSCHED_MAX_TIMELINE_COMMANDS + 1);
     c->list_prepared = (uint32_t)env_u32("MSCHED_LIST_PREPARED", 0, 1, 1);
     c->list_cache_bytes = (uint64_t)env_u32("MSCHED_LIST_CACHE_MB", 1, 65536, 128) << 20;
     c->list_ahead = (uint32_t)env_u32("MSCHED_LIST_AHEAD", 0, 65536, 128);
@@ -285,15 +296,23 @@ int msched_kernel_register(msched_ctx *c, const msched_rule *rules, uint32_t n_r
         k.rules[r] = q;
         if (q.kind == MSCHED_RULE_LIST) has_list = true;
     }
+    const int rc_room = guarded([&]() -> int {               // host tables first, so that nothing below can fail half-way
+        c->kernels.reserve(c->kernels.size() + 1);
+        c->kernel_has_list.reserve(c->kernel_has_list.size() + 1);
+        return MSCHED_OK;
+    });
+    if (rc_room) return rc_room;
     // the table is small and changes rarely: keep a device copy in step with the host one
     if (c->kernels.size() + 1 > c->kernels_cap) {
         const size_t ncap = std::max<size_t>(64, c->kernels_cap * 2);
         DevKernel *nd = nullptr;
         HIP_TRY(c, hipStreamSynchronize(c->stream));
         HIP_TRY(c, hipMalloc((void **)&nd, ncap * sizeof(DevKernel)));
-        if (!c->kernels.empty())
-            HIP_TRY(c, hipMemcpy(nd, c->kernels.data(), c->kernels.size() * sizeof(DevKernel), hipMemcpyHostToDevice));
-        if (c->kernels_dev) HIP_TRY(c, hipFree(c->kernels_dev));
+        if (!c->kernels.empty()) {
+            const hipError_t e = hipMemcpy(nd, c->kernels.data(), c->kernels.size() * sizeof(DevKernel), hipMemcpyHostToDevice);
+            if (e != hipSuccess) { (void)hipFree(nd); HIP_TRY(c, e); }
+        }
+        if (c->kernels_dev) (void)hipFree(c->kernels_dev);
         c->kernels_dev = nd;
         c->kernels_cap = ncap;
     }
@@ -308,9 +327,11 @@ int msched_kernel_register(msched_ctx *c, const msched_rule *rules, uint32_t n_r
 
 int msched_task_create(msched_ctx *c, uint32_t *task_id) {
     if (!c || !task_id) return MSCHED_E_INVAL;
-    c->tasks.emplace_back();
-    *task_id = (uint32_t)(c->tasks.size() - 1);
-    return MSCHED_OK;
+    return guarded([&]() -> int {
+        c->tasks.emplace_back();
+        *task_id = (uint32_t)(c->tasks.size() - 1);
+        return MSCHED_OK;
+    });
 }
 
 int msched_launch_enqueue(msched_ctx *c, uint32_t task, uint32_t kernel_id, const uint64_t *args, uint32_t n_args,
@@ -328,9 +349,10 @@ int msched_launch_enqueue(msched_ctx *c, uint32_t task, uint32_t kernel_id, cons
         const size_t ncap = std::max<size_t>(256, live * 2);
         CmdRec *nr = nullptr, *nd = nullptr;
         HIP_TRY(c, hipHostMalloc((void **)&nr, ncap * sizeof(CmdRec), hipHostMallocDefault));
-        HIP_TRY(c, hipHostGetDevicePointer((void **)&nd, nr, 0));
+        const hipError_t e = hipHostGetDevicePointer((void **)&nd, nr, 0);
+        if (e != hipSuccess) { (void)hipHostFree(nr); HIP_TRY(c, e); }
         if (live) memcpy(nr, t.recs + (t.cursor - t.base), live * sizeof(CmdRec));
-        if (t.recs) HIP_TRY(c, hipHostFree(t.recs));
+        if (t.recs) (void)hipHostFree(t.recs);
         t.recs = nr; t.recs_dev = nd; t.cap = ncap; t.base = t.cursor;
     }
     CmdRec &r = t.recs[t.n - t.base];
@@ -353,10 +375,14 @@ namespace {
 
 // Room for `bytes` in a task's ring of prepared id lists.  Blocks are handed out roughly in program order and
 // die with their command's retirement, so the ring's tail is the oldest block a queued command still owns.
-bool ring_alloc(msched_ctx *c, TaskQueue &t, uint64_t bytes, uint64_t &off, hipError_t &err) {
-    err = hipSuccess;
+bool ring_alloc(msched_ctx *c, TaskQueue &t, uint64_t bytes, uint64_t &off) {
     if (!t.prep_buf) {
-        if ((err = hipMalloc((void **)&t.prep_buf, c->list_cache_bytes)) != hipSuccess) return false;
+        if (hipMalloc((void **)&t.prep_buf, c->list_cache_bytes) != hipSuccess) {
+            (void)hipGetLastError();               // no memory for a ring: plans bin their lists from scratch from now on
+            t.prep_buf = nullptr;
+            c->list_prepared = 0;
+            return false;
+        }
         t.prep_size = c->list_cache_bytes;
     }
     if (bytes > t.prep_size) return false;
@@ -378,14 +404,18 @@ bool ring_alloc(msched_ctx *c, TaskQueue &t, uint64_t bytes, uint64_t &off, hipE
 // has the command in its timeline (a command is typically planned once per task of the round).
 // Returns 0 and fills the two pinned tables, 1 when the pieces do not fit (the caller bins from scratch), or < 0.
 int gather_list_sources(msched_ctx *c, uint32_t G, PlanGeom &g) {
-    if (!c->list_src_host) {
-        HIP_TRY(c, hipHostMalloc((void **)&c->list_src_host, sizeof(ListSource) * kMaxListSources, hipHostMallocDefault));
-        HIP_TRY(c, hipHostGetDevicePointer((void **)&c->list_src_dev, c->list_src_host, 0));
-        HIP_TRY(c, hipHostMalloc((void **)&c->list_prep_host, sizeof(ListPrep) * kMaxListSources, hipHostMallocDefault));
-        HIP_TRY(c, hipHostGetDevicePointer((void **)&c->list_prep_dev, c->list_prep_host, 0));
-        HIP_TRY(c, hipMalloc((void **)&c->list_src_stage, sizeof(ListSource) * kMaxListSources));
-        HIP_TRY(c, hipMalloc((void **)&c->bucket_mark, 4 * kMaxBuckets));
-        HIP_TRY(c, hipMemset(c->bucket_mark, 0, 4 * kMaxBuckets));
+    // first use; each piece on its own so that a failure half-way neither leaks nor leaves a hole
+    if (!c->list_src_host) HIP_TRY(c, hipHostMalloc((void **)&c->list_src_host, sizeof(ListSource) * kMaxListSources, hipHostMallocDefault));
+    if (!c->list_src_dev) HIP_TRY(c, hipHostGetDevicePointer((void **)&c->list_src_dev, c->list_src_host, 0));
+    if (!c->list_prep_host) HIP_TRY(c, hipHostMalloc((void **)&c->list_prep_host, sizeof(ListPrep) * kMaxListSources, hipHostMallocDefault));
+    if (!c->list_prep_dev) HIP_TRY(c, hipHostGetDevicePointer((void **)&c->list_prep_dev, c->list_prep_host, 0));
+    if (!c->list_src_stage) HIP_TRY(c, hipMalloc((void **)&c->list_src_stage, sizeof(ListSource) * kMaxListSources));
+    if (!c->bucket_mark) {
+        uint32_t *marks = nullptr;
+        HIP_TRY(c, hipMalloc((void **)&marks, 4 * kMaxBuckets));
+        const hipError_t e = hipMemset(marks, 0, 4 * kMaxBuckets);
+        if (e != hipSuccess) { (void)hipFree(marks); HIP_TRY(c, e); }
+        c->bucket_mark = marks;
     }
     uint32_t n_src = 0, n_new = 0;
     std::vector<CmdRec *> fresh;
@@ -409,12 +439,10 @@ int gather_list_sources(msched_ctx *c, uint32_t G, PlanGeom &g) {
         if (is_new) {
             const uint64_t bytes = (((uint64_t)pieces * hdr_words + rec.n_ids) * 4 + 15) & ~15ull;
             uint64_t off;
-            hipError_t err;
             heads.emplace_back(&t, t.prep_head);
-            if (!ring_alloc(c, t, bytes, off, err)) {
+            if (!ring_alloc(c, t, bytes, off)) {
                 heads.pop_back();
                 undo();
-                if (err != hipSuccess) { c->last_hip = g_last_hip = (int)err; return MSCHED_E_HIP; }
                 return 1;
             }
             rec.reserved = off + 1;
@@ -435,7 +463,17 @@ int gather_list_sources(msched_ctx *c, uint32_t G, PlanGeom &g) {
 
 }  // namespace
 
+namespace {
+int plan_body(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entries, msched_plan_t *out);
+}
+
 int msched_plan(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entries, msched_plan_t *out) {
+    return guarded([&]() -> int { return plan_body(c, tl, n_entries, out); });
+}
+
+namespace {
+
+int plan_body(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entries, msched_plan_t *out) {
     if (!c || !out || (n_entries && !tl) || n_entries > MSCHED_MAX_TIMELINE_ENTRIES) return MSCHED_E_INVAL;
     for (uint32_t e = 0; e < n_entries; ++e) if (tl[e].task >= c->tasks.size()) return MSCHED_E_INVAL;
     c->pending_plan = 0;
@@ -589,24 +627,38 @@ int msched_plan(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entri
     return MSCHED_OK;
 }
 
-namespace {
-
 // Bin the id lists of commands queued behind the ones just planned, while the migration keeps the host link
 // busy and most compute units idle: the next plan then finds them prepared.  Blocks are handed out in program
 // order, so a task stops at the first command that does not fit its ring.
-int prepare_ahead(msched_ctx *c) {
-    if (!c->list_ahead || !c->list_prepared || !c->last_plan_prepared) return MSCHED_OK;
+void prepare_ahead(msched_ctx *c) {
+    if (!c->list_ahead || !c->list_prepared || !c->last_plan_prepared) return;
     const uint32_t n_buckets = (uint32_t)((c->V + (1u << kBucketShift) - 1) >> kBucketShift);
-    if (!c->list_ahead_host) {
-        HIP_TRY(c, hipHostMalloc((void **)&c->list_ahead_host, sizeof(ListPrep) * kMaxListSources, hipHostMallocDefault));
-        HIP_TRY(c, hipHostGetDevicePointer((void **)&c->list_ahead_dev, c->list_ahead_host, 0));
-        HIP_TRY(c, hipEventCreateWithFlags(&c->ahead_ev, hipEventDisableTiming));
+    // Look-ahead is an optimisation: whatever goes wrong here switches it off and leaves the lists to the plans.
+    auto give_up = [&](hipError_t e) { c->last_hip = g_last_hip = (int)e; (void)hipGetLastError(); c->list_ahead = 0; };
+    hipError_t e;
+    if (!c->list_ahead_host &&
+        (e = hipHostMalloc((void **)&c->list_ahead_host, sizeof(ListPrep) * kMaxListSources, hipHostMallocDefault)) != hipSuccess) {
+        c->list_ahead_host = nullptr;
+        return give_up(e);
     }
-    if (c->ahead_pending) { HIP_TRY(c, hipEventSynchronize(c->ahead_ev)); c->ahead_pending = false; }   // the table is free again
+    if (!c->list_ahead_dev && (e = hipHostGetDevicePointer((void **)&c->list_ahead_dev, c->list_ahead_host, 0)) != hipSuccess)
+        return give_up(e);
+    if (!c->ahead_ev && (e = hipEventCreateWithFlags(&c->ahead_ev, hipEventDisableTiming)) != hipSuccess) {
+        c->ahead_ev = nullptr;
+        return give_up(e);
+    }
+    if (c->ahead_pending) {                                  // the table is free again once the last batch has been read
+        if ((e = hipEventSynchronize(c->ahead_ev)) != hipSuccess) return give_up(e);
+        c->ahead_pending = false;
+    }
     const uint64_t hdr_words = (uint64_t)n_buckets + 2;
     uint32_t n_new = 0;
     bool full = false;
-    for (TaskQueue &t : c->tasks) {
+    std::vector<CmdRec *> fresh;
+    std::vector<size_t> scan0(c->tasks.size());
+    for (size_t ti = 0; ti < c->tasks.size(); ++ti) {
+        TaskQueue &t = c->tasks[ti];
+        scan0[ti] = t.prep_scan;
         size_t i = std::max(t.prep_scan, t.cursor);
         const size_t end = std::min(t.n, t.cursor + (size_t)c->list_ahead);
         for (; i < end && !full; ++i) {
@@ -616,12 +668,9 @@ int prepare_ahead(msched_ctx *c) {
             if (n_new + pieces > kMaxListSources) { full = true; break; }
             const uint64_t bytes = (((uint64_t)pieces * hdr_words + rec.n_ids) * 4 + 15) & ~15ull;
             uint64_t off;
-            hipError_t err;
-            if (!ring_alloc(c, t, bytes, off, err)) {
-                if (err != hipSuccess) { c->last_hip = g_last_hip = (int)err; return MSCHED_E_HIP; }
-                break;                                   // no room now: the plan that needs it will see to it
-            }
+            if (!ring_alloc(c, t, bytes, off)) break;        // no room now: the plan that needs it will see to it
             rec.reserved = off + 1;
+            fresh.push_back(&rec);
             uint32_t *block = reinterpret_cast<uint32_t *>(t.prep_buf + off % t.prep_size);
             for (uint32_t p = 0; p < pieces; ++p) {
                 const uint32_t n = std::min<uint32_t>(kPrepBlock, rec.n_ids - p * kPrepBlock);
@@ -632,11 +681,17 @@ int prepare_ahead(msched_ctx *c) {
         t.prep_scan = i;
         if (full) break;
     }
-    if (n_new == 0) return MSCHED_OK;
-    HIP_TRY(c, launch_list_prepare(c, c->list_ahead_dev, n_new, n_buckets));
-    HIP_TRY(c, hipEventRecord(c->ahead_ev, c->stream));
+    if (n_new == 0) return;
+    if ((e = launch_list_prepare(c, c->list_ahead_dev, n_new, n_buckets)) != hipSuccess ||
+        (e = hipEventRecord(c->ahead_ev, c->stream)) != hipSuccess) {
+        // nothing was binned: the records must not point at blocks that hold no list
+        // (a launch that did go out before a failed record is waited for, so the table is not rewritten under it)
+        (void)hipStreamSynchronize(c->stream);
+        for (CmdRec *r : fresh) r->reserved = 0;
+        for (size_t ti = 0; ti < c->tasks.size(); ++ti) c->tasks[ti].prep_scan = scan0[ti];
+        return give_up(e);
+    }
     c->ahead_pending = true;
-    return MSCHED_OK;
 }
 
 }  // namespace
@@ -649,24 +704,36 @@ int msched_migrate(msched_ctx *c, const msched_plan_t *plan) {
     if (c->profiling) { HIP_TRY(c, hipEventRecord(c->ev[6], c->stream)); c->migrate_timed = 1; }
     c->n_resident += c->pending.n_free_used;
     c->pending_plan = 0;
-    return prepare_ahead(c);
+    return guarded([&]() -> int { prepare_ahead(c); return MSCHED_OK; });
 }
 
 int msched_set_early_start(msched_ctx *c, int enable) {
     if (!c) return MSCHED_E_INVAL;
-    if (enable && !c->landed) {                              // first use: bookkeeping of the in-order landing
-        HIP_TRY(c, hipMalloc((void **)&c->page_done, (size_t)c->F * 4));
-        HIP_TRY(c, hipMalloc((void **)&c->chunks_done, (size_t)c->F * 4));
-        HIP_TRY(c, hipMalloc((void **)&c->landed, 256));
-        HIP_TRY(c, hipMemset(c->page_done, 0, (size_t)c->F * 4));
-        HIP_TRY(c, hipMemset(c->chunks_done, 0, (size_t)c->F * 4));
-        HIP_TRY(c, hipMemset(c->landed, 0, 256));
-        HIP_TRY(c, hipHostMalloc((void **)&c->need_host, (MSCHED_MAX_TIMELINE_COMMANDS + 1) * 4, hipHostMallocDefault));
-        HIP_TRY(c, hipHostMalloc((void **)&c->progress_host, 64, hipHostMallocDefault));
-        *c->progress_host = 0;
-        HIP_TRY(c, hipStreamCreateWithFlags(&c->poll_stream, hipStreamNonBlocking));
+    if (enable && !c->early_ready) {
+        // First use: bookkeeping of the in-order landing.  Each piece on its own, so that a failure half-way neither
+        // leaks nor leaves a hole; early execution stays off until all of them exist.
+        auto zeroed = [&](uint32_t **ptr, size_t bytes) -> hipError_t {
+            if (*ptr) return hipSuccess;
+            uint32_t *m = nullptr;
+            hipError_t e = hipMalloc((void **)&m, bytes);
+            if (e != hipSuccess) return e;
+            if ((e = hipMemset(m, 0, bytes)) != hipSuccess) { (void)hipFree(m); return e; }
+            *ptr = m;
+            return hipSuccess;
+        };
+        HIP_TRY(c, zeroed(&c->page_done, (size_t)c->F * 4));
+        HIP_TRY(c, zeroed(&c->chunks_done, (size_t)c->F * 4));
+        HIP_TRY(c, zeroed(&c->landed, 256));
+        if (!c->need_host)
+            HIP_TRY(c, hipHostMalloc((void **)&c->need_host, (MSCHED_MAX_TIMELINE_COMMANDS + 1) * 4, hipHostMallocDefault));
+        if (!c->progress_host) {
+            HIP_TRY(c, hipHostMalloc((void **)&c->progress_host, 64, hipHostMallocDefault));
+            *c->progress_host = 0;
+        }
+        if (!c->poll_stream) HIP_TRY(c, hipStreamCreateWithFlags(&c->poll_stream, hipStreamNonBlocking));
         HIP_TRY(c, launch_peek(c));                          // the first launch on a stream sets up its queue: not during a migration
         HIP_TRY(c, hipDeviceSynchronize());
+        c->early_ready = true;
     }
     c->early = enable ? 1 : 0;
     return MSCHED_OK;
@@ -675,13 +742,14 @@ int msched_set_early_start(msched_ctx *c, int enable) {
 int msched_plan_ready_need(msched_ctx *c, const msched_plan_t *plan, uint32_t *need) {
     if (!c || !plan || (plan->covered_launches && !need)) return MSCHED_E_INVAL;
     if (plan->plan_id != c->plan_seq || !c->plan_early) return MSCHED_E_STALE_PLAN;
-    memcpy(need, c->need_host, (size_t)plan->covered_launches * 4);   // written by the plan's kernels, which have finished
+    if (plan->covered_launches)                                // written by the plan's kernels, which have finished
+        memcpy(need, c->need_host, (size_t)plan->covered_launches * 4);
     return MSCHED_OK;
 }
 
 int msched_progress(msched_ctx *c, uint32_t *landed) {
     if (!c || !landed) return MSCHED_E_INVAL;
-    if (!c->landed) { *landed = 0; return MSCHED_OK; }
+    if (!c->early_ready) { *landed = 0; return MSCHED_OK; }
     HIP_TRY(c, launch_peek(c));
     HIP_TRY(c, hipStreamSynchronize(c->poll_stream));
     *landed = *c->progress_host;
@@ -699,13 +767,15 @@ int msched_pagetable_query(msched_ctx *c, const uint64_t *page_ids, uint32_t n, 
         HIP_TRY(c, hipMalloc((void **)&c->query_buf, (size_t)n * 2 * 4));
         c->query_cap = (size_t)n * 2;
     }
-    std::vector<uint32_t> ids(n);
-    for (uint32_t i = 0; i < n; ++i) ids[i] = (uint32_t)page_ids[i];
-    HIP_TRY(c, hipMemcpyAsync(c->query_buf, ids.data(), (size_t)n * 4, hipMemcpyHostToDevice, c->stream));
-    HIP_TRY(c, launch_query(c, c->query_buf, n, c->query_buf + n));
-    HIP_TRY(c, hipMemcpyAsync(out, c->query_buf + n, (size_t)n * 4, hipMemcpyDeviceToHost, c->stream));
-    HIP_TRY(c, hipStreamSynchronize(c->stream));
-    return MSCHED_OK;
+    return guarded([&]() -> int {
+        std::vector<uint32_t> ids(n);
+        for (uint32_t i = 0; i < n; ++i) ids[i] = (uint32_t)page_ids[i];
+        HIP_TRY(c, hipMemcpyAsync(c->query_buf, ids.data(), (size_t)n * 4, hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, launch_query(c, c->query_buf, n, c->query_buf + n));
+        HIP_TRY(c, hipMemcpyAsync(out, c->query_buf + n, (size_t)n * 4, hipMemcpyDeviceToHost, c->stream));
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        return MSCHED_OK;
+    });
 }
 
 int msched_plan_copy_lists(msched_ctx *c, const msched_plan_t *plan, uint32_t *evict_pages, uint32_t *evict_frames,

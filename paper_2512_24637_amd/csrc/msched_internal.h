@@ -170,6 +170,7 @@ struct msched_ctx {
     uint32_t *progress_host = nullptr;          // pinned: where msched_progress reads `landed` into
     hipStream_t poll_stream = nullptr;          // msched_progress works here, beside the migration
     uint32_t early_tag = 0;                     // nonzero tag of the latest early migration
+    bool early_ready = false;                   // every piece of the early-execution bookkeeping exists
     int plan_early = 0;                         // the latest plan computed need[] and reset landed
     int profiling = 0;
     int migrate_timed = 0;                      // ev[5], ev[6] have been recorded
