@@ -333,6 +333,46 @@ def test_id_lists_longer_than_one_prepared_piece(oracle_mod, monkeypatch):
         o.close()
 
 
+def test_a_plan_with_more_than_a_thousand_prepared_lists(oracle_mod, monkeypatch):
+    """1300 commands, each with a short id list of its own: the merge keeps a table entry per list in LDS, which
+    at this count asks for more than 64 KiB per workgroup."""
+    import torch
+    monkeypatch.setenv("MSCHED_LIST_BINNED_MIN_IDS", "0")
+    V, F, n_cmds, n_ids = 40000, 30000, 650, 48
+    trace = explicit_trace([[[0]], [[1]]], V, F, timeslice=n_cmds, page_shift=6)
+    g = GpuSide(trace)
+    o = make_oracle(oracle_mod, trace, with_bytes=False)
+    rng = np.random.default_rng(17)
+    try:
+        ids = rng.integers(0, V, (2, n_cmds, n_ids)).astype(np.uint32)
+        dev = torch.from_numpy(ids.view(np.int32)).cuda()
+        kg = g.ms.kernel_register([Rule(RULE_LIST)])
+        ko = o.kernel_register([Rule(RULE_LIST)])
+        for impl in (g.ms, o):
+            impl.launch_retire(0, 1)
+            impl.launch_retire(1, 1)
+        for task in (0, 1):
+            for i in range(n_cmds):
+                g.ms.launch_enqueue(task, kg, [], 0, ids_ptr=dev[task, i].data_ptr(), n_ids=n_ids)
+                o.launch_enqueue(task, ko, [], 0, ids=ids[task, i])
+        for k, tl in enumerate(([(0, n_cmds), (1, n_cmds)], [(1, n_cmds), (0, n_cmds)], [(0, n_cmds), (1, n_cmds)])):
+            po, pg = o.plan(tl), g.ms.plan(tl)
+            if k == 0:
+                assert pg.n_commands == 2 * n_cmds
+            assert_same_plan(po, pg, tl)
+            o.migrate()
+            g.ms.migrate()
+            pto, foo = o.state()
+            ptg, fog = g.ms.state()
+            assert np.array_equal(pto, ptg) and np.array_equal(foo, fog)
+            n = min(po.covered_launches, 200)                  # the rest of the slice stays queued: most lists are planned again
+            o.launch_retire(tl[0][0], n)
+            g.ms.launch_retire(tl[0][0], n)
+    finally:
+        g.close()
+        o.close()
+
+
 def test_a_prepared_list_with_a_bad_id_is_refused_by_every_plan(oracle_mod, monkeypatch):
     import torch
     from paper_2512_24637_amd import MSchedError
