@@ -599,7 +599,7 @@ int plan_body(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entries
             HIP_TRY(c, hipStreamSynchronize(c->stream));
             if (c->matrix) HIP_TRY(c, hipFree(c->matrix));
             c->matrix = nullptr; c->matrix_cap = 0;
-            HIP_TRY(c, hipMalloc((void **)&c->matrix, need * 4));
+            HIP_TRY(c, hipMalloc((void **)&c->matrix, need * 4 * 2));     // counts, and behind them the chunk start positions
             c->matrix_cap = need;
         }
         const clk::time_point t_prep = clk::now();

@@ -137,7 +137,7 @@ struct msched_ctx {
     uint32_t *page_table = nullptr, *frame_owner = nullptr, *nu = nullptr, *slot = nullptr;  // device
     uint32_t *evict_pages = nullptr, *evict_frames = nullptr, *fetch_pages = nullptr, *fetch_frames = nullptr;
     uint32_t *flags = nullptr;                  // device status word
-    uint32_t *matrix = nullptr; size_t matrix_cap = 0;       // [n_chunks][n_keys] counts, then offsets
+    uint32_t *matrix = nullptr; size_t matrix_cap = 0;       // [n_chunks][n_keys] counts; behind them [matrix_cap...) the chunks' start positions
     uint32_t *partial = nullptr;                             // [kRowGroups][n_keys], all zero between plans
     uint32_t *offsets = nullptr;                // [2 * (MAX_G + 1)] per-class output offsets
     msched::PlanHeader *hdr_dev = nullptr;      // device

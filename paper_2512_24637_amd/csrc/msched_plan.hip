@@ -788,14 +788,33 @@ struct CutArgs {
     uint32_t in_place;                 // replace `groups` by their exclusive prefix over the rows (they are the matrix itself)
 };
 
+// Exclusive scan of n values by ONE wavefront, no barrier: lane l owns the segment [l * per, (l + 1) * per) of
+// the sequence value(0..n), sums it, the lane sums are scanned with shuffles, then put(i, exclusive prefix,
+// value) is called for the lane's elements in order.  Returns the total to every lane.
+template <class Value, class Put>
+__device__ __forceinline__ uint32_t wave_exclusive_scan(uint32_t n, Value value, Put put) {
+    const uint32_t lane = (uint32_t)lane_id();
+    const uint32_t per = (n + kWave - 1) / kWave;
+    const uint32_t i0 = min(n, lane * per), i1 = min(n, i0 + per);
+    uint32_t local = 0;
+    for (uint32_t i = i0; i < i1; ++i) local += value(i);
+    uint32_t incl = local;
+    for (int d = 1; d < kWave; d <<= 1) {
+        const uint32_t up = __shfl_up(incl, d, kWave);
+        if ((int)lane >= d) incl += up;
+    }
+    const uint32_t total = __shfl(incl, kWave - 1, kWave);
+    uint32_t run = incl - local;
+    for (uint32_t i = i0; i < i1; ++i) { const uint32_t v = value(i); put(i, run, v); run += v; }
+    return total;
+}
+
 __device__ void cut_body(const CutArgs &a, uint32_t *lds) {
     const uint32_t G = a.G, K = G + 1, n_keys = 2 * K, g_end0 = a.g_end0, nthreads = blockDim.x;
     uint32_t *tot = lds;                 // [n_keys]
-    uint32_t *sc = lds + n_keys;         // [K]
-    __shared__ uint32_t wave_sums[1024 / kWave];
-    __shared__ uint32_t s_cut, s_res;
-    const uint32_t tid = threadIdx.x;
-    if (tid == 0) { s_cut = 0; s_res = 0; }
+    __shared__ uint32_t s_cut, s_res, s_fetch;
+    const uint32_t tid = threadIdx.x, wave = tid / kWave;
+    if (tid == 0) { s_cut = 0; s_res = 0; s_fetch = 0; }
     for (uint32_t key = tid; key < n_keys; key += nthreads) {
         uint32_t v[kRowGroups];
 #pragma unroll
@@ -809,33 +828,45 @@ __device__ void cut_body(const CutArgs &a, uint32_t *lds) {
         tot[key] = run;
     }
     __syncthreads();
-    // cut
-    for (uint32_t c = tid; c < K; c += nthreads) sc[c] = (c < g_end0) ? tot[c] + tot[K + c] : 0;
-    __syncthreads();
-    block_exclusive_scan(sc, K, wave_sums);                          // sc[k] = D(k) for k < K
-    uint32_t fit = 0, res = 0;
-    for (uint32_t k = 1 + tid; k <= g_end0; k += nthreads) fit += (sc[k] <= a.F) ? 1u : 0u;   // g_end0 <= G < K
-    for (uint32_t c = tid; c < K; c += nthreads) res += tot[K + c];
-    if (fit) atomicAdd(&s_cut, fit);
-    if (res) atomicAdd(&s_res, res);
+    // The three scans below are short (K = G + 1 values): each is done by one wavefront without a barrier, the
+    // cut by the first, resident pages counted by the others meanwhile; then fetch and victim offsets side by side.
+    if (wave == 0) {
+        // D(k) = pages first used before command k; the cut keeps the longest prefix of the first entry that fits
+        uint32_t fit = 0;
+        wave_exclusive_scan(g_end0, [&](uint32_t c) { return tot[c] + tot[K + c]; },
+                            [&](uint32_t, uint32_t before, uint32_t v) { fit += (before + v <= a.F) ? 1u : 0u; });
+        for (int d = kWave / 2; d > 0; d >>= 1) fit += __shfl_xor(fit, d, kWave);
+        if (tid == 0) s_cut = fit;                          // D is monotone: the count of fitting k is the largest one
+    }
+    if (wave != 0 || nthreads == kWave) {
+        uint32_t res = 0;
+        const uint32_t first = nthreads == kWave ? tid : tid - kWave, step = nthreads == kWave ? kWave : nthreads - kWave;
+        for (uint32_t c = first; c < K; c += step) res += tot[K + c];
+        for (int d = kWave / 2; d > 0; d >>= 1) res += __shfl_xor(res, d, kWave);
+        if (res && (tid % kWave) == 0) atomicAdd(&s_res, res);          // one add per wavefront, not per thread
+    }
     __syncthreads();
     const uint32_t g_cut = s_cut, n_res = s_res;
-    // fetch offsets
-    for (uint32_t c = tid; c < K; c += nthreads) sc[c] = (c < g_cut) ? tot[c] : 0;
+    const uint32_t last_wave = nthreads / kWave - 1;
+    if (wave == 0) {
+        // fetch offsets: classes 0 .. g_cut - 1 of the pages that are not resident, in order of use
+        const uint32_t n_fetch = wave_exclusive_scan(K, [&](uint32_t c) { return c < g_cut ? tot[c] : 0u; },
+                                                     [&](uint32_t c, uint32_t before, uint32_t v) {
+                                                         a.offsets[c] = (c < g_cut) ? before : kSkip;
+                                                         // early execution: command c may start once the fetches of classes 0..c have landed
+                                                         if (a.need_host && c < g_cut) a.need_host[c] = before + v;
+                                                     });
+        if (tid == 0) s_fetch = n_fetch;
+    }
+    if (wave == last_wave) {
+        // victim offsets, farthest next use first: resident classes G (never used), G - 1, ..., g_cut
+        wave_exclusive_scan(K, [&](uint32_t j) { return (G - j >= g_cut) ? tot[K + (G - j)] : 0u; },
+                            [&](uint32_t j, uint32_t before, uint32_t) { a.offsets[K + (G - j)] = (G - j >= g_cut) ? before : kSkip; });
+        if (a.landed && (tid % kWave) == 0) { a.landed[0] = 0; a.landed[1] = 0; }   // entries landed, work units handed out
+    }
     __syncthreads();
-    uint32_t n_fetch = block_exclusive_scan(sc, K, wave_sums);
-    for (uint32_t c = tid; c < K; c += nthreads) a.offsets[c] = (c < g_cut) ? sc[c] : kSkip;
-    // early execution: command c may start once the fetches of classes 0..c have landed
-    if (a.need_host)
-        for (uint32_t c = tid; c < g_cut; c += nthreads) a.need_host[c] = sc[c] + tot[c];
-    if (a.landed && tid == 0) { a.landed[0] = 0; a.landed[1] = 0; }   // entries landed, work units handed out
-    __syncthreads();
-    // victim offsets, farthest next use first
-    for (uint32_t j = tid; j < K; j += nthreads) sc[j] = (G - j >= g_cut) ? tot[K + (G - j)] : 0;
-    __syncthreads();
-    block_exclusive_scan(sc, K, wave_sums);
-    for (uint32_t c = tid; c < K; c += nthreads) a.offsets[K + c] = (c >= g_cut) ? sc[G - c] : kSkip;
     if (tid == 0) {
+        uint32_t n_fetch = s_fetch;
         uint32_t status = *a.flags;
         a.flags[0] = 0;                                     // clean for the next plan's expansion
         a.flags[1] = 0;                                     // work-unit counter of the migration that follows
@@ -857,32 +888,52 @@ __global__ __launch_bounds__(1024) void k_cut(CutArgs a) {
     cut_body(a, lds);
 }
 
-// matrix[w][key] = pages of that key in chunks before w (exclusive prefix down each column), one thread per
-// (key, row group): it starts from the sums of the row groups before its own and walks its rows.
-__device__ __forceinline__ void offsets_body(uint32_t *__restrict__ matrix, uint32_t n_chunks, uint32_t n_keys,
+constexpr uint32_t kOffsetSplit = 4;
+// starts[w][key] = pages of that key in chunks before w (exclusive prefix down each column of the count matrix),
+// one thread per (key, row group, quarter): it starts from the sums of the row groups before its own, adds the
+// rows of the quarters before its own and walks its rows.  Out of place: other threads still read those counts.
+__device__ __forceinline__ void offsets_body(const uint32_t *__restrict__ matrix, uint32_t *__restrict__ starts,
+                                             uint32_t n_chunks, uint32_t n_keys,
                                              const uint32_t *__restrict__ partial, uint32_t item) {
-    const uint32_t key = item % n_keys, rg = item / n_keys;
+    // item = (key, row group, quarter of the group): a compute unit fetches a few tens of GB/s at most, so the
+    // matrix is spread over four times as many workgroups as there are row groups x keys / block size; a thread
+    // re-reads the rows of the quarters before its own instead of waiting for anybody.
+    const uint32_t key = item % n_keys, part = item / n_keys;
+    const uint32_t rg = part / kOffsetSplit, sub = part % kOffsetSplit;
     if (rg >= kRowGroups) return;
     uint32_t run = 0;
     for (uint32_t before = 0; before < rg; ++before) run += partial[before * n_keys + key];
     const uint32_t rows = (n_chunks + kRowGroups - 1) / kRowGroups;
-    const uint32_t w0 = rg * rows, w1 = min(n_chunks, w0 + rows);
-#pragma unroll 8
-    for (uint32_t w = w0; w < w1; ++w) {
-        const size_t i = (size_t)w * n_keys + key;
-        const uint32_t v = matrix[i];
-        matrix[i] = run;
-        run += v;
+    const uint32_t rows_sub = (rows + kOffsetSplit - 1) / kOffsetSplit;
+    const uint32_t g0 = rg * rows, g1 = min(n_chunks, g0 + rows);       // the row group
+    const uint32_t w0 = min(g1, g0 + sub * rows_sub), w1 = min(g1, w0 + rows_sub);
+    constexpr uint32_t kRows = 16;
+    for (uint32_t w = g0; w < w0; w += kRows) {              // rows of the quarters before this one
+        uint32_t v[kRows];
+#pragma unroll
+        for (uint32_t j = 0; j < kRows; ++j) v[j] = (w + j < w0) ? matrix[(size_t)(w + j) * n_keys + key] : 0u;
+#pragma unroll
+        for (uint32_t j = 0; j < kRows; ++j) run += v[j];
+    }
+    for (uint32_t w = w0; w < w1; w += kRows) {
+        uint32_t v[kRows];
+#pragma unroll
+        for (uint32_t j = 0; j < kRows; ++j) v[j] = (w + j < w1) ? matrix[(size_t)(w + j) * n_keys + key] : 0u;
+#pragma unroll
+        for (uint32_t j = 0; j < kRows; ++j) {
+            if (w + j < w1) starts[(size_t)(w + j) * n_keys + key] = run;
+            run += v[j];
+        }
     }
 }
 
-// The cut (one workgroup, a chain of block-wide scans) and the column prefixes (wide) need the same input,
+// The cut (one workgroup, three short scans) and the column prefixes (wide) need the same input,
 // the per-key sums of the row groups, and nothing from each other: one launch, block 0 cuts.
-__global__ __launch_bounds__(1024) void k_cut_offsets(CutArgs a, uint32_t *__restrict__ matrix, uint32_t n_chunks,
-                                                        uint32_t n_keys) {
+__global__ __launch_bounds__(1024) void k_cut_offsets(CutArgs a, const uint32_t *__restrict__ matrix,
+                                                        uint32_t *__restrict__ starts, uint32_t n_chunks, uint32_t n_keys) {
     extern __shared__ uint32_t lds[];
     if (blockIdx.x == 0) { cut_body(a, lds); return; }
-    offsets_body(matrix, n_chunks, n_keys, a.groups, (blockIdx.x - 1) * blockDim.x + threadIdx.x);
+    offsets_body(matrix, starts, n_chunks, n_keys, a.groups, (blockIdx.x - 1) * blockDim.x + threadIdx.x);
 }
 
 // Second sweep over one chunk: every listed page goes to its final position =
@@ -1140,7 +1191,8 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     ca.need_host = c->early ? c->need_host : nullptr; ca.landed = c->early ? c->landed : nullptr;
     ca.in_place = few_rows ? 1u : 0u;
     EmitArgs ea;
-    ea.page_table = c->page_table; ea.nu = c->nu; ea.matrix = c->matrix; ea.offsets = c->offsets; ea.hdr = c->hdr_dev;
+    ea.page_table = c->page_table; ea.nu = c->nu; ea.matrix = few_rows ? c->matrix : c->matrix + c->matrix_cap;   // chunk start positions
+    ea.offsets = c->offsets; ea.hdr = c->hdr_dev;
     ea.fetch_pages = c->fetch_pages; ea.evict_pages = c->evict_pages; ea.evict_frames = c->evict_frames;
     const size_t cut_lds = (size_t)(g.n_keys + g.G + 1) * 4, emit_lds = (size_t)(g.waves + 1) * g.n_keys * 4;
     if (g.single) {
@@ -1151,12 +1203,12 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     k_count<<<g.n_chunks, threads, (size_t)g.n_keys * 4 + paint_lds, st>>>(c->page_table, c->nu, sg, c->matrix,
                                                                 few_rows ? nullptr : c->partial);
     if (prof) CK(hipEventRecord(c->ev[2], st));
-    const uint32_t cut_threads = std::min<uint32_t>(1024, std::max<uint32_t>(256, (g.n_keys / 2 + 63) / 64 * 64));
+    const uint32_t cut_threads = std::min<uint32_t>(1024, std::max<uint32_t>(256, (g.n_keys + 63) / 64 * 64));   // a key per thread
     if (few_rows) {
         k_cut<<<1, cut_threads, cut_lds, st>>>(ca);
     } else {
-        const uint32_t items = g.n_keys * kRowGroups;
-        k_cut_offsets<<<1 + (items + cut_threads - 1) / cut_threads, cut_threads, cut_lds, st>>>(ca, c->matrix, g.n_chunks, g.n_keys);
+        const uint32_t items = g.n_keys * kRowGroups * kOffsetSplit;
+        k_cut_offsets<<<1 + (items + cut_threads - 1) / cut_threads, cut_threads, cut_lds, st>>>(ca, c->matrix, c->matrix + c->matrix_cap, g.n_chunks, g.n_keys);
     }
     if (prof) CK(hipEventRecord(c->ev[3], st));
     k_emit<<<g.n_chunks, threads, emit_lds, st>>>(ea, sg);
