@@ -656,13 +656,13 @@ __device__ __forceinline__ void count_batch(uint32_t n_steps, uint32_t *hist, co
 // order), counting into the wavefront's own LDS histogram.  Lanes with equal keys are grouped by
 // ballot, so a step costs one pass per distinct key present, not one per page, and the loop itself
 // touches no memory; one LDS atomic per distinct key then reserves the group's slots.
-__device__ __forceinline__ void rank_tile(const SweepGeom &sg, uint32_t *hist, const uint32_t (&key)[kMaxSteps],
-                                          uint32_t (&rk)[kMaxSteps]) {
+// On return key[s] holds (rank << 16) | key for a ranked page (ranks stay below the 1024 pages of a slice, keys below
+// 2^16) and kNone for a page that takes no part: half the registers of two arrays.
+__device__ __forceinline__ void rank_tile(const SweepGeom &sg, uint32_t *hist, uint32_t (&key)[kMaxSteps]) {
     const int lane = lane_id();
     const uint64_t below = lanes_below();
 #pragma unroll
     for (int s = 0; s < kMaxSteps; ++s) {
-        rk[s] = 0;
         if ((uint32_t)s < sg.steps) {
             const bool valid = key[s] != kNone;
             int my_leader = lane;
@@ -682,7 +682,7 @@ __device__ __forceinline__ void rank_tile(const SweepGeom &sg, uint32_t *hist, c
             uint32_t before = 0;
             if (valid && lane == my_leader) before = atomicAdd(&hist[key[s]], group);
             before = __shfl(before, my_leader, kWave);
-            rk[s] = before + my_rank;
+            if (valid) key[s] |= (before + my_rank) << 16;
         }
     }
 }
@@ -945,39 +945,63 @@ struct EmitArgs {
     uint32_t *fetch_pages, *evict_pages, *evict_frames;
 };
 
+// LDS words emit_body needs: a histogram per wavefront, the running positions, and a 2 KiB staging line per wavefront.
+__host__ __device__ inline size_t emit_lds_words(uint32_t waves, uint32_t n_keys) {
+    return (((size_t)(waves + 1) * n_keys + 3) & ~(size_t)3) + (size_t)waves * (kMaxSteps * kWave / 2);   // staging lines 16-byte aligned
+}
+
 __device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg, uint32_t chunk, uint32_t *lds) {
-    const uint32_t n_fetch = a.hdr->n_fetch, n_evict = a.hdr->n_evict;
-    if (n_fetch == 0) return;                             // same for every thread of the block
     const uint32_t K = sg.G + 1, n_keys = 2 * K;
     const uint32_t waves = blockDim.x / kWave, wave = threadIdx.x / kWave;
     const int lane = lane_id();
+    const uint64_t p_begin = (uint64_t)chunk * sg.chunk_pages;
+    const uint64_t p_end = min(sg.V, p_begin + sg.chunk_pages);
+    const uint64_t tile_pages = (uint64_t)waves * sg.steps * kWave;
+    // The classes of a wavefront's slice (up to 1024 pages, 2 bytes each) are two 16-byte loads per lane, requested
+    // before anything else so that their way from memory overlaps the set-up below; the lanes then exchange them
+    // through LDS, because lane l ranks pages l, 64 + l, ... (page order inside a step), not 16 l .. 16 l + 15.
+    constexpr uint32_t kLanePages = kMaxSteps * kWave / kWave;                    // consecutive pages a lane requests
+    static_assert(kLanePages == 16, "two uint4 of 16-bit classes per lane cover the slice");
+    struct Raw { uint4 lo, hi; };
+    const uint4 none4 = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};     // kNoKey16 in every half
+    auto request_slice = [&](uint32_t round) -> Raw {
+        const uint64_t first = p_begin + round * tile_pages + (uint64_t)wave * sg.steps * kWave + (uint32_t)lane * kLanePages;
+        // pages past the chunk's end are masked when the classes are read back; the array is padded past V
+        if ((uint32_t)lane * kLanePages >= sg.steps * kWave || first >= p_end) return Raw{none4, none4};
+        const uint4 *src = reinterpret_cast<const uint4 *>(sg.key16 + first);
+        return Raw{src[0], src[1]};
+    };
+    Raw raw = request_slice(0);
+    const uint32_t n_fetch = a.hdr->n_fetch, n_evict = a.hdr->n_evict;
+    if (n_fetch == 0) return;                             // same for every thread of the block
     uint32_t *base = lds + waves * n_keys;               // [n_keys] running output position per key
     uint32_t *hist = lds + wave * n_keys;
+    uint16_t *stage = reinterpret_cast<uint16_t *>(lds + (((size_t)(waves + 1) * n_keys + 3) & ~(size_t)3)) + wave * (kMaxSteps * kWave);
     const uint32_t *row = a.matrix + (size_t)chunk * n_keys;
     for (uint32_t k = threadIdx.x; k < n_keys; k += blockDim.x) {
         const uint32_t off = a.offsets[k];
         base[k] = (off == kSkip) ? kSkip : off + row[k];
     }
-    const uint64_t p_begin = (uint64_t)chunk * sg.chunk_pages;
-    const uint64_t p_end = min(sg.V, p_begin + sg.chunk_pages);
-    const uint64_t tile_pages = (uint64_t)waves * sg.steps * kWave;
     for (uint32_t round = 0; round < sg.rounds; ++round) {
+        if (round) raw = request_slice(round);
         for (uint32_t i = threadIdx.x; i < waves * n_keys; i += blockDim.x) lds[i] = 0;
+        reinterpret_cast<uint4 *>(stage + lane * kLanePages)[0] = raw.lo;      // read back by this wavefront only
+        reinterpret_cast<uint4 *>(stage + lane * kLanePages)[1] = raw.hi;
         __syncthreads();
         const uint64_t tile_begin = p_begin + round * tile_pages;
         const uint64_t wave_begin = tile_begin + (uint64_t)wave * sg.steps * kWave;
-        uint32_t key[kMaxSteps], rk[kMaxSteps];
+        uint32_t key[kMaxSteps];
 #pragma unroll
         for (int s = 0; s < kMaxSteps; ++s) {
             const uint64_t p = wave_begin + (uint64_t)s * kWave + lane;
-            const uint16_t k16 = ((uint32_t)s < sg.steps && p < p_end) ? sg.key16[p] : kNoKey16;
+            const uint16_t k16 = ((uint32_t)s < sg.steps && p < p_end) ? stage[s * kWave + lane] : kNoKey16;
             key[s] = k16 == kNoKey16 ? kNone : (uint32_t)k16;
         }
         // a key none of whose pages in this chunk can land inside its list is dropped here
 #pragma unroll
         for (int s = 0; s < kMaxSteps; ++s)
             if (key[s] != kNone && base[key[s]] >= (key[s] < K ? n_fetch : n_evict)) key[s] = kNone;
-        rank_tile(sg, hist, key, rk);
+        rank_tile(sg, hist, key);
         __syncthreads();
         // per key: each wavefront's start position in this tile; carry the running position on
         for (uint32_t k = threadIdx.x; k < n_keys; k += blockDim.x) {
@@ -993,9 +1017,10 @@ __device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg
 #pragma unroll
         for (int s = 0; s < kMaxSteps; ++s) {
             if ((uint32_t)s < sg.steps && key[s] != kNone) {
-                const uint32_t where = hist[key[s]] + rk[s];
+                const uint32_t k = key[s] & 0xFFFFu;
+                const uint32_t where = hist[k] + (key[s] >> 16);
                 const uint32_t p = (uint32_t)(wave_begin + (uint64_t)s * kWave + lane);
-                if (key[s] < K) {
+                if (k < K) {
                     if (where < n_fetch) a.fetch_pages[where] = p;
                 } else if (where < n_evict) {
                     a.evict_pages[where] = p;
@@ -1194,7 +1219,7 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     ea.page_table = c->page_table; ea.nu = c->nu; ea.matrix = few_rows ? c->matrix : c->matrix + c->matrix_cap;   // chunk start positions
     ea.offsets = c->offsets; ea.hdr = c->hdr_dev;
     ea.fetch_pages = c->fetch_pages; ea.evict_pages = c->evict_pages; ea.evict_frames = c->evict_frames;
-    const size_t cut_lds = (size_t)(g.n_keys + g.G + 1) * 4, emit_lds = (size_t)(g.waves + 1) * g.n_keys * 4;
+    const size_t cut_lds = (size_t)(g.n_keys + g.G + 1) * 4, emit_lds = emit_lds_words(g.waves, g.n_keys) * 4;
     if (g.single) {
         k_tail<<<1, threads, std::max(cut_lds, emit_lds + paint_lds), st>>>(sg, ca, ea, c->fetch_frames);
         if (c->profiling) CK(hipEventRecord(c->ev[4], st));
