@@ -234,9 +234,10 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     auto fail = [&](hipError_t e) { c->last_hip = g_last_hip = (int)e; rc = MSCHED_E_HIP; };
     hipError_t e;
 #define ALLOC(ptr, bytes) if (rc == MSCHED_OK && (e = hipMalloc((void **)&(ptr), (bytes))) != hipSuccess) fail(e)
-    ALLOC(c->page_table, c->V * 4);
+    // page table, next use and slots are read 16 bytes at a time: padded, so that the last lane may run past V
+    ALLOC(c->page_table, c->V * 4 + 64);
     ALLOC(c->frame_owner, (size_t)c->F * 4);
-    ALLOC(c->nu, c->V * 4);
+    ALLOC(c->nu, c->V * 4 + 64);
     ALLOC(c->evict_pages, (size_t)c->F * 4);
     ALLOC(c->evict_frames, (size_t)c->F * 4);
     ALLOC(c->fetch_pages, (size_t)c->F * 4);

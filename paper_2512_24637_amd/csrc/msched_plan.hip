@@ -560,6 +560,8 @@ constexpr uint16_t kNoKey16 = 0xffff;                  // keys are below 2 * (MS
 //     together when it is long, by one thread when it is a few pages.
 // Nothing per page goes through memory: that is what the scatter path (k_expand) spends its time on.
 // ------------------------------------------------------------------------------------------
+// Where the painted tile starts in the first sweep's LDS: behind the histogram, on a 16-byte boundary.
+__host__ __device__ inline uint32_t count_paint_offset(uint32_t n_keys) { return (n_keys + 3u) & ~3u; }
 constexpr uint32_t kPaintQueue = kWave * kMaxWaves;       // one slot per thread and batch
 constexpr uint32_t kPaintSerial = 32;                     // ranges up to this many pages are painted by one thread
 
@@ -605,49 +607,33 @@ __device__ void paint_tile(const SweepGeom &sg, uint64_t t0, uint64_t t1, uint32
     }
 }
 
-// A batch of a tile: the wavefront loads kCountBatch x 64 consecutive pages of its slice (all loads issued
-// before any use) and classifies them.  Eight steps at a time keep the first sweep at half the registers of
-// a whole 16-step slice, which doubles the workgroups a compute unit holds.
+// A batch of a tile: kCountBatch x 64 consecutive pages of the wavefront's slice, lane l taking the kCountBatch
+// consecutive pages from kCountBatch * l on.  Counting needs no page order, and eight consecutive pages make every
+// access a 16-byte one: two loads each for page table and next use, two LDS reads for the painted tile, one
+// store for the classes.  Eight pages at a time also keep the first sweep at half the registers of a whole
+// 16-step slice, which doubles the workgroups a compute unit holds.
 constexpr int kCountBatch = 8;
-__device__ __forceinline__ void load_batch(const uint32_t *__restrict__ page_table, const uint32_t *__restrict__ nu,
-                                           const SweepGeom &sg, uint64_t batch_begin, uint32_t n_steps, uint64_t p_end,
-                                           uint32_t (&key)[kCountBatch], const uint32_t *paint, uint64_t tile_begin,
-                                           uint32_t floor) {
-    const int lane = lane_id();
-    uint32_t enc[kCountBatch], fr[kCountBatch];
-#pragma unroll
-    for (int s = 0; s < kCountBatch; ++s) {
-        const uint64_t p = batch_begin + (uint64_t)s * kWave + lane;
-        const bool in = (uint32_t)s < n_steps && p < p_end;
-        fr[s] = in ? page_table[p] : kNone;
-        enc[s] = (in && sg.use_nu) ? nu[p] : 0u;
-    }
-#pragma unroll
-    for (int s = 0; s < kCountBatch; ++s) {
-        const uint64_t p = batch_begin + (uint64_t)s * kWave + lane;
-        const bool in = (uint32_t)s < n_steps && p < p_end;
-        const uint32_t painted = (in && sg.n_ranges) ? min(floor, paint[p - tile_begin]) : sg.G;
-        key[s] = classify(fr[s], enc[s], sg.epoch, sg.G, painted);
-    }
+struct Eight { uint4 lo, hi; };
+__device__ __forceinline__ uint32_t eight_at(const Eight &e, int j) {
+    const uint4 &h = j < 4 ? e.lo : e.hi;
+    switch (j & 3) { case 0: return h.x; case 1: return h.y; case 2: return h.z; default: return h.w; }
 }
 
 // Count the batch's pages per key into one LDS histogram.  Runs of pages usually share a key (dense
 // ranges, long stretches of resident pages nobody will use), so the first lane's key is settled for
 // all its lanes with one add; whatever other keys the step holds go through per-lane LDS atomics.
-__device__ __forceinline__ void count_batch(uint32_t n_steps, uint32_t *hist, const uint32_t (&key)[kCountBatch]) {
+__device__ __forceinline__ void count_batch(uint32_t *hist, const uint32_t (&key)[kCountBatch]) {
     const int lane = lane_id();
 #pragma unroll
     for (int s = 0; s < kCountBatch; ++s) {
-        if ((uint32_t)s < n_steps) {
-            const bool valid = key[s] != kNone;
-            const uint64_t any = __ballot(valid);
-            if (any) {
-                const int leader = __ffsll((long long)any) - 1;
-                const uint32_t k = __builtin_amdgcn_readlane(key[s], leader);
-                const uint64_t same = __ballot(valid && key[s] == k);
-                if (lane == leader) atomicAdd(&hist[k], (uint32_t)__popcll(same));
-                if (valid && key[s] != k) atomicAdd(&hist[key[s]], 1u);
-            }
+        const bool valid = key[s] != kNone;
+        const uint64_t any = __ballot(valid);
+        if (any) {
+            const int leader = __ffsll((long long)any) - 1;
+            const uint32_t k = __builtin_amdgcn_readlane(key[s], leader);
+            const uint64_t same = __ballot(valid && key[s] == k);
+            if (lane == leader) atomicAdd(&hist[k], (uint32_t)__popcll(same));
+            if (valid && key[s] != k) atomicAdd(&hist[key[s]], 1u);
         }
     }
 }
@@ -699,29 +685,56 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
     const uint64_t p_begin = (uint64_t)chunk * sg.chunk_pages;
     const uint64_t p_end = min(sg.V, p_begin + sg.chunk_pages);
     const uint64_t tile_pages = (uint64_t)waves * sg.steps * kWave;
-    uint32_t *paint = lds + n_keys;                       // [tile_pages] when there are ranges to paint
+    uint32_t *paint = lds + count_paint_offset(n_keys);   // [tile_pages] when there are ranges to paint, 16-byte aligned
     __shared__ PaintLds s_paint;
-    const int lane = lane_id();
+    const uint32_t lane = (uint32_t)lane_id();
+    const uint4 none4 = {kNone, kNone, kNone, kNone}, zero4 = {0u, 0u, 0u, 0u};
     for (uint32_t round = 0; round < sg.rounds; ++round) {
         const uint64_t tile_begin = p_begin + round * tile_pages;
         if (sg.n_ranges) paint_tile(sg, tile_begin, min(p_end, tile_begin + tile_pages), paint, s_paint);
         const uint64_t wave_begin = tile_begin + (uint64_t)wave * sg.steps * kWave;
         for (uint32_t s0 = 0; s0 < sg.steps; s0 += kCountBatch) {
+            const uint32_t batch_pages = min((uint32_t)kCountBatch, sg.steps - s0) * kWave;
+            const uint64_t first = wave_begin + (uint64_t)s0 * kWave + lane * kCountBatch;   // this lane's eight pages
+            const bool live = lane * kCountBatch < batch_pages && first < p_end;
+            // the arrays are padded, so a lane whose eight pages straddle the end of the table may load all eight
+            Eight fr{none4, none4}, enc{zero4, zero4}, pt{zero4, zero4};
+            if (live) {
+                const uint4 *src = reinterpret_cast<const uint4 *>(page_table + first);
+                fr = Eight{src[0], src[1]};
+                if (sg.use_nu) { const uint4 *e = reinterpret_cast<const uint4 *>(nu + first); enc = Eight{e[0], e[1]}; }
+                if (sg.n_ranges) { const uint4 *q = reinterpret_cast<const uint4 *>(paint + (first - tile_begin)); pt = Eight{q[0], q[1]}; }
+            }
             uint32_t key[kCountBatch];
-            const uint32_t n_steps = min((uint32_t)kCountBatch, sg.steps - s0);
-            const uint64_t batch_begin = wave_begin + (uint64_t)s0 * kWave;
-            load_batch(page_table, nu, sg, batch_begin, n_steps, p_end, key, paint, tile_begin, s_paint.floor);
+#pragma unroll
+            for (int j = 0; j < kCountBatch; ++j) {
+                const bool in = live && first + j < p_end;
+                const uint32_t painted = (in && sg.n_ranges) ? min(s_paint.floor, eight_at(pt, j)) : sg.G;
+                key[j] = in ? classify(eight_at(fr, j), eight_at(enc, j), sg.epoch, sg.G, painted) : kNone;
+            }
             if (sg.slot != nullptr && sg.n_ranges) {      // a page a range wants must have a backing slot
 #pragma unroll
-                for (int s = 0; s < kCountBatch; ++s)
-                    if (key[s] < sg.G && sg.slot[batch_begin + (uint64_t)s * kWave + lane] == kNone) atomicOr(sg.flags, kStatRange);
+                for (int j = 0; j < kCountBatch; ++j)
+                    if (key[j] < sg.G && sg.slot[first + j] == kNone) atomicOr(sg.flags, kStatRange);
             }
+            // the second sweep reads the classes from here, 2 bytes a page
+            if (live) {
+                uint32_t w[kCountBatch / 2];
 #pragma unroll
-            for (int s = 0; s < kCountBatch; ++s) {       // the second sweep reads the classes from here, 2 bytes a page
-                const uint64_t p = batch_begin + (uint64_t)s * kWave + lane;
-                if ((uint32_t)s < n_steps && p < p_end) sg.key16[p] = key[s] == kNone ? kNoKey16 : (uint16_t)key[s];
+                for (int j = 0; j < kCountBatch; j += 2) {
+                    const uint32_t a = key[j] == kNone ? (uint32_t)kNoKey16 : key[j];
+                    const uint32_t b = key[j + 1] == kNone ? (uint32_t)kNoKey16 : key[j + 1];
+                    w[j / 2] = a | (b << 16);
+                }
+                if (first + kCountBatch <= p_end) {
+                    *reinterpret_cast<uint4 *>(sg.key16 + first) = uint4{w[0], w[1], w[2], w[3]};
+                } else {
+#pragma unroll
+                    for (int j = 0; j < kCountBatch; ++j)
+                        if (first + j < p_end) sg.key16[first + j] = (uint16_t)(w[j / 2] >> (16 * (j & 1)));
+                }
             }
-            count_batch(n_steps, lds, key);
+            count_batch(lds, key);
         }
         if (sg.n_ranges) __syncthreads();                 // the next tile repaints
     }
@@ -1221,11 +1234,11 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     ea.fetch_pages = c->fetch_pages; ea.evict_pages = c->evict_pages; ea.evict_frames = c->evict_frames;
     const size_t cut_lds = (size_t)(g.n_keys + g.G + 1) * 4, emit_lds = emit_lds_words(g.waves, g.n_keys) * 4;
     if (g.single) {
-        k_tail<<<1, threads, std::max(cut_lds, emit_lds + paint_lds), st>>>(sg, ca, ea, c->fetch_frames);
+        k_tail<<<1, threads, std::max(cut_lds, emit_lds + paint_lds + 16), st>>>(sg, ca, ea, c->fetch_frames);
         if (c->profiling) CK(hipEventRecord(c->ev[4], st));
         return hipGetLastError();
     }
-    k_count<<<g.n_chunks, threads, (size_t)g.n_keys * 4 + paint_lds, st>>>(c->page_table, c->nu, sg, c->matrix,
+    k_count<<<g.n_chunks, threads, (size_t)count_paint_offset(g.n_keys) * 4 + paint_lds, st>>>(c->page_table, c->nu, sg, c->matrix,
                                                                 few_rows ? nullptr : c->partial);
     if (prof) CK(hipEventRecord(c->ev[2], st));
     const uint32_t cut_threads = std::min<uint32_t>(1024, std::max<uint32_t>(256, (g.n_keys + 63) / 64 * 64));   // a key per thread
