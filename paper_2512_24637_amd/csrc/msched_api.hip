@@ -413,8 +413,9 @@ int gather_list_sources(msched_ctx *c, uint32_t G, PlanGeom &g) {
     if (!c->list_src_stage) HIP_TRY(c, hipMalloc((void **)&c->list_src_stage, sizeof(ListSource) * kMaxListSources));
     if (!c->bucket_mark) {
         uint32_t *marks = nullptr;
-        HIP_TRY(c, hipMalloc((void **)&marks, 4 * kMaxBuckets));
-        const hipError_t e = hipMemset(marks, 0, 4 * kMaxBuckets);
+        const size_t bytes = 4 * (size_t)kMaxBuckets;
+        HIP_TRY(c, hipMalloc((void **)&marks, bytes));
+        const hipError_t e = hipMemset(marks, 0, bytes);
         if (e != hipSuccess) { (void)hipFree(marks); HIP_TRY(c, e); }
         c->bucket_mark = marks;
     }

@@ -430,81 +430,91 @@ __global__ __launch_bounds__(kListThreads) void k_list_prepare(const ListPrep *_
     }
 }
 
-constexpr uint32_t kMergeHints = 4096;
 struct MergeArgs {
     const ListSource *src; uint32_t n_src, n_buckets;
     uint32_t *nu; uint32_t *flags; uint64_t V; uint32_t epoch_base;
     const uint32_t *bucket_mark;        // [n_buckets] has any prepared piece of this context ever put an id here?
 };
 
+// A workgroup per bucket.  The bucket's ids sit in one short segment per piece (tens of ids when a plan holds
+// hundreds of pieces), so the pieces are dealt to the wavefronts, kMergePieces at a time: what a piece needs
+// (segment address, length, next-use code) is the same for all lanes and is read once per piece, the lanes load
+// the segments' ids side by side, and an id costs one load and one LDS atomic.  Whatever a segment holds beyond
+// kMergeHead ids (a few long lists instead of many short ones) is shared out over the whole workgroup afterwards.
+// (Measured and dropped: the per-piece values in scalar registers, a second workgroup for buckets with many ids,
+// the marked buckets listed first in dispatch order - each slower than this on the planning-stress structure.)
+constexpr int kMergePieces = 8;                     // segments in flight per wavefront
+constexpr uint32_t kMergeHead = 4 * kWave;          // ids of a segment its wavefront takes itself
+
 __global__ __launch_bounds__(kListThreads) void k_list_merge(MergeArgs a) {
     // buckets with ids tend to be neighbours (one table): the strided map spreads them over the dispatch order
+    // and with it over the compute units
     const uint32_t b = chunk_of_block(blockIdx.x, gridDim.x);
     if (b != 0 && !a.bucket_mark[b]) return;                // bucket 0 always runs: it also reports unplannable ids
     __shared__ uint32_t tab[kBucketPages];
-    __shared__ uint32_t wave_sums[kListThreads / kWave];
     extern __shared__ uint64_t merge_lds[];
     const uint32_t **first = reinterpret_cast<const uint32_t **>(merge_lds);   // [n_src] this bucket's first id in piece s
-    uint32_t *pre = reinterpret_cast<uint32_t *>(first + a.n_src);             // [n_src + 1] ids of this bucket in the pieces before s
-    uint32_t *enc = pre + a.n_src + 1;                                          // [n_src] next-use code of the piece's command
-    uint32_t *hint = enc + a.n_src;                                             // [kMergeHints] piece of every 64th (or 128th, ...) id
+    uint32_t *len = reinterpret_cast<uint32_t *>(first + a.n_src);             // [n_src] ids of this bucket in piece s
+    uint32_t *enc = len + a.n_src;                                              // [n_src] next-use code of the piece's command
+    uint32_t longest = 0;
     for (uint32_t s = threadIdx.x; s < a.n_src; s += blockDim.x) {
         const ListSource S = a.src[s];
         const uint32_t lo = S.block[1 + b], hi = S.block[2 + b];
         first[s] = S.block + a.n_buckets + 2 + lo;
-        pre[s] = hi - lo;
+        len[s] = hi - lo;
         enc[s] = kNuMask - S.g;
+        longest = max(longest, hi - lo);
         if (b == 0 && S.block[0]) atomicOr(a.flags, kStatRange);   // the piece held an id that cannot be planned
     }
-    if (threadIdx.x == 0) pre[a.n_src] = 0;
-    __syncthreads();
-    const uint32_t total = block_exclusive_scan(pre, a.n_src + 1, wave_sums);
-    if (total == 0) return;
     for (uint32_t i = threadIdx.x; i < kBucketPages; i += blockDim.x) tab[i] = 0;
-    __syncthreads();
-    // Which piece holds the i-th id of the bucket?  One binary search per 64 ids (or more) fills a table of starting
-    // points; from there a lane walks forward over at most a few pieces (a piece holds tens of ids per bucket).
-    uint32_t hint_shift = 6;                                               // the table has kMergeHints entries: coarser for huge buckets
-    while ((total >> hint_shift) >= kMergeHints) ++hint_shift;
-    const uint32_t n_hint = (total >> hint_shift) + 1;
-    for (uint32_t h = threadIdx.x; h < n_hint; h += blockDim.x) {
-        const uint32_t i = h << hint_shift;
-        uint32_t lo = 0, hi = a.n_src;                                      // last s with pre[s] <= i
-        while (hi - lo > 1) { const uint32_t mid = (lo + hi) >> 1; if (pre[mid] <= i) lo = mid; else hi = mid; }
-        hint[h] = lo;
-    }
-    __syncthreads();
-    // Every step is taken for all of a lane's ids before the next one starts, so that their LDS and memory round
-    // trips overlap instead of queueing behind each other (the piece lookup is a chain of dependent LDS reads).
-    constexpr int kInFlight = 8;                                            // ids in flight per lane
-    for (uint32_t i0 = threadIdx.x; i0 < total; i0 += blockDim.x * kInFlight) {
-        uint32_t s[kInFlight], nxt[kInFlight], id[kInFlight];
+    const int any_ids = __syncthreads_or(longest != 0);
+    const int any_long = __syncthreads_or(longest > kMergeHead);
+    if (!any_ids) return;
+    const uint32_t lane = (uint32_t)lane_id(), wave = threadIdx.x / kWave, waves = blockDim.x / kWave;
+    for (uint32_t s0 = wave * kMergePieces; s0 < a.n_src; s0 += waves * kMergePieces) {
+        const uint32_t *ptr[kMergePieces];
+        uint32_t n[kMergePieces], e[kMergePieces];
 #pragma unroll
-        for (int j = 0; j < kInFlight; ++j) {
-            const uint32_t i = i0 + j * blockDim.x;
-            s[j] = i < total ? hint[i >> hint_shift] : 0u;
+        for (int j = 0; j < kMergePieces; ++j) {             // the same for every lane
+            const uint32_t s = min(s0 + j, a.n_src - 1);
+            n[j] = (s0 + j < a.n_src) ? min(len[s], kMergeHead) : 0u;
+            e[j] = enc[s];
+            ptr[j] = first[s];
         }
-        for (bool moved = true; moved;) {                                   // walk forward to the piece that holds id i
-            moved = false;
+        uint32_t n_max = 0;
 #pragma unroll
-            for (int j = 0; j < kInFlight; ++j) nxt[j] = pre[s[j] + 1];
+        for (int j = 0; j < kMergePieces; ++j) n_max = max(n_max, n[j]);
+        // two rows of 64 ids from each of the segments per pass: every load of a pass is issued before its first atomic
+        for (uint32_t r0 = 0; r0 < n_max; r0 += 2 * kWave) {
+            uint32_t id[2][kMergePieces];
 #pragma unroll
-            for (int j = 0; j < kInFlight; ++j) {
-                const uint32_t i = i0 + j * blockDim.x;
-                if (i < total && nxt[j] <= i) { ++s[j]; moved = true; }     // pre[n_src] = total > i ends the walk
+            for (int q = 0; q < 2; ++q)
+#pragma unroll
+                for (int j = 0; j < kMergePieces; ++j)
+                    id[q][j] = r0 + q * kWave + lane < n[j] ? ptr[j][r0 + q * kWave + lane] : kNone;
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+#pragma unroll
+                for (int j = 0; j < kMergePieces; ++j)
+                    if (id[q][j] != kNone) atomicMax(&tab[id[q][j] & (kBucketPages - 1)], e[j]);   // never 0
+        }
+    }
+    if (any_long) {
+        for (uint32_t s = 0; s < a.n_src; ++s) {
+            const uint32_t n = len[s];
+            if (n <= kMergeHead) continue;
+            const uint32_t *ptr = first[s];
+            const uint32_t code = enc[s];
+            constexpr int kInFlight = 4;
+            for (uint32_t i0 = kMergeHead + threadIdx.x; i0 < n; i0 += blockDim.x * kInFlight) {
+                uint32_t id[kInFlight];
+#pragma unroll
+                for (int j = 0; j < kInFlight; ++j) id[j] = i0 + j * blockDim.x < n ? ptr[i0 + j * blockDim.x] : kNone;
+#pragma unroll
+                for (int j = 0; j < kInFlight; ++j)
+                    if (id[j] != kNone) atomicMax(&tab[id[j] & (kBucketPages - 1)], code);
             }
         }
-        const uint32_t *src_ptr[kInFlight];
-#pragma unroll
-        for (int j = 0; j < kInFlight; ++j) {
-            const uint32_t i = i0 + j * blockDim.x;
-            src_ptr[j] = i < total ? first[s[j]] + (i - pre[s[j]]) : nullptr;
-        }
-#pragma unroll
-        for (int j = 0; j < kInFlight; ++j) id[j] = src_ptr[j] ? *src_ptr[j] : kNone;
-#pragma unroll
-        for (int j = 0; j < kInFlight; ++j)
-            if (id[j] != kNone) atomicMax(&tab[id[j] & (kBucketPages - 1)], enc[s[j]]);   // never 0
     }
     __syncthreads();
     const uint64_t p0 = (uint64_t)b << kBucketShift;
@@ -1194,7 +1204,7 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
             ma.src = c->list_src_stage; ma.n_src = g.n_list_sources; ma.n_buckets = g.n_buckets;
             ma.nu = c->nu; ma.flags = c->flags; ma.V = c->V; ma.epoch_base = a.epoch_base; ma.bucket_mark = c->bucket_mark;
             if (g.n_list_sources)
-                k_list_merge<<<g.n_buckets, kListThreads, (size_t)g.n_list_sources * 16 + 16 + kMergeHints * 4, st>>>(ma);
+                k_list_merge<<<g.n_buckets, kListThreads, (size_t)g.n_list_sources * 16, st>>>(ma);
         } else if (c->has_list_rule && g.list_binned) {
             ListArgs la;
             la.e = a; la.bucket_fill = c->list_bucket_fill; la.pairs = c->list_pairs;
