@@ -917,13 +917,16 @@ constexpr uint32_t kOffsetSplit = 4;
 // rows of the quarters before its own and walks its rows.  Out of place: other threads still read those counts.
 __device__ __forceinline__ void offsets_body(const uint32_t *__restrict__ matrix, uint32_t *__restrict__ starts,
                                              uint32_t n_chunks, uint32_t n_keys,
-                                             const uint32_t *__restrict__ partial, uint32_t item) {
+                                             const uint32_t *__restrict__ partial, uint32_t item, uint32_t g_end0) {
     // item = (key, row group, quarter of the group): a compute unit fetches a few tens of GB/s at most, so the
     // matrix is spread over four times as many workgroups as there are row groups x keys / block size; a thread
     // re-reads the rows of the quarters before its own instead of waiting for anybody.
     const uint32_t key = item % n_keys, part = item / n_keys;
     const uint32_t rg = part / kOffsetSplit, sub = part % kOffsetSplit;
     if (rg >= kRowGroups) return;
+    // pages that are not resident and first used after the incoming task's entry are never fetched, whatever the
+    // cut turns out to be (g_cut <= g_end0): their columns get no offset and their start positions are never read
+    if (key < n_keys / 2 && key >= g_end0) return;
     uint32_t run = 0;
     for (uint32_t before = 0; before < rg; ++before) run += partial[before * n_keys + key];
     const uint32_t rows = (n_chunks + kRowGroups - 1) / kRowGroups;
@@ -956,7 +959,7 @@ __global__ __launch_bounds__(1024) void k_cut_offsets(CutArgs a, const uint32_t 
                                                         uint32_t *__restrict__ starts, uint32_t n_chunks, uint32_t n_keys) {
     extern __shared__ uint32_t lds[];
     if (blockIdx.x == 0) { cut_body(a, lds); return; }
-    offsets_body(matrix, starts, n_chunks, n_keys, a.groups, (blockIdx.x - 1) * blockDim.x + threadIdx.x);
+    offsets_body(matrix, starts, n_chunks, n_keys, a.groups, (blockIdx.x - 1) * blockDim.x + threadIdx.x, a.g_end0);
 }
 
 // Second sweep over one chunk: every listed page goes to its final position =
@@ -964,6 +967,7 @@ __global__ __launch_bounds__(1024) void k_cut_offsets(CutArgs a, const uint32_t 
 //   chunk + rank inside the wavefront's slice.
 struct EmitArgs {
     const uint32_t *page_table, *nu, *matrix, *offsets;
+    const uint32_t *counts;           // the chunks' page counts per key, or null when only their start positions survive
     const PlanHeader *hdr;
     uint32_t *fetch_pages, *evict_pages, *evict_frames;
 };
@@ -1001,10 +1005,17 @@ __device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg
     uint32_t *hist = lds + wave * n_keys;
     uint16_t *stage = reinterpret_cast<uint16_t *>(lds + (((size_t)(waves + 1) * n_keys + 3) & ~(size_t)3)) + wave * (kMaxSteps * kWave);
     const uint32_t *row = a.matrix + (size_t)chunk * n_keys;
+    // Most chunks of a large table hold no page that ends up in a list (a plan moves a few per cent of the pages):
+    // the chunk's counts tell, before any page is looked at, whether some key with room left in its list occurs here.
+    const uint32_t *cnt_row = a.counts ? a.counts + (size_t)chunk * n_keys : nullptr;
+    bool live = cnt_row == nullptr;
     for (uint32_t k = threadIdx.x; k < n_keys; k += blockDim.x) {
         const uint32_t off = a.offsets[k];
-        base[k] = (off == kSkip) ? kSkip : off + row[k];
+        const uint32_t at = (off == kSkip) ? kSkip : off + row[k];
+        base[k] = at;
+        if (cnt_row != nullptr && at < (k < K ? n_fetch : n_evict) && cnt_row[k] != 0) live = true;
     }
+    if (!__syncthreads_or(live)) return;
     for (uint32_t round = 0; round < sg.rounds; ++round) {
         if (round) raw = request_slice(round);
         for (uint32_t i = threadIdx.x; i < waves * n_keys; i += blockDim.x) lds[i] = 0;
@@ -1187,8 +1198,10 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         const bool stage = records && ((uint64_t)g.G * c->max_rules * a.n_split > c->stage_threshold || c->has_list_rule);
         a.cmds = stage ? c->cmd_dev : nullptr;
         const bool copy_ranges = g.n_ranges && !g.single;
+        // prepared id lists and painted ranges together need no record on the device: only the two small tables travel
+        const uint32_t n_records = (g.painted && g.list_prepared) ? 0u : g.G;
         if (stage)
-            k_stage<<<(g.G * 8 + 255) / 256, 256, 0, st>>>(c->cmd_ptrs_dev, g.G, c->cmd_dev, c->list_bucket_fill,
+            k_stage<<<(std::max<uint32_t>(std::max(n_records * 8, g.n_ranges + g.n_list_sources), 1u) + 255) / 256, 256, 0, st>>>(c->cmd_ptrs_dev, n_records, c->cmd_dev, c->list_bucket_fill,
                                                            g.list_binned ? g.n_buckets * 8 : 0, c->ranges_host_dev,
                                                            c->ranges_dev, copy_ranges ? g.n_ranges : 0,
                                                            c->list_src_dev, c->list_src_stage,
@@ -1240,6 +1253,7 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     ca.in_place = few_rows ? 1u : 0u;
     EmitArgs ea;
     ea.page_table = c->page_table; ea.nu = c->nu; ea.matrix = few_rows ? c->matrix : c->matrix + c->matrix_cap;   // chunk start positions
+    ea.counts = few_rows ? nullptr : c->matrix;
     ea.offsets = c->offsets; ea.hdr = c->hdr_dev;
     ea.fetch_pages = c->fetch_pages; ea.evict_pages = c->evict_pages; ea.evict_frames = c->evict_frames;
     const size_t cut_lds = (size_t)(g.n_keys + g.G + 1) * 4, emit_lds = emit_lds_words(g.waves, g.n_keys) * 4;
