@@ -556,6 +556,8 @@ struct SweepGeom {
     const PageRange *ranges;
     uint32_t n_ranges;        // 0: nothing to paint
     uint32_t use_nu;          // 0: nu[] holds nothing for this plan and is not read
+    const uint32_t *bucket_mark;   // non-null: nu[] holds something of this plan only in buckets marked here (all its
+                                   // id lists came through prepared pieces); the sweep skips nu[] elsewhere
     const uint32_t *slot;     // page -> backing slot (or null): a wanted page without one is an error
     uint32_t *flags;
     uint16_t *key16;          // [V] class key of every page, written by the first sweep for the second
@@ -572,7 +574,8 @@ constexpr uint16_t kNoKey16 = 0xffff;                  // keys are below 2 * (MS
 // ------------------------------------------------------------------------------------------
 // Where the painted tile starts in the first sweep's LDS: behind the histogram, on a 16-byte boundary.
 __host__ __device__ inline uint32_t count_paint_offset(uint32_t n_keys) { return (n_keys + 3u) & ~3u; }
-constexpr uint32_t kPaintQueue = kWave * kMaxWaves;       // one slot per thread and batch
+constexpr uint32_t kPaintQueue = 64;                      // partial ranges queued per batch; a tile meets a handful (LDS decides how
+                                                          // many sweep workgroups a compute unit holds)
 constexpr uint32_t kPaintSerial = 32;                     // ranges up to this many pages are painted by one thread
 
 struct PaintLds {
@@ -595,12 +598,16 @@ __device__ void paint_tile(const SweepGeom &sg, uint64_t t0, uint64_t t1, uint32
                     atomicMin(&q.floor, R.g);
                 } else {
                     const uint32_t at = atomicAdd(&q.n_queued, 1u);
-                    q.lo[at] = (uint32_t)(lo - t0); q.hi[at] = (uint32_t)(hi - t0); q.g[at] = R.g;
+                    if (at < kPaintQueue) {
+                        q.lo[at] = (uint32_t)(lo - t0); q.hi[at] = (uint32_t)(hi - t0); q.g[at] = R.g;
+                    } else {                                  // queue full (many small ranges in one tile): paint it here
+                        for (uint32_t i = (uint32_t)(lo - t0); i < (uint32_t)(hi - t0); ++i) atomicMin(&paint[i], R.g);
+                    }
                 }
             }
         }
         __syncthreads();
-        const uint32_t nq = q.n_queued;
+        const uint32_t nq = min(q.n_queued, kPaintQueue);
         for (uint32_t w = 0; w < nq; ++w) {
             const uint32_t lo = q.lo[w], hi = q.hi[w];
             if (hi - lo > kPaintSerial)
@@ -702,6 +709,14 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
     for (uint32_t round = 0; round < sg.rounds; ++round) {
         const uint64_t tile_begin = p_begin + round * tile_pages;
         if (sg.n_ranges) paint_tile(sg, tile_begin, min(p_end, tile_begin + tile_pages), paint, s_paint);
+        // does any id list of this plan reach into this tile?  (the same answer for every thread)
+        bool tile_nu = sg.use_nu != 0;
+        if (tile_nu && sg.bucket_mark != nullptr && tile_begin < p_end) {
+            uint32_t any = 0;
+            const uint64_t last = min(p_end, tile_begin + tile_pages) - 1;
+            for (uint64_t bk = tile_begin >> kBucketShift; bk <= (last >> kBucketShift); ++bk) any |= sg.bucket_mark[bk];
+            tile_nu = any != 0;
+        }
         const uint64_t wave_begin = tile_begin + (uint64_t)wave * sg.steps * kWave;
         for (uint32_t s0 = 0; s0 < sg.steps; s0 += kCountBatch) {
             const uint32_t batch_pages = min((uint32_t)kCountBatch, sg.steps - s0) * kWave;
@@ -712,7 +727,7 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
             if (live) {
                 const uint4 *src = reinterpret_cast<const uint4 *>(page_table + first);
                 fr = Eight{src[0], src[1]};
-                if (sg.use_nu) { const uint4 *e = reinterpret_cast<const uint4 *>(nu + first); enc = Eight{e[0], e[1]}; }
+                if (tile_nu) { const uint4 *e = reinterpret_cast<const uint4 *>(nu + first); enc = Eight{e[0], e[1]}; }
                 if (sg.n_ranges) { const uint4 *q = reinterpret_cast<const uint4 *>(paint + (first - tile_begin)); pt = Eight{q[0], q[1]}; }
             }
             uint32_t key[kCountBatch];
@@ -1237,7 +1252,9 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     SweepGeom sg;
     sg.V = c->V; sg.chunk_pages = g.chunk_pages; sg.steps = g.steps; sg.rounds = g.rounds; sg.G = g.G;
     sg.epoch = c->epoch;
-    sg.n_ranges = g.n_ranges; sg.use_nu = g.use_nu ? 1u : 0u; sg.slot = c->slot; sg.flags = c->flags; sg.key16 = c->key16;
+    sg.n_ranges = g.n_ranges; sg.use_nu = g.use_nu ? 1u : 0u;
+    sg.bucket_mark = (g.painted && g.list_prepared) ? c->bucket_mark : nullptr;   // nothing but prepared lists wrote nu[] for this plan
+    sg.slot = c->slot; sg.flags = c->flags; sg.key16 = c->key16;
     // one workgroup reads the range list where the host wrote it; many read a device copy
     sg.ranges = g.single ? c->ranges_host_dev : c->ranges_dev;
     if (prof) CK(hipEventRecord(c->ev[1], st));
