@@ -61,6 +61,18 @@ def test_many_commands_in_one_timeline(oracle_mod):
     assert lockstep(oracle_mod, trace, with_bytes=True, horizon="full", max_plans=4) == 4
 
 
+@pytest.mark.parametrize("n_pages,force_multi", [(500, True), (20000, False)])
+def test_many_commands_through_the_multi_kernel_cut(oracle_mod, monkeypatch, n_pages, force_multi):
+    """G = 3000 classes through the stand-alone cut (few chunks) and through the cut fused with the column
+    prefixes (79 chunks): a wavefront's scan then walks 47 classes per lane."""
+    if force_multi:
+        monkeypatch.setenv("MSCHED_FORCE_MULTI_KERNEL", "1")
+    rng = np.random.default_rng(12)
+    cmds = [[[int(rng.integers(0, n_pages))] for _ in range(3000)]]
+    trace = explicit_trace(cmds, n_pages, 64, timeslice=100, page_shift=6)
+    assert lockstep(oracle_mod, trace, with_bytes=True, horizon="full", max_plans=3) == 3
+
+
 def test_next_use_epoch_wraps_cleanly(oracle_mod, monkeypatch):
     # the next-use array is never cleared between plans: entries carry a plan epoch that wraps
     # after 2^20 - 1 plans; start 5 plans before the wrap and run across it
