@@ -150,6 +150,10 @@ int msched_plan(msched_ctx *ctx, const msched_timeline_entry *tl, uint32_t n_ent
  * host_store[slot(evict[i])] <- pool[evict_frames[i]], pool[fetch_frames[i]] <- host_store[slot(fetch[i])],
  * then the page table and frame owners are updated.  Asynchronous on the context's stream; a plan
  * can be carried out once.
+ * Behind the migration, on the same stream, the call may also bin the id lists of commands queued beyond the
+ * planned ones (preparation for the next plans, hidden behind the host-link transfer): those lists are read
+ * then, which is why they must be valid from msched_launch_enqueue on.  A failure of that preparation never
+ * fails the call (it switches the look-ahead off).
  */
 int msched_migrate(msched_ctx *ctx, const msched_plan_t *plan);
 
