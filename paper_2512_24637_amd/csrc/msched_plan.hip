@@ -588,9 +588,12 @@ __device__ void paint_tile(const SweepGeom &sg, uint64_t t0, uint64_t t1, uint32
     for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) paint[i] = sg.G;
     if (threadIdx.x == 0) { q.n_queued = 0; q.floor = sg.G; }
     __syncthreads();
-    for (uint32_t r0 = 0; r0 < sg.n_ranges; r0 += blockDim.x) {
-        const uint32_t r = r0 + threadIdx.x;
-        if (r < sg.n_ranges) {
+    constexpr uint32_t kPerThread = 4;                        // ranges a thread tests per pass (a pass costs three barriers)
+    for (uint32_t r0 = 0; r0 < sg.n_ranges; r0 += blockDim.x * kPerThread) {
+#pragma unroll
+        for (uint32_t j = 0; j < kPerThread; ++j) {
+            const uint32_t r = r0 + j * blockDim.x + threadIdx.x;
+            if (r >= sg.n_ranges) continue;
             const PageRange R = sg.ranges[r];
             const uint64_t lo = max((uint64_t)R.lo, t0), hi = min((uint64_t)R.hi, t1);
             if (lo < hi) {
