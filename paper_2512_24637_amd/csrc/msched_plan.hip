@@ -987,7 +987,7 @@ struct EmitArgs {
     const uint32_t *page_table, *nu, *matrix, *offsets;
     const uint32_t *counts;           // the chunks' page counts per key, or null when only their start positions survive
     const PlanHeader *hdr;
-    uint32_t *fetch_pages, *evict_pages, *evict_frames;
+    uint32_t *fetch_pages, *evict_pages, *evict_frames, *fetch_frames;
 };
 
 // LDS words emit_body needs: a histogram per wavefront, the running positions, and a 2 KiB staging line per wavefront.
@@ -1018,6 +1018,7 @@ __device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg
     };
     Raw raw = request_slice(0);
     const uint32_t n_fetch = a.hdr->n_fetch, n_evict = a.hdr->n_evict;
+    const uint32_t n_free_used = a.hdr->n_free_used, first_free = a.hdr->first_free;
     if (n_fetch == 0) return;                             // same for every thread of the block
     uint32_t *base = lds + waves * n_keys;               // [n_keys] running output position per key
     uint32_t *hist = lds + wave * n_keys;
@@ -1072,11 +1073,20 @@ __device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg
                 const uint32_t k = key[s] & 0xFFFFu;
                 const uint32_t where = hist[k] + (key[s] >> 16);
                 const uint32_t p = (uint32_t)(wave_begin + (uint64_t)s * kWave + lane);
+                // Frames (Sec. 6.3: target i is populated into the space reclaimed from victim i): the first fetches
+                // take the free frames, lowest first - frames are handed out in ascending order and only ever reused
+                // through an eviction, so the free ones are [first_free, F) - and fetch n_free_used + j takes the
+                // frame of victim j, which the workgroup that emits that victim writes into both lists.
                 if (k < K) {
-                    if (where < n_fetch) a.fetch_pages[where] = p;
+                    if (where < n_fetch) {
+                        a.fetch_pages[where] = p;
+                        if (where < n_free_used) a.fetch_frames[where] = first_free + where;
+                    }
                 } else if (where < n_evict) {
+                    const uint32_t frame = a.page_table[p];
                     a.evict_pages[where] = p;
-                    a.evict_frames[where] = a.page_table[p];
+                    a.evict_frames[where] = frame;
+                    a.fetch_frames[n_free_used + where] = frame;
                 }
             }
         }
@@ -1084,41 +1094,23 @@ __device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg
     }
 }
 
-__global__ __launch_bounds__(kWave * kMaxWaves, 6) void k_emit(EmitArgs a, SweepGeom sg) {
+__global__ __launch_bounds__(kWave * kMaxWaves, 6) void k_emit(EmitArgs a, SweepGeom sg, uint32_t *__restrict__ partial,
+                                                                uint32_t n_partial) {
     extern __shared__ uint32_t lds[];
+    // the row-group sums have been read by the cut: the next plan's first sweep adds into them again
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n_partial; i += gridDim.x * blockDim.x) partial[i] = 0;
     emit_body(a, sg, chunk_of_block(blockIdx.x, gridDim.x), lds);
-}
-
-// Frame of every fetched page: free frames lowest first, then the victims' frames in eviction order
-// (Sec. 6.3: target i is populated into the space reclaimed from victim i).  Frames are handed out
-// in ascending order and only ever reused through an eviction, so the free ones are [first_free, F).
-__device__ __forceinline__ void frames_body(const PlanHeader *hdr, const uint32_t *evict_frames,
-                                            uint32_t *fetch_frames, uint32_t t0, uint32_t nthreads) {
-    const uint32_t n = hdr->n_fetch, nfu = hdr->n_free_used, first = hdr->first_free;
-    for (uint32_t i = t0; i < n; i += nthreads) fetch_frames[i] = (i < nfu) ? first + i : evict_frames[i - nfu];
-}
-
-__global__ __launch_bounds__(256) void k_frames(const PlanHeader *__restrict__ hdr,
-                                                const uint32_t *__restrict__ evict_frames,
-                                                uint32_t *__restrict__ fetch_frames, uint32_t *__restrict__ partial,
-                                                uint32_t n_partial) {
-    const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x, nt = gridDim.x * blockDim.x;
-    for (uint32_t i = t; i < n_partial; i += nt) partial[i] = 0;    // the next plan's first sweep adds into these
-    frames_body(hdr, evict_frames, fetch_frames, t, nt);
 }
 
 // Page tables small enough for one workgroup: count, cut, emit and frame assignment in one launch
 // (planning such a table is bound by launch latency, not by bandwidth).
-__global__ __launch_bounds__(kWave * kMaxWaves) void k_tail(SweepGeom sg, CutArgs ca, EmitArgs ea,
-                                                             uint32_t *__restrict__ fetch_frames) {
+__global__ __launch_bounds__(kWave * kMaxWaves) void k_tail(SweepGeom sg, CutArgs ca, EmitArgs ea) {
     extern __shared__ uint32_t lds[];
     count_body(ea.page_table, ea.nu, sg, 0, lds, ca.groups, nullptr);
     __syncthreads();
     cut_body(ca, lds);
     __syncthreads();
     emit_body(ea, sg, 0, lds);
-    __syncthreads();
-    frames_body(ea.hdr, ea.evict_frames, fetch_frames, threadIdx.x, blockDim.x);
 }
 
 __global__ __launch_bounds__(256) void k_zero(uint32_t *dst, uint64_t n) {
@@ -1276,9 +1268,10 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     ea.counts = few_rows ? nullptr : c->matrix;
     ea.offsets = c->offsets; ea.hdr = c->hdr_dev;
     ea.fetch_pages = c->fetch_pages; ea.evict_pages = c->evict_pages; ea.evict_frames = c->evict_frames;
+    ea.fetch_frames = c->fetch_frames;
     const size_t cut_lds = (size_t)(g.n_keys + g.G + 1) * 4, emit_lds = emit_lds_words(g.waves, g.n_keys) * 4;
     if (g.single) {
-        k_tail<<<1, threads, std::max(cut_lds, emit_lds + paint_lds + 16), st>>>(sg, ca, ea, c->fetch_frames);
+        k_tail<<<1, threads, std::max(cut_lds, emit_lds + paint_lds + 16), st>>>(sg, ca, ea);
         if (c->profiling) CK(hipEventRecord(c->ev[4], st));
         return hipGetLastError();
     }
@@ -1293,10 +1286,7 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         k_cut_offsets<<<1 + (items + cut_threads - 1) / cut_threads, cut_threads, cut_lds, st>>>(ca, c->matrix, c->matrix + c->matrix_cap, g.n_chunks, g.n_keys);
     }
     if (prof) CK(hipEventRecord(c->ev[3], st));
-    k_emit<<<g.n_chunks, threads, emit_lds, st>>>(ea, sg);
-    const uint32_t fblocks = (uint32_t)std::min<uint64_t>(2048, ((uint64_t)c->F + 255) / 256);
-    k_frames<<<fblocks, 256, 0, st>>>(c->hdr_dev, c->evict_frames, c->fetch_frames, c->partial,
-                                      few_rows ? 0 : kRowGroups * g.n_keys);
+    k_emit<<<g.n_chunks, threads, emit_lds, st>>>(ea, sg, c->partial, few_rows ? 0 : kRowGroups * g.n_keys);
     if (c->profiling) CK(hipEventRecord(c->ev[4], st));
     return hipGetLastError();
 }
