@@ -68,3 +68,14 @@ def test_create_refuses_bad_configurations_before_touching_the_gpu():
     assert lib.msched_plan(None, None, 0, None) == -1
     assert lib.msched_migrate(None, None) == -1
     assert lib.msched_pagetable_query(None, None, 0, None) == -1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """Every box has one GPU: the benchmark says so instead of starting ranks."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], cwd=root,
+                       stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stdout or "1 GPU" in r.stdout or "single" in r.stdout.lower()
