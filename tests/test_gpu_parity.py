@@ -264,10 +264,10 @@ def _random_rule_trace(rng, page_shift, V, n_frames, n_tasks, n_cmds, with_lists
                  timeslice=4, kernels=kernels, tasks=tasks, ids_pool=ids_pool, n_slots=V)
 
 
-@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+@pytest.mark.parametrize("seed", [0, 1, 2, 3, 4, 5])
 def test_random_templates_of_every_kind(oracle_mod, seed):
     rng = np.random.default_rng(100 + seed)
-    V = int(rng.choice([700, 3000, 9000]))
+    V = int(rng.choice([700, 3000, 9000])) if seed < 4 else {4: 20000, 5: 70000}[seed]   # 5: many chunks, fused cut
     trace = _random_rule_trace(rng, page_shift=8, V=V, n_frames=V // 3 + 200, n_tasks=3, n_cmds=30,
                                with_lists=bool(seed % 2))
     assert lockstep(oracle_mod, trace, with_bytes=True, bytes_every=5) >= 10
