@@ -95,7 +95,7 @@ typedef struct {
     uint32_t g_end0;              /* commands entry 0 holds; covered_launches < g_end0 means the slice was cut */
     uint32_t n_commands;          /* G: commands in the flattened timeline */
     uint32_t reserved;
-    const uint32_t *evict_pages;  /* DEVICE, context-owned, valid until the next msched_plan */
+    const uint32_t *evict_pages;  /* DEVICE, context-owned, valid until the next msched_plan; complete in stream order */
     const uint32_t *evict_frames; /* DEVICE */
     const uint32_t *fetch_pages;  /* DEVICE */
     const uint32_t *fetch_frames; /* DEVICE */
@@ -140,7 +140,10 @@ int msched_launch_retire(msched_ctx *ctx, uint32_t task, uint32_t n_launches);
  *   evict  = first max(0, n_fetch - free frames) resident pages that are not wanted, ordered by
  *            (first use descending with never-used first, page id)
  * Fetched page i takes the i-th lowest free frame, or the frame of evict[i - n_free_used].
- * Does not change the page table.  Blocks until the counts in *out are known.
+ * Does not change the page table.  Blocks until the counts in *out are known - which is before the four
+ * device lists are complete: the kernels that fill them may still be running on the context's stream when
+ * the call returns.  Work on that stream (msched_migrate) sees them complete; so does any caller after
+ * msched_plan_copy_lists, msched_state_copy or a synchronisation of the stream.
  */
 int msched_plan(msched_ctx *ctx, const msched_timeline_entry *tl, uint32_t n_entries, msched_plan_t *out);
 

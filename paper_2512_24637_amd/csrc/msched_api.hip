@@ -1,6 +1,7 @@
 // C-ABI entry points of libmsched: context, template registry, per-task command queues,
 // timeline flattening, and the calls that drive the planning and migration kernels.
 #include <algorithm>
+#include <atomic>
 #include <chrono>
 #include <cstdlib>
 #include <cstring>
@@ -224,6 +225,7 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     c->list_prepared = (uint32_t)env_u32("MSCHED_LIST_PREPARED", 0, 1, 1);
     c->list_cache_bytes = (uint64_t)env_u32("MSCHED_LIST_CACHE_MB", 1, 65536, 128) << 20;
     c->list_ahead = (uint32_t)env_u32("MSCHED_LIST_AHEAD", 0, 65536, 128);
+    c->plan_spin = (uint32_t)env_u32("MSCHED_PLAN_SPIN", 0, 1, 1);
     c->force_multi_kernel = env_u32("MSCHED_FORCE_MULTI_KERNEL", 0, 1, 0) != 0;
     c->list_binned_min_ids = (uint64_t)env_u32("MSCHED_LIST_BINNED_MIN_IDS", 0, 1 << 30, 262144);
     c->list_b0 = (uint32_t)env_u32("MSCHED_LIST_B0", 0, 4096, 4);
@@ -255,6 +257,7 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     }
 #undef ALLOC
     if (rc == MSCHED_OK && (e = hipHostMalloc((void **)&c->hdr_host, sizeof(PlanHeader), hipHostMallocDefault)) != hipSuccess) fail(e);
+    if (rc == MSCHED_OK) memset(c->hdr_host, 0, sizeof(PlanHeader));            // no stamp yet
     if (rc == MSCHED_OK && (e = hipHostMalloc((void **)&c->cmd_ptrs_host,
                                               sizeof(void *) * (MSCHED_MAX_TIMELINE_COMMANDS + 1), hipHostMallocDefault)) != hipSuccess) fail(e);
     if (rc == MSCHED_OK && (e = hipHostGetDevicePointer((void **)&c->cmd_ptrs_dev, (void *)c->cmd_ptrs_host, 0)) != hipSuccess) fail(e);
@@ -605,17 +608,29 @@ int plan_body(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entries
             c->matrix_cap = need;
         }
         const clk::time_point t_prep = clk::now();
+        if (++c->hdr_seq == 0) c->hdr_seq = 1;
         HIP_TRY(c, launch_plan(c, g));
         const clk::time_point t_launch = clk::now();
-        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        // The counts are all the caller waits for: the cut stamps the pinned header once they (and need[]) are
+        // written, while the second sweep is still filling the lists, which only stream-ordered work reads.
+        const volatile uint32_t *stamp = &c->hdr_host->seq;
+        bool landed = false;
+        if (c->plan_spin) {
+            for (uint32_t spins = 0; !(landed = *stamp == c->hdr_seq); ++spins)
+                if ((spins & 0xfff) == 0xfff && hipStreamQuery(c->stream) != hipErrorNotReady) break;   // finished or failed
+            (void)hipGetLastError();                    // hipErrorNotReady from the queries is not an error
+        }
+        if (!landed) {
+            HIP_TRY(c, hipStreamSynchronize(c->stream));
+            if (*stamp != c->hdr_seq) { c->last_hip = g_last_hip = (int)hipErrorUnknown; return MSCHED_E_HIP; }
+        }
+        std::atomic_thread_fence(std::memory_order_acquire);
         h = *c->hdr_host;
         const clk::time_point t_done = clk::now();
         c->phase_ms[MSCHED_HOST_PREP] = std::chrono::duration<float, std::milli>(t_prep - t_start).count();
         c->phase_ms[MSCHED_HOST_LAUNCH] = std::chrono::duration<float, std::milli>(t_launch - t_prep).count();
         c->phase_ms[MSCHED_HOST_WAIT] = std::chrono::duration<float, std::milli>(t_done - t_launch).count();
-        if (c->profiling) HIP_TRY(c, hipEventElapsedTime(&c->phase_ms[MSCHED_PHASE_PLAN], c->ev[0], c->ev[4]));
-        if (c->profiling >= 2)
-            for (int i = 0; i < 4; ++i) HIP_TRY(c, hipEventElapsedTime(&c->phase_ms[i], c->ev[i], c->ev[i + 1]));
+        c->plan_timing_pending = c->profiling != 0;     // read from the events when somebody asks (that waits for the stream)
         if (h.status & kStatRange) return MSCHED_E_RANGE;
         if (h.status & kStatWset) return MSCHED_E_WSET_TOO_LARGE;
     }
@@ -810,6 +825,13 @@ int msched_set_profiling(msched_ctx *c, int level) {
 
 int msched_get_phase_ms(msched_ctx *c, float *ms) {
     if (!c || !ms) return MSCHED_E_INVAL;
+    if (c->plan_timing_pending) {
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        HIP_TRY(c, hipEventElapsedTime(&c->phase_ms[MSCHED_PHASE_PLAN], c->ev[0], c->ev[4]));
+        if (c->profiling >= 2)
+            for (int i = 0; i < 4; ++i) HIP_TRY(c, hipEventElapsedTime(&c->phase_ms[i], c->ev[i], c->ev[i + 1]));
+        c->plan_timing_pending = false;
+    }
     if (c->profiling && c->migrate_timed) {
         HIP_TRY(c, hipStreamSynchronize(c->stream));
         HIP_TRY(c, hipEventElapsedTime(&c->phase_ms[MSCHED_PHASE_MIGRATE], c->ev[5], c->ev[6]));

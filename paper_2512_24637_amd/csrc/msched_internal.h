@@ -46,7 +46,8 @@ struct DevKernel {
 // Written by the cut kernel; read by later kernels (device copy) and by the host (pinned copy).
 struct PlanHeader {
     uint32_t n_fetch, n_evict, n_free_used, g_cut;
-    uint32_t n_resident, status, first_free, pad;
+    uint32_t n_resident, status, first_free;
+    uint32_t seq;       // host copy only: written last, after everything else of the plan that the host reads has been written
 };
 
 struct TaskQueue {
@@ -170,6 +171,9 @@ struct msched_ctx {
     uint32_t *progress_host = nullptr;          // pinned: where msched_progress reads `landed` into
     hipStream_t poll_stream = nullptr;          // msched_progress works here, beside the migration
     uint32_t early_tag = 0;                     // nonzero tag of the latest early migration
+    uint32_t hdr_seq = 0;                       // stamp of the header the host is waiting for (never 0)
+    uint32_t plan_spin = 1;                     // msched_plan returns when the counts have landed, not when the lists are complete
+    bool plan_timing_pending = false;           // device times of the last plan have not been read from their events yet
     bool early_ready = false;                   // every piece of the early-execution bookkeeping exists
     int plan_early = 0;                         // the latest plan computed need[] and reset landed
     int profiling = 0;

@@ -825,6 +825,7 @@ struct CutArgs {
     uint32_t *groups; uint32_t n_groups, G, g_end0, F;
     uint32_t *flags, *offsets;
     PlanHeader *hdr_dev, *hdr_host;
+    uint32_t seq;                      // stamp for the host copy of the header
     uint32_t *need_host, *landed;      // early execution (both null when it is off)
     uint32_t in_place;                 // replace `groups` by their exclusive prefix over the rows (they are the matrix itself)
 };
@@ -897,6 +898,7 @@ __device__ void cut_body(const CutArgs &a, uint32_t *lds) {
                                                          // early execution: command c may start once the fetches of classes 0..c have landed
                                                          if (a.need_host && c < g_cut) a.need_host[c] = before + v;
                                                      });
+        if (a.need_host) __threadfence_system();           // need[] is in host memory: ahead of the header's stamp
         if (tid == 0) s_fetch = n_fetch;
     }
     if (wave == last_wave) {
@@ -918,9 +920,13 @@ __device__ void cut_body(const CutArgs &a, uint32_t *lds) {
         h.n_fetch = n_fetch;
         h.n_free_used = min(n_free, n_fetch);
         h.n_evict = n_fetch - h.n_free_used;
-        h.g_cut = g_cut; h.n_resident = n_res; h.status = status; h.first_free = n_res; h.pad = 0;
+        h.g_cut = g_cut; h.n_resident = n_res; h.status = status; h.first_free = n_res; h.seq = 0;
         *a.hdr_dev = h;
+        // The host waits for the stamp, not for the end of the kernel: the counts (and need[]) go first, the stamp
+        // after a system-scope fence, so that whoever sees the stamp sees them.
         *a.hdr_host = h;
+        __threadfence_system();
+        __hip_atomic_store(&a.hdr_host->seq, a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
     }
 }
 
@@ -1260,7 +1266,7 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     CutArgs ca;
     ca.groups = few_rows ? c->matrix : c->partial; ca.n_groups = few_rows ? g.n_chunks : kRowGroups;
     ca.G = g.G; ca.g_end0 = g.g_end0; ca.F = c->F; ca.flags = c->flags; ca.offsets = c->offsets;
-    ca.hdr_dev = c->hdr_dev; ca.hdr_host = c->hdr_host;
+    ca.hdr_dev = c->hdr_dev; ca.hdr_host = c->hdr_host; ca.seq = c->hdr_seq;
     ca.need_host = c->early ? c->need_host : nullptr; ca.landed = c->early ? c->landed : nullptr;
     ca.in_place = few_rows ? 1u : 0u;
     EmitArgs ea;

@@ -293,13 +293,14 @@ def test_allocation_granularity_ablation_runs_bit_exact(oracle_mod):
 
 @pytest.mark.parametrize("env", [{"MSCHED_PAINT": "0"}, {"MSCHED_LIST_PREPARED": "0"},
                                  {"MSCHED_PAINT": "0", "MSCHED_LIST_PREPARED": "0"},
-                                 {"MSCHED_LIST_CACHE_MB": "1"}, {"MSCHED_LIST_AHEAD": "0"}],
-                         ids=["scatter-ranges", "bin-per-plan", "both-earlier-paths", "one-megabyte-ring", "no-look-ahead"])
+                                 {"MSCHED_LIST_CACHE_MB": "1"}, {"MSCHED_LIST_AHEAD": "0"}, {"MSCHED_PLAN_SPIN": "0"}],
+                         ids=["scatter-ranges", "bin-per-plan", "both-earlier-paths", "one-megabyte-ring", "no-look-ahead",
+                              "plan-waits-for-the-stream"])
 def test_earlier_planning_paths_stay_bit_exact(oracle_mod, monkeypatch, env):
     """Range pages scattered into the next-use array instead of painted, id lists binned from scratch in every
     plan instead of prepared once per command, a ring too small for the prepared lists (which makes plans fall
-    back to binning from scratch part of the time), and lists prepared by the plan that first sees them instead of
-    behind the previous migration."""
+    back to binning from scratch part of the time), lists prepared by the plan that first sees them instead of
+    behind the previous migration, and a plan call that waits for the whole stream instead of the stamped counts."""
     monkeypatch.setenv("MSCHED_LIST_BINNED_MIN_IDS", "0")
     for k, v in env.items():
         monkeypatch.setenv(k, v)
