@@ -74,8 +74,6 @@ int validate_launch(const msched_ctx *c, const DevKernel &k, const uint64_t *arg
 // fixed-size, Sec. 5.2), which makes most rules of a timeline repeats.  The test is exact: regions are
 // compared as full tuples (page range for fixed/linear rules, the four strided parameters, or the
 // id-list address and length), never by hash alone.
-struct RegionSig { uint64_t a, b, c, d; };
-
 inline bool region_signature(const msched_ctx *c, const msched_rule &q, const CmdRec &r, RegionSig &sig, bool &empty) {
     empty = false;
     if (q.kind == MSCHED_RULE_LIST) {
@@ -355,14 +353,29 @@ int msched_launch_enqueue(msched_ctx *c, uint32_t task, uint32_t kernel_id, cons
         HIP_TRY(c, hipHostMalloc((void **)&nr, ncap * sizeof(CmdRec), hipHostMallocDefault));
         const hipError_t e = hipHostGetDevicePointer((void **)&nd, nr, 0);
         if (e != hipSuccess) { (void)hipHostFree(nr); HIP_TRY(c, e); }
-        if (live) memcpy(nr, t.recs + (t.cursor - t.base), live * sizeof(CmdRec));
+        std::vector<RegionSig> nsig;
+        const int rc_sig = guarded([&]() -> int { nsig.resize(ncap * MSCHED_MAX_RULES); return MSCHED_OK; });
+        if (rc_sig) { (void)hipHostFree(nr); return rc_sig; }
+        if (live) {
+            memcpy(nr, t.recs + (t.cursor - t.base), live * sizeof(CmdRec));
+            memcpy(nsig.data(), t.sig.data() + (t.cursor - t.base) * MSCHED_MAX_RULES, live * MSCHED_MAX_RULES * sizeof(RegionSig));
+        }
         if (t.recs) (void)hipHostFree(t.recs);
         t.recs = nr; t.recs_dev = nd; t.cap = ncap; t.base = t.cursor;
+        t.sig.swap(nsig);
     }
     CmdRec &r = t.recs[t.n - t.base];
     memset(&r, 0, sizeof r);
     r.kernel = kernel_id; r.n_args = n_args; r.latency = latency_ticks; r.n_ids = n_ids; r.ids = id_list;
     for (uint32_t i = 0; i < n_args; ++i) r.args[i] = args[i];
+    // the regions its rules describe never change: every plan that looks at the command finds them ready
+    const DevKernel &k = c->kernels[kernel_id];
+    RegionSig *sig = t.sig.data() + (t.n - t.base) * MSCHED_MAX_RULES;
+    for (uint32_t q = 0; q < k.n_rules; ++q) {
+        bool empty;
+        region_signature(c, k.rules[q], r, sig[q], empty);
+        if (empty) sig[q] = RegionSig{~0ull, ~0ull, 0, 0};
+    }
     t.n++;
     return MSCHED_OK;
 }
@@ -517,11 +530,12 @@ int plan_body(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entries
         for (uint32_t g = 0; g < G; ++g) {
             const CmdRec &rec = *c->plan_recs[g];
             const DevKernel &k = c->kernels[rec.kernel];
+            const TaskQueue &t = c->tasks[c->plan_task[g]];
+            const RegionSig *sigs = t.sig.data() + (size_t)(&rec - t.recs) * MSCHED_MAX_RULES;   // computed at enqueue
             uint64_t skip = 0;
             for (uint32_t r = 0; r < k.n_rules; ++r) {
-                RegionSig sig;
-                bool empty;
-                region_signature(c, k.rules[r], rec, sig, empty);
+                const RegionSig &sig = sigs[r];
+                const bool empty = sig.a == ~0ull && sig.b == ~0ull;
                 if (empty || seen_before(c, sig, cap - 1)) skip |= 1ull << r;
             }
             c->cmd_ptrs_host[g] = reinterpret_cast<const CmdRec *>(

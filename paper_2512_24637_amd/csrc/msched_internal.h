@@ -50,8 +50,13 @@ struct PlanHeader {
     uint32_t seq;       // host copy only: written last, after everything else of the plan that the host reads has been written
 };
 
+// What a rule of a queued command describes, as an exact tuple (page range of a fixed / linear rule; the four
+// strided parameters; address and length of an id list).  a == b == ~0: the rule describes nothing.
+struct RegionSig { uint64_t a, b, c, d; };
+
 struct TaskQueue {
     CmdRec *recs = nullptr;                     // pinned host memory
+    std::vector<RegionSig> sig;                 // [cap][MSCHED_MAX_RULES] the regions of recs[i]'s rules, computed once at enqueue
     CmdRec *recs_dev = nullptr;                 // same memory, device address
     size_t cap = 0;                             // records allocated
     size_t base = 0;                            // program-order index of recs[0]
