@@ -4,7 +4,7 @@ import sys
 import numpy as np
 import pytest
 
-from workloads import make_trace, Rule, RULE_LIST, RULE_LINEAR
+from workloads import make_trace, run_schedule, Rule, RULE_LIST, RULE_LINEAR
 from helpers import explicit_trace
 from gpu_common import lockstep, GpuSide, make_oracle, assert_same_plan
 
@@ -420,6 +420,53 @@ def test_a_refused_plan_leaves_nothing_behind_for_the_next_one(oracle_mod):
         assert e.value.name == "E_WSET_TOO_LARGE"
         for tl in ([(1, 2), (0, 2)], [(1, 1)]):
             assert_same_plan(o.plan(tl), g.ms.plan(tl), tl)
+    finally:
+        g.close()
+        o.close()
+
+
+class _NoReadBack:
+    """Drives the HIP path the way a scheduler would: counts from msched_plan, then msched_migrate at once - no list
+    is read back and nothing waits for the stream in between."""
+
+    def __init__(self, ms):
+        self.ms = ms
+        self.counts = []
+
+    def plan(self, timeline):
+        p = self.ms.plan(timeline)
+        self.counts.append((p.n_fetch, p.n_evict, p.n_free_used, p.g_cut, p.covered_launches))
+        return p
+
+    def migrate(self):
+        self.ms.migrate_only()
+
+    def launch_retire(self, task, n):
+        self.ms.launch_retire(task, n)
+
+
+@pytest.mark.parametrize("cfg,kw", [(1, dict(seed=3)), (5, dict(scale=64, n_launches=100)),
+                                    (4, dict(page_shift=12, layers=8, steps=16))])
+def test_migrate_straight_after_plan_without_any_wait(oracle_mod, monkeypatch, cfg, kw):
+    """msched_plan returns when the counts are known, while the kernels that fill the lists may still run; the
+    migration queued behind them must find the lists complete.  Counts of every switch, and page table, frame
+    owners, pool and host bytes at the end, against the oracle."""
+    monkeypatch.setenv("MSCHED_LIST_BINNED_MIN_IDS", "0")
+    trace = make_trace(cfg, **kw)
+    g = GpuSide(trace)
+    o = make_oracle(oracle_mod, trace, with_bytes=True)
+    try:
+        drv = _NoReadBack(g.ms)
+        n = sum(1 for _ in run_schedule(trace, drv))
+        expected = []
+        for rec in run_schedule(trace, o):
+            expected.append((rec.plan.n_fetch, rec.plan.n_evict, rec.plan.n_free_used, rec.plan.g_cut, rec.plan.covered_launches))
+        assert n == len(expected) and drv.counts == expected
+        pto, foo = o.state()
+        ptg, fog = g.ms.state()
+        assert np.array_equal(pto, ptg) and np.array_equal(foo, fog)
+        assert np.array_equal(o.pool_words, g.pool_words()), "pool bytes"
+        assert np.array_equal(o.host_words, g.host_words()), "host bytes"
     finally:
         g.close()
         o.close()
