@@ -22,7 +22,7 @@ constexpr uint32_t kNuMask = (1u << kNuShift) - 1;
 constexpr uint64_t kPtrMask = (1ull << 56) - 1; // record address without the skip mask in its top byte
 constexpr uint32_t kMaxEpoch = (1u << (32 - kNuShift)) - 1;
 static_assert(MSCHED_MAX_TIMELINE_COMMANDS < kNuMask, "g must fit the next-use encoding");
-constexpr uint32_t kRowGroups = 32;             // row groups of the chunk x class count matrix
+constexpr uint32_t kRowGroups = 16;             // row groups of the chunk x class count matrix
 
 // status bits raised by device code while planning
 constexpr uint32_t kStatRange = 1u;             // a LIST id >= V, or a touched page without backing slot
