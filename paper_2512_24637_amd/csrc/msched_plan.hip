@@ -542,6 +542,8 @@ __device__ __forceinline__ uint32_t classify(uint32_t frame, uint32_t enc, uint3
 // the block -> chunk map spreads them over the whole launch instead of leaving them for its tail.
 __device__ __forceinline__ uint32_t chunk_of_block(uint32_t block, uint32_t n_chunks) {
     constexpr uint32_t kStride = 61;                       // prime; the map is a bijection when it does not divide n
+    // (On a 1280-chunk sweep strides 3, 7, 13, 61, 257, 509 and 641 are within 1 % of each other; 31, 101 and 1021
+    // are 9 % slower: some strides line the heavy chunks up on few compute units.)
     if (n_chunks % kStride == 0) return block;
     return (uint32_t)(((uint64_t)block * kStride) % n_chunks);
 }
