@@ -224,6 +224,7 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     c->list_cache_bytes = (uint64_t)env_u32("MSCHED_LIST_CACHE_MB", 1, 65536, 128) << 20;
     c->list_ahead = (uint32_t)env_u32("MSCHED_LIST_AHEAD", 0, 65536, 128);
     c->plan_spin = (uint32_t)env_u32("MSCHED_PLAN_SPIN", 0, 1, 1);
+    c->fuse_lists = (uint32_t)env_u32("MSCHED_FUSE_LISTS", 0, 1, 1);
     c->force_multi_kernel = env_u32("MSCHED_FORCE_MULTI_KERNEL", 0, 1, 0) != 0;
     c->list_binned_min_ids = (uint64_t)env_u32("MSCHED_LIST_BINNED_MIN_IDS", 0, 1 << 30, 262144);
     c->list_b0 = (uint32_t)env_u32("MSCHED_LIST_B0", 0, 4096, 4);
@@ -429,7 +430,7 @@ int gather_list_sources(msched_ctx *c, uint32_t G, PlanGeom &g) {
     if (!c->list_src_stage) HIP_TRY(c, hipMalloc((void **)&c->list_src_stage, sizeof(ListSource) * kMaxListSources));
     if (!c->bucket_mark) {
         uint32_t *marks = nullptr;
-        const size_t bytes = 4 * (size_t)kMaxBuckets;
+        const size_t bytes = 4 * ((size_t)kMaxBuckets + kMaxChunks);     // behind the marks: the first sweep's chunk order
         HIP_TRY(c, hipMalloc((void **)&marks, bytes));
         const hipError_t e = hipMemset(marks, 0, bytes);
         if (e != hipSuccess) { (void)hipFree(marks); HIP_TRY(c, e); }

@@ -129,7 +129,7 @@ struct msched_ctx {
     msched::ListSource *list_src_dev = nullptr;    // the same memory, device address
     msched::ListPrep *list_prep_host = nullptr;    // pinned [kMaxListSources]: the pieces this plan has to prepare first
     msched::ListPrep *list_prep_dev = nullptr;
-    uint32_t *bucket_mark = nullptr;               // device [kMaxBuckets]: buckets some prepared piece has put an id in
+    uint32_t *bucket_mark = nullptr;               // device [kMaxBuckets]: buckets some prepared piece has put an id in; then [kMaxChunks] chunk order
     msched::ListSource *list_src_stage = nullptr;  // device copy of the source table (every merge workgroup reads it)
     std::vector<uint32_t> plan_task;               // task of the g-th future command
     // look-ahead preparation: id lists of queued commands are binned behind a migration, off the plan's path
@@ -177,6 +177,7 @@ struct msched_ctx {
     hipStream_t poll_stream = nullptr;          // msched_progress works here, beside the migration
     uint32_t early_tag = 0;                     // nonzero tag of the latest early migration
     uint32_t hdr_seq = 0;                       // stamp of the header the host is waiting for (never 0)
+    uint32_t fuse_lists = 1;                    // prepared id lists are merged inside the first sweep (MSCHED_FUSE_LISTS, 0 = own kernel)
     uint32_t plan_spin = 1;                     // msched_plan returns when the counts have landed, not when the lists are complete
     bool plan_timing_pending = false;           // device times of the last plan have not been read from their events yet
     bool early_ready = false;                   // every piece of the early-execution bookkeeping exists

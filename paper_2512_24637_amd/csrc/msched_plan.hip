@@ -31,17 +31,30 @@ __device__ __forceinline__ uint64_t lanes_below() { return (1ull << lane_id()) -
 // pass over the link instead of one round trip per expansion workgroup).  Short timelines skip this
 // and let the few expansion workgroups read their record through the pinned table themselves.
 // ------------------------------------------------------------------------------------------
+// When the first sweep merges the id lists itself (k_count_lists), one more workgroup rides along and writes the
+// order in which that sweep takes its chunks.
+struct ChunkOrder {
+    const uint32_t *bucket_mark;        // null: no order wanted
+    uint32_t n_buckets, n_chunks, buckets_per_chunk;
+    uint32_t *order;                    // [n_chunks] chunks that hold a bucket with ids first, then the others
+};
+__device__ void chunk_order_block(const ChunkOrder &o);
+
 __global__ __launch_bounds__(256) void k_stage(const CmdRec *const *__restrict__ cmd_ptrs, uint32_t G,
                                                 CmdRec *__restrict__ cmd_dev, uint32_t *__restrict__ bucket_fill,
                                                 uint32_t n_buckets, const PageRange *__restrict__ ranges_src,
                                                 PageRange *__restrict__ ranges_dst, uint32_t n_ranges,
                                                 const ListSource *__restrict__ list_src, ListSource *__restrict__ list_dst,
-                                                uint32_t n_list_src) {
+                                                uint32_t n_list_src, ChunkOrder co) {
+    uint32_t n_blocks = gridDim.x;
+    if (co.bucket_mark != nullptr) {                        // the last workgroup is the extra one
+        if (blockIdx.x == --n_blocks) { chunk_order_block(co); return; }
+    }
     const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
-    for (uint32_t i = t; i < n_list_src; i += gridDim.x * blockDim.x)                      // and so does the table of list pieces
+    for (uint32_t i = t; i < n_list_src; i += n_blocks * blockDim.x)                      // and so does the table of list pieces
         reinterpret_cast<uint4 *>(list_dst)[i] = reinterpret_cast<const uint4 *>(list_src)[i];
-    for (uint32_t b = t; b < n_buckets; b += gridDim.x * blockDim.x) bucket_fill[b] = 0;   // binned id lists start empty
-    for (uint32_t r = t; r < n_ranges; r += gridDim.x * blockDim.x)                        // the range list rides along
+    for (uint32_t b = t; b < n_buckets; b += n_blocks * blockDim.x) bucket_fill[b] = 0;   // binned id lists start empty
+    for (uint32_t r = t; r < n_ranges; r += n_blocks * blockDim.x)                        // the range list rides along
         reinterpret_cast<uint4 *>(ranges_dst)[r] = reinterpret_cast<const uint4 *>(ranges_src)[r];
     const uint32_t g = t >> 3, part = t & 7;
     if (g >= G) return;
@@ -446,6 +459,60 @@ struct MergeArgs {
 constexpr int kMergePieces = 8;                     // segments in flight per wavefront
 constexpr uint32_t kMergeHead = 4 * kWave;          // ids of a segment its wavefront takes itself
 
+// The segments of one bucket, staged in LDS: for piece s its first id, its length and the value `code[s]` that goes
+// into the bucket's table.  `put(id, code)` is the LDS atomic of the caller (the largest code or the smallest
+// command wins, depending on what the table holds).
+template <int kPieces, class Put>
+__device__ __forceinline__ void merge_segments(const uint32_t *const *first, const uint32_t *len, const uint32_t *code,
+                                               uint32_t n_src, bool any_long, Put put) {
+    const uint32_t lane = (uint32_t)lane_id(), wave = threadIdx.x / kWave, waves = blockDim.x / kWave;
+    for (uint32_t s0 = wave * kPieces; s0 < n_src; s0 += waves * kPieces) {
+        const uint32_t *ptr[kPieces];
+        uint32_t n[kPieces], e[kPieces];
+#pragma unroll
+        for (int j = 0; j < kPieces; ++j) {             // the same for every lane
+            const uint32_t s = min(s0 + j, n_src - 1);
+            n[j] = (s0 + j < n_src) ? min(len[s], kMergeHead) : 0u;
+            e[j] = code[s];
+            ptr[j] = first[s];
+        }
+        uint32_t n_max = 0;
+#pragma unroll
+        for (int j = 0; j < kPieces; ++j) n_max = max(n_max, n[j]);
+        // two rows of 64 ids from each of the segments per pass: every load of a pass is issued before its first atomic
+        for (uint32_t r0 = 0; r0 < n_max; r0 += 2 * kWave) {
+            uint32_t id[2][kPieces];
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+#pragma unroll
+                for (int j = 0; j < kPieces; ++j)
+                    id[q][j] = r0 + q * kWave + lane < n[j] ? ptr[j][r0 + q * kWave + lane] : kNone;
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+#pragma unroll
+                for (int j = 0; j < kPieces; ++j)
+                    if (id[q][j] != kNone) put(id[q][j], e[j]);
+        }
+    }
+    if (any_long) {
+        for (uint32_t s = 0; s < n_src; ++s) {
+            const uint32_t n = len[s];
+            if (n <= kMergeHead) continue;
+            const uint32_t *ptr = first[s];
+            const uint32_t c = code[s];
+            constexpr int kInFlight = 4;
+            for (uint32_t i0 = kMergeHead + threadIdx.x; i0 < n; i0 += blockDim.x * kInFlight) {
+                uint32_t id[kInFlight];
+#pragma unroll
+                for (int j = 0; j < kInFlight; ++j) id[j] = i0 + j * blockDim.x < n ? ptr[i0 + j * blockDim.x] : kNone;
+#pragma unroll
+                for (int j = 0; j < kInFlight; ++j)
+                    if (id[j] != kNone) put(id[j], c);
+            }
+        }
+    }
+}
+
 __global__ __launch_bounds__(kListThreads) void k_list_merge(MergeArgs a) {
     // buckets with ids tend to be neighbours (one table): the strided map spreads them over the dispatch order
     // and with it over the compute units
@@ -470,52 +537,8 @@ __global__ __launch_bounds__(kListThreads) void k_list_merge(MergeArgs a) {
     const int any_ids = __syncthreads_or(longest != 0);
     const int any_long = __syncthreads_or(longest > kMergeHead);
     if (!any_ids) return;
-    const uint32_t lane = (uint32_t)lane_id(), wave = threadIdx.x / kWave, waves = blockDim.x / kWave;
-    for (uint32_t s0 = wave * kMergePieces; s0 < a.n_src; s0 += waves * kMergePieces) {
-        const uint32_t *ptr[kMergePieces];
-        uint32_t n[kMergePieces], e[kMergePieces];
-#pragma unroll
-        for (int j = 0; j < kMergePieces; ++j) {             // the same for every lane
-            const uint32_t s = min(s0 + j, a.n_src - 1);
-            n[j] = (s0 + j < a.n_src) ? min(len[s], kMergeHead) : 0u;
-            e[j] = enc[s];
-            ptr[j] = first[s];
-        }
-        uint32_t n_max = 0;
-#pragma unroll
-        for (int j = 0; j < kMergePieces; ++j) n_max = max(n_max, n[j]);
-        // two rows of 64 ids from each of the segments per pass: every load of a pass is issued before its first atomic
-        for (uint32_t r0 = 0; r0 < n_max; r0 += 2 * kWave) {
-            uint32_t id[2][kMergePieces];
-#pragma unroll
-            for (int q = 0; q < 2; ++q)
-#pragma unroll
-                for (int j = 0; j < kMergePieces; ++j)
-                    id[q][j] = r0 + q * kWave + lane < n[j] ? ptr[j][r0 + q * kWave + lane] : kNone;
-#pragma unroll
-            for (int q = 0; q < 2; ++q)
-#pragma unroll
-                for (int j = 0; j < kMergePieces; ++j)
-                    if (id[q][j] != kNone) atomicMax(&tab[id[q][j] & (kBucketPages - 1)], e[j]);   // never 0
-        }
-    }
-    if (any_long) {
-        for (uint32_t s = 0; s < a.n_src; ++s) {
-            const uint32_t n = len[s];
-            if (n <= kMergeHead) continue;
-            const uint32_t *ptr = first[s];
-            const uint32_t code = enc[s];
-            constexpr int kInFlight = 4;
-            for (uint32_t i0 = kMergeHead + threadIdx.x; i0 < n; i0 += blockDim.x * kInFlight) {
-                uint32_t id[kInFlight];
-#pragma unroll
-                for (int j = 0; j < kInFlight; ++j) id[j] = i0 + j * blockDim.x < n ? ptr[i0 + j * blockDim.x] : kNone;
-#pragma unroll
-                for (int j = 0; j < kInFlight; ++j)
-                    if (id[j] != kNone) atomicMax(&tab[id[j] & (kBucketPages - 1)], code);
-            }
-        }
-    }
+    merge_segments<kMergePieces>(first, len, enc, a.n_src, any_long != 0,
+                   [&](uint32_t id, uint32_t code) { atomicMax(&tab[id & (kBucketPages - 1)], code); });   // never 0
     __syncthreads();
     const uint64_t p0 = (uint64_t)b << kBucketShift;
     const uint64_t p1 = min(a.V, p0 + kBucketPages);
@@ -697,9 +720,23 @@ __device__ __forceinline__ void rank_tile(const SweepGeom &sg, uint32_t *hist, u
 
 // First sweep: pages per key in one chunk -> one matrix row.  Counting needs no order, so all
 // wavefronts of the workgroup add into one LDS histogram.
+//
+// kLists: the plan's id lists arrive as prepared pieces and a tile is exactly one bucket.  Then the workgroup merges
+// its bucket's segments straight into the painted tile (the smallest command wins there, for ranges and lists
+// alike) and nu[] is neither written nor read: the separate merge launch, 4 bytes written and 4 read per page of a
+// bucket with ids, and one kernel boundary fall away.
+struct TileLists {
+    const ListSource *src; uint32_t n_src, n_buckets;
+    const uint32_t *bucket_mark;        // [n_buckets] does any prepared piece hold an id of this bucket?
+    const uint32_t *order;              // [n_chunks] the chunk of each workgroup (chunk_order_block)
+};
+constexpr int kFusedPieces = 4;
+constexpr uint32_t kStagePieces = 1024;  // segments of a bucket described in LDS at a time (16 bytes each)
+
+template <bool kLists>
 __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_table, const uint32_t *__restrict__ nu,
                                            const SweepGeom &sg, uint32_t chunk, uint32_t *lds, uint32_t *row,
-                                           uint32_t *group_row) {
+                                           uint32_t *group_row, const TileLists *tl = nullptr) {
     const uint32_t n_keys = 2 * (sg.G + 1);
     const uint32_t waves = blockDim.x / kWave, wave = threadIdx.x / kWave;
     for (uint32_t i = threadIdx.x; i < n_keys; i += blockDim.x) lds[i] = 0;
@@ -713,60 +750,105 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
     const uint4 none4 = {kNone, kNone, kNone, kNone}, zero4 = {0u, 0u, 0u, 0u};
     for (uint32_t round = 0; round < sg.rounds; ++round) {
         const uint64_t tile_begin = p_begin + round * tile_pages;
-        if (sg.n_ranges) paint_tile(sg, tile_begin, min(p_end, tile_begin + tile_pages), paint, s_paint);
-        // does any id list of this plan reach into this tile?  (the same answer for every thread)
-        bool tile_nu = sg.use_nu != 0;
-        if (tile_nu && sg.bucket_mark != nullptr && tile_begin < p_end) {
-            uint32_t any = 0;
-            const uint64_t last = min(p_end, tile_begin + tile_pages) - 1;
-            for (uint64_t bk = tile_begin >> kBucketShift; bk <= (last >> kBucketShift); ++bk) any |= sg.bucket_mark[bk];
-            tile_nu = any != 0;
-        }
+        const uint64_t tile_end = min(p_end, tile_begin + tile_pages);
         const uint64_t wave_begin = tile_begin + (uint64_t)wave * sg.steps * kWave;
-        for (uint32_t s0 = 0; s0 < sg.steps; s0 += kCountBatch) {
-            const uint32_t batch_pages = min((uint32_t)kCountBatch, sg.steps - s0) * kWave;
-            const uint64_t first = wave_begin + (uint64_t)s0 * kWave + lane * kCountBatch;   // this lane's eight pages
-            const bool live = lane * kCountBatch < batch_pages && first < p_end;
-            // the arrays are padded, so a lane whose eight pages straddle the end of the table may load all eight
-            Eight fr{none4, none4}, enc{zero4, zero4}, pt{zero4, zero4};
-            if (live) {
-                const uint4 *src = reinterpret_cast<const uint4 *>(page_table + first);
-                fr = Eight{src[0], src[1]};
-                if (tile_nu) { const uint4 *e = reinterpret_cast<const uint4 *>(nu + first); enc = Eight{e[0], e[1]}; }
-                if (sg.n_ranges) { const uint4 *q = reinterpret_cast<const uint4 *>(paint + (first - tile_begin)); pt = Eight{q[0], q[1]}; }
-            }
-            uint32_t key[kCountBatch];
-#pragma unroll
-            for (int j = 0; j < kCountBatch; ++j) {
-                const bool in = live && first + j < p_end;
-                const uint32_t painted = (in && sg.n_ranges) ? min(s_paint.floor, eight_at(pt, j)) : sg.G;
-                key[j] = in ? classify(eight_at(fr, j), eight_at(enc, j), sg.epoch, sg.G, painted) : kNone;
-            }
-            if (sg.slot != nullptr && sg.n_ranges) {      // a page a range wants must have a backing slot
-#pragma unroll
-                for (int j = 0; j < kCountBatch; ++j)
-                    if (key[j] < sg.G && sg.slot[first + j] == kNone) atomicOr(sg.flags, kStatRange);
-            }
-            // the second sweep reads the classes from here, 2 bytes a page
-            if (live) {
-                uint32_t w[kCountBatch / 2];
-#pragma unroll
-                for (int j = 0; j < kCountBatch; j += 2) {
-                    const uint32_t a = key[j] == kNone ? (uint32_t)kNoKey16 : key[j];
-                    const uint32_t b = key[j + 1] == kNone ? (uint32_t)kNoKey16 : key[j + 1];
-                    w[j / 2] = a | (b << 16);
+        // The tile's pages, a batch at a time: classes from page table, nu[] (tile_nu) and the painted tile
+        // (tile_paint), written for the second sweep and counted.
+        auto sweep_tile = [&](bool tile_paint, bool tile_nu) {
+            for (uint32_t s0 = 0; s0 < sg.steps; s0 += kCountBatch) {
+                const uint32_t batch_pages = min((uint32_t)kCountBatch, sg.steps - s0) * kWave;
+                const uint64_t first = wave_begin + (uint64_t)s0 * kWave + lane * kCountBatch;   // this lane's eight pages
+                const bool live = lane * kCountBatch < batch_pages && first < p_end;
+                // the arrays are padded, so a lane whose eight pages straddle the end of the table may load all eight
+                Eight fr{none4, none4}, enc{zero4, zero4}, pt{zero4, zero4};
+                if (live) {
+                    const uint4 *src = reinterpret_cast<const uint4 *>(page_table + first);
+                    fr = Eight{src[0], src[1]};
+                    if (tile_nu) { const uint4 *e = reinterpret_cast<const uint4 *>(nu + first); enc = Eight{e[0], e[1]}; }
+                    if (tile_paint) { const uint4 *q = reinterpret_cast<const uint4 *>(paint + (first - tile_begin)); pt = Eight{q[0], q[1]}; }
                 }
-                if (first + kCountBatch <= p_end) {
-                    *reinterpret_cast<uint4 *>(sg.key16 + first) = uint4{w[0], w[1], w[2], w[3]};
-                } else {
+                uint32_t key[kCountBatch];
+#pragma unroll
+                for (int j = 0; j < kCountBatch; ++j) {
+                    const bool in = live && first + j < p_end;
+                    const uint32_t painted = (in && tile_paint) ? min(s_paint.floor, eight_at(pt, j)) : sg.G;
+                    key[j] = in ? classify(eight_at(fr, j), eight_at(enc, j), sg.epoch, sg.G, painted) : kNone;
+                }
+                if (sg.slot != nullptr && sg.n_ranges) {      // a page a range wants must have a backing slot
 #pragma unroll
                     for (int j = 0; j < kCountBatch; ++j)
-                        if (first + j < p_end) sg.key16[first + j] = (uint16_t)(w[j / 2] >> (16 * (j & 1)));
+                        if (key[j] < sg.G && sg.slot[first + j] == kNone) atomicOr(sg.flags, kStatRange);
+                }
+                // the second sweep reads the classes from here, 2 bytes a page
+                if (live) {
+                    uint32_t w[kCountBatch / 2];
+#pragma unroll
+                    for (int j = 0; j < kCountBatch; j += 2) {
+                        const uint32_t a = key[j] == kNone ? (uint32_t)kNoKey16 : key[j];
+                        const uint32_t b = key[j + 1] == kNone ? (uint32_t)kNoKey16 : key[j + 1];
+                        w[j / 2] = a | (b << 16);
+                    }
+                    if (first + kCountBatch <= p_end) {
+                        *reinterpret_cast<uint4 *>(sg.key16 + first) = uint4{w[0], w[1], w[2], w[3]};
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < kCountBatch; ++j)
+                            if (first + j < p_end) sg.key16[first + j] = (uint16_t)(w[j / 2] >> (16 * (j & 1)));
+                    }
+                }
+                count_batch(lds, key);
+            }
+        };
+        if (kLists) {
+            if (tile_begin < p_end) {
+                const uint32_t b = (uint32_t)(tile_begin >> kBucketShift);      // the tile is this bucket
+                if (b == 0) {                                 // its workgroup also reports ids that cannot be planned
+                    for (uint32_t s = threadIdx.x; s < tl->n_src; s += blockDim.x)
+                        if (tl->src[s].block[0]) atomicOr(sg.flags, kStatRange);
+                }
+                // (Measured and dropped: asking for the page-table entries and the segment descriptions before
+                // painting, so that their round trips overlap it - 5 us slower per plan.)
+                if (!tl->bucket_mark[b]) {
+                    if (sg.n_ranges) paint_tile(sg, tile_begin, tile_end, paint, s_paint);
+                    sweep_tile(sg.n_ranges != 0, false);
+                } else {
+                    paint_tile(sg, tile_begin, tile_end, paint, s_paint);
+                    const uint32_t **first = reinterpret_cast<const uint32_t **>(paint + tile_pages);   // [kStagePieces]
+                    uint32_t *len = reinterpret_cast<uint32_t *>(first + kStagePieces);
+                    uint32_t *cmd = len + kStagePieces;
+                    for (uint32_t s_base = 0; s_base < tl->n_src; s_base += kStagePieces) {
+                        const uint32_t n_here = min(kStagePieces, tl->n_src - s_base);
+                        uint32_t longest = 0;
+                        for (uint32_t s = threadIdx.x; s < n_here; s += blockDim.x) {
+                            const ListSource S = tl->src[s_base + s];
+                            const uint32_t lo = S.block[1 + b], hi = S.block[2 + b];
+                            first[s] = S.block + tl->n_buckets + 2 + lo;
+                            len[s] = hi - lo;
+                            cmd[s] = S.g;
+                            longest = max(longest, hi - lo);
+                        }
+                        const int any_ids = __syncthreads_or(longest != 0);
+                        const int any_long = __syncthreads_or(longest > kMergeHead);
+                        if (any_ids)
+                            merge_segments<kFusedPieces>(first, len, cmd, n_here, any_long != 0,
+                                           [&](uint32_t id, uint32_t g) { atomicMin(&paint[id & (kBucketPages - 1)], g); });
+                        __syncthreads();                   // the next pieces overwrite the descriptions; the tile is read below
+                    }
+                    sweep_tile(true, false);
                 }
             }
-            count_batch(lds, key);
+        } else {
+            if (sg.n_ranges) paint_tile(sg, tile_begin, tile_end, paint, s_paint);
+            // does any id list of this plan reach into this tile?  (the same answer for every thread)
+            bool tile_nu = sg.use_nu != 0;
+            if (tile_nu && sg.bucket_mark != nullptr && tile_begin < p_end) {
+                uint32_t any = 0;
+                for (uint64_t bk = tile_begin >> kBucketShift; bk <= ((tile_end - 1) >> kBucketShift); ++bk) any |= sg.bucket_mark[bk];
+                tile_nu = any != 0;
+            }
+            sweep_tile(sg.n_ranges != 0, tile_nu);
         }
-        if (sg.n_ranges) __syncthreads();                 // the next tile repaints
+        if (sg.n_ranges || kLists) __syncthreads();       // the next tile repaints
     }
     __syncthreads();
     for (uint32_t k = threadIdx.x; k < n_keys; k += blockDim.x) {
@@ -783,8 +865,22 @@ __global__ __launch_bounds__(kWave * kMaxWaves) void k_count(const uint32_t *__r
     extern __shared__ uint32_t lds[];
     const uint32_t chunk = chunk_of_block(blockIdx.x, gridDim.x), n_keys = 2 * (sg.G + 1);
     const uint32_t rows = (gridDim.x + kRowGroups - 1) / kRowGroups;      // chunks per row group
-    count_body(page_table, nu, sg, chunk, lds, matrix + (size_t)chunk * n_keys,
-               partial ? partial + (size_t)(chunk / rows) * n_keys : nullptr);
+    count_body<false>(page_table, nu, sg, chunk, lds, matrix + (size_t)chunk * n_keys,
+                      partial ? partial + (size_t)(chunk / rows) * n_keys : nullptr);
+}
+
+// The first sweep with the id lists merged in (see count_body): twice the wavefronts on half the steps each, the
+// same tile, because a bucket with ids is mostly merging and the merge is a matter of wavefronts in flight.
+static_assert(kMaxWaves * kMaxSteps * kWave == (int)kBucketPages, "a full-size tile is one bucket");
+constexpr int kFusedThreads = 1024;
+__global__ __launch_bounds__(kFusedThreads, 8) void k_count_lists(const uint32_t *__restrict__ page_table, SweepGeom sg,
+                                                              TileLists tl, uint32_t *__restrict__ matrix,
+                                                              uint32_t *__restrict__ partial) {
+    extern __shared__ uint32_t lds[];
+    const uint32_t chunk = tl.order[blockIdx.x], n_keys = 2 * (sg.G + 1);
+    const uint32_t rows = (gridDim.x + kRowGroups - 1) / kRowGroups;
+    count_body<true>(page_table, nullptr, sg, chunk, lds, matrix + (size_t)chunk * n_keys,
+                     partial ? partial + (size_t)(chunk / rows) * n_keys : nullptr, &tl);
 }
 
 // In-place exclusive scan of a[0..n) in LDS by the whole block (a multiple of 64 threads, at most
@@ -816,6 +912,32 @@ __device__ uint32_t block_exclusive_scan(uint32_t *a, uint32_t n, uint32_t *wave
     __syncthreads();
     return total;
 }
+
+// Chunks whose buckets hold ids cost the first sweep several times what the others cost (they merge their
+// segments first): dispatched first, the others fill in around them instead of waiting for the last of them.
+// One workgroup of 256 threads; the marks are sticky, so an order made from marks a later preparation adds to
+// is still a permutation - only less good.
+__device__ void chunk_order_block(const ChunkOrder &o) {
+    __shared__ uint32_t s_cnt[256], s_wave[4];
+    const uint32_t per = (o.n_chunks + blockDim.x - 1) / blockDim.x;      // at most kMaxChunks / 256 = 8
+    const uint32_t c0 = min(o.n_chunks, threadIdx.x * per), c1 = min(o.n_chunks, c0 + per);
+    uint32_t mask = 0;
+    for (uint32_t c = c0; c < c1; ++c) {
+        uint32_t any = 0;
+        const uint32_t b1 = min(o.n_buckets, (c + 1) * o.buckets_per_chunk);
+        for (uint32_t b = c * o.buckets_per_chunk; b < b1; ++b) any |= o.bucket_mark[b];
+        if (any) mask |= 1u << (c - c0);
+    }
+    s_cnt[threadIdx.x] = __popc(mask);
+    __syncthreads();
+    const uint32_t n_marked = block_exclusive_scan(s_cnt, blockDim.x, s_wave);
+    uint32_t before = s_cnt[threadIdx.x];                                  // marked chunks below c
+    for (uint32_t c = c0; c < c1; ++c) {
+        if ((mask >> (c - c0)) & 1u) o.order[before++] = c;
+        else o.order[n_marked + (c - before)] = c;
+    }
+}
+static_assert(kMaxChunks <= 256 * 32, "a thread of chunk_order_block keeps its chunks' marks in one word");
 
 // Budget cut, counts, victim threshold (implicit in the offsets) and per-class output offsets.
 //   D(k) = pages with nu < k; g_cut = largest k <= g_end0 with D(k) <= F            (cut)
@@ -1115,7 +1237,7 @@ __global__ __launch_bounds__(kWave * kMaxWaves, 6) void k_emit(EmitArgs a, Sweep
 // (planning such a table is bound by launch latency, not by bandwidth).
 __global__ __launch_bounds__(kWave * kMaxWaves) void k_tail(SweepGeom sg, CutArgs ca, EmitArgs ea) {
     extern __shared__ uint32_t lds[];
-    count_body(ea.page_table, ea.nu, sg, 0, lds, ca.groups, nullptr);
+    count_body<false>(ea.page_table, ea.nu, sg, 0, lds, ca.groups, nullptr);
     __syncthreads();
     cut_body(ca, lds);
     __syncthreads();
@@ -1204,6 +1326,9 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     (void)hipGetLastError();   // launches below are checked through the sticky error: start clean
     hipStream_t st = c->stream;
     const bool prof = c->profiling >= 2;
+    // prepared id lists, painted ranges and full-size tiles (one bucket each): the first sweep merges the lists itself
+    const bool fuse_lists = c->fuse_lists && c->has_list_rule && g.painted && g.list_prepared && g.n_list_sources &&
+                            !g.single && g.waves == (uint32_t)kMaxWaves && g.steps == (uint32_t)kMaxSteps;
     if (c->profiling) CK(hipEventRecord(c->ev[0], st));
     {
         ExpandArgs a;
@@ -1219,12 +1344,13 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         const bool copy_ranges = g.n_ranges && !g.single;
         // prepared id lists and painted ranges together need no record on the device: only the two small tables travel
         const uint32_t n_records = (g.painted && g.list_prepared) ? 0u : g.G;
+        ChunkOrder co{nullptr, 0, 0, 0, nullptr};
+        if (fuse_lists) co = ChunkOrder{c->bucket_mark, g.n_buckets, g.n_chunks, g.rounds, c->bucket_mark + kMaxBuckets};
         if (stage)
-            k_stage<<<(std::max<uint32_t>(std::max(n_records * 8, g.n_ranges + g.n_list_sources), 1u) + 255) / 256, 256, 0, st>>>(c->cmd_ptrs_dev, n_records, c->cmd_dev, c->list_bucket_fill,
-                                                           g.list_binned ? g.n_buckets * 8 : 0, c->ranges_host_dev,
-                                                           c->ranges_dev, copy_ranges ? g.n_ranges : 0,
-                                                           c->list_src_dev, c->list_src_stage,
-                                                           g.list_prepared ? g.n_list_sources : 0);
+            k_stage<<<(std::max<uint32_t>(std::max(n_records * 8, g.n_ranges + g.n_list_sources), 1u) + 255) / 256 + (fuse_lists ? 1 : 0), 256, 0, st>>>(
+                c->cmd_ptrs_dev, n_records, c->cmd_dev, c->list_bucket_fill, g.list_binned ? g.n_buckets * 8 : 0,
+                c->ranges_host_dev, c->ranges_dev, copy_ranges ? g.n_ranges : 0, c->list_src_dev, c->list_src_stage,
+                g.list_prepared ? g.n_list_sources : 0, co);
         else if (copy_ranges)
             k_copy_ranges<<<(g.n_ranges + 255) / 256, 256, 0, st>>>(c->ranges_host_dev, c->ranges_dev, g.n_ranges);
         // Id lists go first in three stream-ordered batches of growing size: the smallest g wins a page,
@@ -1235,7 +1361,7 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
             MergeArgs ma;
             ma.src = c->list_src_stage; ma.n_src = g.n_list_sources; ma.n_buckets = g.n_buckets;
             ma.nu = c->nu; ma.flags = c->flags; ma.V = c->V; ma.epoch_base = a.epoch_base; ma.bucket_mark = c->bucket_mark;
-            if (g.n_list_sources)
+            if (g.n_list_sources && !fuse_lists)
                 k_list_merge<<<g.n_buckets, kListThreads, (size_t)g.n_list_sources * 16, st>>>(ma);
         } else if (c->has_list_rule && g.list_binned) {
             ListArgs la;
@@ -1284,8 +1410,18 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         if (c->profiling) CK(hipEventRecord(c->ev[4], st));
         return hipGetLastError();
     }
-    k_count<<<g.n_chunks, threads, (size_t)count_paint_offset(g.n_keys) * 4 + paint_lds, st>>>(c->page_table, c->nu, sg, c->matrix,
-                                                                few_rows ? nullptr : c->partial);
+    if (fuse_lists) {
+        SweepGeom sc = sg;
+        sc.steps = g.steps * g.waves / (kFusedThreads / kWave);       // the same tile on the wider workgroup
+        TileLists tl;
+        tl.src = c->list_src_stage; tl.n_src = g.n_list_sources; tl.n_buckets = g.n_buckets; tl.bucket_mark = c->bucket_mark;
+        tl.order = c->bucket_mark + kMaxBuckets;
+        const size_t lds = ((size_t)count_paint_offset(g.n_keys) + kBucketPages) * 4 + (size_t)kStagePieces * 16;
+        k_count_lists<<<g.n_chunks, kFusedThreads, lds, st>>>(c->page_table, sc, tl, c->matrix, few_rows ? nullptr : c->partial);
+    } else {
+        k_count<<<g.n_chunks, threads, (size_t)count_paint_offset(g.n_keys) * 4 + paint_lds, st>>>(c->page_table, c->nu, sg, c->matrix,
+                                                                    few_rows ? nullptr : c->partial);
+    }
     if (prof) CK(hipEventRecord(c->ev[2], st));
     const uint32_t cut_threads = std::min<uint32_t>(1024, std::max<uint32_t>(256, (g.n_keys + 63) / 64 * 64));   // a key per thread
     if (few_rows) {

@@ -293,14 +293,20 @@ def test_allocation_granularity_ablation_runs_bit_exact(oracle_mod):
 
 @pytest.mark.parametrize("env", [{"MSCHED_PAINT": "0"}, {"MSCHED_LIST_PREPARED": "0"},
                                  {"MSCHED_PAINT": "0", "MSCHED_LIST_PREPARED": "0"},
-                                 {"MSCHED_LIST_CACHE_MB": "1"}, {"MSCHED_LIST_AHEAD": "0"}, {"MSCHED_PLAN_SPIN": "0"}],
+                                 {"MSCHED_LIST_CACHE_MB": "1"}, {"MSCHED_LIST_AHEAD": "0"}, {"MSCHED_PLAN_SPIN": "0"},
+                                 {"MSCHED_MAX_CHUNKS": "16"}, {"MSCHED_MAX_CHUNKS": "16", "MSCHED_FUSE_LISTS": "0"},
+                                 {"MSCHED_MAX_CHUNKS": "16", "MSCHED_LIST_AHEAD": "0"}],
                          ids=["scatter-ranges", "bin-per-plan", "both-earlier-paths", "one-megabyte-ring", "no-look-ahead",
-                              "plan-waits-for-the-stream"])
+                              "plan-waits-for-the-stream", "lists-merged-in-the-sweep", "full-size-tiles-own-merge",
+                              "lists-merged-in-the-sweep-no-look-ahead"])
 def test_earlier_planning_paths_stay_bit_exact(oracle_mod, monkeypatch, env):
     """Range pages scattered into the next-use array instead of painted, id lists binned from scratch in every
     plan instead of prepared once per command, a ring too small for the prepared lists (which makes plans fall
     back to binning from scratch part of the time), lists prepared by the plan that first sees them instead of
-    behind the previous migration, and a plan call that waits for the whole stream instead of the stamped counts."""
+    behind the previous migration, and a plan call that waits for the whole stream instead of the stamped counts.
+    With at most 16 sweep workgroups the scaled tables get the full-size tiles (one bucket of id lists each) of
+    the large ones, where the first sweep merges the prepared lists itself - or, switched off, leaves that to the
+    merge kernel."""
     monkeypatch.setenv("MSCHED_LIST_BINNED_MIN_IDS", "0")
     for k, v in env.items():
         monkeypatch.setenv(k, v)
@@ -381,6 +387,57 @@ def test_a_plan_with_more_than_a_thousand_prepared_lists(oracle_mod, monkeypatch
             n = min(po.covered_launches, 200)                  # the rest of the slice stays queued: most lists are planned again
             o.launch_retire(tl[0][0], n)
             g.ms.launch_retire(tl[0][0], n)
+    finally:
+        g.close()
+        o.close()
+
+
+def test_lists_merged_in_the_sweep_more_pieces_than_one_staging_round(oracle_mod, monkeypatch):
+    """Full-size tiles (three sweep workgroups for 70 000 pages, the last tile ragged) and 402 commands whose lists
+    of 60 000 ids are prepared as three pieces each: the sweep describes a bucket's 1206 segments in LDS in two
+    rounds.  Then a list with an id beyond the table, which the sweep of bucket 0 has to report."""
+    import torch
+    from paper_2512_24637_amd import MSchedError
+    monkeypatch.setenv("MSCHED_LIST_BINNED_MIN_IDS", "0")
+    monkeypatch.setenv("MSCHED_MAX_CHUNKS", "3")
+    V, F, n_cmds, n_ids = 70000, 50000, 201, 60000
+    trace = explicit_trace([[[0]], [[1]]], V, F, timeslice=n_cmds, page_shift=6)
+    g = GpuSide(trace)
+    o = make_oracle(oracle_mod, trace, with_bytes=False)
+    rng = np.random.default_rng(23)
+    try:
+        # every command reads one window of a quarter of the table; the windows move with the command
+        lo = rng.integers(0, V - V // 4, (2, n_cmds))
+        ids = (lo[:, :, None] + rng.integers(0, V // 4, (2, n_cmds, n_ids))).astype(np.uint32)
+        dev = torch.from_numpy(ids.view(np.int32)).cuda()
+        kg = g.ms.kernel_register([Rule(RULE_LINEAR, 0, (1,), 4), Rule(RULE_LIST)])
+        ko = o.kernel_register([Rule(RULE_LINEAR, 0, (1,), 4), Rule(RULE_LIST)])
+        for impl in (g.ms, o):
+            impl.launch_retire(0, 1)
+            impl.launch_retire(1, 1)
+        for task in (0, 1):
+            for i in range(n_cmds):
+                args = [int(rng.integers(0, V - 600)) * 64, int(rng.integers(1, 500)) * 16]
+                g.ms.launch_enqueue(task, kg, args, 2, ids_ptr=dev[task, i].data_ptr(), n_ids=n_ids)
+                o.launch_enqueue(task, ko, args, 2, ids=ids[task, i])
+        for k, tl in enumerate(([(0, n_cmds), (1, n_cmds)], [(1, n_cmds), (0, n_cmds)], [(0, n_cmds), (1, n_cmds)])):
+            po, pg = o.plan(tl), g.ms.plan(tl)
+            if k == 0:
+                assert pg.n_commands == 2 * n_cmds
+            assert_same_plan(po, pg, tl)
+            o.migrate()
+            g.ms.migrate()
+            pto, foo = o.state()
+            ptg, fog = g.ms.state()
+            assert np.array_equal(pto, ptg) and np.array_equal(foo, fog)
+            n = min(po.covered_launches, 60)
+            o.launch_retire(tl[0][0], n)
+            g.ms.launch_retire(tl[0][0], n)
+        bad = torch.tensor([3, V + 5, 9], dtype=torch.int32, device="cuda")
+        g.ms.launch_enqueue(1, kg, [0, 16], 2, ids_ptr=bad.data_ptr(), n_ids=3)
+        with pytest.raises(MSchedError) as e:
+            g.ms.plan([(0, 2), (1, n_cmds + 5)])
+        assert e.value.name == "E_RANGE"
     finally:
         g.close()
         o.close()
