@@ -652,12 +652,46 @@ __device__ void paint_tile(const SweepGeom &sg, uint64_t t0, uint64_t t1, uint32
     }
 }
 
+// The cheap case of painting: a tile that only a few ranges reach into part of (dense ranges are long, a tile
+// typically meets the end of one and the start of another).  The ranges are only tested and queued here, two
+// barriers; every lane then applies the queue to its own pages in registers (sweep_tile), and nothing is painted
+// in LDS.  Returns how many ranges were offered to the queue, the same number to every thread: above
+// kPaintInRegisters the caller paints the tile in LDS instead (after a barrier of its own: paint_tile resets the
+// queue).
+constexpr uint32_t kPaintInRegisters = 16;
+__device__ uint32_t queue_ranges(const SweepGeom &sg, uint64_t t0, uint64_t t1, PaintLds &q) {
+    if (threadIdx.x == 0) { q.n_queued = 0; q.floor = sg.G; }
+    __syncthreads();
+    constexpr uint32_t kPerThread = 4;
+    for (uint32_t r0 = 0; r0 < sg.n_ranges; r0 += blockDim.x * kPerThread) {
+#pragma unroll
+        for (uint32_t j = 0; j < kPerThread; ++j) {
+            const uint32_t r = r0 + j * blockDim.x + threadIdx.x;
+            if (r >= sg.n_ranges) continue;
+            const PageRange R = sg.ranges[r];
+            const uint64_t lo = max((uint64_t)R.lo, t0), hi = min((uint64_t)R.hi, t1);
+            if (lo < hi) {
+                if (lo == t0 && hi == t1) {
+                    atomicMin(&q.floor, R.g);
+                } else {
+                    const uint32_t at = atomicAdd(&q.n_queued, 1u);
+                    if (at < kPaintInRegisters) { q.lo[at] = (uint32_t)(lo - t0); q.hi[at] = (uint32_t)(hi - t0); q.g[at] = R.g; }
+                }
+            }
+        }
+    }
+    __syncthreads();
+    return q.n_queued;
+}
+static_assert(kPaintInRegisters <= kPaintQueue, "the queue holds what is applied from registers");
+
 // A batch of a tile: kCountBatch x 64 consecutive pages of the wavefront's slice, lane l taking the kCountBatch
 // consecutive pages from kCountBatch * l on.  Counting needs no page order, and eight consecutive pages make every
 // access a 16-byte one: two loads each for page table and next use, two LDS reads for the painted tile, one
 // store for the classes.  Eight pages at a time also keep the first sweep at half the registers of a whole
 // 16-step slice, which doubles the workgroups a compute unit holds.
 constexpr int kCountBatch = 8;
+enum { kPaintNone = 0, kPaintLds = 1, kPaintQueued = 2 };   // where a tile's next uses from ranges are
 struct Eight { uint4 lo, hi; };
 __device__ __forceinline__ uint32_t eight_at(const Eight &e, int j) {
     const uint4 &h = j < 4 ? e.lo : e.hi;
@@ -752,9 +786,9 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
         const uint64_t tile_begin = p_begin + round * tile_pages;
         const uint64_t tile_end = min(p_end, tile_begin + tile_pages);
         const uint64_t wave_begin = tile_begin + (uint64_t)wave * sg.steps * kWave;
-        // The tile's pages, a batch at a time: classes from page table, nu[] (tile_nu) and the painted tile
-        // (tile_paint), written for the second sweep and counted.
-        auto sweep_tile = [&](bool tile_paint, bool tile_nu) {
+        // The tile's pages, a batch at a time: classes from page table, nu[] (tile_nu) and the ranges (painted in
+        // LDS, or still in the queue and applied here), written for the second sweep and counted.
+        auto sweep_tile = [&](int tile_paint, bool tile_nu) {
             for (uint32_t s0 = 0; s0 < sg.steps; s0 += kCountBatch) {
                 const uint32_t batch_pages = min((uint32_t)kCountBatch, sg.steps - s0) * kWave;
                 const uint64_t first = wave_begin + (uint64_t)s0 * kWave + lane * kCountBatch;   // this lane's eight pages
@@ -765,13 +799,25 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
                     const uint4 *src = reinterpret_cast<const uint4 *>(page_table + first);
                     fr = Eight{src[0], src[1]};
                     if (tile_nu) { const uint4 *e = reinterpret_cast<const uint4 *>(nu + first); enc = Eight{e[0], e[1]}; }
-                    if (tile_paint) { const uint4 *q = reinterpret_cast<const uint4 *>(paint + (first - tile_begin)); pt = Eight{q[0], q[1]}; }
+                    if (tile_paint == kPaintLds) { const uint4 *q = reinterpret_cast<const uint4 *>(paint + (first - tile_begin)); pt = Eight{q[0], q[1]}; }
+                }
+                uint32_t from_ranges[kCountBatch];
+#pragma unroll
+                for (int j = 0; j < kCountBatch; ++j) from_ranges[j] = tile_paint == kPaintLds ? eight_at(pt, j) : sg.G;
+                if (tile_paint == kPaintQueued) {
+                    const uint32_t nq = s_paint.n_queued, at = (uint32_t)(first - tile_begin);
+                    for (uint32_t w = 0; w < nq; ++w) {          // the same range for every lane: LDS broadcasts
+                        const uint32_t lo = s_paint.lo[w], n = s_paint.hi[w] - lo, g = s_paint.g[w];
+#pragma unroll
+                        for (int j = 0; j < kCountBatch; ++j)
+                            if (at + j - lo < n) from_ranges[j] = min(from_ranges[j], g);
+                    }
                 }
                 uint32_t key[kCountBatch];
 #pragma unroll
                 for (int j = 0; j < kCountBatch; ++j) {
                     const bool in = live && first + j < p_end;
-                    const uint32_t painted = (in && tile_paint) ? min(s_paint.floor, eight_at(pt, j)) : sg.G;
+                    const uint32_t painted = (in && tile_paint != kPaintNone) ? min(s_paint.floor, from_ranges[j]) : sg.G;
                     key[j] = in ? classify(eight_at(fr, j), eight_at(enc, j), sg.epoch, sg.G, painted) : kNone;
                 }
                 if (sg.slot != nullptr && sg.n_ranges) {      // a page a range wants must have a backing slot
@@ -799,6 +845,14 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
                 count_batch(lds, key);
             }
         };
+        // ranges of a tile without id lists: queued and applied from registers when they are few
+        auto paint_ranges = [&]() -> int {
+            if (!sg.n_ranges) return kPaintNone;
+            if (queue_ranges(sg, tile_begin, tile_end, s_paint) <= kPaintInRegisters) return kPaintQueued;
+            __syncthreads();                                  // everybody has read the count
+            paint_tile(sg, tile_begin, tile_end, paint, s_paint);
+            return kPaintLds;
+        };
         if (kLists) {
             if (tile_begin < p_end) {
                 const uint32_t b = (uint32_t)(tile_begin >> kBucketShift);      // the tile is this bucket
@@ -809,8 +863,7 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
                 // (Measured and dropped: asking for the page-table entries and the segment descriptions before
                 // painting, so that their round trips overlap it - 5 us slower per plan.)
                 if (!tl->bucket_mark[b]) {
-                    if (sg.n_ranges) paint_tile(sg, tile_begin, tile_end, paint, s_paint);
-                    sweep_tile(sg.n_ranges != 0, false);
+                    sweep_tile(paint_ranges(), false);
                 } else {
                     paint_tile(sg, tile_begin, tile_end, paint, s_paint);
                     const uint32_t **first = reinterpret_cast<const uint32_t **>(paint + tile_pages);   // [kStagePieces]
@@ -834,11 +887,11 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
                                            [&](uint32_t id, uint32_t g) { atomicMin(&paint[id & (kBucketPages - 1)], g); });
                         __syncthreads();                   // the next pieces overwrite the descriptions; the tile is read below
                     }
-                    sweep_tile(true, false);
+                    sweep_tile(kPaintLds, false);
                 }
             }
         } else {
-            if (sg.n_ranges) paint_tile(sg, tile_begin, tile_end, paint, s_paint);
+            const int tile_paint = paint_ranges();
             // does any id list of this plan reach into this tile?  (the same answer for every thread)
             bool tile_nu = sg.use_nu != 0;
             if (tile_nu && sg.bucket_mark != nullptr && tile_begin < p_end) {
@@ -846,7 +899,7 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
                 for (uint64_t bk = tile_begin >> kBucketShift; bk <= ((tile_end - 1) >> kBucketShift); ++bk) any |= sg.bucket_mark[bk];
                 tile_nu = any != 0;
             }
-            sweep_tile(sg.n_ranges != 0, tile_nu);
+            sweep_tile(tile_paint, tile_nu);
         }
         if (sg.n_ranges || kLists) __syncthreads();       // the next tile repaints
     }
