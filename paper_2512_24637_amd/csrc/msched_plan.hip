@@ -1186,9 +1186,9 @@ __device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg
     const uint64_t p_begin = (uint64_t)chunk * sg.chunk_pages;
     const uint64_t p_end = min(sg.V, p_begin + sg.chunk_pages);
     const uint64_t tile_pages = (uint64_t)waves * sg.steps * kWave;
-    // The classes of a wavefront's slice (up to 1024 pages, 2 bytes each) are two 16-byte loads per lane, requested
-    // before anything else so that their way from memory overlaps the set-up below; the lanes then exchange them
-    // through LDS, because lane l ranks pages l, 64 + l, ... (page order inside a step), not 16 l .. 16 l + 15.
+    // The classes of a wavefront's slice (up to 1024 pages, 2 bytes each) are two 16-byte loads per lane; the lanes
+    // then exchange them through LDS, because lane l ranks pages l, 64 + l, ... (page order inside a step), not
+    // 16 l .. 16 l + 15.
     constexpr uint32_t kLanePages = kMaxSteps * kWave / kWave;                    // consecutive pages a lane requests
     static_assert(kLanePages == 16, "two uint4 of 16-bit classes per lane cover the slice");
     struct Raw { uint4 lo, hi; };
@@ -1200,7 +1200,6 @@ __device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg
         const uint4 *src = reinterpret_cast<const uint4 *>(sg.key16 + first);
         return Raw{src[0], src[1]};
     };
-    Raw raw = request_slice(0);
     const uint32_t n_fetch = a.hdr->n_fetch, n_evict = a.hdr->n_evict;
     const uint32_t n_free_used = a.hdr->n_free_used, first_free = a.hdr->first_free;
     if (n_fetch == 0) return;                             // same for every thread of the block
@@ -1212,13 +1211,36 @@ __device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg
     // the chunk's counts tell, before any page is looked at, whether some key with room left in its list occurs here.
     const uint32_t *cnt_row = a.counts ? a.counts + (size_t)chunk * n_keys : nullptr;
     bool live = cnt_row == nullptr;
-    for (uint32_t k = threadIdx.x; k < n_keys; k += blockDim.x) {
+    // The per-key tables first, two keys per thread in flight.  The slice's classes are asked for only once the
+    // chunk is known to have work: three chunks in four of a large table have none, and loads come back in the
+    // order they were issued, so a request for classes (memory) in front would hold up the tables (cache hits)
+    // for nothing (measured: classes first 70.4 us per plan, between tables and their use 69.7, here 68.4).
+    constexpr int kKeysAhead = 2;
+    uint32_t off_a[kKeysAhead], row_a[kKeysAhead], cnt_a[kKeysAhead];
+#pragma unroll
+    for (int j = 0; j < kKeysAhead; ++j) {
+        const uint32_t k = threadIdx.x + j * blockDim.x;
+        off_a[j] = k < n_keys ? a.offsets[k] : kSkip;
+        row_a[j] = k < n_keys ? row[k] : 0u;
+        cnt_a[j] = (k < n_keys && cnt_row != nullptr) ? cnt_row[k] : 0u;
+    }
+#pragma unroll
+    for (int j = 0; j < kKeysAhead; ++j) {
+        const uint32_t k = threadIdx.x + j * blockDim.x;
+        if (k < n_keys) {
+            const uint32_t at = (off_a[j] == kSkip) ? kSkip : off_a[j] + row_a[j];
+            base[k] = at;
+            if (cnt_row != nullptr && at < (k < K ? n_fetch : n_evict) && cnt_a[j] != 0) live = true;
+        }
+    }
+    for (uint32_t k = threadIdx.x + kKeysAhead * blockDim.x; k < n_keys; k += blockDim.x) {
         const uint32_t off = a.offsets[k];
         const uint32_t at = (off == kSkip) ? kSkip : off + row[k];
         base[k] = at;
         if (cnt_row != nullptr && at < (k < K ? n_fetch : n_evict) && cnt_row[k] != 0) live = true;
     }
     if (!__syncthreads_or(live)) return;
+    Raw raw = request_slice(0);
     for (uint32_t round = 0; round < sg.rounds; ++round) {
         if (round) raw = request_slice(round);
         for (uint32_t i = threadIdx.x; i < waves * n_keys; i += blockDim.x) lds[i] = 0;
