@@ -247,8 +247,8 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     ALLOC(c->offsets, (size_t)2 * (MSCHED_MAX_TIMELINE_COMMANDS + 1) * 4);
     ALLOC(c->hdr_dev, sizeof(PlanHeader));
     // row-group sums of the count matrix: the counting sweep adds into them, k_offsets clears what it read
-    ALLOC(c->partial, (size_t)kRowGroups * 2 * (MSCHED_MAX_TIMELINE_COMMANDS + 1) * 4);
-    if (rc == MSCHED_OK && (e = hipMemset(c->partial, 0, (size_t)kRowGroups * 2 * (MSCHED_MAX_TIMELINE_COMMANDS + 1) * 4)) != hipSuccess) fail(e);
+    ALLOC(c->partial, (size_t)kSumRows * 2 * (MSCHED_MAX_TIMELINE_COMMANDS + 1) * 4);
+    if (rc == MSCHED_OK && (e = hipMemset(c->partial, 0, (size_t)kSumRows * 2 * (MSCHED_MAX_TIMELINE_COMMANDS + 1) * 4)) != hipSuccess) fail(e);
     ALLOC(c->cmd_dev, sizeof(CmdRec) * (MSCHED_MAX_TIMELINE_COMMANDS + 1));
     if (cfg->host_slot) {
         ALLOC(c->slot, c->V * 4);

@@ -23,6 +23,8 @@ constexpr uint64_t kPtrMask = (1ull << 56) - 1; // record address without the sk
 constexpr uint32_t kMaxEpoch = (1u << (32 - kNuShift)) - 1;
 static_assert(MSCHED_MAX_TIMELINE_COMMANDS < kNuMask, "g must fit the next-use encoding");
 constexpr uint32_t kRowGroups = 16;             // row groups of the chunk x class count matrix
+constexpr uint32_t kOffsetSplit = 8;            // slices of a row group: the column prefixes are taken slice by slice
+constexpr uint32_t kSumRows = kRowGroups * (1 + kOffsetSplit);   // rows of per-key sums the first sweep keeps: row groups, then their slices
 
 // status bits raised by device code while planning
 constexpr uint32_t kStatRange = 1u;             // a LIST id >= V, or a touched page without backing slot
@@ -144,7 +146,7 @@ struct msched_ctx {
     uint32_t *evict_pages = nullptr, *evict_frames = nullptr, *fetch_pages = nullptr, *fetch_frames = nullptr;
     uint32_t *flags = nullptr;                  // device status word
     uint32_t *matrix = nullptr; size_t matrix_cap = 0;       // [n_chunks][n_keys] counts; behind them [matrix_cap...) the chunks' start positions
-    uint32_t *partial = nullptr;                             // [kRowGroups][n_keys], all zero between plans
+    uint32_t *partial = nullptr;                             // [kSumRows][n_keys] sums by row group, then by slice; all zero between plans
     uint32_t *offsets = nullptr;                // [2 * (MAX_G + 1)] per-class output offsets
     msched::PlanHeader *hdr_dev = nullptr;      // device
     msched::PlanHeader *hdr_host = nullptr;     // pinned

@@ -770,7 +770,7 @@ constexpr uint32_t kStagePieces = 1024;  // segments of a bucket described in LD
 template <bool kLists>
 __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_table, const uint32_t *__restrict__ nu,
                                            const SweepGeom &sg, uint32_t chunk, uint32_t *lds, uint32_t *row,
-                                           uint32_t *group_row, const TileLists *tl = nullptr) {
+                                           uint32_t *group_row, uint32_t *slice_row, const TileLists *tl = nullptr) {
     const uint32_t n_keys = 2 * (sg.G + 1);
     const uint32_t waves = blockDim.x / kWave, wave = threadIdx.x / kWave;
     for (uint32_t i = threadIdx.x; i < n_keys; i += blockDim.x) lds[i] = 0;
@@ -907,8 +907,24 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
     for (uint32_t k = threadIdx.x; k < n_keys; k += blockDim.x) {
         const uint32_t v = lds[k];
         row[k] = v;
-        if (group_row != nullptr && v) atomicAdd(&group_row[k], v);     // column sums by row group, few keys are non-zero
+        if (group_row != nullptr && v) {                                // column sums by row group and by slice of it,
+            atomicAdd(&group_row[k], v);                                // few keys are non-zero
+            atomicAdd(&slice_row[k], v);
+        }
     }
+}
+
+// Where a chunk's counts are added up for the column prefixes: the sums of its row group, and behind the
+// kRowGroups rows of those the sums of its slice of the group (offsets_body).
+__device__ __forceinline__ void sum_rows(uint32_t *partial, uint32_t chunk, uint32_t n_chunks, uint32_t n_keys,
+                                         uint32_t *&group_row, uint32_t *&slice_row) {
+    group_row = slice_row = nullptr;
+    if (partial == nullptr) return;
+    const uint32_t rows = (n_chunks + kRowGroups - 1) / kRowGroups;      // chunks per row group
+    const uint32_t rows_sub = (rows + kOffsetSplit - 1) / kOffsetSplit;  // chunks per slice
+    const uint32_t rg = chunk / rows, sub = (chunk - rg * rows) / rows_sub;
+    group_row = partial + (size_t)rg * n_keys;
+    slice_row = partial + (size_t)(kRowGroups + rg * kOffsetSplit + sub) * n_keys;
 }
 
 __global__ __launch_bounds__(kWave * kMaxWaves) void k_count(const uint32_t *__restrict__ page_table,
@@ -917,9 +933,9 @@ __global__ __launch_bounds__(kWave * kMaxWaves) void k_count(const uint32_t *__r
                                                               uint32_t *__restrict__ partial) {
     extern __shared__ uint32_t lds[];
     const uint32_t chunk = chunk_of_block(blockIdx.x, gridDim.x), n_keys = 2 * (sg.G + 1);
-    const uint32_t rows = (gridDim.x + kRowGroups - 1) / kRowGroups;      // chunks per row group
-    count_body<false>(page_table, nu, sg, chunk, lds, matrix + (size_t)chunk * n_keys,
-                      partial ? partial + (size_t)(chunk / rows) * n_keys : nullptr);
+    uint32_t *group_row, *slice_row;
+    sum_rows(partial, chunk, gridDim.x, n_keys, group_row, slice_row);
+    count_body<false>(page_table, nu, sg, chunk, lds, matrix + (size_t)chunk * n_keys, group_row, slice_row);
 }
 
 // The first sweep with the id lists merged in (see count_body): twice the wavefronts on half the steps each, the
@@ -931,9 +947,9 @@ __global__ __launch_bounds__(kFusedThreads, 8) void k_count_lists(const uint32_t
                                                               uint32_t *__restrict__ partial) {
     extern __shared__ uint32_t lds[];
     const uint32_t chunk = tl.order[blockIdx.x], n_keys = 2 * (sg.G + 1);
-    const uint32_t rows = (gridDim.x + kRowGroups - 1) / kRowGroups;
-    count_body<true>(page_table, nullptr, sg, chunk, lds, matrix + (size_t)chunk * n_keys,
-                     partial ? partial + (size_t)(chunk / rows) * n_keys : nullptr, &tl);
+    uint32_t *group_row, *slice_row;
+    sum_rows(partial, chunk, gridDim.x, n_keys, group_row, slice_row);
+    count_body<true>(page_table, nullptr, sg, chunk, lds, matrix + (size_t)chunk * n_keys, group_row, slice_row, &tl);
 }
 
 // In-place exclusive scan of a[0..n) in LDS by the whole block (a multiple of 64 threads, at most
@@ -1112,41 +1128,44 @@ __global__ __launch_bounds__(1024) void k_cut(CutArgs a) {
     cut_body(a, lds);
 }
 
-constexpr uint32_t kOffsetSplit = 8;
 // starts[w][key] = pages of that key in chunks before w (exclusive prefix down each column of the count matrix),
-// one thread per (key, row group, slice of the group): it starts from the sums of the row groups before its own,
-// adds the rows of the slices before its own and walks its rows.  Out of place: other threads still read those counts.
+// one thread per (key, row group, slice of the group): it starts from the sums of the row groups before its own
+// and of the slices before its own in its group - the first sweep added both up - and walks its rows.
 __device__ __forceinline__ void offsets_body(const uint32_t *__restrict__ matrix, uint32_t *__restrict__ starts,
                                              uint32_t n_chunks, uint32_t n_keys,
                                              const uint32_t *__restrict__ partial, uint32_t item, uint32_t g_end0) {
     // item = (key, row group, slice of the group): a compute unit fetches a few tens of GB/s at most, so the
-    // matrix is spread over kOffsetSplit times as many workgroups as there are row groups x keys / block size; a
-    // thread re-reads the rows of the slices before its own instead of waiting for anybody.  (16 row groups of 8
-    // slices measured best on a 1280-chunk sweep: 32 x 4 is 2 % slower, 64 groups 13 %.)
+    // matrix is spread over kOffsetSplit times as many workgroups as there are row groups x keys / block size.
+    // (16 row groups of 8 slices measured best on a 1280-chunk sweep: 32 x 4 is 2 % slower, 64 groups 13 %.)
     const uint32_t key = item % n_keys, part = item / n_keys;
     const uint32_t rg = part / kOffsetSplit, sub = part % kOffsetSplit;
     if (rg >= kRowGroups) return;
     // pages that are not resident and first used after the incoming task's entry are never fetched, whatever the
     // cut turns out to be (g_cut <= g_end0): their columns get no offset and their start positions are never read
     if (key < n_keys / 2 && key >= g_end0) return;
-    uint32_t run = 0;
-    for (uint32_t before = 0; before < rg; ++before) run += partial[before * n_keys + key];
     const uint32_t rows = (n_chunks + kRowGroups - 1) / kRowGroups;
     const uint32_t rows_sub = (rows + kOffsetSplit - 1) / kOffsetSplit;
     const uint32_t g0 = rg * rows, g1 = min(n_chunks, g0 + rows);       // the row group
     const uint32_t w0 = min(g1, g0 + sub * rows_sub), w1 = min(g1, w0 + rows_sub);
+    // every load of the thread is asked for before the first is used: the sums in front of the slice, then its rows
+    uint32_t front[kRowGroups + kOffsetSplit];
+#pragma unroll
+    for (uint32_t j = 0; j < kRowGroups; ++j) front[j] = j < rg ? partial[(size_t)j * n_keys + key] : 0u;
+#pragma unroll
+    for (uint32_t j = 0; j < kOffsetSplit; ++j)
+        front[kRowGroups + j] = j < sub ? partial[(size_t)(kRowGroups + rg * kOffsetSplit + j) * n_keys + key] : 0u;
     constexpr uint32_t kRows = 16;
-    for (uint32_t w = g0; w < w0; w += kRows) {              // rows of the slices before this one
-        uint32_t v[kRows];
+    uint32_t v[kRows];
 #pragma unroll
-        for (uint32_t j = 0; j < kRows; ++j) v[j] = (w + j < w0) ? matrix[(size_t)(w + j) * n_keys + key] : 0u;
+    for (uint32_t j = 0; j < kRows; ++j) v[j] = (w0 + j < w1) ? matrix[(size_t)(w0 + j) * n_keys + key] : 0u;
+    uint32_t run = 0;
 #pragma unroll
-        for (uint32_t j = 0; j < kRows; ++j) run += v[j];
-    }
+    for (uint32_t j = 0; j < kRowGroups + kOffsetSplit; ++j) run += front[j];
     for (uint32_t w = w0; w < w1; w += kRows) {
-        uint32_t v[kRows];
+        if (w != w0) {
 #pragma unroll
-        for (uint32_t j = 0; j < kRows; ++j) v[j] = (w + j < w1) ? matrix[(size_t)(w + j) * n_keys + key] : 0u;
+            for (uint32_t j = 0; j < kRows; ++j) v[j] = (w + j < w1) ? matrix[(size_t)(w + j) * n_keys + key] : 0u;
+        }
 #pragma unroll
         for (uint32_t j = 0; j < kRows; ++j) {
             if (w + j < w1) starts[(size_t)(w + j) * n_keys + key] = run;
@@ -1312,7 +1331,7 @@ __global__ __launch_bounds__(kWave * kMaxWaves, 6) void k_emit(EmitArgs a, Sweep
 // (planning such a table is bound by launch latency, not by bandwidth).
 __global__ __launch_bounds__(kWave * kMaxWaves) void k_tail(SweepGeom sg, CutArgs ca, EmitArgs ea) {
     extern __shared__ uint32_t lds[];
-    count_body<false>(ea.page_table, ea.nu, sg, 0, lds, ca.groups, nullptr);
+    count_body<false>(ea.page_table, ea.nu, sg, 0, lds, ca.groups, nullptr, nullptr);
     __syncthreads();
     cut_body(ca, lds);
     __syncthreads();
@@ -1506,7 +1525,7 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         k_cut_offsets<<<1 + (items + cut_threads - 1) / cut_threads, cut_threads, cut_lds, st>>>(ca, c->matrix, c->matrix + c->matrix_cap, g.n_chunks, g.n_keys);
     }
     if (prof) CK(hipEventRecord(c->ev[3], st));
-    k_emit<<<g.n_chunks, threads, emit_lds, st>>>(ea, sg, c->partial, few_rows ? 0 : kRowGroups * g.n_keys);
+    k_emit<<<g.n_chunks, threads, emit_lds, st>>>(ea, sg, c->partial, few_rows ? 0 : kSumRows * g.n_keys);
     if (c->profiling) CK(hipEventRecord(c->ev[4], st));
     return hipGetLastError();
 }
