@@ -409,8 +409,19 @@ __global__ __launch_bounds__(kListThreads) void k_list_prepare(const ListPrep *_
             if (ok[j] && p[j] >= V) { bad = 1; ok[j] = false; }
             if (ok[j] && slot != nullptr && slot[p[j]] == kNone) { bad = 1; ok[j] = false; }
             if (ok[j]) {
+                // Repeats are dropped through a table of pairs of entries: an id goes into the first entry of its
+                // pair and moves what was there into the second.  Two popular ids that share a pair then both stay
+                // visible - with one entry each would throw the other out every time, and a gather's most popular
+                // pages would reach the merge once per repeat (twice the ids in the heaviest buckets, measured).
+                // An id is only ever dropped on finding itself, so whatever threads race here, one copy survives.
                 const uint32_t h = (p[j] * 2654435761u) >> (32 - kBinSeenBits);
-                if (atomicExch(&seen[h], p[j]) == p[j]) ok[j] = false;
+                if (seen[h ^ 1u] == p[j]) {
+                    ok[j] = false;
+                } else {
+                    const uint32_t was = atomicExch(&seen[h], p[j]);
+                    if (was == p[j]) ok[j] = false;
+                    else if (was != kNone) seen[h ^ 1u] = was;
+                }
             }
             const uint64_t keep = __ballot(ok[j]);
             if (keep) {
@@ -659,9 +670,8 @@ __device__ void paint_tile(const SweepGeom &sg, uint64_t t0, uint64_t t1, uint32
 // kPaintInRegisters the caller paints the tile in LDS instead (after a barrier of its own: paint_tile resets the
 // queue).
 constexpr uint32_t kPaintInRegisters = 16;
+// The queue is empty on entry (count_body resets it ahead of a barrier it needs anyway).
 __device__ uint32_t queue_ranges(const SweepGeom &sg, uint64_t t0, uint64_t t1, PaintLds &q) {
-    if (threadIdx.x == 0) { q.n_queued = 0; q.floor = sg.G; }
-    __syncthreads();
     constexpr uint32_t kPerThread = 4;
     for (uint32_t r0 = 0; r0 < sg.n_ranges; r0 += blockDim.x * kPerThread) {
 #pragma unroll
@@ -773,13 +783,14 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
                                            uint32_t *group_row, uint32_t *slice_row, const TileLists *tl = nullptr) {
     const uint32_t n_keys = 2 * (sg.G + 1);
     const uint32_t waves = blockDim.x / kWave, wave = threadIdx.x / kWave;
+    __shared__ PaintLds s_paint;
     for (uint32_t i = threadIdx.x; i < n_keys; i += blockDim.x) lds[i] = 0;
+    if (threadIdx.x == 0) { s_paint.n_queued = 0; s_paint.floor = sg.G; }     // queue_ranges expects it empty
     __syncthreads();
     const uint64_t p_begin = (uint64_t)chunk * sg.chunk_pages;
     const uint64_t p_end = min(sg.V, p_begin + sg.chunk_pages);
     const uint64_t tile_pages = (uint64_t)waves * sg.steps * kWave;
     uint32_t *paint = lds + count_paint_offset(n_keys);   // [tile_pages] when there are ranges to paint, 16-byte aligned
-    __shared__ PaintLds s_paint;
     const uint32_t lane = (uint32_t)lane_id();
     const uint4 none4 = {kNone, kNone, kNone, kNone}, zero4 = {0u, 0u, 0u, 0u};
     for (uint32_t round = 0; round < sg.rounds; ++round) {
@@ -901,7 +912,11 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
             }
             sweep_tile(tile_paint, tile_nu);
         }
-        if (sg.n_ranges || kLists) __syncthreads();       // the next tile repaints
+        if (round + 1 < sg.rounds && (sg.n_ranges || kLists)) {
+            __syncthreads();                              // the next tile repaints, and queues its ranges afresh
+            if (threadIdx.x == 0) { s_paint.n_queued = 0; s_paint.floor = sg.G; }
+            __syncthreads();
+        }
     }
     __syncthreads();
     for (uint32_t k = threadIdx.x; k < n_keys; k += blockDim.x) {
