@@ -39,10 +39,10 @@ HBM_PEAK_GBS = 8000.0
 # (profiles/k_migrate_c2_stencil_pmc_traffic.md).
 MIGRATE_TRAFFIC_RATIO = {"read": 1.0001, "write": 1.0018}
 # Same for all planning kernels of one plan on the planning-stress structure (list preparation included at its
-# per-plan share): 133.6 MiB measured against 251.9 MiB by the algorithmic count (profiles/planning_c5_structure_kernels_and_traffic.md); below 1 because
+# per-plan share): 127.4 MiB measured against 251.9 MiB by the algorithmic count (profiles/planning_c5_structure_kernels_and_traffic.md); below 1 because
 # range rules are painted in LDS and no longer cost a memory access per page touch, and the sweeps skip what they
 # can prove they do not need.
-PLAN_TRAFFIC_RATIO = 0.530
+PLAN_TRAFFIC_RATIO = 0.506
 WORKLOADS = {
     1: "c1-tiny-round-robin: 3 tasks, 64 KiB pages, pool 256 frames (16 MiB), footprint 24 MiB, timeslice 10 launches",
     2: "c2-stencil-sweep: 4 tasks x 3 arrays of 256 MiB, 2 MiB pages, pool 1024 frames (2 GiB), footprint 3 GiB "
