@@ -73,6 +73,45 @@ def test_many_commands_through_the_multi_kernel_cut(oracle_mod, monkeypatch, n_p
     assert lockstep(oracle_mod, trace, with_bytes=True, horizon="full", max_plans=3) == 3
 
 
+@pytest.mark.parametrize("n_ranges", [15, 16, 17, 70])
+@pytest.mark.parametrize("force_multi", [False, True])
+def test_ranges_per_tile_around_the_limit_of_the_register_path(oracle_mod, monkeypatch, n_ranges, force_multi):
+    """Up to 16 partial ranges of a tile are applied from registers, more are painted in LDS (queue of 64, then
+    in place): n short ranges inside one tile, long ranges that cover whole tiles and end inside others, and the
+    table's ragged end; the second plan has to evict part of what the first brought in."""
+    if force_multi:
+        monkeypatch.setenv("MSCHED_FORCE_MULTI_KERNEL", "1")
+    V, F, P = 6000, 3000, 64
+    trace = explicit_trace([[[0]], [[1]]], V, F, timeslice=4, page_shift=6)
+    g = GpuSide(trace)
+    o = make_oracle(oracle_mod, trace, with_bytes=False)
+    rng = np.random.default_rng(n_ranges)
+    try:
+        rule = [Rule(RULE_LINEAR, 0, (1,), P)]
+        kg, ko = g.ms.kernel_register(rule), o.kernel_register(rule)
+        for impl in (g.ms, o):
+            impl.launch_retire(0, 1)
+            impl.launch_retire(1, 1)
+        starts = rng.permutation(120)[:n_ranges - 1] * 4 + 20            # short ranges, 3 pages each, inside pages [20, 500)
+        cmds0 = [(int(a), 3) for a in starts] + [(2500, 1500)]           # and one long range further up
+        cmds1 = [(0, 2800), (4000, 100), (5990, 10)]                     # whole tiles and the short ranges' pages; elsewhere; the ragged end
+        for task, cmds, k in ((0, cmds0, (kg, ko)), (1, cmds1, (kg, ko))):
+            for a, n in cmds:
+                g.ms.launch_enqueue(task, k[0], [a * P, n], 2)
+                o.launch_enqueue(task, k[1], [a * P, n], 2)
+        for tl in ([(0, len(cmds0)), (1, 3)], [(1, 3), (0, len(cmds0))], [(0, 7), (1, 1)]):
+            po, pg = o.plan(tl), g.ms.plan(tl)
+            assert_same_plan(po, pg, tl)
+            o.migrate()
+            g.ms.migrate()
+            pto, foo = o.state()
+            ptg, fog = g.ms.state()
+            assert np.array_equal(pto, ptg) and np.array_equal(foo, fog)
+    finally:
+        g.close()
+        o.close()
+
+
 def test_next_use_epoch_wraps_cleanly(oracle_mod, monkeypatch):
     # the next-use array is never cleared between plans: entries carry a plan epoch that wraps
     # after 2^20 - 1 plans; start 5 plans before the wrap and run across it
