@@ -431,10 +431,15 @@ def test_a_plan_with_more_than_a_thousand_prepared_lists(oracle_mod, monkeypatch
         o.close()
 
 
-def test_lists_merged_in_the_sweep_more_pieces_than_one_staging_round(oracle_mod, monkeypatch):
+@pytest.mark.parametrize("layout", ["everywhere", "apart"])
+def test_lists_merged_in_the_sweep_more_pieces_than_one_staging_round(oracle_mod, monkeypatch, layout):
     """Full-size tiles (three sweep workgroups for 70 000 pages, the last tile ragged) and 402 commands whose lists
     of 60 000 ids are prepared as three pieces each: the sweep describes a bucket's 1206 segments in LDS in two
-    rounds.  Then a list with an id beyond the table, which the sweep of bucket 0 has to report."""
+    rounds.  Then a list with an id beyond the table, which the sweep of bucket 0 has to report.
+    "everywhere": every tile holds ids and dozens of short ranges (painted in LDS, lists merged on top).
+    "apart": the ids stay in the upper half of the table; most commands repeat one range (described once per
+    plan), a few bring long ranges of their own in the lower half, so the tiles there hold no ids and only a few
+    ranges (applied from registers), and one range reaches into the tiles with ids."""
     import torch
     from paper_2512_24637_amd import MSchedError
     monkeypatch.setenv("MSCHED_LIST_BINNED_MIN_IDS", "0")
@@ -446,7 +451,7 @@ def test_lists_merged_in_the_sweep_more_pieces_than_one_staging_round(oracle_mod
     rng = np.random.default_rng(23)
     try:
         # every command reads one window of a quarter of the table; the windows move with the command
-        lo = rng.integers(0, V - V // 4, (2, n_cmds))
+        lo = rng.integers(V // 2 if layout == "apart" else 0, V - V // 4, (2, n_cmds))
         ids = (lo[:, :, None] + rng.integers(0, V // 4, (2, n_cmds, n_ids))).astype(np.uint32)
         dev = torch.from_numpy(ids.view(np.int32)).cuda()
         kg = g.ms.kernel_register([Rule(RULE_LINEAR, 0, (1,), 4), Rule(RULE_LIST)])
@@ -457,6 +462,12 @@ def test_lists_merged_in_the_sweep_more_pieces_than_one_staging_round(oracle_mod
         for task in (0, 1):
             for i in range(n_cmds):
                 args = [int(rng.integers(0, V - 600)) * 64, int(rng.integers(1, 500)) * 16]
+                if layout == "apart":
+                    args = [1000 * 64, 300 * 16]
+                    if i % 40 == 7:
+                        args = [int(rng.integers(0, V // 2 - 9000)) * 64, int(rng.integers(3000, 9000)) * 16]
+                    if i == 100:
+                        args = [30000 * 64, 12000 * 16]
                 g.ms.launch_enqueue(task, kg, args, 2, ids_ptr=dev[task, i].data_ptr(), n_ids=n_ids)
                 o.launch_enqueue(task, ko, args, 2, ids=ids[task, i])
         for k, tl in enumerate(([(0, n_cmds), (1, n_cmds)], [(1, n_cmds), (0, n_cmds)], [(0, n_cmds), (1, n_cmds)])):
