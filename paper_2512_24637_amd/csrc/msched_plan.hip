@@ -377,6 +377,8 @@ __global__ __launch_bounds__(kListThreads) void k_list_reduce(ListArgs a) {
 //                   write the bucket starts and the ids grouped by bucket
 //   k_list_merge    per bucket: gather that bucket's ids from every piece of the plan, max-reduce them under
 //                   their commands' g in a 32 KiB LDS table, merge the table into the bucket's slice of nu[]
+//   k_count_lists   large tables, whose sweep tiles are exactly one bucket: the first sweep gathers the bucket's
+//                   ids itself, into its LDS tile, and nu[] is neither written nor read (count_body)
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kListThreads) void k_list_prepare(const ListPrep *__restrict__ prep, uint32_t n_buckets,
                                                                uint64_t V, const uint32_t *__restrict__ slot,
@@ -775,7 +777,7 @@ struct TileLists {
     const uint32_t *order;              // [n_chunks] the chunk of each workgroup (chunk_order_block)
 };
 constexpr int kFusedPieces = 4;
-constexpr uint32_t kStagePieces = 1024;  // segments of a bucket described in LDS at a time (16 bytes each)
+constexpr uint32_t kStagePieces = 512;   // segments of a bucket described in LDS at a time (16 bytes each)
 
 template <bool kLists>
 __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_table, const uint32_t *__restrict__ nu,
@@ -953,10 +955,13 @@ __global__ __launch_bounds__(kWave * kMaxWaves) void k_count(const uint32_t *__r
     count_body<false>(page_table, nu, sg, chunk, lds, matrix + (size_t)chunk * n_keys, group_row, slice_row);
 }
 
-// The first sweep with the id lists merged in (see count_body): twice the wavefronts on half the steps each, the
-// same tile, because a bucket with ids is mostly merging and the merge is a matter of wavefronts in flight.
+// The first sweep with the id lists merged in (see count_body).  At most 64 registers: with 44 KiB of LDS a
+// compute unit then holds three of these workgroups, a tile with ids next to two without.  (Measured on the
+// planning-stress structure: 1024 threads with half the steps each, two workgroups per compute unit, 0.6 us slower
+// per plan; 8 segments in flight per wavefront at 89 registers 2 us slower; 128 or 192 segments described at a
+// time, which fits a fourth workgroup, 1.8 and 2.5 us slower.)
 static_assert(kMaxWaves * kMaxSteps * kWave == (int)kBucketPages, "a full-size tile is one bucket");
-constexpr int kFusedThreads = 1024;
+constexpr int kFusedThreads = kWave * kMaxWaves;
 __global__ __launch_bounds__(kFusedThreads, 8) void k_count_lists(const uint32_t *__restrict__ page_table, SweepGeom sg,
                                                               TileLists tl, uint32_t *__restrict__ matrix,
                                                               uint32_t *__restrict__ partial) {
@@ -1521,7 +1526,7 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     }
     if (fuse_lists) {
         SweepGeom sc = sg;
-        sc.steps = g.steps * g.waves / (kFusedThreads / kWave);       // the same tile on the wider workgroup
+        sc.steps = g.steps * g.waves / (kFusedThreads / kWave);       // the same tile, whatever the workgroup's width
         TileLists tl;
         tl.src = c->list_src_stage; tl.n_src = g.n_list_sources; tl.n_buckets = g.n_buckets; tl.bucket_mark = c->bucket_mark;
         tl.order = c->bucket_mark + kMaxBuckets;
