@@ -475,7 +475,7 @@ constexpr uint32_t kMergeHead = 4 * kWave;          // ids of a segment its wave
 // The segments of one bucket, staged in LDS: for piece s its first id, its length and the value `code[s]` that goes
 // into the bucket's table.  `put(id, code)` is the LDS atomic of the caller (the largest code or the smallest
 // command wins, depending on what the table holds).
-template <int kPieces, class Put>
+template <int kPieces, int kRowsPerPass, class Put>
 __device__ __forceinline__ void merge_segments(const uint32_t *const *first, const uint32_t *len, const uint32_t *code,
                                                uint32_t n_src, bool any_long, Put put) {
     const uint32_t lane = (uint32_t)lane_id(), wave = threadIdx.x / kWave, waves = blockDim.x / kWave;
@@ -492,16 +492,16 @@ __device__ __forceinline__ void merge_segments(const uint32_t *const *first, con
         uint32_t n_max = 0;
 #pragma unroll
         for (int j = 0; j < kPieces; ++j) n_max = max(n_max, n[j]);
-        // two rows of 64 ids from each of the segments per pass: every load of a pass is issued before its first atomic
-        for (uint32_t r0 = 0; r0 < n_max; r0 += 2 * kWave) {
-            uint32_t id[2][kPieces];
+        // kRowsPerPass rows of 64 ids from each of the segments per pass: every load of a pass is issued before its first atomic
+        for (uint32_t r0 = 0; r0 < n_max; r0 += kRowsPerPass * kWave) {
+            uint32_t id[kRowsPerPass][kPieces];
 #pragma unroll
-            for (int q = 0; q < 2; ++q)
+            for (int q = 0; q < kRowsPerPass; ++q)
 #pragma unroll
                 for (int j = 0; j < kPieces; ++j)
                     id[q][j] = r0 + q * kWave + lane < n[j] ? ptr[j][r0 + q * kWave + lane] : kNone;
 #pragma unroll
-            for (int q = 0; q < 2; ++q)
+            for (int q = 0; q < kRowsPerPass; ++q)
 #pragma unroll
                 for (int j = 0; j < kPieces; ++j)
                     if (id[q][j] != kNone) put(id[q][j], e[j]);
@@ -550,7 +550,7 @@ __global__ __launch_bounds__(kListThreads) void k_list_merge(MergeArgs a) {
     const int any_ids = __syncthreads_or(longest != 0);
     const int any_long = __syncthreads_or(longest > kMergeHead);
     if (!any_ids) return;
-    merge_segments<kMergePieces>(first, len, enc, a.n_src, any_long != 0,
+    merge_segments<kMergePieces, 2>(first, len, enc, a.n_src, any_long != 0,
                    [&](uint32_t id, uint32_t code) { atomicMax(&tab[id & (kBucketPages - 1)], code); });   // never 0
     __syncthreads();
     const uint64_t p0 = (uint64_t)b << kBucketShift;
@@ -776,7 +776,8 @@ struct TileLists {
     const uint32_t *bucket_mark;        // [n_buckets] does any prepared piece hold an id of this bucket?
     const uint32_t *order;              // [n_chunks] the chunk of each workgroup (chunk_order_block)
 };
-constexpr int kFusedPieces = 4;
+constexpr int kFusedPieces = 6;         // segments in flight per wavefront of the sweep, one row of 64 ids each per pass: what
+constexpr int kFusedRows = 1;           // 64 registers hold (a segment of one bucket and piece is a few dozen ids; 4 x 2 rows: +0.7 us)
 constexpr uint32_t kStagePieces = 512;   // segments of a bucket described in LDS at a time (16 bytes each)
 
 template <bool kLists>
@@ -896,7 +897,7 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
                         const int any_ids = __syncthreads_or(longest != 0);
                         const int any_long = __syncthreads_or(longest > kMergeHead);
                         if (any_ids)
-                            merge_segments<kFusedPieces>(first, len, cmd, n_here, any_long != 0,
+                            merge_segments<kFusedPieces, kFusedRows>(first, len, cmd, n_here, any_long != 0,
                                            [&](uint32_t id, uint32_t g) { atomicMin(&paint[id & (kBucketPages - 1)], g); });
                         __syncthreads();                   // the next pieces overwrite the descriptions; the tile is read below
                     }
