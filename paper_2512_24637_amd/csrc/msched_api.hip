@@ -152,7 +152,7 @@ void free_ctx(msched_ctx *c) {
     if (c->list_ahead_host) (void)hipHostFree(c->list_ahead_host);
     if (c->ahead_ev) (void)hipEventDestroy(c->ahead_ev);
     void *dev[] = {c->page_table, c->frame_owner, c->nu, c->slot, c->evict_pages, c->evict_frames, c->fetch_pages,
-                   c->fetch_frames, c->flags, c->matrix, c->partial, c->offsets, c->hdr_dev, c->kernels_dev,
+                   c->fetch_frames, c->flags, c->matrix, c->partial, c->chunk_hint, c->offsets, c->hdr_dev, c->kernels_dev,
                    c->query_buf, c->cmd_dev, c->list_bucket_fill, c->list_pairs};
     for (void *p : dev) if (p) (void)hipFree(p);
     if (c->hdr_host) (void)hipHostFree(c->hdr_host);
@@ -225,6 +225,7 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     c->list_ahead = (uint32_t)env_u32("MSCHED_LIST_AHEAD", 0, 65536, 128);
     c->plan_spin = (uint32_t)env_u32("MSCHED_PLAN_SPIN", 0, 1, 1);
     c->fuse_lists = (uint32_t)env_u32("MSCHED_FUSE_LISTS", 0, 1, 1);
+    c->order_emit = (uint32_t)env_u32("MSCHED_ORDER_EMIT", 0, 1, 1);
     c->force_multi_kernel = env_u32("MSCHED_FORCE_MULTI_KERNEL", 0, 1, 0) != 0;
     c->list_binned_min_ids = (uint64_t)env_u32("MSCHED_LIST_BINNED_MIN_IDS", 0, 1 << 30, 262144);
     c->list_b0 = (uint32_t)env_u32("MSCHED_LIST_B0", 0, 4096, 4);
@@ -246,6 +247,7 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     ALLOC(c->flags, 256);
     ALLOC(c->offsets, (size_t)2 * (MSCHED_MAX_TIMELINE_COMMANDS + 1) * 4);
     ALLOC(c->hdr_dev, sizeof(PlanHeader));
+    ALLOC(c->chunk_hint, (size_t)2 * kMaxChunks * 4);
     // row-group sums of the count matrix: the counting sweep adds into them, k_offsets clears what it read
     ALLOC(c->partial, (size_t)kSumRows * 2 * (MSCHED_MAX_TIMELINE_COMMANDS + 1) * 4);
     if (rc == MSCHED_OK && (e = hipMemset(c->partial, 0, (size_t)kSumRows * 2 * (MSCHED_MAX_TIMELINE_COMMANDS + 1) * 4)) != hipSuccess) fail(e);

@@ -146,6 +146,7 @@ struct msched_ctx {
     uint32_t *evict_pages = nullptr, *evict_frames = nullptr, *fetch_pages = nullptr, *fetch_frames = nullptr;
     uint32_t *flags = nullptr;                  // device status word
     uint32_t *matrix = nullptr; size_t matrix_cap = 0;       // [n_chunks][n_keys] counts; behind them [matrix_cap...) the chunks' start positions
+    uint32_t *chunk_hint = nullptr;                          // [2][kMaxChunks]: what the first sweep saw per chunk for the second; the second sweep's chunk order
     uint32_t *partial = nullptr;                             // [kSumRows][n_keys] sums by row group, then by slice; all zero between plans
     uint32_t *offsets = nullptr;                // [2 * (MAX_G + 1)] per-class output offsets
     msched::PlanHeader *hdr_dev = nullptr;      // device
@@ -179,6 +180,7 @@ struct msched_ctx {
     hipStream_t poll_stream = nullptr;          // msched_progress works here, beside the migration
     uint32_t early_tag = 0;                     // nonzero tag of the latest early migration
     uint32_t hdr_seq = 0;                       // stamp of the header the host is waiting for (never 0)
+    uint32_t order_emit = 1;                    // the second sweep takes the chunks it may have to list pages of first (MSCHED_ORDER_EMIT)
     uint32_t fuse_lists = 1;                    // prepared id lists are merged inside the first sweep (MSCHED_FUSE_LISTS, 0 = own kernel)
     uint32_t plan_spin = 1;                     // msched_plan returns when the counts have landed, not when the lists are complete
     bool plan_timing_pending = false;           // device times of the last plan have not been read from their events yet

@@ -36,6 +36,7 @@ __device__ __forceinline__ uint64_t lanes_below() { return (1ull << lane_id()) -
 struct ChunkOrder {
     const uint32_t *bucket_mark;        // null: no order wanted
     uint32_t n_buckets, n_chunks, buckets_per_chunk;
+    uint32_t first_rank;                // marks from this value on put a chunk first; smaller non-zero ones second
     uint32_t *order;                    // [n_chunks] chunks that hold a bucket with ids first, then the others
 };
 __device__ void chunk_order_block(const ChunkOrder &o);
@@ -599,6 +600,9 @@ struct SweepGeom {
     const uint32_t *slot;     // page -> backing slot (or null): a wanted page without one is an error
     uint32_t *flags;
     uint16_t *key16;          // [V] class key of every page, written by the first sweep for the second
+    uint32_t g_end0;          // commands of the first timeline entry: only their pages can be fetched
+    uint32_t *emit_hint;      // [n_chunks] or null: what the first sweep saw in a chunk that the second may have to list
+                              // (2: a page that may be fetched, 1: a resident page the first entry does not use)
 };
 constexpr uint16_t kNoKey16 = 0xffff;                  // keys are below 2 * (MSCHED_MAX_TIMELINE_COMMANDS + 1) = 6144
 
@@ -789,6 +793,7 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
     __shared__ PaintLds s_paint;
     for (uint32_t i = threadIdx.x; i < n_keys; i += blockDim.x) lds[i] = 0;
     if (threadIdx.x == 0) { s_paint.n_queued = 0; s_paint.floor = sg.G; }     // queue_ranges expects it empty
+    if (threadIdx.x == 0 && sg.emit_hint != nullptr) sg.emit_hint[chunk] = 0;   // raised below, behind barriers
     __syncthreads();
     const uint64_t p_begin = (uint64_t)chunk * sg.chunk_pages;
     const uint64_t p_end = min(sg.V, p_begin + sg.chunk_pages);
@@ -922,6 +927,7 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
         }
     }
     __syncthreads();
+    uint32_t hint = 0;
     for (uint32_t k = threadIdx.x; k < n_keys; k += blockDim.x) {
         const uint32_t v = lds[k];
         row[k] = v;
@@ -929,6 +935,13 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
             atomicAdd(&group_row[k], v);                                // few keys are non-zero
             atomicAdd(&slice_row[k], v);
         }
+        if (v) hint = max(hint, k < sg.g_end0 ? 2u : (k >= sg.G + 1 + sg.g_end0 ? 1u : 0u));
+    }
+    // Most chunks of a large table give the second sweep nothing to list, and those that do take it several times
+    // longer: it starts with them (chunk_order_block in the cut kernel).  One atomic per wavefront that saw something.
+    if (sg.emit_hint != nullptr) {
+        const bool two = __ballot(hint == 2u) != 0, one = __ballot(hint == 1u) != 0;
+        if (lane_id() == 0 && (two || one)) atomicMax(&sg.emit_hint[chunk], two ? 2u : 1u);
     }
 }
 
@@ -1008,23 +1021,30 @@ __device__ uint32_t block_exclusive_scan(uint32_t *a, uint32_t n, uint32_t *wave
 // One workgroup of 256 threads; the marks are sticky, so an order made from marks a later preparation adds to
 // is still a permutation - only less good.
 __device__ void chunk_order_block(const ChunkOrder &o) {
-    __shared__ uint32_t s_cnt[256], s_wave[4];
+    __shared__ uint32_t s_cnt[1024], s_wave[16];
     const uint32_t per = (o.n_chunks + blockDim.x - 1) / blockDim.x;      // at most kMaxChunks / 256 = 8
     const uint32_t c0 = min(o.n_chunks, threadIdx.x * per), c1 = min(o.n_chunks, c0 + per);
-    uint32_t mask = 0;
+    uint32_t first = 0, second = 0;                                        // my chunks of the first and of the second rank
     for (uint32_t c = c0; c < c1; ++c) {
-        uint32_t any = 0;
+        uint32_t rank = 0;                                                 // the largest mark among the chunk's buckets
         const uint32_t b1 = min(o.n_buckets, (c + 1) * o.buckets_per_chunk);
-        for (uint32_t b = c * o.buckets_per_chunk; b < b1; ++b) any |= o.bucket_mark[b];
-        if (any) mask |= 1u << (c - c0);
+        for (uint32_t b = c * o.buckets_per_chunk; b < b1; ++b) rank = max(rank, o.bucket_mark[b]);
+        if (rank >= o.first_rank) first |= 1u << (c - c0);
+        else if (rank != 0) second |= 1u << (c - c0);
     }
-    s_cnt[threadIdx.x] = __popc(mask);
+    s_cnt[threadIdx.x] = __popc(first);
     __syncthreads();
-    const uint32_t n_marked = block_exclusive_scan(s_cnt, blockDim.x, s_wave);
-    uint32_t before = s_cnt[threadIdx.x];                                  // marked chunks below c
+    const uint32_t n_first = block_exclusive_scan(s_cnt, blockDim.x, s_wave);
+    uint32_t before_first = s_cnt[threadIdx.x];                            // chunks of the first rank below c
+    __syncthreads();
+    s_cnt[threadIdx.x] = __popc(second);
+    __syncthreads();
+    const uint32_t n_second = block_exclusive_scan(s_cnt, blockDim.x, s_wave);
+    uint32_t before_second = s_cnt[threadIdx.x];
     for (uint32_t c = c0; c < c1; ++c) {
-        if ((mask >> (c - c0)) & 1u) o.order[before++] = c;
-        else o.order[n_marked + (c - before)] = c;
+        if ((first >> (c - c0)) & 1u) o.order[before_first++] = c;
+        else if ((second >> (c - c0)) & 1u) o.order[n_first + before_second++] = c;
+        else o.order[n_first + n_second + (c - before_first - before_second)] = c;
     }
 }
 static_assert(kMaxChunks <= 256 * 32, "a thread of chunk_order_block keeps its chunks' marks in one word");
@@ -1198,9 +1218,11 @@ __device__ __forceinline__ void offsets_body(const uint32_t *__restrict__ matrix
 // The cut (one workgroup, three short scans) and the column prefixes (wide) need the same input,
 // the per-key sums of the row groups, and nothing from each other: one launch, block 0 cuts.
 __global__ __launch_bounds__(1024) void k_cut_offsets(CutArgs a, const uint32_t *__restrict__ matrix,
-                                                        uint32_t *__restrict__ starts, uint32_t n_chunks, uint32_t n_keys) {
+                                                        uint32_t *__restrict__ starts, uint32_t n_chunks, uint32_t n_keys,
+                                                        ChunkOrder co) {
     extern __shared__ uint32_t lds[];
     if (blockIdx.x == 0) { cut_body(a, lds); return; }
+    if (co.bucket_mark != nullptr && blockIdx.x == gridDim.x - 1) { chunk_order_block(co); return; }   // the extra workgroup
     offsets_body(matrix, starts, n_chunks, n_keys, a.groups, (blockIdx.x - 1) * blockDim.x + threadIdx.x, a.g_end0);
 }
 
@@ -1341,11 +1363,11 @@ __device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg
 }
 
 __global__ __launch_bounds__(kWave * kMaxWaves, 6) void k_emit(EmitArgs a, SweepGeom sg, uint32_t *__restrict__ partial,
-                                                                uint32_t n_partial) {
+                                                                uint32_t n_partial, const uint32_t *__restrict__ order) {
     extern __shared__ uint32_t lds[];
     // the row-group sums have been read by the cut: the next plan's first sweep adds into them again
     for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n_partial; i += gridDim.x * blockDim.x) partial[i] = 0;
-    emit_body(a, sg, chunk_of_block(blockIdx.x, gridDim.x), lds);
+    emit_body(a, sg, order != nullptr ? order[blockIdx.x] : chunk_of_block(blockIdx.x, gridDim.x), lds);
 }
 
 // Page tables small enough for one workgroup: count, cut, emit and frame assignment in one launch
@@ -1459,8 +1481,8 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         const bool copy_ranges = g.n_ranges && !g.single;
         // prepared id lists and painted ranges together need no record on the device: only the two small tables travel
         const uint32_t n_records = (g.painted && g.list_prepared) ? 0u : g.G;
-        ChunkOrder co{nullptr, 0, 0, 0, nullptr};
-        if (fuse_lists) co = ChunkOrder{c->bucket_mark, g.n_buckets, g.n_chunks, g.rounds, c->bucket_mark + kMaxBuckets};
+        ChunkOrder co{nullptr, 0, 0, 0, 0, nullptr};
+        if (fuse_lists) co = ChunkOrder{c->bucket_mark, g.n_buckets, g.n_chunks, g.rounds, 1, c->bucket_mark + kMaxBuckets};
         if (stage)
             k_stage<<<(std::max<uint32_t>(std::max(n_records * 8, g.n_ranges + g.n_list_sources), 1u) + 255) / 256 + (fuse_lists ? 1 : 0), 256, 0, st>>>(
                 c->cmd_ptrs_dev, n_records, c->cmd_dev, c->list_bucket_fill, g.list_binned ? g.n_buckets * 8 : 0,
@@ -1500,6 +1522,9 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     sg.n_ranges = g.n_ranges; sg.use_nu = g.use_nu ? 1u : 0u;
     sg.bucket_mark = (g.painted && g.list_prepared) ? c->bucket_mark : nullptr;   // nothing but prepared lists wrote nu[] for this plan
     sg.slot = c->slot; sg.flags = c->flags; sg.key16 = c->key16;
+    // the second sweep's order: only where the cut kernel has its wide part to carry the extra workgroup
+    const bool order_emit = c->order_emit && !g.single && g.n_chunks > kRowGroups;
+    sg.g_end0 = g.g_end0; sg.emit_hint = order_emit ? c->chunk_hint : nullptr;
     // one workgroup reads the range list where the host wrote it; many read a device copy
     sg.ranges = g.single ? c->ranges_host_dev : c->ranges_dev;
     if (prof) CK(hipEventRecord(c->ev[1], st));
@@ -1543,10 +1568,14 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         k_cut<<<1, cut_threads, cut_lds, st>>>(ca);
     } else {
         const uint32_t items = g.n_keys * kRowGroups * kOffsetSplit;
-        k_cut_offsets<<<1 + (items + cut_threads - 1) / cut_threads, cut_threads, cut_lds, st>>>(ca, c->matrix, c->matrix + c->matrix_cap, g.n_chunks, g.n_keys);
+        ChunkOrder eo{nullptr, 0, 0, 0, 0, nullptr};
+        if (order_emit) eo = ChunkOrder{c->chunk_hint, g.n_chunks, g.n_chunks, 1, 2, c->chunk_hint + kMaxChunks};
+        k_cut_offsets<<<1 + (items + cut_threads - 1) / cut_threads + (order_emit ? 1 : 0), cut_threads, cut_lds, st>>>(
+            ca, c->matrix, c->matrix + c->matrix_cap, g.n_chunks, g.n_keys, eo);
     }
     if (prof) CK(hipEventRecord(c->ev[3], st));
-    k_emit<<<g.n_chunks, threads, emit_lds, st>>>(ea, sg, c->partial, few_rows ? 0 : kSumRows * g.n_keys);
+    k_emit<<<g.n_chunks, threads, emit_lds, st>>>(ea, sg, c->partial, few_rows ? 0 : kSumRows * g.n_keys,
+                                                  order_emit ? c->chunk_hint + kMaxChunks : nullptr);
     if (c->profiling) CK(hipEventRecord(c->ev[4], st));
     return hipGetLastError();
 }
