@@ -935,7 +935,9 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
             atomicAdd(&group_row[k], v);                                // few keys are non-zero
             atomicAdd(&slice_row[k], v);
         }
-        if (v) hint = max(hint, k < sg.g_end0 ? 2u : (k >= sg.G + 1 + sg.g_end0 ? 1u : 0u));
+        // first: a page that may be fetched, or a resident one whose next use lies in the last quarter of the timeline
+        // (victims are taken from the far end); second: any other resident page the first entry does not use
+        if (v) hint = max(hint, (k < sg.g_end0 || k >= 2 * sg.G + 1 - sg.G / 4) ? 2u : (k >= sg.G + 1 + sg.g_end0 ? 1u : 0u));
     }
     // Most chunks of a large table give the second sweep nothing to list, and those that do take it several times
     // longer: it starts with them (chunk_order_block in the cut kernel).  One atomic per wavefront that saw something.
