@@ -334,10 +334,10 @@ def test_allocation_granularity_ablation_runs_bit_exact(oracle_mod):
                                  {"MSCHED_PAINT": "0", "MSCHED_LIST_PREPARED": "0"},
                                  {"MSCHED_LIST_CACHE_MB": "1"}, {"MSCHED_LIST_AHEAD": "0"}, {"MSCHED_PLAN_SPIN": "0"},
                                  {"MSCHED_MAX_CHUNKS": "16"}, {"MSCHED_MAX_CHUNKS": "16", "MSCHED_FUSE_LISTS": "0"},
-                                 {"MSCHED_MAX_CHUNKS": "16", "MSCHED_LIST_AHEAD": "0"}],
+                                 {"MSCHED_MAX_CHUNKS": "16", "MSCHED_LIST_AHEAD": "0"}, {"MSCHED_ORDER_EMIT": "0"}],
                          ids=["scatter-ranges", "bin-per-plan", "both-earlier-paths", "one-megabyte-ring", "no-look-ahead",
                               "plan-waits-for-the-stream", "lists-merged-in-the-sweep", "full-size-tiles-own-merge",
-                              "lists-merged-in-the-sweep-no-look-ahead"])
+                              "lists-merged-in-the-sweep-no-look-ahead", "second-sweep-in-strided-order"])
 def test_earlier_planning_paths_stay_bit_exact(oracle_mod, monkeypatch, env):
     """Range pages scattered into the next-use array instead of painted, id lists binned from scratch in every
     plan instead of prepared once per command, a ring too small for the prepared lists (which makes plans fall
@@ -345,7 +345,8 @@ def test_earlier_planning_paths_stay_bit_exact(oracle_mod, monkeypatch, env):
     behind the previous migration, and a plan call that waits for the whole stream instead of the stamped counts.
     With at most 16 sweep workgroups the scaled tables get the full-size tiles (one bucket of id lists each) of
     the large ones, where the first sweep merges the prepared lists itself - or, switched off, leaves that to the
-    merge kernel."""
+    merge kernel.  Last, the second sweep taking its chunks in the strided order of the first instead of those
+    that may list pages first."""
     monkeypatch.setenv("MSCHED_LIST_BINNED_MIN_IDS", "0")
     for k, v in env.items():
         monkeypatch.setenv(k, v)
