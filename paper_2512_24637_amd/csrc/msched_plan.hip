@@ -899,11 +899,9 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
                             cmd[s] = S.g;
                             longest = max(longest, hi - lo);
                         }
-                        const int any_ids = __syncthreads_or(longest != 0);
-                        const int any_long = __syncthreads_or(longest > kMergeHead);
-                        if (any_ids)
-                            merge_segments<kFusedPieces, kFusedRows>(first, len, cmd, n_here, any_long != 0,
-                                           [&](uint32_t id, uint32_t g) { atomicMin(&paint[id & (kBucketPages - 1)], g); });
+                        const int any_long = __syncthreads_or(longest > kMergeHead);     // also the barrier behind the descriptions
+                        merge_segments<kFusedPieces, kFusedRows>(first, len, cmd, n_here, any_long != 0,
+                                       [&](uint32_t id, uint32_t g) { atomicMin(&paint[id & (kBucketPages - 1)], g); });
                         __syncthreads();                   // the next pieces overwrite the descriptions; the tile is read below
                     }
                     sweep_tile(kPaintLds, false);
