@@ -194,9 +194,19 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
         ((uintptr_t)cfg->hbm_pool & 15) || ((uintptr_t)cfg->host_store & 15))
         return MSCHED_E_INVAL;
     if (!cfg->host_slot && cfg->n_host_slots < cfg->n_virtual_pages) return MSCHED_E_INVAL;
-    if (cfg->host_slot)
-        for (uint64_t p = 0; p < cfg->n_virtual_pages; ++p)
-            if (cfg->host_slot[p] != MSCHED_NO_SLOT && cfg->host_slot[p] >= cfg->n_host_slots) return MSCHED_E_RANGE;
+    if (cfg->host_slot) {
+        // two pages that shared a slot would overwrite each other's backing bytes on eviction
+        std::vector<uint64_t> taken;
+        const int rc_map = guarded([&]() -> int { taken.assign((cfg->n_host_slots + 63) / 64, 0); return MSCHED_OK; });
+        if (rc_map) return rc_map;
+        for (uint64_t p = 0; p < cfg->n_virtual_pages; ++p) {
+            const uint64_t s = cfg->host_slot[p];
+            if (s == MSCHED_NO_SLOT) continue;
+            if (s >= cfg->n_host_slots) return MSCHED_E_RANGE;
+            if (taken[s >> 6] & (1ull << (s & 63))) return MSCHED_E_INVAL;
+            taken[s >> 6] |= 1ull << (s & 63);
+        }
+    }
     msched_ctx *c = new (std::nothrow) msched_ctx();
     if (!c) return MSCHED_E_NOMEM;
     const int rc_tables = guarded([&]() -> int {
@@ -227,6 +237,7 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     c->fuse_lists = (uint32_t)env_u32("MSCHED_FUSE_LISTS", 0, 1, 1);
     c->order_emit = (uint32_t)env_u32("MSCHED_ORDER_EMIT", 0, 1, 1);
     c->force_multi_kernel = env_u32("MSCHED_FORCE_MULTI_KERNEL", 0, 1, 0) != 0;
+    c->no_large_lds = env_u32("MSCHED_NO_LARGE_LDS", 0, 1, 0) != 0;
     c->list_binned_min_ids = (uint64_t)env_u32("MSCHED_LIST_BINNED_MIN_IDS", 0, 1 << 30, 262144);
     c->list_b0 = (uint32_t)env_u32("MSCHED_LIST_B0", 0, 4096, 4);
     c->list_b1 = std::max(c->list_b0, (uint32_t)env_u32("MSCHED_LIST_B1", 0, 4096, 32));
@@ -348,8 +359,13 @@ int msched_launch_enqueue(msched_ctx *c, uint32_t task, uint32_t kernel_id, cons
     if (rc) return rc;
     TaskQueue &t = c->tasks[task];
     if (t.n - t.base == t.cap) {
-        // Grow the pinned record array, dropping retired records.  No kernel can be reading it:
-        // msched_plan returns only after its kernels have finished.
+        // Grow the pinned record array, dropping retired records.  Kernels read queue records only ahead of the cut
+        // of a plan (staging, expansion, id-list binning), and msched_plan returns after the cut has stamped its
+        // header; what msched_migrate queues behind the copy (id-list preparation) reads the caller's id arrays
+        // and a table of its own, never a record.  So nothing that is still queued or running can hold an address
+        // into the old array - and the stream is drained here all the same, so that this stays true if a later
+        // kernel of a plan ever reads records: growing a queue is rare, a wait costs nothing then.
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
         const size_t live = t.n - t.cursor;
         const size_t ncap = std::max<size_t>(256, live * 2);
         CmdRec *nr = nullptr, *nd = nullptr;

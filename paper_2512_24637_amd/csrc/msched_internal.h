@@ -120,6 +120,7 @@ struct msched_ctx {
     std::vector<const msched::CmdRec *> plan_recs;   // host addresses of this plan's records, in g order
     std::vector<SeenEntry> seen;                // open-addressing table of region signatures, stamped per plan
     bool force_multi_kernel = false;            // test hook: never use the fused single-workgroup tail
+    bool no_large_lds = false;                  // MSCHED_NO_LARGE_LDS: never ask for more than the default dynamic LDS
     bool has_list_rule = false;                 // some registered kernel has a LIST rule
     // binned id lists (allocated on first use)
     uint32_t *list_bucket_fill = nullptr;       // [kMaxBuckets][8]

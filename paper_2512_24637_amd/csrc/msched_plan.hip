@@ -1530,7 +1530,7 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     if (prof) CK(hipEventRecord(c->ev[1], st));
     const uint32_t threads = g.waves * kWave;
     const size_t paint_lds = g.n_ranges ? (size_t)g.waves * g.steps * kWave * 4 : 0;
-    if (!getenv("MSCHED_NO_LARGE_LDS")) CK(allow_large_lds());
+    if (!c->no_large_lds) CK(allow_large_lds());
     const bool few_rows = g.n_chunks <= kRowGroups;          // the matrix rows are the row groups
     CutArgs ca;
     ca.groups = few_rows ? c->matrix : c->partial; ca.n_groups = few_rows ? g.n_chunks : kRowGroups;
