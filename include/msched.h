@@ -40,7 +40,8 @@ enum {
     MSCHED_E_WSET_TOO_LARGE = -4,  /* the first command of the incoming task alone needs more than n_frames pages */
     MSCHED_E_STALE_PLAN = -5,      /* migrate with a plan that is not the latest, or already carried out */
     MSCHED_E_NOMEM = -6,
-    MSCHED_E_HIP = -7              /* a HIP call failed; see msched_last_hip_error() */
+    MSCHED_E_HIP = -7,             /* a HIP call failed; see msched_last_hip_error() */
+    MSCHED_E_TOO_LARGE = -8        /* request larger than a fixed-size buffer of the library (msched_pagetable_query_static) */
 };
 
 typedef struct msched_ctx msched_ctx;          /* opaque, library-owned */
@@ -162,6 +163,20 @@ int msched_migrate(msched_ctx *ctx, const msched_plan_t *plan);
 
 /* Frame of each page, or MSCHED_NOT_RESIDENT.  page_ids: HOST, out: HOST.  Waits for the stream. */
 int msched_pagetable_query(msched_ctx *ctx, const uint64_t *page_ids, uint32_t n, uint32_t *out);
+
+/*
+ * msched_pagetable_query for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arguments, same result, but the ids and the answers are
+ * staged in a fixed device array that is part of the library's code object, so the call never allocates or
+ * frees memory, on the device or on the host, and never grows a buffer of the context.
+ * n <= MSCHED_QUERY_STATIC_MAX, else MSCHED_E_TOO_LARGE (nothing is done).  Each GPU holds one copy of the
+ * array (MSCHED_QUERY_STATIC_MAX * 12 bytes) from the first msched_create on it until the process ends.  Every
+ * call on a GPU, from any context, uses that one array: calls that overlap on one GPU race (callers serialise
+ * them; one context is single-threaded anyway).  Nothing in the array has to start at zero: a call overwrites
+ * the n ids and n answers it uses and reads nothing else.  Waits for the stream like msched_pagetable_query.
+ */
+#define MSCHED_QUERY_STATIC_MAX 65536u
+int msched_pagetable_query_static(msched_ctx *ctx, const uint64_t *page_ids, uint32_t n, uint32_t *out);
 
 /* Copy the lists of the latest plan to HOST arrays (any may be NULL) of n_evict / n_fetch entries. */
 int msched_plan_copy_lists(msched_ctx *ctx, const msched_plan_t *plan, uint32_t *evict_pages,

@@ -10,11 +10,12 @@ import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 NOT_RESIDENT = 0xFFFFFFFF
+QUERY_STATIC_MAX = 65536
 PHASES = ("expand", "count", "cut", "emit", "migrate", "plan", "host_prep", "host_launch", "host_wait")
 EXPORTED_SYMBOLS = (
     "msched_create", "msched_destroy", "msched_kernel_register", "msched_task_create",
     "msched_launch_enqueue", "msched_launch_retire", "msched_plan", "msched_migrate",
-    "msched_pagetable_query", "msched_plan_copy_lists", "msched_state_copy",
+    "msched_pagetable_query", "msched_pagetable_query_static", "msched_plan_copy_lists", "msched_state_copy",
     "msched_set_profiling", "msched_get_phase_ms", "msched_strerror", "msched_last_hip_error",
     "msched_analyze", "msched_set_early_start", "msched_plan_ready_need", "msched_progress",
 )
@@ -57,7 +58,7 @@ assert C.sizeof(_Rule) == 48
 
 class MSchedError(RuntimeError):
     NAMES = {-1: "E_INVAL", -2: "E_RANGE", -3: "E_OVERFLOW", -4: "E_WSET_TOO_LARGE",
-             -5: "E_STALE_PLAN", -6: "E_NOMEM", -7: "E_HIP"}
+             -5: "E_STALE_PLAN", -6: "E_NOMEM", -7: "E_HIP", -8: "E_TOO_LARGE"}
 
     def __init__(self, code, text="", hip=0):
         self.code, self.name, self.hip = code, self.NAMES.get(code, "?"), hip
@@ -95,6 +96,7 @@ def load_library():
         "msched_plan": [vp, C.POINTER(_TimelineEntry), u32, C.POINTER(_Plan)],
         "msched_migrate": [vp, C.POINTER(_Plan)],
         "msched_pagetable_query": [vp, vp, u32, vp],
+        "msched_pagetable_query_static": [vp, vp, u32, vp],
         "msched_plan_copy_lists": [vp, C.POINTER(_Plan), vp, vp, vp, vp],
         "msched_state_copy": [vp, vp, vp],
         "msched_set_profiling": [vp, C.c_int],
@@ -268,6 +270,13 @@ class MSched:
         pages = np.ascontiguousarray(pages, np.uint64)
         out = np.zeros(max(pages.shape[0], 1), np.uint32)
         self._check(self.lib.msched_pagetable_query(self.h, _np_ptr(pages), pages.shape[0], _np_ptr(out)))
+        return out[:pages.shape[0]]
+
+    def pagetable_query_static(self, pages) -> np.ndarray:
+        """pagetable_query through the library's static staging array (no allocation; at most QUERY_STATIC_MAX ids)."""
+        pages = np.ascontiguousarray(pages, np.uint64)
+        out = np.zeros(max(pages.shape[0], 1), np.uint32)
+        self._check(self.lib.msched_pagetable_query_static(self.h, _np_ptr(pages), pages.shape[0], _np_ptr(out)))
         return out[:pages.shape[0]]
 
     def state(self):

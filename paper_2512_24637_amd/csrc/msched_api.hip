@@ -246,6 +246,9 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     int rc = MSCHED_OK;
     auto fail = [&](hipError_t e) { c->last_hip = g_last_hip = (int)e; rc = MSCHED_E_HIP; };
     hipError_t e;
+    if ((e = hipGetDevice(&c->device)) != hipSuccess) fail(e);
+    // the static staging array of msched_pagetable_query_static: its address on this device, looked up once
+    if (rc == MSCHED_OK && (e = query_scratch_init(nullptr)) != hipSuccess) fail(e);
 #define ALLOC(ptr, bytes) if (rc == MSCHED_OK && (e = hipMalloc((void **)&(ptr), (bytes))) != hipSuccess) fail(e)
     // page table, next use and slots are read 16 bytes at a time: padded, so that the last lane may run past V
     ALLOC(c->page_table, c->V * 4 + 64);
@@ -828,6 +831,15 @@ int msched_pagetable_query(msched_ctx *c, const uint64_t *page_ids, uint32_t n, 
     });
 }
 
+int msched_pagetable_query_static(msched_ctx *c, const uint64_t *page_ids, uint32_t n, uint32_t *out) {
+    if (!c || (n && (!page_ids || !out))) return MSCHED_E_INVAL;
+    if (n > MSCHED_QUERY_STATIC_MAX) return MSCHED_E_TOO_LARGE;
+    for (uint32_t i = 0; i < n; ++i) if (page_ids[i] >= c->V) return MSCHED_E_RANGE;
+    if (n == 0) return MSCHED_OK;
+    HIP_TRY(c, query_static(c, page_ids, n, out));
+    return MSCHED_OK;
+}
+
 int msched_plan_copy_lists(msched_ctx *c, const msched_plan_t *plan, uint32_t *evict_pages, uint32_t *evict_frames,
                            uint32_t *fetch_pages, uint32_t *fetch_frames) {
     if (!c || !plan) return MSCHED_E_INVAL;
@@ -883,6 +895,7 @@ const char *msched_strerror(int code) {
         case MSCHED_E_STALE_PLAN: return "plan is not the latest or was already carried out";
         case MSCHED_E_NOMEM: return "out of memory";
         case MSCHED_E_HIP: return "HIP call failed";
+        case MSCHED_E_TOO_LARGE: return "request exceeds a fixed-size buffer of the library";
         default: return "unknown error";
     }
 }

@@ -104,6 +104,7 @@ struct PlanGeom {
 struct msched_ctx {
     msched_config cfg;
     hipStream_t stream;
+    int device = 0;                             // the GPU that was current at msched_create
     uint64_t V;
     uint32_t F, page_shift;
     void *host_dev = nullptr;                   // device address of cfg.host_store
@@ -204,6 +205,8 @@ void plan_geometry(const msched_ctx *c, uint32_t G, PlanGeom &g);
 hipError_t launch_migrate(msched_ctx *c, const PlanHeader &h);
 hipError_t launch_query(msched_ctx *c, const uint32_t *ids_dev, uint32_t n, uint32_t *out_dev);
 hipError_t launch_init_tables(msched_ctx *c);
+hipError_t query_scratch_init(uint8_t **out);                                         // address of the static staging array on the current device
+hipError_t query_static(msched_ctx *c, const uint64_t *page_ids, uint32_t n, uint32_t *out);
 hipError_t launch_peek(msched_ctx *c);
 hipError_t launch_list_prepare(msched_ctx *c, const ListPrep *table_dev, uint32_t n, uint32_t n_buckets);      // landed -> progress_host on the poll stream
 

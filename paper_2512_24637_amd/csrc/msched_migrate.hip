@@ -157,10 +157,35 @@ __global__ __launch_bounds__(256) void k_fill_u32(uint32_t *dst, uint64_t n, uin
         dst[i] = v;
 }
 
-__global__ __launch_bounds__(256) void k_query(const uint32_t *__restrict__ page_table, const uint32_t *__restrict__ ids,
+template <typename Id>
+__global__ __launch_bounds__(256) void k_query(const uint32_t *__restrict__ page_table, const Id *__restrict__ ids,
                                                uint32_t n, uint32_t *__restrict__ out) {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) out[i] = page_table[ids[i]];
+}
+
+// Staging of msched_pagetable_query_static: n 64-bit page ids, then n 32-bit answers.  The array is part of the
+// code object, so every GPU the library runs on holds its own copy at its own address; in host code its name is
+// only a handle for hipGetSymbolAddress, never an address a kernel or a copy may be given.
+constexpr size_t kQueryScratchBytes = (size_t)MSCHED_QUERY_STATIC_MAX * (sizeof(uint64_t) + sizeof(uint32_t));
+static __device__ __align__(256) uint8_t scratch[kQueryScratchBytes];
+constexpr int kMaxDevices = 64;
+static uint8_t *g_scratch_ptr[kMaxDevices] = {};          // device address of `scratch` on each GPU, once looked up
+
+// Look the array's address up on the current device (once per device) and keep it.
+hipError_t query_scratch_init(uint8_t **out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (g_scratch_ptr[dev] == nullptr) {
+        uint8_t *ptr = nullptr;
+        if ((e = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch))) != hipSuccess) return e;
+        if (ptr == nullptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    if (out) *out = g_scratch_ptr[dev];
+    return hipSuccess;
 }
 
 hipError_t launch_init_tables(msched_ctx *c) {
@@ -175,8 +200,23 @@ hipError_t launch_init_tables(msched_ctx *c) {
 hipError_t launch_query(msched_ctx *c, const uint32_t *ids_dev, uint32_t n, uint32_t *out_dev) {
     if (n == 0) return hipSuccess;
     (void)hipGetLastError();
-    k_query<<<(n + 255) / 256, 256, 0, c->stream>>>(c->page_table, ids_dev, n, out_dev);
+    k_query<uint32_t><<<(n + 255) / 256, 256, 0, c->stream>>>(c->page_table, ids_dev, n, out_dev);
     return hipGetLastError();
+}
+
+// The same gather through the static staging array: ids in, answers out, no allocation anywhere.
+hipError_t query_static(msched_ctx *c, const uint64_t *page_ids, uint32_t n, uint32_t *out) {
+    uint8_t *ptr = nullptr;
+    hipError_t e = query_scratch_init(&ptr);               // a table look-up after msched_create has run on this device
+    if (e != hipSuccess) return e;
+    uint64_t *ids_dev = reinterpret_cast<uint64_t *>(ptr);
+    uint32_t *out_dev = reinterpret_cast<uint32_t *>(ptr + (size_t)MSCHED_QUERY_STATIC_MAX * sizeof(uint64_t));
+    if ((e = hipMemcpyAsync(ids_dev, page_ids, (size_t)n * sizeof(uint64_t), hipMemcpyHostToDevice, c->stream)) != hipSuccess) return e;
+    (void)hipGetLastError();
+    k_query<uint64_t><<<(n + 255) / 256, 256, 0, c->stream>>>(c->page_table, ids_dev, n, out_dev);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = hipMemcpyAsync(out, out_dev, (size_t)n * sizeof(uint32_t), hipMemcpyDeviceToHost, c->stream)) != hipSuccess) return e;
+    return hipStreamSynchronize(c->stream);
 }
 
 hipError_t launch_migrate(msched_ctx *c, const PlanHeader &h) {
