@@ -38,11 +38,18 @@ HBM_PEAK_GBS = 8000.0
 # move, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script calibrated against a 1 GiB device copy
 # (profiles/k_migrate_c2_stencil_pmc_traffic.md).
 MIGRATE_TRAFFIC_RATIO = {"read": 1.0001, "write": 1.0018}
+MIGRATE_TRAFFIC_SOURCE = ("profiles/k_migrate_c2_stencil_pmc_traffic.md (FETCH_SIZE x2.000 and WRITE_SIZE x1.000 after "
+                          "calibration; bytes per launch at the L2 external port relative to the algorithmic bytes)")
 # Same for all planning kernels of one plan on the planning-stress structure (list preparation included at its
 # per-plan share): 127.4 MiB measured against 251.9 MiB by the algorithmic count (profiles/planning_c5_structure_kernels_and_traffic.md); below 1 because
 # range rules are painted in LDS and no longer cost a memory access per page touch, and the sweeps skip what they
 # can prove they do not need.
 PLAN_TRAFFIC_RATIO = 0.506
+# The same counters for the planning kernels of one context switch of config 5 itself (plan + its share of the id-list
+# preparation), in bytes per plan.
+PLAN_TRAFFIC_BYTES_PER_PLAN = 133.6e6
+PLAN_TRAFFIC_SOURCE = ("profiles/planning_c5_structure_kernels_and_traffic.md (FETCH_SIZE + WRITE_SIZE of all planning "
+                       "kernels, calibrated, per plan)")
 WORKLOADS = {
     1: "c1-tiny-round-robin: 3 tasks, 64 KiB pages, pool 256 frames (16 MiB), footprint 24 MiB, timeslice 10 launches",
     2: "c2-stencil-sweep: 4 tasks x 3 arrays of 256 MiB, 2 MiB pages, pool 1024 frames (2 GiB), footprint 3 GiB "
@@ -531,14 +538,177 @@ def bench_early_start(torch, switches=8, warm=2):
     return out
 
 
+def trace_args_for(config, need):
+    """Schedule long enough for `need` context switches at the configuration's full size."""
+    if config == 1:
+        return dict(config=1, n_launches=max(200, 10 * (need + 3)))
+    if config == 2:
+        return dict(config=2, n_launches=max(500, 25 * (-(-need // 4))))
+    if config == 3:
+        return dict(config=3, iterations=max(2, -(-need // 2)))           # >= 1 plan per iteration and task
+    if config == 4:
+        return dict(config=4, steps=4 * (-(-need // 2)))
+    return dict(config=5, n_launches=50 * (-(-need // 8) + 1))             # one slice more than is run: full queues
+
+
+def measure_link_pair(torch, nbytes_h2d, nbytes_d2h, reps=5):
+    """hipMemcpyAsync of the given sizes, both directions at once on two streams: what the DMA engines reach at
+    the transfer size of a small context switch (launch and completion latency included, as for the kernel)."""
+    dev = torch.device("cuda:0")
+    n_in, n_out = max(8, nbytes_h2d) // 8, max(8, nbytes_d2h) // 8
+    h_src = torch.empty(n_in, dtype=torch.int64, pin_memory=True).fill_(3)
+    h_dst = torch.empty(n_out, dtype=torch.int64, pin_memory=True).fill_(4)
+    d_dst = torch.empty(n_in, dtype=torch.int64, device=dev)
+    d_src = torch.full((n_out,), 5, dtype=torch.int64, device=dev)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    best = None
+    for _ in range(reps + 2):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        with torch.cuda.stream(s1):
+            d_dst.copy_(h_src, non_blocking=True)
+        with torch.cuda.stream(s2):
+            h_dst.copy_(d_src, non_blocking=True)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        best = dt if best is None else min(best, dt)
+    return (nbytes_h2d + nbytes_d2h) / best / 1e9
+
+
+def bench_config(torch, config, warmup, steps, link, extra_phase_steps=0):
+    """One configuration at full size: `warmup` untimed context switches, then exactly `steps` timed ones."""
+    from workloads import make_trace
+    t_setup = time.perf_counter()
+    need = warmup + steps + extra_phase_steps
+    trace_args = trace_args_for(config, need)
+    trace = make_trace(**trace_args)
+    P = trace.page_bytes
+    # Contents do not change what is timed; they are filled where that is cheap (the parity tests check bytes).
+    buf, ms = make_context(torch, trace, fill_contents=config in (1, 2))
+    log(f"[bench] {trace.name}: V={trace.n_virtual_pages} F={trace.n_frames} page={P >> 10} KiB, "
+        f"set up in {time.perf_counter() - t_setup:.1f} s")
+    from workloads import run_schedule
+    impl = TimedImpl(ms, torch.cuda.current_stream().synchronize, 1)
+    gen = run_schedule(trace, impl)
+    for _ in range(warmup):
+        next(gen)
+    impl.finish()
+    torch.cuda.synchronize()
+    n_warm_plans, n_warm_mig = len(impl.plans), len(impl.migrate_ms)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        next(gen)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    impl.finish()
+    plans = impl.plans[n_warm_plans:]
+    plan_wall = impl.plan_wall[n_warm_plans:]
+    phases = impl.phases[n_warm_plans:]
+    migrate_ms = impl.migrate_ms[n_warm_mig:]
+    phase_split = None
+    if extra_phase_steps:                       # the per-kernel split: its extra events lengthen each plan a little
+        ms.set_profiling(2)
+        impl.profile = 2
+        n0 = len(impl.phases)
+        for _ in range(extra_phase_steps):
+            next(gen)
+        torch.cuda.synchronize()
+        impl.finish()
+        ph2 = impl.phases[n0 + 1:]              # the first of them still carries the level-1 times
+        if ph2:
+            phase_split = {k: float(np.mean([ph[k] for ph in ph2])) * 1e3 for k in ("expand", "count", "cut", "emit")}
+    h2d = sum(p.n_fetch for p in plans) * P
+    d2h = sum(p.n_evict for p in plans) * P
+    moved = h2d + d2h
+    mig_s = sum(migrate_ms) / 1e3
+    roof_s = sum(max(p.n_fetch * P / (link["h2d_bidir_GBs"] * 1e9), p.n_evict * P / (link["d2h_bidir_GBs"] * 1e9))
+                 for p in plans)
+    n_copy = sum(1 for p in plans if p.n_fetch)
+    achieved = moved / mig_s / 1e9 if mig_s > 0 else 0.0
+    peak = moved / roof_s / 1e9 if roof_s > 0 else 0.0
+    plan_dev = [ph["plan"] for ph in phases]
+    prep_dev = [ph.get("prepare", 0.0) for ph in phases]
+    host_wall = np.array(plan_wall) * 1e6
+    out = {
+        "workload": WORKLOADS[config], "steps": steps, "warmup": warmup,
+        "page_bytes": P, "n_virtual_pages": trace.n_virtual_pages, "n_frames": trace.n_frames,
+        "value_GBs": moved / wall / 1e9, "ms_per_step": wall / steps * 1e3,
+        "bytes_migrated": {"h2d": h2d, "d2h": d2h},
+        "migrate": {"achieved_GBs": achieved, "peak_GBs": peak, "frac": (achieved / peak) if peak else None,
+                    "launches": n_copy, "avg_launch_ms": (mig_s / n_copy * 1e3) if n_copy else None,
+                    "bytes_per_launch": (moved / n_copy) if n_copy else None},
+        "plan_latency_us": {"host_wall_mean": float(host_wall.mean()), "host_wall_p50": float(np.median(host_wall)),
+                            "host_wall_max": float(host_wall.max()),
+                            "device_mean": float(np.mean(plan_dev)) * 1e3,
+                            "host_minus_device_mean": float(host_wall.mean() - np.mean(plan_dev) * 1e3),
+                            "list_prepare_device_mean": float(np.mean(prep_dev)) * 1e3,
+                            "host_flatten_mean": float(np.mean([ph["host_prep"] for ph in phases])) * 1e3,
+                            "host_launch_mean": float(np.mean([ph["host_launch"] for ph in phases])) * 1e3,
+                            "host_wait_mean": float(np.mean([ph["host_wait"] for ph in phases])) * 1e3,
+                            "n_commands_mean": float(np.mean([p.n_commands for p in plans]))},
+    }
+    if phase_split:
+        out["plan_latency_us"]["phase_split"] = phase_split
+    raw = {"trace": trace, "plans": plans, "plan_dev_ms": plan_dev, "prep_dev_ms": prep_dev,
+           "cold_plan_us": impl.plan_wall[0] * 1e6, "moved": moved, "wall": wall, "n_copy": n_copy, "mig_s": mig_s,
+           "achieved": achieved, "peak": peak, "trace_args": trace_args}
+    ms.close()
+    buf.release()
+    if config == 1 and n_copy:
+        # the link denominator at the transfer size of this schedule's switches, beside the 1 GiB figure
+        pair = measure_link_pair(torch, h2d // n_copy, d2h // n_copy)
+        out["migrate"]["hipMemcpyAsync_pair_same_size_GBs"] = pair
+        out["migrate"]["frac_of_same_size_hipMemcpy"] = achieved / pair if pair else None
+    return out, raw
+
+
+def planning_roofline(raw, hbm_copy_rate):
+    """The planning kernels of the timed context switches of config 5 against HBM bandwidth.  Three byte counts
+    for the same device time: the two-sweep count the first version of the path was priced with (kept so that
+    fractions stay comparable), the one-fused-pass count (what the method itself must move at least), and the
+    bytes the kernels really moved through the L2's external port (rocprofv3 counters, per plan)."""
+    trace, plans = raw["trace"], raw["plans"]
+    V = trace.n_virtual_pages
+    G = float(np.mean([p.n_commands for p in plans]))
+    ids_per_cmd = int(trace.tasks[0].n_ids[0])
+    n_ids = ids_per_cmd * G
+    n_touch = n_ids + 2 * G * (1024 + 16384) / 2             # two dense ranges of 1 Ki - 16 Ki pages per command
+    lists = float(np.mean([8 * p.n_fetch + 8 * p.n_evict for p in plans]))
+    upper = 4 * n_touch + 4 * n_ids + 16 * V + lists        # two sweeps over page table + next use
+    lower = 4 * n_touch + 4 * n_ids + 8 * V + lists         # one fused pass
+    traffic = PLAN_TRAFFIC_BYTES_PER_PLAN
+    dev_s = float(np.mean(raw["plan_dev_ms"])) / 1e3
+    prep_s = float(np.mean(raw["prep_dev_ms"])) / 1e3
+    tot_s = dev_s + prep_s
+    gbs = lambda b, t: b / t / 1e9 if t > 0 else 0.0
+    return {"bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "achieved": gbs(upper, tot_s), "frac": gbs(upper, tot_s) / HBM_PEAK_GBS,
+            "frac_lower": gbs(lower, tot_s) / HBM_PEAK_GBS,
+            "frac_by_traffic": (gbs(traffic, tot_s) / HBM_PEAK_GBS) if traffic else None,
+            "frac_excl_prepare": gbs(upper, dev_s) / HBM_PEAK_GBS,
+            "traffic": traffic, "traffic_source": PLAN_TRAFFIC_SOURCE,
+            "algorithmic_bytes_per_plan": upper, "algorithmic_bytes_lower": lower,
+            "plan_device_us_mean": dev_s * 1e6, "list_prepare_device_us_per_switch": prep_s * 1e6,
+            "plan_device_us_incl_prepare": tot_s * 1e6, "cold_plan_us": raw["cold_plan_us"],
+            "hbm_copy_measured_GBs": hbm_copy_rate,
+            "frac_of_measured_copy": gbs(upper, tot_s) / hbm_copy_rate if hbm_copy_rate else None,
+            "workload": f"the timed context switches of config 5 themselves (V={V}, F={trace.n_frames}, "
+                        f"G={G:.0f}, 4 KiB pages, a migration between every two plans)",
+            "note": "achieved / frac price the time of the plan's kernels plus the id-list preparation that "
+                    "msched_migrate queues behind the copy for the commands of the next plans (per switch) with the "
+                    "two-sweep byte count; frac_lower prices the same time with the one-pass count, frac_by_traffic "
+                    "with the bytes counted at the L2's external port"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--steps", type=int, default=24)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5],
-                    help="workload (default 2 = the configuration the metric is quoted on)")
-    ap.add_argument("--no-plan-stress", action="store_true", help="skip the planning-stress leg")
+    ap.add_argument("--config", type=int, default=0, choices=[0, 1, 2, 3, 4, 5],
+                    help="run this workload only (default 0: all five, the headline value on config 5, the largest)")
+    ap.add_argument("--other-steps", type=int, default=20, help="timed context switches of the configurations beside the headline")
+    ap.add_argument("--no-plan-stress", action="store_true", help="skip the back-to-back planning leg on config 5's page structure")
     ap.add_argument("--plan-stress-only", action="store_true",
                     help="run only the planning-stress leg (for profiling the planning kernels)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -546,12 +716,13 @@ def main():
     ap.add_argument("--no-early-start", action="store_true", help="skip the early-execution leg")
     ap.add_argument("--no-priority", action="store_true", help="skip the priority-policy leg")
     ap.add_argument("--no-ablation", action="store_true", help="skip the predictor-ablation leg")
+    ap.add_argument("--no-legs", action="store_true", help="skip every leg beside the configurations themselves")
     ap.add_argument("--ablation-only", action="store_true", help="run only the predictor-ablation leg")
     ap.add_argument("--priority-only", action="store_true", help="run only the priority-policy leg")
     ap.add_argument("--early-start-only", action="store_true", help="run only the early-execution leg")
     ap.add_argument("--analyzer-only", action="store_true",
                     help="run only the memory-analyzer leg (for profiling k_analyze)")
-    ap.add_argument("--cpu-sample-steps", type=int, default=480)
+    ap.add_argument("--cpu-sample-steps", type=int, default=0, help="context switches the oracle is timed on (0: by configuration)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (a context is per GPU: N GPUs would be "
@@ -561,7 +732,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
-    from workloads import make_trace
+    if args.no_legs:
+        args.no_plan_stress = args.no_analyzer = args.no_early_start = args.no_priority = args.no_ablation = True
 
     if args.plan_stress_only:
         r = bench_planning_stress(torch, warmup=args.warmup, steps=min(args.steps, 24), phases=False)
@@ -600,70 +772,54 @@ def main():
                           "cpu_baseline": r.get("cpu_baseline")}), flush=True)
         return
 
+    t_all = time.perf_counter()
     link = measure_link_peak(torch)
     log(f"[bench] link peak: {json.dumps(link)}")
 
-    need = args.steps + args.warmup
-    if args.config == 1:
-        trace_args = dict(config=1, n_launches=max(200, 10 * (need + 3)))
-    elif args.config == 2:
-        trace_args = dict(config=2, n_launches=max(500, 25 * (-(-need // 4))))
-    elif args.config == 3:
-        trace_args = dict(config=3, iterations=max(2, -(-need // 2)))        # >= 1 plan per iteration and task
-    elif args.config == 4:
-        trace_args = dict(config=4, steps=4 * (-(-need // 2)))
-    else:
-        trace_args = dict(config=5, n_launches=50 * (-(-need // 8)))
-    trace = make_trace(**trace_args)
-    P = trace.page_bytes
-    buf, ms = make_context(torch, trace, fill_contents=True)
-    log(f"[bench] {trace.name}: V={trace.n_virtual_pages} F={trace.n_frames} page={P >> 10} KiB")
-    r = run_steps(torch, trace, ms, args.warmup, args.steps)
-    plans = r["plans"]
-    h2d = sum(p.n_fetch for p in plans) * P
-    d2h = sum(p.n_evict for p in plans) * P
-    moved = h2d + d2h
-    value = moved / r["wall_s"] / 1e9
-    mig_s = sum(r["migrate_ms"]) / 1e3
-    roof_s = sum(max(p.n_fetch * P / (link["h2d_bidir_GBs"] * 1e9), p.n_evict * P / (link["d2h_bidir_GBs"] * 1e9))
-                 for p in plans)
-    n_copy = sum(1 for p in plans if p.n_fetch)
-    achieved = moved / mig_s / 1e9 if mig_s > 0 else 0.0
-    peak = moved / roof_s / 1e9 if roof_s > 0 else 0.0
-    plan_dev = [ph["plan"] for ph in r["phases"]]
-    ms.close()
-    buf.release()
+    headline = args.config or 5
+    others = [] if args.config else [1, 2, 3, 4]
+    per_config = {}
+    for cfg in others:
+        t0 = time.perf_counter()
+        per_config[f"c{cfg}"], _ = bench_config(torch, cfg, args.warmup, args.other_steps, link)
+        log(f"[bench] c{cfg}: {per_config[f'c{cfg}']['value_GBs']:.2f} GB/s, migrate frac "
+            f"{per_config[f'c{cfg}']['migrate']['frac']:.3f}, plan host {per_config[f'c{cfg}']['plan_latency_us']['host_wall_mean']:.1f} us "
+            f"device {per_config[f'c{cfg}']['plan_latency_us']['device_mean']:.1f} us ({time.perf_counter() - t0:.1f} s)")
+    t0 = time.perf_counter()
+    head, raw = bench_config(torch, headline, args.warmup, args.steps, link, extra_phase_steps=8 if headline == 5 else 0)
+    per_config[f"c{headline}"] = head
+    log(f"[bench] c{headline} (headline): {head['value_GBs']:.2f} GB/s, migrate frac {head['migrate']['frac']:.3f}, "
+        f"plan host {head['plan_latency_us']['host_wall_mean']:.1f} us device {head['plan_latency_us']['device_mean']:.1f} us "
+        f"({time.perf_counter() - t0:.1f} s)")
+    moved, n_copy = raw["moved"], raw["n_copy"]
 
     result = {
         "metric": "migrated GB/s vs host-link peak; plan latency (us) per context switch",
-        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": r["wall_s"] / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "value": head["value_GBs"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u8", "data": "synthetic",
-        "config": {"workload": WORKLOADS[args.config],
-                   "page_bytes": P, "n_virtual_pages": trace.n_virtual_pages, "n_frames": trace.n_frames},
-        "bytes_migrated": {"h2d": h2d, "d2h": d2h},
-        "plan_latency_us": {"host_wall_mean": float(np.mean(r["plan_wall_s"])) * 1e6,
-                            "host_wall_p50": float(np.median(r["plan_wall_s"])) * 1e6,
-                            "host_wall_max": float(np.max(r["plan_wall_s"])) * 1e6,
-                            "device_mean": float(np.mean(plan_dev)) * 1e3,
-                            "host_flatten_mean": float(np.mean([ph["host_prep"] for ph in r["phases"]])) * 1e3,
-                            "host_launch_mean": float(np.mean([ph["host_launch"] for ph in r["phases"]])) * 1e3,
-                            "host_wait_mean": float(np.mean([ph["host_wait"] for ph in r["phases"]])) * 1e3},
-        "roofline": {"bound": "host-link", "achieved": achieved, "peak": peak, "unit": "GB/s",
-                     "frac": (achieved / peak) if peak else None,
+        "config": {"workload": WORKLOADS[headline],
+                   "page_bytes": head["page_bytes"], "n_virtual_pages": head["n_virtual_pages"], "n_frames": head["n_frames"]},
+        "bytes_migrated": head["bytes_migrated"],
+        "plan_latency_us": head["plan_latency_us"],
+        "roofline": {"bound": "host-link", "achieved": raw["achieved"], "peak": raw["peak"], "unit": "GB/s",
+                     "frac": (raw["achieved"] / raw["peak"]) if raw["peak"] else None,
                      "traffic": (MIGRATE_TRAFFIC_RATIO["read"] * moved / n_copy) if n_copy else None,
                      "traffic_write": (MIGRATE_TRAFFIC_RATIO["write"] * moved / n_copy) if n_copy else None,
                      "algorithmic_bytes_per_launch": (moved / n_copy) if n_copy else None,
-                     "traffic_source": "profiles/k_migrate_c2_stencil_pmc_traffic.md (FETCH_SIZE x2.000 and "
-                                       "WRITE_SIZE x1.000 after calibration; bytes per launch at the L2 external port)",
+                     "traffic_source": MIGRATE_TRAFFIC_SOURCE,
                      "kernel": "k_migrate", "launches": n_copy,
-                     "avg_launch_ms": (mig_s / n_copy * 1e3) if n_copy else None,
+                     "avg_launch_ms": (raw["mig_s"] / n_copy * 1e3) if n_copy else None,
                      "note": "peak = the same per-step byte mix at the pinned hipMemcpyAsync rates measured "
                              "in this run with both directions busy"},
         "link_peak": link,
+        "per_config": per_config,
     }
-    if not args.no_plan_stress:
-        result["roofline_plan"] = bench_planning_stress(torch)
+    if headline == 5:
+        result["roofline_plan"] = planning_roofline(raw, measure_hbm_copy(torch))
+        if not args.no_plan_stress:
+            result["roofline_plan"]["back_to_back_on_page_structure"] = bench_planning_stress(torch, phases=False)
+    del raw["trace"]
     if not args.no_early_start:
         result["early_start"] = bench_early_start(torch)
     if not args.no_ablation:
@@ -673,12 +829,14 @@ def main():
     if not args.no_analyzer:
         result["analyzer"] = bench_analyzer(torch, cpu=not args.no_cpu_baseline)
     if not args.no_cpu_baseline:
-        if args.config == 2:
-            cpu_args = dict(config=2, n_launches=max(500, 25 * (-(-args.cpu_sample_steps // 4))))
-            result["cpu_baseline"] = cpu_baseline(cpu_args, args.cpu_sample_steps)
+        n_cpu = args.cpu_sample_steps or {1: 60, 2: 480, 3: 6, 4: 6, 5: 10}[headline]
+        t0 = time.perf_counter()
+        result["cpu_baseline"] = cpu_baseline(trace_args_for(headline, n_cpu), n_cpu)
+        log(f"[bench] cpu baseline: {result['cpu_baseline']['value']:.2f} GB/s ({time.perf_counter() - t0:.1f} s)")
+        if headline <= 2 or not args.config:
             result["miss_volume"] = miss_volume(dict(config=2))
-        else:
-            result["cpu_baseline"] = None      # the oracle leg is sized for the default workload only
+            result["miss_volume"]["workload"] = "config 2 (stencil sweep), whole schedule"
+    log(f"[bench] whole run {time.perf_counter() - t_all:.1f} s")
     print(json.dumps(result), flush=True)
 
 

@@ -199,7 +199,8 @@ enum { MSCHED_PHASE_EXPAND = 0,   /* next-use reset + template expansion + scatt
        MSCHED_HOST_PREP = 6,      /* host clock: timeline flatten + repeat detection of the last plan */
        MSCHED_HOST_LAUNCH = 7,    /* host clock: issuing the plan's kernel launches */
        MSCHED_HOST_WAIT = 8,      /* host clock: waiting for the plan's kernels and reading the counts */
-       MSCHED_N_PHASES = 9 };
+       MSCHED_PHASE_PREPARE = 9,  /* id-list preparation the last msched_migrate queued behind its copy (0 if none) */
+       MSCHED_N_PHASES = 10 };
 /* level 0: off; 1: time each plan as a whole and each migrate (two events per call); 2: also time the
  * four planning phases separately (the extra events between kernels add a few microseconds each). */
 int msched_set_profiling(msched_ctx *ctx, int level);

@@ -11,7 +11,7 @@ import numpy as np
 _PKG = os.path.dirname(os.path.abspath(__file__))
 NOT_RESIDENT = 0xFFFFFFFF
 QUERY_STATIC_MAX = 65536
-PHASES = ("expand", "count", "cut", "emit", "migrate", "plan", "host_prep", "host_launch", "host_wait")
+PHASES = ("expand", "count", "cut", "emit", "migrate", "plan", "host_prep", "host_launch", "host_wait", "prepare")
 EXPORTED_SYMBOLS = (
     "msched_create", "msched_destroy", "msched_kernel_register", "msched_task_create",
     "msched_launch_enqueue", "msched_launch_retire", "msched_plan", "msched_migrate",

@@ -281,7 +281,7 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     if (rc == MSCHED_OK && (e = hipHostGetDevicePointer((void **)&c->ranges_host_dev, c->ranges_host, 0)) != hipSuccess) fail(e);
     if (rc == MSCHED_OK && (e = hipMalloc((void **)&c->ranges_dev, sizeof(PageRange) * kMaxRanges)) != hipSuccess) fail(e);
     if (rc == MSCHED_OK && (e = hipMalloc((void **)&c->key16, c->V * 2 + 64)) != hipSuccess) fail(e);
-    for (int i = 0; i < 8 && rc == MSCHED_OK; ++i)
+    for (int i = 0; i < 10 && rc == MSCHED_OK; ++i)
         if ((e = hipEventCreate(&c->ev[i])) != hipSuccess) fail(e);
 
     if (rc == MSCHED_OK && (e = launch_init_tables(c)) != hipSuccess) fail(e);
@@ -735,6 +735,7 @@ void prepare_ahead(msched_ctx *c) {
         if (full) break;
     }
     if (n_new == 0) return;
+    const bool timed = c->profiling && hipEventRecord(c->ev[8], c->stream) == hipSuccess;
     if ((e = launch_list_prepare(c, c->list_ahead_dev, n_new, n_buckets)) != hipSuccess ||
         (e = hipEventRecord(c->ahead_ev, c->stream)) != hipSuccess) {
         // nothing was binned: the records must not point at blocks that hold no list
@@ -745,6 +746,7 @@ void prepare_ahead(msched_ctx *c) {
         return give_up(e);
     }
     c->ahead_pending = true;
+    if (timed && hipEventRecord(c->ev[9], c->stream) == hipSuccess) c->prepare_timed = 1;
 }
 
 }  // namespace
@@ -757,6 +759,7 @@ int msched_migrate(msched_ctx *c, const msched_plan_t *plan) {
     if (c->profiling) { HIP_TRY(c, hipEventRecord(c->ev[6], c->stream)); c->migrate_timed = 1; }
     c->n_resident += c->pending.n_free_used;
     c->pending_plan = 0;
+    c->prepare_timed = 0;
     return guarded([&]() -> int { prepare_ahead(c); return MSCHED_OK; });
 }
 
@@ -880,6 +883,8 @@ int msched_get_phase_ms(msched_ctx *c, float *ms) {
     if (c->profiling && c->migrate_timed) {
         HIP_TRY(c, hipStreamSynchronize(c->stream));
         HIP_TRY(c, hipEventElapsedTime(&c->phase_ms[MSCHED_PHASE_MIGRATE], c->ev[5], c->ev[6]));
+        c->phase_ms[MSCHED_PHASE_PREPARE] = 0.f;
+        if (c->prepare_timed) HIP_TRY(c, hipEventElapsedTime(&c->phase_ms[MSCHED_PHASE_PREPARE], c->ev[8], c->ev[9]));
     }
     for (int i = 0; i < MSCHED_N_PHASES; ++i) ms[i] = c->phase_ms[i];
     return MSCHED_OK;

@@ -190,7 +190,8 @@ struct msched_ctx {
     int plan_early = 0;                         // the latest plan computed need[] and reset landed
     int profiling = 0;
     int migrate_timed = 0;                      // ev[5], ev[6] have been recorded
-    hipEvent_t ev[8] = {};
+    int prepare_timed = 0;                      // ev[8], ev[9] have been recorded around the look-ahead preparation of the last migrate
+    hipEvent_t ev[10] = {};
     float phase_ms[MSCHED_N_PHASES] = {};
     int last_hip = 0;
 };
