@@ -641,6 +641,11 @@ def bench_config(torch, config, warmup, steps, link, extra_phase_steps=0):
                             "host_wall_max": float(host_wall.max()),
                             "device_mean": float(np.mean(plan_dev)) * 1e3,
                             "host_minus_device_mean": float(host_wall.mean() - np.mean(plan_dev) * 1e3),
+                            # the same call timed inside the library, from its first line to the counts being known
+                            # (host_wall is the Python caller's clock around the ctypes call and its marshalling)
+                            "c_abi_wall_mean": float(np.mean([ph["host_prep"] + ph["host_launch"] + ph["host_wait"] for ph in phases])) * 1e3,
+                            "c_abi_minus_device_mean": float(np.mean([ph["host_prep"] + ph["host_launch"] + ph["host_wait"] - ph["plan"]
+                                                                      for ph in phases])) * 1e3,
                             "list_prepare_device_mean": float(np.mean(prep_dev)) * 1e3,
                             "host_flatten_mean": float(np.mean([ph["host_prep"] for ph in phases])) * 1e3,
                             "host_launch_mean": float(np.mean([ph["host_launch"] for ph in phases])) * 1e3,

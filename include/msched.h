@@ -53,7 +53,8 @@ typedef struct {
     void *hbm_pool;               /* DEVICE, n_frames << page_shift bytes, 16-byte aligned, caller-owned */
     void *host_store;             /* HOST pinned and device-accessible, n_host_slots << page_shift bytes, caller-owned */
     uint64_t n_host_slots;        /* pages in host_store */
-    const uint32_t *host_slot;    /* HOST, V entries (page -> slot, MSCHED_NO_SLOT = none) or NULL = identity; copied */
+    const uint32_t *host_slot;    /* HOST, V entries (page -> slot, MSCHED_NO_SLOT = none) or NULL = identity; copied.
+                                     No two pages may share a slot (E_INVAL); a slot >= n_host_slots is E_RANGE */
     void *stream;                 /* hipStream_t all device work is issued on (NULL = default stream) */
 } msched_config;
 
@@ -118,9 +119,13 @@ int msched_task_create(msched_ctx *ctx, uint32_t *task_id);
  * Append a launch to a task's queue (Sec. 5.2 "Memory access prediction": launch arguments are
  * captured when the command is issued; Sec. 6.2: the queue holds the command and its profiled
  * latency).  args: HOST, n_args <= MSCHED_MAX_ARGS values (32-bit arguments zero-extended).
- * id_list: DEVICE array of n_ids page ids for the kernel's LIST rule, or NULL; it is NOT copied
- * and must stay valid and unchanged until the launch has been retired.
- * The template is evaluated here once for validation: E_RANGE / E_OVERFLOW launches are refused.
+ * id_list: DEVICE array of n_ids page ids for the kernel's LIST rule, or NULL; it is NOT copied.
+ * It must stay valid and unchanged from this call until the launch has been retired AND the context's
+ * stream has passed the last msched_plan / msched_migrate issued before that msched_launch_retire:
+ * retiring is a host-side step that does not wait, and a migration may still have the list's preparation
+ * queued behind its copy.  (Synchronise the stream, or free the list in stream order, after the retire.)
+ * The template's formulas are evaluated here, once, with these arguments (Sec. 5.2: prediction at launch
+ * time): E_RANGE / E_OVERFLOW launches are refused, and plans reuse the page ranges worked out here.
  * (Ids inside id_list are checked by msched_plan, which then returns E_RANGE.)
  */
 int msched_launch_enqueue(msched_ctx *ctx, uint32_t task, uint32_t kernel_id,

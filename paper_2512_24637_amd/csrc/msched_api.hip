@@ -68,18 +68,18 @@ int validate_launch(const msched_ctx *c, const DevKernel &k, const uint64_t *arg
     return MSCHED_OK;
 }
 
-// A later command whose rule describes exactly the region an earlier command of this plan already
-// described cannot lower any page's first use, so its expansion is skipped.  Iterative workloads
-// launch the same kernels over the same buffers again and again (the paper finds 77 % of accesses
-// fixed-size, Sec. 5.2), which makes most rules of a timeline repeats.  The test is exact: regions are
-// compared as full tuples (page range for fixed/linear rules, the four strided parameters, or the
-// id-list address and length), never by hash alone.
-inline bool region_signature(const msched_ctx *c, const msched_rule &q, const CmdRec &r, RegionSig &sig, bool &empty) {
+// A later command whose rule describes exactly the region an earlier queued command of its task already
+// describes cannot lower any page's first use while that command is queued, so a plan leaves it out.
+// Iterative workloads launch the same kernels over the same buffers again and again (the paper finds 77 % of
+// accesses fixed-size, Sec. 5.2), which makes most rules of a timeline repeats.  The test is exact: regions
+// are compared as full tuples (page range for fixed/linear rules, the four strided parameters, or the id-list
+// address and length), never by hash alone.  `empty`: the rule describes nothing.
+inline void region_signature(const msched_ctx *c, const msched_rule &q, const CmdRec &r, RegionSig &sig, bool &empty) {
     empty = false;
     if (q.kind == MSCHED_RULE_LIST) {
         sig = {4, (uint64_t)(uintptr_t)r.ids, r.n_ids, 0};
         empty = r.n_ids == 0;
-        return true;
+        return;
     }
     auto eval = [&](uint64_t coeff, const uint8_t *idx, int n) {
         uint64_t v = coeff;
@@ -89,21 +89,20 @@ inline bool region_signature(const msched_ctx *c, const msched_rule &q, const Cm
     const uint64_t base = r.args[q.base_arg];
     const uint64_t size = q.kind == MSCHED_RULE_FIXED ? q.size_coeff : eval(q.size_coeff, q.size_args, q.n_size_args);
     if (q.kind != MSCHED_RULE_STRIDED) {
-        if (size == 0) { empty = true; return true; }
+        if (size == 0) { empty = true; return; }
         sig = {1, base >> c->page_shift, (base + size - 1) >> c->page_shift, 0};
-        return true;
+        return;
     }
     const uint64_t stride = eval(q.stride_coeff, q.stride_args, q.n_stride_args);
     const uint64_t count = eval(q.count_coeff, q.count_args, q.n_count_args);
-    if (size == 0 || count == 0) { empty = true; return true; }
+    if (size == 0 || count == 0) { empty = true; return; }
     sig = {base, size, stride, count ^ (3ull << 62)};
-    return true;
 }
 
-// The page ranges a fixed / linear / strided rule describes for one command, appended to out[n..cap).
-// Returns false when they do not fit (the plan then scatters next uses per page instead).
-inline bool append_ranges(const msched_ctx *c, const msched_rule &q, const CmdRec &r, uint32_t g, PageRange *out,
-                          uint32_t &n, uint32_t cap) {
+// The page ranges a fixed / linear / strided rule describes for one command (template expansion, Sec. 5.2),
+// appended to `out`.  Returns false when the command would hold more than `cap` ranges.
+inline bool append_ranges(const msched_ctx *c, const msched_rule &q, uint32_t rule, const CmdRec &r, uint32_t back,
+                          std::vector<RangeRec> &out, size_t first, size_t cap) {
     auto eval = [&](uint64_t coeff, const uint8_t *idx, int cnt) {
         uint64_t v = coeff;
         for (int j = 0; j < cnt; ++j) v *= r.args[idx[j]];    // validated at enqueue: cannot overflow
@@ -120,24 +119,17 @@ inline bool append_ranges(const msched_ctx *c, const msched_rule &q, const CmdRe
         if (count == 0) return true;
         if (size >= stride || count == 1) { size = (count - 1) * stride + size; count = 1; }   // the chunks abut or overlap
     }
-    if (count > cap - n) return false;
+    if (count > cap - (out.size() - first)) return false;
     for (uint64_t j = 0; j < count; ++j) {
         const uint64_t c0 = base + j * stride;
-        out[n++] = {(uint32_t)(c0 >> sh), (uint32_t)(((c0 + size - 1) >> sh) + 1), g, 0};
+        out.push_back(RangeRec{(uint32_t)(c0 >> sh), (uint32_t)(((c0 + size - 1) >> sh) + 1), back, rule});
     }
     return true;
 }
 
-// Insert sig into the per-plan table; returns true when it was already there.
-inline bool seen_before(msched_ctx *c, const RegionSig &sig, size_t mask) {
-    uint64_t h = sig.a * 0x9E3779B97F4A7C15ull ^ (sig.b + 0x7F4A7C15ull) * 0xC2B2AE3D27D4EB4Full ^
-                 (sig.c * 0x165667B19E3779F9ull) ^ (sig.d * 0x27D4EB2F165667C5ull);
-    h ^= h >> 29;
-    for (size_t i = h & mask;; i = (i + 1) & mask) {
-        msched_ctx::SeenEntry &e = c->seen[i];
-        if (e.stamp != c->dedupe_stamp) { e = {sig.a, sig.b, sig.c, sig.d, c->dedupe_stamp}; return false; }
-        if (e.a == sig.a && e.b == sig.b && e.c == sig.c && e.d == sig.d) return true;
-    }
+// Is the command `back` places before command i of a task still queued (and with it in every timeline)?
+inline bool repeats_queued(const msched_ctx *c, const TaskQueue &t, size_t i, uint32_t back) {
+    return c->dedupe_regions && back != 0 && i - back >= t.cursor;
 }
 
 void free_ctx(msched_ctx *c) {
@@ -210,9 +202,8 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     msched_ctx *c = new (std::nothrow) msched_ctx();
     if (!c) return MSCHED_E_NOMEM;
     const int rc_tables = guarded([&]() -> int {
-        c->seen.assign(131072, msched_ctx::SeenEntry{0, 0, 0, 0, 0});     // >= 4 x MAX_TIMELINE_COMMANDS x MAX_RULES
-        c->plan_recs.resize(MSCHED_MAX_TIMELINE_COMMANDS + 1);
-        c->plan_task.resize(MSCHED_MAX_TIMELINE_COMMANDS + 1);
+        c->runs.reserve(MSCHED_MAX_TIMELINE_ENTRIES);
+        c->reserved.reserve(kMaxListSources);
         return MSCHED_OK;
     });
     if (rc_tables) { delete c; return rc_tables; }
@@ -281,6 +272,11 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     if (rc == MSCHED_OK && (e = hipHostGetDevicePointer((void **)&c->ranges_host_dev, c->ranges_host, 0)) != hipSuccess) fail(e);
     if (rc == MSCHED_OK && (e = hipMalloc((void **)&c->ranges_dev, sizeof(PageRange) * kMaxRanges)) != hipSuccess) fail(e);
     if (rc == MSCHED_OK && (e = hipMalloc((void **)&c->key16, c->V * 2 + 64)) != hipSuccess) fail(e);
+    if (rc == MSCHED_OK && c->page_shift > std::min(c->migrate_chunk_shift, c->early_chunk_shift)) {
+        // pages larger than a work unit of the copy: their chunks are counted, the last one maps the page
+        if ((e = hipMalloc((void **)&c->chunks_done, (size_t)c->F * 4)) != hipSuccess) fail(e);
+        else if ((e = hipMemset(c->chunks_done, 0, (size_t)c->F * 4)) != hipSuccess) fail(e);
+    }
     for (int i = 0; i < 10 && rc == MSCHED_OK; ++i)
         if ((e = hipEventCreate(&c->ev[i])) != hipSuccess) fail(e);
 
@@ -347,7 +343,9 @@ int msched_kernel_register(msched_ctx *c, const msched_rule *rules, uint32_t n_r
 int msched_task_create(msched_ctx *c, uint32_t *task_id) {
     if (!c || !task_id) return MSCHED_E_INVAL;
     return guarded([&]() -> int {
+        c->pos.reserve(c->tasks.size() + 1);
         c->tasks.emplace_back();
+        c->pos.resize(c->tasks.size());
         *task_id = (uint32_t)(c->tasks.size() - 1);
         return MSCHED_OK;
     });
@@ -369,37 +367,87 @@ int msched_launch_enqueue(msched_ctx *c, uint32_t task, uint32_t kernel_id, cons
         // into the old array - and the stream is drained here all the same, so that this stays true if a later
         // kernel of a plan ever reads records: growing a queue is rare, a wait costs nothing then.
         HIP_TRY(c, hipStreamSynchronize(c->stream));
-        const size_t live = t.n - t.cursor;
+        const size_t live = t.n - t.cursor, off = t.cursor - t.base;
         const size_t ncap = std::max<size_t>(256, live * 2);
+        // the compact arrays first: if one of them cannot grow, nothing has changed yet
+        std::vector<uint32_t> lat, n_ids, list_back;
+        std::vector<uint64_t> range_end, prep;
+        std::vector<const uint32_t *> ids;
+        std::vector<uint8_t> flag;
+        const int rc_room = guarded([&]() -> int {
+            lat.resize(ncap); n_ids.resize(ncap); list_back.resize(ncap); range_end.resize(ncap); prep.resize(ncap);
+            ids.resize(ncap); flag.resize(ncap);
+            return MSCHED_OK;
+        });
+        if (rc_room) return rc_room;
         CmdRec *nr = nullptr, *nd = nullptr;
         HIP_TRY(c, hipHostMalloc((void **)&nr, ncap * sizeof(CmdRec), hipHostMallocDefault));
         const hipError_t e = hipHostGetDevicePointer((void **)&nd, nr, 0);
         if (e != hipSuccess) { (void)hipHostFree(nr); HIP_TRY(c, e); }
-        std::vector<RegionSig> nsig;
-        const int rc_sig = guarded([&]() -> int { nsig.resize(ncap * MSCHED_MAX_RULES); return MSCHED_OK; });
-        if (rc_sig) { (void)hipHostFree(nr); return rc_sig; }
+        const uint64_t keep_from = t.cap ? t.range_begin(t.cursor) : 0;      // the retired commands' ranges go too
         if (live) {
-            memcpy(nr, t.recs + (t.cursor - t.base), live * sizeof(CmdRec));
-            memcpy(nsig.data(), t.sig.data() + (t.cursor - t.base) * MSCHED_MAX_RULES, live * MSCHED_MAX_RULES * sizeof(RegionSig));
+            memcpy(nr, t.recs + off, live * sizeof(CmdRec));
+            std::copy_n(t.lat.begin() + off, live, lat.begin());
+            std::copy_n(t.n_ids.begin() + off, live, n_ids.begin());
+            std::copy_n(t.list_back.begin() + off, live, list_back.begin());
+            std::copy_n(t.range_end.begin() + off, live, range_end.begin());
+            std::copy_n(t.prep.begin() + off, live, prep.begin());
+            std::copy_n(t.ids.begin() + off, live, ids.begin());
+            std::copy_n(t.flag.begin() + off, live, flag.begin());
         }
+        t.ranges.erase(t.ranges.begin(), t.ranges.begin() + (keep_from - t.ranges_base));
+        t.ranges_base = keep_from;
         if (t.recs) (void)hipHostFree(t.recs);
         t.recs = nr; t.recs_dev = nd; t.cap = ncap; t.base = t.cursor;
-        t.sig.swap(nsig);
+        t.lat.swap(lat); t.n_ids.swap(n_ids); t.list_back.swap(list_back); t.range_end.swap(range_end);
+        t.prep.swap(prep); t.ids.swap(ids); t.flag.swap(flag);
     }
-    CmdRec &r = t.recs[t.n - t.base];
-    memset(&r, 0, sizeof r);
-    r.kernel = kernel_id; r.n_args = n_args; r.latency = latency_ticks; r.n_ids = n_ids; r.ids = id_list;
-    for (uint32_t i = 0; i < n_args; ++i) r.args[i] = args[i];
-    // the regions its rules describe never change: every plan that looks at the command finds them ready
-    const DevKernel &k = c->kernels[kernel_id];
-    RegionSig *sig = t.sig.data() + (t.n - t.base) * MSCHED_MAX_RULES;
-    for (uint32_t q = 0; q < k.n_rules; ++q) {
-        bool empty;
-        region_signature(c, k.rules[q], r, sig[q], empty);
-        if (empty) sig[q] = RegionSig{~0ull, ~0ull, 0, 0};
-    }
-    t.n++;
-    return MSCHED_OK;
+    return guarded([&]() -> int {
+        const size_t i = t.n, li = i - t.base;
+        CmdRec &r = t.recs[li];
+        memset(&r, 0, sizeof r);
+        r.kernel = kernel_id; r.n_args = n_args; r.latency = latency_ticks; r.n_ids = n_ids; r.ids = id_list;
+        for (uint32_t a = 0; a < n_args; ++a) r.args[a] = args[a];
+        // Template expansion (Sec. 5.2): the formulas are evaluated here, once, with the launch's arguments; a plan
+        // only walks the page ranges.  A rule's region is also looked up among the regions earlier commands of the
+        // task described, so that plans can leave repeats out without looking anything up themselves.
+        const DevKernel &k = c->kernels[kernel_id];
+        const size_t first = t.ranges.size();
+        uint8_t flag = 0;
+        uint32_t list_back = 0;
+        struct Unwind {                              // a failure half-way must not leave ranges for the next command to inherit
+            std::vector<RangeRec> &v; size_t n; bool armed = true;
+            ~Unwind() { if (armed) v.resize(n); }
+        } unwind{t.ranges, first};
+        if (t.last_region.size() > 4096 && t.last_region.size() > 2 * t.pruned_at) {
+            // regions only retired commands described can no longer make anything a repeat
+            for (auto it = t.last_region.begin(); it != t.last_region.end();)
+                it = it->second < t.cursor ? t.last_region.erase(it) : std::next(it);
+            t.pruned_at = t.last_region.size();
+        }
+        for (uint32_t q = 0; q < k.n_rules; ++q) {
+            RegionSig sig;
+            bool empty;
+            region_signature(c, k.rules[q], r, sig, empty);
+            if (empty) continue;
+            size_t &last = t.last_region.try_emplace(sig, (size_t)-1).first->second;
+            const uint32_t back = (last != (size_t)-1 && i - last < 0xFFFFFFFFull) ? (uint32_t)(i - last) : 0u;
+            last = i;
+            if (k.rules[q].kind == MSCHED_RULE_LIST) {
+                flag |= kCmdList;
+                list_back = back;
+            } else if (!(flag & kCmdNoPaint) && !append_ranges(c, k.rules[q], q, r, back, t.ranges, first, kMaxRanges)) {
+                flag |= kCmdNoPaint;               // too many chunks to keep: plans that hold this command expand it per page
+                t.ranges.resize(first);
+            }
+        }
+        t.lat[li] = latency_ticks; t.n_ids[li] = n_ids; t.ids[li] = id_list; t.prep[li] = 0;
+        t.flag[li] = flag; t.list_back[li] = list_back;
+        t.range_end[li] = t.ranges_base + t.ranges.size();
+        t.n++;
+        unwind.armed = false;
+        return MSCHED_OK;
+    });
 }
 
 int msched_launch_retire(msched_ctx *c, uint32_t task, uint32_t n_launches) {
@@ -431,7 +479,7 @@ bool ring_alloc(msched_ctx *c, TaskQueue &t, uint64_t bytes, uint64_t &off) {
     if (head + bytes - t.prep_tail > t.prep_size) {
         t.prep_tail = t.prep_head;                                     // nothing live, unless a queued command says otherwise
         for (size_t i = t.cursor; i < t.n; ++i)                        // (mostly, not strictly, in program order: take the oldest)
-            if (t.recs[i - t.base].reserved) t.prep_tail = std::min(t.prep_tail, t.recs[i - t.base].reserved - 1);
+            if (t.prep[i - t.base]) t.prep_tail = std::min(t.prep_tail, t.prep[i - t.base] - 1);
         if (head + bytes - t.prep_tail > t.prep_size) return false;
     }
     off = head;
@@ -439,10 +487,22 @@ bool ring_alloc(msched_ctx *c, TaskQueue &t, uint64_t bytes, uint64_t &off) {
     return true;
 }
 
+// Give back the ring blocks a plan reserved for id lists it was going to prepare itself, newest first: the plan
+// failed before its kernels were launched, so the blocks hold nothing.
+void undo_reservations(msched_ctx *c) {
+    for (auto it = c->reserved.rbegin(); it != c->reserved.rend(); ++it) {
+        TaskQueue &t = c->tasks[it->task];
+        t.prep[it->cmd - t.base] = 0;
+        t.prep_head = it->head;
+    }
+    c->reserved.clear();
+}
+
 // The pieces of every live id list of the plan: prepared on first sight, reused by every later plan that still
 // has the command in its timeline (a command is typically planned once per task of the round).
 // Returns 0 and fills the two pinned tables, 1 when the pieces do not fit (the caller bins from scratch), or < 0.
-int gather_list_sources(msched_ctx *c, uint32_t G, PlanGeom &g) {
+// Blocks reserved here are listed in c->reserved until the plan's kernels are out.
+int gather_list_sources(msched_ctx *c, PlanGeom &g) {
     // first use; each piece on its own so that a failure half-way neither leaks nor leaves a hole
     if (!c->list_src_host) HIP_TRY(c, hipHostMalloc((void **)&c->list_src_host, sizeof(ListSource) * kMaxListSources, hipHostMallocDefault));
     if (!c->list_src_dev) HIP_TRY(c, hipHostGetDevicePointer((void **)&c->list_src_dev, c->list_src_host, 0));
@@ -458,42 +518,32 @@ int gather_list_sources(msched_ctx *c, uint32_t G, PlanGeom &g) {
         c->bucket_mark = marks;
     }
     uint32_t n_src = 0, n_new = 0;
-    std::vector<CmdRec *> fresh;
-    std::vector<std::pair<TaskQueue *, uint64_t>> heads;
-    auto undo = [&]() {
-        for (CmdRec *r : fresh) r->reserved = 0;
-        for (auto it = heads.rbegin(); it != heads.rend(); ++it) it->first->prep_head = it->second;
-    };
+    c->reserved.clear();
     const uint64_t hdr_words = (uint64_t)g.n_buckets + 2;
-    for (uint32_t gi = 0; gi < G; ++gi) {
-        CmdRec &rec = const_cast<CmdRec &>(*c->plan_recs[gi]);
-        const DevKernel &k = c->kernels[rec.kernel];
-        const uint64_t skip = reinterpret_cast<uintptr_t>(c->cmd_ptrs_host[gi]) >> 56;
-        bool live = false;
-        for (uint32_t r = 0; r < k.n_rules; ++r) live |= k.rules[r].kind == MSCHED_RULE_LIST && !((skip >> r) & 1);
-        if (!live || rec.n_ids == 0) continue;
-        const uint32_t pieces = (rec.n_ids + kPrepBlock - 1) / kPrepBlock;
-        if (n_src + pieces > kMaxListSources) { undo(); return 1; }
-        TaskQueue &t = c->tasks[c->plan_task[gi]];
-        const bool is_new = rec.reserved == 0;
-        if (is_new) {
-            const uint64_t bytes = (((uint64_t)pieces * hdr_words + rec.n_ids) * 4 + 15) & ~15ull;
-            uint64_t off;
-            heads.emplace_back(&t, t.prep_head);
-            if (!ring_alloc(c, t, bytes, off)) {
-                heads.pop_back();
-                undo();
-                return 1;
+    for (const PlanRun &run : c->runs) {
+        TaskQueue &t = c->tasks[run.task];
+        for (uint32_t j = 0; j < run.count; ++j) {
+            const size_t i = run.first + j, li = i - t.base;
+            if (!(t.flag[li] & kCmdList) || repeats_queued(c, t, i, t.list_back[li])) continue;
+            const uint32_t n_ids = t.n_ids[li];
+            const uint32_t pieces = (n_ids + kPrepBlock - 1) / kPrepBlock;
+            if (n_src + pieces > kMaxListSources) { undo_reservations(c); return 1; }
+            const bool is_new = t.prep[li] == 0;
+            if (is_new) {
+                const uint64_t bytes = (((uint64_t)pieces * hdr_words + n_ids) * 4 + 15) & ~15ull;
+                const uint64_t head = t.prep_head;
+                uint64_t off;
+                if (!ring_alloc(c, t, bytes, off)) { undo_reservations(c); return 1; }
+                t.prep[li] = off + 1;
+                c->reserved.push_back({run.task, i, head});
             }
-            rec.reserved = off + 1;
-            fresh.push_back(&rec);
-        }
-        uint32_t *block = reinterpret_cast<uint32_t *>(t.prep_buf + (rec.reserved - 1) % t.prep_size);
-        for (uint32_t p = 0; p < pieces; ++p) {
-            const uint32_t n = std::min<uint32_t>(kPrepBlock, rec.n_ids - p * kPrepBlock);
-            if (is_new) c->list_prep_host[n_new++] = {rec.ids + (size_t)p * kPrepBlock, block, n, {0, 0, 0}};
-            c->list_src_host[n_src++] = {block, gi, 0};
-            block += hdr_words + n;
+            uint32_t *block = reinterpret_cast<uint32_t *>(t.prep_buf + (t.prep[li] - 1) % t.prep_size);
+            for (uint32_t p = 0; p < pieces; ++p) {
+                const uint32_t n = std::min<uint32_t>(kPrepBlock, n_ids - p * kPrepBlock);
+                if (is_new) c->list_prep_host[n_new++] = {t.ids[li] + (size_t)p * kPrepBlock, block, n, {0, 0, 0}};
+                c->list_src_host[n_src++] = {block, run.g0 + j, 0};
+                block += hdr_words + n;
+            }
         }
     }
     g.n_list_sources = n_src;
@@ -513,6 +563,29 @@ int msched_plan(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entri
 
 namespace {
 
+// Bit r of a command's mask: rule r of its template has nothing to add to this plan - it describes nothing, or
+// repeats a region of a command that is still queued in front of it.  Only the per-page and binning kernels, which
+// read whole records, want this; the mask rides in the top byte of the record's address (addresses use 48 bits).
+uint64_t skip_mask(const msched_ctx *c, const TaskQueue &t, size_t i) {
+    const size_t li = i - t.base;
+    const DevKernel &k = c->kernels[t.recs[li].kernel];
+    if (t.flag[li] & kCmdNoPaint) {                            // nothing was kept of its ranges: every range rule is expanded
+        uint64_t skip = 0;
+        for (uint32_t r = 0; r < k.n_rules; ++r)
+            if (k.rules[r].kind == MSCHED_RULE_LIST &&
+                (!(t.flag[li] & kCmdList) || repeats_queued(c, t, i, t.list_back[li]))) skip |= 1ull << r;
+        return skip;
+    }
+    uint64_t live = 0;
+    for (uint64_t q = t.range_begin(i); q < t.range_end[li]; ++q) {
+        const RangeRec &rr = t.ranges[q - t.ranges_base];
+        if (!repeats_queued(c, t, i, rr.back)) live |= 1ull << rr.rule;
+    }
+    if ((t.flag[li] & kCmdList) && !repeats_queued(c, t, i, t.list_back[li]))
+        for (uint32_t r = 0; r < k.n_rules; ++r) if (k.rules[r].kind == MSCHED_RULE_LIST) live |= 1ull << r;
+    return ~live & ((1ull << k.n_rules) - 1);
+}
+
 int plan_body(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entries, msched_plan_t *out) {
     if (!c || !out || (n_entries && !tl) || n_entries > MSCHED_MAX_TIMELINE_ENTRIES) return MSCHED_E_INVAL;
     for (uint32_t e = 0; e < n_entries; ++e) if (tl[e].task >= c->tasks.size()) return MSCHED_E_INVAL;
@@ -523,59 +596,46 @@ int plan_body(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entries
     // Flatten the timeline into the order of future commands (Sec. 6.1: the timeline says which
     // task runs, for how long and in what order; Sec. 6.2: each queue holds command latencies).
     // A command belongs to the entry in which it starts.  G sizes every launch below, so this
-    // short walk is done here and its result handed to the kernels as a table of record addresses.
-    std::vector<size_t> pos(c->tasks.size());
-    for (size_t t = 0; t < c->tasks.size(); ++t) pos[t] = c->tasks[t].cursor;
+    // short walk over the latencies is done here; an entry becomes one run of consecutive commands.
+    for (size_t t = 0; t < c->tasks.size(); ++t) c->pos[t] = c->tasks[t].cursor;
+    c->runs.clear();
     uint32_t G = 0, g_end0 = 0;
     for (uint32_t e = 0; e < n_entries; ++e) {
-        TaskQueue &t = c->tasks[tl[e].task];
-        size_t &p = pos[tl[e].task];
+        const TaskQueue &t = c->tasks[tl[e].task];
+        size_t &p = c->pos[tl[e].task];
+        const size_t first = p;
+        const uint32_t g0 = G;
         uint64_t elapsed = 0;
         while (p < t.n && elapsed < tl[e].timeslice) {
             if (G == MSCHED_MAX_TIMELINE_COMMANDS) return MSCHED_E_INVAL;
-            c->plan_recs[G] = &t.recs[p - t.base];
-            c->plan_task[G] = tl[e].task;
-            c->cmd_ptrs_host[G++] = t.recs_dev + (p - t.base);
-            elapsed += t.recs[p - t.base].latency;
-            ++p;
+            elapsed += t.lat[p - t.base];
+            ++p; ++G;
         }
+        if (p > first) c->runs.push_back(PlanRun{tl[e].task, g0, (uint32_t)(p - first), first});
         if (e == 0) g_end0 = G;
     }
-    ++c->dedupe_stamp;                   // per attempt, not per successful plan: a refused plan leaves its entries behind
-    if (c->dedupe_regions && G > 1) {
-        // bit r of a command's skip mask: rule r repeats a region an earlier command already brought
-        // in.  The mask rides in the top byte of the record's address (addresses use 48 bits).  The
-        // table is sized to this plan so that it stays in the host's cache.
-        size_t cap = 64;
-        while (cap < (size_t)4 * G * std::max<uint32_t>(1, c->max_rules)) cap <<= 1;
-        cap = std::min(cap, c->seen.size());
-        for (uint32_t g = 0; g < G; ++g) {
-            const CmdRec &rec = *c->plan_recs[g];
-            const DevKernel &k = c->kernels[rec.kernel];
-            const TaskQueue &t = c->tasks[c->plan_task[g]];
-            const RegionSig *sigs = t.sig.data() + (size_t)(&rec - t.recs) * MSCHED_MAX_RULES;   // computed at enqueue
-            uint64_t skip = 0;
-            for (uint32_t r = 0; r < k.n_rules; ++r) {
-                const RegionSig &sig = sigs[r];
-                const bool empty = sig.a == ~0ull && sig.b == ~0ull;
-                if (empty || seen_before(c, sig, cap - 1)) skip |= 1ull << r;
-            }
-            c->cmd_ptrs_host[g] = reinterpret_cast<const CmdRec *>(
-                reinterpret_cast<uintptr_t>(c->cmd_ptrs_host[g]) | (skip << 56));
-        }
-    }
-    // Range rules as a list of page ranges: the sweeps paint them into LDS tile by tile, and no per-page next
-    // use goes through memory.  Id lists, and plans with more ranges than the list holds, scatter into nu[].
+    // Range rules as a list of page ranges, copied from what msched_launch_enqueue worked out, with the command's
+    // position: the sweeps paint them into LDS tile by tile, and no per-page next use goes through memory.  Rules
+    // that repeat a region of a command queued in front of them are left out.  Id lists, and plans with more
+    // ranges than the list holds, scatter into nu[].
     uint32_t n_ranges = 0;
     bool painted = c->paint != 0, live_list = false;
-    for (uint32_t g = 0; g < G; ++g) {
-        const CmdRec &rec = *c->plan_recs[g];
-        const DevKernel &k = c->kernels[rec.kernel];
-        const uint64_t skip = reinterpret_cast<uintptr_t>(c->cmd_ptrs_host[g]) >> 56;
-        for (uint32_t r = 0; r < k.n_rules; ++r) {
-            if ((skip >> r) & 1) continue;
-            if (k.rules[r].kind == MSCHED_RULE_LIST) { live_list |= rec.n_ids != 0; continue; }
-            if (painted && !append_ranges(c, k.rules[r], rec, g, c->ranges_host, n_ranges, kMaxRanges)) painted = false;
+    uint64_t total_ids = 0;
+    for (const PlanRun &run : c->runs) {
+        const TaskQueue &t = c->tasks[run.task];
+        for (uint32_t j = 0; j < run.count; ++j) {
+            const size_t i = run.first + j, li = i - t.base;
+            const uint8_t flag = t.flag[li];
+            if ((flag & kCmdList) && !repeats_queued(c, t, i, t.list_back[li])) { live_list = true; total_ids += t.n_ids[li]; }
+            if (flag & kCmdNoPaint) painted = false;
+            if (!painted) continue;
+            const uint32_t g = run.g0 + j;
+            for (uint64_t q = t.range_begin(i), q1 = t.range_end[li]; q < q1; ++q) {
+                const RangeRec &rr = t.ranges[q - t.ranges_base];
+                if (repeats_queued(c, t, i, rr.back)) continue;
+                if (n_ranges == kMaxRanges) { painted = false; break; }
+                c->ranges_host[n_ranges++] = PageRange{rr.lo, rr.hi, g, 0};
+            }
         }
     }
     memset(out, 0, sizeof *out);
@@ -593,48 +653,7 @@ int plan_body(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entries
         g.painted = painted;
         g.n_ranges = painted ? n_ranges : 0;
         g.use_nu = !painted || live_list;
-        // Id lists: how many ids does this plan carry (repeated lists excluded)?  Many -> bucket path.
-        g.list_binned = false;
-        g.list_prepared = false;
-        g.n_list_sources = g.n_list_new = 0;
-        g.n_buckets = (uint32_t)((c->V + (1u << kBucketShift) - 1) >> kBucketShift);
-        if (c->has_list_rule && g.n_buckets <= kMaxBuckets) {
-            uint64_t total = 0;
-            for (uint32_t gi = 0; gi < G; ++gi) {
-                const CmdRec &rec = *c->plan_recs[gi];
-                const DevKernel &k = c->kernels[rec.kernel];
-                const uint64_t skip = reinterpret_cast<uintptr_t>(c->cmd_ptrs_host[gi]) >> 56;
-                bool live = false;
-                for (uint32_t r = 0; r < k.n_rules; ++r)
-                    live |= k.rules[r].kind == MSCHED_RULE_LIST && !((skip >> r) & 1);
-                if (live) total += rec.n_ids;
-            }
-            if (total >= c->list_binned_min_ids && total < (1ull << 31) && c->list_prepared) {
-                const int rc_src = gather_list_sources(c, G, g);
-                if (rc_src < 0) return rc_src;
-                g.list_prepared = rc_src == 0;
-            }
-            c->last_plan_prepared = g.list_prepared;
-            if (total >= c->list_binned_min_ids && total < (1ull << 31) && !g.list_prepared) {
-                g.list_binned = true;
-                // room per sub-segment (8 per bucket): four times the average, at least 256 pairs
-                g.bucket_cap = (uint32_t)std::max<uint64_t>(256, 4 * total / ((uint64_t)g.n_buckets * 8) + 1);
-                const size_t need = (size_t)g.n_buckets * 8 * g.bucket_cap;
-                if (!c->list_bucket_fill) HIP_TRY(c, hipMalloc((void **)&c->list_bucket_fill, 4 * kMaxBuckets * 8));
-                if (need > c->list_cap) {
-                    HIP_TRY(c, hipStreamSynchronize(c->stream));
-                    if (c->list_pairs) HIP_TRY(c, hipFree(c->list_pairs));
-                    c->list_pairs = nullptr; c->list_cap = 0;
-                    HIP_TRY(c, hipMalloc((void **)&c->list_pairs, (need + need / 4) * 4));
-                    c->list_cap = need + need / 4;
-                }
-            }
-        }
-        if (c->epoch == kMaxEpoch) {                 // the epoch field is about to wrap: start over
-            HIP_TRY(c, launch_nu_reset(c));
-            c->epoch = 0;
-        }
-        ++c->epoch;
+        g.live_list = live_list;
         const size_t need = (size_t)g.n_chunks * g.n_keys;
         if (need > c->matrix_cap) {
             HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -643,9 +662,65 @@ int plan_body(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entries
             HIP_TRY(c, hipMalloc((void **)&c->matrix, need * 4 * 2));     // counts, and behind them the chunk start positions
             c->matrix_cap = need;
         }
+        // Id lists: how many ids does this plan carry (repeated lists excluded)?  Many -> bucket path.
+        g.list_binned = false;
+        g.list_prepared = false;
+        g.n_list_sources = g.n_list_new = 0;
+        g.n_buckets = (uint32_t)((c->V + (1u << kBucketShift) - 1) >> kBucketShift);
+        c->reserved.clear();
+        if (c->has_list_rule && g.n_buckets <= kMaxBuckets) {
+            const bool many = live_list && total_ids >= c->list_binned_min_ids && total_ids < (1ull << 31);
+            if (many && c->list_prepared) {
+                const int rc_src = gather_list_sources(c, g);
+                if (rc_src < 0) return rc_src;
+                g.list_prepared = rc_src == 0;
+            }
+            c->last_plan_prepared = g.list_prepared;
+            if (many && !g.list_prepared) {
+                g.list_binned = true;
+                // room per sub-segment (8 per bucket): four times the average, at least 256 pairs
+                g.bucket_cap = (uint32_t)std::max<uint64_t>(256, 4 * total_ids / ((uint64_t)g.n_buckets * 8) + 1);
+                const size_t pairs = (size_t)g.n_buckets * 8 * g.bucket_cap;
+                if (!c->list_bucket_fill) HIP_TRY(c, hipMalloc((void **)&c->list_bucket_fill, 4 * kMaxBuckets * 8));
+                if (pairs > c->list_cap) {
+                    HIP_TRY(c, hipStreamSynchronize(c->stream));
+                    if (c->list_pairs) HIP_TRY(c, hipFree(c->list_pairs));
+                    c->list_pairs = nullptr; c->list_cap = 0;
+                    HIP_TRY(c, hipMalloc((void **)&c->list_pairs, (pairs + pairs / 4) * 4));
+                    c->list_cap = pairs + pairs / 4;
+                }
+            }
+        }
+        // From here to the launch, a failure must give the reserved ring blocks back: the records would otherwise
+        // point at blocks that hold no list, and the next plan would merge whatever is in them.
+        struct GiveBack {
+            msched_ctx *c; bool armed = true;
+            ~GiveBack() { if (armed) undo_reservations(c); }
+        } give_back{c};
+        // The kernels that read whole records (next uses scattered per page, id lists binned per plan or expanded
+        // directly) find them through a table of record addresses, one per position; painted plans whose lists
+        // are prepared need no record on the device.
+        g.needs_records = !painted || (live_list && !g.list_prepared);
+        if (g.needs_records) {
+            for (const PlanRun &run : c->runs) {
+                const TaskQueue &t = c->tasks[run.task];
+                for (uint32_t j = 0; j < run.count; ++j) {
+                    const size_t i = run.first + j;
+                    c->cmd_ptrs_host[run.g0 + j] = reinterpret_cast<const CmdRec *>(
+                        reinterpret_cast<uintptr_t>(t.recs_dev + (i - t.base)) | (skip_mask(c, t, i) << 56));
+                }
+            }
+        }
+        if (c->epoch == kMaxEpoch) {                 // the epoch field is about to wrap: start over
+            HIP_TRY(c, launch_nu_reset(c));
+            c->epoch = 0;
+        }
+        ++c->epoch;
         const clk::time_point t_prep = clk::now();
         if (++c->hdr_seq == 0) c->hdr_seq = 1;
         HIP_TRY(c, launch_plan(c, g));
+        give_back.armed = false;                      // the preparation is queued: the blocks will hold their lists
+        c->reserved.clear();
         const clk::time_point t_launch = clk::now();
         // The counts are all the caller waits for: the cut stamps the pinned header once they (and need[]) are
         // written, while the second sweep is still filling the lists, which only stream-ordered work reads.
@@ -707,7 +782,8 @@ void prepare_ahead(msched_ctx *c) {
     const uint64_t hdr_words = (uint64_t)n_buckets + 2;
     uint32_t n_new = 0;
     bool full = false;
-    std::vector<CmdRec *> fresh;
+    struct Fresh { uint32_t task; size_t li; };
+    std::vector<Fresh> fresh;
     std::vector<size_t> scan0(c->tasks.size());
     for (size_t ti = 0; ti < c->tasks.size(); ++ti) {
         TaskQueue &t = c->tasks[ti];
@@ -715,19 +791,20 @@ void prepare_ahead(msched_ctx *c) {
         size_t i = std::max(t.prep_scan, t.cursor);
         const size_t end = std::min(t.n, t.cursor + (size_t)c->list_ahead);
         for (; i < end && !full; ++i) {
-            CmdRec &rec = t.recs[i - t.base];
-            if (!c->kernel_has_list[rec.kernel] || rec.n_ids == 0 || rec.reserved) continue;
-            const uint32_t pieces = (rec.n_ids + kPrepBlock - 1) / kPrepBlock;
+            const size_t li = i - t.base;
+            if (!(t.flag[li] & kCmdList) || t.prep[li]) continue;
+            const uint32_t n_ids = t.n_ids[li];
+            const uint32_t pieces = (n_ids + kPrepBlock - 1) / kPrepBlock;
             if (n_new + pieces > kMaxListSources) { full = true; break; }
-            const uint64_t bytes = (((uint64_t)pieces * hdr_words + rec.n_ids) * 4 + 15) & ~15ull;
+            const uint64_t bytes = (((uint64_t)pieces * hdr_words + n_ids) * 4 + 15) & ~15ull;
             uint64_t off;
             if (!ring_alloc(c, t, bytes, off)) break;        // no room now: the plan that needs it will see to it
-            rec.reserved = off + 1;
-            fresh.push_back(&rec);
+            t.prep[li] = off + 1;
+            fresh.push_back({(uint32_t)ti, li});
             uint32_t *block = reinterpret_cast<uint32_t *>(t.prep_buf + off % t.prep_size);
             for (uint32_t p = 0; p < pieces; ++p) {
-                const uint32_t n = std::min<uint32_t>(kPrepBlock, rec.n_ids - p * kPrepBlock);
-                c->list_ahead_host[n_new++] = {rec.ids + (size_t)p * kPrepBlock, block, n, {0, 0, 0}};
+                const uint32_t n = std::min<uint32_t>(kPrepBlock, n_ids - p * kPrepBlock);
+                c->list_ahead_host[n_new++] = {t.ids[li] + (size_t)p * kPrepBlock, block, n, {0, 0, 0}};
                 block += hdr_words + n;
             }
         }
@@ -741,7 +818,7 @@ void prepare_ahead(msched_ctx *c) {
         // nothing was binned: the records must not point at blocks that hold no list
         // (a launch that did go out before a failed record is waited for, so the table is not rewritten under it)
         (void)hipStreamSynchronize(c->stream);
-        for (CmdRec *r : fresh) r->reserved = 0;
+        for (const Fresh &f : fresh) c->tasks[f.task].prep[f.li] = 0;
         for (size_t ti = 0; ti < c->tasks.size(); ++ti) c->tasks[ti].prep_scan = scan0[ti];
         return give_up(e);
     }

@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <unordered_map>
 #include <vector>
 
 #include "msched.h"
@@ -34,8 +35,7 @@ constexpr uint32_t kStatWset = 2u;              // first command alone exceeds t
 struct alignas(16) CmdRec {
     uint32_t kernel, n_args, latency, n_ids;
     const uint32_t *ids;                        // device pointer (caller-owned) or null
-    uint64_t reserved;                          // host copy: 1 + ring offset of the command's prepared id list (0 = none);
-                                                // device copy: mask of rules to skip in this plan
+    uint64_t reserved;                          // host copy: 0; device copy: mask of rules to skip in this plan
     uint64_t args[MSCHED_MAX_ARGS];
 };
 static_assert(sizeof(CmdRec) == 128, "CmdRec layout");
@@ -53,22 +53,57 @@ struct PlanHeader {
 };
 
 // What a rule of a queued command describes, as an exact tuple (page range of a fixed / linear rule; the four
-// strided parameters; address and length of an id list).  a == b == ~0: the rule describes nothing.
-struct RegionSig { uint64_t a, b, c, d; };
+// strided parameters; address and length of an id list).
+struct RegionSig {
+    uint64_t a, b, c, d;
+    bool operator==(const RegionSig &o) const { return a == o.a && b == o.b && c == o.c && d == o.d; }
+};
+struct RegionSigHash {
+    size_t operator()(const RegionSig &s) const {
+        uint64_t h = s.a * 0x9E3779B97F4A7C15ull ^ (s.b + 0x7F4A7C15ull) * 0xC2B2AE3D27D4EB4Full ^
+                     (s.c * 0x165667B19E3779F9ull) ^ (s.d * 0x27D4EB2F165667C5ull);
+        return (size_t)(h ^ (h >> 29));
+    }
+};
+
+// One page range [lo, hi) of a queued command, evaluated when the launch was queued (Sec. 5.2: the predictor
+// evaluates the formulas with the launch arguments at launch time).  `back` is the distance, in commands of the
+// task, to the latest earlier command one of whose rules described the very same region (0: none): while that
+// command is still queued it comes first in every timeline, so this range cannot lower any page's first use and
+// a plan leaves it out.  All ranges of one rule share `back`; `rule` is the rule's index in its template.
+struct RangeRec { uint32_t lo, hi, back, rule; };
+constexpr uint8_t kCmdList = 1;                 // the command has a live id list (a LIST rule and at least one id)
+constexpr uint8_t kCmdNoPaint = 2;              // its ranges were too many to keep: plans that hold it scatter next uses per page
 
 struct TaskQueue {
-    CmdRec *recs = nullptr;                     // pinned host memory
-    std::vector<RegionSig> sig;                 // [cap][MSCHED_MAX_RULES] the regions of recs[i]'s rules, computed once at enqueue
+    CmdRec *recs = nullptr;                     // pinned host memory: what kernels read of a command (the per-page and binning paths)
     CmdRec *recs_dev = nullptr;                 // same memory, device address
     size_t cap = 0;                             // records allocated
     size_t base = 0;                            // program-order index of recs[0]
     size_t n = 0;                               // commands ever enqueued
     size_t cursor = 0;                          // first command not yet retired
+    // What a plan walks: compact arrays in ordinary host memory, entry i - base for command i.  Everything a plan
+    // needs of a command was worked out when it was queued; the plan only reads, in order.
+    std::vector<uint32_t> lat;                  // profiled latency
+    std::vector<uint64_t> range_end;            // the command's ranges are ranges[range_end[i - 1] - ranges_base, range_end[i] - ranges_base)
+    std::vector<uint32_t> n_ids;
+    std::vector<const uint32_t *> ids;          // device pointer (caller-owned) or null
+    std::vector<uint32_t> list_back;            // like RangeRec::back, for the id list (same address and length)
+    std::vector<uint8_t> flag;                  // kCmdList, kCmdNoPaint
+    std::vector<uint64_t> prep;                 // 1 + ring offset of the command's prepared id list (0 = none)
+    std::vector<RangeRec> ranges;
+    uint64_t ranges_base = 0;                   // running index of ranges[0]
+    std::unordered_map<RegionSig, size_t, RegionSigHash> last_region;   // region -> latest command that described it
+    size_t pruned_at = 0;                       // size of last_region after its last clean-up
     // prepared id lists of this task's queued commands: a ring in device memory, filled in program order
     uint8_t *prep_buf = nullptr;
     uint64_t prep_size = 0, prep_head = 0, prep_tail = 0;   // head / tail are running byte offsets (never wrap)
     size_t prep_scan = 0;                       // commands before this index have been looked at by the look-ahead preparation
+    uint64_t range_begin(size_t i) const { return i == base ? ranges_base : range_end[i - base - 1]; }
 };
+
+// A run of one timeline entry: commands [first, first + count) of `task` take the positions g0, g0 + 1, ...
+struct PlanRun { uint32_t task, g0, count; size_t first; };
 
 // One source of the id-list merge: a prepared (de-duplicated, grouped by bucket) piece of a command's list.
 //   block[0] = 1 if the piece held an id that is out of range or has no backing slot
@@ -94,6 +129,8 @@ struct PlanGeom {
     bool list_prepared;                                  // ... from per-command prepared pieces (cached across plans)
     uint32_t n_list_sources, n_list_new;                 // pieces merged by this plan; of those, prepared by it
     uint32_t n_buckets, bucket_cap;                      // bucket_cap: pairs per sub-segment
+    bool live_list;                                      // some command of the plan brings an id list that is not a repeat
+    bool needs_records;                                  // some kernel of the plan reads whole command records (table of record addresses filled)
     bool painted;                                        // range rules arrive as a range list the sweeps paint into LDS
     bool use_nu;                                         // some next uses are in nu[] (id lists, or the scatter path)
     uint32_t n_ranges;
@@ -116,10 +153,11 @@ struct msched_ctx {
     uint32_t expand_split = 0;                  // workgroups per (command, rule); 0 = by page-table size
     uint32_t max_chunks = msched::kMaxChunks;   // page-table chunks (sweep workgroups) at most
     uint32_t stage_threshold = 2048;            // expansion workgroups above which records are staged first
-    bool dedupe_regions = true;                 // skip rules that repeat a region seen earlier in the plan
-    struct SeenEntry { uint64_t a, b, c, d, stamp; };
-    std::vector<const msched::CmdRec *> plan_recs;   // host addresses of this plan's records, in g order
-    std::vector<SeenEntry> seen;                // open-addressing table of region signatures, stamped per plan
+    bool dedupe_regions = true;                 // leave out rules that repeat a region an earlier queued command of the task describes
+    std::vector<msched::PlanRun> runs;          // the flattened timeline of the plan being made, one run per entry
+    std::vector<size_t> pos;                    // per task: next command the flattening takes
+    struct Reserved { uint32_t task; size_t cmd; uint64_t head; };
+    std::vector<Reserved> reserved;             // ring blocks this plan handed out for id lists it prepares itself (undone if it fails)
     bool force_multi_kernel = false;            // test hook: never use the fused single-workgroup tail
     bool no_large_lds = false;                  // MSCHED_NO_LARGE_LDS: never ask for more than the default dynamic LDS
     bool has_list_rule = false;                 // some registered kernel has a LIST rule
@@ -135,7 +173,6 @@ struct msched_ctx {
     msched::ListPrep *list_prep_dev = nullptr;
     uint32_t *bucket_mark = nullptr;               // device [kMaxBuckets]: buckets some prepared piece has put an id in; then [kMaxChunks] chunk order
     msched::ListSource *list_src_stage = nullptr;  // device copy of the source table (every merge workgroup reads it)
-    std::vector<uint32_t> plan_task;               // task of the g-th future command
     // look-ahead preparation: id lists of queued commands are binned behind a migration, off the plan's path
     uint32_t list_ahead = 128;                     // commands per task looked ahead at each migration (MSCHED_LIST_AHEAD, 0 = off)
     msched::ListPrep *list_ahead_host = nullptr;   // pinned [kMaxListSources]
@@ -163,7 +200,6 @@ struct msched_ctx {
     uint32_t max_rules = 0;
     uint32_t n_resident = 0;
     uint64_t plan_seq = 0, pending_plan = 0;    // pending_plan == 0: nothing to migrate
-    uint64_t dedupe_stamp = 0;                  // tags the entries of the repeat-region table with the plan attempt that wrote them
     msched::PlanHeader pending{};
     uint32_t *query_buf = nullptr; size_t query_cap = 0;     // device scratch for pagetable_query
     // early execution: in-order landing of the fetch list

@@ -107,7 +107,20 @@ __global__ __launch_bounds__(256) void k_migrate(MigrateArgs a) {
             }
         }
         if (!kEarly) {
-            if (chunk_off == 0 && threadIdx.x == 0) {          // unmap the victim, map the target
+            // Unmap the victim, map the target: the last of the four steps of a swap (Sec. 6.3), so it comes after
+            // the page's last chunk.  A page of one chunk is mapped by the workgroup that copied it; the chunks of a
+            // larger page are counted, and the workgroup whose chunk completes the count maps it.  (Readers of the
+            // table are ordered behind the whole kernel by the stream; the order inside it is the paper's.)
+            bool complete = true;
+            if (cpp_shift) {
+                __builtin_amdgcn_s_waitcnt(0);                 // this lane's loads and stores have been acknowledged
+                __syncthreads();
+                if (threadIdx.x == 0) {
+                    complete = __hip_atomic_fetch_add(&a.chunks_done[i], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1 == (1u << cpp_shift);
+                    if (complete) __hip_atomic_store(&a.chunks_done[i], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next migration
+                }
+            }
+            if (complete && threadIdx.x == 0) {
                 if (swap) a.page_table[vpage] = kNone;
                 a.page_table[fpage] = frame;
                 a.frame_owner[frame] = fpage;
@@ -116,8 +129,12 @@ __global__ __launch_bounds__(256) void k_migrate(MigrateArgs a) {
         }
         // Early execution: declare the entry complete and move `landed` over every leading complete entry.
         // All atomics below are relaxed and write through to the device's coherence point; program order between
-        // them is kept by waiting for each to be acknowledged (the workgroup-scope fences are those waits).
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this lane's stores have been acknowledged
+        // them is kept by waiting for each to be acknowledged.  The wait is written out (s_waitcnt 0: every
+        // outstanding load, write-through frame store and non-temporal host store of this lane has been
+        // acknowledged) and does not rest on how the compiler lowers a workgroup-scope fence, which it may lower
+        // to nothing when a workgroup cannot span compute units.
+        __builtin_amdgcn_s_waitcnt(0);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __syncthreads();
         if (threadIdx.x == 0) {
             bool complete = true;
@@ -132,6 +149,7 @@ __global__ __launch_bounds__(256) void k_migrate(MigrateArgs a) {
                 // "mine is done" then "how far are we", against "we are this far" then "is the next one done":
                 // with each step acknowledged before the next is issued, one of two workgroups sees the other's write
                 __hip_atomic_store(&a.page_done[i], a.early_tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __builtin_amdgcn_s_waitcnt(0);                 // the table and the mark are out before `landed` is read
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
                 uint32_t p = __hip_atomic_load(a.landed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 while (p < a.n_fetch &&
@@ -231,7 +249,8 @@ hipError_t launch_migrate(msched_ctx *c, const PlanHeader &h) {
     a.n_fetch = h.n_fetch; a.n_free_used = h.n_free_used; a.page_shift = c->page_shift;
     a.chunk_shift = std::min<uint32_t>(c->page_shift, c->migrate_chunk_shift);
     a.hints = c->migrate_hints;
-    a.page_done = a.chunks_done = a.landed = nullptr; a.early_tag = 0;
+    a.page_done = a.landed = nullptr; a.early_tag = 0;
+    a.chunks_done = c->chunks_done;                            // counts the chunks of pages larger than a work unit (null if none can be)
     if (c->early && c->plan_early) {
         // Workgroups take consecutive chunks, so with chunks much smaller than the whole transfer the
         // entries are worked on, and complete, in list order.

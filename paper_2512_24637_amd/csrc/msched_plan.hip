@@ -1473,14 +1473,15 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         a.nu = c->nu; a.slot = c->slot; a.flags = c->flags; a.V = c->V; a.page_shift = c->page_shift;
         a.n_split = c->expand_split ? c->expand_split : ((c->V > (1u << 20)) ? 8 : 1);
         a.epoch_base = c->epoch << kNuShift;
-        // few expansion workgroups: each reads its record over the link itself; many: stage once
-        // painted plans without id lists need no command records on the device at all
-        const bool records = !g.painted || c->has_list_rule;
-        const bool stage = records && ((uint64_t)g.G * c->max_rules * a.n_split > c->stage_threshold || c->has_list_rule);
-        a.cmds = stage ? c->cmd_dev : nullptr;
+        // Records travel only when some kernel of this plan reads them (needs_records): a few expansion workgroups
+        // read their record over the link themselves, many - and the id-list kernels - find a staged copy.  Painted
+        // plans whose lists are prepared send only the two small tables (ranges, list pieces).
+        const bool stage_records = g.needs_records &&
+                                   ((uint64_t)g.G * c->max_rules * a.n_split > c->stage_threshold || g.live_list);
+        const bool stage = stage_records || g.list_prepared || g.list_binned;
+        a.cmds = stage_records ? c->cmd_dev : nullptr;
         const bool copy_ranges = g.n_ranges && !g.single;
-        // prepared id lists and painted ranges together need no record on the device: only the two small tables travel
-        const uint32_t n_records = (g.painted && g.list_prepared) ? 0u : g.G;
+        const uint32_t n_records = stage_records ? g.G : 0u;
         ChunkOrder co{nullptr, 0, 0, 0, 0, nullptr};
         if (fuse_lists) co = ChunkOrder{c->bucket_mark, g.n_buckets, g.n_chunks, g.rounds, 1, c->bucket_mark + kMaxBuckets};
         if (stage)
@@ -1493,21 +1494,21 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         // Id lists go first in three stream-ordered batches of growing size: the smallest g wins a page,
         // so once the first few commands have written the popular pages, the check in front of the
         // atomic turns every later touch of them into a plain (cached) load.
-        if (c->has_list_rule && g.list_prepared) {
+        if (g.list_prepared) {
             if (g.n_list_new) CK(launch_list_prepare(c, c->list_prep_dev, g.n_list_new, g.n_buckets));
             MergeArgs ma;
             ma.src = c->list_src_stage; ma.n_src = g.n_list_sources; ma.n_buckets = g.n_buckets;
             ma.nu = c->nu; ma.flags = c->flags; ma.V = c->V; ma.epoch_base = a.epoch_base; ma.bucket_mark = c->bucket_mark;
             if (g.n_list_sources && !fuse_lists)
                 k_list_merge<<<g.n_buckets, kListThreads, (size_t)g.n_list_sources * 16, st>>>(ma);
-        } else if (c->has_list_rule && g.list_binned) {
+        } else if (g.list_binned) {
             ListArgs la;
             la.e = a; la.bucket_fill = c->list_bucket_fill; la.pairs = c->list_pairs;
             la.n_buckets = g.n_buckets; la.sub_cap = g.bucket_cap;
             const size_t bin_lds = 4 * ((size_t)(1u << kBinSeenBits) + kBinBlock + g.n_buckets);
             k_list_bin<<<g.G, kListThreads, bin_lds, st>>>(la, 1);
             k_list_reduce<<<g.n_buckets, kListThreads, 0, st>>>(la);
-        } else if (c->has_list_rule) {
+        } else if (g.live_list) {
             const uint32_t b0 = std::min<uint32_t>(g.G, c->list_b0), b1 = std::min<uint32_t>(g.G, c->list_b1);
             if (b0) k_expand_list<<<b0 * 16, kListThreads, 0, st>>>(a, 0, 16, kListSeenBits - 3);
             if (b1 > b0) k_expand_list<<<(b1 - b0) * 4, kListThreads, 0, st>>>(a, b0, 4, kListSeenBits - 2);

@@ -17,19 +17,22 @@ def test_c2_stencil_full_size(oracle_mod):
     assert lockstep_sampled(oracle_mod, make_trace(2), n_sample=512, check_every=5, log=_log) == 80
 
 
-def test_c3_training_full_size_first_switches(oracle_mod):
-    trace = make_trace(3, iterations=3)            # full layer sizes and pool; 3 of the 20 iterations
-    assert lockstep_sampled(oracle_mod, trace, n_sample=8192, check_every=2, log=_log) >= 6
+def test_c3_training_full_size_all_20_iterations(oracle_mod):
+    trace = make_trace(3)                          # full layer sizes and pool, all 20 iterations of both tasks
+    assert sum(len(t) for t in trace.tasks) == 2 * 20 * 96
+    assert lockstep_sampled(oracle_mod, trace, n_sample=8192, check_every=4, log=_log) >= 40
 
 
-def test_c4_decode_full_size_first_switches(oracle_mod):
-    trace = make_trace(4, steps=24)                # full model and pool; 24 of the 256 decode steps
-    assert lockstep_sampled(oracle_mod, trace, n_sample=1024, check_every=3, log=_log) >= 12
+def test_c4_decode_full_size_all_256_steps(oracle_mod):
+    trace = make_trace(4)                          # full model and pool, all 256 decode steps of both tasks:
+    assert sum(len(t) for t in trace.tasks) == 2 * 256 * 64      # the cached sequence grows from 385 to 640 tokens
+    assert lockstep_sampled(oracle_mod, trace, n_sample=1024, check_every=8, log=_log) == 128
 
 
-def test_c5_planning_stress_full_size_first_switches(oracle_mod):
-    trace = make_trace(5, n_launches=100)          # full page counts; 100 of the 625 launches per task
-    assert lockstep_sampled(oracle_mod, trace, n_sample=16384, check_every=4, log=_log) >= 16
+def test_c5_planning_stress_full_size_all_5000_launches(oracle_mod):
+    trace = make_trace(5)                          # full page counts, all 625 launches of each of the 8 tasks
+    assert sum(len(t) for t in trace.tasks) == 5000
+    assert lockstep_sampled(oracle_mod, trace, n_sample=16384, check_every=10, log=_log) == 104      # 12.5 timeslices per task
 
 
 def test_c6_priority_colocation_full_size_first_requests(oracle_mod):

@@ -355,6 +355,43 @@ def test_earlier_planning_paths_stay_bit_exact(oracle_mod, monkeypatch, env):
     assert lockstep(oracle_mod, make_trace(4, page_shift=12, layers=8, steps=16), with_bytes=True, bytes_every=3) >= 8
 
 
+@pytest.mark.parametrize("early", [False, True], ids=["plain", "early-execution"])
+def test_pages_larger_than_a_work_unit_of_the_copy(oracle_mod, monkeypatch, early):
+    """Pages of several chunks: 4 MiB pages (two 2 MiB chunks each; 64 chunks of 64 KiB under early execution) on
+    the tiny round-robin schedule, then its 64 KiB pages cut into 16 chunks of 4 KiB by the launch-shape hook.
+    The page is mapped by the workgroup that finishes its last chunk; plans, tables and every byte must equal the
+    oracle's after every switch."""
+    from workloads.harness import load_trace
+    for page_shift, chunk in ((22, None), (16, "12")):
+        if chunk:
+            monkeypatch.setenv("MSCHED_MIGRATE_CHUNK_SHIFT", chunk)
+            monkeypatch.setenv("MSCHED_EARLY_CHUNK_SHIFT", chunk)
+        trace = make_trace(1, seed=3, page_shift=page_shift, n_launches=60)     # 384 pages, 256 frames: 1 GiB pool at 4 MiB
+        if not early:
+            assert lockstep(oracle_mod, trace, with_bytes=True, bytes_every=2) >= 6
+            continue
+        g = GpuSide(trace)
+        o = make_oracle(oracle_mod, trace, with_bytes=True)
+        try:
+            g.ms.set_early_start(True)
+            n = 0
+            for ro, rg in zip(run_schedule(trace, o), run_schedule(trace, g.ms)):
+                assert_same_plan(ro.plan, rg.plan, (trace.name, ro.index))
+                assert g.ms.progress() <= rg.plan.n_fetch
+                pto, foo = o.state()
+                ptg, fog = g.ms.state()
+                assert np.array_equal(pto, ptg) and np.array_equal(foo, fog)
+                assert g.ms.progress() == rg.plan.n_fetch          # the stream has drained: everything has landed
+                if n % 2 == 0:
+                    assert np.array_equal(o.pool_words, g.pool_words())
+                    assert np.array_equal(o.host_words, g.host_words())
+                n += 1
+            assert n >= 6
+        finally:
+            g.close()
+            o.close()
+
+
 def test_id_lists_longer_than_one_prepared_piece(oracle_mod, monkeypatch):
     """A list of 60 000 ids is prepared as three pieces of up to 24 576; the same list object repeated by a later
     command is skipped, a different list over the same pages is merged."""

@@ -62,12 +62,17 @@ def test_create_refuses_bad_configurations_before_touching_the_gpu():
     cfg = b._Config(**{**good, "host_slot": slot.ctypes.data})
     h = C.c_void_p()
     assert lib.msched_create(C.byref(cfg), C.byref(h)) == -2
+    slot = np.arange(8, dtype=np.uint32)
+    slot[5] = 2                                             # two pages on one backing slot
+    cfg = b._Config(**{**good, "host_slot": slot.ctypes.data})
+    assert lib.msched_create(C.byref(cfg), C.byref(h)) == -1 and not h.value
     assert lib.msched_create(None, C.byref(h)) == -1
     for fn in (lib.msched_destroy, lib.msched_last_hip_error):
         fn(None)
     assert lib.msched_plan(None, None, 0, None) == -1
     assert lib.msched_migrate(None, None) == -1
     assert lib.msched_pagetable_query(None, None, 0, None) == -1
+    assert lib.msched_pagetable_query_static(None, None, 0, None) == -1
 
 
 def test_bench_refuses_more_than_one_gpu():
