@@ -222,6 +222,9 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     c->stage_threshold = (uint32_t)env_u32("MSCHED_STAGE_THRESHOLD", 0, 1 << 30, 2048);
     c->dedupe_regions = env_u32("MSCHED_DEDUPE_REGIONS", 0, 1, 1) != 0;
     c->list_prepared = (uint32_t)env_u32("MSCHED_LIST_PREPARED", 0, 1, 1);
+    // One part measured as good as four on the planning-stress schedule (the kernel's time is the instructions a
+    // thread spends on its 24 ids, whichever of them it keeps) at a quarter of the ring memory: parts stay a switch.
+    c->prep_split_max = (uint32_t)env_u32("MSCHED_PREP_SPLIT", 1, kMaxPrepSplit, 1);
     c->list_cache_bytes = (uint64_t)env_u32("MSCHED_LIST_CACHE_MB", 1, 65536, 128) << 20;
     c->list_ahead = (uint32_t)env_u32("MSCHED_LIST_AHEAD", 0, 65536, 128);
     c->plan_spin = (uint32_t)env_u32("MSCHED_PLAN_SPIN", 0, 1, 1);
@@ -519,7 +522,7 @@ int gather_list_sources(msched_ctx *c, PlanGeom &g) {
     }
     uint32_t n_src = 0, n_new = 0;
     c->reserved.clear();
-    const uint64_t hdr_words = (uint64_t)g.n_buckets + 2;
+    const uint64_t split = g.split, hdr_words = (uint64_t)prep_part_buckets(g.n_buckets, g.split) + 2;
     for (const PlanRun &run : c->runs) {
         TaskQueue &t = c->tasks[run.task];
         for (uint32_t j = 0; j < run.count; ++j) {
@@ -530,7 +533,7 @@ int gather_list_sources(msched_ctx *c, PlanGeom &g) {
             if (n_src + pieces > kMaxListSources) { undo_reservations(c); return 1; }
             const bool is_new = t.prep[li] == 0;
             if (is_new) {
-                const uint64_t bytes = (((uint64_t)pieces * hdr_words + n_ids) * 4 + 15) & ~15ull;
+                const uint64_t bytes = (split * ((uint64_t)pieces * hdr_words + n_ids) * 4 + 15) & ~15ull;
                 const uint64_t head = t.prep_head;
                 uint64_t off;
                 if (!ring_alloc(c, t, bytes, off)) { undo_reservations(c); return 1; }
@@ -541,8 +544,8 @@ int gather_list_sources(msched_ctx *c, PlanGeom &g) {
             for (uint32_t p = 0; p < pieces; ++p) {
                 const uint32_t n = std::min<uint32_t>(kPrepBlock, n_ids - p * kPrepBlock);
                 if (is_new) c->list_prep_host[n_new++] = {t.ids[li] + (size_t)p * kPrepBlock, block, n, {0, 0, 0}};
-                c->list_src_host[n_src++] = {block, run.g0 + j, 0};
-                block += hdr_words + n;
+                c->list_src_host[n_src++] = {block, run.g0 + j, (uint32_t)(hdr_words + n)};
+                block += split * (hdr_words + n);
             }
         }
     }
@@ -667,6 +670,7 @@ int plan_body(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entries
         g.list_prepared = false;
         g.n_list_sources = g.n_list_new = 0;
         g.n_buckets = (uint32_t)((c->V + (1u << kBucketShift) - 1) >> kBucketShift);
+        g.split = prep_split(g.n_buckets, c->prep_split_max);
         c->reserved.clear();
         if (c->has_list_rule && g.n_buckets <= kMaxBuckets) {
             const bool many = live_list && total_ids >= c->list_binned_min_ids && total_ids < (1ull << 31);
@@ -779,7 +783,7 @@ void prepare_ahead(msched_ctx *c) {
         if ((e = hipEventSynchronize(c->ahead_ev)) != hipSuccess) return give_up(e);
         c->ahead_pending = false;
     }
-    const uint64_t hdr_words = (uint64_t)n_buckets + 2;
+    const uint64_t split = prep_split(n_buckets, c->prep_split_max), hdr_words = (uint64_t)prep_part_buckets(n_buckets, (uint32_t)split) + 2;
     uint32_t n_new = 0;
     bool full = false;
     struct Fresh { uint32_t task; size_t li; };
@@ -796,7 +800,7 @@ void prepare_ahead(msched_ctx *c) {
             const uint32_t n_ids = t.n_ids[li];
             const uint32_t pieces = (n_ids + kPrepBlock - 1) / kPrepBlock;
             if (n_new + pieces > kMaxListSources) { full = true; break; }
-            const uint64_t bytes = (((uint64_t)pieces * hdr_words + n_ids) * 4 + 15) & ~15ull;
+            const uint64_t bytes = (split * ((uint64_t)pieces * hdr_words + n_ids) * 4 + 15) & ~15ull;
             uint64_t off;
             if (!ring_alloc(c, t, bytes, off)) break;        // no room now: the plan that needs it will see to it
             t.prep[li] = off + 1;
@@ -805,7 +809,7 @@ void prepare_ahead(msched_ctx *c) {
             for (uint32_t p = 0; p < pieces; ++p) {
                 const uint32_t n = std::min<uint32_t>(kPrepBlock, n_ids - p * kPrepBlock);
                 c->list_ahead_host[n_new++] = {t.ids[li] + (size_t)p * kPrepBlock, block, n, {0, 0, 0}};
-                block += hdr_words + n;
+                block += split * (hdr_words + n);
             }
         }
         t.prep_scan = i;
@@ -813,7 +817,7 @@ void prepare_ahead(msched_ctx *c) {
     }
     if (n_new == 0) return;
     const bool timed = c->profiling && hipEventRecord(c->ev[8], c->stream) == hipSuccess;
-    if ((e = launch_list_prepare(c, c->list_ahead_dev, n_new, n_buckets)) != hipSuccess ||
+    if ((e = launch_list_prepare(c, c->list_ahead_dev, n_new, n_buckets, (uint32_t)split)) != hipSuccess ||
         (e = hipEventRecord(c->ahead_ev, c->stream)) != hipSuccess) {
         // nothing was binned: the records must not point at blocks that hold no list
         // (a launch that did go out before a failed record is waited for, so the table is not rewritten under it)

@@ -106,12 +106,26 @@ struct TaskQueue {
 struct PlanRun { uint32_t task, g0, count; size_t first; };
 
 // One source of the id-list merge: a prepared (de-duplicated, grouped by bucket) piece of a command's list.
-//   block[0] = 1 if the piece held an id that is out of range or has no backing slot
-//   block[1 .. n_buckets + 1] = start of every bucket's ids (exclusive prefix, last = total)
-//   block[n_buckets + 2 ..] = the ids
-struct ListSource { const uint32_t *block; uint32_t g, pad; };
+// A piece is prepared in `split` parts (prep_split), each by a workgroup of its own, part q taking the buckets
+// q, q + split, q + 2 split, ... (every workgroup reads the whole piece and keeps the ids of its
+// buckets): part q of the piece starts at block + q * part_words and holds
+//   part[0] = 1 if the part saw an id it cannot plan (out of range - reported by part 0 - or without backing slot)
+//   part[1 .. Bq + 1] = start of each of its buckets' ids (exclusive prefix, last = total), Bq = buckets per part
+//   part[Bq + 2 ..] = the ids (room for every id of the piece)
+struct ListSource { const uint32_t *block; uint32_t g, part_words; };
 // A piece still to be prepared: n ids of a command's list, and where its block goes.
 struct ListPrep { const uint32_t *ids; uint32_t *block; uint32_t n, pad[3]; };
+constexpr uint32_t kMaxPrepSplit = 8;
+// parts a piece is prepared in: at least 16 buckets per part, at most `most` parts (MSCHED_PREP_SPLIT)
+inline uint32_t prep_split(uint32_t n_buckets, uint32_t most) {
+    const uint32_t s = n_buckets / 16;
+    return s < 1 ? 1u : (s > most ? most : s);
+}
+__host__ __device__ inline uint32_t prep_part_buckets(uint32_t n_buckets, uint32_t split) { return (n_buckets + split - 1) / split; }
+// 32-bit words of one part of a piece of n ids
+__host__ __device__ inline uint32_t prep_part_words(uint32_t n_buckets, uint32_t split, uint32_t n) {
+    return prep_part_buckets(n_buckets, split) + 2 + n;
+}
 constexpr uint32_t kMaxListSources = 4096;
 constexpr uint32_t kBucketShift = 13;           // id lists are grouped by bucket of this many (log2) consecutive pages
 constexpr uint32_t kPrepBlock = 24576;          // ids per prepared piece (what one workgroup keeps in LDS)
@@ -129,6 +143,7 @@ struct PlanGeom {
     bool list_prepared;                                  // ... from per-command prepared pieces (cached across plans)
     uint32_t n_list_sources, n_list_new;                 // pieces merged by this plan; of those, prepared by it
     uint32_t n_buckets, bucket_cap;                      // bucket_cap: pairs per sub-segment
+    uint32_t split;                                      // parts a prepared piece consists of
     bool live_list;                                      // some command of the plan brings an id list that is not a repeat
     bool needs_records;                                  // some kernel of the plan reads whole command records (table of record addresses filled)
     bool painted;                                        // range rules arrive as a range list the sweeps paint into LDS
@@ -166,6 +181,7 @@ struct msched_ctx {
     uint32_t *list_pairs = nullptr; size_t list_cap = 0;   // n_buckets x 8 x bucket_cap
     uint64_t list_binned_min_ids = 262144;      // plans with at least this many ids take the bucket path
     uint32_t list_prepared = 1;                 // 0: bin every plan's ids from scratch (MSCHED_LIST_PREPARED)
+    uint32_t prep_split_max = 1;                // parts (workgroups) an id-list piece is prepared in, at most (MSCHED_PREP_SPLIT)
     uint64_t list_cache_bytes = 128ull << 20;   // ring of prepared pieces per task (MSCHED_LIST_CACHE_MB)
     msched::ListSource *list_src_host = nullptr;   // pinned [kMaxListSources]: the pieces this plan merges
     msched::ListSource *list_src_dev = nullptr;    // the same memory, device address
@@ -245,7 +261,7 @@ hipError_t launch_init_tables(msched_ctx *c);
 hipError_t query_scratch_init(uint8_t **out);                                         // address of the static staging array on the current device
 hipError_t query_static(msched_ctx *c, const uint64_t *page_ids, uint32_t n, uint32_t *out);
 hipError_t launch_peek(msched_ctx *c);
-hipError_t launch_list_prepare(msched_ctx *c, const ListPrep *table_dev, uint32_t n, uint32_t n_buckets);      // landed -> progress_host on the poll stream
+hipError_t launch_list_prepare(msched_ctx *c, const ListPrep *table_dev, uint32_t n, uint32_t n_buckets, uint32_t split);      // landed -> progress_host on the poll stream
 
 extern int g_last_hip;                        // hipError_t of the last failed HIP call of any context
 

@@ -21,6 +21,26 @@
 
 #include "msched_internal.h"
 
+// In-kernel timers, a compile-time option (-DMSCHED_KERNEL_TIMERS; paper_2512_24637_amd/build.py build(timers=True)
+// writes libmsched_timers.so beside the library): thread 0 of every workgroup of an instrumented kernel stores the
+// 100 MHz wall clock at the kernel's phase boundaries, slot i of the workgroup's row of 16 in the kernel's table
+// of 4096 rows, in a device buffer of 8 tables the caller hands over with msched_debug_set_ticks (exported by that
+// build only; null switches the timers off).  Compiled out otherwise.
+#ifdef MSCHED_KERNEL_TIMERS
+static __device__ uint64_t *g_ticks = nullptr;
+#define MSCHED_TICK(kernel, i)                                                                              \
+    do {                                                                                                    \
+        if (threadIdx.x == 0 && g_ticks != nullptr && blockIdx.x < 4096)                                    \
+            g_ticks[((size_t)(kernel) * 4096 + blockIdx.x) * 16 + (i)] = wall_clock64();                    \
+    } while (0)
+extern "C" int msched_debug_set_ticks(uint64_t *buf) {
+    return hipMemcpyToSymbol(HIP_SYMBOL(g_ticks), &buf, sizeof buf) == hipSuccess ? MSCHED_OK : MSCHED_E_HIP;
+}
+#else
+#define MSCHED_TICK(kernel, i) do { } while (0)
+#endif
+enum { kTickPrepare = 0, kTickCount = 1, kTickCut = 2, kTickEmit = 3, kTickStage = 4 };
+
 namespace msched {
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
@@ -382,83 +402,164 @@ __global__ __launch_bounds__(kListThreads) void k_list_reduce(ListArgs a) {
 //                   ids itself, into its LDS tile, and nu[] is neither written nor read (count_body)
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kListThreads) void k_list_prepare(const ListPrep *__restrict__ prep, uint32_t n_buckets,
-                                                               uint64_t V, const uint32_t *__restrict__ slot,
+                                                               uint32_t split, uint64_t V, const uint32_t *__restrict__ slot,
                                                                uint32_t *__restrict__ bucket_mark) {
     extern __shared__ uint32_t bin_lds[];
     uint32_t *seen = bin_lds;                               // [1 << kBinSeenBits]
     uint32_t *kept = seen + (1u << kBinSeenBits);           // [kPrepBlock]
-    uint32_t *cnt = kept + kPrepBlock;                      // [n_buckets + 1] counts, then starts, then write cursors
+    uint32_t *cnt = kept + kPrepBlock;                      // [buckets of the part + 1] counts, then starts, then write cursors
     __shared__ uint32_t n_kept, bad;
     __shared__ uint32_t wave_sums[kListThreads / kWave];
-    const ListPrep pr = prep[blockIdx.x];
+    // A piece is prepared by prep_split workgroups, neighbours in dispatch order: each reads all its ids (the
+    // second to fourth reader find them in the L2) and keeps those of its own range of buckets, a part of the work
+    // in LDS and of the output each.  One workgroup per piece left most of the chip idle: a context switch brings a
+    // few dozen new commands.
+    const uint32_t per_part = prep_part_buckets(n_buckets, split);
+    const uint32_t part = blockIdx.x % split;
+    const ListPrep pr = prep[blockIdx.x / split];
     const uint32_t n = min(pr.n, kPrepBlock);
+    // part q takes the buckets q, q + split, q + 2 split, ...: a gather's pages sit in one region of the page table,
+    // and consecutive ranges of buckets would leave all of them to one part
+    const uint32_t nb = part < n_buckets ? (n_buckets - part + split - 1) / split : 0;   // buckets of this part
+    MSCHED_TICK(kTickPrepare, 0);
     for (uint32_t i = threadIdx.x; i < (1u << kBinSeenBits); i += blockDim.x) seen[i] = kNone;
-    for (uint32_t b = threadIdx.x; b <= n_buckets; b += blockDim.x) cnt[b] = 0;
+    for (uint32_t b = threadIdx.x; b <= per_part; b += blockDim.x) cnt[b] = 0;
     if (threadIdx.x == 0) { n_kept = 0; bad = 0; }
     __syncthreads();
+    MSCHED_TICK(kTickPrepare, 1);
     const int lane = lane_id();
-    const uint64_t below = lanes_below();
-    for (uint32_t base = 0; base < n; base += blockDim.x * kBatch) {
-        uint32_t p[kBatch];
-        bool ok[kBatch];
+    // A piece is at most kPrepBlock = 24 x 1024 ids, 24 per thread.  The work on them is done in passes over all of
+    // a thread's ids, so that the round trips of one pass (memory, or an LDS operation whose result is needed)
+    // overlap instead of queueing up id by id: all loads; all look-ups of the second entries; all exchanges with
+    // the first entries; then one reservation per wavefront for everything it keeps.
+    constexpr int kPerThread = kPrepBlock / kListThreads;
+    static_assert(kPerThread * kListThreads == (int)kPrepBlock, "a thread's share of a piece");
+    {
+        uint32_t p[kPerThread];
+        uint32_t ok = 0;                                  // bit j: id j of this thread is (still) to be kept
 #pragma unroll
-        for (int j = 0; j < kBatch; ++j) {
-            const uint32_t i = base + j * blockDim.x + threadIdx.x;
-            ok[j] = i < n;
-            p[j] = ok[j] ? pr.ids[i] : 0u;
+        for (int j = 0; j < kPerThread; ++j) {
+            const uint32_t i = j * blockDim.x + threadIdx.x;
+            p[j] = i < n ? pr.ids[i] : 0u;
+            if (i < n) ok |= 1u << j;
         }
 #pragma unroll
-        for (int j = 0; j < kBatch; ++j) {
-            if (ok[j] && p[j] >= V) { bad = 1; ok[j] = false; }
-            if (ok[j] && slot != nullptr && slot[p[j]] == kNone) { bad = 1; ok[j] = false; }
-            if (ok[j]) {
-                // Repeats are dropped through a table of pairs of entries: an id goes into the first entry of its
-                // pair and moves what was there into the second.  Two popular ids that share a pair then both stay
-                // visible - with one entry each would throw the other out every time, and a gather's most popular
-                // pages would reach the merge once per repeat (twice the ids in the heaviest buckets, measured).
-                // An id is only ever dropped on finding itself, so whatever threads race here, one copy survives.
+        for (int j = 0; j < kPerThread; ++j) {
+            if (!((ok >> j) & 1u)) continue;
+            if (p[j] >= V) { if (part == 0) bad = 1; ok &= ~(1u << j); continue; }
+            if ((p[j] >> kBucketShift) % split != part) ok &= ~(1u << j);   // another part's
+        }
+        if (slot != nullptr) {
+#pragma unroll
+            for (int j = 0; j < kPerThread; ++j)
+                if (((ok >> j) & 1u) && slot[p[j]] == kNone) { bad = 1; ok &= ~(1u << j); }
+        }
+        MSCHED_TICK(kTickPrepare, 2);
+        // Repeats are dropped through a table of pairs of entries: an id goes into the first entry of its
+        // pair and moves what was there into the second.  Two popular ids that share a pair then both stay
+        // visible - with one entry each would throw the other out every time, and a gather's most popular
+        // pages would reach the merge once per repeat (twice the ids in the heaviest buckets, measured).
+        // An id is only ever dropped on finding itself, and only a thread that keeps an id (or found it there)
+        // puts it into the table, so whatever threads race here, one copy survives.
+        // Both entries are first looked at with plain reads (lanes reading one address are served together), and
+        // only an id that finds itself in neither goes on to the exchange: a gather's hottest page is a tenth of
+        // all ids, and that many exchanges on one LDS address, which are served one by one, took longer than
+        // everything else in this kernel together.  Ids go through in groups of kGroup, so that from the second
+        // group on the popular ones are already there to be found.
+        constexpr int kGroup = 4;
+        static_assert(kPerThread % kGroup == 0, "whole groups");
+#pragma unroll
+        for (int j0 = 0; j0 < kPerThread; j0 += kGroup) {
+            uint32_t first[kGroup], second[kGroup];
+#pragma unroll
+            for (int u = 0; u < kGroup; ++u) {
+                const int j = j0 + u;
                 const uint32_t h = (p[j] * 2654435761u) >> (32 - kBinSeenBits);
-                if (seen[h ^ 1u] == p[j]) {
-                    ok[j] = false;
-                } else {
-                    const uint32_t was = atomicExch(&seen[h], p[j]);
-                    if (was == p[j]) ok[j] = false;
-                    else if (was != kNone) seen[h ^ 1u] = was;
-                }
+                first[u] = ((ok >> j) & 1u) ? seen[h] : kNone;
+                second[u] = ((ok >> j) & 1u) ? seen[h ^ 1u] : kNone;
             }
-            const uint64_t keep = __ballot(ok[j]);
-            if (keep) {
-                uint32_t start = 0;
-                const int leader = __ffsll((long long)keep) - 1;
-                if (lane == leader) start = atomicAdd(&n_kept, (uint32_t)__popcll(keep));
-                start = __builtin_amdgcn_readlane(start, leader);
-                if (ok[j]) {
-                    kept[start + __popcll(keep & below)] = p[j];
-                    atomicAdd(&cnt[p[j] >> kBucketShift], 1u);
-                }
+#pragma unroll
+            for (int u = 0; u < kGroup; ++u) {
+                const int j = j0 + u;
+                if (!((ok >> j) & 1u)) continue;
+                if (first[u] == p[j] || second[u] == p[j]) { ok &= ~(1u << j); first[u] = kNone; continue; }
+                first[u] = atomicExch(&seen[(p[j] * 2654435761u) >> (32 - kBinSeenBits)], p[j]);   // what was in the first entry
+            }
+#pragma unroll
+            for (int u = 0; u < kGroup; ++u) {
+                const int j = j0 + u;
+                if (!((ok >> j) & 1u)) continue;
+                if (first[u] == p[j]) ok &= ~(1u << j);
+                else if (first[u] != kNone) seen[((p[j] * 2654435761u) >> (32 - kBinSeenBits)) ^ 1u] = first[u];
             }
         }
+        MSCHED_TICK(kTickPrepare, 3);
+        // room in `kept`: one LDS add per wavefront for all its survivors, then every lane places its own
+        uint32_t mine = __popc(ok), before = mine;         // inclusive prefix over the lanes
+        for (int d = 1; d < kWave; d <<= 1) {
+            const uint32_t up = __shfl_up(before, d, kWave);
+            if (lane >= d) before += up;
+        }
+        uint32_t start = 0;
+        if (lane == kWave - 1 && before) start = atomicAdd(&n_kept, before);
+        start = __shfl(start, kWave - 1, kWave) + before - mine;
+        MSCHED_TICK(kTickPrepare, 4);
+#pragma unroll
+        for (int j = 0; j < kPerThread; ++j) {
+            if ((ok >> j) & 1u) {
+                kept[start++] = p[j];
+                atomicAdd(&cnt[(p[j] >> kBucketShift) / split], 1u);
+            }
+        }
+        MSCHED_TICK(kTickPrepare, 5);
     }
     __syncthreads();
+    MSCHED_TICK(kTickPrepare, 6);
     // Buckets that ever received an id stay marked for the life of the context: the merge looks at no other.
     // (Marks are never taken back, so a bucket whose commands have all retired costs a look, not a wrong result.)
-    for (uint32_t b = threadIdx.x; b < n_buckets; b += blockDim.x)
-        if (cnt[b] && !bucket_mark[b]) bucket_mark[b] = 1;
-    block_exclusive_scan(cnt, n_buckets + 1, wave_sums);   // cnt[b] = start of bucket b, cnt[n_buckets] = total
-    uint32_t *block = pr.block;
+    for (uint32_t b = threadIdx.x; b < nb; b += blockDim.x)
+        if (cnt[b] && !bucket_mark[part + b * split]) bucket_mark[part + b * split] = 1;
+    MSCHED_TICK(kTickPrepare, 7);
+    block_exclusive_scan(cnt, per_part + 1, wave_sums);    // cnt[b] = start of the part's bucket b, cnt[per_part] = total
+    MSCHED_TICK(kTickPrepare, 8);
+    uint32_t *block = pr.block + (size_t)part * prep_part_words(n_buckets, split, pr.n);
     if (threadIdx.x == 0) block[0] = bad;
-    for (uint32_t b = threadIdx.x; b <= n_buckets; b += blockDim.x) block[1 + b] = cnt[b];
+    for (uint32_t b = threadIdx.x; b <= per_part; b += blockDim.x) block[1 + b] = cnt[b];
     __syncthreads();
-    uint32_t *out = block + n_buckets + 2;
+    MSCHED_TICK(kTickPrepare, 9);
+    uint32_t *out = block + per_part + 2;
     const uint32_t m = n_kept;
-    for (uint32_t i = threadIdx.x; i < m; i += blockDim.x) {
-        const uint32_t p = kept[i];
-        out[atomicAdd(&cnt[p >> kBucketShift], 1u)] = p;   // the starts double as write cursors
+    for (uint32_t i0 = threadIdx.x; i0 < m; i0 += blockDim.x * 4) {   // four positions asked for before the first is used
+        uint32_t p[4], at[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) p[j] = i0 + j * blockDim.x < m ? kept[i0 + j * blockDim.x] : kNone;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            at[j] = p[j] != kNone ? atomicAdd(&cnt[(p[j] >> kBucketShift) / split], 1u) : 0u;   // the starts double as write cursors
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (p[j] != kNone) out[at[j]] = p[j];
     }
+    MSCHED_TICK(kTickPrepare, 10);
+}
+
+// The ids of bucket b in one prepared piece: where they start and how many they are.
+__device__ __forceinline__ const uint32_t *piece_segment(const ListSource &S, uint32_t b, uint32_t split, uint32_t per_part, uint32_t &len) {
+    const uint32_t q = b % split, j = b / split;
+    const uint32_t *part = S.block + (size_t)q * S.part_words;
+    const uint32_t lo = part[1 + j], hi = part[2 + j];
+    len = hi - lo;
+    return part + per_part + 2 + lo;
+}
+// Did any part of the piece see an id that cannot be planned?
+__device__ __forceinline__ bool piece_bad(const ListSource &S, uint32_t split) {
+    bool bad = false;
+    for (uint32_t q = 0; q < split; ++q) bad |= S.block[(size_t)q * S.part_words] != 0;
+    return bad;
 }
 
 struct MergeArgs {
-    const ListSource *src; uint32_t n_src, n_buckets;
+    const ListSource *src; uint32_t n_src, n_buckets, split;
     uint32_t *nu; uint32_t *flags; uint64_t V; uint32_t epoch_base;
     const uint32_t *bucket_mark;        // [n_buckets] has any prepared piece of this context ever put an id here?
 };
@@ -538,14 +639,15 @@ __global__ __launch_bounds__(kListThreads) void k_list_merge(MergeArgs a) {
     uint32_t *len = reinterpret_cast<uint32_t *>(first + a.n_src);             // [n_src] ids of this bucket in piece s
     uint32_t *enc = len + a.n_src;                                              // [n_src] next-use code of the piece's command
     uint32_t longest = 0;
+    const uint32_t split = a.split, per_part = prep_part_buckets(a.n_buckets, split);
     for (uint32_t s = threadIdx.x; s < a.n_src; s += blockDim.x) {
         const ListSource S = a.src[s];
-        const uint32_t lo = S.block[1 + b], hi = S.block[2 + b];
-        first[s] = S.block + a.n_buckets + 2 + lo;
-        len[s] = hi - lo;
+        uint32_t n;
+        first[s] = piece_segment(S, b, split, per_part, n);
+        len[s] = n;
         enc[s] = kNuMask - S.g;
-        longest = max(longest, hi - lo);
-        if (b == 0 && S.block[0]) atomicOr(a.flags, kStatRange);   // the piece held an id that cannot be planned
+        longest = max(longest, n);
+        if (b == 0 && piece_bad(S, split)) atomicOr(a.flags, kStatRange);   // the piece held an id that cannot be planned
     }
     for (uint32_t i = threadIdx.x; i < kBucketPages; i += blockDim.x) tab[i] = 0;
     const int any_ids = __syncthreads_or(longest != 0);
@@ -776,7 +878,7 @@ __device__ __forceinline__ void rank_tile(const SweepGeom &sg, uint32_t *hist, u
 // alike) and nu[] is neither written nor read: the separate merge launch, 4 bytes written and 4 read per page of a
 // bucket with ids, and one kernel boundary fall away.
 struct TileLists {
-    const ListSource *src; uint32_t n_src, n_buckets;
+    const ListSource *src; uint32_t n_src, n_buckets, split;
     const uint32_t *bucket_mark;        // [n_buckets] does any prepared piece hold an id of this bucket?
     const uint32_t *order;              // [n_chunks] the chunk of each workgroup (chunk_order_block)
 };
@@ -877,7 +979,7 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
                 const uint32_t b = (uint32_t)(tile_begin >> kBucketShift);      // the tile is this bucket
                 if (b == 0) {                                 // its workgroup also reports ids that cannot be planned
                     for (uint32_t s = threadIdx.x; s < tl->n_src; s += blockDim.x)
-                        if (tl->src[s].block[0]) atomicOr(sg.flags, kStatRange);
+                        if (piece_bad(tl->src[s], tl->split)) atomicOr(sg.flags, kStatRange);
                 }
                 // (Measured and dropped: asking for the page-table entries and the segment descriptions before
                 // painting, so that their round trips overlap it - 5 us slower per plan.)
@@ -893,11 +995,11 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
                         uint32_t longest = 0;
                         for (uint32_t s = threadIdx.x; s < n_here; s += blockDim.x) {
                             const ListSource S = tl->src[s_base + s];
-                            const uint32_t lo = S.block[1 + b], hi = S.block[2 + b];
-                            first[s] = S.block + tl->n_buckets + 2 + lo;
-                            len[s] = hi - lo;
+                            uint32_t n;
+                            first[s] = piece_segment(S, b, tl->split, prep_part_buckets(tl->n_buckets, tl->split), n);
+                            len[s] = n;
                             cmd[s] = S.g;
-                            longest = max(longest, hi - lo);
+                            longest = max(longest, n);
                         }
                         const int any_long = __syncthreads_or(longest > kMergeHead);     // also the barrier behind the descriptions
                         merge_segments<kFusedPieces, kFusedRows>(first, len, cmd, n_here, any_long != 0,
@@ -1451,11 +1553,11 @@ hipError_t allow_large_lds() {
     return hipSuccess;
 }
 
-hipError_t launch_list_prepare(msched_ctx *c, const ListPrep *table_dev, uint32_t n, uint32_t n_buckets) {
+hipError_t launch_list_prepare(msched_ctx *c, const ListPrep *table_dev, uint32_t n, uint32_t n_buckets, uint32_t split) {
     if (n == 0) return hipSuccess;
     (void)hipGetLastError();
-    const size_t prep_lds = 4 * ((size_t)(1u << kBinSeenBits) + kPrepBlock + n_buckets + 1);
-    k_list_prepare<<<n, kListThreads, prep_lds, c->stream>>>(table_dev, n_buckets, c->V, c->slot, c->bucket_mark);
+    const size_t prep_lds = 4 * ((size_t)(1u << kBinSeenBits) + kPrepBlock + prep_part_buckets(n_buckets, split) + 1);
+    k_list_prepare<<<n * split, kListThreads, prep_lds, c->stream>>>(table_dev, n_buckets, split, c->V, c->slot, c->bucket_mark);
     return hipGetLastError();
 }
 
@@ -1495,9 +1597,9 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         // so once the first few commands have written the popular pages, the check in front of the
         // atomic turns every later touch of them into a plain (cached) load.
         if (g.list_prepared) {
-            if (g.n_list_new) CK(launch_list_prepare(c, c->list_prep_dev, g.n_list_new, g.n_buckets));
+            if (g.n_list_new) CK(launch_list_prepare(c, c->list_prep_dev, g.n_list_new, g.n_buckets, g.split));
             MergeArgs ma;
-            ma.src = c->list_src_stage; ma.n_src = g.n_list_sources; ma.n_buckets = g.n_buckets;
+            ma.src = c->list_src_stage; ma.n_src = g.n_list_sources; ma.n_buckets = g.n_buckets; ma.split = g.split;
             ma.nu = c->nu; ma.flags = c->flags; ma.V = c->V; ma.epoch_base = a.epoch_base; ma.bucket_mark = c->bucket_mark;
             if (g.n_list_sources && !fuse_lists)
                 k_list_merge<<<g.n_buckets, kListThreads, (size_t)g.n_list_sources * 16, st>>>(ma);
@@ -1555,7 +1657,7 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         SweepGeom sc = sg;
         sc.steps = g.steps * g.waves / (kFusedThreads / kWave);       // the same tile, whatever the workgroup's width
         TileLists tl;
-        tl.src = c->list_src_stage; tl.n_src = g.n_list_sources; tl.n_buckets = g.n_buckets; tl.bucket_mark = c->bucket_mark;
+        tl.src = c->list_src_stage; tl.n_src = g.n_list_sources; tl.n_buckets = g.n_buckets; tl.split = g.split; tl.bucket_mark = c->bucket_mark;
         tl.order = c->bucket_mark + kMaxBuckets;
         const size_t lds = ((size_t)count_paint_offset(g.n_keys) + kBucketPages) * 4 + (size_t)kStagePieces * 16;
         k_count_lists<<<g.n_chunks, kFusedThreads, lds, st>>>(c->page_table, sc, tl, c->matrix, few_rows ? nullptr : c->partial);

@@ -392,6 +392,20 @@ def test_pages_larger_than_a_work_unit_of_the_copy(oracle_mod, monkeypatch, earl
             o.close()
 
 
+@pytest.mark.parametrize("env", [{}, {"MSCHED_FUSE_LISTS": "0"}, {"MSCHED_LIST_AHEAD": "0"}], ids=["merged-in-the-sweep", "own-merge-kernel", "no-look-ahead"])
+def test_id_lists_prepared_in_parts_by_bucket_range(oracle_mod, monkeypatch, env):
+    """With MSCHED_PREP_SPLIT every piece of an id list of a table of 32 buckets or more is prepared by several
+    workgroups, part q taking the buckets q, q + parts, ...: 80 buckets in 4 parts here (config 5 at 1/16 of its
+    pages, 64-byte pages), 40 buckets in 2 parts at 1/32."""
+    monkeypatch.setenv("MSCHED_LIST_BINNED_MIN_IDS", "0")
+    monkeypatch.setenv("MSCHED_PREP_SPLIT", "4")
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    for scale in (16, 32):
+        trace = make_trace(5, scale=scale, page_shift=6, n_launches=100)
+        assert lockstep(oracle_mod, trace, with_bytes=True, bytes_every=5) >= 16
+
+
 def test_id_lists_longer_than_one_prepared_piece(oracle_mod, monkeypatch):
     """A list of 60 000 ids is prepared as three pieces of up to 24 576; the same list object repeated by a later
     command is skipped, a different list over the same pages is merged."""
