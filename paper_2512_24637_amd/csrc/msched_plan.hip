@@ -577,31 +577,44 @@ constexpr uint32_t kMergeHead = 4 * kWave;          // ids of a segment its wave
 // The segments of one bucket, staged in LDS: for piece s its first id, its length and the value `code[s]` that goes
 // into the bucket's table.  `put(id, code)` is the LDS atomic of the caller (the largest code or the smallest
 // command wins, depending on what the table holds).
-template <int kPieces, int kRowsPerPass, class Put>
+// kWidth: lanes that share a segment.  With 64 a wave-wide load takes a row of 64 ids from one segment; with 32 (16)
+// it takes a row of 32 (16) ids from each of two (four) segments, which suits the short segments of plans with
+// hundreds of pieces: a tile's merge is a chain of load round trips, and the fewer lanes a load leaves idle, the
+// fewer round trips it takes.
+template <int kPieces, int kRowsPerPass, int kWidth, class Put>
 __device__ __forceinline__ void merge_segments(const uint32_t *const *first, const uint32_t *len, const uint32_t *code,
                                                uint32_t n_src, bool any_long, Put put) {
+    static_assert(kWidth == 64 || kWidth == 32 || kWidth == 16, "lanes per segment");
+    constexpr int kPerLoad = kWave / kWidth;                 // segments a wave-wide load reads from
+    constexpr int kPerPass = kPieces * kPerLoad;             // segments a wavefront takes per pass
     const uint32_t lane = (uint32_t)lane_id(), wave = threadIdx.x / kWave, waves = blockDim.x / kWave;
-    for (uint32_t s0 = wave * kPieces; s0 < n_src; s0 += waves * kPieces) {
+    const uint32_t sub = lane / kWidth, off = lane % kWidth;
+    for (uint32_t s0 = wave * kPerPass; s0 < n_src; s0 += waves * kPerPass) {
         const uint32_t *ptr[kPieces];
         uint32_t n[kPieces], e[kPieces];
 #pragma unroll
-        for (int j = 0; j < kPieces; ++j) {             // the same for every lane
-            const uint32_t s = min(s0 + j, n_src - 1);
-            n[j] = (s0 + j < n_src) ? min(len[s], kMergeHead) : 0u;
+        for (int j = 0; j < kPieces; ++j) {             // the same for the kWidth lanes of a group
+            const uint32_t want = s0 + j * kPerLoad + sub;
+            const uint32_t s = min(want, n_src - 1);
+            n[j] = (want < n_src) ? min(len[s], kMergeHead) : 0u;
             e[j] = code[s];
             ptr[j] = first[s];
         }
         uint32_t n_max = 0;
 #pragma unroll
         for (int j = 0; j < kPieces; ++j) n_max = max(n_max, n[j]);
-        // kRowsPerPass rows of 64 ids from each of the segments per pass: every load of a pass is issued before its first atomic
-        for (uint32_t r0 = 0; r0 < n_max; r0 += kRowsPerPass * kWave) {
+        if (kPerLoad > 1) {                                  // the longest segment of any group decides the passes
+#pragma unroll
+            for (int d = kWidth; d < kWave; d <<= 1) n_max = max(n_max, (uint32_t)__shfl_xor((int)n_max, d, kWave));
+        }
+        // kRowsPerPass rows of kWidth ids from each of the segments per pass: every load of a pass is issued before its first atomic
+        for (uint32_t r0 = 0; r0 < n_max; r0 += kRowsPerPass * kWidth) {
             uint32_t id[kRowsPerPass][kPieces];
 #pragma unroll
             for (int q = 0; q < kRowsPerPass; ++q)
 #pragma unroll
                 for (int j = 0; j < kPieces; ++j)
-                    id[q][j] = r0 + q * kWave + lane < n[j] ? ptr[j][r0 + q * kWave + lane] : kNone;
+                    id[q][j] = r0 + q * kWidth + off < n[j] ? ptr[j][r0 + q * kWidth + off] : kNone;
 #pragma unroll
             for (int q = 0; q < kRowsPerPass; ++q)
 #pragma unroll
@@ -653,7 +666,7 @@ __global__ __launch_bounds__(kListThreads) void k_list_merge(MergeArgs a) {
     const int any_ids = __syncthreads_or(longest != 0);
     const int any_long = __syncthreads_or(longest > kMergeHead);
     if (!any_ids) return;
-    merge_segments<kMergePieces, 2>(first, len, enc, a.n_src, any_long != 0,
+    merge_segments<kMergePieces, 2, kWave>(first, len, enc, a.n_src, any_long != 0,
                    [&](uint32_t id, uint32_t code) { atomicMax(&tab[id & (kBucketPages - 1)], code); });   // never 0
     __syncthreads();
     const uint64_t p0 = (uint64_t)b << kBucketShift;
@@ -883,6 +896,11 @@ struct TileLists {
     const uint32_t *order;              // [n_chunks] the chunk of each workgroup (chunk_order_block)
 };
 constexpr int kFusedPieces = 6;         // segments in flight per wavefront of the sweep, one row of 64 ids each per pass: what
+#ifndef MSCHED_FUSED_WIDTH
+#define MSCHED_FUSED_WIDTH 32
+#endif
+constexpr int kFusedWidth = MSCHED_FUSED_WIDTH;   // lanes per segment in the sweep's merge (on the planning-stress schedule the merge
+                                                  // of a tile takes 10.8 us with 64, 9.6 with 32, 9.3 with 16)
 constexpr int kFusedRows = 1;           // 64 registers hold (a segment of one bucket and piece is a few dozen ids; 4 x 2 rows: +0.7 us)
 constexpr uint32_t kStagePieces = 512;   // segments of a bucket described in LDS at a time (16 bytes each)
 
@@ -893,10 +911,12 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
     const uint32_t n_keys = 2 * (sg.G + 1);
     const uint32_t waves = blockDim.x / kWave, wave = threadIdx.x / kWave;
     __shared__ PaintLds s_paint;
+    MSCHED_TICK(kTickCount, 0);
     for (uint32_t i = threadIdx.x; i < n_keys; i += blockDim.x) lds[i] = 0;
     if (threadIdx.x == 0) { s_paint.n_queued = 0; s_paint.floor = sg.G; }     // queue_ranges expects it empty
     if (threadIdx.x == 0 && sg.emit_hint != nullptr) sg.emit_hint[chunk] = 0;   // raised below, behind barriers
     __syncthreads();
+    MSCHED_TICK(kTickCount, 1);
     const uint64_t p_begin = (uint64_t)chunk * sg.chunk_pages;
     const uint64_t p_end = min(sg.V, p_begin + sg.chunk_pages);
     const uint64_t tile_pages = (uint64_t)waves * sg.steps * kWave;
@@ -984,9 +1004,13 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
                 // (Measured and dropped: asking for the page-table entries and the segment descriptions before
                 // painting, so that their round trips overlap it - 5 us slower per plan.)
                 if (!tl->bucket_mark[b]) {
-                    sweep_tile(paint_ranges(), false);
+                    const int how = paint_ranges();
+                    MSCHED_TICK(kTickCount, 2);
+                    sweep_tile(how, false);
+                    MSCHED_TICK(kTickCount, 5);
                 } else {
                     paint_tile(sg, tile_begin, tile_end, paint, s_paint);
+                    MSCHED_TICK(kTickCount, 2);
                     const uint32_t **first = reinterpret_cast<const uint32_t **>(paint + tile_pages);   // [kStagePieces]
                     uint32_t *len = reinterpret_cast<uint32_t *>(first + kStagePieces);
                     uint32_t *cmd = len + kStagePieces;
@@ -1002,11 +1026,14 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
                             longest = max(longest, n);
                         }
                         const int any_long = __syncthreads_or(longest > kMergeHead);     // also the barrier behind the descriptions
-                        merge_segments<kFusedPieces, kFusedRows>(first, len, cmd, n_here, any_long != 0,
+                        MSCHED_TICK(kTickCount, 3);
+                        merge_segments<kFusedPieces, kFusedRows, kFusedWidth>(first, len, cmd, n_here, any_long != 0,
                                        [&](uint32_t id, uint32_t g) { atomicMin(&paint[id & (kBucketPages - 1)], g); });
                         __syncthreads();                   // the next pieces overwrite the descriptions; the tile is read below
                     }
+                    MSCHED_TICK(kTickCount, 4);
                     sweep_tile(kPaintLds, false);
+                    MSCHED_TICK(kTickCount, 5);
                 }
             }
         } else {
@@ -1045,6 +1072,7 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
         const bool two = __ballot(hint == 2u) != 0, one = __ballot(hint == 1u) != 0;
         if (lane_id() == 0 && (two || one)) atomicMax(&sg.emit_hint[chunk], two ? 2u : 1u);
     }
+    MSCHED_TICK(kTickCount, 6);
 }
 
 // Where a chunk's counts are added up for the column prefixes: the sums of its row group, and behind the
@@ -1078,7 +1106,12 @@ __global__ __launch_bounds__(kWave * kMaxWaves) void k_count(const uint32_t *__r
 // time, which fits a fourth workgroup, 1.8 and 2.5 us slower.)
 static_assert(kMaxWaves * kMaxSteps * kWave == (int)kBucketPages, "a full-size tile is one bucket");
 constexpr int kFusedThreads = kWave * kMaxWaves;
-__global__ __launch_bounds__(kFusedThreads, 8) void k_count_lists(const uint32_t *__restrict__ page_table, SweepGeom sg,
+// Registers: three of these workgroups (24 wavefronts, 6 per SIMD) share a compute unit, its LDS allows no more, so
+// the kernel may use the 85 registers 6 wavefronts per SIMD leave each (at the 64 of 8 per SIMD it spilled).
+#ifndef MSCHED_FUSED_MIN_WAVES
+#define MSCHED_FUSED_MIN_WAVES 6
+#endif
+__global__ __launch_bounds__(kFusedThreads, MSCHED_FUSED_MIN_WAVES) void k_count_lists(const uint32_t *__restrict__ page_table, SweepGeom sg,
                                                               TileLists tl, uint32_t *__restrict__ matrix,
                                                               uint32_t *__restrict__ partial) {
     extern __shared__ uint32_t lds[];
@@ -1193,6 +1226,7 @@ __device__ void cut_body(const CutArgs &a, uint32_t *lds) {
     __shared__ uint32_t s_cut, s_res, s_fetch;
     const uint32_t tid = threadIdx.x, wave = tid / kWave;
     if (tid == 0) { s_cut = 0; s_res = 0; s_fetch = 0; }
+    MSCHED_TICK(kTickCut, 0);
     for (uint32_t key = tid; key < n_keys; key += nthreads) {
         uint32_t v[kRowGroups];
 #pragma unroll
@@ -1206,6 +1240,7 @@ __device__ void cut_body(const CutArgs &a, uint32_t *lds) {
         tot[key] = run;
     }
     __syncthreads();
+    MSCHED_TICK(kTickCut, 1);
     // The three scans below are short (K = G + 1 values): each is done by one wavefront without a barrier, the
     // cut by the first, resident pages counted by the others meanwhile; then fetch and victim offsets side by side.
     if (wave == 0) {
@@ -1224,6 +1259,7 @@ __device__ void cut_body(const CutArgs &a, uint32_t *lds) {
         if (res && (tid % kWave) == 0) atomicAdd(&s_res, res);          // one add per wavefront, not per thread
     }
     __syncthreads();
+    MSCHED_TICK(kTickCut, 2);
     const uint32_t g_cut = s_cut, n_res = s_res;
     const uint32_t last_wave = nthreads / kWave - 1;
     if (wave == 0) {
@@ -1244,6 +1280,7 @@ __device__ void cut_body(const CutArgs &a, uint32_t *lds) {
         if (a.landed && (tid % kWave) == 0) { a.landed[0] = 0; a.landed[1] = 0; }   // entries landed, work units handed out
     }
     __syncthreads();
+    MSCHED_TICK(kTickCut, 3);
     if (tid == 0) {
         uint32_t n_fetch = s_fetch;
         uint32_t status = *a.flags;
@@ -1264,6 +1301,7 @@ __device__ void cut_body(const CutArgs &a, uint32_t *lds) {
         __threadfence_system();
         __hip_atomic_store(&a.hdr_host->seq, a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
     }
+    MSCHED_TICK(kTickCut, 4);
 }
 
 __global__ __launch_bounds__(1024) void k_cut(CutArgs a) {
@@ -1364,6 +1402,7 @@ __device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg
         const uint4 *src = reinterpret_cast<const uint4 *>(sg.key16 + first);
         return Raw{src[0], src[1]};
     };
+    MSCHED_TICK(kTickEmit, 0);
     const uint32_t n_fetch = a.hdr->n_fetch, n_evict = a.hdr->n_evict;
     const uint32_t n_free_used = a.hdr->n_free_used, first_free = a.hdr->first_free;
     if (n_fetch == 0) return;                             // same for every thread of the block
@@ -1403,6 +1442,7 @@ __device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg
         base[k] = at;
         if (cnt_row != nullptr && at < (k < K ? n_fetch : n_evict) && cnt_row[k] != 0) live = true;
     }
+    MSCHED_TICK(kTickEmit, 1);
     if (!__syncthreads_or(live)) return;
     Raw raw = request_slice(0);
     for (uint32_t round = 0; round < sg.rounds; ++round) {
@@ -1424,8 +1464,10 @@ __device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg
 #pragma unroll
         for (int s = 0; s < kMaxSteps; ++s)
             if (key[s] != kNone && base[key[s]] >= (key[s] < K ? n_fetch : n_evict)) key[s] = kNone;
+        MSCHED_TICK(kTickEmit, 2);
         rank_tile(sg, hist, key);
         __syncthreads();
+        MSCHED_TICK(kTickEmit, 3);
         // per key: each wavefront's start position in this tile; carry the running position on
         for (uint32_t k = threadIdx.x; k < n_keys; k += blockDim.x) {
             uint32_t run = base[k];
@@ -1437,6 +1479,7 @@ __device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg
             base[k] = run;
         }
         __syncthreads();
+        MSCHED_TICK(kTickEmit, 4);
 #pragma unroll
         for (int s = 0; s < kMaxSteps; ++s) {
             if ((uint32_t)s < sg.steps && key[s] != kNone) {
@@ -1461,6 +1504,7 @@ __device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg
             }
         }
         __syncthreads();
+        MSCHED_TICK(kTickEmit, 5);
     }
 }
 
