@@ -19,6 +19,22 @@
 
 #include "msched_internal.h"
 
+// In-kernel timers of the timers build (see msched_plan.hip): thread 0 stores the 100 MHz wall clock at the phase
+// boundaries of k_analyze, slot i of the wavefront's row of 16, for the first 65536 kernels of a batch.
+#ifdef MSCHED_KERNEL_TIMERS
+static __device__ uint64_t *g_ana_ticks = nullptr;
+#define ANA_TICK(i)                                                                                          \
+    do {                                                                                                    \
+        if (threadIdx.x == 0 && g_ana_ticks != nullptr && blockIdx.x < 65536)                               \
+            g_ana_ticks[(size_t)blockIdx.x * 16 + (i)] = wall_clock64();                                    \
+    } while (0)
+extern "C" int msched_debug_set_analyzer_ticks(uint64_t *buf) {
+    return hipMemcpyToSymbol(HIP_SYMBOL(g_ana_ticks), &buf, sizeof buf) == hipSuccess ? MSCHED_OK : MSCHED_E_HIP;
+}
+#else
+#define ANA_TICK(i) do { } while (0)
+#endif
+
 namespace msched {
 
 constexpr int kAnaMaxInv = 512;
@@ -261,6 +277,7 @@ __global__ __launch_bounds__(kWave) void k_analyze(AnaArgs a) {
     const ulonglong2 *g_args = reinterpret_cast<const ulonglong2 *>(a.args + (size_t)k * n_inv * MSCHED_MAX_ARGS);
     const ulonglong2 *g_iv = reinterpret_cast<const ulonglong2 *>(a.iv + (size_t)k * n_inv * max_iv * 2);   // (start, length)
     const uint32_t *g_niv = a.n_iv + (size_t)k * n_inv;
+    ANA_TICK(0);
     // 0. arguments and interval counts into LDS
     uint32_t total = 0;
     {
@@ -286,6 +303,7 @@ __global__ __launch_bounds__(kWave) void k_analyze(AnaArgs a) {
     const int n_args = min(max(a.n_args[k], 0), MSCHED_MAX_ARGS);
     const uint32_t mask = a.int64_mask[k] & ((1u << n_args) - 1);
     __syncthreads();
+    ANA_TICK(1);
     // 1. base pointers: 64-bit arguments whose value starts an interval in every invocation.  Every interval
     //    start is read once, eight lanes to a row, and compared with the invocation's 64-bit arguments.
     auto match = [&](uint32_t i, uint32_t m, uint64_t start) {
@@ -313,6 +331,7 @@ __global__ __launch_bounds__(kWave) void k_analyze(AnaArgs a) {
             }
         }
     __syncthreads();
+    ANA_TICK(2);
     uint32_t nc = 0, base_mask = 0;
     for (int arg = 0; arg < n_args; ++arg) {
         bool missing = !((mask >> arg) & 1);
@@ -348,12 +367,14 @@ __global__ __launch_bounds__(kWave) void k_analyze(AnaArgs a) {
         window(__builtin_ctz(live_mask));
         for (uint32_t r = lane; r < n_subsets; r += kWave) s_subsets[r] = g_subset_table[nc][r];
     }
+    ANA_TICK(3);
     Analyzer an;
     an.n_inv = n_inv; an.lane = lane; an.s_args = s_args; an.count = count;
     an.subsets = s_subsets; an.cand = s_cand; an.n_subsets = n_subsets; an.n_singles = nc;
     uint32_t n_rules = 0, covered = 0, accepted_mask = 0;
     for (uint32_t rest = live_mask; rest; rest &= rest - 1) {
         const uint32_t arg = __builtin_ctz(rest);
+        if (n_rules == 0) ANA_TICK(4);
         // 2. the region that starts at this base, per invocation: a run of equal intervals at a regular stride
         bool any_multi = false;
         for (uint32_t i = lane; i < n_inv; i += kWave) {
@@ -380,6 +401,7 @@ __global__ __launch_bounds__(kWave) void k_analyze(AnaArgs a) {
             any_multi |= cnt > 1;
         }
         __syncthreads();
+        if (n_rules == 0) ANA_TICK(5);
         if (rest & (rest - 1)) window(__builtin_ctz(rest & (rest - 1)));
         const bool strided = __ballot(any_multi) != 0;
         // 3. templates in order: invariant size, size proportional to arguments, strided
@@ -394,6 +416,7 @@ __global__ __launch_bounds__(kWave) void k_analyze(AnaArgs a) {
             ok = an.search(S, c);
             if (q == 0) { S_size = S; c_size = c; } else if (q == 1) { S_stride = S; c_stride = c; } else { S_count = S; c_count = c; }
         }
+        if (n_rules == 0) ANA_TICK(6);
         if (ok && n_rules < MSCHED_MAX_RULES) {
             uint64_t w[3];
             rule_words(strided ? MSCHED_RULE_STRIDED : (S_size.n == 0 ? MSCHED_RULE_FIXED : MSCHED_RULE_LINEAR), arg,
@@ -414,12 +437,14 @@ __global__ __launch_bounds__(kWave) void k_analyze(AnaArgs a) {
         }
         __syncthreads();                                          // chunk / stride / count are reused by the next base
     }
+    ANA_TICK(7);
     int unexplained = (int)total - (int)covered;
     for (int off = kWave / 2; off > 0; off >>= 1) unexplained += __shfl_down(unexplained, off);
     if (lane == 0) {
         a.n_rules[k] = n_rules;
         a.unexplained[k] = (uint32_t)unexplained;
     }
+    ANA_TICK(8);
 }
 
 }  // namespace msched
