@@ -475,18 +475,17 @@ def bench_ablation(torch, steps=16, cpu=True):
 
 def bench_early_start(torch, switches=8, warm=2):
     """LLM-decode schedule (config 4) with 512 KiB pages, i.e. the same page structure at a quarter of the bytes:
-    every launch of a decode step needs one more layer's weights, so readiness grows along the fetch list."""
+    every launch of a decode step needs one more layer's weights, so readiness grows along the fetch list.  The
+    consumer is the device-side gate (msched_gate_enqueue): one per covered launch on a second stream, each
+    reporting on the device's clock when it saw its pages resident."""
     from workloads import make_trace
-    from workloads.device import DeviceBuffers
-    from paper_2512_24637_amd import MSched
     trace = make_trace(4, page_shift=19, steps=4 * (switches + 2))
     out = {"workload": "c4-llm-decode page structure with 512 KiB pages (pool 4 GiB, 6656 pages in, 6656 out per switch)"}
+    side = torch.cuda.Stream()
     for early in (False, True):
         buf, ms = make_context(torch, trace, fill_contents=False)
         ms.set_early_start(early)
-        main = torch.cuda.current_stream()
-        rates, first_ms, mean_frac, total_ms, ramp_frac, ramp_len = [], [], [], [], [], []
-        cursor = [0] * trace.n_tasks
+        rates, first_ms, mean_frac, total_ms, ramp_frac, ramp_len, gave_up = [], [], [], [], [], [], 0
         for sw in range(switches):
             t = sw % trace.n_tasks
             p = ms.plan([((t + k) % trace.n_tasks, trace.timeslice) for k in range(trace.n_tasks)])
@@ -494,27 +493,20 @@ def bench_early_start(torch, switches=8, warm=2):
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            t0 = time.perf_counter()
             ms.migrate_only(p)
             e1.record()
-            seen = []
             if early:
-                while True:
-                    v = ms.progress()
-                    now = time.perf_counter() - t0
-                    seen.append((now, v))
-                    if main.query():
-                        break
+                for g in range(p.covered_launches):
+                    ms.gate_enqueue(p, g, side.cuda_stream)
             torch.cuda.synchronize()
             dur = e0.elapsed_time(e1)
             if sw >= warm and p.n_fetch:
                 rates.append((p.n_fetch + p.n_evict) * trace.page_bytes / dur / 1e6)
                 total_ms.append(dur)
                 if early:
-                    ts = np.array([a for a, _ in seen]) * 1e3
-                    vs = np.array([v for _, v in seen])
-                    ready = ts[np.minimum(np.searchsorted(vs, need, side="left"), len(ts) - 1)]   # first poll that saw need[g]
-                    ready = np.minimum(ready, dur)
+                    res = [ms.gate_result(g) for g in range(p.covered_launches)]
+                    gave_up += sum(1 for st, _ in res if st != 1)
+                    ready = np.minimum(np.array([r for _, r in res]), dur)
                     first_ms.append(float(ready[0]))
                     mean_frac.append(float(np.mean(ready) / dur))
                     ramp = int(np.searchsorted(need, p.n_fetch, side="left")) + 1     # launches before everything is needed
@@ -529,10 +521,12 @@ def bench_early_start(torch, switches=8, warm=2):
             out["mean_launch_ready_fraction"] = float(np.mean(mean_frac))
             out["first_pass_launches"] = float(np.mean(ramp_len))
             out["first_pass_mean_ready_fraction"] = float(np.mean(ramp_frac))
-            out["note"] = ("ready = first progress poll (about 2 ms apart) that saw need[g] entries landed; fraction = mean over "
-                           "the covered launches of ready time / whole migration; first pass = the launches up to the first "
-                           "that needs the whole fetch list (one decode step; later steps reuse its pages); without early "
-                           "execution every launch waits for the whole migration (fraction 1)")
+            out["gates_that_gave_up"] = gave_up
+            out["note"] = ("ready = device clock at which the launch's gate kernel (a second stream, no host in between) saw "
+                           "need[g] fetch entries landed, after the start of the migration kernel; fraction = mean over the covered "
+                           "launches of ready time / whole migration; first pass = the launches up to the first that needs the "
+                           "whole fetch list (one decode step; later steps reuse its pages); without early execution every "
+                           "launch waits for the whole migration (fraction 1)")
         ms.close()
         buf.release()
     return out

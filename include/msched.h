@@ -232,6 +232,25 @@ int msched_plan_ready_need(msched_ctx *ctx, const msched_plan_t *plan, uint32_t 
 int msched_progress(msched_ctx *ctx, uint32_t *landed);
 
 /*
+ * The same hand-over without the host in between (Sec. 6.3 signals from the copy to the compute side on the
+ * device): msched_gate_enqueue puts a one-wavefront kernel on `stream` (the stream the task's commands are
+ * launched on; NOT the context's stream) that returns once landed >= need[g] of the latest plan, so that whatever
+ * the caller launches on that stream afterwards - command g - starts when its pages are resident, while the
+ * migration is still running on the context's stream.  g < covered_launches; the plan must be the latest one, made
+ * with early start enabled, and msched_migrate must already have been called for it (else E_STALE_PLAN: a gate
+ * queued ahead of its migration could sit in front of it in a hardware queue the two streams share, and would
+ * then hold it up until the gate gives up); call it before the next msched_plan.  The wait is bounded: after timeout_us microseconds (0 = 2 seconds) on the device's wall
+ * clock the kernel gives up and returns all the same, and the caller finds that out from msched_gate_result and
+ * waits for the migration in the ordinary way (an event on the context's stream) before it launches the command.
+ * msched_gate_result reports gate g of the latest plan, as its kernel left it in host memory (synchronise `stream`
+ * first): *status 0 = has not finished, 1 = its pages were resident, 2 = gave up; *ready_ms = when it saw them
+ * resident, in milliseconds after the migration kernel started (0 if it returned before the migration began, e.g.
+ * need[g] == 0).  Either pointer may be NULL.
+ */
+int msched_gate_enqueue(msched_ctx *ctx, const msched_plan_t *plan, uint32_t g, void *stream, uint32_t timeout_us);
+int msched_gate_result(msched_ctx *ctx, uint32_t g, uint32_t *status, float *ready_ms);
+
+/*
  * Offline memory analyzer (Sec. 5.2, "Memory analyzer"): derive access rules from profiled invocations.
  * A batch holds n_kernels kernels, each with n_invocations profiled invocations.  Per invocation: the
  * launch arguments as 64-bit values (32-bit ones zero-extended), and the byte intervals (start, length)

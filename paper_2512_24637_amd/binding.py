@@ -18,6 +18,7 @@ EXPORTED_SYMBOLS = (
     "msched_pagetable_query", "msched_pagetable_query_static", "msched_plan_copy_lists", "msched_state_copy",
     "msched_set_profiling", "msched_get_phase_ms", "msched_strerror", "msched_last_hip_error",
     "msched_analyze", "msched_set_early_start", "msched_plan_ready_need", "msched_progress",
+    "msched_gate_enqueue", "msched_gate_result",
 )
 
 
@@ -106,6 +107,8 @@ def load_library():
         "msched_set_early_start": [vp, C.c_int],
         "msched_plan_ready_need": [vp, C.POINTER(_Plan), vp],
         "msched_progress": [vp, C.POINTER(u32)],
+        "msched_gate_enqueue": [vp, C.POINTER(_Plan), u32, vp, u32],
+        "msched_gate_result": [vp, u32, C.POINTER(u32), C.POINTER(C.c_float)],
     }
     for name, argtypes in sig.items():
         fn = getattr(lib, name)
@@ -265,6 +268,16 @@ class MSched:
         v = C.c_uint32(0)
         self._check(self.lib.msched_progress(self.h, C.byref(v)))
         return int(v.value)
+
+    def gate_enqueue(self, plan: Plan, g: int, stream: int, timeout_us: int = 0):
+        """Put the device-side gate of covered command g on `stream` (a hipStream_t handle other than the context's)."""
+        self._check(self.lib.msched_gate_enqueue(self.h, C.byref(plan._raw), int(g), stream, int(timeout_us)))
+
+    def gate_result(self, g: int):
+        """(status, ready_ms) of gate g: 0 not finished, 1 pages were resident, 2 gave up."""
+        st, ms = C.c_uint32(0), C.c_float(0.0)
+        self._check(self.lib.msched_gate_result(self.h, int(g), C.byref(st), C.byref(ms)))
+        return int(st.value), float(ms.value)
 
     def pagetable_query(self, pages) -> np.ndarray:
         pages = np.ascontiguousarray(pages, np.uint64)

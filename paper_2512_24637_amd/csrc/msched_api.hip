@@ -154,6 +154,7 @@ void free_ctx(msched_ctx *c) {
     if (c->poll_stream) { (void)hipStreamSynchronize(c->poll_stream); (void)hipStreamDestroy(c->poll_stream); }
     for (void *p : {(void *)c->page_done, (void *)c->chunks_done, (void *)c->landed}) if (p) (void)hipFree(p);
     if (c->need_host) (void)hipHostFree(c->need_host);
+    if (c->gate_host) (void)hipHostFree(c->gate_host);
     if (c->progress_host) (void)hipHostFree(c->progress_host);
     if (c->cmd_ptrs_host) (void)hipHostFree((void *)c->cmd_ptrs_host);
     for (auto &e : c->ev) if (e) (void)hipEventDestroy(e);
@@ -867,6 +868,10 @@ int msched_set_early_start(msched_ctx *c, int enable) {
             HIP_TRY(c, hipHostMalloc((void **)&c->progress_host, 64, hipHostMallocDefault));
             *c->progress_host = 0;
         }
+        if (!c->gate_host) {
+            HIP_TRY(c, hipHostMalloc((void **)&c->gate_host, sizeof(GateRec) * (MSCHED_MAX_TIMELINE_COMMANDS + 1), hipHostMallocDefault));
+            memset(c->gate_host, 0, sizeof(GateRec) * (MSCHED_MAX_TIMELINE_COMMANDS + 1));
+        }
         if (!c->poll_stream) HIP_TRY(c, hipStreamCreateWithFlags(&c->poll_stream, hipStreamNonBlocking));
         HIP_TRY(c, launch_peek(c));                          // the first launch on a stream sets up its queue: not during a migration
         HIP_TRY(c, hipDeviceSynchronize());
@@ -881,6 +886,28 @@ int msched_plan_ready_need(msched_ctx *c, const msched_plan_t *plan, uint32_t *n
     if (plan->plan_id != c->plan_seq || !c->plan_early) return MSCHED_E_STALE_PLAN;
     if (plan->covered_launches)                                // written by the plan's kernels, which have finished
         memcpy(need, c->need_host, (size_t)plan->covered_launches * 4);
+    return MSCHED_OK;
+}
+
+int msched_gate_enqueue(msched_ctx *c, const msched_plan_t *plan, uint32_t g, void *stream, uint32_t timeout_us) {
+    if (!c || !plan) return MSCHED_E_INVAL;
+    if (plan->plan_id != c->plan_seq || !c->plan_early || !c->early_ready) return MSCHED_E_STALE_PLAN;
+    if (c->pending_plan != 0) return MSCHED_E_STALE_PLAN;       // not migrated yet: see the header
+    if (g >= plan->covered_launches || (hipStream_t)stream == c->stream) return MSCHED_E_INVAL;   // on the context's own stream it would wait for itself
+    const uint64_t ticks = (uint64_t)(timeout_us ? timeout_us : 2000000u) * 100u;                   // 100 MHz wall clock
+    c->gate_host[g].status = 0;
+    std::atomic_thread_fence(std::memory_order_release);
+    HIP_TRY(c, launch_gate(c, g, c->need_host[g], ticks, (hipStream_t)stream));
+    return MSCHED_OK;
+}
+
+int msched_gate_result(msched_ctx *c, uint32_t g, uint32_t *status, float *ready_ms) {
+    if (!c || g > MSCHED_MAX_TIMELINE_COMMANDS) return MSCHED_E_INVAL;
+    if (!c->gate_host) return MSCHED_E_STALE_PLAN;
+    const uint32_t st = *(volatile uint32_t *)&c->gate_host[g].status;
+    std::atomic_thread_fence(std::memory_order_acquire);
+    if (status) *status = st;
+    if (ready_ms) *ready_ms = st == 1 ? (float)((double)c->gate_host[g].ticks / 1e5) : 0.f;
     return MSCHED_OK;
 }
 

@@ -103,6 +103,10 @@ struct TaskQueue {
 };
 
 // A run of one timeline entry: commands [first, first + count) of `task` take the positions g0, g0 + 1, ...
+// What a gate kernel (msched_gate_enqueue) reports: status 1 = pages resident, 2 = gave up; the fetch entries it saw
+// landed; 100 MHz ticks from the start of the migration kernel to that moment (0 if the migration had not begun).
+struct GateRec { uint32_t status, seen; uint64_t ticks; };
+
 struct PlanRun { uint32_t task, g0, count; size_t first; };
 
 // One source of the id-list merge: a prepared (de-duplicated, grouped by bucket) piece of a command's list.
@@ -229,7 +233,9 @@ struct msched_ctx {
     uint32_t *need_host = nullptr;              // pinned [MAX_G + 1]: need[g] of the latest plan (written by the cut kernel)
     uint32_t *page_done = nullptr;              // device [F]: tag of the migration that completed fetch entry i
     uint32_t *chunks_done = nullptr;            // device [F]: chunks of entry i copied so far (zero between migrations)
-    uint32_t *landed = nullptr;                 // device: [0] leading fetch entries complete, [1] work units handed out
+    uint32_t *landed = nullptr;                 // device: [0] leading fetch entries complete, [1] work units handed out,
+                                                // [2..3] wall clock at which the latest early migration kernel started (0: not yet)
+    msched::GateRec *gate_host = nullptr;       // pinned [MAX_G + 1]: what the gate kernel of command g left behind
     uint32_t *progress_host = nullptr;          // pinned: where msched_progress reads `landed` into
     hipStream_t poll_stream = nullptr;          // msched_progress works here, beside the migration
     uint32_t early_tag = 0;                     // nonzero tag of the latest early migration
@@ -261,6 +267,7 @@ hipError_t launch_init_tables(msched_ctx *c);
 hipError_t query_scratch_init(uint8_t **out);                                         // address of the static staging array on the current device
 hipError_t query_static(msched_ctx *c, const uint64_t *page_ids, uint32_t n, uint32_t *out);
 hipError_t launch_peek(msched_ctx *c);
+hipError_t launch_gate(msched_ctx *c, uint32_t g, uint32_t need, uint64_t timeout_ticks, hipStream_t stream);
 hipError_t launch_list_prepare(msched_ctx *c, const ListPrep *table_dev, uint32_t n, uint32_t n_buckets, uint32_t split);      // landed -> progress_host on the poll stream
 
 extern int g_last_hip;                        // hipError_t of the last failed HIP call of any context

@@ -46,6 +46,8 @@ __global__ __launch_bounds__(256) void k_migrate(MigrateArgs a) {
     const uint32_t chunk_bytes = 1u << a.chunk_shift;
     const uint32_t sweep = 256 * kLanesBytes;                  // bytes one pass of the workgroup covers
     __shared__ uint32_t s_unit;
+    if (kEarly && blockIdx.x == 0 && threadIdx.x == 0)         // when this migration began, for the gates' reports
+        __hip_atomic_store(reinterpret_cast<uint64_t *>(a.landed + 2), (uint64_t)wall_clock64(), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     for (uint64_t unit = blockIdx.x;; unit += gridDim.x) {
         if (kTicket) {
             // Units are handed out in list order from a counter, not dealt round-robin: workgroups
@@ -166,6 +168,27 @@ __global__ __launch_bounds__(256) void k_migrate(MigrateArgs a) {
     }
 }
 
+// The device-side consumer of `landed`: one lane waits until the fetch entries command g needs are complete and
+// returns, which lets the next kernel of its stream start.  The wait ends in any case: after timeout_ticks of the
+// 100 MHz wall clock it gives up, and says so.  Frames were written with write-through stores before `landed`
+// moved over them, and a kernel that starts after this one begins with fresh caches.
+__global__ void k_gate(const uint32_t *landed, uint32_t need, uint64_t timeout_ticks, GateRec *out) {
+    const uint64_t t0 = wall_clock64();
+    uint32_t seen, status = 2;
+    for (;;) {
+        seen = __hip_atomic_load(landed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (seen >= need) { status = 1; break; }
+        if (wall_clock64() - t0 > timeout_ticks) break;
+        __builtin_amdgcn_s_sleep(64);
+    }
+    const uint64_t now = wall_clock64();
+    const uint64_t began = __hip_atomic_load(reinterpret_cast<const uint64_t *>(landed + 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    out->seen = seen;
+    out->ticks = (status == 1 && began != 0 && now > began) ? now - began : 0;
+    __threadfence_system();
+    __hip_atomic_store(&out->status, status, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 __global__ void k_peek(const uint32_t *landed, uint32_t *out) {
     *out = __hip_atomic_load(landed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -265,6 +288,15 @@ hipError_t launch_migrate(msched_ctx *c, const PlanHeader &h) {
     if (a.landed) k_migrate<true, true><<<(uint32_t)blocks, 256, 0, c->stream>>>(a);
     else if (c->migrate_ticket) k_migrate<false, true><<<(uint32_t)blocks, 256, 0, c->stream>>>(a);
     else k_migrate<false, false><<<(uint32_t)blocks, 256, 0, c->stream>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_gate(msched_ctx *c, uint32_t g, uint32_t need, uint64_t timeout_ticks, hipStream_t stream) {
+    (void)hipGetLastError();
+    GateRec *out = nullptr;
+    hipError_t e = hipHostGetDevicePointer((void **)&out, c->gate_host + g, 0);
+    if (e != hipSuccess) return e;
+    k_gate<<<1, 1, 0, stream>>>(c->landed, need, timeout_ticks, out);
     return hipGetLastError();
 }
 

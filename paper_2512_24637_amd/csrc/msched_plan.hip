@@ -1277,7 +1277,9 @@ __device__ void cut_body(const CutArgs &a, uint32_t *lds) {
         // victim offsets, farthest next use first: resident classes G (never used), G - 1, ..., g_cut
         wave_exclusive_scan(K, [&](uint32_t j) { return (G - j >= g_cut) ? tot[K + (G - j)] : 0u; },
                             [&](uint32_t j, uint32_t before, uint32_t) { a.offsets[K + (G - j)] = (G - j >= g_cut) ? before : kSkip; });
-        if (a.landed && (tid % kWave) == 0) { a.landed[0] = 0; a.landed[1] = 0; }   // entries landed, work units handed out
+        if (a.landed && (tid % kWave) == 0) {   // entries landed, work units handed out, start of the migration kernel
+            a.landed[0] = 0; a.landed[1] = 0; a.landed[2] = 0; a.landed[3] = 0;
+        }
     }
     __syncthreads();
     MSCHED_TICK(kTickCut, 3);

@@ -166,3 +166,64 @@ class _SampledMigrate:
             assert np.array_equal(got.numpy(), want), ("entries", lo, hi, "read before they had landed")
             _SampledMigrate.entries_checked += hi - lo
             _SampledMigrate.in_flight += int(busy)
+
+
+def test_device_side_gates_release_consumers_when_their_pages_are_in():
+    """msched_gate_enqueue: gates for the first, a middle and the last covered command on a second stream, each
+    followed by a kernel that reads the frames of the fetch entries the command needs while the migration is still
+    running on the context's stream; every gate reports "resident", later gates report later times, the reads
+    find the pages' words, and the first command's gate opens while the migration is still in flight.  A gate with
+    a microsecond to live, queued behind the start of a migration of hundreds of megabytes, gives up (status 2)
+    and its stream moves on."""
+    import torch
+    from workloads import page_words
+    from paper_2512_24637_amd import MSchedError
+    trace = make_trace(4, page_shift=16, n_launches=512)     # decode: every launch of a step needs one more layer
+    g = GpuSide(trace)
+    try:
+        g.ms.set_early_start(True)
+        side = torch.cuda.Stream()
+        wpp = trace.page_bytes // 8
+        seen_in_flight = gave_up = 0
+        for sw in range(4):
+            t = sw % trace.n_tasks
+            p = g.ms.plan([((t + k) % trace.n_tasks, trace.timeslice) for k in range(trace.n_tasks)])
+            need = g.ms.ready_need(p)
+            with pytest.raises(MSchedError):                  # not before its migration
+                g.ms.gate_enqueue(p, 0, side.cuda_stream)
+            fetch_pages, fetch_frames = p.fetch_pages.copy(), p.fetch_frames.copy()
+            frames_dev = torch.from_numpy(fetch_frames.astype(np.int64)).cuda()
+            last = p.covered_launches - 1
+            torch.cuda.synchronize()
+            g.ms.migrate_only(p)
+            if sw == 1:
+                g.ms.gate_enqueue(p, last, side.cuda_stream, timeout_us=1)
+                side.synchronize()
+                st, ms = g.ms.gate_result(last)
+                assert st in (1, 2) and (st == 1 or ms == 0.0)
+                gave_up += st == 2
+            picks = sorted({0, p.covered_launches // 3, last})
+            got = []
+            with torch.cuda.stream(side):
+                for j, gi in enumerate(picks):
+                    g.ms.gate_enqueue(p, gi, side.cuda_stream)
+                    lo = max(0, int(need[gi]) - 64)
+                    got.append((gi, lo, g.pool[frames_dev[lo:int(need[gi])]].clone()))   # runs behind the gate
+                    if j == 0:
+                        side.synchronize()
+                        seen_in_flight += not g.stream.query()
+            side.synchronize()
+            results = [g.ms.gate_result(gi) for gi in picks]
+            assert all(st == 1 for st, _ in results), results
+            times = [ms for _, ms in results]
+            assert times == sorted(times), times
+            for gi, lo, words in got:
+                want = page_words(fetch_pages[lo:int(need[gi])], wpp)
+                assert np.array_equal(words.cpu().numpy().view(np.uint64), want), (sw, gi)
+            torch.cuda.synchronize()
+            assert g.ms.progress() == p.n_fetch
+            g.ms.launch_retire(t, p.covered_launches)
+        assert seen_in_flight >= 2, "the first command's gate should open while the migration is still running"
+        assert gave_up == 1
+    finally:
+        g.close()
