@@ -895,7 +895,10 @@ struct TileLists {
     const uint32_t *bucket_mark;        // [n_buckets] does any prepared piece hold an id of this bucket?
     const uint32_t *order;              // [n_chunks] the chunk of each workgroup (chunk_order_block)
 };
-constexpr int kFusedPieces = 6;         // segments in flight per wavefront of the sweep, one row of 64 ids each per pass: what
+#ifndef MSCHED_FUSED_PIECES
+#define MSCHED_FUSED_PIECES 6
+#endif
+constexpr int kFusedPieces = MSCHED_FUSED_PIECES;         // segments in flight per wavefront of the sweep, one row of 64 ids each per pass: what
 #ifndef MSCHED_FUSED_WIDTH
 #define MSCHED_FUSED_WIDTH 32
 #endif
