@@ -18,6 +18,7 @@
 #include <algorithm>
 
 #include <cstdlib>
+#include <cstring>
 
 #include "msched_internal.h"
 
@@ -790,7 +791,10 @@ __device__ void paint_tile(const SweepGeom &sg, uint64_t t0, uint64_t t1, uint32
 // in LDS.  Returns how many ranges were offered to the queue, the same number to every thread: above
 // kPaintInRegisters the caller paints the tile in LDS instead (after a barrier of its own: paint_tile resets the
 // queue).
-constexpr uint32_t kPaintInRegisters = 16;
+#ifndef MSCHED_PAINT_IN_REGISTERS
+#define MSCHED_PAINT_IN_REGISTERS 64
+#endif
+constexpr uint32_t kPaintInRegisters = MSCHED_PAINT_IN_REGISTERS;
 // The queue is empty on entry (count_body resets it ahead of a barrier it needs anyway).
 __device__ uint32_t queue_ranges(const SweepGeom &sg, uint64_t t0, uint64_t t1, PaintLds &q) {
     constexpr uint32_t kPerThread = 4;
@@ -949,9 +953,17 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
 #pragma unroll
                 for (int j = 0; j < kCountBatch; ++j) from_ranges[j] = tile_paint == kPaintLds ? eight_at(pt, j) : sg.G;
                 if (tile_paint == kPaintQueued) {
-                    const uint32_t nq = s_paint.n_queued, at = (uint32_t)(first - tile_begin);
-                    for (uint32_t w = 0; w < nq; ++w) {          // the same range for every lane: LDS broadcasts
-                        const uint32_t lo = s_paint.lo[w], n = s_paint.hi[w] - lo, g = s_paint.g[w];
+                    // every lane applies every queued range to its eight pages: lane w fetches range w from LDS once,
+                    // and the loop takes it from that lane's registers (a dependent LDS read per range and lane made
+                    // a tile with dozens of short ranges spend most of its time here)
+                    const uint32_t nq = __builtin_amdgcn_readfirstlane(s_paint.n_queued), at = (uint32_t)(first - tile_begin);   // uniform: a scalar loop
+                    static_assert(kPaintInRegisters <= (uint32_t)kWave, "one queued range per lane");
+                    const uint32_t q_lo = lane < nq ? s_paint.lo[lane] : 0u;
+                    const uint32_t q_n = lane < nq ? s_paint.hi[lane] - q_lo : 0u;
+                    const uint32_t q_g = lane < nq ? s_paint.g[lane] : 0u;
+                    for (uint32_t w = 0; w < nq; ++w) {
+                        const uint32_t lo = __builtin_amdgcn_readlane(q_lo, w), n = __builtin_amdgcn_readlane(q_n, w),
+                                       g = __builtin_amdgcn_readlane(q_g, w);
 #pragma unroll
                         for (int j = 0; j < kCountBatch; ++j)
                             if (at + j - lo < n) from_ranges[j] = min(from_ranges[j], g);
@@ -1041,6 +1053,7 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
             }
         } else {
             const int tile_paint = paint_ranges();
+            MSCHED_TICK(kTickCount, 2);
             // does any id list of this plan reach into this tile?  (the same answer for every thread)
             bool tile_nu = sg.use_nu != 0;
             if (tile_nu && sg.bucket_mark != nullptr && tile_begin < p_end) {
@@ -1049,6 +1062,7 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
                 tile_nu = any != 0;
             }
             sweep_tile(tile_paint, tile_nu);
+            MSCHED_TICK(kTickCount, 5);
         }
         if (round + 1 < sg.rounds && (sg.n_ranges || kLists)) {
             __syncthreads();                              // the next tile repaints, and queues its ranges afresh
@@ -1200,6 +1214,7 @@ struct CutArgs {
     uint32_t seq;                      // stamp for the host copy of the header
     uint32_t *need_host, *landed;      // early execution (both null when it is off)
     uint32_t in_place;                 // replace `groups` by their exclusive prefix over the rows (they are the matrix itself)
+    uint32_t counts_in_lds;            // one workgroup does everything: the per-key totals are already in lds[0 .. n_keys)
 };
 
 // Exclusive scan of n values by ONE wavefront, no barrier: lane l owns the segment [l * per, (l + 1) * per) of
@@ -1230,7 +1245,7 @@ __device__ void cut_body(const CutArgs &a, uint32_t *lds) {
     const uint32_t tid = threadIdx.x, wave = tid / kWave;
     if (tid == 0) { s_cut = 0; s_res = 0; s_fetch = 0; }
     MSCHED_TICK(kTickCut, 0);
-    for (uint32_t key = tid; key < n_keys; key += nthreads) {
+    for (uint32_t key = tid; key < n_keys && !a.counts_in_lds; key += nthreads) {
         uint32_t v[kRowGroups];
 #pragma unroll
         for (uint32_t rg = 0; rg < kRowGroups; ++rg) v[rg] = (rg < a.n_groups) ? a.groups[rg * n_keys + key] : 0;
@@ -1242,6 +1257,8 @@ __device__ void cut_body(const CutArgs &a, uint32_t *lds) {
         }
         tot[key] = run;
     }
+    if (a.counts_in_lds)                                     // the one row's exclusive prefix over the rows: all zero
+        for (uint32_t key = tid; key < n_keys; key += nthreads) a.groups[key] = 0;
     __syncthreads();
     MSCHED_TICK(kTickCut, 1);
     // The three scans below are short (K = G + 1 values): each is done by one wavefront without a barrier, the
@@ -1523,10 +1540,17 @@ __global__ __launch_bounds__(kWave * kMaxWaves, 6) void k_emit(EmitArgs a, Sweep
 
 // Page tables small enough for one workgroup: count, cut, emit and frame assignment in one launch
 // (planning such a table is bound by launch latency, not by bandwidth).
-__global__ __launch_bounds__(kWave * kMaxWaves) void k_tail(SweepGeom sg, CutArgs ca, EmitArgs ea) {
+// A short range list rides in the kernel's arguments: the workgroup then reads it from the argument segment
+// instead of from the pinned host memory the plan wrote it to - two passes over the list, each a round trip over
+// the host link (9 of the 22 us of this kernel on the tiny round-robin schedule).
+constexpr uint32_t kInlineRanges = 160;
+struct InlineRanges { PageRange r[kInlineRanges]; };
+__global__ __launch_bounds__(kWave * kMaxWaves) void k_tail(SweepGeom sg, CutArgs ca, EmitArgs ea, const InlineRanges inl) {
     extern __shared__ uint32_t lds[];
+    if (sg.ranges == nullptr) sg.ranges = inl.r;
     count_body<false>(ea.page_table, ea.nu, sg, 0, lds, ca.groups, nullptr, nullptr);
     __syncthreads();
+    ca.counts_in_lds = 1;                                 // the only chunk's counts are where the sweep left them
     cut_body(ca, lds);
     __syncthreads();
     emit_body(ea, sg, 0, lds);
@@ -1690,6 +1714,7 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     ca.hdr_dev = c->hdr_dev; ca.hdr_host = c->hdr_host; ca.seq = c->hdr_seq;
     ca.need_host = c->early ? c->need_host : nullptr; ca.landed = c->early ? c->landed : nullptr;
     ca.in_place = few_rows ? 1u : 0u;
+    ca.counts_in_lds = 0;
     EmitArgs ea;
     ea.page_table = c->page_table; ea.nu = c->nu; ea.matrix = few_rows ? c->matrix : c->matrix + c->matrix_cap;   // chunk start positions
     ea.counts = few_rows ? nullptr : c->matrix;
@@ -1698,7 +1723,12 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     ea.fetch_frames = c->fetch_frames;
     const size_t cut_lds = (size_t)(g.n_keys + g.G + 1) * 4, emit_lds = emit_lds_words(g.waves, g.n_keys) * 4;
     if (g.single) {
-        k_tail<<<1, threads, std::max(cut_lds, emit_lds + paint_lds + 16), st>>>(sg, ca, ea);
+        InlineRanges inl;                                    // copied into the launch's argument buffer (unused entries are never read)
+        if (g.n_ranges && g.n_ranges <= kInlineRanges) {
+            memcpy(inl.r, c->ranges_host, sizeof(PageRange) * g.n_ranges);
+            sg.ranges = nullptr;                             // the kernel points it at its argument
+        }
+        k_tail<<<1, threads, std::max(cut_lds, emit_lds + paint_lds + 16), st>>>(sg, ca, ea, inl);
         if (c->profiling) CK(hipEventRecord(c->ev[4], st));
         return hipGetLastError();
     }

@@ -73,7 +73,7 @@ def test_many_commands_through_the_multi_kernel_cut(oracle_mod, monkeypatch, n_p
     assert lockstep(oracle_mod, trace, with_bytes=True, horizon="full", max_plans=3) == 3
 
 
-@pytest.mark.parametrize("n_ranges", [15, 16, 17, 70])
+@pytest.mark.parametrize("n_ranges", [16, 63, 64, 65, 66, 70, 118])
 @pytest.mark.parametrize("force_multi", [False, True])
 def test_ranges_per_tile_around_the_limit_of_the_register_path(oracle_mod, monkeypatch, n_ranges, force_multi):
     """Up to 16 partial ranges of a tile are applied from registers, more are painted in LDS (queue of 64, then
