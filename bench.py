@@ -35,21 +35,20 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 # Measured traffic of k_migrate at the L2's external port (HBM + host fabric) relative to the bytes it has to
-# move, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script calibrated against a 1 GiB device copy
-# (profiles/k_migrate_c2_stencil_pmc_traffic.md).
-MIGRATE_TRAFFIC_RATIO = {"read": 1.0001, "write": 1.0018}
-MIGRATE_TRAFFIC_SOURCE = ("profiles/k_migrate_c2_stencil_pmc_traffic.md (FETCH_SIZE x2.000 and WRITE_SIZE x1.000 after "
-                          "calibration; bytes per launch at the L2 external port relative to the algorithmic bytes)")
-# Same for all planning kernels of one plan on the planning-stress structure (list preparation included at its
-# per-plan share): 127.4 MiB measured against 251.9 MiB by the algorithmic count (profiles/planning_c5_structure_kernels_and_traffic.md); below 1 because
-# range rules are painted in LDS and no longer cost a memory access per page touch, and the sweeps skip what they
-# can prove they do not need.
-PLAN_TRAFFIC_RATIO = 0.506
-# The same counters for the planning kernels of one context switch of config 5 itself (plan + its share of the id-list
-# preparation), in bytes per plan.
-PLAN_TRAFFIC_BYTES_PER_PLAN = 133.6e6
-PLAN_TRAFFIC_SOURCE = ("profiles/planning_c5_structure_kernels_and_traffic.md (FETCH_SIZE + WRITE_SIZE of all planning "
-                       "kernels, calibrated, per plan)")
+# move, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script on config 5 calibrated against its 1 GiB
+# device copies (profiles/k_migrate_c5_planning_stress_kernel_trace_and_traffic.md).
+MIGRATE_TRAFFIC_RATIO = {"read": 1.033, "write": 1.015}
+MIGRATE_TRAFFIC_SOURCE = ("profiles/k_migrate_c5_planning_stress_kernel_trace_and_traffic.md (FETCH_SIZE x2.000 and WRITE_SIZE "
+                          "x1.000 after calibration; bytes per launch at the L2 external port relative to the algorithmic bytes; "
+                          "1.0001 / 1.0018 on the 2 MiB pages of config 2)")
+# The same counters for all planning kernels on the back-to-back planning leg (64-byte pages) relative to its
+# two-sweep byte count.
+PLAN_TRAFFIC_RATIO = 0.50
+# ... and for the planning kernels of one context switch of config 5 itself (plan + the id-list preparation behind
+# the preceding migration), in bytes per context switch (profiles/planning_c5_context_kernels_and_traffic.md).
+PLAN_TRAFFIC_BYTES_PER_PLAN = 131.65e6
+PLAN_TRAFFIC_SOURCE = ("profiles/planning_c5_context_kernels_and_traffic.md (FETCH_SIZE x2.000 + WRITE_SIZE x1.000 of "
+                       "k_stage, k_count_lists, k_cut_offsets, k_emit and k_list_prepare, per context switch)")
 WORKLOADS = {
     1: "c1-tiny-round-robin: 3 tasks, 64 KiB pages, pool 256 frames (16 MiB), footprint 24 MiB, timeslice 10 launches",
     2: "c2-stencil-sweep: 4 tasks x 3 arrays of 256 MiB, 2 MiB pages, pool 1024 frames (2 GiB), footprint 3 GiB "
@@ -292,8 +291,8 @@ def bench_planning_stress(torch, warmup=8, steps=16, phases=True):
     ach = sum(bytes_) / (sum(dev_ms) / 1e3) / 1e9
     out = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
            "traffic": PLAN_TRAFFIC_RATIO * float(np.mean(bytes_)),
-           "traffic_source": "profiles/planning_c5_structure_kernels_and_traffic.md (FETCH_SIZE + WRITE_SIZE of all "
-                             "planning kernels, calibrated, per plan)",
+           "traffic_source": "profiles/planning_c5_context_kernels_and_traffic.md (the same kernels on config 5's own context "
+                             "switches: 0.50 x this count)",
            "workload": "c5-planning-stress page structure (V=10485760, F=4194304, G=400)",
            "plan_device_us_mean": float(np.mean(dev_ms)) * 1e3,
            "plan_host_wall_us_mean": float(np.mean(r["plan_wall_s"])) * 1e6,
