@@ -3,17 +3,19 @@
 
 A step is one context switch: msched_plan (timeline -> fetch / eviction lists) followed by
 msched_migrate (full-duplex batched copy + page-table update), on a synthetic schedule with
-the page structure of the configured workload.  Prints ONE JSON line on stdout.
+the page structure of the configured workload, at its full size.  Prints ONE JSON line on stdout.
 
-  value         migrated GB/s over the K timed steps (bytes evicted + fetched, divided by
-                the wall time of plan + migrate)
+  value         migrated GB/s over the K timed steps of config 5, the largest configuration (bytes evicted +
+                fetched, divided by the wall time of plan + migrate)
+  per_config    the same for each of the five configurations (20 timed steps each beside the headline), with
+                the copy kernel against the host link and the plan latency on the host and on the device
   roofline      the copy kernel against the host link: the same byte mix at the
                 hipMemcpy rates measured in this run with both directions busy
-  roofline_plan the planning kernels against HBM bandwidth on the planning-stress
-                page structure (10 M pages, 4 M frames, 8 M page ids per plan)
+  roofline_plan the planning kernels of the same timed context switches against HBM bandwidth, the id-list
+                preparation behind each migration included, priced with three byte counts
   cpu_baseline  the plain CPU oracle timed on a bounded sample of the same schedule
   early_start   early execution on the LLM-decode schedule: copy rate with the in-order landing switched on,
-                and when each covered launch could start, against the end of the whole migration
+                and when each covered launch's device-side gate opened, against the end of the whole migration
   priority      real-time inference preempting best-effort training under the priority policy (latency-weighted
                 timelines): what a request's context switch costs (plan + restore of its working set)
   ablation      allocation-granularity prediction against the templates on the LLM-decode schedule (migration volume
