@@ -76,7 +76,7 @@ def test_many_commands_through_the_multi_kernel_cut(oracle_mod, monkeypatch, n_p
 @pytest.mark.parametrize("n_ranges", [16, 63, 64, 65, 66, 70, 118])
 @pytest.mark.parametrize("force_multi", [False, True])
 def test_ranges_per_tile_around_the_limit_of_the_register_path(oracle_mod, monkeypatch, n_ranges, force_multi):
-    """Up to 16 partial ranges of a tile are applied from registers, more are painted in LDS (queue of 64, then
+    """Up to 64 partial ranges of a tile are applied from registers, more are painted in LDS (queue of 64, then
     in place): n short ranges inside one tile, long ranges that cover whole tiles and end inside others, and the
     table's ragged end; the second plan has to evict part of what the first brought in."""
     if force_multi:
@@ -353,6 +353,44 @@ def test_earlier_planning_paths_stay_bit_exact(oracle_mod, monkeypatch, env):
     assert lockstep(oracle_mod, make_trace(5, scale=64, n_launches=100), with_bytes=True, bytes_every=4) >= 16
     assert lockstep(oracle_mod, make_trace(3, scale=16, iterations=2), with_bytes=True, bytes_every=3) >= 4
     assert lockstep(oracle_mod, make_trace(4, page_shift=12, layers=8, steps=16), with_bytes=True, bytes_every=3) >= 8
+
+
+@pytest.mark.parametrize("case", ["one-launch-of-5000-chunks", "6000-chunks-over-300-launches"])
+def test_more_ranges_than_the_range_list_holds(oracle_mod, case):
+    """Plans whose range rules do not fit the list the sweeps paint from (4096 ranges) scatter next uses per page
+    instead: a single launch whose strided rule has 5000 one-page chunks (nothing is kept of its ranges when it is
+    queued), and 300 launches of 20 chunks each (every launch fits, the plan does not).  Launches that repeat a region
+    of a queued launch, and plain ranges beside the strided ones, go through the same plans."""
+    from workloads import Trace, RULE_STRIDED
+    from workloads.trace import CommandBuilder
+    P = 64
+    strided = [Rule(RULE_STRIDED, 0, (1,), 1, (2,), 1, (3,), 1)]          # args: base, chunk bytes, stride bytes, chunks
+    linear = [Rule(RULE_LINEAR, 0, (1,), 1)]
+    both = [Rule(RULE_STRIDED, 0, (2,), 1, (3,), 1, (4,), 1), Rule(RULE_LINEAR, 1, (5,), 1)]
+    kernels = [strided, linear, both]
+    t0, t1 = CommandBuilder(), CommandBuilder()
+    if case == "one-launch-of-5000-chunks":
+        V, F, slice_len = 40000, 9000, 3
+        for rep in range(4):
+            t0.add(0, [0, P, 2 * P, 5000])                                  # pages 0, 2, ..., 9998
+            t0.add(1, [12000 * P + 8, 500 * P])                             # a ragged plain range
+            t0.add(0, [0, P, 2 * P, 5000])                                  # the same region again
+            t0.add(2, [20000 * P, 30000 * P, 3 * P, 7 * P, 40, 100 * P])    # 40 chunks of 3 pages + a plain range
+            t1.add(0, [1 * P, P, 2 * P, 4500])                              # the odd pages
+            t1.add(1, [35000 * P, 2000 * P])
+            t1.add(2, [20000 * P, 30000 * P, 3 * P, 7 * P, 40, 100 * P])    # task 0's region, from another task
+    else:
+        V, F, slice_len = 40000, 12000, 150
+        rng = np.random.default_rng(5)
+        for t in (t0, t1):
+            for i in range(300):
+                base = int(rng.integers(0, 30000))
+                t.add(0, [base * P, 2 * P, 9 * P, 20])                      # 20 chunks of 2 pages
+                if i % 7 == 0:
+                    t.add(0, [base * P, 2 * P, 9 * P, 20])                  # a repeat right behind it
+    trace = Trace(name=case, page_shift=6, n_virtual_pages=V, n_frames=F, timeslice=slice_len, kernels=kernels,
+                  tasks=[t0.build(), t1.build()], n_slots=V)
+    assert lockstep(oracle_mod, trace, with_bytes=True, bytes_every=2) >= 4
 
 
 @pytest.mark.parametrize("early", [False, True], ids=["plain", "early-execution"])
