@@ -899,16 +899,20 @@ struct TileLists {
     const uint32_t *bucket_mark;        // [n_buckets] does any prepared piece hold an id of this bucket?
     const uint32_t *order;              // [n_chunks] the chunk of each workgroup (chunk_order_block)
 };
+// Shape of the merge inside the sweep, as build-time constants so that variants can be measured side by side:
+// kFusedPieces loads in flight per wavefront and pass, each a row of kFusedWidth ids from each of 64 / kFusedWidth
+// segments (a segment of one bucket and piece is a few dozen ids).  On the planning-stress schedule a tile's merge
+// takes 10.8 us with rows of 64 ids, 9.6 with 32, 9.3 with 16; 8, 10 or 12 loads in flight instead of 6 are equal or
+// slower, and so are two rows per segment and pass.
 #ifndef MSCHED_FUSED_PIECES
 #define MSCHED_FUSED_PIECES 6
 #endif
-constexpr int kFusedPieces = MSCHED_FUSED_PIECES;         // segments in flight per wavefront of the sweep, one row of 64 ids each per pass: what
 #ifndef MSCHED_FUSED_WIDTH
 #define MSCHED_FUSED_WIDTH 32
 #endif
-constexpr int kFusedWidth = MSCHED_FUSED_WIDTH;   // lanes per segment in the sweep's merge (on the planning-stress schedule the merge
-                                                  // of a tile takes 10.8 us with 64, 9.6 with 32, 9.3 with 16)
-constexpr int kFusedRows = 1;           // 64 registers hold (a segment of one bucket and piece is a few dozen ids; 4 x 2 rows: +0.7 us)
+constexpr int kFusedPieces = MSCHED_FUSED_PIECES;
+constexpr int kFusedWidth = MSCHED_FUSED_WIDTH;
+constexpr int kFusedRows = 1;
 constexpr uint32_t kStagePieces = 512;   // segments of a bucket described in LDS at a time (16 bytes each)
 
 template <bool kLists>
@@ -1116,11 +1120,10 @@ __global__ __launch_bounds__(kWave * kMaxWaves) void k_count(const uint32_t *__r
     count_body<false>(page_table, nu, sg, chunk, lds, matrix + (size_t)chunk * n_keys, group_row, slice_row);
 }
 
-// The first sweep with the id lists merged in (see count_body).  At most 64 registers: with 44 KiB of LDS a
-// compute unit then holds three of these workgroups, a tile with ids next to two without.  (Measured on the
-// planning-stress structure: 1024 threads with half the steps each, two workgroups per compute unit, 0.6 us slower
-// per plan; 8 segments in flight per wavefront at 89 registers 2 us slower; 128 or 192 segments described at a
-// time, which fits a fourth workgroup, 1.8 and 2.5 us slower.)
+// The first sweep with the id lists merged in (see count_body).  With 44 KiB of LDS a compute unit holds three
+// of these workgroups, a tile with ids next to two without.  (Measured on the planning-stress structure: 1024
+// threads with half the steps each, two workgroups per compute unit, 0.6 us slower per plan; 128 or 192 segments
+// described at a time, which fits a fourth workgroup, 1.8 and 2.5 us slower.)
 static_assert(kMaxWaves * kMaxSteps * kWave == (int)kBucketPages, "a full-size tile is one bucket");
 constexpr int kFusedThreads = kWave * kMaxWaves;
 // Registers: three of these workgroups (24 wavefronts, 6 per SIMD) share a compute unit, its LDS allows no more, so
