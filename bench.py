@@ -624,6 +624,7 @@ def bench_config(torch, config, warmup, steps, link, extra_phase_steps=0):
     plan_dev = [ph["plan"] for ph in phases]
     prep_dev = [ph.get("prepare", 0.0) for ph in phases]
     host_wall = np.array(plan_wall) * 1e6
+    abi_wall = np.array([ph["host_prep"] + ph["host_launch"] + ph["host_wait"] for ph in phases]) * 1e3
     out = {
         "workload": WORKLOADS[config], "steps": steps, "warmup": warmup,
         "page_bytes": P, "n_virtual_pages": trace.n_virtual_pages, "n_frames": trace.n_frames,
@@ -632,15 +633,14 @@ def bench_config(torch, config, warmup, steps, link, extra_phase_steps=0):
         "migrate": {"achieved_GBs": achieved, "peak_GBs": peak, "frac": (achieved / peak) if peak else None,
                     "launches": n_copy, "avg_launch_ms": (mig_s / n_copy * 1e3) if n_copy else None,
                     "bytes_per_launch": (moved / n_copy) if n_copy else None},
-        "plan_latency_us": {"host_wall_mean": float(host_wall.mean()), "host_wall_p50": float(np.median(host_wall)),
-                            "host_wall_max": float(host_wall.max()),
+        # host_wall: msched_plan timed inside the library, from its first line to the counts being known (the call
+        # returns there, while the kernel that fills the lists still runs); python_call_wall: the Python caller's clock
+        # around the ctypes call, i.e. with the binding's marshalling on top
+        "plan_latency_us": {"host_wall_mean": float(abi_wall.mean()), "host_wall_p50": float(np.median(abi_wall)),
+                            "host_wall_max": float(abi_wall.max()),
                             "device_mean": float(np.mean(plan_dev)) * 1e3,
-                            "host_minus_device_mean": float(host_wall.mean() - np.mean(plan_dev) * 1e3),
-                            # the same call timed inside the library, from its first line to the counts being known
-                            # (host_wall is the Python caller's clock around the ctypes call and its marshalling)
-                            "c_abi_wall_mean": float(np.mean([ph["host_prep"] + ph["host_launch"] + ph["host_wait"] for ph in phases])) * 1e3,
-                            "c_abi_minus_device_mean": float(np.mean([ph["host_prep"] + ph["host_launch"] + ph["host_wait"] - ph["plan"]
-                                                                      for ph in phases])) * 1e3,
+                            "host_minus_device_mean": float(abi_wall.mean() - np.mean(plan_dev) * 1e3),
+                            "python_call_wall_mean": float(host_wall.mean()),
                             "list_prepare_device_mean": float(np.mean(prep_dev)) * 1e3,
                             "host_flatten_mean": float(np.mean([ph["host_prep"] for ph in phases])) * 1e3,
                             "host_launch_mean": float(np.mean([ph["host_launch"] for ph in phases])) * 1e3,
