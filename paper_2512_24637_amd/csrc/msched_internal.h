@@ -132,7 +132,7 @@ __host__ __device__ inline uint32_t prep_part_words(uint32_t n_buckets, uint32_t
 }
 constexpr uint32_t kMaxListSources = 4096;
 constexpr uint32_t kBucketShift = 13;           // id lists are grouped by bucket of this many (log2) consecutive pages
-constexpr uint32_t kPrepBlock = 24576;          // ids per prepared piece (what one workgroup keeps in LDS)
+constexpr uint32_t kPrepBlock = 24576;          // ids per prepared piece (24 per thread of the workgroup that prepares it, in registers)
 
 // A page range [lo, hi) first used by command g: what a fixed / linear rule, or one chunk of a strided
 // rule, describes once its formulas are evaluated.

@@ -407,9 +407,8 @@ __global__ __launch_bounds__(kListThreads) void k_list_prepare(const ListPrep *_
                                                                uint32_t *__restrict__ bucket_mark) {
     extern __shared__ uint32_t bin_lds[];
     uint32_t *seen = bin_lds;                               // [1 << kBinSeenBits]
-    uint32_t *kept = seen + (1u << kBinSeenBits);           // [kPrepBlock]
-    uint32_t *cnt = kept + kPrepBlock;                      // [buckets of the part + 1] counts, then starts, then write cursors
-    __shared__ uint32_t n_kept, bad;
+    uint32_t *cnt = seen + (1u << kBinSeenBits);            // [buckets of the part + 1] counts, then starts, then write cursors
+    __shared__ uint32_t bad;
     __shared__ uint32_t wave_sums[kListThreads / kWave];
     // A piece is prepared by prep_split workgroups, neighbours in dispatch order: each reads all its ids (the
     // second to fourth reader find them in the L2) and keeps those of its own range of buckets, a part of the work
@@ -425,19 +424,19 @@ __global__ __launch_bounds__(kListThreads) void k_list_prepare(const ListPrep *_
     MSCHED_TICK(kTickPrepare, 0);
     for (uint32_t i = threadIdx.x; i < (1u << kBinSeenBits); i += blockDim.x) seen[i] = kNone;
     for (uint32_t b = threadIdx.x; b <= per_part; b += blockDim.x) cnt[b] = 0;
-    if (threadIdx.x == 0) { n_kept = 0; bad = 0; }
+    if (threadIdx.x == 0) bad = 0;
     __syncthreads();
     MSCHED_TICK(kTickPrepare, 1);
-    const int lane = lane_id();
     // A piece is at most kPrepBlock = 24 x 1024 ids, 24 per thread.  The work on them is done in passes over all of
     // a thread's ids, so that the round trips of one pass (memory, or an LDS operation whose result is needed)
-    // overlap instead of queueing up id by id: all loads; all look-ups of the second entries; all exchanges with
-    // the first entries; then one reservation per wavefront for everything it keeps.
+    // overlap instead of queueing up id by id: all loads; look-ups and exchanges with the table of repeats, four
+    // ids at a time; counts per bucket.  What a thread keeps stays in its registers (24 ids and a mask) until the
+    // bucket starts are known and it writes them out: no copy of the survivors in LDS (96 KiB less of it).
     constexpr int kPerThread = kPrepBlock / kListThreads;
     static_assert(kPerThread * kListThreads == (int)kPrepBlock, "a thread's share of a piece");
+    uint32_t p[kPerThread];
+    uint32_t ok = 0;                                      // bit j: id j of this thread is (still) to be kept
     {
-        uint32_t p[kPerThread];
-        uint32_t ok = 0;                                  // bit j: id j of this thread is (still) to be kept
 #pragma unroll
         for (int j = 0; j < kPerThread; ++j) {
             const uint32_t i = j * blockDim.x + threadIdx.x;
@@ -495,23 +494,9 @@ __global__ __launch_bounds__(kListThreads) void k_list_prepare(const ListPrep *_
             }
         }
         MSCHED_TICK(kTickPrepare, 3);
-        // room in `kept`: one LDS add per wavefront for all its survivors, then every lane places its own
-        uint32_t mine = __popc(ok), before = mine;         // inclusive prefix over the lanes
-        for (int d = 1; d < kWave; d <<= 1) {
-            const uint32_t up = __shfl_up(before, d, kWave);
-            if (lane >= d) before += up;
-        }
-        uint32_t start = 0;
-        if (lane == kWave - 1 && before) start = atomicAdd(&n_kept, before);
-        start = __shfl(start, kWave - 1, kWave) + before - mine;
-        MSCHED_TICK(kTickPrepare, 4);
 #pragma unroll
-        for (int j = 0; j < kPerThread; ++j) {
-            if ((ok >> j) & 1u) {
-                kept[start++] = p[j];
-                atomicAdd(&cnt[(p[j] >> kBucketShift) / split], 1u);
-            }
-        }
+        for (int j = 0; j < kPerThread; ++j)
+            if ((ok >> j) & 1u) atomicAdd(&cnt[(p[j] >> kBucketShift) / split], 1u);
         MSCHED_TICK(kTickPrepare, 5);
     }
     __syncthreads();
@@ -529,17 +514,16 @@ __global__ __launch_bounds__(kListThreads) void k_list_prepare(const ListPrep *_
     __syncthreads();
     MSCHED_TICK(kTickPrepare, 9);
     uint32_t *out = block + per_part + 2;
-    const uint32_t m = n_kept;
-    for (uint32_t i0 = threadIdx.x; i0 < m; i0 += blockDim.x * 4) {   // four positions asked for before the first is used
-        uint32_t p[4], at[4];
+    constexpr int kAhead = 4;                                 // positions asked for before the first is used
 #pragma unroll
-        for (int j = 0; j < 4; ++j) p[j] = i0 + j * blockDim.x < m ? kept[i0 + j * blockDim.x] : kNone;
+    for (int j0 = 0; j0 < kPerThread; j0 += kAhead) {
+        uint32_t at[kAhead];
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            at[j] = p[j] != kNone ? atomicAdd(&cnt[(p[j] >> kBucketShift) / split], 1u) : 0u;   // the starts double as write cursors
+        for (int u = 0; u < kAhead; ++u)
+            at[u] = ((ok >> (j0 + u)) & 1u) ? atomicAdd(&cnt[(p[j0 + u] >> kBucketShift) / split], 1u) : 0u;   // the starts double as write cursors
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (p[j] != kNone) out[at[j]] = p[j];
+        for (int u = 0; u < kAhead; ++u)
+            if ((ok >> (j0 + u)) & 1u) out[at[u]] = p[j0 + u];
     }
     MSCHED_TICK(kTickPrepare, 10);
 }
@@ -1632,7 +1616,7 @@ hipError_t allow_large_lds() {
 hipError_t launch_list_prepare(msched_ctx *c, const ListPrep *table_dev, uint32_t n, uint32_t n_buckets, uint32_t split) {
     if (n == 0) return hipSuccess;
     (void)hipGetLastError();
-    const size_t prep_lds = 4 * ((size_t)(1u << kBinSeenBits) + kPrepBlock + prep_part_buckets(n_buckets, split) + 1);
+    const size_t prep_lds = 4 * ((size_t)(1u << kBinSeenBits) + prep_part_buckets(n_buckets, split) + 1);
     k_list_prepare<<<n * split, kListThreads, prep_lds, c->stream>>>(table_dev, n_buckets, split, c->V, c->slot, c->bucket_mark);
     return hipGetLastError();
 }
