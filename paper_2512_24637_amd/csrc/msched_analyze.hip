@@ -273,7 +273,7 @@ __global__ __launch_bounds__(kWave) void k_analyze(AnaArgs a) {
     uint64_t *stride = chunk + n_inv, *count = stride + n_inv;    // [n_inv] each
     uint32_t *s_niv = reinterpret_cast<uint32_t *>(count + n_inv);                 // [n_inv]
     uint16_t *s_m0 = reinterpret_cast<uint16_t *>(s_niv + n_inv); // [12][n_inv]: interval index at each pointer
-    __shared__ uint32_t s_cand[MSCHED_MAX_ARGS], s_subsets[kAnaMaxSubsets];
+    __shared__ uint32_t s_cand[MSCHED_MAX_ARGS];
     const ulonglong2 *g_args = reinterpret_cast<const ulonglong2 *>(a.args + (size_t)k * n_inv * MSCHED_MAX_ARGS);
     const ulonglong2 *g_iv = reinterpret_cast<const ulonglong2 *>(a.iv + (size_t)k * n_inv * max_iv * 2);   // (start, length)
     const uint32_t *g_niv = a.n_iv + (size_t)k * n_inv;
@@ -365,12 +365,12 @@ __global__ __launch_bounds__(kWave) void k_analyze(AnaArgs a) {
     };
     if (live_mask) {
         window(__builtin_ctz(live_mask));
-        for (uint32_t r = lane; r < n_subsets; r += kWave) s_subsets[r] = g_subset_table[nc][r];
+
     }
     ANA_TICK(3);
     Analyzer an;
     an.n_inv = n_inv; an.lane = lane; an.s_args = s_args; an.count = count;
-    an.subsets = s_subsets; an.cand = s_cand; an.n_subsets = n_subsets; an.n_singles = nc;
+    an.subsets = g_subset_table[nc]; an.cand = s_cand; an.n_subsets = n_subsets; an.n_singles = nc;
     uint32_t n_rules = 0, covered = 0, accepted_mask = 0;
     for (uint32_t rest = live_mask; rest; rest &= rest - 1) {
         const uint32_t arg = __builtin_ctz(rest);

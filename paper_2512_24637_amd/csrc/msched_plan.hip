@@ -1710,7 +1710,7 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     ea.fetch_frames = c->fetch_frames;
     const size_t cut_lds = (size_t)(g.n_keys + g.G + 1) * 4, emit_lds = emit_lds_words(g.waves, g.n_keys) * 4;
     if (g.single) {
-        InlineRanges inl;                                    // copied into the launch's argument buffer (unused entries are never read)
+        InlineRanges inl{};                                  // copied into the launch's argument buffer (entries beyond n_ranges are never read)
         if (g.n_ranges && g.n_ranges <= kInlineRanges) {
             memcpy(inl.r, c->ranges_host, sizeof(PageRange) * g.n_ranges);
             sg.ranges = nullptr;                             // the kernel points it at its argument
