@@ -1231,6 +1231,9 @@ __device__ void cut_body(const CutArgs &a, uint32_t *lds) {
     __shared__ uint32_t s_cut, s_res, s_fetch;
     const uint32_t tid = threadIdx.x, wave = tid / kWave;
     if (tid == 0) { s_cut = 0; s_res = 0; s_fetch = 0; }
+    // what the kernels before raised (every one of them is complete, or - in the single-workgroup kernel - behind a
+    // barrier); asked for here so that the round trip is over by the time the header is written
+    const uint32_t status_seen = tid == 0 ? __hip_atomic_load(a.flags, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
     MSCHED_TICK(kTickCut, 0);
     for (uint32_t key = tid; key < n_keys && !a.counts_in_lds; key += nthreads) {
         uint32_t v[kRowGroups];
@@ -1292,7 +1295,7 @@ __device__ void cut_body(const CutArgs &a, uint32_t *lds) {
     MSCHED_TICK(kTickCut, 3);
     if (tid == 0) {
         uint32_t n_fetch = s_fetch;
-        uint32_t status = *a.flags;
+        uint32_t status = status_seen;
         a.flags[0] = 0;                                     // clean for the next plan's expansion
         a.flags[1] = 0;                                     // work-unit counter of the migration that follows
         if (g_end0 > 0 && g_cut == 0) status |= kStatWset;
