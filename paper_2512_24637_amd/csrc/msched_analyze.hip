@@ -123,14 +123,15 @@ struct Analyzer {
     const uint64_t *val;            // LDS [n_inv]: the quantity being fitted
     const uint64_t *count;          // LDS [n_inv]: chunks in the region
     bool multi_only;                // fit over invocations with more than one chunk only
-    const uint32_t *subsets;        // LDS [n_subsets] packed positions
+    const uint32_t *subsets;        // global [n_subsets] packed positions (a row of the subset table)
     const uint32_t *cand;           // LDS [nc] argument index of each candidate
     uint32_t n_subsets, n_singles;
+    uint32_t first_ranks, next_ranks;   // this lane's entry of the table for the first two screening rounds (ranks 1 + lane
+                                        // and 1 + n_singles + lane): every search starts with them, so they are read once
 
     __device__ __forceinline__ bool used(uint32_t i) const { return !multi_only || count[i] > 1; }
 
-    __device__ __forceinline__ Subset subset(uint32_t rank) const {
-        const uint32_t packed = subsets[rank];
+    __device__ __forceinline__ Subset unpack(uint32_t packed) const {
         Subset S;
         S.n = (int)(packed >> 24);
         S.a0 = S.n > 0 ? cand[packed & 0xff] : 0;
@@ -214,13 +215,16 @@ struct Analyzer {
         for (uint32_t r0 = 1; r0 < n_subsets;) {
             const uint32_t r1 = min(r0 <= n_cand ? 1 + n_cand : r0 + kWave, n_subsets);
             const uint32_t rank = r0 + lane;
-            bool pass = false;
-            if (rank < r1) pass = screen(subset(rank), probe);
+            uint32_t packed = 0;
+            if (r0 == 1) packed = first_ranks;
+            else if (r0 == 1 + n_cand) packed = next_ranks;
+            else if (rank < r1) packed = subsets[rank];
+            const bool pass = rank < r1 && screen(unpack(packed), probe);
             uint64_t m = __ballot(pass);
             while (m) {
-                const uint32_t best = r0 + __ffsll((unsigned long long)m) - 1;
+                const int l = __ffsll((unsigned long long)m) - 1;      // the lowest rank that passed the screen
                 m &= m - 1;
-                const Subset S = subset(best);
+                const Subset S = unpack((uint32_t)__shfl((int)packed, l));
                 if (verify(S, c_out)) { S_out = S; return true; }
             }
             r0 = r1;
@@ -256,11 +260,55 @@ __device__ __forceinline__ void rule_words(uint32_t kind, uint32_t base_arg, con
     w[2] = 0;
 }
 
-constexpr uint32_t kRowLanes = 8;                 // lanes that share one invocation's interval row when matching pointers
-constexpr uint32_t kRowsPerLane = kWave / kRowLanes;           // rows each lane visits per block of 64 invocations
+constexpr uint32_t kHead = 8;                     // intervals of an invocation that its lane keeps in registers
+
+// The value itself, but of unknown origin to the optimizer: a tree of selects over the elements of a local array is
+// otherwise rewritten as one load at a computed index, which moves the array from registers to scratch memory.
+__device__ __forceinline__ uint64_t from_register(uint64_t v) {
+    asm("" : "+v"(v));
+    return v;
+}
+
+// entry m (0..7) of eight values a lane holds, where m differs from lane to lane: a tree of selects, no memory
+__device__ __forceinline__ ulonglong2 pick8(const ulonglong2 (&c)[kHead], uint32_t m) {
+    const bool b0 = m & 1, b1 = m & 2, b2 = m & 4;
+    uint64_t x[kHead], y[kHead];
+    #pragma unroll
+    for (uint32_t j = 0; j < kHead; ++j) { x[j] = from_register(c[j].x); y[j] = from_register(c[j].y); }
+    ulonglong2 lo, hi, r;
+    lo.x = b1 ? (b0 ? x[3] : x[2]) : (b0 ? x[1] : x[0]);
+    lo.y = b1 ? (b0 ? y[3] : y[2]) : (b0 ? y[1] : y[0]);
+    hi.x = b1 ? (b0 ? x[7] : x[6]) : (b0 ? x[5] : x[4]);
+    hi.y = b1 ? (b0 ? y[7] : y[6]) : (b0 ? y[5] : y[4]);
+    r.x = b2 ? hi.x : lo.x;
+    r.y = b2 ? hi.y : lo.y;
+    return r;
+}
+
+// intervals mo .. mo + 7 of one invocation's row (indices clamped to the row: every row has max_iv entries allocated)
+__device__ __forceinline__ void load8(const ulonglong2 *row, uint32_t mo, uint32_t max_iv, ulonglong2 (&c)[kHead]) {
+    #pragma unroll
+    for (uint32_t j = 0; j < kHead; ++j) c[j] = row[min(mo + j, max_iv - 1)];
+}
+
+// where, among the intervals mo .. mo + 7 of a row of n, does each 64-bit argument (bits of mask) start one?
+__device__ __forceinline__ void scan8(const ulonglong2 (&c)[kHead], uint32_t mo, uint32_t n, uint32_t mask,
+                                      const ulonglong2 (&av)[MSCHED_MAX_ARGS / 2], uint32_t (&found)[MSCHED_MAX_ARGS]) {
+    #pragma unroll
+    for (int arg = 0; arg < MSCHED_MAX_ARGS; ++arg) {
+        if ((mask >> arg) & 1) {
+            const uint64_t v = (arg & 1) ? av[arg / 2].y : av[arg / 2].x;
+            #pragma unroll
+            for (int j = (int)kHead - 1; j >= 0; --j)
+                if (mo + j < n && c[j].x == v) found[arg] = mo + j;
+        }
+    }
+}
+
 constexpr uint32_t kArgBatch = 6;                 // 16-byte loads a lane keeps in flight while staging arguments
 constexpr uint32_t kNoInterval = 0xffff;
 static_assert(kArgBatch * 2 == MSCHED_MAX_ARGS, "one trip of the staging loop moves 64 whole argument rows");
+static_assert(MSCHED_MAX_ARGS % 2 == 0, "argument rows are read two at a time");
 
 // Every phase that reads global memory issues all its loads before it looks at any of them: one wavefront
 // has little else to hide a memory round trip behind, and the number of dependent round trips is what its
@@ -278,6 +326,12 @@ __global__ __launch_bounds__(kWave) void k_analyze(AnaArgs a) {
     const ulonglong2 *g_iv = reinterpret_cast<const ulonglong2 *>(a.iv + (size_t)k * n_inv * max_iv * 2);   // (start, length)
     const uint32_t *g_niv = a.n_iv + (size_t)k * n_inv;
     ANA_TICK(0);
+    // A lane keeps the first eight intervals of "its" invocation (the one with its number) in registers from here to
+    // the end: pointer matching, and the regions measured at every base, find them there.  They are asked for before
+    // anything else, so that they travel together with the arguments; slots beyond a row's count lie inside the row
+    // and are ignored.  A row of eight intervals is one 128-byte line, read by one lane.
+    ulonglong2 head[kHead];
+    load8(g_iv + (size_t)min(lane, n_inv - 1) * max_iv, 0, max_iv, head);
     // 0. arguments and interval counts into LDS
     uint32_t total = 0;
     {
@@ -299,43 +353,44 @@ __global__ __launch_bounds__(kWave) void k_analyze(AnaArgs a) {
             if (i < n_inv) { niv = min(niv, max_iv); s_niv[i] = niv; total += niv; }
         }
     }
-    for (uint32_t f = lane; f < n_inv * MSCHED_MAX_ARGS; f += kWave) s_m0[f] = kNoInterval;
     const int n_args = min(max(a.n_args[k], 0), MSCHED_MAX_ARGS);
     const uint32_t mask = a.int64_mask[k] & ((1u << n_args) - 1);
     __syncthreads();
     ANA_TICK(1);
-    // 1. base pointers: 64-bit arguments whose value starts an interval in every invocation.  Every interval
-    //    start is read once, eight lanes to a row, and compared with the invocation's 64-bit arguments.
-    auto match = [&](uint32_t i, uint32_t m, uint64_t start) {
-        for (uint32_t rest = mask; rest; rest &= rest - 1) {
-            const uint32_t arg = __builtin_ctz(rest);
-            if (s_args[i * MSCHED_MAX_ARGS + arg] == start) s_m0[arg * n_inv + i] = (uint16_t)m;
-        }
-    };
+    // 1. base pointers: 64-bit arguments whose value starts an interval in every invocation.  A lane takes whole
+    //    invocations: the row of arguments from LDS in one go, the row's intervals eight at a time, every start
+    //    compared with every 64-bit argument.  (Starts within a row are distinct: at most one interval matches.)
+    uint32_t unmatched = 0;                  // bit a: argument a starts no interval in one of this lane's invocations
     if (mask)
         for (uint32_t ib = 0; ib < n_inv; ib += kWave) {
-            const uint32_t sub = lane % kRowLanes;
-            uint64_t start[kRowsPerLane];
-            uint32_t nn[kRowsPerLane];
+            const uint32_t i = ib + lane;
+            if (i >= n_inv) continue;
+            const uint32_t n = s_niv[i];
+            const ulonglong2 *arow2 = reinterpret_cast<const ulonglong2 *>(s_args + i * MSCHED_MAX_ARGS);
+            ulonglong2 av[MSCHED_MAX_ARGS / 2];
             #pragma unroll
-            for (uint32_t p = 0; p < kRowsPerLane; ++p) {
-                const uint32_t i = ib + p * kRowsPerLane + lane / kRowLanes;
-                nn[p] = i < n_inv ? s_niv[i] : 0;
-                start[p] = sub < nn[p] ? g_iv[(size_t)i * max_iv + sub].x : 0;
+            for (int j = 0; j < MSCHED_MAX_ARGS / 2; ++j) av[j] = arow2[j];
+            uint32_t found[MSCHED_MAX_ARGS];
+            #pragma unroll
+            for (int arg = 0; arg < MSCHED_MAX_ARGS; ++arg) found[arg] = kNoInterval;
+            if (ib == 0) scan8(head, 0, n, mask, av, found);
+            for (uint32_t mo = ib == 0 ? kHead : 0; mo < n; mo += kHead) {
+                ulonglong2 c[kHead];
+                load8(g_iv + (size_t)i * max_iv, mo, max_iv, c);
+                scan8(c, mo, n, mask, av, found);
             }
             #pragma unroll
-            for (uint32_t p = 0; p < kRowsPerLane; ++p) {
-                const uint32_t i = ib + p * kRowsPerLane + lane / kRowLanes;
-                if (sub < nn[p]) match(i, sub, start[p]);
-                for (uint32_t m = sub + kRowLanes; m < nn[p]; m += kRowLanes) match(i, m, g_iv[(size_t)i * max_iv + m].x);
-            }
+            for (int arg = 0; arg < MSCHED_MAX_ARGS; ++arg)
+                if ((mask >> arg) & 1) {
+                    s_m0[arg * n_inv + i] = (uint16_t)found[arg];
+                    unmatched |= (found[arg] == kNoInterval ? 1u : 0u) << arg;
+                }
         }
     __syncthreads();
     ANA_TICK(2);
     uint32_t nc = 0, base_mask = 0;
     for (int arg = 0; arg < n_args; ++arg) {
-        bool missing = !((mask >> arg) & 1);
-        for (uint32_t i = lane; i < n_inv && !missing; i += kWave) missing = s_m0[arg * n_inv + i] == kNoInterval;
+        const bool missing = !((mask >> arg) & 1) || ((unmatched >> arg) & 1);
         if (__ballot(missing) == 0) base_mask |= 1u << arg;
         else { if (lane == 0) s_cand[nc] = arg; ++nc; }
     }
@@ -354,23 +409,30 @@ __global__ __launch_bounds__(kWave) void k_analyze(AnaArgs a) {
         if (!alias) live_mask |= 1u << arg;
     }
     const uint32_t n_subsets = subsets_of(nc);
-    // the first two intervals at a base, for the first 64 invocations: loaded one base ahead of their use
-    ulonglong2 w0 = {0, 0}, w1 = {0, 0};
-    auto window = [&](uint32_t arg) {
-        if (lane < n_inv) {
-            const uint32_t n = s_niv[lane], m0 = s_m0[arg * n_inv + lane];
-            w0 = g_iv[(size_t)lane * max_iv + m0];
-            if (m0 + 1 < n) w1 = g_iv[(size_t)lane * max_iv + m0 + 1];
-        }
-    };
-    if (live_mask) {
-        window(__builtin_ctz(live_mask));
-
-    }
-    ANA_TICK(3);
     Analyzer an;
+    an.subsets = g_subset_table[nc];
+    an.first_ranks = 1 + lane < n_subsets ? an.subsets[1 + lane] : 0;
+    an.next_ranks = 1 + nc + lane < n_subsets ? an.subsets[1 + nc + lane] : 0;
+    // Which of the first 32 intervals of invocation i start at a base pointer: a region's run of chunks ends in front
+    // of them.  All twelve index entries are read at once (those of other arguments hold nothing and are masked out).
+    auto bases_at = [&](uint32_t i) __attribute__((always_inline)) -> uint32_t {
+        uint32_t at = 0;
+        #pragma unroll
+        for (int b = 0; b < MSCHED_MAX_ARGS; ++b) {
+            const uint32_t m = s_m0[b * n_inv + i];
+            at |= ((base_mask >> b) & 1) && m < 32 ? 1u << m : 0u;
+        }
+        return at;
+    };
+    const uint32_t own_bases_at = lane < n_inv ? bases_at(lane) : 0;
+    // interval m of invocation i, for the lane that owns the invocation (i = lane, lane + 64, ...)
+    auto interval = [&](uint32_t i, uint32_t m) __attribute__((always_inline)) -> ulonglong2 {
+        if (i < kWave && m < kHead) return pick8(head, m);
+        return g_iv[(size_t)i * max_iv + m];
+    };
+    ANA_TICK(3);
     an.n_inv = n_inv; an.lane = lane; an.s_args = s_args; an.count = count;
-    an.subsets = g_subset_table[nc]; an.cand = s_cand; an.n_subsets = n_subsets; an.n_singles = nc;
+    an.cand = s_cand; an.n_subsets = n_subsets; an.n_singles = nc;
     uint32_t n_rules = 0, covered = 0, accepted_mask = 0;
     for (uint32_t rest = live_mask; rest; rest &= rest - 1) {
         const uint32_t arg = __builtin_ctz(rest);
@@ -378,21 +440,19 @@ __global__ __launch_bounds__(kWave) void k_analyze(AnaArgs a) {
         // 2. the region that starts at this base, per invocation: a run of equal intervals at a regular stride
         bool any_multi = false;
         for (uint32_t i = lane; i < n_inv; i += kWave) {
-            const ulonglong2 *row = g_iv + (size_t)i * max_iv;
             const uint64_t *arow = s_args + i * MSCHED_MAX_ARGS;
             const uint32_t n = s_niv[i], m0 = s_m0[arg * n_inv + i];
-            ulonglong2 first = w0, next = w1;
-            if (i >= kWave) {
-                first = row[m0];
-                if (m0 + 1 < n) next = row[m0 + 1];
-            }
+            const ulonglong2 first = interval(i, m0);
             const uint64_t len = first.y;
+            const uint32_t at = i < kWave ? own_bases_at : bases_at(i);
             uint64_t st = 0, cnt = 1, prev = first.x;
             for (uint32_t m = m0 + 1; m < n; ++m) {
-                if (m > m0 + 1) next = row[m];
+                const ulonglong2 next = interval(i, m);
                 bool other = next.y != len;
-                for (uint32_t bases = base_mask & ~(1u << arg); bases; bases &= bases - 1)
-                    other |= arow[__builtin_ctz(bases)] == next.x;
+                if (m < 32) other |= (at >> m) & 1;
+                else
+                    for (uint32_t bases = base_mask & ~(1u << arg); bases; bases &= bases - 1)
+                        other |= arow[__builtin_ctz(bases)] == next.x;
                 const uint64_t gap = next.x - prev;
                 if (other || (cnt > 1 && gap != st)) break;
                 st = gap; prev = next.x; ++cnt;
@@ -402,7 +462,6 @@ __global__ __launch_bounds__(kWave) void k_analyze(AnaArgs a) {
         }
         __syncthreads();
         if (n_rules == 0) ANA_TICK(5);
-        if (rest & (rest - 1)) window(__builtin_ctz(rest & (rest - 1)));
         const bool strided = __ballot(any_multi) != 0;
         // 3. templates in order: invariant size, size proportional to arguments, strided
         Subset S_size, S_stride, S_count;

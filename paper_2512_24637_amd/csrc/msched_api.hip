@@ -364,47 +364,58 @@ int msched_launch_enqueue(msched_ctx *c, uint32_t task, uint32_t kernel_id, cons
     if (rc) return rc;
     TaskQueue &t = c->tasks[task];
     if (t.n - t.base == t.cap) {
-        // Grow the pinned record array, dropping retired records.  Kernels read queue records only ahead of the cut
-        // of a plan (staging, expansion, id-list binning), and msched_plan returns after the cut has stamped its
-        // header; what msched_migrate queues behind the copy (id-list preparation) reads the caller's id arrays
-        // and a table of its own, never a record.  So nothing that is still queued or running can hold an address
-        // into the old array - and the stream is drained here all the same, so that this stays true if a later
-        // kernel of a plan ever reads records: growing a queue is rare, a wait costs nothing then.
+        // The record array is full: drop the retired records, and grow it if most of it is still live.  Kernels read
+        // queue records only ahead of the cut of a plan (staging, expansion, id-list binning), and msched_plan returns
+        // after the cut has stamped its header; what msched_migrate queues behind the copy (id-list preparation) reads
+        // the caller's id arrays and a table of its own, never a record.  So nothing that is still queued or running
+        // can hold an address into the array - and the stream is drained here all the same, so that this stays true
+        // if a later kernel of a plan ever reads records: this happens once per `cap` launches, a wait costs nothing then.
         HIP_TRY(c, hipStreamSynchronize(c->stream));
         const size_t live = t.n - t.cursor, off = t.cursor - t.base;
-        const size_t ncap = std::max<size_t>(256, live * 2);
-        // the compact arrays first: if one of them cannot grow, nothing has changed yet
-        std::vector<uint32_t> lat, n_ids, list_back;
-        std::vector<uint64_t> range_end, prep;
-        std::vector<const uint32_t *> ids;
-        std::vector<uint8_t> flag;
-        const int rc_room = guarded([&]() -> int {
-            lat.resize(ncap); n_ids.resize(ncap); list_back.resize(ncap); range_end.resize(ncap); prep.resize(ncap);
-            ids.resize(ncap); flag.resize(ncap);
-            return MSCHED_OK;
-        });
-        if (rc_room) return rc_room;
-        CmdRec *nr = nullptr, *nd = nullptr;
-        HIP_TRY(c, hipHostMalloc((void **)&nr, ncap * sizeof(CmdRec), hipHostMallocDefault));
-        const hipError_t e = hipHostGetDevicePointer((void **)&nd, nr, 0);
-        if (e != hipSuccess) { (void)hipHostFree(nr); HIP_TRY(c, e); }
         const uint64_t keep_from = t.cap ? t.range_begin(t.cursor) : 0;      // the retired commands' ranges go too
-        if (live) {
-            memcpy(nr, t.recs + off, live * sizeof(CmdRec));
-            std::copy_n(t.lat.begin() + off, live, lat.begin());
-            std::copy_n(t.n_ids.begin() + off, live, n_ids.begin());
-            std::copy_n(t.list_back.begin() + off, live, list_back.begin());
-            std::copy_n(t.range_end.begin() + off, live, range_end.begin());
-            std::copy_n(t.prep.begin() + off, live, prep.begin());
-            std::copy_n(t.ids.begin() + off, live, ids.begin());
-            std::copy_n(t.flag.begin() + off, live, flag.begin());
+        if (t.cap && live <= t.cap / 2) {
+            // a queue in steady state (launches retire as fast as they arrive): the live records move to the front,
+            // nothing is allocated
+            if (live && off) {
+                memmove(t.recs, t.recs + off, live * sizeof(CmdRec));
+                auto front = [&](auto &v) { std::copy(v.begin() + off, v.begin() + off + live, v.begin()); };
+                front(t.lat); front(t.n_ids); front(t.list_back); front(t.range_end); front(t.prep); front(t.ids); front(t.flag);
+            }
+        } else {
+            const size_t ncap = std::max<size_t>(256, live * 2);
+            // the compact arrays first: if one of them cannot grow, nothing has changed yet
+            std::vector<uint32_t> lat, n_ids, list_back;
+            std::vector<uint64_t> range_end, prep;
+            std::vector<const uint32_t *> ids;
+            std::vector<uint8_t> flag;
+            const int rc_room = guarded([&]() -> int {
+                lat.resize(ncap); n_ids.resize(ncap); list_back.resize(ncap); range_end.resize(ncap); prep.resize(ncap);
+                ids.resize(ncap); flag.resize(ncap);
+                return MSCHED_OK;
+            });
+            if (rc_room) return rc_room;
+            CmdRec *nr = nullptr, *nd = nullptr;
+            HIP_TRY(c, hipHostMalloc((void **)&nr, ncap * sizeof(CmdRec), hipHostMallocDefault));
+            const hipError_t e = hipHostGetDevicePointer((void **)&nd, nr, 0);
+            if (e != hipSuccess) { (void)hipHostFree(nr); HIP_TRY(c, e); }
+            if (live) {
+                memcpy(nr, t.recs + off, live * sizeof(CmdRec));
+                std::copy_n(t.lat.begin() + off, live, lat.begin());
+                std::copy_n(t.n_ids.begin() + off, live, n_ids.begin());
+                std::copy_n(t.list_back.begin() + off, live, list_back.begin());
+                std::copy_n(t.range_end.begin() + off, live, range_end.begin());
+                std::copy_n(t.prep.begin() + off, live, prep.begin());
+                std::copy_n(t.ids.begin() + off, live, ids.begin());
+                std::copy_n(t.flag.begin() + off, live, flag.begin());
+            }
+            if (t.recs) (void)hipHostFree(t.recs);
+            t.recs = nr; t.recs_dev = nd; t.cap = ncap;
+            t.lat.swap(lat); t.n_ids.swap(n_ids); t.list_back.swap(list_back); t.range_end.swap(range_end);
+            t.prep.swap(prep); t.ids.swap(ids); t.flag.swap(flag);
         }
         t.ranges.erase(t.ranges.begin(), t.ranges.begin() + (keep_from - t.ranges_base));
         t.ranges_base = keep_from;
-        if (t.recs) (void)hipHostFree(t.recs);
-        t.recs = nr; t.recs_dev = nd; t.cap = ncap; t.base = t.cursor;
-        t.lat.swap(lat); t.n_ids.swap(n_ids); t.list_back.swap(list_back); t.range_end.swap(range_end);
-        t.prep.swap(prep); t.ids.swap(ids); t.flag.swap(flag);
+        t.base = t.cursor;
     }
     return guarded([&]() -> int {
         const size_t i = t.n, li = i - t.base;

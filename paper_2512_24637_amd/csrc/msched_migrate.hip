@@ -10,6 +10,7 @@
 // workgroup keeps host-bound writes and host reads in flight at once, which is what fills the
 // full-duplex link.  Lists are processed in plan order, i.e. in order of first use.
 #include <algorithm>
+#include <atomic>
 #include <cstdlib>
 
 #include "msched_internal.h"
@@ -211,7 +212,9 @@ __global__ __launch_bounds__(256) void k_query(const uint32_t *__restrict__ page
 constexpr size_t kQueryScratchBytes = (size_t)MSCHED_QUERY_STATIC_MAX * (sizeof(uint64_t) + sizeof(uint32_t));
 static __device__ __align__(256) uint8_t scratch[kQueryScratchBytes];
 constexpr int kMaxDevices = 64;
-static uint8_t *g_scratch_ptr[kMaxDevices] = {};          // device address of `scratch` on each GPU, once looked up
+// device address of `scratch` on each GPU, once looked up (contexts of different threads may ask at the same time:
+// they would store the same address)
+static std::atomic<uint8_t *> g_scratch_ptr[kMaxDevices] = {};
 
 // Look the array's address up on the current device (once per device) and keep it.
 hipError_t query_scratch_init(uint8_t **out) {
@@ -219,13 +222,13 @@ hipError_t query_scratch_init(uint8_t **out) {
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
-    if (g_scratch_ptr[dev] == nullptr) {
-        uint8_t *ptr = nullptr;
+    uint8_t *ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (ptr == nullptr) {
         if ((e = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch))) != hipSuccess) return e;
         if (ptr == nullptr) return hipErrorInvalidSymbol;
-        g_scratch_ptr[dev] = ptr;
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);
     }
-    if (out) *out = g_scratch_ptr[dev];
+    if (out) *out = ptr;
     return hipSuccess;
 }
 
