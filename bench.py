@@ -318,9 +318,9 @@ def bench_planning_stress(torch, warmup=8, steps=16, phases=True):
     return out
 
 
-# k_analyze: 329 MB measured (FETCH_SIZE + WRITE_SIZE, calibrated) against 164.3 MB algorithmic per launch
+# k_analyze: 249.9 MB measured (FETCH_SIZE + WRITE_SIZE, calibrated) against 164.3 MB algorithmic per launch
 # (profiles/k_analyze_batch16384_kernel_trace_and_traffic.md).
-ANALYZER_TRAFFIC_RATIO = 2.00
+ANALYZER_TRAFFIC_RATIO = 1.52
 
 
 def bench_analyzer(torch, base_kernels=256, tile=64, n_inv=64, max_iv=48, reps=20, cpu=True):
