@@ -142,6 +142,9 @@ def test_launches_arriving_between_switches(oracle_mod):
                     lazy_slices=2) >= 90
     assert lockstep(oracle_mod, make_trace(4, page_shift=12, layers=8, steps=40), with_bytes=True, bytes_every=5,
                     lazy_slices=3) >= 20
+    # a queue in steady state: 800 launches pass through a record array of 256, which is compacted in place
+    assert lockstep(oracle_mod, make_trace(1, seed=9, n_launches=2400), with_bytes=True, bytes_every=40,
+                    lazy_slices=1) >= 240
 
 
 @pytest.mark.parametrize("binned", [False, True])
