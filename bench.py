@@ -786,7 +786,7 @@ def main():
             f"{per_config[f'c{cfg}']['migrate']['frac']:.3f}, plan host {per_config[f'c{cfg}']['plan_latency_us']['host_wall_mean']:.1f} us "
             f"device {per_config[f'c{cfg}']['plan_latency_us']['device_mean']:.1f} us ({time.perf_counter() - t0:.1f} s)")
     t0 = time.perf_counter()
-    head, raw = bench_config(torch, headline, args.warmup, args.steps, link, extra_phase_steps=8 if headline == 5 else 0)
+    head, raw = bench_config(torch, headline, args.warmup, args.steps, link, extra_phase_steps=8 if headline >= 3 else 0)
     per_config[f"c{headline}"] = head
     log(f"[bench] c{headline} (headline): {head['value_GBs']:.2f} GB/s, migrate frac {head['migrate']['frac']:.3f}, "
         f"plan host {head['plan_latency_us']['host_wall_mean']:.1f} us device {head['plan_latency_us']['device_mean']:.1f} us "

@@ -23,6 +23,13 @@ namespace {
         if (e_ != hipSuccess) { (c)->last_hip = g_last_hip = (int)e_; return MSCHED_E_HIP; } \
     } while (0)
 
+// Nothing may be thrown across the C boundary: the few container operations inside can only fail for memory.
+template <class F> int guarded(F &&body) noexcept {
+    try { return body(); }
+    catch (const std::bad_alloc &) { return MSCHED_E_NOMEM; }
+    catch (...) { return MSCHED_E_INVAL; }
+}
+
 // value = coeff * product(args[idx]), refusing arithmetic that leaves 64 bits (Sec. 5.2: extents
 // are a linear coefficient times a product of launch arguments).
 int checked_formula(uint64_t coeff, const uint8_t *idx, int n, const uint64_t *args, uint32_t n_args, uint64_t *out) {
@@ -99,10 +106,32 @@ inline void region_signature(const msched_ctx *c, const msched_rule &q, const Cm
     sig = {base, size, stride, count ^ (3ull << 62)};
 }
 
-// The page ranges a fixed / linear / strided rule describes for one command (template expansion, Sec. 5.2),
-// appended to `out`.  Returns false when the command would hold more than `cap` ranges.
-inline bool append_ranges(const msched_ctx *c, const msched_rule &q, uint32_t rule, const CmdRec &r, uint32_t back,
-                          std::vector<RangeRec> &out, size_t first, size_t cap) {
+// Room for `count` more ranges in a task's ring: ranges of retired commands are dead, and when the live ones fill
+// it, a ring of twice the size takes over (pinned memory and its mirror: rare, so the stream is drained first - a
+// sweep of a plan whose second half still runs may be reading the mirror).
+int range_room(msched_ctx *c, TaskQueue &t, uint64_t count) {
+    const uint64_t live_from = t.ranges_live_from();
+    if (t.rng_end + count - live_from <= t.rng_cap) return MSCHED_OK;
+    uint64_t ncap = std::max<uint64_t>(4096, t.rng_cap);
+    while (ncap < 2 * (t.rng_end + count - live_from)) ncap *= 2;
+    if (ncap > (1ull << 30)) return MSCHED_E_NOMEM;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    RangeRec *nh = nullptr, *nd = nullptr;
+    HIP_TRY(c, hipHostMalloc((void **)&nh, ncap * sizeof(RangeRec), hipHostMallocDefault));
+    const hipError_t e = hipMalloc((void **)&nd, ncap * sizeof(RangeRec));
+    if (e != hipSuccess) { (void)hipHostFree(nh); HIP_TRY(c, e); }
+    for (uint64_t q = live_from; q < t.rng_end; ++q) nh[q & (ncap - 1)] = t.rng[q & (t.rng_cap - 1)];
+    if (t.rng) (void)hipHostFree(t.rng);
+    if (t.rng_dev) (void)hipFree(t.rng_dev);
+    t.rng = nh; t.rng_dev = nd; t.rng_cap = ncap;
+    t.rng_uploaded = live_from;                  // the new mirror holds nothing yet
+    return MSCHED_OK;
+}
+
+// The page ranges a fixed / linear / strided rule describes for command i of a task (template expansion, Sec. 5.2),
+// appended to the task's ring.  Returns 1 when the command would hold more than `cap` ranges, < 0 on failure.
+inline int append_ranges(msched_ctx *c, TaskQueue &t, const msched_rule &q, const CmdRec &r, size_t i,
+                         uint32_t back, uint64_t first, size_t cap) {
     auto eval = [&](uint64_t coeff, const uint8_t *idx, int cnt) {
         uint64_t v = coeff;
         for (int j = 0; j < cnt; ++j) v *= r.args[idx[j]];    // validated at enqueue: cannot overflow
@@ -111,20 +140,34 @@ inline bool append_ranges(const msched_ctx *c, const msched_rule &q, uint32_t ru
     const uint32_t sh = c->page_shift;
     const uint64_t base = r.args[q.base_arg];
     uint64_t size = q.kind == MSCHED_RULE_FIXED ? q.size_coeff : eval(q.size_coeff, q.size_args, q.n_size_args);
-    if (size == 0) return true;
+    if (size == 0) return MSCHED_OK;
     uint64_t stride = 0, count = 1;
     if (q.kind == MSCHED_RULE_STRIDED) {
         stride = eval(q.stride_coeff, q.stride_args, q.n_stride_args);
         count = eval(q.count_coeff, q.count_args, q.n_count_args);
-        if (count == 0) return true;
+        if (count == 0) return MSCHED_OK;
         if (size >= stride || count == 1) { size = (count - 1) * stride + size; count = 1; }   // the chunks abut or overlap
     }
-    if (count > cap - (out.size() - first)) return false;
+    if (count > cap - (t.rng_end - first)) return 1;
+    const int rc = range_room(c, t, count);
+    if (rc) return rc;
     for (uint64_t j = 0; j < count; ++j) {
-        const uint64_t c0 = base + j * stride;
-        out.push_back(RangeRec{(uint32_t)(c0 >> sh), (uint32_t)(((c0 + size - 1) >> sh) + 1), back, rule});
+        const uint64_t c0 = base + j * stride, at = t.rng_end++ & (t.rng_cap - 1);
+        t.rng[at] = RangeRec{(uint32_t)(c0 >> sh), (uint32_t)(((c0 + size - 1) >> sh) + 1), back, (uint32_t)i};
     }
-    return true;
+    return MSCHED_OK;
+}
+
+// Bring a task's range mirror up to date (one or two copies on the context's stream, straight from the pinned ring).
+int upload_ranges(msched_ctx *c, TaskQueue &t) {
+    const uint64_t from = std::max(t.rng_uploaded, t.ranges_live_from());
+    if (from < t.rng_end) {
+        const uint64_t mask = t.rng_cap - 1, pos = from & mask, n = t.rng_end - from, n1 = std::min(n, t.rng_cap - pos);
+        HIP_TRY(c, hipMemcpyAsync(t.rng_dev + pos, t.rng + pos, n1 * sizeof(RangeRec), hipMemcpyHostToDevice, c->stream));
+        if (n > n1) HIP_TRY(c, hipMemcpyAsync(t.rng_dev, t.rng, (n - n1) * sizeof(RangeRec), hipMemcpyHostToDevice, c->stream));
+    }
+    t.rng_uploaded = t.rng_end;
+    return MSCHED_OK;
 }
 
 // Is the command `back` places before command i of a task still queued (and with it in every timeline)?
@@ -137,6 +180,7 @@ void free_ctx(msched_ctx *c) {
     (void)hipStreamSynchronize(c->stream);
     for (auto &t : c->tasks) if (t.recs) (void)hipHostFree(t.recs);
     for (auto &t : c->tasks) if (t.prep_buf) (void)hipFree(t.prep_buf);
+    for (auto &t : c->tasks) { if (t.rng) (void)hipHostFree(t.rng); if (t.rng_dev) (void)hipFree(t.rng_dev); }
     if (c->list_src_host) (void)hipHostFree(c->list_src_host);
     if (c->list_prep_host) (void)hipHostFree(c->list_prep_host);
     if (c->list_src_stage) (void)hipFree(c->list_src_stage);
@@ -159,13 +203,6 @@ void free_ctx(msched_ctx *c) {
     if (c->cmd_ptrs_host) (void)hipHostFree((void *)c->cmd_ptrs_host);
     for (auto &e : c->ev) if (e) (void)hipEventDestroy(e);
     delete c;
-}
-
-// Nothing may be thrown across the C boundary: the few container operations inside can only fail for memory.
-template <class F> int guarded(F &&body) noexcept {
-    try { return body(); }
-    catch (const std::bad_alloc &) { return MSCHED_E_NOMEM; }
-    catch (...) { return MSCHED_E_INVAL; }
 }
 
 int env_u32(const char *name, uint32_t lo, uint32_t hi, uint32_t dflt) {
@@ -216,6 +253,7 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     c->early_chunk_shift = (uint32_t)env_u32("MSCHED_EARLY_CHUNK_SHIFT", 12, 24, 16);
     c->migrate_ticket = (uint32_t)env_u32("MSCHED_MIGRATE_TICKET", 0, 1, 0);
     c->paint = (uint32_t)env_u32("MSCHED_PAINT", 0, 1, 1);
+    c->resident_ranges = (uint32_t)env_u32("MSCHED_RESIDENT_RANGES", 0, 1, 1);
     c->migrate_max_blocks = (uint32_t)env_u32("MSCHED_MIGRATE_BLOCKS", 1, 1 << 20, 512);
     c->migrate_hints = (uint32_t)env_u32("MSCHED_MIGRATE_HINTS", 0, 3, 0);
     c->expand_split = (uint32_t)env_u32("MSCHED_EXPAND_SPLIT", 1, 64, 0);
@@ -380,17 +418,18 @@ int msched_launch_enqueue(msched_ctx *c, uint32_t task, uint32_t kernel_id, cons
                 memmove(t.recs, t.recs + off, live * sizeof(CmdRec));
                 auto front = [&](auto &v) { std::copy(v.begin() + off, v.begin() + off + live, v.begin()); };
                 front(t.lat); front(t.n_ids); front(t.list_back); front(t.range_end); front(t.prep); front(t.ids); front(t.flag);
+                std::copy(t.rule_back.begin() + off * MSCHED_MAX_RULES, t.rule_back.begin() + (off + live) * MSCHED_MAX_RULES, t.rule_back.begin());
             }
         } else {
             const size_t ncap = std::max<size_t>(256, live * 2);
             // the compact arrays first: if one of them cannot grow, nothing has changed yet
-            std::vector<uint32_t> lat, n_ids, list_back;
+            std::vector<uint32_t> lat, n_ids, list_back, rule_back;
             std::vector<uint64_t> range_end, prep;
             std::vector<const uint32_t *> ids;
             std::vector<uint8_t> flag;
             const int rc_room = guarded([&]() -> int {
                 lat.resize(ncap); n_ids.resize(ncap); list_back.resize(ncap); range_end.resize(ncap); prep.resize(ncap);
-                ids.resize(ncap); flag.resize(ncap);
+                ids.resize(ncap); flag.resize(ncap); rule_back.resize(ncap * MSCHED_MAX_RULES);
                 return MSCHED_OK;
             });
             if (rc_room) return rc_room;
@@ -407,13 +446,13 @@ int msched_launch_enqueue(msched_ctx *c, uint32_t task, uint32_t kernel_id, cons
                 std::copy_n(t.prep.begin() + off, live, prep.begin());
                 std::copy_n(t.ids.begin() + off, live, ids.begin());
                 std::copy_n(t.flag.begin() + off, live, flag.begin());
+                std::copy_n(t.rule_back.begin() + off * MSCHED_MAX_RULES, live * MSCHED_MAX_RULES, rule_back.begin());
             }
             if (t.recs) (void)hipHostFree(t.recs);
             t.recs = nr; t.recs_dev = nd; t.cap = ncap;
             t.lat.swap(lat); t.n_ids.swap(n_ids); t.list_back.swap(list_back); t.range_end.swap(range_end);
-            t.prep.swap(prep); t.ids.swap(ids); t.flag.swap(flag);
+            t.prep.swap(prep); t.ids.swap(ids); t.flag.swap(flag); t.rule_back.swap(rule_back);
         }
-        t.ranges.erase(t.ranges.begin(), t.ranges.begin() + (keep_from - t.ranges_base));
         t.ranges_base = keep_from;
         t.base = t.cursor;
     }
@@ -427,38 +466,45 @@ int msched_launch_enqueue(msched_ctx *c, uint32_t task, uint32_t kernel_id, cons
         // only walks the page ranges.  A rule's region is also looked up among the regions earlier commands of the
         // task described, so that plans can leave repeats out without looking anything up themselves.
         const DevKernel &k = c->kernels[kernel_id];
-        const size_t first = t.ranges.size();
+        const uint64_t first = t.rng_end;
         uint8_t flag = 0;
         uint32_t list_back = 0;
         struct Unwind {                              // a failure half-way must not leave ranges for the next command to inherit
-            std::vector<RangeRec> &v; size_t n; bool armed = true;
-            ~Unwind() { if (armed) v.resize(n); }
-        } unwind{t.ranges, first};
+            TaskQueue &t; uint64_t end; bool armed = true;
+            ~Unwind() { if (armed) t.rng_end = end; }
+        } unwind{t, first};
         if (t.last_region.size() > 4096 && t.last_region.size() > 2 * t.pruned_at) {
             // regions only retired commands described can no longer make anything a repeat
             for (auto it = t.last_region.begin(); it != t.last_region.end();)
                 it = it->second < t.cursor ? t.last_region.erase(it) : std::next(it);
             t.pruned_at = t.last_region.size();
         }
+        uint32_t *rule_back = &t.rule_back[li * MSCHED_MAX_RULES];
+        for (uint32_t q = 0; q < MSCHED_MAX_RULES; ++q) rule_back[q] = kRuleEmpty;
         for (uint32_t q = 0; q < k.n_rules; ++q) {
             RegionSig sig;
             bool empty;
             region_signature(c, k.rules[q], r, sig, empty);
             if (empty) continue;
             size_t &last = t.last_region.try_emplace(sig, (size_t)-1).first->second;
-            const uint32_t back = (last != (size_t)-1 && i - last < 0xFFFFFFFFull) ? (uint32_t)(i - last) : 0u;
+            const uint32_t back = (last != (size_t)-1 && i - last < 0xFFFFFFFEull) ? (uint32_t)(i - last) : 0u;
             last = i;
+            rule_back[q] = back;
             if (k.rules[q].kind == MSCHED_RULE_LIST) {
                 flag |= kCmdList;
                 list_back = back;
-            } else if (!(flag & kCmdNoPaint) && !append_ranges(c, k.rules[q], q, r, back, t.ranges, first, kMaxRanges)) {
-                flag |= kCmdNoPaint;               // too many chunks to keep: plans that hold this command expand it per page
-                t.ranges.resize(first);
+            } else if (!(flag & kCmdNoPaint)) {
+                const int rc_app = append_ranges(c, t, k.rules[q], r, i, back, first, kMaxRanges);
+                if (rc_app < 0) return rc_app;
+                if (rc_app == 1) {
+                    flag |= kCmdNoPaint;           // too many chunks to keep: plans that hold this command expand it per page
+                    t.rng_end = first;
+                }
             }
         }
         t.lat[li] = latency_ticks; t.n_ids[li] = n_ids; t.ids[li] = id_list; t.prep[li] = 0;
         t.flag[li] = flag; t.list_back[li] = list_back;
-        t.range_end[li] = t.ranges_base + t.ranges.size();
+        t.range_end[li] = t.rng_end;
         t.n++;
         unwind.armed = false;
         return MSCHED_OK;
@@ -583,22 +629,12 @@ namespace {
 // read whole records, want this; the mask rides in the top byte of the record's address (addresses use 48 bits).
 uint64_t skip_mask(const msched_ctx *c, const TaskQueue &t, size_t i) {
     const size_t li = i - t.base;
-    const DevKernel &k = c->kernels[t.recs[li].kernel];
-    if (t.flag[li] & kCmdNoPaint) {                            // nothing was kept of its ranges: every range rule is expanded
-        uint64_t skip = 0;
-        for (uint32_t r = 0; r < k.n_rules; ++r)
-            if (k.rules[r].kind == MSCHED_RULE_LIST &&
-                (!(t.flag[li] & kCmdList) || repeats_queued(c, t, i, t.list_back[li]))) skip |= 1ull << r;
-        return skip;
-    }
-    uint64_t live = 0;
-    for (uint64_t q = t.range_begin(i); q < t.range_end[li]; ++q) {
-        const RangeRec &rr = t.ranges[q - t.ranges_base];
-        if (!repeats_queued(c, t, i, rr.back)) live |= 1ull << rr.rule;
-    }
-    if ((t.flag[li] & kCmdList) && !repeats_queued(c, t, i, t.list_back[li]))
-        for (uint32_t r = 0; r < k.n_rules; ++r) if (k.rules[r].kind == MSCHED_RULE_LIST) live |= 1ull << r;
-    return ~live & ((1ull << k.n_rules) - 1);
+    const uint32_t n_rules = c->kernels[t.recs[li].kernel].n_rules;
+    const uint32_t *back = &t.rule_back[li * MSCHED_MAX_RULES];
+    uint64_t skip = 0;
+    for (uint32_t r = 0; r < n_rules; ++r)
+        if (back[r] == kRuleEmpty || repeats_queued(c, t, i, back[r])) skip |= 1ull << r;
+    return skip;
 }
 
 int plan_body(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entries, msched_plan_t *out) {
@@ -629,11 +665,8 @@ int plan_body(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entries
         if (p > first) c->runs.push_back(PlanRun{tl[e].task, g0, (uint32_t)(p - first), first});
         if (e == 0) g_end0 = G;
     }
-    // Range rules as a list of page ranges, copied from what msched_launch_enqueue worked out, with the command's
-    // position: the sweeps paint them into LDS tile by tile, and no per-page next use goes through memory.  Rules
-    // that repeat a region of a command queued in front of them are left out.  Id lists, and plans with more
-    // ranges than the list holds, scatter into nu[].
-    uint32_t n_ranges = 0;
+    // What the commands bring: id lists that are not repeats, and whether every command kept its page ranges
+    // (msched_launch_enqueue worked them out).  Plans with a command that did not scatter next uses per page.
     bool painted = c->paint != 0, live_list = false;
     uint64_t total_ids = 0;
     for (const PlanRun &run : c->runs) {
@@ -643,14 +676,6 @@ int plan_body(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entries
             const uint8_t flag = t.flag[li];
             if ((flag & kCmdList) && !repeats_queued(c, t, i, t.list_back[li])) { live_list = true; total_ids += t.n_ids[li]; }
             if (flag & kCmdNoPaint) painted = false;
-            if (!painted) continue;
-            const uint32_t g = run.g0 + j;
-            for (uint64_t q = t.range_begin(i), q1 = t.range_end[li]; q < q1; ++q) {
-                const RangeRec &rr = t.ranges[q - t.ranges_base];
-                if (repeats_queued(c, t, i, rr.back)) continue;
-                if (n_ranges == kMaxRanges) { painted = false; break; }
-                c->ranges_host[n_ranges++] = PageRange{rr.lo, rr.hi, g, 0};
-            }
         }
     }
     memset(out, 0, sizeof *out);
@@ -665,6 +690,48 @@ int plan_body(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entries
         PlanGeom g;
         plan_geometry(c, G, g);
         g.g_end0 = g_end0;
+        // Range rules reach the sweeps as page ranges with their command's position; the sweeps paint them into LDS
+        // tile by tile, and no per-page next use goes through memory.  Sweeps of many workgroups read the ranges
+        // where they already are - the tasks' mirrors in device memory, a slice per run, repeats left out by the
+        // reader - so that in steady state a plan sends nothing but its kernels' arguments.  Otherwise (one
+        // workgroup, many runs, switched off) the ranges are listed here, and copied over if many workgroups read
+        // them.  Plans with more ranges than the list holds scatter next uses into nu[], like id lists.
+        g.resident = false;
+        uint32_t n_ranges = 0;
+        if (painted && c->resident_ranges && !g.single && c->runs.size() <= std::min<size_t>(kMaxRangeRuns, g.waves)) {
+            RangeRuns &rr = c->range_runs;
+            uint64_t total = 0;
+            rr.n = 0;
+            for (const PlanRun &run : c->runs) {
+                TaskQueue &t = c->tasks[run.task];
+                const uint64_t q0 = t.range_begin(run.first), q1 = t.range_end[run.first + run.count - 1 - t.base];
+                if (q1 == q0) continue;
+                if (t.rng_uploaded < q1) { const int rc_up = upload_ranges(c, t); if (rc_up) return rc_up; }
+                total += q1 - q0;
+                if (total > kMaxResidentRanges) break;
+                rr.run[rr.n++] = RangeRun{t.rng_dev, (uint32_t)(t.rng_cap - 1), (uint32_t)q0, (uint32_t)(q1 - q0), (uint32_t)run.first,
+                                          run.g0, (uint32_t)t.cursor, c->dedupe_regions ? 1u : 0u, 0u};
+            }
+            if (total <= kMaxResidentRanges) {
+                g.resident = true;
+                n_ranges = (uint32_t)total;
+            }
+        }
+        if (painted && !g.resident) {
+            for (const PlanRun &run : c->runs) {
+                const TaskQueue &t = c->tasks[run.task];
+                for (uint32_t j = 0; j < run.count && painted; ++j) {
+                    const size_t i = run.first + j, li = i - t.base;
+                    const uint32_t gpos = run.g0 + j;
+                    for (uint64_t q = t.range_begin(i), q1 = t.range_end[li]; q < q1; ++q) {
+                        const RangeRec &rec = t.range_at(q);
+                        if (repeats_queued(c, t, i, rec.back)) continue;
+                        if (n_ranges == kMaxRanges) { painted = false; break; }
+                        c->ranges_host[n_ranges++] = PageRange{rec.lo, rec.hi, gpos, 0};
+                    }
+                }
+            }
+        }
         g.painted = painted;
         g.n_ranges = painted ? n_ranges : 0;
         g.use_nu = !painted || live_list;
@@ -853,7 +920,14 @@ int msched_migrate(msched_ctx *c, const msched_plan_t *plan) {
     c->n_resident += c->pending.n_free_used;
     c->pending_plan = 0;
     c->prepare_timed = 0;
-    return guarded([&]() -> int { prepare_ahead(c); return MSCHED_OK; });
+    const int rc_prep = guarded([&]() -> int { prepare_ahead(c); return MSCHED_OK; });
+    if (rc_prep) return rc_prep;
+    // Ranges of launches queued since the last migration go to the tasks' mirrors now, behind the copy, so that the
+    // next plans find them there.
+    if (c->resident_ranges)
+        for (TaskQueue &t : c->tasks)
+            if (t.rng_dev != nullptr) { const int rc_up = upload_ranges(c, t); if (rc_up) return rc_up; }
+    return MSCHED_OK;
 }
 
 int msched_set_early_start(msched_ctx *c, int enable) {

@@ -70,8 +70,10 @@ struct RegionSigHash {
 // evaluates the formulas with the launch arguments at launch time).  `back` is the distance, in commands of the
 // task, to the latest earlier command one of whose rules described the very same region (0: none): while that
 // command is still queued it comes first in every timeline, so this range cannot lower any page's first use and
-// a plan leaves it out.  All ranges of one rule share `back`; `rule` is the rule's index in its template.
-struct RangeRec { uint32_t lo, hi, back, rule; };
+// a plan leaves it out.  All ranges of one rule share `back`; `cmd` is the command's program-order index in its
+// task (low 32 bits: only differences between queued commands are ever taken).
+struct RangeRec { uint32_t lo, hi, back, cmd; };
+constexpr uint32_t kRuleEmpty = 0xFFFFFFFFu;
 constexpr uint8_t kCmdList = 1;                 // the command has a live id list (a LIST rule and at least one id)
 constexpr uint8_t kCmdNoPaint = 2;              // its ranges were too many to keep: plans that hold it scatter next uses per page
 
@@ -85,14 +87,22 @@ struct TaskQueue {
     // What a plan walks: compact arrays in ordinary host memory, entry i - base for command i.  Everything a plan
     // needs of a command was worked out when it was queued; the plan only reads, in order.
     std::vector<uint32_t> lat;                  // profiled latency
-    std::vector<uint64_t> range_end;            // the command's ranges are ranges[range_end[i - 1] - ranges_base, range_end[i] - ranges_base)
+    std::vector<uint64_t> range_end;            // the command's ranges have the running indices [range_end[i - 1], range_end[i])
     std::vector<uint32_t> n_ids;
     std::vector<const uint32_t *> ids;          // device pointer (caller-owned) or null
     std::vector<uint32_t> list_back;            // like RangeRec::back, for the id list (same address and length)
     std::vector<uint8_t> flag;                  // kCmdList, kCmdNoPaint
+    std::vector<uint32_t> rule_back;            // [MSCHED_MAX_RULES per command] like RangeRec::back, per rule; kRuleEmpty: the rule describes nothing
     std::vector<uint64_t> prep;                 // 1 + ring offset of the command's prepared id list (0 = none)
-    std::vector<RangeRec> ranges;
-    uint64_t ranges_base = 0;                   // running index of ranges[0]
+    // The commands' page ranges in program order: a ring in pinned host memory, the range with running index q at
+    // q & (rng_cap - 1), and a mirror of it in device memory that the sweeps of large tables read (brought up to
+    // date behind every migration, or by the plan that first needs a range).  Ranges of retired commands are dead.
+    RangeRec *rng = nullptr;                    // pinned host memory [rng_cap]
+    RangeRec *rng_dev = nullptr;                // device memory [rng_cap]
+    uint64_t rng_cap = 0;                       // a power of two
+    uint64_t rng_end = 0;                       // running index behind the last range
+    uint64_t rng_uploaded = 0;                  // ranges with a running index below this are in the mirror
+    uint64_t ranges_base = 0;                   // running index of the first range of command `base`
     std::unordered_map<RegionSig, size_t, RegionSigHash> last_region;   // region -> latest command that described it
     size_t pruned_at = 0;                       // size of last_region after its last clean-up
     // prepared id lists of this task's queued commands: a ring in device memory, filled in program order
@@ -100,6 +110,8 @@ struct TaskQueue {
     uint64_t prep_size = 0, prep_head = 0, prep_tail = 0;   // head / tail are running byte offsets (never wrap)
     size_t prep_scan = 0;                       // commands before this index have been looked at by the look-ahead preparation
     uint64_t range_begin(size_t i) const { return i == base ? ranges_base : range_end[i - base - 1]; }
+    uint64_t ranges_live_from() const { return cursor == n ? rng_end : range_begin(cursor); }   // the oldest range still needed
+    const RangeRec &range_at(uint64_t q) const { return rng[q & (rng_cap - 1)]; }
 };
 
 // A run of one timeline entry: commands [first, first + count) of `task` take the positions g0, g0 + 1, ...
@@ -108,6 +120,32 @@ struct TaskQueue {
 struct GateRec { uint32_t status, seen; uint64_t ticks; };
 
 struct PlanRun { uint32_t task, g0, count; size_t first; };
+
+// The ranges of a plan as the sweeps of large tables read them when nothing is staged: for each run of the flattened
+// timeline the slice of its task's range mirror, and what turns an entry into a range of this plan (the command's
+// position g = g0 + (cmd - cmd_first); a range that repeats a region of a command still queued - cmd - back at or
+// behind the task's cursor - is left out).  Wavefront w of a sweep workgroup serves run w mod n for the whole
+// launch, so it reads the run's description once, into scalar registers, and an entry then costs one load at an
+// address worked out by arithmetic alone (anything looked up per entry - a run table in LDS or in the argument
+// buffer - was measured at 0.5 us and more per row of 64 entries, several times the cost of the range test itself).
+// The table travels in the launch's arguments; plans with more runs than a workgroup has wavefronts list their
+// ranges on the host instead.
+constexpr uint32_t kMaxRangeRuns = 16;
+constexpr uint32_t kRangeRow = 64;
+struct RangeRun {
+    const RangeRec *ring;
+    uint32_t mask, first;          // entry k of the run is ring[(first + k) & mask]
+    uint32_t count;                // entries
+    uint32_t cmd_first, g0, cursor;
+    uint32_t dedupe, pad;
+};
+struct RangeRuns {
+    uint32_t n;
+    uint32_t passes;               // passes of kRangesPerThread rows per wavefront that cover the longest run (set at launch)
+    uint32_t pad[2];
+    RangeRun run[kMaxRangeRuns];
+};
+constexpr uint32_t kRangesPerThread = 4;    // ranges a thread tests per pass over a plan's ranges
 
 // One source of the id-list merge: a prepared (de-duplicated, grouped by bucket) piece of a command's list.
 // A piece is prepared in `split` parts (prep_split), each by a workgroup of its own, part q taking the buckets
@@ -138,6 +176,7 @@ constexpr uint32_t kPrepBlock = 24576;          // ids per prepared piece (24 pe
 // rule, describes once its formulas are evaluated.
 struct PageRange { uint32_t lo, hi, g, pad; };
 constexpr uint32_t kMaxRanges = 4096;           // more ranges than this in one plan: next use is scattered per page instead
+constexpr uint32_t kMaxResidentRanges = 4 * kMaxRanges;   // ... read from the mirrors, where repeats count until the reader drops them
 
 struct PlanGeom {
     uint32_t G, g_end0, n_chunks, chunk_pages, n_keys;   // n_keys = 2 * (G + 1)
@@ -151,6 +190,7 @@ struct PlanGeom {
     bool live_list;                                      // some command of the plan brings an id list that is not a repeat
     bool needs_records;                                  // some kernel of the plan reads whole command records (table of record addresses filled)
     bool painted;                                        // range rules arrive as a range list the sweeps paint into LDS
+    bool resident;                                       // ... which the sweeps read from the tasks' range mirrors (nothing staged)
     bool use_nu;                                         // some next uses are in nu[] (id lists, or the scatter path)
     uint32_t n_ranges;
 };
@@ -174,6 +214,7 @@ struct msched_ctx {
     uint32_t stage_threshold = 2048;            // expansion workgroups above which records are staged first
     bool dedupe_regions = true;                 // leave out rules that repeat a region an earlier queued command of the task describes
     std::vector<msched::PlanRun> runs;          // the flattened timeline of the plan being made, one run per entry
+    msched::RangeRuns range_runs{};             // the same runs as slices of the tasks' range mirrors (plans that stage nothing)
     std::vector<size_t> pos;                    // per task: next command the flattening takes
     struct Reserved { uint32_t task; size_t cmd; uint64_t head; };
     std::vector<Reserved> reserved;             // ring blocks this plan handed out for id lists it prepares itself (undone if it fails)
@@ -229,6 +270,7 @@ struct msched_ctx {
     msched::PageRange *ranges_dev = nullptr;    // device copy for sweeps of many workgroups
     uint16_t *key16 = nullptr;                  // device [V]: class key of every page (first sweep -> second sweep)
     uint32_t paint = 1;                         // 0: always scatter next uses per page (MSCHED_PAINT)
+    uint32_t resident_ranges = 1;               // 0: every plan copies its range list to the device (MSCHED_RESIDENT_RANGES)
     int early = 0;                              // msched_set_early_start
     uint32_t *need_host = nullptr;              // pinned [MAX_G + 1]: need[g] of the latest plan (written by the cut kernel)
     uint32_t *page_done = nullptr;              // device [F]: tag of the migration that completed fetch entry i

@@ -694,6 +694,7 @@ struct SweepGeom {
     // next uses that come from range rules: a list of page ranges painted into LDS tile by tile
     const PageRange *ranges;
     uint32_t n_ranges;        // 0: nothing to paint
+    uint32_t range_runs;      // 1: the ranges are entries of the tasks' mirrors, taken run by run (`ranges` unused)
     uint32_t use_nu;          // 0: nu[] holds nothing for this plan and is not read
     const uint32_t *bucket_mark;   // non-null: nu[] holds something of this plan only in buckets marked here (all its
                                    // id lists came through prepared pieces); the sweep skips nu[] elsewhere
@@ -710,8 +711,8 @@ constexpr uint16_t kNoKey16 = 0xffff;                  // keys are below 2 * (MS
 // Painting.  A tile's next uses from range rules = for every page the smallest g among the ranges that
 // cover it.  Each workgroup scans the plan's range list (a few KB, L2-resident), and
 //   * a range that covers the whole tile only lowers one word, the tile's floor;
-//   * a range that covers part of it is queued and painted with LDS atomic minima, by all threads
-//     together when it is long, by one thread when it is a few pages.
+//   * a range that covers part of it is painted with LDS atomic minima: a few pages at once by the thread that
+//     tested it, many pages queued and painted by all threads together.
 // Nothing per page goes through memory: that is what the scatter path (k_expand) spends its time on.
 // ------------------------------------------------------------------------------------------
 // Where the painted tile starts in the first sweep's LDS: behind the histogram, on a 16-byte boundary.
@@ -725,43 +726,109 @@ struct PaintLds {
     uint32_t lo[kPaintQueue], hi[kPaintQueue], g[kPaintQueue];
 };
 
-__device__ void paint_tile(const SweepGeom &sg, uint64_t t0, uint64_t t1, uint32_t *paint, PaintLds &q) {
+// The plan's ranges are tested in passes of kRangesPerThread per thread.  They come from the plan's own list; or,
+// when the plan brought none (sg.range_runs), from the tasks' range mirrors: a wavefront serves one run of the
+// timeline for the whole launch and takes rows of 64 of its entries, a lane working out its entry's position in the
+// plan.  A range that repeats a region of a command still queued in front of its own is left out.
+struct WaveRun {                      // what a wavefront knows of its run (the same in all lanes)
+    const RangeRec *ring;
+    uint32_t mask, first, count, cmd_first, g0, cursor, dedupe;
+    uint32_t rank, waves;             // this wavefront among the `waves` that share the run
+    uint32_t passes;
+};
+__device__ __forceinline__ WaveRun wave_run(const SweepGeom &sg, const RangeRuns *runs) {
+    WaveRun w{};
+    if (!sg.range_runs) return w;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave)), waves = blockDim.x / kWave;
+    const uint32_t n = runs->n, j = wave % n;                 // n <= waves: every run has a wavefront
+    const RangeRun &run = runs->run[j];
+    // (said to be the same in all lanes once more, so that they live in scalar registers for the rest of the kernel)
+    auto same = [](uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); };
+    const uint64_t ring = reinterpret_cast<uint64_t>(run.ring);
+    w.ring = reinterpret_cast<const RangeRec *>((uint64_t)same((uint32_t)ring) | (uint64_t)same((uint32_t)(ring >> 32)) << 32);
+    w.mask = same(run.mask); w.first = same(run.first); w.count = same(run.count); w.cmd_first = same(run.cmd_first);
+    w.g0 = same(run.g0); w.cursor = same(run.cursor); w.dedupe = same(run.dedupe);
+    w.rank = same(wave / n); w.waves = same((waves - j + n - 1) / n);
+    w.passes = same(runs->passes);
+    return w;
+}
+__device__ __forceinline__ uint32_t range_passes(const SweepGeom &sg, const WaveRun &w) {
+    if (!sg.range_runs) return (sg.n_ranges + blockDim.x * kRangesPerThread - 1) / (blockDim.x * kRangesPerThread);
+    return w.passes;
+}
+// This thread's ranges u0 .. u0 + kRangesInFlight - 1 (of kRangesPerThread) of pass `pass`: R[i] with live[i] set.
+// Their loads are asked for together (more at a time cost the sweeps a workgroup per compute unit in registers).
+constexpr uint32_t kRangesInFlight = 2;
+static_assert(kRangesPerThread % kRangesInFlight == 0, "whole batches");
+__device__ __forceinline__ void pass_ranges(const SweepGeom &sg, const WaveRun &w, uint32_t pass, uint32_t u0,
+                                            PageRange (&R)[kRangesInFlight], bool (&live)[kRangesInFlight]) {
+    uint4 v[kRangesInFlight];
+    if (!sg.range_runs) {
+#pragma unroll
+        for (uint32_t u = 0; u < kRangesInFlight; ++u) {
+            const uint32_t r = (pass * kRangesPerThread + u0 + u) * blockDim.x + threadIdx.x;
+            live[u] = r < sg.n_ranges;
+            v[u] = live[u] ? reinterpret_cast<const uint4 *>(sg.ranges)[r] : uint4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < kRangesInFlight; ++u) { R[u].lo = v[u].x; R[u].hi = v[u].y; R[u].g = v[u].z; R[u].pad = 0; }   // PageRange {lo, hi, g, pad}
+        return;
+    }
+#pragma unroll
+    for (uint32_t u = 0; u < kRangesInFlight; ++u) {
+        const uint32_t k = ((pass * kRangesPerThread + u0 + u) * w.waves + w.rank) * kRangeRow + (uint32_t)lane_id();
+        live[u] = k < w.count;
+        v[u] = live[u] ? reinterpret_cast<const uint4 *>(w.ring)[(w.first + k) & w.mask] : uint4{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (uint32_t u = 0; u < kRangesInFlight; ++u) {                             // RangeRec {lo, hi, back, cmd}
+        R[u].lo = v[u].x; R[u].hi = v[u].y; R[u].pad = 0;
+        R[u].g = w.g0 + (v[u].w - w.cmd_first);
+        if (w.dedupe && v[u].z != 0 && (int32_t)(v[u].w - v[u].z - w.cursor) >= 0) live[u] = false;
+    }
+}
+static_assert(kRangeRow == (uint32_t)kWave, "a row of range entries is read by one wavefront");
+static_assert(sizeof(PageRange) == 16 && sizeof(RangeRec) == 16, "ranges are read as one 16-byte word");
+static_assert(kRangeRow == (uint32_t)kWave, "a row of range entries is read by one wavefront");
+
+__device__ __forceinline__ void paint_tile(const SweepGeom &sg, const WaveRun &runs, uint64_t t0, uint64_t t1, uint32_t *paint, PaintLds &q) {
     const uint32_t n = (t1 > t0) ? (uint32_t)(t1 - t0) : 0;
     for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) paint[i] = sg.G;
     if (threadIdx.x == 0) { q.n_queued = 0; q.floor = sg.G; }
     __syncthreads();
-    constexpr uint32_t kPerThread = 4;                        // ranges a thread tests per pass (a pass costs three barriers)
-    for (uint32_t r0 = 0; r0 < sg.n_ranges; r0 += blockDim.x * kPerThread) {
+    const uint32_t passes = range_passes(sg, runs);           // a thread tests kRangesPerThread ranges per pass (a pass costs three barriers)
+    for (uint32_t pass = 0; pass < passes; ++pass) {
 #pragma unroll
-        for (uint32_t j = 0; j < kPerThread; ++j) {
-            const uint32_t r = r0 + j * blockDim.x + threadIdx.x;
-            if (r >= sg.n_ranges) continue;
-            const PageRange R = sg.ranges[r];
+        for (uint32_t u0 = 0; u0 < kRangesPerThread; u0 += kRangesInFlight) {
+        PageRange Rs[kRangesInFlight];
+        bool live[kRangesInFlight];
+        pass_ranges(sg, runs, pass, u0, Rs, live);
+#pragma unroll
+        for (uint32_t j = 0; j < kRangesInFlight; ++j) {
+            if (!live[j]) continue;
+            const PageRange R = Rs[j];
             const uint64_t lo = max((uint64_t)R.lo, t0), hi = min((uint64_t)R.hi, t1);
             if (lo < hi) {
                 if (lo == t0 && hi == t1) {
                     atomicMin(&q.floor, R.g);
-                } else {
+                } else if (hi - lo <= kPaintSerial) {         // a few pages: painted here and now, by the thread that found them
+                    for (uint32_t i = (uint32_t)(lo - t0); i < (uint32_t)(hi - t0); ++i) atomicMin(&paint[i], R.g);
+                } else {                                      // many pages: queued for all threads together
                     const uint32_t at = atomicAdd(&q.n_queued, 1u);
                     if (at < kPaintQueue) {
                         q.lo[at] = (uint32_t)(lo - t0); q.hi[at] = (uint32_t)(hi - t0); q.g[at] = R.g;
-                    } else {                                  // queue full (many small ranges in one tile): paint it here
+                    } else {                                  // queue full: paint it here after all
                         for (uint32_t i = (uint32_t)(lo - t0); i < (uint32_t)(hi - t0); ++i) atomicMin(&paint[i], R.g);
                     }
                 }
             }
         }
+        }
         __syncthreads();
         const uint32_t nq = min(q.n_queued, kPaintQueue);
         for (uint32_t w = 0; w < nq; ++w) {
             const uint32_t lo = q.lo[w], hi = q.hi[w];
-            if (hi - lo > kPaintSerial)
-                for (uint32_t i = lo + threadIdx.x; i < hi; i += blockDim.x) atomicMin(&paint[i], q.g[w]);
-        }
-        if (threadIdx.x < nq) {
-            const uint32_t lo = q.lo[threadIdx.x], hi = q.hi[threadIdx.x];
-            if (hi - lo <= kPaintSerial)
-                for (uint32_t i = lo; i < hi; ++i) atomicMin(&paint[i], q.g[threadIdx.x]);
+            for (uint32_t i = lo + threadIdx.x; i < hi; i += blockDim.x) atomicMin(&paint[i], q.g[w]);
         }
         __syncthreads();
         if (threadIdx.x == 0) q.n_queued = 0;
@@ -780,14 +847,18 @@ __device__ void paint_tile(const SweepGeom &sg, uint64_t t0, uint64_t t1, uint32
 #endif
 constexpr uint32_t kPaintInRegisters = MSCHED_PAINT_IN_REGISTERS;
 // The queue is empty on entry (count_body resets it ahead of a barrier it needs anyway).
-__device__ uint32_t queue_ranges(const SweepGeom &sg, uint64_t t0, uint64_t t1, PaintLds &q) {
-    constexpr uint32_t kPerThread = 4;
-    for (uint32_t r0 = 0; r0 < sg.n_ranges; r0 += blockDim.x * kPerThread) {
+__device__ __forceinline__ uint32_t queue_ranges(const SweepGeom &sg, const WaveRun &runs, uint64_t t0, uint64_t t1, PaintLds &q) {
+    const uint32_t passes = range_passes(sg, runs);
+    for (uint32_t pass = 0; pass < passes; ++pass) {
 #pragma unroll
-        for (uint32_t j = 0; j < kPerThread; ++j) {
-            const uint32_t r = r0 + j * blockDim.x + threadIdx.x;
-            if (r >= sg.n_ranges) continue;
-            const PageRange R = sg.ranges[r];
+        for (uint32_t u0 = 0; u0 < kRangesPerThread; u0 += kRangesInFlight) {
+        PageRange Rs[kRangesInFlight];
+        bool live[kRangesInFlight];
+        pass_ranges(sg, runs, pass, u0, Rs, live);
+#pragma unroll
+        for (uint32_t j = 0; j < kRangesInFlight; ++j) {
+            if (!live[j]) continue;
+            const PageRange R = Rs[j];
             const uint64_t lo = max((uint64_t)R.lo, t0), hi = min((uint64_t)R.hi, t1);
             if (lo < hi) {
                 if (lo == t0 && hi == t1) {
@@ -797,6 +868,7 @@ __device__ uint32_t queue_ranges(const SweepGeom &sg, uint64_t t0, uint64_t t1, 
                     if (at < kPaintInRegisters) { q.lo[at] = (uint32_t)(lo - t0); q.hi[at] = (uint32_t)(hi - t0); q.g[at] = R.g; }
                 }
             }
+        }
         }
     }
     __syncthreads();
@@ -902,11 +974,15 @@ constexpr uint32_t kStagePieces = 512;   // segments of a bucket described in LD
 template <bool kLists>
 __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_table, const uint32_t *__restrict__ nu,
                                            const SweepGeom &sg, uint32_t chunk, uint32_t *lds, uint32_t *row,
-                                           uint32_t *group_row, uint32_t *slice_row, const TileLists *tl = nullptr) {
+                                           uint32_t *group_row, uint32_t *slice_row, const TileLists *tl = nullptr,
+                                           const RangeRuns *range_runs = nullptr) {
     const uint32_t n_keys = 2 * (sg.G + 1);
     const uint32_t waves = blockDim.x / kWave, wave = threadIdx.x / kWave;
     __shared__ PaintLds s_paint;
     MSCHED_TICK(kTickCount, 0);
+    // asked for first, so that it is there when the tile's ranges are tested; read again behind every tile's sweep
+    // (kept across that loop it would cost it a dozen registers)
+    WaveRun runs = wave_run(sg, range_runs);
     for (uint32_t i = threadIdx.x; i < n_keys; i += blockDim.x) lds[i] = 0;
     if (threadIdx.x == 0) { s_paint.n_queued = 0; s_paint.floor = sg.G; }     // queue_ranges expects it empty
     if (threadIdx.x == 0 && sg.emit_hint != nullptr) sg.emit_hint[chunk] = 0;   // raised below, behind barriers
@@ -992,9 +1068,9 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
         // ranges of a tile without id lists: queued and applied from registers when they are few
         auto paint_ranges = [&]() -> int {
             if (!sg.n_ranges) return kPaintNone;
-            if (queue_ranges(sg, tile_begin, tile_end, s_paint) <= kPaintInRegisters) return kPaintQueued;
+            if (queue_ranges(sg, runs, tile_begin, tile_end, s_paint) <= kPaintInRegisters) return kPaintQueued;
             __syncthreads();                                  // everybody has read the count
-            paint_tile(sg, tile_begin, tile_end, paint, s_paint);
+            paint_tile(sg, runs, tile_begin, tile_end, paint, s_paint);
             return kPaintLds;
         };
         if (kLists) {
@@ -1012,7 +1088,7 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
                     sweep_tile(how, false);
                     MSCHED_TICK(kTickCount, 5);
                 } else {
-                    paint_tile(sg, tile_begin, tile_end, paint, s_paint);
+                    paint_tile(sg, runs, tile_begin, tile_end, paint, s_paint);
                     MSCHED_TICK(kTickCount, 2);
                     const uint32_t **first = reinterpret_cast<const uint32_t **>(paint + tile_pages);   // [kStagePieces]
                     uint32_t *len = reinterpret_cast<uint32_t *>(first + kStagePieces);
@@ -1053,6 +1129,7 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
             MSCHED_TICK(kTickCount, 5);
         }
         if (round + 1 < sg.rounds && (sg.n_ranges || kLists)) {
+            runs = wave_run(sg, range_runs);
             __syncthreads();                              // the next tile repaints, and queues its ranges afresh
             if (threadIdx.x == 0) { s_paint.n_queued = 0; s_paint.floor = sg.G; }
             __syncthreads();
@@ -1096,12 +1173,12 @@ __device__ __forceinline__ void sum_rows(uint32_t *partial, uint32_t chunk, uint
 __global__ __launch_bounds__(kWave * kMaxWaves) void k_count(const uint32_t *__restrict__ page_table,
                                                               const uint32_t *__restrict__ nu, SweepGeom sg,
                                                               uint32_t *__restrict__ matrix,
-                                                              uint32_t *__restrict__ partial) {
+                                                              uint32_t *__restrict__ partial, const RangeRuns rr) {
     extern __shared__ uint32_t lds[];
     const uint32_t chunk = chunk_of_block(blockIdx.x, gridDim.x), n_keys = 2 * (sg.G + 1);
     uint32_t *group_row, *slice_row;
     sum_rows(partial, chunk, gridDim.x, n_keys, group_row, slice_row);
-    count_body<false>(page_table, nu, sg, chunk, lds, matrix + (size_t)chunk * n_keys, group_row, slice_row);
+    count_body<false>(page_table, nu, sg, chunk, lds, matrix + (size_t)chunk * n_keys, group_row, slice_row, nullptr, &rr);
 }
 
 // The first sweep with the id lists merged in (see count_body).  With 44 KiB of LDS a compute unit holds three
@@ -1117,12 +1194,12 @@ constexpr int kFusedThreads = kWave * kMaxWaves;
 #endif
 __global__ __launch_bounds__(kFusedThreads, MSCHED_FUSED_MIN_WAVES) void k_count_lists(const uint32_t *__restrict__ page_table, SweepGeom sg,
                                                               TileLists tl, uint32_t *__restrict__ matrix,
-                                                              uint32_t *__restrict__ partial) {
+                                                              uint32_t *__restrict__ partial, const RangeRuns rr) {
     extern __shared__ uint32_t lds[];
     const uint32_t chunk = tl.order[blockIdx.x], n_keys = 2 * (sg.G + 1);
     uint32_t *group_row, *slice_row;
     sum_rows(partial, chunk, gridDim.x, n_keys, group_row, slice_row);
-    count_body<true>(page_table, nullptr, sg, chunk, lds, matrix + (size_t)chunk * n_keys, group_row, slice_row, &tl);
+    count_body<true>(page_table, nullptr, sg, chunk, lds, matrix + (size_t)chunk * n_keys, group_row, slice_row, &tl, &rr);
 }
 
 // In-place exclusive scan of a[0..n) in LDS by the whole block (a multiple of 64 threads, at most
@@ -1537,7 +1614,11 @@ constexpr uint32_t kInlineRanges = 160;
 struct InlineRanges { PageRange r[kInlineRanges]; };
 __global__ __launch_bounds__(kWave * kMaxWaves) void k_tail(SweepGeom sg, CutArgs ca, EmitArgs ea, const InlineRanges inl) {
     extern __shared__ uint32_t lds[];
-    if (sg.ranges == nullptr) sg.ranges = inl.r;
+    __shared__ PageRange s_inl[kInlineRanges];
+    if (sg.ranges == nullptr) {                           // the ranges came with the arguments: into LDS (count_body's first barrier comes before their use)
+        for (uint32_t i = threadIdx.x; i < sg.n_ranges; i += blockDim.x) s_inl[i] = inl.r[i];
+        sg.ranges = s_inl;
+    }
     count_body<false>(ea.page_table, ea.nu, sg, 0, lds, ca.groups, nullptr, nullptr);
     __syncthreads();
     ca.counts_in_lds = 1;                                 // the only chunk's counts are where the sweep left them
@@ -1645,7 +1726,7 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
                                    ((uint64_t)g.G * c->max_rules * a.n_split > c->stage_threshold || g.live_list);
         const bool stage = stage_records || g.list_prepared || g.list_binned;
         a.cmds = stage_records ? c->cmd_dev : nullptr;
-        const bool copy_ranges = g.n_ranges && !g.single;
+        const bool copy_ranges = g.n_ranges && !g.single && !g.resident;   // resident: the sweep reads the tasks' mirrors
         const uint32_t n_records = stage_records ? g.G : 0u;
         ChunkOrder co{nullptr, 0, 0, 0, 0, nullptr};
         if (fuse_lists) co = ChunkOrder{c->bucket_mark, g.n_buckets, g.n_chunks, g.rounds, 1, c->bucket_mark + kMaxBuckets};
@@ -1691,8 +1772,21 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     // the second sweep's order: only where the cut kernel has its wide part to carry the extra workgroup
     const bool order_emit = c->order_emit && !g.single && g.n_chunks > kRowGroups;
     sg.g_end0 = g.g_end0; sg.emit_hint = order_emit ? c->chunk_hint : nullptr;
-    // one workgroup reads the range list where the host wrote it; many read a device copy
-    sg.ranges = g.single ? c->ranges_host_dev : c->ranges_dev;
+    // one workgroup reads the range list where the host wrote it; many read a device copy, or the tasks' mirrors
+    sg.ranges = g.single ? c->ranges_host_dev : g.resident ? nullptr : c->ranges_dev;
+    sg.range_runs = g.resident && g.n_ranges ? 1u : 0u;
+    RangeRuns no_runs;
+    no_runs.n = no_runs.passes = 0;
+    if (sg.range_runs) {                                     // passes that cover the longest run with the wavefronts it gets
+        RangeRuns &r = c->range_runs;
+        const uint32_t W = fuse_lists ? (uint32_t)kFusedThreads / kWave : g.waves;
+        r.passes = 0;
+        for (uint32_t j = 0; j < r.n; ++j) {
+            const uint32_t waves_j = (W - j + r.n - 1) / r.n, rows = (r.run[j].count + kRangeRow - 1) / kRangeRow;
+            r.passes = std::max(r.passes, (rows + kRangesPerThread * waves_j - 1) / (kRangesPerThread * waves_j));
+        }
+    }
+    const RangeRuns &rr = sg.range_runs ? c->range_runs : no_runs;
     if (prof) CK(hipEventRecord(c->ev[1], st));
     const uint32_t threads = g.waves * kWave;
     const size_t paint_lds = g.n_ranges ? (size_t)g.waves * g.steps * kWave * 4 : 0;
@@ -1729,10 +1823,10 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         tl.src = c->list_src_stage; tl.n_src = g.n_list_sources; tl.n_buckets = g.n_buckets; tl.split = g.split; tl.bucket_mark = c->bucket_mark;
         tl.order = c->bucket_mark + kMaxBuckets;
         const size_t lds = ((size_t)count_paint_offset(g.n_keys) + kBucketPages) * 4 + (size_t)kStagePieces * 16;
-        k_count_lists<<<g.n_chunks, kFusedThreads, lds, st>>>(c->page_table, sc, tl, c->matrix, few_rows ? nullptr : c->partial);
+        k_count_lists<<<g.n_chunks, kFusedThreads, lds, st>>>(c->page_table, sc, tl, c->matrix, few_rows ? nullptr : c->partial, rr);
     } else {
         k_count<<<g.n_chunks, threads, (size_t)count_paint_offset(g.n_keys) * 4 + paint_lds, st>>>(c->page_table, c->nu, sg, c->matrix,
-                                                                    few_rows ? nullptr : c->partial);
+                                                                    few_rows ? nullptr : c->partial, rr);
     }
     if (prof) CK(hipEventRecord(c->ev[2], st));
     const uint32_t cut_threads = std::min<uint32_t>(1024, std::max<uint32_t>(256, (g.n_keys + 63) / 64 * 64));   // a key per thread
