@@ -106,6 +106,25 @@ inline void region_signature(const msched_ctx *c, const msched_rule &q, const Cm
     sig = {base, size, stride, count ^ (3ull << 62)};
 }
 
+constexpr size_t kMirrorArenaBytes = 4u << 20;
+hipError_t mirror_alloc(msched_ctx *c, size_t bytes, void **out) {
+    if (!c->mirror_arena) {
+        if (hipMalloc((void **)&c->mirror_arena, kMirrorArenaBytes) != hipSuccess) { (void)hipGetLastError(); c->mirror_arena = nullptr; }
+        c->mirror_arena_used = 0;
+    }
+    const size_t at = (c->mirror_arena_used + 255) & ~(size_t)255;
+    if (c->mirror_arena && at + bytes <= kMirrorArenaBytes) {
+        *out = c->mirror_arena + at;
+        c->mirror_arena_used = at + bytes;
+        return hipSuccess;
+    }
+    return hipMalloc(out, bytes);
+}
+void mirror_free(msched_ctx *c, void *p) {                   // pieces of the arena are given up with the arena
+    const uint8_t *q = static_cast<const uint8_t *>(p);
+    if (p && !(c->mirror_arena && q >= c->mirror_arena && q < c->mirror_arena + kMirrorArenaBytes)) (void)hipFree(p);
+}
+
 // Room for `count` more ranges in a task's ring: ranges of retired commands are dead, and when the live ones fill
 // it, a ring of twice the size takes over (pinned memory and its mirror: rare, so the stream is drained first - a
 // sweep of a plan whose second half still runs may be reading the mirror).
@@ -118,11 +137,11 @@ int range_room(msched_ctx *c, TaskQueue &t, uint64_t count) {
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     RangeRec *nh = nullptr, *nd = nullptr;
     HIP_TRY(c, hipHostMalloc((void **)&nh, ncap * sizeof(RangeRec), hipHostMallocDefault));
-    const hipError_t e = hipMalloc((void **)&nd, ncap * sizeof(RangeRec));
+    const hipError_t e = mirror_alloc(c, ncap * sizeof(RangeRec), (void **)&nd);
     if (e != hipSuccess) { (void)hipHostFree(nh); HIP_TRY(c, e); }
     for (uint64_t q = live_from; q < t.rng_end; ++q) nh[q & (ncap - 1)] = t.rng[q & (t.rng_cap - 1)];
     if (t.rng) (void)hipHostFree(t.rng);
-    if (t.rng_dev) (void)hipFree(t.rng_dev);
+    mirror_free(c, t.rng_dev);
     t.rng = nh; t.rng_dev = nd; t.rng_cap = ncap;
     t.rng_uploaded = live_from;                  // the new mirror holds nothing yet
     return MSCHED_OK;
@@ -180,7 +199,9 @@ void free_ctx(msched_ctx *c) {
     (void)hipStreamSynchronize(c->stream);
     for (auto &t : c->tasks) if (t.recs) (void)hipHostFree(t.recs);
     for (auto &t : c->tasks) if (t.prep_buf) (void)hipFree(t.prep_buf);
-    for (auto &t : c->tasks) { if (t.rng) (void)hipHostFree(t.rng); if (t.rng_dev) (void)hipFree(t.rng_dev); }
+    for (auto &t : c->tasks) { if (t.rng) (void)hipHostFree(t.rng); mirror_free(c, t.rng_dev); }
+    for (auto &t : c->tasks) { if (t.lst) (void)hipHostFree(t.lst); mirror_free(c, t.lst_dev); }
+    if (c->mirror_arena) (void)hipFree(c->mirror_arena);
     if (c->list_src_host) (void)hipHostFree(c->list_src_host);
     if (c->list_prep_host) (void)hipHostFree(c->list_prep_host);
     if (c->list_src_stage) (void)hipFree(c->list_src_stage);
@@ -254,6 +275,7 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     c->migrate_ticket = (uint32_t)env_u32("MSCHED_MIGRATE_TICKET", 0, 1, 0);
     c->paint = (uint32_t)env_u32("MSCHED_PAINT", 0, 1, 1);
     c->resident_ranges = (uint32_t)env_u32("MSCHED_RESIDENT_RANGES", 0, 1, 1);
+    c->resident_lists = (uint32_t)env_u32("MSCHED_RESIDENT_LISTS", 0, 1, 0);
     c->migrate_max_blocks = (uint32_t)env_u32("MSCHED_MIGRATE_BLOCKS", 1, 1 << 20, 512);
     c->migrate_hints = (uint32_t)env_u32("MSCHED_MIGRATE_HINTS", 0, 3, 0);
     c->expand_split = (uint32_t)env_u32("MSCHED_EXPAND_SPLIT", 1, 64, 0);
@@ -417,19 +439,19 @@ int msched_launch_enqueue(msched_ctx *c, uint32_t task, uint32_t kernel_id, cons
             if (live && off) {
                 memmove(t.recs, t.recs + off, live * sizeof(CmdRec));
                 auto front = [&](auto &v) { std::copy(v.begin() + off, v.begin() + off + live, v.begin()); };
-                front(t.lat); front(t.n_ids); front(t.list_back); front(t.range_end); front(t.prep); front(t.ids); front(t.flag);
+                front(t.lat); front(t.n_ids); front(t.list_back); front(t.range_end); front(t.prep); front(t.ids); front(t.flag); front(t.lq);
                 std::copy(t.rule_back.begin() + off * MSCHED_MAX_RULES, t.rule_back.begin() + (off + live) * MSCHED_MAX_RULES, t.rule_back.begin());
             }
         } else {
             const size_t ncap = std::max<size_t>(256, live * 2);
             // the compact arrays first: if one of them cannot grow, nothing has changed yet
             std::vector<uint32_t> lat, n_ids, list_back, rule_back;
-            std::vector<uint64_t> range_end, prep;
+            std::vector<uint64_t> range_end, prep, lq;
             std::vector<const uint32_t *> ids;
             std::vector<uint8_t> flag;
             const int rc_room = guarded([&]() -> int {
                 lat.resize(ncap); n_ids.resize(ncap); list_back.resize(ncap); range_end.resize(ncap); prep.resize(ncap);
-                ids.resize(ncap); flag.resize(ncap); rule_back.resize(ncap * MSCHED_MAX_RULES);
+                ids.resize(ncap); flag.resize(ncap); rule_back.resize(ncap * MSCHED_MAX_RULES); lq.resize(ncap);
                 return MSCHED_OK;
             });
             if (rc_room) return rc_room;
@@ -444,6 +466,7 @@ int msched_launch_enqueue(msched_ctx *c, uint32_t task, uint32_t kernel_id, cons
                 std::copy_n(t.list_back.begin() + off, live, list_back.begin());
                 std::copy_n(t.range_end.begin() + off, live, range_end.begin());
                 std::copy_n(t.prep.begin() + off, live, prep.begin());
+                std::copy_n(t.lq.begin() + off, live, lq.begin());
                 std::copy_n(t.ids.begin() + off, live, ids.begin());
                 std::copy_n(t.flag.begin() + off, live, flag.begin());
                 std::copy_n(t.rule_back.begin() + off * MSCHED_MAX_RULES, live * MSCHED_MAX_RULES, rule_back.begin());
@@ -451,7 +474,7 @@ int msched_launch_enqueue(msched_ctx *c, uint32_t task, uint32_t kernel_id, cons
             if (t.recs) (void)hipHostFree(t.recs);
             t.recs = nr; t.recs_dev = nd; t.cap = ncap;
             t.lat.swap(lat); t.n_ids.swap(n_ids); t.list_back.swap(list_back); t.range_end.swap(range_end);
-            t.prep.swap(prep); t.ids.swap(ids); t.flag.swap(flag); t.rule_back.swap(rule_back);
+            t.prep.swap(prep); t.ids.swap(ids); t.flag.swap(flag); t.rule_back.swap(rule_back); t.lq.swap(lq);
         }
         t.ranges_base = keep_from;
         t.base = t.cursor;
@@ -502,7 +525,7 @@ int msched_launch_enqueue(msched_ctx *c, uint32_t task, uint32_t kernel_id, cons
                 }
             }
         }
-        t.lat[li] = latency_ticks; t.n_ids[li] = n_ids; t.ids[li] = id_list; t.prep[li] = 0;
+        t.lat[li] = latency_ticks; t.n_ids[li] = n_ids; t.ids[li] = id_list; t.prep[li] = 0; t.lq[li] = 0;
         t.flag[li] = flag; t.list_back[li] = list_back;
         t.range_end[li] = t.rng_end;
         t.n++;
@@ -520,6 +543,39 @@ int msched_launch_retire(msched_ctx *c, uint32_t task, uint32_t n_launches) {
 }
 
 namespace {
+
+// List entries: room for `count` more in a task's ring (entries of retired commands are dead), and the mirror
+// brought up to date.  Same scheme as the ranges.
+int list_room(msched_ctx *c, TaskQueue &t, uint64_t count) {
+    uint64_t live_from = t.lst_end;                            // the first entry of the oldest queued command that has any
+    for (size_t i = t.cursor; i < t.n; ++i)
+        if (t.lq[i - t.base]) { live_from = t.lq[i - t.base] - 1; break; }
+    if (t.lst_end + count - live_from <= t.lst_cap) return MSCHED_OK;
+    uint64_t ncap = std::max<uint64_t>(1024, t.lst_cap);
+    while (ncap < 2 * (t.lst_end + count - live_from)) ncap *= 2;
+    if (ncap > (1ull << 30)) return MSCHED_E_NOMEM;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    ListEntry *nh = nullptr, *nd = nullptr;
+    HIP_TRY(c, hipHostMalloc((void **)&nh, ncap * sizeof(ListEntry), hipHostMallocDefault));
+    const hipError_t e = mirror_alloc(c, ncap * sizeof(ListEntry), (void **)&nd);
+    if (e != hipSuccess) { (void)hipHostFree(nh); HIP_TRY(c, e); }
+    for (uint64_t q = live_from; q < t.lst_end; ++q) nh[q & (ncap - 1)] = t.lst[q & (t.lst_cap - 1)];
+    if (t.lst) (void)hipHostFree(t.lst);
+    mirror_free(c, t.lst_dev);
+    t.lst = nh; t.lst_dev = nd; t.lst_cap = ncap;
+    t.lst_uploaded = live_from;
+    return MSCHED_OK;
+}
+
+int upload_lists(msched_ctx *c, TaskQueue &t) {
+    if (t.lst_uploaded < t.lst_end && t.lst_end - t.lst_uploaded <= t.lst_cap) {
+        const uint64_t mask = t.lst_cap - 1, from = t.lst_uploaded, pos = from & mask, n = t.lst_end - from, n1 = std::min(n, t.lst_cap - pos);
+        HIP_TRY(c, hipMemcpyAsync(t.lst_dev + pos, t.lst + pos, n1 * sizeof(ListEntry), hipMemcpyHostToDevice, c->stream));
+        if (n > n1) HIP_TRY(c, hipMemcpyAsync(t.lst_dev, t.lst, (n - n1) * sizeof(ListEntry), hipMemcpyHostToDevice, c->stream));
+    }
+    t.lst_uploaded = t.lst_end;
+    return MSCHED_OK;
+}
 
 // Room for `bytes` in a task's ring of prepared id lists.  Blocks are handed out roughly in program order and
 // die with their command's retirement, so the ring's tail is the oldest block a queued command still owns.
@@ -555,6 +611,9 @@ void undo_reservations(msched_ctx *c) {
         TaskQueue &t = c->tasks[it->task];
         t.prep[it->cmd - t.base] = 0;
         t.prep_head = it->head;
+        t.lq[it->cmd - t.base] = 0;
+        t.lst_end = it->lst_end;
+        t.lst_uploaded = std::min(t.lst_uploaded, t.lst_end);
     }
     c->reserved.clear();
 }
@@ -594,19 +653,30 @@ int gather_list_sources(msched_ctx *c, PlanGeom &g) {
                 const uint64_t bytes = (split * ((uint64_t)pieces * hdr_words + n_ids) * 4 + 15) & ~15ull;
                 const uint64_t head = t.prep_head;
                 uint64_t off;
+                const int rc_room = c->resident_lists ? list_room(c, t, pieces) : MSCHED_OK;
+                if (rc_room) { undo_reservations(c); return rc_room; }
                 if (!ring_alloc(c, t, bytes, off)) { undo_reservations(c); return 1; }
                 t.prep[li] = off + 1;
-                c->reserved.push_back({run.task, i, head});
+                c->reserved.push_back({run.task, i, head, t.lst_end});
+                if (c->resident_lists) t.lq[li] = t.lst_end + 1;
             }
             uint32_t *block = reinterpret_cast<uint32_t *>(t.prep_buf + (t.prep[li] - 1) % t.prep_size);
             for (uint32_t p = 0; p < pieces; ++p) {
                 const uint32_t n = std::min<uint32_t>(kPrepBlock, n_ids - p * kPrepBlock);
-                if (is_new) c->list_prep_host[n_new++] = {t.ids[li] + (size_t)p * kPrepBlock, block, n, {0, 0, 0}};
+                if (is_new) {
+                    c->list_prep_host[n_new++] = {t.ids[li] + (size_t)p * kPrepBlock, block, n, {0, 0, 0}};
+                    if (c->resident_lists) t.lst[t.lst_end++ & (t.lst_cap - 1)] = ListEntry{block, (uint32_t)i, t.list_back[li]};
+                }
                 c->list_src_host[n_src++] = {block, run.g0 + j, (uint32_t)(hdr_words + n)};
                 block += split * (hdr_words + n);
             }
         }
     }
+    if (c->resident_lists)
+        for (const PlanRun &run : c->runs) {                   // entries of the pieces handed out above go to the mirrors
+            const int rc_up = upload_lists(c, c->tasks[run.task]);
+            if (rc_up) { undo_reservations(c); return rc_up; }
+        }
     g.n_list_sources = n_src;
     g.n_list_new = n_new;
     return 0;
@@ -696,21 +766,28 @@ int plan_body(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entries
         // reader - so that in steady state a plan sends nothing but its kernels' arguments.  Otherwise (one
         // workgroup, many runs, switched off) the ranges are listed here, and copied over if many workgroups read
         // them.  Plans with more ranges than the list holds scatter next uses into nu[], like id lists.
-        g.resident = false;
+        g.resident = g.resident_lists = false;
         uint32_t n_ranges = 0;
-        if (painted && c->resident_ranges && !g.single && c->runs.size() <= std::min<size_t>(kMaxRangeRuns, g.waves)) {
+        // (A plan whose id lists are staged copies its ranges in the same kernel, and a copied list is the cheaper
+        // one to read: the mirrors are for plans that would otherwise stage nothing else.)
+        if (painted && c->resident_ranges && (!live_list || c->resident_lists) && !g.single &&
+            c->runs.size() <= std::min<size_t>(kMaxRangeRuns, g.waves)) {
             RangeRuns &rr = c->range_runs;
             uint64_t total = 0;
-            rr.n = 0;
-            for (const PlanRun &run : c->runs) {
+            rr.n = rr.n_list = 0;
+            for (const PlanRun &run : c->runs) {               // run j of the table is run j of the timeline
                 TaskQueue &t = c->tasks[run.task];
                 const uint64_t q0 = t.range_begin(run.first), q1 = t.range_end[run.first + run.count - 1 - t.base];
-                if (q1 == q0) continue;
-                if (t.rng_uploaded < q1) { const int rc_up = upload_ranges(c, t); if (rc_up) return rc_up; }
+                if (q1 > q0 && t.rng_uploaded < q1) { const int rc_up = upload_ranges(c, t); if (rc_up) return rc_up; }
                 total += q1 - q0;
                 if (total > kMaxResidentRanges) break;
-                rr.run[rr.n++] = RangeRun{t.rng_dev, (uint32_t)(t.rng_cap - 1), (uint32_t)q0, (uint32_t)(q1 - q0), (uint32_t)run.first,
-                                          run.g0, (uint32_t)t.cursor, c->dedupe_regions ? 1u : 0u, 0u};
+                RangeRun &r = rr.run[rr.n++];
+                r = RangeRun{};
+                r.ring = t.rng_dev; r.mask = (uint32_t)(t.rng_cap - 1); r.first = (uint32_t)q0; r.count = (uint32_t)(q1 - q0);
+                if (r.count == 0) {                            // nothing to read, but the reader's load is unconditional: 16 readable bytes
+                    r.ring = reinterpret_cast<const RangeRec *>(c->flags); r.mask = 0; r.first = 0;
+                }
+                r.cmd_first = (uint32_t)run.first; r.g0 = run.g0; r.cursor = (uint32_t)t.cursor; r.dedupe = c->dedupe_regions ? 1u : 0u;
             }
             if (total <= kMaxResidentRanges) {
                 g.resident = true;
@@ -759,6 +836,36 @@ int plan_body(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entries
                 g.list_prepared = rc_src == 0;
             }
             c->last_plan_prepared = g.list_prepared;
+            // The same pieces through the tasks' list mirrors, when the run table is there to carry them: every live
+            // list of a run prepared, the runs' entries in one stretch each, and few enough to be described at once.
+            g.resident_lists = false;
+            if (g.list_prepared && g.resident && g.split == 1 && c->resident_lists) {
+                RangeRuns &rr = c->range_runs;
+                uint64_t slots = 0;
+                bool ok = true;
+                for (size_t jr = 0; jr < c->runs.size() && ok; ++jr) {
+                    const PlanRun &run = c->runs[jr];
+                    TaskQueue &t = c->tasks[run.task];
+                    uint64_t e0 = 0, e1 = 0;                   // the run's entries [e0, e1)
+                    for (uint32_t j = 0; j < run.count && ok; ++j) {
+                        const size_t i = run.first + j, li = i - t.base;
+                        if (!(t.flag[li] & kCmdList)) continue;
+                        if (!t.lq[li]) { ok = repeats_queued(c, t, i, t.list_back[li]); continue; }   // unprepared: fine only if left out anyway
+                        const uint64_t at = t.lq[li] - 1, n = (t.n_ids[li] + kPrepBlock - 1) / kPrepBlock;
+                        if (e1 == e0) e0 = e1 = at;
+                        ok = at == e1;                          // in one stretch, in program order
+                        e1 = at + n;
+                    }
+                    if (!ok) break;
+                    if (e1 > e0 && t.lst_uploaded < e1) ok = upload_lists(c, t) == MSCHED_OK && t.lst_uploaded >= e1;
+                    RangeRun &r = rr.run[jr];
+                    r.lring = t.lst_dev; r.lmask = (uint32_t)(t.lst_cap ? t.lst_cap - 1 : 0); r.lfirst = (uint32_t)e0;
+                    r.lcount = (uint32_t)(e1 - e0); r.lslot0 = (uint32_t)slots;
+                    slots += e1 - e0;
+                    ok = ok && slots <= kStagePieces;
+                }
+                if (ok && slots) { g.resident_lists = true; rr.n_list = (uint32_t)slots; }
+            }
             if (many && !g.list_prepared) {
                 g.list_binned = true;
                 // room per sub-segment (8 per bucket): four times the average, at least 256 pairs
@@ -868,6 +975,17 @@ void prepare_ahead(msched_ctx *c) {
     struct Fresh { uint32_t task; size_t li; };
     std::vector<Fresh> fresh;
     std::vector<size_t> scan0(c->tasks.size());
+    std::vector<uint64_t> lst0(c->tasks.size());
+    for (size_t ti = 0; ti < c->tasks.size(); ++ti) lst0[ti] = c->tasks[ti].lst_end;
+    auto forget = [&]() {                                      // nothing of this batch was (or will be) binned
+        for (const Fresh &f : fresh) { c->tasks[f.task].prep[f.li] = 0; c->tasks[f.task].lq[f.li] = 0; }
+        for (size_t ti = 0; ti < c->tasks.size(); ++ti) {
+            TaskQueue &t = c->tasks[ti];
+            t.prep_scan = scan0[ti];
+            t.lst_end = lst0[ti];
+            t.lst_uploaded = std::min(t.lst_uploaded, t.lst_end);
+        }
+    };
     for (size_t ti = 0; ti < c->tasks.size(); ++ti) {
         TaskQueue &t = c->tasks[ti];
         scan0[ti] = t.prep_scan;
@@ -881,13 +999,16 @@ void prepare_ahead(msched_ctx *c) {
             if (n_new + pieces > kMaxListSources) { full = true; break; }
             const uint64_t bytes = (split * ((uint64_t)pieces * hdr_words + n_ids) * 4 + 15) & ~15ull;
             uint64_t off;
+            if (c->resident_lists && list_room(c, t, pieces) != MSCHED_OK) { (void)hipGetLastError(); break; }
             if (!ring_alloc(c, t, bytes, off)) break;        // no room now: the plan that needs it will see to it
             t.prep[li] = off + 1;
+            if (c->resident_lists) t.lq[li] = t.lst_end + 1;
             fresh.push_back({(uint32_t)ti, li});
             uint32_t *block = reinterpret_cast<uint32_t *>(t.prep_buf + off % t.prep_size);
             for (uint32_t p = 0; p < pieces; ++p) {
                 const uint32_t n = std::min<uint32_t>(kPrepBlock, n_ids - p * kPrepBlock);
                 c->list_ahead_host[n_new++] = {t.ids[li] + (size_t)p * kPrepBlock, block, n, {0, 0, 0}};
+                if (c->resident_lists) t.lst[t.lst_end++ & (t.lst_cap - 1)] = ListEntry{block, (uint32_t)i, t.list_back[li]};
                 block += split * (hdr_words + n);
             }
         }
@@ -901,11 +1022,17 @@ void prepare_ahead(msched_ctx *c) {
         // nothing was binned: the records must not point at blocks that hold no list
         // (a launch that did go out before a failed record is waited for, so the table is not rewritten under it)
         (void)hipStreamSynchronize(c->stream);
-        for (const Fresh &f : fresh) c->tasks[f.task].prep[f.li] = 0;
-        for (size_t ti = 0; ti < c->tasks.size(); ++ti) c->tasks[ti].prep_scan = scan0[ti];
+        forget();
         return give_up(e);
     }
     c->ahead_pending = true;
+    c->order_valid = false;                                  // new pieces may have marked new buckets
+    if (c->resident_lists) {
+        for (TaskQueue &t : c->tasks)
+            if (t.lst_uploaded < t.lst_end && upload_lists(c, t) != MSCHED_OK) { (void)hipGetLastError(); c->list_ahead = 0; break; }
+        if (c->order_chunks != 0 && launch_chunk_order(c, c->order_chunks, c->order_rounds) == hipSuccess) c->order_valid = true;
+        else (void)hipGetLastError();
+    }
     if (timed && hipEventRecord(c->ev[9], c->stream) == hipSuccess) c->prepare_timed = 1;
 }
 

@@ -732,24 +732,23 @@ struct PaintLds {
 // plan.  A range that repeats a region of a command still queued in front of its own is left out.
 struct WaveRun {                      // what a wavefront knows of its run (the same in all lanes)
     const RangeRec *ring;
+    const ListEntry *lring;
     uint32_t mask, first, count, cmd_first, g0, cursor, dedupe;
+    uint32_t lmask, lfirst, lcount, lslot0;
     uint32_t rank, waves;             // this wavefront among the `waves` that share the run
     uint32_t passes;
 };
-__device__ __forceinline__ WaveRun wave_run(const SweepGeom &sg, const RangeRuns *runs) {
+__device__ __forceinline__ WaveRun wave_run(const SweepGeom &sg, const RangeRuns *runs, bool lists) {
     WaveRun w{};
-    if (!sg.range_runs) return w;
-    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave)), waves = blockDim.x / kWave;
-    const uint32_t n = runs->n, j = wave % n;                 // n <= waves: every run has a wavefront
-    const RangeRun &run = runs->run[j];
-    // (said to be the same in all lanes once more, so that they live in scalar registers for the rest of the kernel)
-    auto same = [](uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); };
-    const uint64_t ring = reinterpret_cast<uint64_t>(run.ring);
-    w.ring = reinterpret_cast<const RangeRec *>((uint64_t)same((uint32_t)ring) | (uint64_t)same((uint32_t)(ring >> 32)) << 32);
-    w.mask = same(run.mask); w.first = same(run.first); w.count = same(run.count); w.cmd_first = same(run.cmd_first);
-    w.g0 = same(run.g0); w.cursor = same(run.cursor); w.dedupe = same(run.dedupe);
-    w.rank = same(wave / n); w.waves = same((waves - j + n - 1) / n);
-    w.passes = same(runs->passes);
+    if (!sg.range_runs && !lists) return w;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
+    const RangeRun &run = runs->run[wave];                    // this wavefront's line of the table: one scalar load, tied to nothing
+    w.ring = run.ring;
+    w.mask = run.mask; w.first = run.first; w.count = run.count; w.cmd_first = run.cmd_first;
+    w.g0 = run.g0; w.cursor = run.cursor; w.dedupe = run.dedupe;
+    if (lists) { w.lring = run.lring; w.lmask = run.lmask; w.lfirst = run.lfirst; w.lcount = run.lcount; w.lslot0 = run.lslot0; }
+    w.rank = run.share & 0xffffu; w.waves = run.share >> 16;
+    w.passes = runs->passes;
     return w;
 }
 __device__ __forceinline__ uint32_t range_passes(const SweepGeom &sg, const WaveRun &w) {
@@ -763,12 +762,21 @@ static_assert(kRangesPerThread % kRangesInFlight == 0, "whole batches");
 __device__ __forceinline__ void pass_ranges(const SweepGeom &sg, const WaveRun &w, uint32_t pass, uint32_t u0,
                                             PageRange (&R)[kRangesInFlight], bool (&live)[kRangesInFlight]) {
     uint4 v[kRangesInFlight];
+    // nothing left for this wavefront (the same answer in all its lanes): no loads at all
+    const uint32_t wave_first = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x & ~(uint32_t)(kWave - 1)));
+    const bool none = sg.range_runs ? ((pass * kRangesPerThread + u0) * w.waves + w.rank) * kRangeRow >= w.count
+                                    : (pass * kRangesPerThread + u0) * blockDim.x + wave_first >= sg.n_ranges;
+    if (none) {
+#pragma unroll
+        for (uint32_t u = 0; u < kRangesInFlight; ++u) live[u] = false;
+        return;
+    }
     if (!sg.range_runs) {
 #pragma unroll
         for (uint32_t u = 0; u < kRangesInFlight; ++u) {
             const uint32_t r = (pass * kRangesPerThread + u0 + u) * blockDim.x + threadIdx.x;
             live[u] = r < sg.n_ranges;
-            v[u] = live[u] ? reinterpret_cast<const uint4 *>(sg.ranges)[r] : uint4{0u, 0u, 0u, 0u};
+            v[u] = reinterpret_cast<const uint4 *>(sg.ranges)[min(r, sg.n_ranges - 1)];   // no branch around the load: both are in flight together
         }
 #pragma unroll
         for (uint32_t u = 0; u < kRangesInFlight; ++u) { R[u].lo = v[u].x; R[u].hi = v[u].y; R[u].g = v[u].z; R[u].pad = 0; }   // PageRange {lo, hi, g, pad}
@@ -778,7 +786,8 @@ __device__ __forceinline__ void pass_ranges(const SweepGeom &sg, const WaveRun &
     for (uint32_t u = 0; u < kRangesInFlight; ++u) {
         const uint32_t k = ((pass * kRangesPerThread + u0 + u) * w.waves + w.rank) * kRangeRow + (uint32_t)lane_id();
         live[u] = k < w.count;
-        v[u] = live[u] ? reinterpret_cast<const uint4 *>(w.ring)[(w.first + k) & w.mask] : uint4{0u, 0u, 0u, 0u};
+        // no branch around the load (a run without ranges points at 16 readable bytes): both are in flight together
+        v[u] = reinterpret_cast<const uint4 *>(w.ring)[(w.first + min(k, w.count ? w.count - 1 : 0u)) & w.mask];
     }
 #pragma unroll
     for (uint32_t u = 0; u < kRangesInFlight; ++u) {                             // RangeRec {lo, hi, back, cmd}
@@ -952,6 +961,7 @@ __device__ __forceinline__ void rank_tile(const SweepGeom &sg, uint32_t *hist, u
 // bucket with ids, and one kernel boundary fall away.
 struct TileLists {
     const ListSource *src; uint32_t n_src, n_buckets, split;
+    uint32_t resident;                  // 1: the pieces are found through the runs' list entries (src unused, n_src = entries of all runs)
     const uint32_t *bucket_mark;        // [n_buckets] does any prepared piece hold an id of this bucket?
     const uint32_t *order;              // [n_chunks] the chunk of each workgroup (chunk_order_block)
 };
@@ -969,7 +979,6 @@ struct TileLists {
 constexpr int kFusedPieces = MSCHED_FUSED_PIECES;
 constexpr int kFusedWidth = MSCHED_FUSED_WIDTH;
 constexpr int kFusedRows = 1;
-constexpr uint32_t kStagePieces = 512;   // segments of a bucket described in LDS at a time (16 bytes each)
 
 template <bool kLists>
 __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_table, const uint32_t *__restrict__ nu,
@@ -982,7 +991,8 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
     MSCHED_TICK(kTickCount, 0);
     // asked for first, so that it is there when the tile's ranges are tested; read again behind every tile's sweep
     // (kept across that loop it would cost it a dozen registers)
-    WaveRun runs = wave_run(sg, range_runs);
+    const bool lists_resident = kLists && tl->resident;
+    WaveRun runs = wave_run(sg, range_runs, lists_resident);
     for (uint32_t i = threadIdx.x; i < n_keys; i += blockDim.x) lds[i] = 0;
     if (threadIdx.x == 0) { s_paint.n_queued = 0; s_paint.floor = sg.G; }     // queue_ranges expects it empty
     if (threadIdx.x == 0 && sg.emit_hint != nullptr) sg.emit_hint[chunk] = 0;   // raised below, behind barriers
@@ -1076,9 +1086,21 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
         if (kLists) {
             if (tile_begin < p_end) {
                 const uint32_t b = (uint32_t)(tile_begin >> kBucketShift);      // the tile is this bucket
+                // a wavefront's share of the run's list entries (resident lists): entry k, alive unless its list repeats
+                // one of a command still queued in front of it
+                auto entry_alive = [&](const ListEntry &e) {
+                    return !(runs.dedupe && e.back != 0 && (int32_t)(e.cmd - e.back - runs.cursor) >= 0);
+                };
                 if (b == 0) {                                 // its workgroup also reports ids that cannot be planned
-                    for (uint32_t s = threadIdx.x; s < tl->n_src; s += blockDim.x)
-                        if (piece_bad(tl->src[s], tl->split)) atomicOr(sg.flags, kStatRange);
+                    if (lists_resident) {
+                        for (uint32_t k = runs.rank * kWave + lane; k < runs.lcount; k += runs.waves * kWave) {
+                            const ListEntry e = runs.lring[(runs.lfirst + k) & runs.lmask];
+                            if (entry_alive(e) && e.block[0] != 0) atomicOr(sg.flags, kStatRange);
+                        }
+                    } else {
+                        for (uint32_t s = threadIdx.x; s < tl->n_src; s += blockDim.x)
+                            if (piece_bad(tl->src[s], tl->split)) atomicOr(sg.flags, kStatRange);
+                    }
                 }
                 // (Measured and dropped: asking for the page-table entries and the segment descriptions before
                 // painting, so that their round trips overlap it - 5 us slower per plan.)
@@ -1096,6 +1118,19 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
                     for (uint32_t s_base = 0; s_base < tl->n_src; s_base += kStagePieces) {
                         const uint32_t n_here = min(kStagePieces, tl->n_src - s_base);
                         uint32_t longest = 0;
+                        if (lists_resident) {                 // all entries at once (n_src <= kStagePieces), each wavefront its run's
+                            for (uint32_t k = runs.rank * kWave + lane; k < runs.lcount; k += runs.waves * kWave) {
+                                const ListEntry e = runs.lring[(runs.lfirst + k) & runs.lmask];
+                                const uint32_t s = runs.lslot0 + k;
+                                uint32_t n = 0;
+                                const uint32_t *p = e.block;
+                                if (entry_alive(e)) p = piece_segment(ListSource{e.block, 0, 0}, b, 1, tl->n_buckets, n);
+                                first[s] = p;
+                                len[s] = n;
+                                cmd[s] = runs.g0 + (e.cmd - runs.cmd_first);
+                                longest = max(longest, n);
+                            }
+                        } else
                         for (uint32_t s = threadIdx.x; s < n_here; s += blockDim.x) {
                             const ListSource S = tl->src[s_base + s];
                             uint32_t n;
@@ -1129,7 +1164,7 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
             MSCHED_TICK(kTickCount, 5);
         }
         if (round + 1 < sg.rounds && (sg.n_ranges || kLists)) {
-            runs = wave_run(sg, range_runs);
+            runs = wave_run(sg, range_runs, lists_resident);
             __syncthreads();                              // the next tile repaints, and queues its ranges afresh
             if (threadIdx.x == 0) { s_paint.n_queued = 0; s_paint.floor = sg.G; }
             __syncthreads();
@@ -1264,6 +1299,8 @@ __device__ void chunk_order_block(const ChunkOrder &o) {
     }
 }
 static_assert(kMaxChunks <= 256 * 32, "a thread of chunk_order_block keeps its chunks' marks in one word");
+__global__ __launch_bounds__(256) void k_chunk_order(ChunkOrder co) { chunk_order_block(co); }
+
 
 // Budget cut, counts, victim threshold (implicit in the offsets) and per-class output offsets.
 //   D(k) = pages with nu < k; g_cut = largest k <= g_end0 with D(k) <= F            (cut)
@@ -1705,6 +1742,13 @@ hipError_t launch_list_prepare(msched_ctx *c, const ListPrep *table_dev, uint32_
     return hipGetLastError();
 }
 
+hipError_t launch_chunk_order(msched_ctx *c, uint32_t n_chunks, uint32_t rounds) {
+    (void)hipGetLastError();
+    const uint32_t n_buckets = (uint32_t)((c->V + (1u << kBucketShift) - 1) >> kBucketShift);
+    k_chunk_order<<<1, 256, 0, c->stream>>>(ChunkOrder{c->bucket_mark, n_buckets, n_chunks, rounds, 1, c->bucket_mark + kMaxBuckets});
+    return hipGetLastError();
+}
+
 hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     (void)hipGetLastError();   // launches below are checked through the sticky error: start clean
     hipStream_t st = c->stream;
@@ -1724,17 +1768,27 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         // plans whose lists are prepared send only the two small tables (ranges, list pieces).
         const bool stage_records = g.needs_records &&
                                    ((uint64_t)g.G * c->max_rules * a.n_split > c->stage_threshold || g.live_list);
-        const bool stage = stage_records || g.list_prepared || g.list_binned;
+        // Prepared lists whose pieces the first sweep finds through the tasks' list mirrors need no table either.
+        const bool lists_resident = fuse_lists && g.resident_lists;
+        const bool stage = stage_records || g.list_binned || (g.list_prepared && !lists_resident);
         a.cmds = stage_records ? c->cmd_dev : nullptr;
         const bool copy_ranges = g.n_ranges && !g.single && !g.resident;   // resident: the sweep reads the tasks' mirrors
         const uint32_t n_records = stage_records ? g.G : 0u;
+        // The order in which the first sweep takes its chunks (those with ids first) only changes when a piece is
+        // prepared (a kernel behind that preparation rewrites it) or the geometry does: otherwise it is still there.
         ChunkOrder co{nullptr, 0, 0, 0, 0, nullptr};
-        if (fuse_lists) co = ChunkOrder{c->bucket_mark, g.n_buckets, g.n_chunks, g.rounds, 1, c->bucket_mark + kMaxBuckets};
+        const bool order_there = c->order_valid && c->order_chunks == g.n_chunks && c->order_rounds == g.rounds;
+        if (fuse_lists && !order_there) {
+            co = ChunkOrder{c->bucket_mark, g.n_buckets, g.n_chunks, g.rounds, 1, c->bucket_mark + kMaxBuckets};
+            if (!stage) { k_chunk_order<<<1, 256, 0, st>>>(co); co.bucket_mark = nullptr; }
+            c->order_chunks = g.n_chunks; c->order_rounds = g.rounds; c->order_valid = true;
+        }
+        if (fuse_lists && g.n_list_new) c->order_valid = false;      // this plan's own preparation comes after
         if (stage)
-            k_stage<<<(std::max<uint32_t>(std::max(n_records * 8, g.n_ranges + g.n_list_sources), 1u) + 255) / 256 + (fuse_lists ? 1 : 0), 256, 0, st>>>(
+            k_stage<<<(std::max<uint32_t>(std::max(n_records * 8, (copy_ranges ? g.n_ranges : 0u) + g.n_list_sources), 1u) + 255) / 256 + (co.bucket_mark ? 1 : 0), 256, 0, st>>>(
                 c->cmd_ptrs_dev, n_records, c->cmd_dev, c->list_bucket_fill, g.list_binned ? g.n_buckets * 8 : 0,
                 c->ranges_host_dev, c->ranges_dev, copy_ranges ? g.n_ranges : 0, c->list_src_dev, c->list_src_stage,
-                g.list_prepared ? g.n_list_sources : 0, co);
+                g.list_prepared && !lists_resident ? g.n_list_sources : 0, co);
         else if (copy_ranges)
             k_copy_ranges<<<(g.n_ranges + 255) / 256, 256, 0, st>>>(c->ranges_host_dev, c->ranges_dev, g.n_ranges);
         // Id lists go first in three stream-ordered batches of growing size: the smallest g wins a page,
@@ -1775,18 +1829,23 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     // one workgroup reads the range list where the host wrote it; many read a device copy, or the tasks' mirrors
     sg.ranges = g.single ? c->ranges_host_dev : g.resident ? nullptr : c->ranges_dev;
     sg.range_runs = g.resident && g.n_ranges ? 1u : 0u;
-    RangeRuns no_runs;
-    no_runs.n = no_runs.passes = 0;
-    if (sg.range_runs) {                                     // passes that cover the longest run with the wavefronts it gets
-        RangeRuns &r = c->range_runs;
-        const uint32_t W = fuse_lists ? (uint32_t)kFusedThreads / kWave : g.waves;
-        r.passes = 0;
-        for (uint32_t j = 0; j < r.n; ++j) {
-            const uint32_t waves_j = (W - j + r.n - 1) / r.n, rows = (r.run[j].count + kRangeRow - 1) / kRangeRow;
-            r.passes = std::max(r.passes, (rows + kRangesPerThread * waves_j - 1) / (kRangesPerThread * waves_j));
+    const bool lists_resident = fuse_lists && g.resident_lists;
+    RangeRuns by_wave;                                       // the launch's copy of the table, a line per wavefront
+    by_wave.n = by_wave.passes = by_wave.n_list = 0;
+    if (sg.range_runs || lists_resident) {
+        const RangeRuns &r = c->range_runs;
+        const uint32_t W = fuse_lists ? (uint32_t)kFusedThreads / kWave : g.waves;     // r.n <= W <= kMaxRangeRuns
+        by_wave.n = r.n; by_wave.n_list = r.n_list;
+        for (uint32_t w = 0; w < W; ++w) {
+            const uint32_t j = w % r.n, waves_j = (W - j + r.n - 1) / r.n;
+            by_wave.run[w] = r.run[j];
+            by_wave.run[w].share = (w / r.n) | waves_j << 16;
+            // passes that cover the longest run with the wavefronts it gets
+            const uint32_t rows = (r.run[j].count + kRangeRow - 1) / kRangeRow;
+            by_wave.passes = std::max(by_wave.passes, (rows + kRangesPerThread * waves_j - 1) / (kRangesPerThread * waves_j));
         }
     }
-    const RangeRuns &rr = sg.range_runs ? c->range_runs : no_runs;
+    const RangeRuns &rr = by_wave;
     if (prof) CK(hipEventRecord(c->ev[1], st));
     const uint32_t threads = g.waves * kWave;
     const size_t paint_lds = g.n_ranges ? (size_t)g.waves * g.steps * kWave * 4 : 0;
@@ -1820,7 +1879,9 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         SweepGeom sc = sg;
         sc.steps = g.steps * g.waves / (kFusedThreads / kWave);       // the same tile, whatever the workgroup's width
         TileLists tl;
-        tl.src = c->list_src_stage; tl.n_src = g.n_list_sources; tl.n_buckets = g.n_buckets; tl.split = g.split; tl.bucket_mark = c->bucket_mark;
+        tl.src = lists_resident ? nullptr : c->list_src_stage; tl.n_src = lists_resident ? by_wave.n_list : g.n_list_sources;
+        tl.resident = lists_resident ? 1u : 0u;
+        tl.n_buckets = g.n_buckets; tl.split = g.split; tl.bucket_mark = c->bucket_mark;
         tl.order = c->bucket_mark + kMaxBuckets;
         const size_t lds = ((size_t)count_paint_offset(g.n_keys) + kBucketPages) * 4 + (size_t)kStagePieces * 16;
         k_count_lists<<<g.n_chunks, kFusedThreads, lds, st>>>(c->page_table, sc, tl, c->matrix, few_rows ? nullptr : c->partial, rr);
