@@ -135,15 +135,13 @@ int range_room(msched_ctx *c, TaskQueue &t, uint64_t count) {
     while (ncap < 2 * (t.rng_end + count - live_from)) ncap *= 2;
     if (ncap > (1ull << 30)) return MSCHED_E_NOMEM;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
-    RangeRec *nh = nullptr, *nd = nullptr;
+    RangeRec *nh = nullptr;
     HIP_TRY(c, hipHostMalloc((void **)&nh, ncap * sizeof(RangeRec), hipHostMallocDefault));
-    const hipError_t e = mirror_alloc(c, ncap * sizeof(RangeRec), (void **)&nd);
-    if (e != hipSuccess) { (void)hipHostFree(nh); HIP_TRY(c, e); }
     for (uint64_t q = live_from; q < t.rng_end; ++q) nh[q & (ncap - 1)] = t.rng[q & (t.rng_cap - 1)];
     if (t.rng) (void)hipHostFree(t.rng);
-    mirror_free(c, t.rng_dev);
-    t.rng = nh; t.rng_dev = nd; t.rng_cap = ncap;
-    t.rng_uploaded = live_from;                  // the new mirror holds nothing yet
+    mirror_free(c, t.rng_dev);                   // the mirror, if there was one, is made anew (and filled) by the plan that next wants it
+    t.rng = nh; t.rng_dev = nullptr; t.rng_cap = ncap;
+    t.rng_uploaded = live_from;
     return MSCHED_OK;
 }
 
@@ -178,7 +176,13 @@ inline int append_ranges(msched_ctx *c, TaskQueue &t, const msched_rule &q, cons
 }
 
 // Bring a task's range mirror up to date (one or two copies on the context's stream, straight from the pinned ring).
+// The mirror itself is made when a plan first wants it: tasks whose plans always stage their tables never get one.
 int upload_ranges(msched_ctx *c, TaskQueue &t) {
+    if (t.rng_cap == 0) return MSCHED_OK;
+    if (t.rng_dev == nullptr) {
+        HIP_TRY(c, mirror_alloc(c, t.rng_cap * sizeof(RangeRec), (void **)&t.rng_dev));
+        t.rng_uploaded = 0;
+    }
     const uint64_t from = std::max(t.rng_uploaded, t.ranges_live_from());
     if (from < t.rng_end) {
         const uint64_t mask = t.rng_cap - 1, pos = from & mask, n = t.rng_end - from, n1 = std::min(n, t.rng_cap - pos);
@@ -200,7 +204,6 @@ void free_ctx(msched_ctx *c) {
     for (auto &t : c->tasks) if (t.recs) (void)hipHostFree(t.recs);
     for (auto &t : c->tasks) if (t.prep_buf) (void)hipFree(t.prep_buf);
     for (auto &t : c->tasks) { if (t.rng) (void)hipHostFree(t.rng); mirror_free(c, t.rng_dev); }
-    for (auto &t : c->tasks) { if (t.lst) (void)hipHostFree(t.lst); mirror_free(c, t.lst_dev); }
     if (c->mirror_arena) (void)hipFree(c->mirror_arena);
     if (c->list_src_host) (void)hipHostFree(c->list_src_host);
     if (c->list_prep_host) (void)hipHostFree(c->list_prep_host);
@@ -275,7 +278,6 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     c->migrate_ticket = (uint32_t)env_u32("MSCHED_MIGRATE_TICKET", 0, 1, 0);
     c->paint = (uint32_t)env_u32("MSCHED_PAINT", 0, 1, 1);
     c->resident_ranges = (uint32_t)env_u32("MSCHED_RESIDENT_RANGES", 0, 1, 1);
-    c->resident_lists = (uint32_t)env_u32("MSCHED_RESIDENT_LISTS", 0, 1, 0);
     c->migrate_max_blocks = (uint32_t)env_u32("MSCHED_MIGRATE_BLOCKS", 1, 1 << 20, 512);
     c->migrate_hints = (uint32_t)env_u32("MSCHED_MIGRATE_HINTS", 0, 3, 0);
     c->expand_split = (uint32_t)env_u32("MSCHED_EXPAND_SPLIT", 1, 64, 0);
@@ -439,19 +441,19 @@ int msched_launch_enqueue(msched_ctx *c, uint32_t task, uint32_t kernel_id, cons
             if (live && off) {
                 memmove(t.recs, t.recs + off, live * sizeof(CmdRec));
                 auto front = [&](auto &v) { std::copy(v.begin() + off, v.begin() + off + live, v.begin()); };
-                front(t.lat); front(t.n_ids); front(t.list_back); front(t.range_end); front(t.prep); front(t.ids); front(t.flag); front(t.lq);
+                front(t.lat); front(t.n_ids); front(t.list_back); front(t.range_end); front(t.prep); front(t.ids); front(t.flag);
                 std::copy(t.rule_back.begin() + off * MSCHED_MAX_RULES, t.rule_back.begin() + (off + live) * MSCHED_MAX_RULES, t.rule_back.begin());
             }
         } else {
             const size_t ncap = std::max<size_t>(256, live * 2);
             // the compact arrays first: if one of them cannot grow, nothing has changed yet
             std::vector<uint32_t> lat, n_ids, list_back, rule_back;
-            std::vector<uint64_t> range_end, prep, lq;
+            std::vector<uint64_t> range_end, prep;
             std::vector<const uint32_t *> ids;
             std::vector<uint8_t> flag;
             const int rc_room = guarded([&]() -> int {
                 lat.resize(ncap); n_ids.resize(ncap); list_back.resize(ncap); range_end.resize(ncap); prep.resize(ncap);
-                ids.resize(ncap); flag.resize(ncap); rule_back.resize(ncap * MSCHED_MAX_RULES); lq.resize(ncap);
+                ids.resize(ncap); flag.resize(ncap); rule_back.resize(ncap * MSCHED_MAX_RULES);
                 return MSCHED_OK;
             });
             if (rc_room) return rc_room;
@@ -466,7 +468,6 @@ int msched_launch_enqueue(msched_ctx *c, uint32_t task, uint32_t kernel_id, cons
                 std::copy_n(t.list_back.begin() + off, live, list_back.begin());
                 std::copy_n(t.range_end.begin() + off, live, range_end.begin());
                 std::copy_n(t.prep.begin() + off, live, prep.begin());
-                std::copy_n(t.lq.begin() + off, live, lq.begin());
                 std::copy_n(t.ids.begin() + off, live, ids.begin());
                 std::copy_n(t.flag.begin() + off, live, flag.begin());
                 std::copy_n(t.rule_back.begin() + off * MSCHED_MAX_RULES, live * MSCHED_MAX_RULES, rule_back.begin());
@@ -474,7 +475,7 @@ int msched_launch_enqueue(msched_ctx *c, uint32_t task, uint32_t kernel_id, cons
             if (t.recs) (void)hipHostFree(t.recs);
             t.recs = nr; t.recs_dev = nd; t.cap = ncap;
             t.lat.swap(lat); t.n_ids.swap(n_ids); t.list_back.swap(list_back); t.range_end.swap(range_end);
-            t.prep.swap(prep); t.ids.swap(ids); t.flag.swap(flag); t.rule_back.swap(rule_back); t.lq.swap(lq);
+            t.prep.swap(prep); t.ids.swap(ids); t.flag.swap(flag); t.rule_back.swap(rule_back);
         }
         t.ranges_base = keep_from;
         t.base = t.cursor;
@@ -525,7 +526,7 @@ int msched_launch_enqueue(msched_ctx *c, uint32_t task, uint32_t kernel_id, cons
                 }
             }
         }
-        t.lat[li] = latency_ticks; t.n_ids[li] = n_ids; t.ids[li] = id_list; t.prep[li] = 0; t.lq[li] = 0;
+        t.lat[li] = latency_ticks; t.n_ids[li] = n_ids; t.ids[li] = id_list; t.prep[li] = 0;
         t.flag[li] = flag; t.list_back[li] = list_back;
         t.range_end[li] = t.rng_end;
         t.n++;
@@ -543,39 +544,6 @@ int msched_launch_retire(msched_ctx *c, uint32_t task, uint32_t n_launches) {
 }
 
 namespace {
-
-// List entries: room for `count` more in a task's ring (entries of retired commands are dead), and the mirror
-// brought up to date.  Same scheme as the ranges.
-int list_room(msched_ctx *c, TaskQueue &t, uint64_t count) {
-    uint64_t live_from = t.lst_end;                            // the first entry of the oldest queued command that has any
-    for (size_t i = t.cursor; i < t.n; ++i)
-        if (t.lq[i - t.base]) { live_from = t.lq[i - t.base] - 1; break; }
-    if (t.lst_end + count - live_from <= t.lst_cap) return MSCHED_OK;
-    uint64_t ncap = std::max<uint64_t>(1024, t.lst_cap);
-    while (ncap < 2 * (t.lst_end + count - live_from)) ncap *= 2;
-    if (ncap > (1ull << 30)) return MSCHED_E_NOMEM;
-    HIP_TRY(c, hipStreamSynchronize(c->stream));
-    ListEntry *nh = nullptr, *nd = nullptr;
-    HIP_TRY(c, hipHostMalloc((void **)&nh, ncap * sizeof(ListEntry), hipHostMallocDefault));
-    const hipError_t e = mirror_alloc(c, ncap * sizeof(ListEntry), (void **)&nd);
-    if (e != hipSuccess) { (void)hipHostFree(nh); HIP_TRY(c, e); }
-    for (uint64_t q = live_from; q < t.lst_end; ++q) nh[q & (ncap - 1)] = t.lst[q & (t.lst_cap - 1)];
-    if (t.lst) (void)hipHostFree(t.lst);
-    mirror_free(c, t.lst_dev);
-    t.lst = nh; t.lst_dev = nd; t.lst_cap = ncap;
-    t.lst_uploaded = live_from;
-    return MSCHED_OK;
-}
-
-int upload_lists(msched_ctx *c, TaskQueue &t) {
-    if (t.lst_uploaded < t.lst_end && t.lst_end - t.lst_uploaded <= t.lst_cap) {
-        const uint64_t mask = t.lst_cap - 1, from = t.lst_uploaded, pos = from & mask, n = t.lst_end - from, n1 = std::min(n, t.lst_cap - pos);
-        HIP_TRY(c, hipMemcpyAsync(t.lst_dev + pos, t.lst + pos, n1 * sizeof(ListEntry), hipMemcpyHostToDevice, c->stream));
-        if (n > n1) HIP_TRY(c, hipMemcpyAsync(t.lst_dev, t.lst, (n - n1) * sizeof(ListEntry), hipMemcpyHostToDevice, c->stream));
-    }
-    t.lst_uploaded = t.lst_end;
-    return MSCHED_OK;
-}
 
 // Room for `bytes` in a task's ring of prepared id lists.  Blocks are handed out roughly in program order and
 // die with their command's retirement, so the ring's tail is the oldest block a queued command still owns.
@@ -611,9 +579,6 @@ void undo_reservations(msched_ctx *c) {
         TaskQueue &t = c->tasks[it->task];
         t.prep[it->cmd - t.base] = 0;
         t.prep_head = it->head;
-        t.lq[it->cmd - t.base] = 0;
-        t.lst_end = it->lst_end;
-        t.lst_uploaded = std::min(t.lst_uploaded, t.lst_end);
     }
     c->reserved.clear();
 }
@@ -653,30 +618,19 @@ int gather_list_sources(msched_ctx *c, PlanGeom &g) {
                 const uint64_t bytes = (split * ((uint64_t)pieces * hdr_words + n_ids) * 4 + 15) & ~15ull;
                 const uint64_t head = t.prep_head;
                 uint64_t off;
-                const int rc_room = c->resident_lists ? list_room(c, t, pieces) : MSCHED_OK;
-                if (rc_room) { undo_reservations(c); return rc_room; }
                 if (!ring_alloc(c, t, bytes, off)) { undo_reservations(c); return 1; }
                 t.prep[li] = off + 1;
-                c->reserved.push_back({run.task, i, head, t.lst_end});
-                if (c->resident_lists) t.lq[li] = t.lst_end + 1;
+                c->reserved.push_back({run.task, i, head});
             }
             uint32_t *block = reinterpret_cast<uint32_t *>(t.prep_buf + (t.prep[li] - 1) % t.prep_size);
             for (uint32_t p = 0; p < pieces; ++p) {
                 const uint32_t n = std::min<uint32_t>(kPrepBlock, n_ids - p * kPrepBlock);
-                if (is_new) {
-                    c->list_prep_host[n_new++] = {t.ids[li] + (size_t)p * kPrepBlock, block, n, {0, 0, 0}};
-                    if (c->resident_lists) t.lst[t.lst_end++ & (t.lst_cap - 1)] = ListEntry{block, (uint32_t)i, t.list_back[li]};
-                }
+                if (is_new) c->list_prep_host[n_new++] = {t.ids[li] + (size_t)p * kPrepBlock, block, n, {0, 0, 0}};
                 c->list_src_host[n_src++] = {block, run.g0 + j, (uint32_t)(hdr_words + n)};
                 block += split * (hdr_words + n);
             }
         }
     }
-    if (c->resident_lists)
-        for (const PlanRun &run : c->runs) {                   // entries of the pieces handed out above go to the mirrors
-            const int rc_up = upload_lists(c, c->tasks[run.task]);
-            if (rc_up) { undo_reservations(c); return rc_up; }
-        }
     g.n_list_sources = n_src;
     g.n_list_new = n_new;
     return 0;
@@ -766,19 +720,19 @@ int plan_body(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entries
         // reader - so that in steady state a plan sends nothing but its kernels' arguments.  Otherwise (one
         // workgroup, many runs, switched off) the ranges are listed here, and copied over if many workgroups read
         // them.  Plans with more ranges than the list holds scatter next uses into nu[], like id lists.
-        g.resident = g.resident_lists = false;
+        g.resident = false;
         uint32_t n_ranges = 0;
         // (A plan whose id lists are staged copies its ranges in the same kernel, and a copied list is the cheaper
-        // one to read: the mirrors are for plans that would otherwise stage nothing else.)
-        if (painted && c->resident_ranges && (!live_list || c->resident_lists) && !g.single &&
+        // one to read: the mirrors are for plans that would otherwise stage nothing.)
+        if (painted && c->resident_ranges && !live_list && !g.single &&
             c->runs.size() <= std::min<size_t>(kMaxRangeRuns, g.waves)) {
             RangeRuns &rr = c->range_runs;
             uint64_t total = 0;
-            rr.n = rr.n_list = 0;
+            rr.n = 0;
             for (const PlanRun &run : c->runs) {               // run j of the table is run j of the timeline
                 TaskQueue &t = c->tasks[run.task];
                 const uint64_t q0 = t.range_begin(run.first), q1 = t.range_end[run.first + run.count - 1 - t.base];
-                if (q1 > q0 && t.rng_uploaded < q1) { const int rc_up = upload_ranges(c, t); if (rc_up) return rc_up; }
+                if (q1 > q0 && (t.rng_dev == nullptr || t.rng_uploaded < q1)) { const int rc_up = upload_ranges(c, t); if (rc_up) return rc_up; }
                 total += q1 - q0;
                 if (total > kMaxResidentRanges) break;
                 RangeRun &r = rr.run[rr.n++];
@@ -836,36 +790,6 @@ int plan_body(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entries
                 g.list_prepared = rc_src == 0;
             }
             c->last_plan_prepared = g.list_prepared;
-            // The same pieces through the tasks' list mirrors, when the run table is there to carry them: every live
-            // list of a run prepared, the runs' entries in one stretch each, and few enough to be described at once.
-            g.resident_lists = false;
-            if (g.list_prepared && g.resident && g.split == 1 && c->resident_lists) {
-                RangeRuns &rr = c->range_runs;
-                uint64_t slots = 0;
-                bool ok = true;
-                for (size_t jr = 0; jr < c->runs.size() && ok; ++jr) {
-                    const PlanRun &run = c->runs[jr];
-                    TaskQueue &t = c->tasks[run.task];
-                    uint64_t e0 = 0, e1 = 0;                   // the run's entries [e0, e1)
-                    for (uint32_t j = 0; j < run.count && ok; ++j) {
-                        const size_t i = run.first + j, li = i - t.base;
-                        if (!(t.flag[li] & kCmdList)) continue;
-                        if (!t.lq[li]) { ok = repeats_queued(c, t, i, t.list_back[li]); continue; }   // unprepared: fine only if left out anyway
-                        const uint64_t at = t.lq[li] - 1, n = (t.n_ids[li] + kPrepBlock - 1) / kPrepBlock;
-                        if (e1 == e0) e0 = e1 = at;
-                        ok = at == e1;                          // in one stretch, in program order
-                        e1 = at + n;
-                    }
-                    if (!ok) break;
-                    if (e1 > e0 && t.lst_uploaded < e1) ok = upload_lists(c, t) == MSCHED_OK && t.lst_uploaded >= e1;
-                    RangeRun &r = rr.run[jr];
-                    r.lring = t.lst_dev; r.lmask = (uint32_t)(t.lst_cap ? t.lst_cap - 1 : 0); r.lfirst = (uint32_t)e0;
-                    r.lcount = (uint32_t)(e1 - e0); r.lslot0 = (uint32_t)slots;
-                    slots += e1 - e0;
-                    ok = ok && slots <= kStagePieces;
-                }
-                if (ok && slots) { g.resident_lists = true; rr.n_list = (uint32_t)slots; }
-            }
             if (many && !g.list_prepared) {
                 g.list_binned = true;
                 // room per sub-segment (8 per bucket): four times the average, at least 256 pairs
@@ -975,16 +899,9 @@ void prepare_ahead(msched_ctx *c) {
     struct Fresh { uint32_t task; size_t li; };
     std::vector<Fresh> fresh;
     std::vector<size_t> scan0(c->tasks.size());
-    std::vector<uint64_t> lst0(c->tasks.size());
-    for (size_t ti = 0; ti < c->tasks.size(); ++ti) lst0[ti] = c->tasks[ti].lst_end;
     auto forget = [&]() {                                      // nothing of this batch was (or will be) binned
-        for (const Fresh &f : fresh) { c->tasks[f.task].prep[f.li] = 0; c->tasks[f.task].lq[f.li] = 0; }
-        for (size_t ti = 0; ti < c->tasks.size(); ++ti) {
-            TaskQueue &t = c->tasks[ti];
-            t.prep_scan = scan0[ti];
-            t.lst_end = lst0[ti];
-            t.lst_uploaded = std::min(t.lst_uploaded, t.lst_end);
-        }
+        for (const Fresh &f : fresh) c->tasks[f.task].prep[f.li] = 0;
+        for (size_t ti = 0; ti < c->tasks.size(); ++ti) c->tasks[ti].prep_scan = scan0[ti];
     };
     for (size_t ti = 0; ti < c->tasks.size(); ++ti) {
         TaskQueue &t = c->tasks[ti];
@@ -999,16 +916,13 @@ void prepare_ahead(msched_ctx *c) {
             if (n_new + pieces > kMaxListSources) { full = true; break; }
             const uint64_t bytes = (split * ((uint64_t)pieces * hdr_words + n_ids) * 4 + 15) & ~15ull;
             uint64_t off;
-            if (c->resident_lists && list_room(c, t, pieces) != MSCHED_OK) { (void)hipGetLastError(); break; }
             if (!ring_alloc(c, t, bytes, off)) break;        // no room now: the plan that needs it will see to it
             t.prep[li] = off + 1;
-            if (c->resident_lists) t.lq[li] = t.lst_end + 1;
             fresh.push_back({(uint32_t)ti, li});
             uint32_t *block = reinterpret_cast<uint32_t *>(t.prep_buf + off % t.prep_size);
             for (uint32_t p = 0; p < pieces; ++p) {
                 const uint32_t n = std::min<uint32_t>(kPrepBlock, n_ids - p * kPrepBlock);
                 c->list_ahead_host[n_new++] = {t.ids[li] + (size_t)p * kPrepBlock, block, n, {0, 0, 0}};
-                if (c->resident_lists) t.lst[t.lst_end++ & (t.lst_cap - 1)] = ListEntry{block, (uint32_t)i, t.list_back[li]};
                 block += split * (hdr_words + n);
             }
         }
@@ -1026,13 +940,6 @@ void prepare_ahead(msched_ctx *c) {
         return give_up(e);
     }
     c->ahead_pending = true;
-    c->order_valid = false;                                  // new pieces may have marked new buckets
-    if (c->resident_lists) {
-        for (TaskQueue &t : c->tasks)
-            if (t.lst_uploaded < t.lst_end && upload_lists(c, t) != MSCHED_OK) { (void)hipGetLastError(); c->list_ahead = 0; break; }
-        if (c->order_chunks != 0 && launch_chunk_order(c, c->order_chunks, c->order_rounds) == hipSuccess) c->order_valid = true;
-        else (void)hipGetLastError();
-    }
     if (timed && hipEventRecord(c->ev[9], c->stream) == hipSuccess) c->prepare_timed = 1;
 }
 

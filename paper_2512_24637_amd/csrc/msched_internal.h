@@ -73,8 +73,6 @@ struct RegionSigHash {
 // a plan leaves it out.  All ranges of one rule share `back`; `cmd` is the command's program-order index in its
 // task (low 32 bits: only differences between queued commands are ever taken).
 struct RangeRec { uint32_t lo, hi, back, cmd; };
-// One prepared piece of a queued command's id list: where its block lies, and `cmd` / `back` as in RangeRec.
-struct ListEntry { const uint32_t *block; uint32_t cmd, back; };
 constexpr uint32_t kRuleEmpty = 0xFFFFFFFFu;
 constexpr uint8_t kCmdList = 1;                 // the command has a live id list (a LIST rule and at least one id)
 constexpr uint8_t kCmdNoPaint = 2;              // its ranges were too many to keep: plans that hold it scatter next uses per page
@@ -105,11 +103,6 @@ struct TaskQueue {
     uint64_t rng_end = 0;                       // running index behind the last range
     uint64_t rng_uploaded = 0;                  // ranges with a running index below this are in the mirror
     uint64_t ranges_base = 0;                   // running index of the first range of command `base`
-    // One entry per prepared piece of an id list, in the order of preparation (which is program order unless a
-    // repeated list is prepared late: plans check), kept like the ranges: pinned ring and device mirror.
-    ListEntry *lst = nullptr, *lst_dev = nullptr;
-    uint64_t lst_cap = 0, lst_end = 0, lst_uploaded = 0;
-    std::vector<uint64_t> lq;                   // 1 + running index of the command's first list entry (0: not prepared)
     std::unordered_map<RegionSig, size_t, RegionSigHash> last_region;   // region -> latest command that described it
     size_t pruned_at = 0;                       // size of last_region after its last clean-up
     // prepared id lists of this task's queued commands: a ring in device memory, filled in program order
@@ -139,28 +132,24 @@ struct PlanRun { uint32_t task, g0, count; size_t first; };
 // ranges on the host instead.
 constexpr uint32_t kMaxRangeRuns = 16;
 constexpr uint32_t kRangeRow = 64;
-// The prepared id lists of the run's commands reach the first sweep the same way (when it merges them itself): a
-// slice of the task's mirror of list entries, one entry per prepared piece; entry k of the run describes segment
-// lslot0 + k of the plan.
 struct RangeRun {
     const RangeRec *ring;
-    const ListEntry *lring;
     uint32_t mask, first;          // range k of the run is ring[(first + k) & mask]
     uint32_t count;                // ranges
     uint32_t cmd_first, g0, cursor;
     uint32_t dedupe;
-    uint32_t lmask, lfirst, lcount, lslot0;   // list entry k of the run is lring[(lfirst + k) & lmask]
     uint32_t share;                // set at launch, per wavefront: its rank among the wavefronts that serve the run | their number << 16
+    uint32_t passes;               // set at launch: passes of kRangesPerThread rows per wavefront that cover the longest run
+    uint32_t pad[5];
 };
-static_assert(sizeof(RangeRun) == 64, "RangeRun layout");
+static_assert(sizeof(RangeRun) == 64, "a line of the table");
 // What a launch carries: the runs, copied out once more per wavefront of a workgroup (entry w is the run wavefront w
-// serves, with its share of it), so that a wavefront finds its line of the table without having read anything else.
+// serves, with its share of it), so that a wavefront finds its 64-byte line of the table without having read
+// anything else.
 struct alignas(64) RangeRuns {
-    uint32_t n;                    // runs
-    uint32_t passes;               // passes of kRangesPerThread rows per wavefront that cover the longest run (set at launch)
-    uint32_t n_list;               // list entries of all runs (0: the plan's lists, if any, are staged)
-    uint32_t pad[13];
-    RangeRun run[kMaxRangeRuns];   // by run (host side); rewritten by wavefront at launch
+    uint32_t n;                    // runs (host side)
+    uint32_t pad[15];
+    RangeRun run[kMaxRangeRuns];   // by run (host side); by wavefront in the copy a launch carries
 };
 static_assert(sizeof(RangeRuns) == 64 + 64 * kMaxRangeRuns, "RangeRuns layout");
 constexpr uint32_t kStagePieces = 512;      // segments of a bucket described in LDS at a time (16 bytes each)
@@ -210,7 +199,6 @@ struct PlanGeom {
     bool needs_records;                                  // some kernel of the plan reads whole command records (table of record addresses filled)
     bool painted;                                        // range rules arrive as a range list the sweeps paint into LDS
     bool resident;                                       // ... which the sweeps read from the tasks' range mirrors (nothing staged)
-    bool resident_lists;                                 // the prepared id lists can be found through the tasks' list mirrors as well
     bool use_nu;                                         // some next uses are in nu[] (id lists, or the scatter path)
     uint32_t n_ranges;
 };
@@ -240,7 +228,7 @@ struct msched_ctx {
     uint8_t *mirror_arena = nullptr;
     size_t mirror_arena_used = 0;
     std::vector<size_t> pos;                    // per task: next command the flattening takes
-    struct Reserved { uint32_t task; size_t cmd; uint64_t head, lst_end; };
+    struct Reserved { uint32_t task; size_t cmd; uint64_t head; };
     std::vector<Reserved> reserved;             // ring blocks this plan handed out for id lists it prepares itself (undone if it fails)
     bool force_multi_kernel = false;            // test hook: never use the fused single-workgroup tail
     bool no_large_lds = false;                  // MSCHED_NO_LARGE_LDS: never ask for more than the default dynamic LDS
@@ -264,8 +252,6 @@ struct msched_ctx {
     msched::ListPrep *list_ahead_dev = nullptr;
     hipEvent_t ahead_ev = nullptr; bool ahead_pending = false;   // the last look-ahead kernel still reads the table
     bool last_plan_prepared = false;               // the latest plan merged prepared pieces
-    uint32_t order_chunks = 0, order_rounds = 0;   // geometry the chunk order behind bucket_mark was last written for
-    bool order_valid = false;                      // ... and no piece has been prepared since (marks unchanged)
     std::vector<uint8_t> kernel_has_list;          // per registered kernel
     uint32_t list_b0 = 4, list_b1 = 32;         // id lists: commands [0,b0), [b0,b1), [b1,G) run as ordered batches
     uint32_t *page_table = nullptr, *frame_owner = nullptr, *nu = nullptr, *slot = nullptr;  // device
@@ -297,9 +283,6 @@ struct msched_ctx {
     uint16_t *key16 = nullptr;                  // device [V]: class key of every page (first sweep -> second sweep)
     uint32_t paint = 1;                         // 0: always scatter next uses per page (MSCHED_PAINT)
     uint32_t resident_ranges = 1;               // 0: every plan copies its range list to the device (MSCHED_RESIDENT_RANGES)
-    uint32_t resident_lists = 0;                // 1: the first sweep finds prepared id lists through the tasks' list mirrors, and plans
-                                                // with lists stage nothing either (MSCHED_RESIDENT_LISTS; measured: 1 us per plan, 7 us
-                                                // more behind every migration)
     int early = 0;                              // msched_set_early_start
     uint32_t *need_host = nullptr;              // pinned [MAX_G + 1]: need[g] of the latest plan (written by the cut kernel)
     uint32_t *page_done = nullptr;              // device [F]: tag of the migration that completed fetch entry i
@@ -340,7 +323,6 @@ hipError_t query_static(msched_ctx *c, const uint64_t *page_ids, uint32_t n, uin
 hipError_t launch_peek(msched_ctx *c);
 hipError_t launch_gate(msched_ctx *c, uint32_t g, uint32_t need, uint64_t timeout_ticks, hipStream_t stream);
 hipError_t launch_list_prepare(msched_ctx *c, const ListPrep *table_dev, uint32_t n, uint32_t n_buckets, uint32_t split);
-hipError_t launch_chunk_order(msched_ctx *c, uint32_t n_chunks, uint32_t rounds);   // the first sweep's chunk order, from the bucket marks
 //      // landed -> progress_host on the poll stream
 
 extern int g_last_hip;                        // hipError_t of the last failed HIP call of any context

@@ -694,7 +694,6 @@ struct SweepGeom {
     // next uses that come from range rules: a list of page ranges painted into LDS tile by tile
     const PageRange *ranges;
     uint32_t n_ranges;        // 0: nothing to paint
-    uint32_t range_runs;      // 1: the ranges are entries of the tasks' mirrors, taken run by run (`ranges` unused)
     uint32_t use_nu;          // 0: nu[] holds nothing for this plan and is not read
     const uint32_t *bucket_mark;   // non-null: nu[] holds something of this plan only in buckets marked here (all its
                                    // id lists came through prepared pieces); the sweep skips nu[] elsewhere
@@ -727,67 +726,61 @@ struct PaintLds {
 };
 
 // The plan's ranges are tested in passes of kRangesPerThread per thread.  They come from the plan's own list; or,
-// when the plan brought none (sg.range_runs), from the tasks' range mirrors: a wavefront serves one run of the
+// in the sweep for plans that brought none (kRuns), from the tasks' range mirrors: a wavefront serves one run of the
 // timeline for the whole launch and takes rows of 64 of its entries, a lane working out its entry's position in the
 // plan.  A range that repeats a region of a command still queued in front of its own is left out.
 struct WaveRun {                      // what a wavefront knows of its run (the same in all lanes)
     const RangeRec *ring;
-    const ListEntry *lring;
     uint32_t mask, first, count, cmd_first, g0, cursor, dedupe;
-    uint32_t lmask, lfirst, lcount, lslot0;
     uint32_t rank, waves;             // this wavefront among the `waves` that share the run
     uint32_t passes;
 };
-__device__ __forceinline__ WaveRun wave_run(const SweepGeom &sg, const RangeRuns *runs, bool lists) {
-    WaveRun w{};
-    if (!sg.range_runs && !lists) return w;
+__device__ __forceinline__ WaveRun wave_run(const RangeRuns *runs) {
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
     const RangeRun &run = runs->run[wave];                    // this wavefront's line of the table: one scalar load, tied to nothing
+    WaveRun w;
     w.ring = run.ring;
     w.mask = run.mask; w.first = run.first; w.count = run.count; w.cmd_first = run.cmd_first;
     w.g0 = run.g0; w.cursor = run.cursor; w.dedupe = run.dedupe;
-    if (lists) { w.lring = run.lring; w.lmask = run.lmask; w.lfirst = run.lfirst; w.lcount = run.lcount; w.lslot0 = run.lslot0; }
     w.rank = run.share & 0xffffu; w.waves = run.share >> 16;
-    w.passes = runs->passes;
+    w.passes = run.passes;
     return w;
 }
+template <bool kRuns>
 __device__ __forceinline__ uint32_t range_passes(const SweepGeom &sg, const WaveRun &w) {
-    if (!sg.range_runs) return (sg.n_ranges + blockDim.x * kRangesPerThread - 1) / (blockDim.x * kRangesPerThread);
+    if (!kRuns) return (sg.n_ranges + blockDim.x * kRangesPerThread - 1) / (blockDim.x * kRangesPerThread);
     return w.passes;
 }
 // This thread's ranges u0 .. u0 + kRangesInFlight - 1 (of kRangesPerThread) of pass `pass`: R[i] with live[i] set.
 // Their loads are asked for together (more at a time cost the sweeps a workgroup per compute unit in registers).
 constexpr uint32_t kRangesInFlight = 2;
 static_assert(kRangesPerThread % kRangesInFlight == 0, "whole batches");
+template <bool kRuns>
 __device__ __forceinline__ void pass_ranges(const SweepGeom &sg, const WaveRun &w, uint32_t pass, uint32_t u0,
                                             PageRange (&R)[kRangesInFlight], bool (&live)[kRangesInFlight]) {
-    uint4 v[kRangesInFlight];
-    // nothing left for this wavefront (the same answer in all its lanes): no loads at all
-    const uint32_t wave_first = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x & ~(uint32_t)(kWave - 1)));
-    const bool none = sg.range_runs ? ((pass * kRangesPerThread + u0) * w.waves + w.rank) * kRangeRow >= w.count
-                                    : (pass * kRangesPerThread + u0) * blockDim.x + wave_first >= sg.n_ranges;
-    if (none) {
-#pragma unroll
-        for (uint32_t u = 0; u < kRangesInFlight; ++u) live[u] = false;
-        return;
-    }
-    if (!sg.range_runs) {
+    if (!kRuns) {
 #pragma unroll
         for (uint32_t u = 0; u < kRangesInFlight; ++u) {
             const uint32_t r = (pass * kRangesPerThread + u0 + u) * blockDim.x + threadIdx.x;
             live[u] = r < sg.n_ranges;
-            v[u] = reinterpret_cast<const uint4 *>(sg.ranges)[min(r, sg.n_ranges - 1)];   // no branch around the load: both are in flight together
+            if (live[u]) R[u] = sg.ranges[r];
         }
-#pragma unroll
-        for (uint32_t u = 0; u < kRangesInFlight; ++u) { R[u].lo = v[u].x; R[u].hi = v[u].y; R[u].g = v[u].z; R[u].pad = 0; }   // PageRange {lo, hi, g, pad}
         return;
     }
+    // nothing left for this wavefront (the same answer in all its lanes): no loads at all
+    if (((pass * kRangesPerThread + u0) * w.waves + w.rank) * kRangeRow >= w.count) {
+#pragma unroll
+        for (uint32_t u = 0; u < kRangesInFlight; ++u) live[u] = false;
+        return;
+    }
+    uint4 v[kRangesInFlight];
 #pragma unroll
     for (uint32_t u = 0; u < kRangesInFlight; ++u) {
         const uint32_t k = ((pass * kRangesPerThread + u0 + u) * w.waves + w.rank) * kRangeRow + (uint32_t)lane_id();
         live[u] = k < w.count;
-        // no branch around the load (a run without ranges points at 16 readable bytes): both are in flight together
-        v[u] = reinterpret_cast<const uint4 *>(w.ring)[(w.first + min(k, w.count ? w.count - 1 : 0u)) & w.mask];
+        // no branch around the load (under a condition it is compiled as a branch with the wait for the load inside,
+        // and the loads of a batch take a round trip each instead of one together)
+        v[u] = reinterpret_cast<const uint4 *>(w.ring)[(w.first + min(k, w.count - 1)) & w.mask];
     }
 #pragma unroll
     for (uint32_t u = 0; u < kRangesInFlight; ++u) {                             // RangeRec {lo, hi, back, cmd}
@@ -797,21 +790,21 @@ __device__ __forceinline__ void pass_ranges(const SweepGeom &sg, const WaveRun &
     }
 }
 static_assert(kRangeRow == (uint32_t)kWave, "a row of range entries is read by one wavefront");
-static_assert(sizeof(PageRange) == 16 && sizeof(RangeRec) == 16, "ranges are read as one 16-byte word");
-static_assert(kRangeRow == (uint32_t)kWave, "a row of range entries is read by one wavefront");
+static_assert(sizeof(RangeRec) == 16, "range entries are read as one 16-byte word");
 
+template <bool kRuns>
 __device__ __forceinline__ void paint_tile(const SweepGeom &sg, const WaveRun &runs, uint64_t t0, uint64_t t1, uint32_t *paint, PaintLds &q) {
     const uint32_t n = (t1 > t0) ? (uint32_t)(t1 - t0) : 0;
     for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) paint[i] = sg.G;
     if (threadIdx.x == 0) { q.n_queued = 0; q.floor = sg.G; }
     __syncthreads();
-    const uint32_t passes = range_passes(sg, runs);           // a thread tests kRangesPerThread ranges per pass (a pass costs three barriers)
+    const uint32_t passes = range_passes<kRuns>(sg, runs);           // a thread tests kRangesPerThread ranges per pass (a pass costs three barriers)
     for (uint32_t pass = 0; pass < passes; ++pass) {
 #pragma unroll
         for (uint32_t u0 = 0; u0 < kRangesPerThread; u0 += kRangesInFlight) {
         PageRange Rs[kRangesInFlight];
         bool live[kRangesInFlight];
-        pass_ranges(sg, runs, pass, u0, Rs, live);
+        pass_ranges<kRuns>(sg, runs, pass, u0, Rs, live);
 #pragma unroll
         for (uint32_t j = 0; j < kRangesInFlight; ++j) {
             if (!live[j]) continue;
@@ -856,14 +849,15 @@ __device__ __forceinline__ void paint_tile(const SweepGeom &sg, const WaveRun &r
 #endif
 constexpr uint32_t kPaintInRegisters = MSCHED_PAINT_IN_REGISTERS;
 // The queue is empty on entry (count_body resets it ahead of a barrier it needs anyway).
+template <bool kRuns>
 __device__ __forceinline__ uint32_t queue_ranges(const SweepGeom &sg, const WaveRun &runs, uint64_t t0, uint64_t t1, PaintLds &q) {
-    const uint32_t passes = range_passes(sg, runs);
+    const uint32_t passes = range_passes<kRuns>(sg, runs);
     for (uint32_t pass = 0; pass < passes; ++pass) {
 #pragma unroll
         for (uint32_t u0 = 0; u0 < kRangesPerThread; u0 += kRangesInFlight) {
         PageRange Rs[kRangesInFlight];
         bool live[kRangesInFlight];
-        pass_ranges(sg, runs, pass, u0, Rs, live);
+        pass_ranges<kRuns>(sg, runs, pass, u0, Rs, live);
 #pragma unroll
         for (uint32_t j = 0; j < kRangesInFlight; ++j) {
             if (!live[j]) continue;
@@ -961,7 +955,6 @@ __device__ __forceinline__ void rank_tile(const SweepGeom &sg, uint32_t *hist, u
 // bucket with ids, and one kernel boundary fall away.
 struct TileLists {
     const ListSource *src; uint32_t n_src, n_buckets, split;
-    uint32_t resident;                  // 1: the pieces are found through the runs' list entries (src unused, n_src = entries of all runs)
     const uint32_t *bucket_mark;        // [n_buckets] does any prepared piece hold an id of this bucket?
     const uint32_t *order;              // [n_chunks] the chunk of each workgroup (chunk_order_block)
 };
@@ -980,7 +973,7 @@ constexpr int kFusedPieces = MSCHED_FUSED_PIECES;
 constexpr int kFusedWidth = MSCHED_FUSED_WIDTH;
 constexpr int kFusedRows = 1;
 
-template <bool kLists>
+template <bool kLists, bool kRuns = false>
 __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_table, const uint32_t *__restrict__ nu,
                                            const SweepGeom &sg, uint32_t chunk, uint32_t *lds, uint32_t *row,
                                            uint32_t *group_row, uint32_t *slice_row, const TileLists *tl = nullptr,
@@ -991,8 +984,8 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
     MSCHED_TICK(kTickCount, 0);
     // asked for first, so that it is there when the tile's ranges are tested; read again behind every tile's sweep
     // (kept across that loop it would cost it a dozen registers)
-    const bool lists_resident = kLists && tl->resident;
-    WaveRun runs = wave_run(sg, range_runs, lists_resident);
+    WaveRun runs{};
+    if (kRuns) runs = wave_run(range_runs);
     for (uint32_t i = threadIdx.x; i < n_keys; i += blockDim.x) lds[i] = 0;
     if (threadIdx.x == 0) { s_paint.n_queued = 0; s_paint.floor = sg.G; }     // queue_ranges expects it empty
     if (threadIdx.x == 0 && sg.emit_hint != nullptr) sg.emit_hint[chunk] = 0;   // raised below, behind barriers
@@ -1078,29 +1071,17 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
         // ranges of a tile without id lists: queued and applied from registers when they are few
         auto paint_ranges = [&]() -> int {
             if (!sg.n_ranges) return kPaintNone;
-            if (queue_ranges(sg, runs, tile_begin, tile_end, s_paint) <= kPaintInRegisters) return kPaintQueued;
+            if (queue_ranges<kRuns>(sg, runs, tile_begin, tile_end, s_paint) <= kPaintInRegisters) return kPaintQueued;
             __syncthreads();                                  // everybody has read the count
-            paint_tile(sg, runs, tile_begin, tile_end, paint, s_paint);
+            paint_tile<kRuns>(sg, runs, tile_begin, tile_end, paint, s_paint);
             return kPaintLds;
         };
         if (kLists) {
             if (tile_begin < p_end) {
                 const uint32_t b = (uint32_t)(tile_begin >> kBucketShift);      // the tile is this bucket
-                // a wavefront's share of the run's list entries (resident lists): entry k, alive unless its list repeats
-                // one of a command still queued in front of it
-                auto entry_alive = [&](const ListEntry &e) {
-                    return !(runs.dedupe && e.back != 0 && (int32_t)(e.cmd - e.back - runs.cursor) >= 0);
-                };
                 if (b == 0) {                                 // its workgroup also reports ids that cannot be planned
-                    if (lists_resident) {
-                        for (uint32_t k = runs.rank * kWave + lane; k < runs.lcount; k += runs.waves * kWave) {
-                            const ListEntry e = runs.lring[(runs.lfirst + k) & runs.lmask];
-                            if (entry_alive(e) && e.block[0] != 0) atomicOr(sg.flags, kStatRange);
-                        }
-                    } else {
-                        for (uint32_t s = threadIdx.x; s < tl->n_src; s += blockDim.x)
-                            if (piece_bad(tl->src[s], tl->split)) atomicOr(sg.flags, kStatRange);
-                    }
+                    for (uint32_t s = threadIdx.x; s < tl->n_src; s += blockDim.x)
+                        if (piece_bad(tl->src[s], tl->split)) atomicOr(sg.flags, kStatRange);
                 }
                 // (Measured and dropped: asking for the page-table entries and the segment descriptions before
                 // painting, so that their round trips overlap it - 5 us slower per plan.)
@@ -1110,7 +1091,7 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
                     sweep_tile(how, false);
                     MSCHED_TICK(kTickCount, 5);
                 } else {
-                    paint_tile(sg, runs, tile_begin, tile_end, paint, s_paint);
+                    paint_tile<kRuns>(sg, runs, tile_begin, tile_end, paint, s_paint);
                     MSCHED_TICK(kTickCount, 2);
                     const uint32_t **first = reinterpret_cast<const uint32_t **>(paint + tile_pages);   // [kStagePieces]
                     uint32_t *len = reinterpret_cast<uint32_t *>(first + kStagePieces);
@@ -1118,19 +1099,6 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
                     for (uint32_t s_base = 0; s_base < tl->n_src; s_base += kStagePieces) {
                         const uint32_t n_here = min(kStagePieces, tl->n_src - s_base);
                         uint32_t longest = 0;
-                        if (lists_resident) {                 // all entries at once (n_src <= kStagePieces), each wavefront its run's
-                            for (uint32_t k = runs.rank * kWave + lane; k < runs.lcount; k += runs.waves * kWave) {
-                                const ListEntry e = runs.lring[(runs.lfirst + k) & runs.lmask];
-                                const uint32_t s = runs.lslot0 + k;
-                                uint32_t n = 0;
-                                const uint32_t *p = e.block;
-                                if (entry_alive(e)) p = piece_segment(ListSource{e.block, 0, 0}, b, 1, tl->n_buckets, n);
-                                first[s] = p;
-                                len[s] = n;
-                                cmd[s] = runs.g0 + (e.cmd - runs.cmd_first);
-                                longest = max(longest, n);
-                            }
-                        } else
                         for (uint32_t s = threadIdx.x; s < n_here; s += blockDim.x) {
                             const ListSource S = tl->src[s_base + s];
                             uint32_t n;
@@ -1164,7 +1132,7 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
             MSCHED_TICK(kTickCount, 5);
         }
         if (round + 1 < sg.rounds && (sg.n_ranges || kLists)) {
-            runs = wave_run(sg, range_runs, lists_resident);
+            if (kRuns) runs = wave_run(range_runs);
             __syncthreads();                              // the next tile repaints, and queues its ranges afresh
             if (threadIdx.x == 0) { s_paint.n_queued = 0; s_paint.floor = sg.G; }
             __syncthreads();
@@ -1208,12 +1176,24 @@ __device__ __forceinline__ void sum_rows(uint32_t *partial, uint32_t chunk, uint
 __global__ __launch_bounds__(kWave * kMaxWaves) void k_count(const uint32_t *__restrict__ page_table,
                                                               const uint32_t *__restrict__ nu, SweepGeom sg,
                                                               uint32_t *__restrict__ matrix,
-                                                              uint32_t *__restrict__ partial, const RangeRuns rr) {
+                                                              uint32_t *__restrict__ partial) {
     extern __shared__ uint32_t lds[];
     const uint32_t chunk = chunk_of_block(blockIdx.x, gridDim.x), n_keys = 2 * (sg.G + 1);
     uint32_t *group_row, *slice_row;
     sum_rows(partial, chunk, gridDim.x, n_keys, group_row, slice_row);
-    count_body<false>(page_table, nu, sg, chunk, lds, matrix + (size_t)chunk * n_keys, group_row, slice_row, nullptr, &rr);
+    count_body<false>(page_table, nu, sg, chunk, lds, matrix + (size_t)chunk * n_keys, group_row, slice_row);
+}
+
+// The same sweep for plans that brought no range list: the ranges are read from the tasks' mirrors, run by run.
+__global__ __launch_bounds__(kWave * kMaxWaves) void k_count_runs(const uint32_t *__restrict__ page_table,
+                                                                   const uint32_t *__restrict__ nu, SweepGeom sg,
+                                                                   uint32_t *__restrict__ matrix,
+                                                                   uint32_t *__restrict__ partial, const RangeRuns rr) {
+    extern __shared__ uint32_t lds[];
+    const uint32_t chunk = chunk_of_block(blockIdx.x, gridDim.x), n_keys = 2 * (sg.G + 1);
+    uint32_t *group_row, *slice_row;
+    sum_rows(partial, chunk, gridDim.x, n_keys, group_row, slice_row);
+    count_body<false, true>(page_table, nu, sg, chunk, lds, matrix + (size_t)chunk * n_keys, group_row, slice_row, nullptr, &rr);
 }
 
 // The first sweep with the id lists merged in (see count_body).  With 44 KiB of LDS a compute unit holds three
@@ -1229,12 +1209,12 @@ constexpr int kFusedThreads = kWave * kMaxWaves;
 #endif
 __global__ __launch_bounds__(kFusedThreads, MSCHED_FUSED_MIN_WAVES) void k_count_lists(const uint32_t *__restrict__ page_table, SweepGeom sg,
                                                               TileLists tl, uint32_t *__restrict__ matrix,
-                                                              uint32_t *__restrict__ partial, const RangeRuns rr) {
+                                                              uint32_t *__restrict__ partial) {
     extern __shared__ uint32_t lds[];
     const uint32_t chunk = tl.order[blockIdx.x], n_keys = 2 * (sg.G + 1);
     uint32_t *group_row, *slice_row;
     sum_rows(partial, chunk, gridDim.x, n_keys, group_row, slice_row);
-    count_body<true>(page_table, nullptr, sg, chunk, lds, matrix + (size_t)chunk * n_keys, group_row, slice_row, &tl, &rr);
+    count_body<true>(page_table, nullptr, sg, chunk, lds, matrix + (size_t)chunk * n_keys, group_row, slice_row, &tl);
 }
 
 // In-place exclusive scan of a[0..n) in LDS by the whole block (a multiple of 64 threads, at most
@@ -1299,8 +1279,6 @@ __device__ void chunk_order_block(const ChunkOrder &o) {
     }
 }
 static_assert(kMaxChunks <= 256 * 32, "a thread of chunk_order_block keeps its chunks' marks in one word");
-__global__ __launch_bounds__(256) void k_chunk_order(ChunkOrder co) { chunk_order_block(co); }
-
 
 // Budget cut, counts, victim threshold (implicit in the offsets) and per-class output offsets.
 //   D(k) = pages with nu < k; g_cut = largest k <= g_end0 with D(k) <= F            (cut)
@@ -1728,6 +1706,7 @@ hipError_t allow_large_lds() {
     if (done[dev]) return hipSuccess;
     const int bytes = 128 * 1024;
     if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_count), hipFuncAttributeMaxDynamicSharedMemorySize, bytes)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_count_runs), hipFuncAttributeMaxDynamicSharedMemorySize, bytes)) != hipSuccess) return e;
     if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_emit), hipFuncAttributeMaxDynamicSharedMemorySize, bytes)) != hipSuccess) return e;
     if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_tail), hipFuncAttributeMaxDynamicSharedMemorySize, bytes)) != hipSuccess) return e;
     done[dev] = true;
@@ -1739,13 +1718,6 @@ hipError_t launch_list_prepare(msched_ctx *c, const ListPrep *table_dev, uint32_
     (void)hipGetLastError();
     const size_t prep_lds = 4 * ((size_t)(1u << kBinSeenBits) + prep_part_buckets(n_buckets, split) + 1);
     k_list_prepare<<<n * split, kListThreads, prep_lds, c->stream>>>(table_dev, n_buckets, split, c->V, c->slot, c->bucket_mark);
-    return hipGetLastError();
-}
-
-hipError_t launch_chunk_order(msched_ctx *c, uint32_t n_chunks, uint32_t rounds) {
-    (void)hipGetLastError();
-    const uint32_t n_buckets = (uint32_t)((c->V + (1u << kBucketShift) - 1) >> kBucketShift);
-    k_chunk_order<<<1, 256, 0, c->stream>>>(ChunkOrder{c->bucket_mark, n_buckets, n_chunks, rounds, 1, c->bucket_mark + kMaxBuckets});
     return hipGetLastError();
 }
 
@@ -1768,27 +1740,17 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         // plans whose lists are prepared send only the two small tables (ranges, list pieces).
         const bool stage_records = g.needs_records &&
                                    ((uint64_t)g.G * c->max_rules * a.n_split > c->stage_threshold || g.live_list);
-        // Prepared lists whose pieces the first sweep finds through the tasks' list mirrors need no table either.
-        const bool lists_resident = fuse_lists && g.resident_lists;
-        const bool stage = stage_records || g.list_binned || (g.list_prepared && !lists_resident);
+        const bool stage = stage_records || g.list_prepared || g.list_binned;
         a.cmds = stage_records ? c->cmd_dev : nullptr;
         const bool copy_ranges = g.n_ranges && !g.single && !g.resident;   // resident: the sweep reads the tasks' mirrors
         const uint32_t n_records = stage_records ? g.G : 0u;
-        // The order in which the first sweep takes its chunks (those with ids first) only changes when a piece is
-        // prepared (a kernel behind that preparation rewrites it) or the geometry does: otherwise it is still there.
         ChunkOrder co{nullptr, 0, 0, 0, 0, nullptr};
-        const bool order_there = c->order_valid && c->order_chunks == g.n_chunks && c->order_rounds == g.rounds;
-        if (fuse_lists && !order_there) {
-            co = ChunkOrder{c->bucket_mark, g.n_buckets, g.n_chunks, g.rounds, 1, c->bucket_mark + kMaxBuckets};
-            if (!stage) { k_chunk_order<<<1, 256, 0, st>>>(co); co.bucket_mark = nullptr; }
-            c->order_chunks = g.n_chunks; c->order_rounds = g.rounds; c->order_valid = true;
-        }
-        if (fuse_lists && g.n_list_new) c->order_valid = false;      // this plan's own preparation comes after
+        if (fuse_lists) co = ChunkOrder{c->bucket_mark, g.n_buckets, g.n_chunks, g.rounds, 1, c->bucket_mark + kMaxBuckets};
         if (stage)
             k_stage<<<(std::max<uint32_t>(std::max(n_records * 8, (copy_ranges ? g.n_ranges : 0u) + g.n_list_sources), 1u) + 255) / 256 + (co.bucket_mark ? 1 : 0), 256, 0, st>>>(
                 c->cmd_ptrs_dev, n_records, c->cmd_dev, c->list_bucket_fill, g.list_binned ? g.n_buckets * 8 : 0,
                 c->ranges_host_dev, c->ranges_dev, copy_ranges ? g.n_ranges : 0, c->list_src_dev, c->list_src_stage,
-                g.list_prepared && !lists_resident ? g.n_list_sources : 0, co);
+                g.list_prepared ? g.n_list_sources : 0, co);
         else if (copy_ranges)
             k_copy_ranges<<<(g.n_ranges + 255) / 256, 256, 0, st>>>(c->ranges_host_dev, c->ranges_dev, g.n_ranges);
         // Id lists go first in three stream-ordered batches of growing size: the smallest g wins a page,
@@ -1828,24 +1790,25 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     sg.g_end0 = g.g_end0; sg.emit_hint = order_emit ? c->chunk_hint : nullptr;
     // one workgroup reads the range list where the host wrote it; many read a device copy, or the tasks' mirrors
     sg.ranges = g.single ? c->ranges_host_dev : g.resident ? nullptr : c->ranges_dev;
-    sg.range_runs = g.resident && g.n_ranges ? 1u : 0u;
-    const bool lists_resident = fuse_lists && g.resident_lists;
+    const bool from_mirrors = g.resident && g.n_ranges;
     RangeRuns by_wave;                                       // the launch's copy of the table, a line per wavefront
-    by_wave.n = by_wave.passes = by_wave.n_list = 0;
-    if (sg.range_runs || lists_resident) {
+    by_wave.n = 0;
+    if (from_mirrors) {
         const RangeRuns &r = c->range_runs;
-        const uint32_t W = fuse_lists ? (uint32_t)kFusedThreads / kWave : g.waves;     // r.n <= W <= kMaxRangeRuns
-        by_wave.n = r.n; by_wave.n_list = r.n_list;
+        const uint32_t W = g.waves;                          // r.n <= W <= kMaxRangeRuns
+        uint32_t passes = 0;                                 // passes that cover the longest run with the wavefronts it gets
+        for (uint32_t j = 0; j < r.n; ++j) {
+            const uint32_t waves_j = (W - j + r.n - 1) / r.n, rows = (r.run[j].count + kRangeRow - 1) / kRangeRow;
+            passes = std::max(passes, (rows + kRangesPerThread * waves_j - 1) / (kRangesPerThread * waves_j));
+        }
+        by_wave.n = r.n;
         for (uint32_t w = 0; w < W; ++w) {
-            const uint32_t j = w % r.n, waves_j = (W - j + r.n - 1) / r.n;
+            const uint32_t j = w % r.n;
             by_wave.run[w] = r.run[j];
-            by_wave.run[w].share = (w / r.n) | waves_j << 16;
-            // passes that cover the longest run with the wavefronts it gets
-            const uint32_t rows = (r.run[j].count + kRangeRow - 1) / kRangeRow;
-            by_wave.passes = std::max(by_wave.passes, (rows + kRangesPerThread * waves_j - 1) / (kRangesPerThread * waves_j));
+            by_wave.run[w].share = (w / r.n) | ((W - j + r.n - 1) / r.n) << 16;
+            by_wave.run[w].passes = passes;
         }
     }
-    const RangeRuns &rr = by_wave;
     if (prof) CK(hipEventRecord(c->ev[1], st));
     const uint32_t threads = g.waves * kWave;
     const size_t paint_lds = g.n_ranges ? (size_t)g.waves * g.steps * kWave * 4 : 0;
@@ -1879,15 +1842,17 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
         SweepGeom sc = sg;
         sc.steps = g.steps * g.waves / (kFusedThreads / kWave);       // the same tile, whatever the workgroup's width
         TileLists tl;
-        tl.src = lists_resident ? nullptr : c->list_src_stage; tl.n_src = lists_resident ? by_wave.n_list : g.n_list_sources;
-        tl.resident = lists_resident ? 1u : 0u;
+        tl.src = c->list_src_stage; tl.n_src = g.n_list_sources;
         tl.n_buckets = g.n_buckets; tl.split = g.split; tl.bucket_mark = c->bucket_mark;
         tl.order = c->bucket_mark + kMaxBuckets;
         const size_t lds = ((size_t)count_paint_offset(g.n_keys) + kBucketPages) * 4 + (size_t)kStagePieces * 16;
-        k_count_lists<<<g.n_chunks, kFusedThreads, lds, st>>>(c->page_table, sc, tl, c->matrix, few_rows ? nullptr : c->partial, rr);
+        k_count_lists<<<g.n_chunks, kFusedThreads, lds, st>>>(c->page_table, sc, tl, c->matrix, few_rows ? nullptr : c->partial);
     } else {
-        k_count<<<g.n_chunks, threads, (size_t)count_paint_offset(g.n_keys) * 4 + paint_lds, st>>>(c->page_table, c->nu, sg, c->matrix,
-                                                                    few_rows ? nullptr : c->partial, rr);
+        const size_t count_lds = (size_t)count_paint_offset(g.n_keys) * 4 + paint_lds;
+        if (from_mirrors)
+            k_count_runs<<<g.n_chunks, threads, count_lds, st>>>(c->page_table, c->nu, sg, c->matrix, few_rows ? nullptr : c->partial, by_wave);
+        else
+            k_count<<<g.n_chunks, threads, count_lds, st>>>(c->page_table, c->nu, sg, c->matrix, few_rows ? nullptr : c->partial);
     }
     if (prof) CK(hipEventRecord(c->ev[2], st));
     const uint32_t cut_threads = std::min<uint32_t>(1024, std::max<uint32_t>(256, (g.n_keys + 63) / 64 * 64));   // a key per thread

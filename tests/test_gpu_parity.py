@@ -447,14 +447,14 @@ def test_id_lists_prepared_in_parts_by_bucket_range(oracle_mod, monkeypatch, env
         assert lockstep(oracle_mod, trace, with_bytes=True, bytes_every=5) >= 16
 
 
-@pytest.mark.parametrize("env", [{"MSCHED_RESIDENT_LISTS": "1"}, {"MSCHED_RESIDENT_LISTS": "1", "MSCHED_LIST_AHEAD": "0"},
-                                 {"MSCHED_RESIDENT_LISTS": "1", "MSCHED_DEDUPE_REGIONS": "0"}, {"MSCHED_RESIDENT_RANGES": "0"}],
-                         ids=["lists-through-mirrors", "mirrors-filled-by-the-plans", "mirrors-no-repeats-dropped", "ranges-listed-per-plan"])
-def test_ranges_and_lists_through_the_tasks_mirrors(oracle_mod, monkeypatch, env):
-    """Sweeps of large tables read page ranges (and, switched on, the prepared id lists) through per-task mirrors in
-    device memory, a wavefront serving one run of the timeline, instead of through tables staged per plan: config 5
-    at 1/8 and 1/16 of its pages (full-size tiles, lists merged inside the first sweep), launches arriving as they
-    go, and the DL-training schedule (ranges only); the last case lists and copies the ranges per plan as before."""
+@pytest.mark.parametrize("env", [{}, {"MSCHED_DEDUPE_REGIONS": "0"}, {"MSCHED_RESIDENT_RANGES": "0"}],
+                         ids=["ranges-through-mirrors", "mirrors-no-repeats-dropped", "ranges-listed-per-plan"])
+def test_ranges_through_the_tasks_mirrors(oracle_mod, monkeypatch, env):
+    """Sweeps of large tables whose plans carry no id lists read the page ranges through per-task mirrors in device
+    memory, a wavefront serving one run of the timeline, instead of through a list made and copied per plan: the
+    DL-training and decode schedules at page sizes that give them multi-workgroup sweeps, launches arriving as they
+    go; plans with id lists (config 5 at 1/8 and 1/16 of its pages) keep their staged tables.  The last case lists
+    and copies the ranges per plan as before."""
     monkeypatch.setenv("MSCHED_LIST_BINNED_MIN_IDS", "0")
     for k, v in env.items():
         monkeypatch.setenv(k, v)
@@ -462,6 +462,8 @@ def test_ranges_and_lists_through_the_tasks_mirrors(oracle_mod, monkeypatch, env
         trace = make_trace(5, scale=scale, page_shift=6, n_launches=100)
         assert lockstep(oracle_mod, trace, with_bytes=True, bytes_every=5, lazy_slices=lazy) >= 16
     assert lockstep(oracle_mod, make_trace(3, page_shift=12, scale=32, layers=8, iterations=3), with_bytes=True, bytes_every=3) >= 4
+    assert lockstep(oracle_mod, make_trace(3, page_shift=12, scale=32, layers=8, iterations=4), with_bytes=False, lazy_slices=1) >= 6
+    assert lockstep(oracle_mod, make_trace(4, page_shift=12, layers=8, steps=24), with_bytes=True, bytes_every=5, lazy_slices=2) >= 10
 
 
 def test_id_lists_longer_than_one_prepared_piece(oracle_mod, monkeypatch):
