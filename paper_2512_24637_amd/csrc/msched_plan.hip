@@ -449,10 +449,18 @@ __global__ __launch_bounds__(kListThreads) void k_list_prepare(const ListPrep *_
             if (p[j] >= V) { if (part == 0) bad = 1; ok &= ~(1u << j); continue; }
             if ((p[j] >> kBucketShift) % split != part) ok &= ~(1u << j);   // another part's
         }
-        if (slot != nullptr) {
+        if (slot != nullptr) {                               // eight look-ups in flight (unconditional, at a clamped page: a load
+            constexpr int kSlotsAhead = 8;                   // under a condition waits inside its branch, one round trip per id)
+            static_assert(kPerThread % kSlotsAhead == 0, "whole batches");
 #pragma unroll
-            for (int j = 0; j < kPerThread; ++j)
-                if (((ok >> j) & 1u) && slot[p[j]] == kNone) { bad = 1; ok &= ~(1u << j); }
+            for (int j0 = 0; j0 < kPerThread; j0 += kSlotsAhead) {
+                uint32_t sl[kSlotsAhead];
+#pragma unroll
+                for (int u = 0; u < kSlotsAhead; ++u) sl[u] = slot[min((uint64_t)p[j0 + u], V - 1)];
+#pragma unroll
+                for (int u = 0; u < kSlotsAhead; ++u)
+                    if (((ok >> (j0 + u)) & 1u) && sl[u] == kNone) { bad = 1; ok &= ~(1u << (j0 + u)); }
+            }
         }
         MSCHED_TICK(kTickPrepare, 2);
         // Repeats are dropped through a table of pairs of entries: an id goes into the first entry of its
