@@ -729,10 +729,20 @@ int plan_body(msched_ctx *c, const msched_timeline_entry *tl, uint32_t n_entries
             RangeRuns &rr = c->range_runs;
             uint64_t total = 0;
             rr.n = 0;
-            for (const PlanRun &run : c->runs) {               // run j of the table is run j of the timeline
+            // Only what is in the mirrors already: ranges of launches queued since the last migration (or a task's
+            // first plan) are listed and copied once more - cheaper on the plan's path than an upload - and the
+            // migration that follows brings the mirrors up to date behind its copy.
+            bool all_there = true;
+            for (const PlanRun &run : c->runs) {
                 TaskQueue &t = c->tasks[run.task];
                 const uint64_t q0 = t.range_begin(run.first), q1 = t.range_end[run.first + run.count - 1 - t.base];
-                if (q1 > q0 && (t.rng_dev == nullptr || t.rng_uploaded < q1)) { const int rc_up = upload_ranges(c, t); if (rc_up) return rc_up; }
+                if (q1 > q0 && (t.rng_dev == nullptr || t.rng_uploaded < q1)) { t.want_mirror = true; all_there = false; }
+            }
+            if (!all_there) total = (uint64_t)kMaxResidentRanges + 1;
+            for (const PlanRun &run : c->runs) {               // run j of the table is run j of the timeline
+                if (!all_there) break;
+                TaskQueue &t = c->tasks[run.task];
+                const uint64_t q0 = t.range_begin(run.first), q1 = t.range_end[run.first + run.count - 1 - t.base];
                 total += q1 - q0;
                 if (total > kMaxResidentRanges) break;
                 RangeRun &r = rr.run[rr.n++];
@@ -960,7 +970,7 @@ int msched_migrate(msched_ctx *c, const msched_plan_t *plan) {
     // next plans find them there.
     if (c->resident_ranges)
         for (TaskQueue &t : c->tasks)
-            if (t.rng_dev != nullptr) { const int rc_up = upload_ranges(c, t); if (rc_up) return rc_up; }
+            if (t.want_mirror) { const int rc_up = upload_ranges(c, t); if (rc_up) return rc_up; }
     return MSCHED_OK;
 }
 

@@ -102,6 +102,7 @@ struct TaskQueue {
     uint64_t rng_cap = 0;                       // a power of two
     uint64_t rng_end = 0;                       // running index behind the last range
     uint64_t rng_uploaded = 0;                  // ranges with a running index below this are in the mirror
+    bool want_mirror = false;                   // a plan would have read this task's ranges from a mirror: keep one, filled behind migrations
     uint64_t ranges_base = 0;                   // running index of the first range of command `base`
     std::unordered_map<RegionSig, size_t, RegionSigHash> last_region;   // region -> latest command that described it
     size_t pruned_at = 0;                       // size of last_region after its last clean-up
