@@ -96,7 +96,7 @@ struct TaskQueue {
     std::vector<uint64_t> prep;                 // 1 + ring offset of the command's prepared id list (0 = none)
     // The commands' page ranges in program order: a ring in pinned host memory, the range with running index q at
     // q & (rng_cap - 1), and a mirror of it in device memory that the sweeps of large tables read (brought up to
-    // date behind every migration, or by the plan that first needs a range).  Ranges of retired commands are dead.
+    // date behind every migration; a plan reads it only when all its ranges are there).  Ranges of retired commands are dead.
     RangeRec *rng = nullptr;                    // pinned host memory [rng_cap]
     RangeRec *rng_dev = nullptr;                // device memory [rng_cap]
     uint64_t rng_cap = 0;                       // a power of two

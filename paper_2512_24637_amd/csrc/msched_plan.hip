@@ -759,42 +759,41 @@ __device__ __forceinline__ uint32_t range_passes(const SweepGeom &sg, const Wave
     if (!kRuns) return (sg.n_ranges + blockDim.x * kRangesPerThread - 1) / (blockDim.x * kRangesPerThread);
     return w.passes;
 }
-// This thread's ranges u0 .. u0 + kRangesInFlight - 1 (of kRangesPerThread) of pass `pass`: R[i] with live[i] set.
-// Their loads are asked for together (more at a time cost the sweeps a workgroup per compute unit in registers).
+// body(R) for every range this thread is to test in pass `pass`.  From a list: range (pass * 4 + j) * blockDim + thread.
+// From the mirrors: the wavefront's rows (pass * 4 + j) * waves + rank of its run, two loads in flight, both
+// unconditional at an index clamped into the run (under a condition a load is compiled as a branch with the wait for
+// it inside, and the two take a round trip each instead of one together; more at a time cost the sweep a workgroup
+// per compute unit in registers).
 constexpr uint32_t kRangesInFlight = 2;
 static_assert(kRangesPerThread % kRangesInFlight == 0, "whole batches");
-template <bool kRuns>
-__device__ __forceinline__ void pass_ranges(const SweepGeom &sg, const WaveRun &w, uint32_t pass, uint32_t u0,
-                                            PageRange (&R)[kRangesInFlight], bool (&live)[kRangesInFlight]) {
+template <bool kRuns, class Body>
+__device__ __forceinline__ void for_pass_ranges(const SweepGeom &sg, const WaveRun &w, uint32_t pass, Body body) {
     if (!kRuns) {
 #pragma unroll
-        for (uint32_t u = 0; u < kRangesInFlight; ++u) {
-            const uint32_t r = (pass * kRangesPerThread + u0 + u) * blockDim.x + threadIdx.x;
-            live[u] = r < sg.n_ranges;
-            if (live[u]) R[u] = sg.ranges[r];
+        for (uint32_t j = 0; j < kRangesPerThread; ++j) {
+            const uint32_t r = (pass * kRangesPerThread + j) * blockDim.x + threadIdx.x;
+            if (r >= sg.n_ranges) continue;
+            body(sg.ranges[r]);
         }
         return;
     }
-    // nothing left for this wavefront (the same answer in all its lanes): no loads at all
-    if (((pass * kRangesPerThread + u0) * w.waves + w.rank) * kRangeRow >= w.count) {
 #pragma unroll
-        for (uint32_t u = 0; u < kRangesInFlight; ++u) live[u] = false;
-        return;
-    }
-    uint4 v[kRangesInFlight];
+    for (uint32_t u0 = 0; u0 < kRangesPerThread; u0 += kRangesInFlight) {
+        // nothing left for this wavefront (the same answer in all its lanes): no loads at all
+        if (((pass * kRangesPerThread + u0) * w.waves + w.rank) * kRangeRow >= w.count) break;
+        uint4 v[kRangesInFlight];
+        bool live[kRangesInFlight];
 #pragma unroll
-    for (uint32_t u = 0; u < kRangesInFlight; ++u) {
-        const uint32_t k = ((pass * kRangesPerThread + u0 + u) * w.waves + w.rank) * kRangeRow + (uint32_t)lane_id();
-        live[u] = k < w.count;
-        // no branch around the load (under a condition it is compiled as a branch with the wait for the load inside,
-        // and the loads of a batch take a round trip each instead of one together)
-        v[u] = reinterpret_cast<const uint4 *>(w.ring)[(w.first + min(k, w.count - 1)) & w.mask];
-    }
+        for (uint32_t u = 0; u < kRangesInFlight; ++u) {
+            const uint32_t k = ((pass * kRangesPerThread + u0 + u) * w.waves + w.rank) * kRangeRow + (uint32_t)lane_id();
+            live[u] = k < w.count;
+            v[u] = reinterpret_cast<const uint4 *>(w.ring)[(w.first + min(k, w.count - 1)) & w.mask];
+        }
 #pragma unroll
-    for (uint32_t u = 0; u < kRangesInFlight; ++u) {                             // RangeRec {lo, hi, back, cmd}
-        R[u].lo = v[u].x; R[u].hi = v[u].y; R[u].pad = 0;
-        R[u].g = w.g0 + (v[u].w - w.cmd_first);
-        if (w.dedupe && v[u].z != 0 && (int32_t)(v[u].w - v[u].z - w.cursor) >= 0) live[u] = false;
+        for (uint32_t u = 0; u < kRangesInFlight; ++u) {                         // RangeRec {lo, hi, back, cmd}
+            if (w.dedupe && v[u].z != 0 && (int32_t)(v[u].w - v[u].z - w.cursor) >= 0) live[u] = false;
+            if (live[u]) body(PageRange{v[u].x, v[u].y, w.g0 + (v[u].w - w.cmd_first), 0u});
+        }
     }
 }
 static_assert(kRangeRow == (uint32_t)kWave, "a row of range entries is read by one wavefront");
@@ -808,32 +807,22 @@ __device__ __forceinline__ void paint_tile(const SweepGeom &sg, const WaveRun &r
     __syncthreads();
     const uint32_t passes = range_passes<kRuns>(sg, runs);           // a thread tests kRangesPerThread ranges per pass (a pass costs three barriers)
     for (uint32_t pass = 0; pass < passes; ++pass) {
-#pragma unroll
-        for (uint32_t u0 = 0; u0 < kRangesPerThread; u0 += kRangesInFlight) {
-        PageRange Rs[kRangesInFlight];
-        bool live[kRangesInFlight];
-        pass_ranges<kRuns>(sg, runs, pass, u0, Rs, live);
-#pragma unroll
-        for (uint32_t j = 0; j < kRangesInFlight; ++j) {
-            if (!live[j]) continue;
-            const PageRange R = Rs[j];
+        for_pass_ranges<kRuns>(sg, runs, pass, [&](const PageRange &R) {
             const uint64_t lo = max((uint64_t)R.lo, t0), hi = min((uint64_t)R.hi, t1);
-            if (lo < hi) {
-                if (lo == t0 && hi == t1) {
-                    atomicMin(&q.floor, R.g);
-                } else if (hi - lo <= kPaintSerial) {         // a few pages: painted here and now, by the thread that found them
+            if (lo >= hi) return;
+            if (lo == t0 && hi == t1) {
+                atomicMin(&q.floor, R.g);
+            } else if (hi - lo <= kPaintSerial) {             // a few pages: painted here and now, by the thread that found them
+                for (uint32_t i = (uint32_t)(lo - t0); i < (uint32_t)(hi - t0); ++i) atomicMin(&paint[i], R.g);
+            } else {                                          // many pages: queued for all threads together
+                const uint32_t at = atomicAdd(&q.n_queued, 1u);
+                if (at < kPaintQueue) {
+                    q.lo[at] = (uint32_t)(lo - t0); q.hi[at] = (uint32_t)(hi - t0); q.g[at] = R.g;
+                } else {                                      // queue full: paint it here after all
                     for (uint32_t i = (uint32_t)(lo - t0); i < (uint32_t)(hi - t0); ++i) atomicMin(&paint[i], R.g);
-                } else {                                      // many pages: queued for all threads together
-                    const uint32_t at = atomicAdd(&q.n_queued, 1u);
-                    if (at < kPaintQueue) {
-                        q.lo[at] = (uint32_t)(lo - t0); q.hi[at] = (uint32_t)(hi - t0); q.g[at] = R.g;
-                    } else {                                  // queue full: paint it here after all
-                        for (uint32_t i = (uint32_t)(lo - t0); i < (uint32_t)(hi - t0); ++i) atomicMin(&paint[i], R.g);
-                    }
                 }
             }
-        }
-        }
+        });
         __syncthreads();
         const uint32_t nq = min(q.n_queued, kPaintQueue);
         for (uint32_t w = 0; w < nq; ++w) {
@@ -860,28 +849,17 @@ constexpr uint32_t kPaintInRegisters = MSCHED_PAINT_IN_REGISTERS;
 template <bool kRuns>
 __device__ __forceinline__ uint32_t queue_ranges(const SweepGeom &sg, const WaveRun &runs, uint64_t t0, uint64_t t1, PaintLds &q) {
     const uint32_t passes = range_passes<kRuns>(sg, runs);
-    for (uint32_t pass = 0; pass < passes; ++pass) {
-#pragma unroll
-        for (uint32_t u0 = 0; u0 < kRangesPerThread; u0 += kRangesInFlight) {
-        PageRange Rs[kRangesInFlight];
-        bool live[kRangesInFlight];
-        pass_ranges<kRuns>(sg, runs, pass, u0, Rs, live);
-#pragma unroll
-        for (uint32_t j = 0; j < kRangesInFlight; ++j) {
-            if (!live[j]) continue;
-            const PageRange R = Rs[j];
+    for (uint32_t pass = 0; pass < passes; ++pass)
+        for_pass_ranges<kRuns>(sg, runs, pass, [&](const PageRange &R) {
             const uint64_t lo = max((uint64_t)R.lo, t0), hi = min((uint64_t)R.hi, t1);
-            if (lo < hi) {
-                if (lo == t0 && hi == t1) {
-                    atomicMin(&q.floor, R.g);
-                } else {
-                    const uint32_t at = atomicAdd(&q.n_queued, 1u);
-                    if (at < kPaintInRegisters) { q.lo[at] = (uint32_t)(lo - t0); q.hi[at] = (uint32_t)(hi - t0); q.g[at] = R.g; }
-                }
+            if (lo >= hi) return;
+            if (lo == t0 && hi == t1) {
+                atomicMin(&q.floor, R.g);
+            } else {
+                const uint32_t at = atomicAdd(&q.n_queued, 1u);
+                if (at < kPaintInRegisters) { q.lo[at] = (uint32_t)(lo - t0); q.hi[at] = (uint32_t)(hi - t0); q.g[at] = R.g; }
             }
-        }
-        }
-    }
+        });
     __syncthreads();
     return q.n_queued;
 }
@@ -1534,10 +1512,12 @@ __device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg
     uint32_t off_a[kKeysAhead], row_a[kKeysAhead], cnt_a[kKeysAhead];
 #pragma unroll
     for (int j = 0; j < kKeysAhead; ++j) {
-        const uint32_t k = threadIdx.x + j * blockDim.x;
-        off_a[j] = k < n_keys ? a.offsets[k] : kSkip;
-        row_a[j] = k < n_keys ? row[k] : 0u;
-        cnt_a[j] = (k < n_keys && cnt_row != nullptr) ? cnt_row[k] : 0u;
+        // unconditional loads at a clamped key (under a condition each is compiled as a branch with its own wait
+        // inside: six round trips in a row instead of one); the values of a key beyond the last are not used
+        const uint32_t k = min(threadIdx.x + j * blockDim.x, n_keys - 1);
+        off_a[j] = a.offsets[k];
+        row_a[j] = row[k];
+        cnt_a[j] = (cnt_row != nullptr ? cnt_row : row)[k];
     }
 #pragma unroll
     for (int j = 0; j < kKeysAhead; ++j) {
