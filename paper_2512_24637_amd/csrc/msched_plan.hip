@@ -755,9 +755,9 @@ __device__ __forceinline__ WaveRun wave_run(const RangeRuns *runs) {
     return w;
 }
 template <bool kRuns>
-__device__ __forceinline__ uint32_t range_passes(const SweepGeom &sg, const WaveRun &w) {
-    if (!kRuns) return (sg.n_ranges + blockDim.x * kRangesPerThread - 1) / (blockDim.x * kRangesPerThread);
-    return w.passes;
+__device__ __forceinline__ bool pass_left(const SweepGeom &sg, const WaveRun &w, uint32_t pass) {   // the same answer in every thread
+    if (!kRuns) return pass * blockDim.x * kRangesPerThread < sg.n_ranges;
+    return pass < w.passes;
 }
 // body(R) for every range this thread is to test in pass `pass`.  From a list: range (pass * 4 + j) * blockDim + thread.
 // From the mirrors: the wavefront's rows (pass * 4 + j) * waves + rank of its run, two loads in flight, both
@@ -805,8 +805,7 @@ __device__ __forceinline__ void paint_tile(const SweepGeom &sg, const WaveRun &r
     for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) paint[i] = sg.G;
     if (threadIdx.x == 0) { q.n_queued = 0; q.floor = sg.G; }
     __syncthreads();
-    const uint32_t passes = range_passes<kRuns>(sg, runs);           // a thread tests kRangesPerThread ranges per pass (a pass costs three barriers)
-    for (uint32_t pass = 0; pass < passes; ++pass) {
+    for (uint32_t pass = 0; pass_left<kRuns>(sg, runs, pass); ++pass) {   // a thread tests kRangesPerThread ranges per pass (a pass costs three barriers)
         for_pass_ranges<kRuns>(sg, runs, pass, [&](const PageRange &R) {
             const uint64_t lo = max((uint64_t)R.lo, t0), hi = min((uint64_t)R.hi, t1);
             if (lo >= hi) return;
@@ -848,8 +847,7 @@ constexpr uint32_t kPaintInRegisters = MSCHED_PAINT_IN_REGISTERS;
 // The queue is empty on entry (count_body resets it ahead of a barrier it needs anyway).
 template <bool kRuns>
 __device__ __forceinline__ uint32_t queue_ranges(const SweepGeom &sg, const WaveRun &runs, uint64_t t0, uint64_t t1, PaintLds &q) {
-    const uint32_t passes = range_passes<kRuns>(sg, runs);
-    for (uint32_t pass = 0; pass < passes; ++pass)
+    for (uint32_t pass = 0; pass_left<kRuns>(sg, runs, pass); ++pass)
         for_pass_ranges<kRuns>(sg, runs, pass, [&](const PageRange &R) {
             const uint64_t lo = max((uint64_t)R.lo, t0), hi = min((uint64_t)R.hi, t1);
             if (lo >= hi) return;
