@@ -727,6 +727,7 @@ __host__ __device__ inline uint32_t count_paint_offset(uint32_t n_keys) { return
 constexpr uint32_t kPaintQueue = 64;                      // partial ranges queued per batch; a tile meets a handful (LDS decides how
                                                           // many sweep workgroups a compute unit holds)
 constexpr uint32_t kPaintSerial = 32;                     // ranges up to this many pages are painted by one thread
+constexpr uint32_t kPaintByAll = 256;                     // queued ranges up to this many pages are painted by one wavefront, longer ones by all threads
 
 struct PaintLds {
     uint32_t n_queued, floor;
@@ -813,8 +814,12 @@ __device__ __forceinline__ void paint_tile(const SweepGeom &sg, const WaveRun &r
                 atomicMin(&q.floor, R.g);
             } else if (hi - lo <= kPaintSerial) {             // a few pages: painted here and now, by the thread that found them
                 for (uint32_t i = (uint32_t)(lo - t0); i < (uint32_t)(hi - t0); ++i) atomicMin(&paint[i], R.g);
-            } else {                                          // many pages: queued for all threads together
-                const uint32_t at = atomicAdd(&q.n_queued, 1u);
+            } else {                                          // many pages: queued (the lanes that are here together share one reservation)
+                const uint64_t here = __ballot(true);
+                const int leader = __ffsll((long long)here) - 1;
+                uint32_t at = 0;
+                if (lane_id() == leader) at = atomicAdd(&q.n_queued, (uint32_t)__popcll(here));
+                at = __shfl(at, leader, kWave) + (uint32_t)__popcll(here & lanes_below());
                 if (at < kPaintQueue) {
                     q.lo[at] = (uint32_t)(lo - t0); q.hi[at] = (uint32_t)(hi - t0); q.g[at] = R.g;
                 } else {                                      // queue full: paint it here after all
@@ -823,10 +828,18 @@ __device__ __forceinline__ void paint_tile(const SweepGeom &sg, const WaveRun &r
             }
         });
         __syncthreads();
+        // the queue: a long range is painted by all threads together, the others by a wavefront each (a tile of many
+        // ranges of some dozens of pages - the tiny schedule's one tile meets 40 - would otherwise walk them one by one)
         const uint32_t nq = min(q.n_queued, kPaintQueue);
         for (uint32_t w = 0; w < nq; ++w) {
             const uint32_t lo = q.lo[w], hi = q.hi[w];
-            for (uint32_t i = lo + threadIdx.x; i < hi; i += blockDim.x) atomicMin(&paint[i], q.g[w]);
+            if (hi - lo > kPaintByAll)
+                for (uint32_t i = lo + threadIdx.x; i < hi; i += blockDim.x) atomicMin(&paint[i], q.g[w]);
+        }
+        for (uint32_t w = threadIdx.x / kWave; w < nq; w += blockDim.x / kWave) {
+            const uint32_t lo = q.lo[w], hi = q.hi[w];
+            if (hi - lo <= kPaintByAll)
+                for (uint32_t i = lo + (uint32_t)lane_id(); i < hi; i += kWave) atomicMin(&paint[i], q.g[w]);
         }
         __syncthreads();
         if (threadIdx.x == 0) q.n_queued = 0;
@@ -840,8 +853,11 @@ __device__ __forceinline__ void paint_tile(const SweepGeom &sg, const WaveRun &r
 // in LDS.  Returns how many ranges were offered to the queue, the same number to every thread: above
 // kPaintInRegisters the caller paints the tile in LDS instead (after a barrier of its own: paint_tile resets the
 // queue).
+// (Applying a queued range costs every lane about 30 instructions per eight pages: up to 32 ranges that is cheaper
+// than painting the tile in LDS - three barriers and a pass over the tile - beyond it is not.  Measured with 8, 16, 32
+// and 64: 32 is best on the tiny, the training and the decode schedule.)
 #ifndef MSCHED_PAINT_IN_REGISTERS
-#define MSCHED_PAINT_IN_REGISTERS 64
+#define MSCHED_PAINT_IN_REGISTERS 32
 #endif
 constexpr uint32_t kPaintInRegisters = MSCHED_PAINT_IN_REGISTERS;
 // The queue is empty on entry (count_body resets it ahead of a barrier it needs anyway).
@@ -1055,7 +1071,10 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
         // ranges of a tile without id lists: queued and applied from registers when they are few
         auto paint_ranges = [&]() -> int {
             if (!sg.n_ranges) return kPaintNone;
-            if (queue_ranges<kRuns>(sg, runs, tile_begin, tile_end, s_paint) <= kPaintInRegisters) return kPaintQueued;
+            // (a tile that is the whole table meets every range: with more ranges than can be applied from registers
+            // there is no point in queueing them first)
+            const bool all_partial = tile_begin == 0 && tile_end == sg.V && sg.n_ranges > kPaintInRegisters;
+            if (!all_partial && queue_ranges<kRuns>(sg, runs, tile_begin, tile_end, s_paint) <= kPaintInRegisters) return kPaintQueued;
             __syncthreads();                                  // everybody has read the count
             paint_tile<kRuns>(sg, runs, tile_begin, tile_end, paint, s_paint);
             return kPaintLds;
