@@ -829,17 +829,22 @@ __device__ __forceinline__ void paint_tile(const SweepGeom &sg, const WaveRun &r
         });
         __syncthreads();
         // the queue: a long range is painted by all threads together, the others by a wavefront each (a tile of many
-        // ranges of some dozens of pages - the tiny schedule's one tile meets 40 - would otherwise walk them one by one)
+        // ranges of some dozens of pages - the tiny schedule's one tile meets 40 - would otherwise walk them one by one).
+        // Every wavefront reads the whole queue at once, an entry per lane, and hands the entries round from there: read
+        // one by one from LDS, 40 entries were 3 us of round trips.
+        static_assert(kPaintQueue <= (uint32_t)kWave, "an entry of the queue per lane");
         const uint32_t nq = min(q.n_queued, kPaintQueue);
-        for (uint32_t w = 0; w < nq; ++w) {
-            const uint32_t lo = q.lo[w], hi = q.hi[w];
-            if (hi - lo > kPaintByAll)
-                for (uint32_t i = lo + threadIdx.x; i < hi; i += blockDim.x) atomicMin(&paint[i], q.g[w]);
+        const uint32_t l = (uint32_t)lane_id();
+        const uint32_t my_lo = l < nq ? q.lo[l] : 0u, my_hi = l < nq ? q.hi[l] : 0u, my_g = l < nq ? q.g[l] : 0u;
+        for (uint64_t far = __ballot(my_hi - my_lo > kPaintByAll); far; far &= far - 1) {
+            const int e = __ffsll((long long)far) - 1;
+            const uint32_t lo = __shfl(my_lo, e, kWave), hi = __shfl(my_hi, e, kWave), g = __shfl(my_g, e, kWave);
+            for (uint32_t i = lo + threadIdx.x; i < hi; i += blockDim.x) atomicMin(&paint[i], g);
         }
-        for (uint32_t w = threadIdx.x / kWave; w < nq; w += blockDim.x / kWave) {
-            const uint32_t lo = q.lo[w], hi = q.hi[w];
+        for (uint32_t e = threadIdx.x / kWave; e < nq; e += blockDim.x / kWave) {
+            const uint32_t lo = __shfl(my_lo, (int)e, kWave), hi = __shfl(my_hi, (int)e, kWave), g = __shfl(my_g, (int)e, kWave);
             if (hi - lo <= kPaintByAll)
-                for (uint32_t i = lo + (uint32_t)lane_id(); i < hi; i += kWave) atomicMin(&paint[i], q.g[w]);
+                for (uint32_t i = lo + l; i < hi; i += kWave) atomicMin(&paint[i], g);
         }
         __syncthreads();
         if (threadIdx.x == 0) q.n_queued = 0;
@@ -1320,7 +1325,9 @@ __device__ __forceinline__ uint32_t wave_exclusive_scan(uint32_t n, Value value,
     return total;
 }
 
-__device__ void cut_body(const CutArgs &a, uint32_t *lds) {
+// off_lds / hdr_lds (the single-workgroup kernel): the offsets and the header are also left in LDS, where the second
+// sweep of the same workgroup finds them without a trip to memory.
+__device__ void cut_body(const CutArgs &a, uint32_t *lds, uint32_t *off_lds = nullptr, PlanHeader *hdr_lds = nullptr) {
     const uint32_t G = a.G, K = G + 1, n_keys = 2 * K, g_end0 = a.g_end0, nthreads = blockDim.x;
     uint32_t *tot = lds;                 // [n_keys]
     __shared__ uint32_t s_cut, s_res, s_fetch;
@@ -1371,17 +1378,26 @@ __device__ void cut_body(const CutArgs &a, uint32_t *lds) {
         // fetch offsets: classes 0 .. g_cut - 1 of the pages that are not resident, in order of use
         const uint32_t n_fetch = wave_exclusive_scan(K, [&](uint32_t c) { return c < g_cut ? tot[c] : 0u; },
                                                      [&](uint32_t c, uint32_t before, uint32_t v) {
-                                                         a.offsets[c] = (c < g_cut) ? before : kSkip;
+                                                         const uint32_t at = (c < g_cut) ? before : kSkip;
+                                                         a.offsets[c] = at;
+                                                         if (off_lds) off_lds[c] = at;
                                                          // early execution: command c may start once the fetches of classes 0..c have landed
                                                          if (a.need_host && c < g_cut) a.need_host[c] = before + v;
                                                      });
-        if (a.need_host) __threadfence_system();           // need[] is in host memory: ahead of the header's stamp
+        if (a.need_host) {                                  // need[] is in host memory: acknowledged ahead of the header's stamp
+            __builtin_amdgcn_s_waitcnt(0);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        }
         if (tid == 0) s_fetch = n_fetch;
     }
     if (wave == last_wave) {
         // victim offsets, farthest next use first: resident classes G (never used), G - 1, ..., g_cut
         wave_exclusive_scan(K, [&](uint32_t j) { return (G - j >= g_cut) ? tot[K + (G - j)] : 0u; },
-                            [&](uint32_t j, uint32_t before, uint32_t) { a.offsets[K + (G - j)] = (G - j >= g_cut) ? before : kSkip; });
+                            [&](uint32_t j, uint32_t before, uint32_t) {
+                                const uint32_t at = (G - j >= g_cut) ? before : kSkip;
+                                a.offsets[K + (G - j)] = at;
+                                if (off_lds) off_lds[K + (G - j)] = at;
+                            });
         if (a.landed && (tid % kWave) == 0) {   // entries landed, work units handed out, start of the migration kernel
             a.landed[0] = 0; a.landed[1] = 0; a.landed[2] = 0; a.landed[3] = 0;
         }
@@ -1401,12 +1417,18 @@ __device__ void cut_body(const CutArgs &a, uint32_t *lds) {
         h.n_free_used = min(n_free, n_fetch);
         h.n_evict = n_fetch - h.n_free_used;
         h.g_cut = g_cut; h.n_resident = n_res; h.status = status; h.first_free = n_res; h.seq = 0;
+        if (hdr_lds) *hdr_lds = h;
         *a.hdr_dev = h;
         // The host waits for the stamp, not for the end of the kernel: the counts (and need[]) go first, the stamp
-        // after a system-scope fence, so that whoever sees the stamp sees them.
+        // once they have been acknowledged, so that whoever sees the stamp sees them.  The header and need[] lie in
+        // pinned host memory, which no cache of the device holds: what orders the stores is the wait for their
+        // acknowledgement, written out here (s_waitcnt 0; the workgroup-scope fence keeps the compiler from moving
+        // stores across it).  A system-scope release would add a write-back of the L2 in front of the same wait -
+        // 0.7 us after a sweep that has just written every page's class.
         *a.hdr_host = h;
-        __threadfence_system();
-        __hip_atomic_store(&a.hdr_host->seq, a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        __builtin_amdgcn_s_waitcnt(0);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __hip_atomic_store(&a.hdr_host->seq, a.seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
     MSCHED_TICK(kTickCut, 4);
 }
@@ -1488,30 +1510,43 @@ __host__ __device__ inline size_t emit_lds_words(uint32_t waves, uint32_t n_keys
     return (((size_t)(waves + 1) * n_keys + 3) & ~(size_t)3) + (size_t)waves * (kMaxSteps * kWave / 2);   // staging lines 16-byte aligned
 }
 
-__device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg, uint32_t chunk, uint32_t *lds) {
+// The classes of a wavefront's slice (up to 1024 pages, 2 bytes each) are two 16-byte loads per lane; the lanes
+// then exchange them through LDS, because lane l ranks pages l, 64 + l, ... (page order inside a step), not
+// 16 l .. 16 l + 15.
+constexpr uint32_t kLanePages = kMaxSteps * kWave / kWave;                    // consecutive pages a lane requests
+static_assert(kLanePages == 16, "two uint4 of 16-bit classes per lane cover the slice");
+struct SliceClasses { uint4 lo, hi; };
+__device__ __forceinline__ SliceClasses request_slice(const SweepGeom &sg, uint32_t chunk, uint32_t round) {
+    const uint32_t waves = blockDim.x / kWave, wave = threadIdx.x / kWave, lane = (uint32_t)lane_id();
+    const uint64_t p_begin = (uint64_t)chunk * sg.chunk_pages;
+    const uint64_t p_end = min(sg.V, p_begin + sg.chunk_pages);
+    const uint64_t tile_pages = (uint64_t)waves * sg.steps * kWave;
+    const uint4 none4 = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};     // kNoKey16 in every half
+    const uint64_t first = p_begin + round * tile_pages + (uint64_t)wave * sg.steps * kWave + lane * kLanePages;
+    // pages past the chunk's end are masked when the classes are read back; the array is padded past V
+    if (lane * kLanePages >= sg.steps * kWave || first >= p_end) return SliceClasses{none4, none4};
+    const uint4 *src = reinterpret_cast<const uint4 *>(sg.key16 + first);
+    return SliceClasses{src[0], src[1]};
+}
+
+// kSingle (the single-workgroup kernel): the cut of the same workgroup has left the header in *hdr_lds and the
+// offsets where the running positions go, and the first slice's classes (written by this workgroup's own first
+// sweep) were asked for before the cut: nothing is read from memory before the pages are ranked.
+template <bool kSingle = false>
+__device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg, uint32_t chunk, uint32_t *lds,
+                                          const PlanHeader *hdr_lds = nullptr, const SliceClasses *first_slice = nullptr) {
     const uint32_t K = sg.G + 1, n_keys = 2 * K;
     const uint32_t waves = blockDim.x / kWave, wave = threadIdx.x / kWave;
     const int lane = lane_id();
     const uint64_t p_begin = (uint64_t)chunk * sg.chunk_pages;
     const uint64_t p_end = min(sg.V, p_begin + sg.chunk_pages);
     const uint64_t tile_pages = (uint64_t)waves * sg.steps * kWave;
-    // The classes of a wavefront's slice (up to 1024 pages, 2 bytes each) are two 16-byte loads per lane; the lanes
-    // then exchange them through LDS, because lane l ranks pages l, 64 + l, ... (page order inside a step), not
-    // 16 l .. 16 l + 15.
-    constexpr uint32_t kLanePages = kMaxSteps * kWave / kWave;                    // consecutive pages a lane requests
-    static_assert(kLanePages == 16, "two uint4 of 16-bit classes per lane cover the slice");
-    struct Raw { uint4 lo, hi; };
-    const uint4 none4 = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};     // kNoKey16 in every half
-    auto request_slice = [&](uint32_t round) -> Raw {
-        const uint64_t first = p_begin + round * tile_pages + (uint64_t)wave * sg.steps * kWave + (uint32_t)lane * kLanePages;
-        // pages past the chunk's end are masked when the classes are read back; the array is padded past V
-        if ((uint32_t)lane * kLanePages >= sg.steps * kWave || first >= p_end) return Raw{none4, none4};
-        const uint4 *src = reinterpret_cast<const uint4 *>(sg.key16 + first);
-        return Raw{src[0], src[1]};
-    };
     MSCHED_TICK(kTickEmit, 0);
-    const uint32_t n_fetch = a.hdr->n_fetch, n_evict = a.hdr->n_evict;
-    const uint32_t n_free_used = a.hdr->n_free_used, first_free = a.hdr->first_free;
+    SliceClasses raw{};
+    if (kSingle) raw = *first_slice;
+    const PlanHeader *hdr = kSingle ? hdr_lds : a.hdr;
+    const uint32_t n_fetch = hdr->n_fetch, n_evict = hdr->n_evict;
+    const uint32_t n_free_used = hdr->n_free_used, first_free = hdr->first_free;
     if (n_fetch == 0) return;                             // same for every thread of the block
     uint32_t *base = lds + waves * n_keys;               // [n_keys] running output position per key
     uint32_t *hist = lds + wave * n_keys;
@@ -1525,6 +1560,7 @@ __device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg
     // chunk is known to have work: three chunks in four of a large table have none, and loads come back in the
     // order they were issued, so a request for classes (memory) in front would hold up the tables (cache hits)
     // for nothing (measured: classes first 70.4 us per plan, between tables and their use 69.7, here 68.4).
+    if (!kSingle) {
     constexpr int kKeysAhead = 2;
     uint32_t off_a[kKeysAhead], row_a[kKeysAhead], cnt_a[kKeysAhead];
 #pragma unroll
@@ -1553,9 +1589,10 @@ __device__ __forceinline__ void emit_body(const EmitArgs &a, const SweepGeom &sg
     }
     MSCHED_TICK(kTickEmit, 1);
     if (!__syncthreads_or(live)) return;
-    Raw raw = request_slice(0);
+    raw = request_slice(sg, chunk, 0);
+    }
     for (uint32_t round = 0; round < sg.rounds; ++round) {
-        if (round) raw = request_slice(round);
+        if (round) raw = request_slice(sg, chunk, round);
         for (uint32_t i = threadIdx.x; i < waves * n_keys; i += blockDim.x) lds[i] = 0;
         reinterpret_cast<uint4 *>(stage + lane * kLanePages)[0] = raw.lo;      // read back by this wavefront only
         reinterpret_cast<uint4 *>(stage + lane * kLanePages)[1] = raw.hi;
@@ -1639,12 +1676,14 @@ __global__ __launch_bounds__(kWave * kMaxWaves) void k_tail(SweepGeom sg, CutArg
         for (uint32_t i = threadIdx.x; i < sg.n_ranges; i += blockDim.x) s_inl[i] = inl.r[i];
         sg.ranges = s_inl;
     }
+    __shared__ PlanHeader s_hdr;
     count_body<false>(ea.page_table, ea.nu, sg, 0, lds, ca.groups, nullptr, nullptr);
     __syncthreads();
+    const SliceClasses first_slice = request_slice(sg, 0, 0);   // the sweep has written them; on their way during the cut
     ca.counts_in_lds = 1;                                 // the only chunk's counts are where the sweep left them
-    cut_body(ca, lds);
+    cut_body(ca, lds, lds + (blockDim.x / kWave) * 2 * (sg.G + 1), &s_hdr);   // the offsets: where emit_body keeps its running positions
     __syncthreads();
-    emit_body(ea, sg, 0, lds);
+    emit_body<true>(ea, sg, 0, lds, &s_hdr, &first_slice);
 }
 
 __global__ __launch_bounds__(256) void k_zero(uint32_t *dst, uint64_t n) {
