@@ -195,6 +195,30 @@ struct Analyzer {
         return true;
     }
 
+    // whole wave: verify() for the empty subset, written out - the product is 1, so the coefficient is the first used
+    // invocation's value, which must not be zero, and every used invocation must show the same value.  Most regions
+    // have an invariant extent and end their search here: no product, no division.
+    __device__ __forceinline__ bool verify_invariant(uint64_t &c_out) const {
+        uint64_t c = 0;
+        bool have_c = false, differs = false;
+        for (uint32_t i0 = 0; i0 < n_inv; i0 += kWave) {
+            const uint32_t i = i0 + lane;
+            const bool act = i < n_inv && used(i);
+            const uint64_t v = act ? val[i] : 0;
+            if (!have_c) {
+                const uint64_t m = __ballot(act);
+                if (!m) continue;
+                c = __shfl((unsigned long long)v, __ffsll((unsigned long long)m) - 1);
+                if (c == 0) return false;
+                have_c = true;
+            }
+            differs |= act && v != c;
+        }
+        if (!have_c || __ballot(differs)) return false;
+        c_out = c;
+        return true;
+    }
+
     // whole wave: the lowest-ranked subset that fits
     __device__ __forceinline__ bool search(Subset &S_out, uint64_t &c_out) const {
         // screen on the first (up to three) used invocations of the first 64-invocation block that has any
@@ -210,7 +234,7 @@ struct Analyzer {
         // {} first and on its own: most regions have an invariant extent (template T1) and need nothing else;
         // then the single arguments, then pairs and triples a wavefront at a time
         Subset none;
-        if (verify(none, c_out)) { S_out = none; return true; }
+        if (verify_invariant(c_out)) { S_out = none; return true; }
         const uint32_t n_cand = n_singles;
         for (uint32_t r0 = 1; r0 < n_subsets;) {
             const uint32_t r1 = min(r0 <= n_cand ? 1 + n_cand : r0 + kWave, n_subsets);
@@ -261,29 +285,6 @@ __device__ __forceinline__ void rule_words(uint32_t kind, uint32_t base_arg, con
 }
 
 constexpr uint32_t kHead = 8;                     // intervals of an invocation that its lane keeps in registers
-
-// The value itself, but of unknown origin to the optimizer: a tree of selects over the elements of a local array is
-// otherwise rewritten as one load at a computed index, which moves the array from registers to scratch memory.
-__device__ __forceinline__ uint64_t from_register(uint64_t v) {
-    asm("" : "+v"(v));
-    return v;
-}
-
-// entry m (0..7) of eight values a lane holds, where m differs from lane to lane: a tree of selects, no memory
-__device__ __forceinline__ ulonglong2 pick8(const ulonglong2 (&c)[kHead], uint32_t m) {
-    const bool b0 = m & 1, b1 = m & 2, b2 = m & 4;
-    uint64_t x[kHead], y[kHead];
-    #pragma unroll
-    for (uint32_t j = 0; j < kHead; ++j) { x[j] = from_register(c[j].x); y[j] = from_register(c[j].y); }
-    ulonglong2 lo, hi, r;
-    lo.x = b1 ? (b0 ? x[3] : x[2]) : (b0 ? x[1] : x[0]);
-    lo.y = b1 ? (b0 ? y[3] : y[2]) : (b0 ? y[1] : y[0]);
-    hi.x = b1 ? (b0 ? x[7] : x[6]) : (b0 ? x[5] : x[4]);
-    hi.y = b1 ? (b0 ? y[7] : y[6]) : (b0 ? y[5] : y[4]);
-    r.x = b2 ? hi.x : lo.x;
-    r.y = b2 ? hi.y : lo.y;
-    return r;
-}
 
 // intervals mo .. mo + 7 of one invocation's row (indices clamped to the row: every row has max_iv entries allocated)
 __device__ __forceinline__ void load8(const ulonglong2 *row, uint32_t mo, uint32_t max_iv, ulonglong2 (&c)[kHead]) {
@@ -425,11 +426,6 @@ __global__ __launch_bounds__(kWave) void k_analyze(AnaArgs a) {
         return at;
     };
     const uint32_t own_bases_at = lane < n_inv ? bases_at(lane) : 0;
-    // interval m of invocation i, for the lane that owns the invocation (i = lane, lane + 64, ...)
-    auto interval = [&](uint32_t i, uint32_t m) __attribute__((always_inline)) -> ulonglong2 {
-        if (i < kWave && m < kHead) return pick8(head, m);
-        return g_iv[(size_t)i * max_iv + m];
-    };
     ANA_TICK(3);
     an.n_inv = n_inv; an.lane = lane; an.s_args = s_args; an.count = count;
     an.cand = s_cand; an.n_subsets = n_subsets; an.n_singles = nc;
@@ -442,12 +438,31 @@ __global__ __launch_bounds__(kWave) void k_analyze(AnaArgs a) {
         for (uint32_t i = lane; i < n_inv; i += kWave) {
             const uint64_t *arow = s_args + i * MSCHED_MAX_ARGS;
             const uint32_t n = s_niv[i], m0 = s_m0[arg * n_inv + i];
-            const ulonglong2 first = interval(i, m0);
-            const uint64_t len = first.y;
             const uint32_t at = i < kWave ? own_bases_at : bases_at(i);
-            uint64_t st = 0, cnt = 1, prev = first.x;
-            for (uint32_t m = m0 + 1; m < n; ++m) {
-                const ulonglong2 next = interval(i, m);
+            uint64_t len = 0, st = 0, cnt = 1, prev = 0;
+            uint32_t m = m0 + 1;                                  // the next interval to look at
+            bool stopped = false;
+            if (i < kWave && m0 < kHead) {
+                // The lane's own first eight intervals are in its registers: walked in order with fixed indices (the
+                // run starts at a different one in every lane), which costs a dozen instructions an interval where a
+                // select over the eight for a lane's own index costs sixty.
+                #pragma unroll
+                for (uint32_t j = 0; j < kHead; ++j) {
+                    const ulonglong2 cur = head[j];
+                    if (j == m0) { len = cur.y; prev = cur.x; }
+                    else if (j > m0 && j < n && !stopped) {
+                        const uint64_t gap = cur.x - prev;
+                        if (cur.y != len || ((at >> j) & 1) || (cnt > 1 && gap != st)) stopped = true;
+                        else { st = gap; prev = cur.x; ++cnt; }
+                    }
+                }
+                m = kHead;
+            } else {
+                const ulonglong2 first = g_iv[(size_t)i * max_iv + m0];
+                len = first.y; prev = first.x;
+            }
+            for (; !stopped && m < n; ++m) {
+                const ulonglong2 next = g_iv[(size_t)i * max_iv + m];
                 bool other = next.y != len;
                 if (m < 32) other |= (at >> m) & 1;
                 else
