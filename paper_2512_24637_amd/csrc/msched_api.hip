@@ -318,7 +318,8 @@ int msched_create(const msched_config *cfg, msched_ctx **out) {
     ALLOC(c->flags, 256);
     ALLOC(c->offsets, (size_t)2 * (MSCHED_MAX_TIMELINE_COMMANDS + 1) * 4);
     ALLOC(c->hdr_dev, sizeof(PlanHeader));
-    ALLOC(c->chunk_hint, (size_t)2 * kMaxChunks * 4);
+    ALLOC(c->chunk_hint, (size_t)3 * kMaxChunks * 4);
+    if (rc == MSCHED_OK && (e = hipMemset(c->chunk_hint, 0, (size_t)3 * kMaxChunks * 4)) != hipSuccess) fail(e);
     // row-group sums of the count matrix: the counting sweep adds into them, k_offsets clears what it read
     ALLOC(c->partial, (size_t)kSumRows * 2 * (MSCHED_MAX_TIMELINE_COMMANDS + 1) * 4);
     if (rc == MSCHED_OK && (e = hipMemset(c->partial, 0, (size_t)kSumRows * 2 * (MSCHED_MAX_TIMELINE_COMMANDS + 1) * 4)) != hipSuccess) fail(e);

@@ -259,7 +259,8 @@ struct msched_ctx {
     uint32_t *evict_pages = nullptr, *evict_frames = nullptr, *fetch_pages = nullptr, *fetch_frames = nullptr;
     uint32_t *flags = nullptr;                  // device status word
     uint32_t *matrix = nullptr; size_t matrix_cap = 0;       // [n_chunks][n_keys] counts; behind them [matrix_cap...) the chunks' start positions
-    uint32_t *chunk_hint = nullptr;                          // [2][kMaxChunks]: what the first sweep saw per chunk for the second; the second sweep's chunk order
+    uint32_t *chunk_hint = nullptr;                          // [3][kMaxChunks]: what the first sweep saw per chunk for the second; the second sweep's chunk order;
+                                                             // how a chunk's ranges were painted by the last plans (SweepGeom::paint_hint)
     uint32_t *partial = nullptr;                             // [kSumRows][n_keys] sums by row group, then by slice; all zero between plans
     uint32_t *offsets = nullptr;                // [2 * (MAX_G + 1)] per-class output offsets
     msched::PlanHeader *hdr_dev = nullptr;      // device

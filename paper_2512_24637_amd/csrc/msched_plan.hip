@@ -710,6 +710,7 @@ struct SweepGeom {
     uint16_t *key16;          // [V] class key of every page, written by the first sweep for the second
     uint32_t g_end0;          // commands of the first timeline entry: only their pages can be fetched
     uint32_t *emit_hint;      // [n_chunks] or null: what the first sweep saw in a chunk that the second may have to list
+    uint32_t *paint_hint;     // [n_chunks] or null: plans left for which the chunk's tiles are painted in LDS without trying the queue first
                               // (2: a page that may be fetched, 1: a resident page the first entry does not use)
 };
 constexpr uint16_t kNoKey16 = 0xffff;                  // keys are below 2 * (MSCHED_MAX_TIMELINE_COMMANDS + 1) = 6144
@@ -727,6 +728,7 @@ __host__ __device__ inline uint32_t count_paint_offset(uint32_t n_keys) { return
 constexpr uint32_t kPaintQueue = 64;                      // partial ranges queued per batch; a tile meets a handful (LDS decides how
                                                           // many sweep workgroups a compute unit holds)
 constexpr uint32_t kPaintSerial = 32;                     // ranges up to this many pages are painted by one thread
+constexpr uint32_t kPaintHintPlans = 16;                  // plans a chunk paints in LDS straight away after its queue has overflowed
 constexpr uint32_t kPaintByAll = 256;                     // queued ranges up to this many pages are painted by one wavefront, longer ones by all threads
 
 struct PaintLds {
@@ -994,6 +996,12 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
     for (uint32_t i = threadIdx.x; i < n_keys; i += blockDim.x) lds[i] = 0;
     if (threadIdx.x == 0) { s_paint.n_queued = 0; s_paint.floor = sg.G; }     // queue_ranges expects it empty
     if (threadIdx.x == 0 && sg.emit_hint != nullptr) sg.emit_hint[chunk] = 0;   // raised below, behind barriers
+    // A chunk whose tiles met more partial ranges than are applied from registers is likely to meet as many in the next
+    // plans (the timeline slides by a timeslice): it then paints them in LDS at once, instead of testing every range
+    // twice - once to find out, once to paint.  A hint, not state: both ways give the same next uses, and it runs out
+    // after kPaintHintPlans plans, when the queue is tried again.
+    const uint32_t paint_hint = (sg.paint_hint != nullptr && sg.n_ranges) ? sg.paint_hint[chunk] : 0u;
+    bool overflowed = false;
     __syncthreads();
     MSCHED_TICK(kTickCount, 1);
     const uint64_t p_begin = (uint64_t)chunk * sg.chunk_pages;
@@ -1079,7 +1087,10 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
             // (a tile that is the whole table meets every range: with more ranges than can be applied from registers
             // there is no point in queueing them first)
             const bool all_partial = tile_begin == 0 && tile_end == sg.V && sg.n_ranges > kPaintInRegisters;
-            if (!all_partial && queue_ranges<kRuns>(sg, runs, tile_begin, tile_end, s_paint) <= kPaintInRegisters) return kPaintQueued;
+            if (!all_partial && paint_hint == 0) {
+                if (queue_ranges<kRuns>(sg, runs, tile_begin, tile_end, s_paint) <= kPaintInRegisters) return kPaintQueued;
+                overflowed = true;
+            }
             __syncthreads();                                  // everybody has read the count
             paint_tile<kRuns>(sg, runs, tile_begin, tile_end, paint, s_paint);
             return kPaintLds;
@@ -1147,6 +1158,8 @@ __device__ __forceinline__ void count_body(const uint32_t *__restrict__ page_tab
         }
     }
     __syncthreads();
+    if (threadIdx.x == 0 && sg.paint_hint != nullptr && (overflowed || paint_hint != 0))
+        sg.paint_hint[chunk] = overflowed ? kPaintHintPlans : paint_hint - 1;
     uint32_t hint = 0;
     for (uint32_t k = threadIdx.x; k < n_keys; k += blockDim.x) {
         const uint32_t v = lds[k];
@@ -1832,6 +1845,7 @@ hipError_t launch_plan(msched_ctx *c, const PlanGeom &g) {
     // the second sweep's order: only where the cut kernel has its wide part to carry the extra workgroup
     const bool order_emit = c->order_emit && !g.single && g.n_chunks > kRowGroups;
     sg.g_end0 = g.g_end0; sg.emit_hint = order_emit ? c->chunk_hint : nullptr;
+    sg.paint_hint = g.single ? nullptr : c->chunk_hint + 2 * kMaxChunks;
     // one workgroup reads the range list where the host wrote it; many read a device copy, or the tasks' mirrors
     sg.ranges = g.single ? c->ranges_host_dev : g.resident ? nullptr : c->ranges_dev;
     const bool from_mirrors = g.resident && g.n_ranges;
