@@ -73,12 +73,13 @@ def test_many_commands_through_the_multi_kernel_cut(oracle_mod, monkeypatch, n_p
     assert lockstep(oracle_mod, trace, with_bytes=True, horizon="full", max_plans=3) == 3
 
 
-@pytest.mark.parametrize("n_ranges", [16, 63, 64, 65, 66, 70, 118])
+@pytest.mark.parametrize("n_ranges", [16, 31, 32, 33, 34, 63, 64, 65, 66, 70, 118])
 @pytest.mark.parametrize("force_multi", [False, True])
 def test_ranges_per_tile_around_the_limit_of_the_register_path(oracle_mod, monkeypatch, n_ranges, force_multi):
-    """Up to 64 partial ranges of a tile are applied from registers, more are painted in LDS (queue of 64, then
-    in place): n short ranges inside one tile, long ranges that cover whole tiles and end inside others, and the
-    table's ragged end; the second plan has to evict part of what the first brought in."""
+    """Up to 32 partial ranges of a tile are applied from registers, more are painted in LDS (short ones by the thread
+    that finds them, longer ones through a queue of 64, then in place): n short ranges inside one tile, long ranges
+    that cover whole tiles and end inside others, and the table's ragged end; the second plan has to evict part of
+    what the first brought in."""
     if force_multi:
         monkeypatch.setenv("MSCHED_FORCE_MULTI_KERNEL", "1")
     V, F, P = 6000, 3000, 64
@@ -107,6 +108,45 @@ def test_ranges_per_tile_around_the_limit_of_the_register_path(oracle_mod, monke
             pto, foo = o.state()
             ptg, fog = g.ms.state()
             assert np.array_equal(pto, ptg) and np.array_equal(foo, fog)
+    finally:
+        g.close()
+        o.close()
+
+
+def test_a_chunk_remembers_for_some_plans_that_its_ranges_overflowed(oracle_mod, monkeypatch):
+    """A chunk whose tile met more partial ranges than are applied from registers paints the next 16 plans' ranges in
+    LDS without trying the queue; then it tries the queue again.  Timelines with 70 short ranges in one tile and
+    with 3 alternate over 45 plans, so that every combination is passed through: overflow with and without the
+    hint set, few ranges with the hint set (painted in LDS), and after it has run out (applied from registers)."""
+    monkeypatch.setenv("MSCHED_FORCE_MULTI_KERNEL", "1")
+    V, F, P = 6000, 3000, 64
+    trace = explicit_trace([[[0]], [[1]]], V, F, timeslice=4, page_shift=6)
+    g = GpuSide(trace)
+    o = make_oracle(oracle_mod, trace, with_bytes=False)
+    rng = np.random.default_rng(5)
+    try:
+        rule = [Rule(RULE_LINEAR, 0, (1,), P)]
+        kg, ko = g.ms.kernel_register(rule), o.kernel_register(rule)
+        for impl in (g.ms, o):
+            impl.launch_retire(0, 1)
+            impl.launch_retire(1, 1)
+        starts = rng.permutation(120)[:69] * 4 + 20
+        cmds0 = [(int(a), 3) for a in starts] + [(2500, 1500)]
+        cmds1 = [(0, 2800), (4000, 100), (5990, 10)]
+        for task, cmds in ((0, cmds0), (1, cmds1)):
+            for a, n in cmds:
+                g.ms.launch_enqueue(task, kg, [a * P, n], 2)
+                o.launch_enqueue(task, ko, [a * P, n], 2)
+        many, few = [(0, len(cmds0)), (1, 3)], [(1, 3), (0, 5)]
+        for i in range(45):
+            tl = many if i in (0, 1, 5, 30, 31) else few
+            po, pg = o.plan(tl), g.ms.plan(tl)
+            assert_same_plan(po, pg, tl)
+            o.migrate()
+            g.ms.migrate()
+            pto, foo = o.state()
+            ptg, fog = g.ms.state()
+            assert np.array_equal(pto, ptg) and np.array_equal(foo, fog), i
     finally:
         g.close()
         o.close()
