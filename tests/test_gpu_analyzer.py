@@ -57,6 +57,17 @@ def test_adversarial_batches(oracle_analyzer, seed):
     assert kinds == {1, 2, 3}
 
 
+@pytest.mark.parametrize("n_inv", [63, 64, 65, 130])
+def test_invocations_around_one_per_lane(oracle_analyzer, n_inv):
+    """A lane keeps the first eight intervals of one invocation in registers and follows runs through them with fixed
+    indices; invocations beyond the first 64, and intervals beyond the eighth, are read from memory.  Batches of the
+    shape bench.py times (64 invocations, runs of up to 13 chunks) and one invocation more or less than the lanes,
+    model and adversarial."""
+    assert_same(make_batch(7, n_kernels=128, n_inv=n_inv, max_iv=48, vary=True), oracle_analyzer)
+    assert_same(make_batch(8, n_kernels=128, n_inv=n_inv, max_iv=48, vary=False), oracle_analyzer)
+    assert_same(make_adversarial_batch(9, n_kernels=128, n_inv=n_inv, max_iv=32), oracle_analyzer)
+
+
 def test_shapes_at_the_limits(oracle_analyzer):
     # the most invocations one call takes, more than one pass of the workgroup over them
     assert_same(make_batch(3, n_kernels=6, n_inv=512, max_iv=48, vary=True), oracle_analyzer)
